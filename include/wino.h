@@ -1,0 +1,142 @@
+/* wino.h -- C ABI of libwino: quantised Winograd/Toom-Cook 2-D convolution
+ * (3x3, stride 1, pad 1) with transforms in the canonical or monic-Legendre
+ * polynomial base, for AMD MI355X (gfx950).
+ *
+ * Conventions
+ *   m = output tile edge, r = kernel edge (3), n = m + r - 1 = Winograd tile
+ *   edge, TH = ceil(H/m), TW = ceil(W/m), T = N*TH*TW tiles, tile index
+ *   t = (b*TH + ty)*TW + tx, Winograd point p = i*n + j.
+ *   Device tensors (all dense, row-major in the order written):
+ *     x [N][H][W][C] int8      activations, NHWC
+ *     w [K][C][3][3] int8      filters, KCRS
+ *     V [n*n][K][C]  int8      transformed filters
+ *     U [n*n][T][C]  int8      transformed input tiles
+ *     M [n*n][T][K]  int8 (bits_hadamard 8) | int16 (9) | int32 (32)
+ *     y [N][H][W][K] float | int8 | int32 (see out_type)
+ *   A stored code q of a tensor with scale s stands for the real value q*s.
+ *
+ * Every function returns WINO_OK (0) or a negative error code and never
+ * throws or aborts; wino_last_error() gives the text of the last failure on
+ * the calling thread.  Functions taking a stream are asynchronous on it,
+ * allocate nothing and never synchronise; all device buffers, the workspace
+ * included, are owned by the caller.
+ */
+#ifndef WINO_H
+#define WINO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  WINO_OK = 0,
+  WINO_EINVAL = -1,       /* bad argument, shape, duplicate point, null pointer */
+  WINO_EUNSUPPORTED = -2, /* (m, r), bits or option combination not built       */
+  WINO_EOVERFLOW = -3,    /* rational or integer-stage bound exceeded           */
+  WINO_EWORKSPACE = -4,   /* workspace too small or misaligned                  */
+  WINO_EHIP = -5          /* HIP runtime error, text in wino_last_error()       */
+};
+
+enum { WINO_BASE_CANONICAL = 0, WINO_BASE_LEGENDRE = 1 };
+enum { WINO_OUT_F32 = 0, WINO_OUT_I32 = 1, WINO_OUT_I8 = 2 };
+enum {
+  WINO_MAT_G = 0,     /* n x r  Section 3: filter transform                    */
+  WINO_MAT_BT = 1,    /* n x n  Section 3: input transform                     */
+  WINO_MAT_AT = 2,    /* m x n  Section 3: output transform                    */
+  WINO_MAT_PT = 3,    /* n x n  Section 4.1: base change P^T                   */
+  WINO_MAT_PINVT = 4, /* n x n  Section 4.1: P^{-T}                            */
+  WINO_MAT_GP = 5,    /* n x r  G_P = P G                                      */
+  WINO_MAT_BPT = 6,   /* n x n  B_P^T = (P B)^T                                */
+  WINO_MAT_APT = 7    /* m x n  A_P^T = (P A)^T                                */
+};
+
+typedef struct { int64_t num, den; } wino_rat_t;   /* den > 0, reduced */
+typedef struct wino_matrices wino_matrices_t;      /* opaque, host memory */
+
+/* Section 3 ("Winograd algorithm") and Section 4.1: exact rational Toom-Cook
+ * matrices G, B^T, A^T for F(m, r) from `n_finite` = m+r-2 distinct finite
+ * points (host array; the point at infinity is implicit and last), plus the
+ * base-change factors P^T, P^{-T} and G_P = P G, B_P = P B, A_P = P A.
+ * base = WINO_BASE_LEGENDRE: P^T rows are the monic Legendre polynomials;
+ * base = WINO_BASE_CANONICAL: P = I.  m+r-1 <= 8.
+ * On success *out owns a host handle to be released with wino_free_matrices.
+ * Errors: EINVAL (null, sizes, zero denominator, duplicate point),
+ * EUNSUPPORTED (m+r-1 > 8), EOVERFLOW (an int64 rational overflowed). */
+int wino_make_matrices(int m, int r, const wino_rat_t* points, int n_finite, int base,
+                       wino_matrices_t** out);
+void wino_free_matrices(wino_matrices_t* h);
+
+/* Copies matrix `which` (WINO_MAT_*) row-major into host buffer `buf`
+ * (room for 64 entries is always enough) and reports its shape. */
+int wino_get_matrix(const wino_matrices_t* h, int which, wino_rat_t* buf, int* rows, int* cols);
+
+/* Integer form used by the quantised stages: matrix = diag(1/row_lcd) * N with
+ * row_lcd[i] the least common denominator of row i.  N: rows*cols int64
+ * row-major, row_lcd: rows int64, both host buffers. */
+int wino_get_int_form(const wino_matrices_t* h, int which, int64_t* N, int64_t* row_lcd,
+                      int* rows, int* cols);
+
+typedef struct {
+  int N, H, W, C, K;          /* C and K multiples of 16                          */
+  int m, r;                   /* (2,3), (4,3) or (6,3); standard point sets
+                                 {0,1,-1}, {0,1,-1,2,-2}, {0,1,-1,2,-2,1/2,-1/2}  */
+  int base;                   /* WINO_BASE_*                                      */
+  int bits_in;                /* 8: int8 path; 32: fp32 path without any cast     */
+  int bits_hadamard;          /* 8 | 9 | 32: width kept for the contraction result
+                                 (Section 5: "Hadamard product on 9 bits")        */
+  int inner_quant;            /* Legendre only: casts on the inner brackets of
+                                 eq. 4 (1) or brackets multiplied out (0)         */
+  int out_type;               /* WINO_OUT_*; I32 needs an integer A^T (canonical
+                                 base, m = 2 or 4)                                */
+  int relu;                   /* clamp the output at zero                         */
+  int weights_pretransformed; /* wino_conv2d: second pointer is V, not w          */
+  int fused;                  /* wino_conv2d: single-kernel variant               */
+} wino_conv_desc_t;
+
+/* Per-tensor symmetric scales, supplied by the caller.  s_x1, s_w1, s_m1 are
+ * the inner brackets of eq. 4 and are ignored for the canonical base or
+ * inner_quant = 0; s_m is ignored for bits_hadamard = 32; s_y only for I8. */
+typedef struct {
+  float s_x, s_x1, s_u, s_w, s_w1, s_v, s_m, s_m1, s_y;
+} wino_scales_t;
+
+/* Bytes of device workspace wino_conv2d needs for this descriptor (V unless
+ * pretransformed, U and M; each 256-byte aligned). */
+int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
+
+/* Eq. 3 (canonical) / eq. 4 (Legendre) for a whole layer, with a symmetric
+ * cast after every bracket (Section 4.2): weight transform (skipped when
+ * pretransformed), input transform, per-point channel contraction, output
+ * transform, all queued on `hip_stream` (a hipStream_t, may be null = default
+ * stream).  x, w_or_V, y, workspace: device pointers; d, s: host pointers.
+ * Errors: EINVAL, EUNSUPPORTED, EOVERFLOW (C too large for exact fp32
+ * conversion of the contraction result), EWORKSPACE, EHIP. */
+int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, void* y,
+                const wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* The four stages on their own (same descriptor and scales; device pointers).
+ * Eq. 1 / eq. 2: w -> V. */
+int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
+                          const wino_scales_t* s, void* hip_stream);
+/* Input bracket of eq. 3 / eq. 4: x -> U. */
+int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
+                         const wino_scales_t* s, void* hip_stream);
+/* Hadamard product summed over input channels: M[p][t][k] = sum_c U V, then
+ * the cast to bits_hadamard (int8 MFMA, int32 accumulation). */
+int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void* M,
+                  const wino_scales_t* s, void* hip_stream);
+/* Output bracket of eq. 3 / eq. 4: M -> y. */
+int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
+                          const wino_scales_t* s, void* hip_stream);
+
+/* Text of the last error on this thread ("" if none); valid until the next
+ * failing call on the same thread. */
+const char* wino_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WINO_H */

@@ -1,0 +1,12 @@
+"""MI355X-native quantised Winograd convolution in the Legendre base.
+
+Thin ctypes binding over libwino.so (HIP kernels + C ABI, see include/wino.h).
+PyTorch is used for device memory and streams only; every step of the
+convolution runs in the library's kernels.  Importing this package without a
+built library raises: there is no CPU fallback.
+"""
+from .binding import (  # noqa: F401
+    BASE_CANONICAL, BASE_LEGENDRE, OUT_F32, OUT_I32, OUT_I8, MAT_NAMES, ConvDesc, Matrices,
+    Scales, WinoError, lib_path, wino_contract, wino_conv2d, wino_input_transform,
+    wino_make_matrices, wino_output_transform, wino_weight_transform, wino_workspace_bytes,
+)

@@ -1,0 +1,194 @@
+"""ctypes marshalling for libwino.so -- argument packing only, no arithmetic."""
+import ctypes as C
+import os
+from fractions import Fraction
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+BASE_CANONICAL, BASE_LEGENDRE = 0, 1
+OUT_F32, OUT_I32, OUT_I8 = 0, 1, 2
+MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
+EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
+           "wino_workspace_bytes", "wino_conv2d", "wino_weight_transform",
+           "wino_input_transform", "wino_contract", "wino_output_transform", "wino_last_error")
+
+
+class WinoError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("libwino error %d: %s" % (code, text))
+        self.code = code
+
+
+class _Rat(C.Structure):
+    _fields_ = [("num", C.c_int64), ("den", C.c_int64)]
+
+
+class ConvDesc(C.Structure):
+    """Mirror of wino_conv_desc_t."""
+    _fields_ = [(n, C.c_int) for n in (
+        "N", "H", "W", "C", "K", "m", "r", "base", "bits_in", "bits_hadamard", "inner_quant",
+        "out_type", "relu", "weights_pretransformed", "fused")]
+
+    def __init__(self, N, H, W, C_, K, m=4, r=3, base=BASE_LEGENDRE, bits_in=8, bits_hadamard=8,
+                 inner_quant=1, out_type=OUT_F32, relu=0, weights_pretransformed=0, fused=0):
+        super().__init__(N, H, W, C_, K, m, r, base, bits_in, bits_hadamard, inner_quant,
+                         out_type, relu, weights_pretransformed, fused)
+
+    @property
+    def n(self):
+        return self.m + self.r - 1
+
+    @property
+    def tiles(self):
+        return self.N * (-(-self.H // self.m)) * (-(-self.W // self.m))
+
+
+class Scales(C.Structure):
+    """Mirror of wino_scales_t."""
+    _fields_ = [(n, C.c_float) for n in (
+        "s_x", "s_x1", "s_u", "s_w", "s_w1", "s_v", "s_m", "s_m1", "s_y")]
+
+    @classmethod
+    def from_dict(cls, d):
+        s = cls()
+        for name, _ in cls._fields_:
+            setattr(s, name, float(d.get(name, 1.0)))
+        return s
+
+
+def lib_path():
+    return os.path.join(HERE, "libwino.so")
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError("libwino.so is not built (run: python -m paper_2004_11077_amd.build); "
+                          "there is no fallback path")
+    lib = C.CDLL(path)
+    vp, ip = C.c_void_p, C.POINTER(C.c_int)
+    lib.wino_last_error.restype = C.c_char_p
+    lib.wino_make_matrices.argtypes = [C.c_int, C.c_int, C.POINTER(_Rat), C.c_int, C.c_int,
+                                       C.POINTER(vp)]
+    lib.wino_free_matrices.argtypes = [vp]
+    lib.wino_free_matrices.restype = None
+    lib.wino_get_matrix.argtypes = [vp, C.c_int, C.POINTER(_Rat), ip, ip]
+    lib.wino_get_int_form.argtypes = [vp, C.c_int, C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                      ip, ip]
+    dp, sp = C.POINTER(ConvDesc), C.POINTER(Scales)
+    lib.wino_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
+    lib.wino_conv2d.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
+    lib.wino_weight_transform.argtypes = [dp, vp, vp, sp, vp]
+    lib.wino_input_transform.argtypes = [dp, vp, vp, sp, vp]
+    lib.wino_contract.argtypes = [dp, vp, vp, vp, sp, vp]
+    lib.wino_output_transform.argtypes = [dp, vp, vp, sp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise WinoError(rc, _load().wino_last_error().decode())
+
+
+class Matrices:
+    """Exact rational matrices of one F(m, r) instance (host side)."""
+
+    def __init__(self, m, r, mats, int_forms):
+        self.m, self.r, self.n = m, r, m + r - 1
+        self._mats, self._int = mats, int_forms
+        for k, v in mats.items():
+            setattr(self, k, v)
+
+    def int_form(self, name):
+        """(N, row_lcd) with matrix = diag(1/row_lcd) N."""
+        return self._int[name]
+
+
+def wino_make_matrices(m, r, points, base=BASE_LEGENDRE):
+    """Exact Toom-Cook G, B^T, A^T and base-change factors; ``points`` are the
+    m+r-2 finite points (ints or Fractions), infinity implicit and last."""
+    lib = _load()
+    pts = [Fraction(p) for p in points]
+    arr = (_Rat * max(1, len(pts)))(*[_Rat(p.numerator, p.denominator) for p in pts])
+    h = C.c_void_p()
+    _check(lib.wino_make_matrices(m, r, arr, len(pts), base, C.byref(h)))
+    try:
+        mats, ints = {}, {}
+        for which, name in enumerate(MAT_NAMES):
+            buf = (_Rat * 64)()
+            rows, cols = C.c_int(), C.c_int()
+            _check(lib.wino_get_matrix(h, which, buf, C.byref(rows), C.byref(cols)))
+            mats[name] = [[Fraction(buf[i * cols.value + j].num, buf[i * cols.value + j].den)
+                           for j in range(cols.value)] for i in range(rows.value)]
+            nb, lb = (C.c_int64 * 64)(), (C.c_int64 * 8)()
+            _check(lib.wino_get_int_form(h, which, nb, lb, C.byref(rows), C.byref(cols)))
+            ints[name] = ([[nb[i * cols.value + j] for j in range(cols.value)]
+                           for i in range(rows.value)], [lb[i] for i in range(rows.value)])
+    finally:
+        lib.wino_free_matrices(h)
+    return Matrices(m, r, mats, ints)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(getattr(stream, "cuda_stream", stream))
+
+
+def _scales(s):
+    return s if isinstance(s, Scales) else Scales.from_dict(s)
+
+
+def wino_workspace_bytes(desc):
+    out = C.c_size_t()
+    _check(_load().wino_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def wino_conv2d(desc, x, w_or_V, y, scales, workspace, stream=None):
+    """Whole layer on ``stream``; all tensors are caller-allocated device tensors."""
+    sc = _scales(scales)
+    _check(_load().wino_conv2d(C.byref(desc), _ptr(x), _ptr(w_or_V), _ptr(y), C.byref(sc),
+                               _ptr(workspace), workspace.numel() * workspace.element_size(),
+                               _stream(stream)))
+    return y
+
+
+def wino_weight_transform(desc, w, V, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_weight_transform(C.byref(desc), _ptr(w), _ptr(V), C.byref(sc),
+                                         _stream(stream)))
+    return V
+
+
+def wino_input_transform(desc, x, U, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_input_transform(C.byref(desc), _ptr(x), _ptr(U), C.byref(sc),
+                                        _stream(stream)))
+    return U
+
+
+def wino_contract(desc, U, V, M, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_contract(C.byref(desc), _ptr(U), _ptr(V), _ptr(M), C.byref(sc),
+                                 _stream(stream)))
+    return M
+
+
+def wino_output_transform(desc, M, y, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_output_transform(C.byref(desc), _ptr(M), _ptr(y), C.byref(sc),
+                                         _stream(stream)))
+    return y

@@ -1,0 +1,371 @@
+// C ABI of libwino (see include/wino.h): argument validation, host-side
+// multiplier tables, workspace carving and kernel dispatch.
+#include "../../include/wino.h"
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "wino_kernels.hpp"
+#include "wino_tables.hpp"
+
+using namespace wino;
+
+struct wino_matrices {
+  MatrixSet ms;
+};
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+int fail_hip(hipError_t e, const char* what) {
+  return fail(WINO_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+const RMat* pick(const MatrixSet& ms, int which) {
+  switch (which) {
+    case WINO_MAT_G: return &ms.G;
+    case WINO_MAT_BT: return &ms.BT;
+    case WINO_MAT_AT: return &ms.AT;
+    case WINO_MAT_PT: return &ms.PT;
+    case WINO_MAT_PINVT: return &ms.PinvT;
+    case WINO_MAT_GP: return &ms.GP;
+    case WINO_MAT_BPT: return &ms.BPT;
+    case WINO_MAT_APT: return &ms.APT;
+  }
+  return nullptr;
+}
+
+// Stage matrices of one standard instance, as run-time references.
+struct Stages {
+  const IMat *G, *BT, *AT, *PinvT, *Pinv, *GP, *BPT, *APT;
+};
+
+template <int M>
+Stages stages_of() {
+  using TB = Tab<M>;
+  return Stages{&TB::G, &TB::BT, &TB::AT, &TB::PinvT, &TB::Pinv, &TB::GP, &TB::BPT, &TB::APT};
+}
+
+bool stages_for(int m, Stages* s) {
+  switch (m) {
+    case 2: *s = stages_of<2>(); return true;
+    case 4: *s = stages_of<4>(); return true;
+    case 6: *s = stages_of<6>(); return true;
+  }
+  return false;
+}
+
+// mult_ij = float( s_prev / ( (rho_i rho_j) * s_next ) ), evaluated in double.
+void fill_mults(MultTable* t, const IMat& im, double s_prev, double s_next) {
+  std::memset(t, 0, sizeof *t);
+  for (int i = 0; i < im.rows; ++i)
+    for (int j = 0; j < im.rows; ++j) {
+      const double rr = (double)(im.rho[i] * im.rho[j]);
+      t->v[i * im.rows + j] = (float)(s_prev / (rr * s_next));
+    }
+}
+
+bool good_scale(float s) { return std::isfinite(s) && s > 0.f; }
+
+struct Plan {
+  Geometry g;
+  Stages st;
+  bool two_brackets;   // Legendre with casts on the inner brackets
+  int m_bits;
+};
+
+int make_plan(const wino_conv_desc_t* d, Plan* p) {
+  if (!d) return fail(WINO_EINVAL, "null descriptor");
+  if (d->r != 3 || !(d->m == 2 || d->m == 4 || d->m == 6))
+    return fail(WINO_EUNSUPPORTED, "F(%d,%d) not built: m must be 2, 4 or 6 and r = 3", d->m, d->r);
+  if (d->base != WINO_BASE_CANONICAL && d->base != WINO_BASE_LEGENDRE)
+    return fail(WINO_EINVAL, "unknown base %d", d->base);
+  if (d->bits_in == 32) return fail(WINO_EUNSUPPORTED, "fp32 path (bits_in = 32) not built");
+  if (d->bits_in != 8) return fail(WINO_EUNSUPPORTED, "bits_in must be 8 (got %d)", d->bits_in);
+  if (d->bits_hadamard != 8 && d->bits_hadamard != 9 && d->bits_hadamard != 32)
+    return fail(WINO_EUNSUPPORTED, "bits_hadamard must be 8, 9 or 32 (got %d)", d->bits_hadamard);
+  if (d->out_type != WINO_OUT_F32 && d->out_type != WINO_OUT_I32 && d->out_type != WINO_OUT_I8)
+    return fail(WINO_EINVAL, "unknown out_type %d", d->out_type);
+  if (d->N < 0 || d->H < 0 || d->W < 0 || d->C < 0 || d->K < 0)
+    return fail(WINO_EINVAL, "negative dimension");
+  if (d->C % 16 != 0 || d->K % 16 != 0)
+    return fail(WINO_EINVAL, "C (%d) and K (%d) must be multiples of 16", d->C, d->K);
+  const long TH = (d->H + d->m - 1) / d->m, TW = (d->W + d->m - 1) / d->m;
+  const long T = (long)d->N * TH * TW;
+  const long n2 = (long)(d->m + 2) * (d->m + 2);
+  if (T > (1L << 30) || T * (long)(d->C > d->K ? d->C : d->K) * n2 > (1L << 40) ||
+      (long)d->N * d->H * d->W * (long)(d->C > d->K ? d->C : d->K) > (1L << 40))
+    return fail(WINO_EINVAL, "problem too large");
+  if (d->bits_hadamard == 32 && d->C > kMaxChannelsExact)
+    return fail(WINO_EOVERFLOW, "C = %d: an unquantised contraction result may exceed 2^24", d->C);
+  p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T};
+  if (!stages_for(d->m, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
+  p->two_brackets = d->base == WINO_BASE_LEGENDRE && d->inner_quant != 0;
+  p->m_bits = d->bits_hadamard;
+  if (d->out_type == WINO_OUT_I32) {
+    const IMat& a = *p->st.AT;
+    bool integer = !p->two_brackets;
+    for (int i = 0; i < a.rows; ++i) integer = integer && a.rho[i] == 1;
+    if (!integer)
+      return fail(WINO_EUNSUPPORTED, "int32 output needs an integer output matrix "
+                                     "(canonical base or inner_quant = 0, m = 2 or 4)");
+  }
+  return WINO_OK;
+}
+
+int need(const void* p, const char* name) {
+  return p ? WINO_OK : fail(WINO_EINVAL, "null pointer: %s", name);
+}
+
+int aligned(const void* p, size_t a, const char* name) {
+  return ((uintptr_t)p % a) == 0 ? WINO_OK
+                                 : fail(WINO_EINVAL, "%s must be %zu-byte aligned", name, a);
+}
+
+size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t m_elem_bytes(int bits) { return bits == 8 ? 1 : bits == 9 ? 2 : 4; }
+
+int weight_mults(const Plan& p, const wino_scales_t* s, StageMults* mu) {
+  if (!good_scale(s->s_w) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_w / s_v");
+  if (p.two_brackets) {
+    if (!good_scale(s->s_w1)) return fail(WINO_EINVAL, "bad s_w1");
+    fill_mults(&mu->inner, *p.st.GP, s->s_w, s->s_w1);
+    fill_mults(&mu->outer, *p.st.Pinv, s->s_w1, s->s_v);
+  } else {
+    fill_mults(&mu->outer, *p.st.G, s->s_w, s->s_v);
+  }
+  return WINO_OK;
+}
+
+int input_mults(const Plan& p, const wino_scales_t* s, StageMults* mu) {
+  if (!good_scale(s->s_x) || !good_scale(s->s_u)) return fail(WINO_EINVAL, "bad s_x / s_u");
+  if (p.two_brackets) {
+    if (!good_scale(s->s_x1)) return fail(WINO_EINVAL, "bad s_x1");
+    fill_mults(&mu->inner, *p.st.PinvT, s->s_x, s->s_x1);
+    fill_mults(&mu->outer, *p.st.BPT, s->s_x1, s->s_u);
+  } else {
+    fill_mults(&mu->outer, *p.st.BT, s->s_x, s->s_u);
+  }
+  return WINO_OK;
+}
+
+int contract_mult(const Plan& p, const wino_scales_t* s, float* mult, double* s_m_eff) {
+  if (!good_scale(s->s_u) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_u / s_v");
+  const double s_uv = (double)s->s_u * (double)s->s_v;
+  if (p.m_bits == 32) {
+    *mult = 1.f;
+    *s_m_eff = s_uv;
+  } else {
+    if (!good_scale(s->s_m)) return fail(WINO_EINVAL, "bad s_m");
+    *mult = (float)(s_uv / (double)s->s_m);
+    *s_m_eff = (double)s->s_m;
+  }
+  return WINO_OK;
+}
+
+int output_mults(const Plan& p, const wino_conv_desc_t* d, const wino_scales_t* s,
+                 StageMults* mu) {
+  float dummy;
+  double s_m;
+  if (int rc = contract_mult(p, s, &dummy, &s_m)) return rc;
+  double s_next = 1.0;   // fp32 output: the table holds dequantisation factors
+  if (d->out_type == WINO_OUT_I8) {
+    if (!good_scale(s->s_y)) return fail(WINO_EINVAL, "bad s_y");
+    s_next = (double)s->s_y;
+  }
+  if (p.two_brackets) {
+    if (!good_scale(s->s_m1)) return fail(WINO_EINVAL, "bad s_m1");
+    fill_mults(&mu->inner, *p.st.PinvT, s_m, s->s_m1);
+    fill_mults(&mu->outer, *p.st.APT, s->s_m1, s_next);
+  } else {
+    fill_mults(&mu->outer, *p.st.AT, s_m, s_next);
+  }
+  return WINO_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* wino_last_error(void) { return g_err.c_str(); }
+
+int wino_make_matrices(int m, int r, const wino_rat_t* points, int n_finite, int base,
+                       wino_matrices_t** out) {
+  if (!out) return fail(WINO_EINVAL, "null out");
+  *out = nullptr;
+  if (m < 1 || r < 1) return fail(WINO_EINVAL, "m and r must be positive");
+  if (m + r - 1 > kMaxN) return fail(WINO_EUNSUPPORTED, "m + r - 1 = %d exceeds %d", m + r - 1, kMaxN);
+  if (n_finite != m + r - 2) return fail(WINO_EINVAL, "need m + r - 2 = %d finite points, got %d", m + r - 2, n_finite);
+  if (n_finite > 0 && !points) return fail(WINO_EINVAL, "null points");
+  if (base != WINO_BASE_CANONICAL && base != WINO_BASE_LEGENDRE)
+    return fail(WINO_EINVAL, "unknown base %d", base);
+  Rat pts[kMaxN];
+  for (int i = 0; i < n_finite; ++i) {
+    if (points[i].den == 0) return fail(WINO_EINVAL, "point %d has a zero denominator", i);
+    pts[i] = make_rat(points[i].num, points[i].den);
+    if (!pts[i].ok) return fail(WINO_EOVERFLOW, "point %d out of range", i);
+    for (int j = 0; j < i; ++j)
+      if (rat_eq(pts[i], pts[j])) return fail(WINO_EINVAL, "points %d and %d coincide", j, i);
+  }
+  wino_matrices* h = new (std::nothrow) wino_matrices;
+  if (!h) return fail(WINO_EINVAL, "out of host memory");
+  h->ms = make_matrix_set(m, r, pts, n_finite, base == WINO_BASE_LEGENDRE);
+  if (!h->ms.ok) {
+    delete h;
+    return fail(WINO_EOVERFLOW, "a rational overflowed int64 while building F(%d,%d)", m, r);
+  }
+  *out = h;
+  return WINO_OK;
+}
+
+void wino_free_matrices(wino_matrices_t* h) { delete h; }
+
+int wino_get_matrix(const wino_matrices_t* h, int which, wino_rat_t* buf, int* rows, int* cols) {
+  if (!h || !buf || !rows || !cols) return fail(WINO_EINVAL, "null argument");
+  const RMat* mtx = pick(h->ms, which);
+  if (!mtx) return fail(WINO_EINVAL, "unknown matrix id %d", which);
+  *rows = mtx->rows;
+  *cols = mtx->cols;
+  for (int i = 0; i < mtx->rows; ++i)
+    for (int j = 0; j < mtx->cols; ++j)
+      buf[i * mtx->cols + j] = wino_rat_t{mtx->a[i][j].num, mtx->a[i][j].den};
+  return WINO_OK;
+}
+
+int wino_get_int_form(const wino_matrices_t* h, int which, int64_t* N, int64_t* row_lcd,
+                      int* rows, int* cols) {
+  if (!h || !N || !row_lcd || !rows || !cols) return fail(WINO_EINVAL, "null argument");
+  const RMat* mtx = pick(h->ms, which);
+  if (!mtx) return fail(WINO_EINVAL, "unknown matrix id %d", which);
+  const IMat im = int_form(*mtx);
+  if (!im.ok) return fail(WINO_EOVERFLOW, "integer form overflowed int64");
+  *rows = im.rows;
+  *cols = im.cols;
+  for (int i = 0; i < im.rows; ++i) {
+    row_lcd[i] = im.rho[i];
+    for (int j = 0; j < im.cols; ++j) N[i * im.cols + j] = im.N[i][j];
+  }
+  return WINO_OK;
+}
+
+int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (!bytes) return fail(WINO_EINVAL, "null bytes");
+  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  size_t total = 0;
+  if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C);
+  total += round256(n2 * p.g.T * d->C);
+  total += round256(n2 * p.g.T * d->K * m_elem_bytes(d->bits_hadamard));
+  *bytes = total;
+  return WINO_OK;
+}
+
+int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
+                          const wino_scales_t* s, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (int rc = need(w, "w")) return rc;
+  if (int rc = need(V, "V")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  StageMults mu;
+  if (int rc = weight_mults(p, s, &mu)) return rc;
+  hipError_t e = launch_weight_transform(p.g, p.two_brackets, (const int8_t*)w, (int8_t*)V, mu,
+                                         (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "weight transform launch");
+}
+
+int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
+                         const wino_scales_t* s, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (int rc = need(x, "x")) return rc;
+  if (int rc = need(U, "U")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  if (int rc = aligned(x, 4, "x")) return rc;
+  if (int rc = aligned(U, 16, "U")) return rc;
+  StageMults mu;
+  if (int rc = input_mults(p, s, &mu)) return rc;
+  hipError_t e = launch_input_transform(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U, mu,
+                                        (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "input transform launch");
+}
+
+int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void* M,
+                  const wino_scales_t* s, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (int rc = need(U, "U")) return rc;
+  if (int rc = need(V, "V")) return rc;
+  if (int rc = need(M, "M")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  if (int rc = aligned(U, 16, "U")) return rc;
+  if (int rc = aligned(V, 16, "V")) return rc;
+  if (int rc = aligned(M, 16, "M")) return rc;
+  float mult;
+  double s_m;
+  if (int rc = contract_mult(p, s, &mult, &s_m)) return rc;
+  hipError_t e = launch_contract(p.g, (const int8_t*)U, (const int8_t*)V, M, p.m_bits, mult,
+                                 (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "contraction launch");
+}
+
+int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
+                          const wino_scales_t* s, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (int rc = need(M, "M")) return rc;
+  if (int rc = need(y, "y")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  if (int rc = aligned(M, 16, "M")) return rc;
+  if (int rc = aligned(y, 16, "y")) return rc;
+  StageMults mu;
+  if (int rc = output_mults(p, d, s, &mu)) return rc;
+  hipError_t e = launch_output_transform(p.g, p.two_brackets, M, p.m_bits, y, d->out_type,
+                                         d->relu != 0, mu, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "output transform launch");
+}
+
+int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, void* y,
+                const wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (d->fused) return fail(WINO_EUNSUPPORTED, "fused variant not built");
+  size_t want = 0;
+  if (int rc = wino_workspace_bytes(d, &want)) return rc;
+  if (int rc = need(workspace, "workspace")) return rc;
+  if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
+  if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  char* ws = static_cast<char*>(workspace);
+  const void* V = w_or_V;
+  if (!d->weights_pretransformed) {
+    if (int rc = wino_weight_transform(d, w_or_V, ws, s, hip_stream)) return rc;
+    V = ws;
+    ws += round256(n2 * d->K * d->C);
+  }
+  void* U = ws;
+  ws += round256(n2 * p.g.T * d->C);
+  void* M = ws;
+  if (int rc = wino_input_transform(d, x, U, s, hip_stream)) return rc;
+  if (int rc = wino_contract(d, U, V, M, s, hip_stream)) return rc;
+  return wino_output_transform(d, M, y, s, hip_stream);
+}
+
+}  // extern "C"

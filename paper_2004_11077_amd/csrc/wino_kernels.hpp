@@ -1,0 +1,61 @@
+// Internal launcher interface between the C ABI (wino_api.cpp) and the HIP
+// kernels (wino_kernels.hip).  Not part of the public boundary.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace wino {
+
+constexpr int kMaxPts = 64;   // n*n for n = 8
+
+// fp32 multipliers of one cast, indexed [i*cols + j] (Section 4.2 cast after a
+// bracket; value = s_prev / (rho_i rho_j s_next), rounded to fp32 on the host).
+struct MultTable {
+  float v[kMaxPts];
+};
+
+struct Geometry {
+  int N, H, W, C, K;
+  int m;        // output tile edge
+  int TH, TW;   // tiles per image
+  int T;        // total tiles
+};
+
+struct StageMults {
+  MultTable inner;   // inner bracket of eq. 2 / eq. 4 (unused when !inner)
+  MultTable outer;   // outer bracket, or the only one for the canonical base
+};
+
+// Per-M launchers of the transform stages (defined in wino_transforms.hpp and
+// instantiated once per M in its own translation unit).
+template <int M>
+struct PerM {
+  static hipError_t weight(const Geometry& g, bool legendre_inner, const int8_t* w, int8_t* V,
+                           const StageMults& mu, hipStream_t st);
+  static hipError_t input(const Geometry& g, bool legendre_inner, const int8_t* x, int8_t* U,
+                          const StageMults& mu, hipStream_t st);
+  static hipError_t output(const Geometry& g, bool legendre_inner, const void* M_, int m_bits,
+                           void* y, int out_type, bool relu, const StageMults& mu,
+                           hipStream_t st);
+};
+extern template struct PerM<2>;
+extern template struct PerM<4>;
+extern template struct PerM<6>;
+
+// legendre_inner == true selects the two-bracket Legendre pipeline; false the
+// single-bracket (canonical, or Legendre with brackets multiplied out).
+hipError_t launch_weight_transform(const Geometry& g, bool legendre_inner, const int8_t* w,
+                                   int8_t* V, const StageMults& mu, hipStream_t st);
+hipError_t launch_input_transform(const Geometry& g, bool legendre_inner, const int8_t* x,
+                                  int8_t* U, const StageMults& mu, hipStream_t st);
+// m_bits: 8 -> int8 M, 9 -> int16 M, 32 -> int32 M (no cast).
+hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* M,
+                           int m_bits, float mult, hipStream_t st);
+// out_type: 0 fp32 (outer table = dequantisation factors), 1 int32 numerators,
+// 2 int8 codes (outer table = cast multipliers).
+hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const void* M,
+                                   int m_bits, void* y, int out_type, bool relu,
+                                   const StageMults& mu, hipStream_t st);
+
+}  // namespace wino

@@ -1,0 +1,356 @@
+// Transform kernels (gfx950) of the quantised Winograd convolution layer,
+// templated on the output tile edge M; one translation unit per M instantiates
+// PerM<M>.  Stages of eq. 3 / eq. 4 covered here:
+//   weight transform   eq. 1 / eq. 2
+//   input transform    input bracket of eq. 3 / eq. 4
+//   output transform   output bracket of eq. 3 / eq. 4
+// Every cast is  q = clamp(rint(float(num) * mult), +-qmax)  on exact integer
+// numerators num = N x N^T (N = integer form of the stage matrix).
+#pragma once
+#include "wino_kernels.hpp"
+#include "wino_tables.hpp"
+
+namespace wino {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+template <int I>
+using IC = std::integral_constant<int, I>;
+
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(IC<B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
+// num = N x N^T with N the compile-time integer matrix T.N (T.rows x T.cols).
+// Zero coefficients generate no code.
+template <const IMat& T, typename AccT, typename InT>
+__device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
+                                         AccT (&num)[T.rows][T.rows]) {
+  AccT tmp[T.rows][T.cols];
+  static_for<0, T.rows>([&](auto i) {
+    static_for<0, T.cols>([&](auto b) {
+      AccT acc = 0;
+      static_for<0, T.cols>([&](auto a) {
+        constexpr int64_t c = T.N[decltype(i)::value][decltype(a)::value];
+        if constexpr (c != 0) acc += (AccT)c * (AccT)x[a][b];
+      });
+      tmp[i][b] = acc;
+    });
+  });
+  static_for<0, T.rows>([&](auto i) {
+    static_for<0, T.rows>([&](auto j) {
+      AccT acc = 0;
+      static_for<0, T.cols>([&](auto b) {
+        constexpr int64_t c = T.N[decltype(j)::value][decltype(b)::value];
+        if constexpr (c != 0) acc += (AccT)c * tmp[i][b];
+      });
+      num[i][j] = acc;
+    });
+  });
+}
+
+// One symmetric cast: round to nearest even, clamp to +-qmax.
+__device__ __forceinline__ int cast_code(float v, float qmax) {
+  v = rintf(v);
+  v = fminf(fmaxf(v, -qmax), qmax);
+  return (int)v;
+}
+
+template <int R, typename AccT>
+__device__ __forceinline__ void cast_tile(const AccT (&num)[R][R], const MultTable& mu, float qmax,
+                                          int (&q)[R][R]) {
+  static_for<0, R>([&](auto i) {
+    static_for<0, R>([&](auto j) {
+      q[i][j] = cast_code((float)num[i][j] * mu.v[decltype(i)::value * R + decltype(j)::value],
+                          qmax);
+    });
+  });
+}
+
+// ---------------------------------------------------------------------------
+// Weight transform: one lane per (k, c) filter.
+// ---------------------------------------------------------------------------
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restrict__ w,
+                                                          int8_t* __restrict__ V, Geometry g,
+                                                          StageMults mu) {
+  constexpr int n = M + 2;
+  using TB = Tab<M>;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long KC = (long)g.K * g.C;
+  if (gid >= KC) return;
+  int wi[3][3];
+  static_for<0, 3>([&](auto a) {
+    static_for<0, 3>([&](auto b) { wi[a][b] = w[gid * 9 + decltype(a)::value * 3 + decltype(b)::value]; });
+  });
+  int q[n][n];
+  if constexpr (LEG) {
+    acc_t<TB::GP, 127> num1[n][n];
+    sandwich<TB::GP>(wi, num1);
+    int w1[n][n];
+    cast_tile<n>(num1, mu.inner, 127.f, w1);
+    acc_t<TB::Pinv, 127> num2[n][n];
+    sandwich<TB::Pinv>(w1, num2);
+    cast_tile<n>(num2, mu.outer, 127.f, q);
+  } else {
+    acc_t<TB::G, 127> num[n][n];
+    sandwich<TB::G>(wi, num);
+    cast_tile<n>(num, mu.outer, 127.f, q);
+  }
+  static_for<0, n>([&](auto i) {
+    static_for<0, n>([&](auto j) {
+      V[(long)(decltype(i)::value * n + decltype(j)::value) * KC + gid] = (int8_t)q[i][j];
+    });
+  });
+}
+
+// ---------------------------------------------------------------------------
+// Input transform: one lane per (tile, 4 consecutive channels).
+// ---------------------------------------------------------------------------
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
+                                                         int8_t* __restrict__ U, Geometry g,
+                                                         StageMults mu) {
+  constexpr int n = M + 2;
+  using TB = Tab<M>;
+  const int c4n = g.C >> 2;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int t = (int)(gid / c4n);
+  const int c4 = (int)(gid - (long)t * c4n);
+  if (t >= g.T) return;
+  const int tx = t % g.TW;
+  const int ty = (t / g.TW) % g.TH;
+  const int b = t / (g.TW * g.TH);
+
+  uint32_t in[n][n];
+  static_for<0, n>([&](auto a) {
+    static_for<0, n>([&](auto bb) {
+      const int h = ty * M - 1 + decltype(a)::value;
+      const int ww = tx * M - 1 + decltype(bb)::value;
+      uint32_t v = 0;
+      if (h >= 0 && h < g.H && ww >= 0 && ww < g.W)
+        v = *reinterpret_cast<const uint32_t*>(x + (((long)b * g.H + h) * g.W + ww) * g.C + c4 * 4);
+      in[a][bb] = v;
+    });
+  });
+
+  uint32_t outw[n][n];
+  static_for<0, n>([&](auto i) { static_for<0, n>([&](auto j) { outw[i][j] = 0; }); });
+
+  static_for<0, 4>([&](auto ch) {
+    int xi[n][n];
+    static_for<0, n>([&](auto a) {
+      static_for<0, n>([&](auto bb) {
+        xi[a][bb] = (int)(int8_t)(in[a][bb] >> (8 * decltype(ch)::value));
+      });
+    });
+    int q[n][n];
+    if constexpr (LEG) {
+      acc_t<TB::PinvT, 127> num1[n][n];
+      sandwich<TB::PinvT>(xi, num1);
+      int x1[n][n];
+      cast_tile<n>(num1, mu.inner, 127.f, x1);
+      acc_t<TB::BPT, 127> num2[n][n];
+      sandwich<TB::BPT>(x1, num2);
+      cast_tile<n>(num2, mu.outer, 127.f, q);
+    } else {
+      acc_t<TB::BT, 127> num[n][n];
+      sandwich<TB::BT>(xi, num);
+      cast_tile<n>(num, mu.outer, 127.f, q);
+    }
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) {
+        outw[i][j] |= ((uint32_t)q[i][j] & 0xffu) << (8 * decltype(ch)::value);
+      });
+    });
+  });
+
+  const long TC = (long)g.T * g.C;
+  static_for<0, n>([&](auto i) {
+    static_for<0, n>([&](auto j) {
+      *reinterpret_cast<uint32_t*>(U + (long)(decltype(i)::value * n + decltype(j)::value) * TC +
+                                   (long)t * g.C + c4 * 4) = outw[i][j];
+    });
+  });
+}
+
+// ---------------------------------------------------------------------------
+// Output transform: one lane per (tile, 4 consecutive output channels).
+// OUT: 0 fp32 dequantised, 1 int32 numerators, 2 int8 codes.
+// ---------------------------------------------------------------------------
+template <typename MT>
+struct MTraits;
+template <>
+struct MTraits<int8_t> {
+  static constexpr int64_t in_max = 127;
+};
+template <>
+struct MTraits<int16_t> {
+  static constexpr int64_t in_max = 255;
+};
+template <>
+struct MTraits<int32_t> {
+  static constexpr int64_t in_max = kMaxAccUnquantised;
+};
+
+template <int M, bool LEG, typename MT, int OUT>
+__global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__ Mq,
+                                                          void* __restrict__ yv, Geometry g,
+                                                          StageMults mu, int relu) {
+  constexpr int n = M + 2;
+  constexpr int64_t IN_MAX = MTraits<MT>::in_max;
+  using TB = Tab<M>;
+  const int k4n = g.K >> 2;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const int t = (int)(gid / k4n);
+  const int k4 = (int)(gid - (long)t * k4n);
+  if (t >= g.T) return;
+  const int tx = t % g.TW;
+  const int ty = (t / g.TW) % g.TH;
+  const int b = t / (g.TW * g.TH);
+  const long TK = (long)g.T * g.K;
+
+  struct alignas(sizeof(MT) * 4) Quad {
+    MT v[4];
+  };
+  Quad in[n][n];
+  static_for<0, n>([&](auto i) {
+    static_for<0, n>([&](auto j) {
+      in[i][j] = *reinterpret_cast<const Quad*>(
+          Mq + (long)(decltype(i)::value * n + decltype(j)::value) * TK + (long)t * g.K + k4 * 4);
+    });
+  });
+
+  float outf[M][M][4];
+  int outi[M][M][4];
+  static_for<0, 4>([&](auto ch) {
+    int xi[n][n];
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) { xi[i][j] = (int)in[i][j].v[decltype(ch)::value]; });
+    });
+    auto finish = [&](auto& num) {
+      static_for<0, M>([&](auto i) {
+        static_for<0, M>([&](auto j) {
+          constexpr int idx = decltype(i)::value * M + decltype(j)::value;
+          if constexpr (OUT == 0) {
+            float v = (float)num[i][j] * mu.outer.v[idx];
+            outf[i][j][ch] = relu ? fmaxf(v, 0.f) : v;
+          } else if constexpr (OUT == 1) {
+            int v = (int)num[i][j];
+            outi[i][j][ch] = relu ? max(v, 0) : v;
+          } else {
+            int v = cast_code((float)num[i][j] * mu.outer.v[idx], 127.f);
+            outi[i][j][ch] = relu ? max(v, 0) : v;
+          }
+        });
+      });
+    };
+    if constexpr (LEG) {
+      acc_t<TB::PinvT, IN_MAX> num1[n][n];
+      sandwich<TB::PinvT>(xi, num1);
+      int m1[n][n];
+      cast_tile<n>(num1, mu.inner, 127.f, m1);
+      acc_t<TB::APT, 127> num2[M][M];
+      sandwich<TB::APT>(m1, num2);
+      finish(num2);
+    } else {
+      acc_t<TB::AT, IN_MAX> num[M][M];
+      sandwich<TB::AT>(xi, num);
+      finish(num);
+    }
+  });
+
+  static_for<0, M>([&](auto i) {
+    static_for<0, M>([&](auto j) {
+      const int h = ty * M + decltype(i)::value;
+      const int ww = tx * M + decltype(j)::value;
+      if (h < g.H && ww < g.W) {
+        const long off = (((long)b * g.H + h) * g.W + ww) * g.K + k4 * 4;
+        if constexpr (OUT == 0) {
+          *reinterpret_cast<float4*>(static_cast<float*>(yv) + off) =
+              make_float4(outf[i][j][0], outf[i][j][1], outf[i][j][2], outf[i][j][3]);
+        } else if constexpr (OUT == 1) {
+          *reinterpret_cast<int4*>(static_cast<int*>(yv) + off) =
+              make_int4(outi[i][j][0], outi[i][j][1], outi[i][j][2], outi[i][j][3]);
+        } else {
+          uint32_t pk = ((uint32_t)outi[i][j][0] & 0xffu) | (((uint32_t)outi[i][j][1] & 0xffu) << 8) |
+                        (((uint32_t)outi[i][j][2] & 0xffu) << 16) |
+                        (((uint32_t)outi[i][j][3] & 0xffu) << 24);
+          *reinterpret_cast<uint32_t*>(static_cast<int8_t*>(yv) + off) = pk;
+        }
+      }
+    });
+  });
+}
+
+// ---------------------------------------------------------------------------
+// Launchers of one M
+// ---------------------------------------------------------------------------
+static inline unsigned blocks_for(long items) { return (unsigned)((items + 255) / 256); }
+
+template <int M>
+hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
+                           const StageMults& mu, hipStream_t st) {
+  const unsigned nb = blocks_for((long)g.K * g.C);
+  if (leg)
+    hipLaunchKernelGGL((k_weight_transform<M, true>), dim3(nb), dim3(256), 0, st, w, V, g, mu);
+  else
+    hipLaunchKernelGGL((k_weight_transform<M, false>), dim3(nb), dim3(256), 0, st, w, V, g, mu);
+  return hipGetLastError();
+}
+
+template <int M>
+hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+                          const StageMults& mu, hipStream_t st) {
+  const unsigned nb = blocks_for((long)g.T * (g.C / 4));
+  if (leg)
+    hipLaunchKernelGGL((k_input_transform<M, true>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
+  else
+    hipLaunchKernelGGL((k_input_transform<M, false>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
+  return hipGetLastError();
+}
+
+template <int M, bool LEG, typename MT>
+static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
+                            const StageMults& mu, hipStream_t st) {
+  const unsigned nb = blocks_for((long)g.T * (g.K / 4));
+  const MT* mp = static_cast<const MT*>(Mq);
+  const int r = relu ? 1 : 0;
+  if (out_type == 0) {
+    hipLaunchKernelGGL((k_output_transform<M, LEG, MT, 0>), dim3(nb), dim3(256), 0, st, mp, y, g,
+                       mu, r);
+  } else if (out_type == 1) {
+    // integer numerators only make sense for a single integer bracket
+    if constexpr (LEG)
+      return hipErrorInvalidValue;
+    else
+      hipLaunchKernelGGL((k_output_transform<M, LEG, MT, 1>), dim3(nb), dim3(256), 0, st, mp, y,
+                         g, mu, r);
+  } else {
+    hipLaunchKernelGGL((k_output_transform<M, LEG, MT, 2>), dim3(nb), dim3(256), 0, st, mp, y, g,
+                       mu, r);
+  }
+  return hipGetLastError();
+}
+
+template <int M, bool LEG>
+static hipError_t output_m(const Geometry& g, const void* Mq, int m_bits, void* y, int out_type,
+                           bool relu, const StageMults& mu, hipStream_t st) {
+  if (m_bits == 8) return output_mt<M, LEG, int8_t>(g, Mq, y, out_type, relu, mu, st);
+  if (m_bits == 9) return output_mt<M, LEG, int16_t>(g, Mq, y, out_type, relu, mu, st);
+  return output_mt<M, LEG, int32_t>(g, Mq, y, out_type, relu, mu, st);
+}
+
+template <int M>
+hipError_t PerM<M>::output(const Geometry& g, bool leg, const void* Mq, int m_bits, void* y,
+                           int out_type, bool relu, const StageMults& mu, hipStream_t st) {
+  return leg ? output_m<M, true>(g, Mq, m_bits, y, out_type, relu, mu, st)
+             : output_m<M, false>(g, Mq, m_bits, y, out_type, relu, mu, st);
+}
+
+}  // namespace wino

@@ -1,0 +1,94 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI.
+
+Bar: int8 transformed tensors (V, U), contraction results (int32, and the
+8 / 9-bit codes) and integer outputs bit-exact; dequantised fp32 outputs within
+max abs error 1e-5 * max|y_oracle|.
+"""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import quantised as oq
+from helpers import assert_layer_parity, gpu_layer, oracle_layer, small_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(xq, wq, s_x, s_w, whole=False, **kw):
+    ora, sc = oracle_layer(xq, wq, s_x, s_w, **kw)
+    got = gpu_layer(xq, wq, sc, whole=whole, **kw)
+    assert_layer_parity(ora, got, kw.get("out_type", "f32"))
+    return ora, got, sc
+
+
+@pytest.mark.parametrize("name", ["cfg1_f2_canonical", "cfg1_f2_legendre"])
+def test_cfg1(name):
+    wl = si.WORKLOADS[name]
+    L = si.make_layer(wl)
+    run_case(L["xq"], L["wq"], L["s_x"], L["s_w"], m=wl.m, base=wl.base)
+    run_case(L["xq"], L["wq"], L["s_x"], L["s_w"], m=wl.m, base=wl.base, whole=True)
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+@pytest.mark.parametrize("base", ["canonical", "legendre"])
+@pytest.mark.parametrize("bits_hadamard", [8, 9, 32])
+def test_small_ragged_all_variants(m, base, bits_hadamard):
+    # several tiles per image, ragged bottom/right edge, tile and channel
+    # counts that are not multiples of the kernels' block sizes
+    xq, wq, s_x, s_w = small_layer(3, 9, 7, 48, 80, seed=20 + m)
+    run_case(xq, wq, s_x, s_w, m=m, base=base, bits_hadamard=bits_hadamard)
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_int8_output_with_relu_and_whole_layer_call(m):
+    xq, wq, s_x, s_w = small_layer(2, 8, 8, 32, 32, seed=31)
+    for base in ("canonical", "legendre"):
+        run_case(xq, wq, s_x, s_w, m=m, base=base, out_type="i8", relu=True, whole=True)
+        run_case(xq, wq, s_x, s_w, m=m, base=base, out_type="f32", relu=True)
+
+
+@pytest.mark.parametrize("m", [2, 4])
+def test_int32_output_canonical(m):
+    xq, wq, s_x, s_w = small_layer(2, 8, 8, 32, 32, seed=32)
+    run_case(xq, wq, s_x, s_w, m=m, base="canonical", out_type="i32")
+    run_case(xq, wq, s_x, s_w, m=m, base="canonical", out_type="i32", bits_hadamard=32)
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_legendre_without_inner_casts_equals_canonical_on_gpu(m):
+    xq, wq, s_x, s_w = small_layer(2, 8, 8, 32, 32, seed=33)
+    ora, got, sc = run_case(xq, wq, s_x, s_w, m=m, base="legendre", inner_quant=False)
+    can = gpu_layer(xq, wq, sc, m=m, base="canonical")
+    for key in ("V", "U", "M", "y"):
+        assert np.array_equal(can[key], got[key])
+
+
+def test_degenerate_shapes():
+    # one pixel, one tile; and an image smaller than a tile with m = 6
+    for (N, H, W, m) in [(1, 1, 1, 4), (2, 4, 4, 6), (1, 2, 3, 2)]:
+        xq, wq, s_x, s_w = small_layer(N, H, W, 16, 16, seed=34)
+        run_case(xq, wq, s_x, s_w, m=m, base="legendre")
+
+
+def test_saturating_scales_clamp_symmetrically():
+    xq, wq, s_x, s_w = small_layer(1, 8, 8, 16, 16, seed=35)
+    ora, sc = oracle_layer(xq, wq, s_x, s_w, m=4, base="legendre")
+    tight = {k: (np.float32(v * 0.25) if k in ("s_u", "s_v", "s_m", "s_x1") else v)
+             for k, v in sc.items()}
+    ora2, _ = oq.run_layer(xq, wq, s_x, s_w, oq.LayerConfig(m=4), scales=tight)
+    got = gpu_layer(xq, wq, tight, m=4, base="legendre")
+    assert_layer_parity(ora2, got)
+    assert got["U"].min() == -127 and got["U"].max() == 127
+
+
+FULL = ["cfg2_f4_c64", "cfg3_f4_c128_h9", "cfg4a_f4_c256", "cfg4b_f4_c512", "cfg4a_f6_c256",
+        "cfg4b_f6_c512"]
+
+
+@pytest.mark.parametrize("name", FULL)
+def test_full_size_configurations(name):
+    """The benchmark shapes, whole-layer call, every element compared."""
+    wl = si.WORKLOADS[name]
+    L = si.make_layer(wl)
+    run_case(L["xq"], L["wq"], L["s_x"], L["s_w"], whole=True, m=wl.m, base=wl.base,
+             bits_hadamard=wl.bits_hadamard)
