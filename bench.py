@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantised Legendre-base Winograd convolution layer on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input:
+weight transform, input transform, per-point int8 MFMA contraction and output
+transform of one 3x3 layer, inputs resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
+
+
+def stage_model(wl, m_bytes, y_bytes):
+    """Algorithmic work of one launch of each stage (bytes or int8 ops)."""
+    n = wl.m + 2
+    T, C, K = wl.tiles, wl.C, wl.K
+    return {
+        # per (k, c): 9 filter bytes in, n*n transformed bytes out
+        "weight_transform": {"bound": "hbm", "work": K * C * (9 + n * n)},
+        # per (tile, c): m*m fresh input bytes in, n*n transformed bytes out
+        "input_transform": {"bound": "hbm", "work": T * C * (wl.m * wl.m + n * n)},
+        # Winograd-domain multiply-accumulates actually issued, 2 ops each
+        "contraction": {"bound": "mfma", "work": 2 * n * n * T * C * K},
+        # per (tile, k): n*n contraction results in, m*m outputs out
+        "output_transform": {"bound": "hbm",
+                             "work": T * K * (n * n * m_bytes + wl.m * wl.m * y_bytes)},
+    }
+
+
+def cpu_baseline(wl):
+    """The oracle, as it stands, timed once on the host cores on the full workload."""
+    import synth_inputs as si
+    from oracle import quantised as oq
+    L = si.make_layer(wl)
+    cfg = oq.LayerConfig(m=wl.m, base=wl.base, bits_hadamard=wl.bits_hadamard)
+    t0 = time.perf_counter()
+    oq.run_layer(L["xq"], L["wq"], L["s_x"], L["s_w"], cfg,
+                 scales=si.workload_scales(wl.name))
+    dt = time.perf_counter() - t0
+    ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": 1, "kind": "oracle",
+            "sample": "full workload %s, one pass, %.2f s (numpy int64, single thread)"
+                      % (wl.name, dt),
+            "host_cpus": len(os.sched_getaffinity(0))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg4a_f4_c256")
+    ap.add_argument("--batch-scale", type=int, default=1,
+                    help="multiply the batch size N (extra, labelled in config)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; a layer shards over the batch "
+              "with no exchange step, so N GPUs would run N independent copies. "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synth_inputs as si
+    import paper_2004_11077_amd as wn
+
+    wl = si.WORKLOADS[args.workload]
+    scales = si.workload_scales(wl.name)
+    if args.batch_scale != 1:
+        wl = si.Workload(**{**wl.__dict__, "N": wl.N * args.batch_scale})
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    L = si.make_layer(si.WORKLOADS[args.workload])
+    reps = args.batch_scale
+    x = torch.from_numpy(L["xq"]).to(dev).repeat(reps, 1, 1, 1).contiguous()
+    w = torch.from_numpy(L["wq"]).to(dev)
+    base = wn.BASE_LEGENDRE if wl.base == "legendre" else wn.BASE_CANONICAL
+    desc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                       bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32)
+    sc = wn.Scales.from_dict(scales)
+    n2, T = desc.n ** 2, desc.tiles
+    mdt = {8: torch.int8, 9: torch.int16, 32: torch.int32}[wl.bits_hadamard]
+    V = torch.empty((n2, wl.K, wl.C), dtype=torch.int8, device=dev)
+    U = torch.empty((n2, T, wl.C), dtype=torch.int8, device=dev)
+    M = torch.empty((n2, T, wl.K), dtype=mdt, device=dev)
+    y = torch.empty((wl.N, wl.H, wl.W, wl.K), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    names = ["weight_transform", "input_transform", "contraction", "output_transform"]
+
+    def step(events=None):
+        if events is not None:
+            events[0].record(stream)
+        wn.wino_weight_transform(desc, w, V, sc, stream)
+        if events is not None:
+            events[1].record(stream)
+        wn.wino_input_transform(desc, x, U, sc, stream)
+        if events is not None:
+            events[2].record(stream)
+        wn.wino_contract(desc, U, V, M, sc, stream)
+        if events is not None:
+            events[3].record(stream)
+        wn.wino_output_transform(desc, M, y, sc, stream)
+        if events is not None:
+            events[4].record(stream)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(evs[i])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    stage_ms = {nm: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1])
+                                   for i in range(args.steps)]))
+                for j, nm in enumerate(names)}
+    model = stage_model(wl, M.element_size(), y.element_size())
+    stages = {}
+    for nm in names:
+        sec = stage_ms[nm] * 1e-3
+        if model[nm]["bound"] == "hbm":
+            ach, peak, unit = model[nm]["work"] / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+        else:
+            ach, peak, unit = model[nm]["work"] / sec / 1e12, INT8_MFMA_PEAK_TOPS, "TOP/s"
+        stages[nm] = {"ms": stage_ms[nm], "bound": model[nm]["bound"], "achieved": ach,
+                      "peak": peak, "unit": unit, "frac": ach / peak}
+    dominant = max(names, key=lambda nm: stage_ms[nm])
+    roofline = {k: stages[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
+    roofline["kernel"] = dominant
+    roofline["traffic"] = None
+
+    ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
+    ms_per_step = dt / args.steps * 1e3
+    out = {
+        "metric": "int8 Winograd conv TOPS (direct-equiv)",
+        "value": ops / (dt / args.steps) / 1e12,
+        "unit": "TOPS",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int8", "data": "synthetic",
+        "config": {"workload": wl.name + ("" if reps == 1 else "_batchx%d" % reps),
+                   "N": wl.N, "H": wl.H, "W": wl.W, "C": wl.C, "K": wl.K,
+                   "algorithm": "F(%dx%d,3x3) %s base" % (wl.m, wl.m, wl.base),
+                   "bits_hadamard": wl.bits_hadamard, "output": "fp32",
+                   "step": "weight+input transform, contraction, output transform"},
+        "roofline": roofline,
+        "stages": stages,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(si.WORKLOADS[args.workload])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

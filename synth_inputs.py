@@ -78,3 +78,13 @@ def make_layer(wl):
     xq, s_x = cast_int8(x)
     wq, s_w = cast_int8(w)
     return {"x": x, "w": w, "xq": xq, "wq": wq, "s_x": s_x, "s_w": s_w}
+
+
+def workload_scales(name):
+    """Caller-supplied scales of a benchmark workload (float values of float32
+    scales), read from workload_scales.json beside this file."""
+    import json
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "workload_scales.json")
+    with open(path) as f:
+        return json.load(f)[name]
