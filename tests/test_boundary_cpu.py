@@ -1,0 +1,123 @@
+"""CPU-only checks of the C-ABI boundary: exports, host matrix builder, error paths.
+
+No kernel is launched here; calls that would reach the GPU are only made with
+arguments that the host-side validation rejects first.
+"""
+import ctypes as C
+import os
+import re
+from fractions import Fraction
+
+import pytest
+
+from oracle import matrices as mx
+
+wn = pytest.importorskip("paper_2004_11077_amd")
+from paper_2004_11077_amd import binding  # noqa: E402
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+pytestmark = pytest.mark.skipif(not os.path.exists(wn.lib_path()),
+                                reason="libwino.so not built (python -m paper_2004_11077_amd.build)")
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "wino.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(wino_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = C.CDLL(wn.lib_path())
+    names = declared_symbols()
+    assert len(names) >= 11
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(binding.EXPORTS)
+
+
+ORACLE_NAMES = {"G": "G", "BT": "BT", "AT": "AT", "PT": "PT", "PINVT": "PinvT", "GP": "GP",
+                "BPT": "BPT", "APT": "APT"}
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_make_matrices_equals_oracle(m):
+    got = wn.wino_make_matrices(m, 3, mx.POINTS[m], wn.BASE_LEGENDRE)
+    ora = mx.Matrices(m, 3)
+    for name, oname in ORACLE_NAMES.items():
+        assert getattr(got, name) == getattr(ora, oname), name
+        N, rho = got.int_form(name)
+        assert (N, rho) == mx.int_form(getattr(ora, oname)), name
+
+
+def test_make_matrices_canonical_base_has_identity_P():
+    got = wn.wino_make_matrices(4, 3, mx.POINTS[4], wn.BASE_CANONICAL)
+    assert got.PT == mx.identity(6) and got.PINVT == mx.identity(6)
+    assert got.GP == got.G and got.BPT == got.BT and got.APT == got.AT
+
+
+@pytest.mark.parametrize("m,r,pts", [(3, 2, [0, 1, -1]), (2, 5, [0, 1, -1, 2, -2]),
+                                     (4, 3, [0, 1, -1, Fraction(1, 2), -2]), (1, 1, []),
+                                     (3, 3, [0, 1, -1, Fraction(3, 2)])])
+def test_make_matrices_other_sizes_and_points(m, r, pts):
+    got = wn.wino_make_matrices(m, r, pts, wn.BASE_LEGENDRE)
+    AT, G, BT = mx.toom_cook(m, r, pts)
+    assert (got.AT, got.G, got.BT) == (AT, G, BT)
+    PT = mx.legendre_PT(m + r - 1)
+    assert got.PT == PT and got.PINVT == mx.inverse(PT)
+
+
+def test_make_matrices_error_codes():
+    for args, code in [((4, 3, [0, 1, 1, 2, -2]), -1),          # duplicate point
+                       ((4, 3, [0, 1, -1]), -1),                 # wrong point count
+                       ((0, 3, [0]), -1),                        # m < 1
+                       ((7, 3, list(range(8))), -2),             # n = 9 > 8
+                       ((6, 3, [0, 10**6, -10**6, 10**7, -10**7, 10**8, -10**8]), -3)]:
+        with pytest.raises(wn.WinoError) as e:
+            wn.wino_make_matrices(*args)
+        assert e.value.code == code, args
+    lib = binding._load()
+    pts = (binding._Rat * 3)(binding._Rat(0, 1), binding._Rat(1, 0), binding._Rat(2, 1))
+    h = C.c_void_p()
+    assert lib.wino_make_matrices(2, 3, pts, 3, 1, C.byref(h)) == -1      # zero denominator
+    assert b"denominator" in lib.wino_last_error()
+    assert lib.wino_make_matrices(2, 3, pts, 3, 1, None) == -1
+
+
+def test_workspace_bytes_and_descriptor_validation():
+    d = wn.ConvDesc(256, 8, 8, 256, 256, m=4)
+    n2, T = 36, 1024
+    r256 = lambda v: (v + 255) // 256 * 256
+    assert wn.wino_workspace_bytes(d) == r256(n2 * 256 * 256) + 2 * r256(n2 * T * 256)
+    d9 = wn.ConvDesc(256, 8, 8, 256, 256, m=4, bits_hadamard=9, weights_pretransformed=1)
+    assert wn.wino_workspace_bytes(d9) == r256(n2 * T * 256) + r256(n2 * T * 256 * 2)
+    for kw, code in [(dict(m=3), -2), (dict(m=4, r=5), -2), (dict(bits_hadamard=7), -2),
+                     (dict(bits_in=16), -2), (dict(base=5), -1), (dict(out_type=9), -1),
+                     (dict(out_type=wn.OUT_I32), -2),            # Legendre has no integer A_P^T
+                     (dict(m=6, base=wn.BASE_CANONICAL, out_type=wn.OUT_I32), -2)]:
+        with pytest.raises(wn.WinoError) as e:
+            wn.wino_workspace_bytes(wn.ConvDesc(1, 8, 8, 16, 16, **kw))
+        assert e.value.code == code, kw
+    for shape in [(1, 8, 8, 12, 16), (1, 8, 8, 16, 24), (-1, 8, 8, 16, 16)]:
+        with pytest.raises(wn.WinoError) as e:
+            wn.wino_workspace_bytes(wn.ConvDesc(*shape))
+        assert e.value.code == -1
+    with pytest.raises(wn.WinoError) as e:                       # C too large for exact fp32
+        wn.wino_workspace_bytes(wn.ConvDesc(1, 8, 8, 2048, 16, bits_hadamard=32))
+    assert e.value.code == -3
+
+
+def test_stage_calls_reject_bad_arguments_before_any_launch():
+    lib = binding._load()
+    d = wn.ConvDesc(1, 8, 8, 16, 16)
+    s = wn.Scales.from_dict({})
+    assert lib.wino_input_transform(C.byref(d), None, None, C.byref(s), None) == -1
+    assert b"null pointer" in lib.wino_last_error()
+    bad = wn.Scales.from_dict({"s_u": 0.0})
+    fake = C.c_void_p(4096)      # never dereferenced: the scale check fails first
+    assert lib.wino_input_transform(C.byref(d), fake, fake, C.byref(bad), None) == -1
+    assert lib.wino_contract(C.byref(d), C.c_void_p(4100), fake, fake, C.byref(s), None) == -1
+    assert b"aligned" in lib.wino_last_error()
+    assert lib.wino_conv2d(C.byref(d), fake, fake, fake, C.byref(s), fake, 16, None) == -4
+    dfused = wn.ConvDesc(1, 8, 8, 16, 16, bits_in=32)
+    assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(s), fake, 1 << 30, None) == -2
