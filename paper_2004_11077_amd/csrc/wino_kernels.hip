@@ -7,72 +7,169 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 // One symmetric cast: round to nearest even, clamp to +-qmax.
+// (clamp first, then the 1.5 * 2^23 trick: the fp32 add rounds to nearest even)
 __device__ __forceinline__ int cast_code(float v, float qmax) {
-  v = rintf(v);
-  v = fminf(fmaxf(v, -qmax), qmax);
-  return (int)v;
+  v = __builtin_amdgcn_fmed3f(v, -qmax, qmax);
+  return __float_as_int(v + 12582912.0f) - 0x4B400000;
 }
 
 // ---------------------------------------------------------------------------
-// Contraction: per Winograd point p, M[p][t][k] = sum_c U[p][t][c] V[p][k][c].
-// One wave computes a 32(k) x 32(t) block with the 32x32x32 int8 MFMA; the A
-// operand is V (rows k), the B operand U (rows t), so that a lane ends up with
-// four consecutive k of one tile per accumulator quad.
+// Contraction: per Winograd point p, M[p][t][k] = sum_c U[p][t][c] V[p][k][c],
+// a batch of n*n int8 GEMMs (the only dense contraction of the path, hence
+// the only MFMA user).
+//
+// Work group = 4 waves, output block 128 (t) x 128 (k); the channel dimension
+// is consumed in chunks of 128 bytes staged through LDS (rows padded by 16 B:
+// eight consecutive rows then cover all banks for the 16-byte fragment reads),
+// with the next chunk prefetched into registers while the current one feeds
+// the MFMAs.  Each wave owns 64 x 64 outputs as 2 x 2 blocks of the 32x32x32
+// int8 MFMA.  The A operand is V (rows k), the B operand U (rows t), so a lane
+// ends up with four consecutive k of one tile per accumulator quad.
+// int8 results are transposed through LDS so that global stores are full
+// 128-byte rows; the wider int16 / int32 results are stored from registers.
+//
+// Blocks are numbered so that all blocks sharing a (point, k block) -- i.e. the
+// same slice of V and the same U[p] -- run on the same XCD (consecutive work
+// group ids go round-robin over the 8 XCDs, each with a private L2).
 // ---------------------------------------------------------------------------
+constexpr int kTT = 128, kKT = 128, kCK = 128, kRow = kCK + 16;
+
 template <typename MT>
 __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
                                                   const int8_t* __restrict__ V,
                                                   MT* __restrict__ Mo, int T, int C, int K,
-                                                  int tblocks, float mult, float qmax) {
-  const int p = blockIdx.y;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int tb = blockIdx.x % tblocks, kb = blockIdx.x / tblocks;
-  const int t0 = tb * 64 + (wave & 1) * 32;
-  const int k0 = kb * 64 + (wave >> 1) * 32;
-  if (t0 >= T || k0 >= K) return;          // whole wave out of range
+                                                  int tblocks, int kblocks, int units, float mult,
+                                                  float qmax) {
+  __shared__ __attribute__((aligned(16))) int8_t smem[(kKT + kTT) * kRow];
+  int8_t* sA = smem;                  // V rows (k)
+  int8_t* sB = smem + kKT * kRow;     // U rows (t)
+
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int unit = (slot / tblocks) * 8 + xcd;
+  if (unit >= units) return;
+  const int tb = slot % tblocks;
+  const int p = unit / kblocks, kb = unit - p * kblocks;
+  const int t0 = tb * kTT, k0 = kb * kKT;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int wt = wave & 1, wk = wave >> 1;
   const int r = lane & 31, h = lane >> 5;
-  const int t = t0 + r, k = k0 + r;
-  const int tl = t < T ? t : T - 1;        // clamp loads, mask stores
-  const int kl = k < K ? k : K - 1;
-  const int8_t* up = U + ((long)p * T + tl) * C + h * 16;
-  const int8_t* vp = V + ((long)p * K + kl) * C + h * 16;
-  v16i acc = {};
-  for (int c0 = 0; c0 < C; c0 += 32) {
-    v4i a = {}, bq = {};
-    if (c0 + h * 16 < C) {
-      a = *reinterpret_cast<const v4i*>(vp + c0);
-      bq = *reinterpret_cast<const v4i*>(up + c0);
-    }
-    acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, bq, acc, 0, 0, 0);
+
+  // staging map: 8 lanes cover one 128-byte row chunk, 4 rows per 32 lanes
+  const int srow = tid >> 3, sseg = (tid & 7) * 16;
+  const int8_t* ga[4];
+  const int8_t* gb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int row = srow + i * 32;
+    const int kr = min(k0 + row, K - 1), tr = min(t0 + row, T - 1);   // clamp, mask later
+    ga[i] = V + ((long)p * K + kr) * C + sseg;
+    gb[i] = U + ((long)p * T + tr) * C + sseg;
   }
-  // acc[4*g+v] = D[row = 8*g + 4*h + v][col = r]  ->  k = k0 + row, tile t0 + r
-  if (t >= T) return;
-  MT* mrow = Mo + ((long)p * T + t) * K;
+  v4i ra[4], rb[4];
+  auto fetch = [&](int c0) {
+    const bool ok = c0 + sseg < C;
 #pragma unroll
-  for (int gq = 0; gq < 4; ++gq) {
-    const int kk = k0 + 8 * gq + 4 * h;
-    if (kk >= K) continue;
-    int q[4];
+    for (int i = 0; i < 4; ++i) {
+      ra[i] = ok ? *reinterpret_cast<const v4i*>(ga[i] + c0) : v4i{0, 0, 0, 0};
+      rb[i] = ok ? *reinterpret_cast<const v4i*>(gb[i] + c0) : v4i{0, 0, 0, 0};
+    }
+  };
+
+  v16i acc[2][2];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      if constexpr (sizeof(MT) == 4)
-        q[v] = acc[4 * gq + v];
-      else
-        q[v] = cast_code((float)acc[4 * gq + v] * mult, qmax);
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = v16i{};
+
+  fetch(0);
+  for (int c0 = 0; c0 < C; c0 += kCK) {
+    if (c0) __syncthreads();             // previous chunk fully consumed
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<v4i*>(sA + (srow + i * 32) * kRow + sseg) = ra[i];
+      *reinterpret_cast<v4i*>(sB + (srow + i * 32) * kRow + sseg) = rb[i];
     }
-    if constexpr (sizeof(MT) == 1) {
-      uint32_t pk = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
-                    (((uint32_t)q[2] & 0xffu) << 16) | (((uint32_t)q[3] & 0xffu) << 24);
-      *reinterpret_cast<uint32_t*>(mrow + kk) = pk;
-    } else if constexpr (sizeof(MT) == 2) {
-      uint2 pk;
-      pk.x = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
-      pk.y = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
-      *reinterpret_cast<uint2*>(mrow + kk) = pk;
-    } else {
-      int4 pk = make_int4(q[0], q[1], q[2], q[3]);
-      *reinterpret_cast<int4*>(mrow + kk) = pk;
+    __syncthreads();
+    if (c0 + kCK < C) fetch(c0 + kCK);
+#pragma unroll
+    for (int ks = 0; ks < kCK / 32; ++ks) {
+      v4i fa[2], fb[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        fa[i] = *reinterpret_cast<const v4i*>(sA + (wk * 64 + i * 32 + r) * kRow + ks * 32 + h * 16);
+        fb[i] = *reinterpret_cast<const v4i*>(sB + (wt * 64 + i * 32 + r) * kRow + ks * 32 + h * 16);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
+  }
+
+  // acc[i][j][4*g+v] = D[k = 32 i + 8 g + 4 h + v][t = 32 j + r] within the wave's 64 x 64
+  if constexpr (sizeof(MT) == 1) {
+    __syncthreads();                     // LDS is reused as the [t][k] output block
+    uint32_t* so = reinterpret_cast<uint32_t*>(smem);
+    constexpr int kORow = kKT / 4 + 1;   // dwords per row, +1 against bank conflicts
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          uint32_t pk = 0;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int q = cast_code((float)acc[i][j][4 * gq + v] * mult, qmax);
+            pk |= ((uint32_t)q & 0xffu) << (8 * v);
+          }
+          const int tl = wt * 64 + j * 32 + r;
+          const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
+          so[tl * kORow + (kl >> 2)] = pk;
+        }
+    __syncthreads();
+    const int kq = tid & 31;             // dword within the 128-byte row
+    if (k0 + kq * 4 < K) {
+#pragma unroll
+      for (int it = 0; it < kTT / 8; ++it) {
+        const int tl = it * 8 + (tid >> 5);
+        if (t0 + tl < T)
+          *reinterpret_cast<uint32_t*>(Mo + ((long)p * T + t0 + tl) * K + k0 + kq * 4) =
+              so[tl * kORow + kq];
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int t = t0 + wt * 64 + j * 32 + r;
+        if (t >= T) continue;
+        MT* mrow = Mo + ((long)p * T + t) * K;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          const int kk = k0 + wk * 64 + i * 32 + 8 * gq + 4 * h;
+          if (kk >= K) continue;
+          int q[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            if constexpr (sizeof(MT) == 4)
+              q[v] = acc[i][j][4 * gq + v];
+            else
+              q[v] = cast_code((float)acc[i][j][4 * gq + v] * mult, qmax);
+          }
+          if constexpr (sizeof(MT) == 2) {
+            uint2 pk;
+            pk.x = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
+            pk.y = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
+            *reinterpret_cast<uint2*>(mrow + kk) = pk;
+          } else {
+            *reinterpret_cast<int4*>(mrow + kk) = make_int4(q[0], q[1], q[2], q[3]);
+          }
+        }
+      }
   }
 }
 
@@ -102,17 +199,20 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
                            int m_bits, float mult, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
   const int n = g.m + 2;
-  const int tblocks = (g.T + 63) / 64, kblocks = (g.K + 63) / 64;
-  dim3 grid((unsigned)(tblocks * kblocks), (unsigned)(n * n));
+  const int tblocks = (g.T + kTT - 1) / kTT, kblocks = (g.K + kKT - 1) / kKT;
+  const int units = n * n * kblocks;                 // (point, k block) pairs
+  const long nblocks = (long)((units + 7) / 8) * 8 * tblocks;
+  if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
+  dim3 grid((unsigned)nblocks);
   if (m_bits == 8)
     hipLaunchKernelGGL((k_contract<int8_t>), grid, dim3(256), 0, st, U, V, (int8_t*)Mo, g.T, g.C,
-                       g.K, tblocks, mult, 127.f);
+                       g.K, tblocks, kblocks, units, mult, 127.f);
   else if (m_bits == 9)
     hipLaunchKernelGGL((k_contract<int16_t>), grid, dim3(256), 0, st, U, V, (int16_t*)Mo, g.T,
-                       g.C, g.K, tblocks, mult, 255.f);
+                       g.C, g.K, tblocks, kblocks, units, mult, 255.f);
   else
     hipLaunchKernelGGL((k_contract<int32_t>), grid, dim3(256), 0, st, U, V, (int32_t*)Mo, g.T,
-                       g.C, g.K, tblocks, mult, 0.f);
+                       g.C, g.K, tblocks, kblocks, units, mult, 0.f);
   return hipGetLastError();
 }
 

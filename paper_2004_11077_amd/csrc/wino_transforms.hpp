@@ -26,18 +26,45 @@ __device__ __forceinline__ void static_for(F&& f) {
   }
 }
 
-// num = N x N^T with N the compile-time integer matrix T.N (T.rows x T.cols).
-// Zero coefficients generate no code.
-template <const IMat& T, typename AccT, typename InT>
+// The 24-bit signed multiply (full rate, v_mul_i32_i24 / v_mad_i32_i24): the
+// low 32 bits of the product of the operands' low 24 bits.
+extern "C" __device__ int llvm_mul_i24(int, int) __asm("llvm.amdgcn.mul.i24.i32");
+
+// x * c for a compile-time coefficient.  S24: the caller proved |x| < 2^23, so
+// the full-rate 24-bit multiplier gives the exact product.
+template <int64_t CF, bool S24>
+__device__ __forceinline__ int32_t mulc(int32_t x) {
+  constexpr int64_t a = CF < 0 ? -CF : CF;
+  if constexpr (CF == 1)
+    return x;
+  else if constexpr (CF == -1)
+    return -x;
+  else if constexpr ((a & (a - 1)) == 0)
+    return x * (int32_t)CF;                      // shift
+  else if constexpr (S24 && a < (1 << 23))
+    return llvm_mul_i24(x, (int32_t)CF);
+  else
+    return x * (int32_t)CF;
+}
+template <int64_t CF, bool S24>
+__device__ __forceinline__ int64_t mulc(int64_t x) {
+  return x * CF;
+}
+
+// num = N x N^T with N the compile-time integer matrix T.N (T.rows x T.cols)
+// and |x| <= IN_MAX.  Zero coefficients generate no code.
+template <const IMat& T, int64_t IN_MAX, typename AccT, typename InT>
 __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
                                          AccT (&num)[T.rows][T.rows]) {
+  constexpr bool s1 = IN_MAX < (1 << 23);
+  constexpr bool s2 = (__int128)IN_MAX * T.rowsum < (1 << 23);
   AccT tmp[T.rows][T.cols];
   static_for<0, T.rows>([&](auto i) {
     static_for<0, T.cols>([&](auto b) {
       AccT acc = 0;
       static_for<0, T.cols>([&](auto a) {
         constexpr int64_t c = T.N[decltype(i)::value][decltype(a)::value];
-        if constexpr (c != 0) acc += (AccT)c * (AccT)x[a][b];
+        if constexpr (c != 0) acc += mulc<c, s1>((AccT)x[a][b]);
       });
       tmp[i][b] = acc;
     });
@@ -47,18 +74,20 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
       AccT acc = 0;
       static_for<0, T.cols>([&](auto b) {
         constexpr int64_t c = T.N[decltype(j)::value][decltype(b)::value];
-        if constexpr (c != 0) acc += (AccT)c * tmp[i][b];
+        if constexpr (c != 0) acc += mulc<c, s2>(tmp[i][b]);
       });
       num[i][j] = acc;
     });
   });
 }
 
-// One symmetric cast: round to nearest even, clamp to +-qmax.
+// One symmetric cast, q = clamp(rint(v), +-qmax) with rint = round half to
+// even.  Clamping first is equivalent (the bounds are integers and rint is
+// monotone); adding 1.5 * 2^23 then leaves the rounded integer in the low
+// mantissa bits (the fp32 add itself rounds to nearest even), for |v| < 2^22.
 __device__ __forceinline__ int cast_code(float v, float qmax) {
-  v = rintf(v);
-  v = fminf(fmaxf(v, -qmax), qmax);
-  return (int)v;
+  v = __builtin_amdgcn_fmed3f(v, -qmax, qmax);
+  return __float_as_int(v + 12582912.0f) - 0x4B400000;
 }
 
 template <int R, typename AccT>
@@ -91,15 +120,15 @@ __global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restri
   int q[n][n];
   if constexpr (LEG) {
     acc_t<TB::GP, 127> num1[n][n];
-    sandwich<TB::GP>(wi, num1);
+    sandwich<TB::GP, 127>(wi, num1);
     int w1[n][n];
     cast_tile<n>(num1, mu.inner, 127.f, w1);
     acc_t<TB::Pinv, 127> num2[n][n];
-    sandwich<TB::Pinv>(w1, num2);
+    sandwich<TB::Pinv, 127>(w1, num2);
     cast_tile<n>(num2, mu.outer, 127.f, q);
   } else {
     acc_t<TB::G, 127> num[n][n];
-    sandwich<TB::G>(wi, num);
+    sandwich<TB::G, 127>(wi, num);
     cast_tile<n>(num, mu.outer, 127.f, q);
   }
   static_for<0, n>([&](auto i) {
@@ -110,7 +139,9 @@ __global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restri
 }
 
 // ---------------------------------------------------------------------------
-// Input transform: one lane per (tile, 4 consecutive channels).
+// Input transform: one lane per (tile, channel); a wave covers 64 consecutive
+// channels, so every load and store instruction moves one contiguous run.
+// Out-of-image pixels are read from a clamped in-bounds address and zeroed.
 // ---------------------------------------------------------------------------
 template <int M, bool LEG>
 __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
@@ -118,69 +149,59 @@ __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restric
                                                          StageMults mu) {
   constexpr int n = M + 2;
   using TB = Tab<M>;
-  const int c4n = g.C >> 2;
   const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  const int t = (int)(gid / c4n);
-  const int c4 = (int)(gid - (long)t * c4n);
+  const int t = (int)(gid / g.C);
+  const int c = (int)(gid - (long)t * g.C);
   if (t >= g.T) return;
   const int tx = t % g.TW;
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
+  const int8_t* xb = x + (long)b * g.H * g.W * g.C + c;
 
-  uint32_t in[n][n];
+  int roff[n], coff[n];
+  bool rok[n], cok[n];
+  static_for<0, n>([&](auto a) {
+    const int h = ty * M - 1 + decltype(a)::value;
+    const int ww = tx * M - 1 + decltype(a)::value;
+    rok[a] = h >= 0 && h < g.H;
+    cok[a] = ww >= 0 && ww < g.W;
+    roff[a] = min(max(h, 0), g.H - 1) * g.W * g.C;
+    coff[a] = min(max(ww, 0), g.W - 1) * g.C;
+  });
+  int xi[n][n];
   static_for<0, n>([&](auto a) {
     static_for<0, n>([&](auto bb) {
-      const int h = ty * M - 1 + decltype(a)::value;
-      const int ww = tx * M - 1 + decltype(bb)::value;
-      uint32_t v = 0;
-      if (h >= 0 && h < g.H && ww >= 0 && ww < g.W)
-        v = *reinterpret_cast<const uint32_t*>(x + (((long)b * g.H + h) * g.W + ww) * g.C + c4 * 4);
-      in[a][bb] = v;
+      const int v = xb[roff[a] + coff[bb]];
+      xi[a][bb] = (rok[a] && cok[bb]) ? v : 0;
     });
   });
 
-  uint32_t outw[n][n];
-  static_for<0, n>([&](auto i) { static_for<0, n>([&](auto j) { outw[i][j] = 0; }); });
-
-  static_for<0, 4>([&](auto ch) {
-    int xi[n][n];
-    static_for<0, n>([&](auto a) {
-      static_for<0, n>([&](auto bb) {
-        xi[a][bb] = (int)(int8_t)(in[a][bb] >> (8 * decltype(ch)::value));
-      });
-    });
-    int q[n][n];
-    if constexpr (LEG) {
-      acc_t<TB::PinvT, 127> num1[n][n];
-      sandwich<TB::PinvT>(xi, num1);
-      int x1[n][n];
-      cast_tile<n>(num1, mu.inner, 127.f, x1);
-      acc_t<TB::BPT, 127> num2[n][n];
-      sandwich<TB::BPT>(x1, num2);
-      cast_tile<n>(num2, mu.outer, 127.f, q);
-    } else {
-      acc_t<TB::BT, 127> num[n][n];
-      sandwich<TB::BT>(xi, num);
-      cast_tile<n>(num, mu.outer, 127.f, q);
-    }
-    static_for<0, n>([&](auto i) {
-      static_for<0, n>([&](auto j) {
-        outw[i][j] |= ((uint32_t)q[i][j] & 0xffu) << (8 * decltype(ch)::value);
-      });
-    });
-  });
+  int q[n][n];
+  if constexpr (LEG) {
+    acc_t<TB::PinvT, 127> num1[n][n];
+    sandwich<TB::PinvT, 127>(xi, num1);
+    int x1[n][n];
+    cast_tile<n>(num1, mu.inner, 127.f, x1);
+    acc_t<TB::BPT, 127> num2[n][n];
+    sandwich<TB::BPT, 127>(x1, num2);
+    cast_tile<n>(num2, mu.outer, 127.f, q);
+  } else {
+    acc_t<TB::BT, 127> num[n][n];
+    sandwich<TB::BT, 127>(xi, num);
+    cast_tile<n>(num, mu.outer, 127.f, q);
+  }
 
   const long TC = (long)g.T * g.C;
+  int8_t* ub = U + (long)t * g.C + c;
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
-      *reinterpret_cast<uint32_t*>(U + (long)(decltype(i)::value * n + decltype(j)::value) * TC +
-                                   (long)t * g.C + c4 * 4) = outw[i][j];
+      ub[(long)(decltype(i)::value * n + decltype(j)::value) * TC] = (int8_t)q[i][j];
     });
   });
 }
 
 // ---------------------------------------------------------------------------
-// Output transform: one lane per (tile, 4 consecutive output channels).
+// Output transform: one lane per (tile, output channel).
 // OUT: 0 fp32 dequantised, 1 int32 numerators, 2 int8 codes.
 // ---------------------------------------------------------------------------
 template <typename MT>
@@ -205,87 +226,58 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   constexpr int n = M + 2;
   constexpr int64_t IN_MAX = MTraits<MT>::in_max;
   using TB = Tab<M>;
-  const int k4n = g.K >> 2;
   const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  const int t = (int)(gid / k4n);
-  const int k4 = (int)(gid - (long)t * k4n);
+  const int t = (int)(gid / g.K);
+  const int k = (int)(gid - (long)t * g.K);
   if (t >= g.T) return;
   const int tx = t % g.TW;
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
   const long TK = (long)g.T * g.K;
 
-  struct alignas(sizeof(MT) * 4) Quad {
-    MT v[4];
-  };
-  Quad in[n][n];
+  const MT* mb = Mq + (long)t * g.K + k;
+  int xi[n][n];
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
-      in[i][j] = *reinterpret_cast<const Quad*>(
-          Mq + (long)(decltype(i)::value * n + decltype(j)::value) * TK + (long)t * g.K + k4 * 4);
+      xi[i][j] = (int)mb[(long)(decltype(i)::value * n + decltype(j)::value) * TK];
     });
   });
 
-  float outf[M][M][4];
-  int outi[M][M][4];
-  static_for<0, 4>([&](auto ch) {
-    int xi[n][n];
-    static_for<0, n>([&](auto i) {
-      static_for<0, n>([&](auto j) { xi[i][j] = (int)in[i][j].v[decltype(ch)::value]; });
-    });
-    auto finish = [&](auto& num) {
-      static_for<0, M>([&](auto i) {
-        static_for<0, M>([&](auto j) {
-          constexpr int idx = decltype(i)::value * M + decltype(j)::value;
+  auto finish = [&](auto& num) {
+    static_for<0, M>([&](auto i) {
+      static_for<0, M>([&](auto j) {
+        constexpr int idx = decltype(i)::value * M + decltype(j)::value;
+        const int h = ty * M + decltype(i)::value;
+        const int ww = tx * M + decltype(j)::value;
+        if (h < g.H && ww < g.W) {
+          const long off = (((long)b * g.H + h) * g.W + ww) * g.K + k;
           if constexpr (OUT == 0) {
             float v = (float)num[i][j] * mu.outer.v[idx];
-            outf[i][j][ch] = relu ? fmaxf(v, 0.f) : v;
+            static_cast<float*>(yv)[off] = relu ? fmaxf(v, 0.f) : v;
           } else if constexpr (OUT == 1) {
             int v = (int)num[i][j];
-            outi[i][j][ch] = relu ? max(v, 0) : v;
+            static_cast<int*>(yv)[off] = relu ? max(v, 0) : v;
           } else {
             int v = cast_code((float)num[i][j] * mu.outer.v[idx], 127.f);
-            outi[i][j][ch] = relu ? max(v, 0) : v;
+            static_cast<int8_t*>(yv)[off] = (int8_t)(relu ? max(v, 0) : v);
           }
-        });
-      });
-    };
-    if constexpr (LEG) {
-      acc_t<TB::PinvT, IN_MAX> num1[n][n];
-      sandwich<TB::PinvT>(xi, num1);
-      int m1[n][n];
-      cast_tile<n>(num1, mu.inner, 127.f, m1);
-      acc_t<TB::APT, 127> num2[M][M];
-      sandwich<TB::APT>(m1, num2);
-      finish(num2);
-    } else {
-      acc_t<TB::AT, IN_MAX> num[M][M];
-      sandwich<TB::AT>(xi, num);
-      finish(num);
-    }
-  });
-
-  static_for<0, M>([&](auto i) {
-    static_for<0, M>([&](auto j) {
-      const int h = ty * M + decltype(i)::value;
-      const int ww = tx * M + decltype(j)::value;
-      if (h < g.H && ww < g.W) {
-        const long off = (((long)b * g.H + h) * g.W + ww) * g.K + k4 * 4;
-        if constexpr (OUT == 0) {
-          *reinterpret_cast<float4*>(static_cast<float*>(yv) + off) =
-              make_float4(outf[i][j][0], outf[i][j][1], outf[i][j][2], outf[i][j][3]);
-        } else if constexpr (OUT == 1) {
-          *reinterpret_cast<int4*>(static_cast<int*>(yv) + off) =
-              make_int4(outi[i][j][0], outi[i][j][1], outi[i][j][2], outi[i][j][3]);
-        } else {
-          uint32_t pk = ((uint32_t)outi[i][j][0] & 0xffu) | (((uint32_t)outi[i][j][1] & 0xffu) << 8) |
-                        (((uint32_t)outi[i][j][2] & 0xffu) << 16) |
-                        (((uint32_t)outi[i][j][3] & 0xffu) << 24);
-          *reinterpret_cast<uint32_t*>(static_cast<int8_t*>(yv) + off) = pk;
         }
-      }
+      });
     });
-  });
+  };
+  if constexpr (LEG) {
+    acc_t<TB::PinvT, IN_MAX> num1[n][n];
+    sandwich<TB::PinvT, IN_MAX>(xi, num1);
+    int m1[n][n];
+    cast_tile<n>(num1, mu.inner, 127.f, m1);
+    acc_t<TB::APT, 127> num2[M][M];
+    sandwich<TB::APT, 127>(m1, num2);
+    finish(num2);
+  } else {
+    acc_t<TB::AT, IN_MAX> num[M][M];
+    sandwich<TB::AT, IN_MAX>(xi, num);
+    finish(num);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -307,7 +299,7 @@ hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t*
 template <int M>
 hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st) {
-  const unsigned nb = blocks_for((long)g.T * (g.C / 4));
+  const unsigned nb = blocks_for((long)g.T * g.C);
   if (leg)
     hipLaunchKernelGGL((k_input_transform<M, true>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
   else
@@ -318,7 +310,7 @@ hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* 
 template <int M, bool LEG, typename MT>
 static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
                             const StageMults& mu, hipStream_t st) {
-  const unsigned nb = blocks_for((long)g.T * (g.K / 4));
+  const unsigned nb = blocks_for((long)g.T * g.K);
   const MT* mp = static_cast<const MT*>(Mq);
   const int r = relu ? 1 : 0;
   if (out_type == 0) {
