@@ -119,17 +119,29 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    # HIP events bracket every stage of every `stride`-th timed step (recording
+    # five events around four microsecond-scale kernels in every step would
+    # itself add a third to the step time).  A sixth event directly after the
+    # fifth measures what an empty event-to-event interval costs; that
+    # overhead is subtracted from each stage interval.
+    stride = 8
+    sampled = list(range(0, args.steps, stride))
+    evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(6)] for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(evs[i])
+        if i in evs:
+            step(evs[i])
+            evs[i][5].record(stream)
+        else:
+            step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    stage_ms = {nm: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1])
-                                   for i in range(args.steps)]))
-                for j, nm in enumerate(names)}
+    null_ms = float(np.median([evs[i][4].elapsed_time(evs[i][5]) for i in sampled]))
+    raw_ms = {nm: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in sampled]))
+              for j, nm in enumerate(names)}
+    stage_ms = {nm: max(raw_ms[nm] - null_ms, 1e-6) for nm in names}
     model = stage_model(wl, M.element_size(), y.element_size())
     stages = {}
     for nm in names:
@@ -138,12 +150,13 @@ def main():
             ach, peak, unit = model[nm]["work"] / sec / 1e9, HBM_PEAK_GBS, "GB/s"
         else:
             ach, peak, unit = model[nm]["work"] / sec / 1e12, INT8_MFMA_PEAK_TOPS, "TOP/s"
-        stages[nm] = {"ms": stage_ms[nm], "bound": model[nm]["bound"], "achieved": ach,
+        stages[nm] = {"ms": stage_ms[nm], "ms_event_raw": raw_ms[nm], "bound": model[nm]["bound"], "achieved": ach,
                       "peak": peak, "unit": unit, "frac": ach / peak}
     dominant = max(names, key=lambda nm: stage_ms[nm])
     roofline = {k: stages[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
     roofline["kernel"] = dominant
     roofline["traffic"] = None
+    roofline["event_overhead_ms"] = null_ms
 
     ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
     ms_per_step = dt / args.steps * 1e3

@@ -298,7 +298,7 @@ int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
   if (int rc = need(x, "x")) return rc;
   if (int rc = need(U, "U")) return rc;
   if (int rc = need(s, "scales")) return rc;
-  if (int rc = aligned(x, 4, "x")) return rc;
+  if (int rc = aligned(x, 16, "x")) return rc;
   if (int rc = aligned(U, 16, "U")) return rc;
   StageMults mu;
   if (int rc = input_mults(p, s, &mu)) return rc;

@@ -30,6 +30,21 @@ __device__ __forceinline__ void static_for(F&& f) {
 // low 32 bits of the product of the operands' low 24 bits.
 extern "C" __device__ int llvm_mul_i24(int, int) __asm("llvm.amdgcn.mul.i24.i32");
 
+// A compile-time constant parked in a scalar register.  VOP3 instructions on
+// gfx9-class ISAs take no 32-bit literal, so a multiply-add by a large literal
+// is otherwise split into a literal multiply and a separate add; with the
+// constant in an SGPR it stays one v_mad_i32_i24.
+template <int32_t CF>
+__device__ __forceinline__ int32_t sconst() {
+  if constexpr (CF >= -16 && CF <= 64) {
+    return CF;                                   // inline constant, free
+  } else {
+    int32_t k;
+    asm("s_mov_b32 %0, %1" : "=s"(k) : "i"(CF));
+    return k;
+  }
+}
+
 // x * c for a compile-time coefficient.  S24: the caller proved |x| < 2^23, so
 // the full-rate 24-bit multiplier gives the exact product.
 template <int64_t CF, bool S24>
@@ -42,14 +57,33 @@ __device__ __forceinline__ int32_t mulc(int32_t x) {
   else if constexpr ((a & (a - 1)) == 0)
     return x * (int32_t)CF;                      // shift
   else if constexpr (S24 && a < (1 << 23))
-    return llvm_mul_i24(x, (int32_t)CF);
+    return llvm_mul_i24(x, sconst<(int32_t)CF>());
   else
     return x * (int32_t)CF;
 }
-template <int64_t CF, bool S24>
-__device__ __forceinline__ int64_t mulc(int64_t x) {
+// 32-bit operand, 64-bit product (one v_mad_i64_i32 when accumulated).
+template <int64_t CF>
+__device__ __forceinline__ int64_t mulc_wide(int32_t x) {
+  static_assert(CF >= INT32_MIN && CF <= INT32_MAX);
+  return (int64_t)x * (int64_t)(int32_t)CF;
+}
+template <int64_t CF>
+__device__ __forceinline__ int64_t mulc_wide(int64_t x) {
   return x * CF;
 }
+
+constexpr bool coef_fit_i32(const IMat& t) {
+  for (int i = 0; i < t.rows; ++i)
+    for (int j = 0; j < t.cols; ++j)
+      if (t.N[i][j] > INT32_MAX || t.N[i][j] < INT32_MIN) return false;
+  return true;
+}
+
+// Accumulator of the first (left) pass: |N x| <= IN_MAX * rowsum.
+template <const IMat& T, int64_t IN_MAX>
+using tmp_t = std::conditional_t<((__int128)IN_MAX * T.rowsum < ((__int128)1 << 31)) &&
+                                     coef_fit_i32(T),
+                                 int32_t, int64_t>;
 
 // num = N x N^T with N the compile-time integer matrix T.N (T.rows x T.cols)
 // and |x| <= IN_MAX.  Zero coefficients generate no code.
@@ -58,13 +92,19 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
                                          AccT (&num)[T.rows][T.rows]) {
   constexpr bool s1 = IN_MAX < (1 << 23);
   constexpr bool s2 = (__int128)IN_MAX * T.rowsum < (1 << 23);
-  AccT tmp[T.rows][T.cols];
+  using TmpT = std::conditional_t<sizeof(AccT) == 4, int32_t, tmp_t<T, IN_MAX>>;
+  TmpT tmp[T.rows][T.cols];
   static_for<0, T.rows>([&](auto i) {
     static_for<0, T.cols>([&](auto b) {
-      AccT acc = 0;
+      TmpT acc = 0;
       static_for<0, T.cols>([&](auto a) {
         constexpr int64_t c = T.N[decltype(i)::value][decltype(a)::value];
-        if constexpr (c != 0) acc += mulc<c, s1>((AccT)x[a][b]);
+        if constexpr (c != 0) {
+          if constexpr (sizeof(TmpT) == 4)
+            acc += mulc<c, s1>((int32_t)x[a][b]);
+          else
+            acc += mulc_wide<c>((int64_t)x[a][b]);
+        }
       });
       tmp[i][b] = acc;
     });
@@ -74,7 +114,12 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
       AccT acc = 0;
       static_for<0, T.cols>([&](auto b) {
         constexpr int64_t c = T.N[decltype(j)::value][decltype(b)::value];
-        if constexpr (c != 0) acc += mulc<c, s2>(tmp[i][b]);
+        if constexpr (c != 0) {
+          if constexpr (sizeof(AccT) == 4)
+            acc += mulc<c, s2>(tmp[i][b]);
+          else
+            acc += mulc_wide<c>(tmp[i][b]);
+        }
       });
       num[i][j] = acc;
     });
@@ -139,43 +184,57 @@ __global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restri
 }
 
 // ---------------------------------------------------------------------------
-// Input transform: one lane per (tile, channel); a wave covers 64 consecutive
-// channels, so every load and store instruction moves one contiguous run.
-// Out-of-image pixels are read from a clamped in-bounds address and zeroed.
+// Input transform: one lane per (tile, channel).  A work group owns 256
+// consecutive (tile, channel) items (channel fastest).  Because C is a
+// multiple of 16, each 16-byte unit of that range lies inside one tile, so the
+// block's input pixels are fetched with 16-byte loads into LDS ([pixel][item]),
+// every lane then reads its own channel byte per pixel, and the n*n results go
+// back through LDS ([point][item]) to 16-byte stores.  HBM and the texture
+// path see only 16-byte accesses; the byte traffic stays inside LDS.
+// Out-of-image pixels are staged as zeros.
 // ---------------------------------------------------------------------------
 template <int M, bool LEG>
 __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
                                                          int8_t* __restrict__ U, Geometry g,
                                                          StageMults mu) {
-  constexpr int n = M + 2;
+  constexpr int n = M + 2, n2 = n * n;
   using TB = Tab<M>;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  const int t = (int)(gid / g.C);
-  const int c = (int)(gid - (long)t * g.C);
-  if (t >= g.T) return;
-  const int tx = t % g.TW;
-  const int ty = (t / g.TW) % g.TH;
-  const int b = t / (g.TW * g.TH);
-  const int8_t* xb = x + (long)b * g.H * g.W * g.C + c;
+  __shared__ __attribute__((aligned(16))) int8_t s_in[n2 * 256];
+  __shared__ __attribute__((aligned(16))) int8_t s_out[n2 * 256];
+  const int tid = threadIdx.x;
+  const long gid0 = (long)blockIdx.x * 256;
+  const long total = (long)g.T * g.C;
 
-  int roff[n], coff[n];
-  bool rok[n], cok[n];
-  static_for<0, n>([&](auto a) {
-    const int h = ty * M - 1 + decltype(a)::value;
-    const int ww = tx * M - 1 + decltype(a)::value;
-    rok[a] = h >= 0 && h < g.H;
-    cok[a] = ww >= 0 && ww < g.W;
-    roff[a] = min(max(h, 0), g.H - 1) * g.W * g.C;
-    coff[a] = min(max(ww, 0), g.W - 1) * g.C;
-  });
+  // staging role of this lane: 16-byte unit `u` of the block's item range
+  const int u = tid & 15, prow = tid >> 4;
+  const long ug = gid0 + u * 16;
+  const bool uok = ug < total;
+  const int ut = uok ? (int)(ug / g.C) : 0;
+  const int uc = uok ? (int)(ug - (long)ut * g.C) : 0;
+  const int tx = ut % g.TW;
+  const int ty = (ut / g.TW) % g.TH;
+  const int b = ut / (g.TW * g.TH);
+  const int8_t* xb = x + (long)b * g.H * g.W * g.C + uc;
+#pragma unroll
+  for (int it = 0; it < (n2 + 15) / 16; ++it) {
+    const int pix = it * 16 + prow;
+    if (pix < n2) {
+      const int a = pix / n, bb = pix - a * n;
+      const int h = ty * M - 1 + a, ww = tx * M - 1 + bb;
+      v4i v = {0, 0, 0, 0};
+      if (uok && h >= 0 && h < g.H && ww >= 0 && ww < g.W)
+        v = *reinterpret_cast<const v4i*>(xb + ((long)h * g.W + ww) * g.C);
+      *reinterpret_cast<v4i*>(s_in + pix * 256 + u * 16) = v;
+    }
+  }
+  __syncthreads();
+
   int xi[n][n];
   static_for<0, n>([&](auto a) {
     static_for<0, n>([&](auto bb) {
-      const int v = xb[roff[a] + coff[bb]];
-      xi[a][bb] = (rok[a] && cok[bb]) ? v : 0;
+      xi[a][bb] = s_in[(decltype(a)::value * n + decltype(bb)::value) * 256 + tid];
     });
   });
-
   int q[n][n];
   if constexpr (LEG) {
     acc_t<TB::PinvT, 127> num1[n][n];
@@ -190,14 +249,21 @@ __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restric
     sandwich<TB::BT, 127>(xi, num);
     cast_tile<n>(num, mu.outer, 127.f, q);
   }
-
-  const long TC = (long)g.T * g.C;
-  int8_t* ub = U + (long)t * g.C + c;
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
-      ub[(long)(decltype(i)::value * n + decltype(j)::value) * TC] = (int8_t)q[i][j];
+      s_out[(decltype(i)::value * n + decltype(j)::value) * 256 + tid] = (int8_t)q[i][j];
     });
   });
+  __syncthreads();
+
+  int8_t* ub = U + (long)ut * g.C + uc;
+#pragma unroll
+  for (int it = 0; it < (n2 + 15) / 16; ++it) {
+    const int p = it * 16 + prow;
+    if (p < n2 && uok)
+      *reinterpret_cast<v4i*>(ub + (long)p * total) =
+          *reinterpret_cast<const v4i*>(s_out + p * 256 + u * 16);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -223,26 +289,70 @@ template <int M, bool LEG, typename MT, int OUT>
 __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__ Mq,
                                                           void* __restrict__ yv, Geometry g,
                                                           StageMults mu, int relu) {
-  constexpr int n = M + 2;
+  constexpr int n = M + 2, n2 = n * n;
   constexpr int64_t IN_MAX = MTraits<MT>::in_max;
   using TB = Tab<M>;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  const int t = (int)(gid / g.K);
-  const int k = (int)(gid - (long)t * g.K);
-  if (t >= g.T) return;
+  const int tid = threadIdx.x;
+  const long gid0 = (long)blockIdx.x * 256;
+  const long total = (long)g.T * g.K;
+  const long gid = gid0 + tid;
+  const bool active = gid < total;
+  const int t = active ? (int)(gid / g.K) : 0;
+  const int k = active ? (int)(gid - (long)t * g.K) : 0;
   const int tx = t % g.TW;
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
-  const long TK = (long)g.T * g.K;
 
-  const MT* mb = Mq + (long)t * g.K + k;
   int xi[n][n];
-  static_for<0, n>([&](auto i) {
-    static_for<0, n>([&](auto j) {
-      xi[i][j] = (int)mb[(long)(decltype(i)::value * n + decltype(j)::value) * TK];
+  if constexpr (sizeof(MT) == 1) {
+    // int8 M: fetch the block's 256 consecutive (tile, k) items of every point
+    // with 16-byte loads into LDS, then each lane picks its own byte.
+    __shared__ __attribute__((aligned(16))) int8_t s_in[n2 * 256];
+    const int u = tid & 15, prow = tid >> 4;
+    const long ug = gid0 + u * 16;
+    const bool uok = ug < total;
+#pragma unroll
+    for (int it = 0; it < (n2 + 15) / 16; ++it) {
+      const int p = it * 16 + prow;
+      if (p < n2) {
+        v4i v = {0, 0, 0, 0};
+        if (uok) v = *reinterpret_cast<const v4i*>(Mq + (long)p * total + ug);
+        *reinterpret_cast<v4i*>(s_in + p * 256 + u * 16) = v;
+      }
+    }
+    __syncthreads();
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) {
+        xi[i][j] = s_in[(decltype(i)::value * n + decltype(j)::value) * 256 + tid];
+      });
     });
-  });
+    if (!active) return;
+  } else {
+    if (!active) return;
+    const MT* mb = Mq + (long)t * g.K + k;
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) {
+        xi[i][j] = (int)mb[(long)(decltype(i)::value * n + decltype(j)::value) * total];
+      });
+    });
+  }
 
+  // Numerator -> fp32 for the dequantised output.  64-bit numerators go
+  // through their two halves (two conversions and one fma): not the correctly
+  // rounded conversion, but within 2 ulp, which the fp32 output tolerates; the
+  // int8 output below keeps the exact single-rounding conversion.
+  auto to_float_approx = [](auto v) -> float {
+    if constexpr (sizeof(v) == 8) {
+      const uint64_t a = (uint64_t)(v < 0 ? -v : v);     // magnitude first: no cancellation
+      const float f = __builtin_fmaf((float)(uint32_t)(a >> 32), 4294967296.0f,
+                                     (float)(uint32_t)a);
+      return v < 0 ? -f : f;
+    } else {
+      return (float)v;
+    }
+  };
+  const long ybase = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K + k;
+  const int wk = g.W * g.K;
   auto finish = [&](auto& num) {
     static_for<0, M>([&](auto i) {
       static_for<0, M>([&](auto j) {
@@ -250,16 +360,16 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
         const int h = ty * M + decltype(i)::value;
         const int ww = tx * M + decltype(j)::value;
         if (h < g.H && ww < g.W) {
-          const long off = (((long)b * g.H + h) * g.W + ww) * g.K + k;
+          const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
           if constexpr (OUT == 0) {
-            float v = (float)num[i][j] * mu.outer.v[idx];
-            static_cast<float*>(yv)[off] = relu ? fmaxf(v, 0.f) : v;
+            float v = to_float_approx(num[i][j]) * mu.outer.v[idx];
+            (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
           } else if constexpr (OUT == 1) {
             int v = (int)num[i][j];
-            static_cast<int*>(yv)[off] = relu ? max(v, 0) : v;
+            (static_cast<int*>(yv) + ybase)[rel] = relu ? max(v, 0) : v;
           } else {
             int v = cast_code((float)num[i][j] * mu.outer.v[idx], 127.f);
-            static_cast<int8_t*>(yv)[off] = (int8_t)(relu ? max(v, 0) : v);
+            (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
           }
         }
       });
