@@ -28,9 +28,10 @@ __device__ __forceinline__ int cast_code(float v, float qmax) {
 // int8 results are transposed through LDS so that global stores are full
 // 128-byte rows; the wider int16 / int32 results are stored from registers.
 //
-// Blocks are numbered so that all blocks sharing a (point, k block) -- i.e. the
-// same slice of V and the same U[p] -- run on the same XCD (consecutive work
-// group ids go round-robin over the 8 XCDs, each with a private L2).
+// Blocks are numbered so that all blocks of a (point, group of t blocks) run
+// on the same XCD (consecutive work group ids go round-robin over the 8 XCDs,
+// each with a private L2): the k blocks that share a set of U rows then share
+// one L2, and the number of groups is chosen to spread n*n points evenly.
 // ---------------------------------------------------------------------------
 constexpr int kTT = 128, kKT = 128, kCK = 128, kRow = kCK + 16;
 
@@ -38,17 +39,23 @@ template <typename MT>
 __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
                                                   const int8_t* __restrict__ V,
                                                   MT* __restrict__ Mo, int T, int C, int K,
-                                                  int tblocks, int kblocks, int units, float mult,
-                                                  float qmax) {
+                                                  int tblocks, int kblocks, int tgroups, int tpg,
+                                                  int units, float mult, float qmax) {
   __shared__ __attribute__((aligned(16))) int8_t smem[(kKT + kTT) * kRow];
   int8_t* sA = smem;                  // V rows (k)
   int8_t* sB = smem + kKT * kRow;     // U rows (t)
 
+  // unit = (point, group of t blocks); all k blocks of a t block are adjacent
+  // slots of the same XCD, so U rows are fetched into that L2 once.
   const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-  const int unit = (slot / tblocks) * 8 + xcd;
+  const int nbu = tpg * kblocks;                 // blocks per unit
+  const int unit = (slot / nbu) * 8 + xcd;
   if (unit >= units) return;
-  const int tb = slot % tblocks;
-  const int p = unit / kblocks, kb = unit - p * kblocks;
+  const int inner = slot % nbu;
+  const int kb = inner % kblocks;
+  const int p = unit / tgroups;
+  const int tb = (unit - p * tgroups) * tpg + inner / kblocks;
+  if (tb >= tblocks) return;
   const int t0 = tb * kTT, k0 = kb * kKT;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -66,13 +73,19 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
     ga[i] = V + ((long)p * K + kr) * C + sseg;
     gb[i] = U + ((long)p * T + tr) * C + sseg;
   }
-  v4i ra[4], rb[4];
-  auto fetch = [&](int c0) {
+  // one register set: the next chunk is in flight while this one feeds the MFMAs
+  // (a second set costs a third of the occupancy and measured slower)
+  v4i ra0[4], rb0[4];
+  auto fetch = [&](v4i (&ra)[4], v4i (&rb)[4], int c0) {
+    // columns past C (last chunk when C is not a multiple of 128) are read
+    // from a clamped in-bounds column and zeroed, without branching
     const bool ok = c0 + sseg < C;
+    const int cc = ok ? c0 : C - 16 - sseg;
+    const int keep = ok ? -1 : 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      ra[i] = ok ? *reinterpret_cast<const v4i*>(ga[i] + c0) : v4i{0, 0, 0, 0};
-      rb[i] = ok ? *reinterpret_cast<const v4i*>(gb[i] + c0) : v4i{0, 0, 0, 0};
+      ra[i] = *reinterpret_cast<const v4i*>(ga[i] + cc) & keep;
+      rb[i] = *reinterpret_cast<const v4i*>(gb[i] + cc) & keep;
     }
   };
 
@@ -82,8 +95,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = v16i{};
 
-  fetch(0);
-  for (int c0 = 0; c0 < C; c0 += kCK) {
+  auto chunk = [&](v4i (&ra)[4], v4i (&rb)[4], int c0) {
     if (c0) __syncthreads();             // previous chunk fully consumed
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -91,7 +103,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
       *reinterpret_cast<v4i*>(sB + (srow + i * 32) * kRow + sseg) = rb[i];
     }
     __syncthreads();
-    if (c0 + kCK < C) fetch(c0 + kCK);
+    if (c0 + kCK < C) fetch(ra, rb, c0 + kCK);
 #pragma unroll
     for (int ks = 0; ks < kCK / 32; ++ks) {
       v4i fa[2], fb[2];
@@ -106,7 +118,10 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
         for (int j = 0; j < 2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
-  }
+  };
+
+  fetch(ra0, rb0, 0);
+  for (int c0 = 0; c0 < C; c0 += kCK) chunk(ra0, rb0, c0);
 
   // acc[i][j][4*g+v] = D[k = 32 i + 8 g + 4 h + v][t = 32 j + r] within the wave's 64 x 64
   if constexpr (sizeof(MT) == 1) {
@@ -200,19 +215,22 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
   if ((long)g.T * g.K == 0) return hipSuccess;
   const int n = g.m + 2;
   const int tblocks = (g.T + kTT - 1) / kTT, kblocks = (g.K + kKT - 1) / kKT;
-  const int units = n * n * kblocks;                 // (point, k block) pairs
-  const long nblocks = (long)((units + 7) / 8) * 8 * tblocks;
+  int tgroups = 1;                                   // smallest split that fills 8 XCDs evenly
+  while (tgroups < 8 && (n * n * tgroups) % 8 != 0 && tgroups * 2 <= tblocks) tgroups *= 2;
+  const int tpg = (tblocks + tgroups - 1) / tgroups;
+  const int units = n * n * tgroups;
+  const long nblocks = (long)((units + 7) / 8) * 8 * tpg * kblocks;
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   dim3 grid((unsigned)nblocks);
   if (m_bits == 8)
     hipLaunchKernelGGL((k_contract<int8_t>), grid, dim3(256), 0, st, U, V, (int8_t*)Mo, g.T, g.C,
-                       g.K, tblocks, kblocks, units, mult, 127.f);
+                       g.K, tblocks, kblocks, tgroups, tpg, units, mult, 127.f);
   else if (m_bits == 9)
     hipLaunchKernelGGL((k_contract<int16_t>), grid, dim3(256), 0, st, U, V, (int16_t*)Mo, g.T,
-                       g.C, g.K, tblocks, kblocks, units, mult, 255.f);
+                       g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 255.f);
   else
     hipLaunchKernelGGL((k_contract<int32_t>), grid, dim3(256), 0, st, U, V, (int32_t*)Mo, g.T,
-                       g.C, g.K, tblocks, kblocks, units, mult, 0.f);
+                       g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 0.f);
   return hipGetLastError();
 }
 
