@@ -18,12 +18,48 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
+# Non-packed vector ALU issue rate: 256 CU x 64 lanes x 2.4 GHz lane-operations/s
+# (the published 157.3 TFLOP/s fp32 figure counts packed 2-wide FMAs as 4 flops).
+VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
+# a plain 64 MiB device copy of the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
+MEASURED_TRAFFIC_BYTES = {
+    "cfg4a_f4_c256": {"weight_transform": (675.7 + 2304.0) * 1024,
+                      "input_transform": (6525.2 + 9216.0) * 1024,
+                      "contraction": (20866.0 + 9216.0) * 1024,
+                      "output_transform": (9369.9 + 16384.0) * 1024},
+}
 
 
-def stage_model(wl, m_bytes, y_bytes):
-    """Algorithmic work of one launch of each stage (bytes or int8 ops)."""
+def bracket_ops(mats, names):
+    """Algorithmic vector-ALU operations of one item: per bracket N X N^T, one
+    operation per non-zero coefficient application (two passes) plus four per
+    cast (convert, multiply, clamp, round)."""
+    ops = 0
+    for name in names:
+        N, _ = mats.int_form(name)
+        rows, cols = len(N), len(N[0])
+        nnz = sum(1 for r in N for v in r if v != 0)
+        ops += nnz * cols + nnz * rows + 4 * rows * rows
+    return ops
+
+
+def stage_model(wl, m_bytes, y_bytes, mats):
+    """Algorithmic work of one launch of each stage (bytes, int8 ops, ALU ops)."""
     n = wl.m + 2
     T, C, K = wl.tiles, wl.C, wl.K
+    leg = wl.base == "legendre"
+    alu = {"weight_transform": K * C * bracket_ops(mats, ["GP", "PINVT"] if leg else ["G"]),
+           "input_transform": T * C * bracket_ops(mats, ["PINVT", "BPT"] if leg else ["BT"]),
+           "output_transform": T * K * bracket_ops(mats, ["PINVT", "APT"] if leg else ["AT"])}
+    model = _stage_bytes(wl, m_bytes, y_bytes, n, T, C, K)
+    for k, v in alu.items():
+        model[k]["alu_ops"] = v
+    return model
+
+
+def _stage_bytes(wl, m_bytes, y_bytes, n, T, C, K):
     return {
         # per (k, c): 9 filter bytes in, n*n transformed bytes out
         "weight_transform": {"bound": "hbm", "work": K * C * (9 + n * n)},
@@ -154,20 +190,42 @@ def main():
     raw_ms = {nm: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in sampled]))
               for j, nm in enumerate(names)}
     stage_ms = raw_ms
-    model = stage_model(wl, M.element_size(), y.element_size())
+    pts = {2: [0, 1, -1], 4: [0, 1, -1, 2, -2], 6: [0, 1, -1, 2, -2, (1, 2), (-1, 2)]}[wl.m]
+    from fractions import Fraction
+    mats = wn.wino_make_matrices(wl.m, 3, [Fraction(*p) if isinstance(p, tuple) else p
+                                           for p in pts], base)
+    model = stage_model(wl, M.element_size(), y.element_size(), mats)
+    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name, {}) if reps == 1 else {}
     stages = {}
     for nm in names:
         sec = stage_ms[nm] * 1e-3
+        st = {"ms": stage_ms[nm]}
         if model[nm]["bound"] == "hbm":
-            ach, peak, unit = model[nm]["work"] / sec / 1e9, HBM_PEAK_GBS, "GB/s"
+            hbm = model[nm]["work"] / sec / 1e9
+            alu = model[nm]["alu_ops"] / sec / 1e12
+            st.update({"hbm_GBps": hbm, "hbm_frac": hbm / HBM_PEAK_GBS,
+                       "alu_Tops": alu, "alu_frac": alu / VALU_PEAK_TOPS})
+            # the binding ceiling is the one whose ideal time is longer
+            if model[nm]["alu_ops"] / VALU_PEAK_TOPS / 1e12 > model[nm]["work"] / HBM_PEAK_GBS / 1e9:
+                st.update({"bound": "alu", "achieved": alu, "peak": VALU_PEAK_TOPS,
+                           "unit": "TOP/s", "frac": alu / VALU_PEAK_TOPS})
+            else:
+                st.update({"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS,
+                           "unit": "GB/s", "frac": hbm / HBM_PEAK_GBS})
         else:
-            ach, peak, unit = model[nm]["work"] / sec / 1e12, INT8_MFMA_PEAK_TOPS, "TOP/s"
-        stages[nm] = {"ms": stage_ms[nm], "bound": model[nm]["bound"], "achieved": ach,
-                      "peak": peak, "unit": unit, "frac": ach / peak}
+            ach = model[nm]["work"] / sec / 1e12
+            st.update({"bound": "mfma", "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS,
+                       "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS})
+        st["traffic"] = traffic.get(nm)
+        st["algorithmic_bytes"] = (model[nm]["work"] if model[nm]["bound"] == "hbm" else None)
+        stages[nm] = st
     dominant = max(names, key=lambda nm: stage_ms[nm])
-    roofline = {k: stages[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac")}
+    roofline = {k: stages[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac",
+                                                   "traffic")}
     roofline["kernel"] = dominant
-    roofline["traffic"] = None
+    for k in ("hbm_GBps", "hbm_frac"):
+        if k in stages[dominant]:
+            roofline[k] = stages[dominant][k]
     roofline["empty_event_interval_ms"] = null_ms
 
     ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9

@@ -84,7 +84,9 @@ typedef struct {
   int m, r;                   /* (2,3), (4,3) or (6,3); standard point sets
                                  {0,1,-1}, {0,1,-1,2,-2}, {0,1,-1,2,-2,1/2,-1/2}  */
   int base;                   /* WINO_BASE_*                                      */
-  int bits_in;                /* 8: int8 path; 32: fp32 path without any cast     */
+  int bits_in;                /* 8: int8 path; 32: fp32 path without any cast: x, w,
+                                 U, V, M, y are float in the same layouts, scales
+                                 are ignored (may be null), output is fp32        */
   int bits_hadamard;          /* 8 | 9 | 32: width kept for the contraction result
                                  (Section 5: "Hadamard product on 9 bits")        */
   int inner_quant;            /* Legendre only: casts on the inner brackets of

@@ -87,6 +87,8 @@ struct Plan {
   Stages st;
   bool two_brackets;   // Legendre with casts on the inner brackets
   int m_bits;
+  bool fp32;           // bits_in = 32: float tensors, no cast anywhere
+  bool legendre;
 };
 
 int make_plan(const wino_conv_desc_t* d, Plan* p) {
@@ -95,9 +97,12 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
     return fail(WINO_EUNSUPPORTED, "F(%d,%d) not built: m must be 2, 4 or 6 and r = 3", d->m, d->r);
   if (d->base != WINO_BASE_CANONICAL && d->base != WINO_BASE_LEGENDRE)
     return fail(WINO_EINVAL, "unknown base %d", d->base);
-  if (d->bits_in == 32) return fail(WINO_EUNSUPPORTED, "fp32 path (bits_in = 32) not built");
-  if (d->bits_in != 8) return fail(WINO_EUNSUPPORTED, "bits_in must be 8 (got %d)", d->bits_in);
-  if (d->bits_hadamard != 8 && d->bits_hadamard != 9 && d->bits_hadamard != 32)
+  if (d->bits_in != 8 && d->bits_in != 32)
+    return fail(WINO_EUNSUPPORTED, "bits_in must be 8 or 32 (got %d)", d->bits_in);
+  p->fp32 = d->bits_in == 32;
+  if (p->fp32 && d->out_type != WINO_OUT_F32)
+    return fail(WINO_EUNSUPPORTED, "the fp32 path (bits_in = 32) has fp32 output only");
+  if (!p->fp32 && d->bits_hadamard != 8 && d->bits_hadamard != 9 && d->bits_hadamard != 32)
     return fail(WINO_EUNSUPPORTED, "bits_hadamard must be 8, 9 or 32 (got %d)", d->bits_hadamard);
   if (d->out_type != WINO_OUT_F32 && d->out_type != WINO_OUT_I32 && d->out_type != WINO_OUT_I8)
     return fail(WINO_EINVAL, "unknown out_type %d", d->out_type);
@@ -111,12 +116,13 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
   if (T > (1L << 30) || T * (long)(d->C > d->K ? d->C : d->K) * n2 > (1L << 40) ||
       (long)d->N * d->H * d->W * (long)(d->C > d->K ? d->C : d->K) > (1L << 40))
     return fail(WINO_EINVAL, "problem too large");
-  if (d->bits_hadamard == 32 && d->C > kMaxChannelsExact)
+  if (!p->fp32 && d->bits_hadamard == 32 && d->C > kMaxChannelsExact)
     return fail(WINO_EOVERFLOW, "C = %d: an unquantised contraction result may exceed 2^24", d->C);
   p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T};
   if (!stages_for(d->m, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
   p->two_brackets = d->base == WINO_BASE_LEGENDRE && d->inner_quant != 0;
-  p->m_bits = d->bits_hadamard;
+  p->m_bits = p->fp32 ? 32 : d->bits_hadamard;
+  p->legendre = d->base == WINO_BASE_LEGENDRE;
   if (d->out_type == WINO_OUT_I32) {
     const IMat& a = *p->st.AT;
     bool integer = !p->two_brackets;
@@ -269,10 +275,11 @@ int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   if (int rc = make_plan(d, &p)) return rc;
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  const size_t eb = p.fp32 ? 4 : 1;
   size_t total = 0;
-  if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C);
-  total += round256(n2 * p.g.T * d->C);
-  total += round256(n2 * p.g.T * d->K * m_elem_bytes(d->bits_hadamard));
+  if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C * eb);
+  total += round256(n2 * p.g.T * d->C * eb);
+  total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
   *bytes = total;
   return WINO_OK;
 }
@@ -283,6 +290,11 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
   if (int rc = make_plan(d, &p)) return rc;
   if (int rc = need(w, "w")) return rc;
   if (int rc = need(V, "V")) return rc;
+  if (p.fp32) {
+    hipError_t e = launch_stage_f32(0, p.g, p.legendre, (const float*)w, (const float*)nullptr,
+                                    (float*)V, false, (hipStream_t)hip_stream);
+    return e == hipSuccess ? WINO_OK : fail_hip(e, "fp32 weight launch");
+  }
   if (int rc = need(s, "scales")) return rc;
   StageMults mu;
   if (int rc = weight_mults(p, s, &mu)) return rc;
@@ -297,6 +309,11 @@ int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
   if (int rc = make_plan(d, &p)) return rc;
   if (int rc = need(x, "x")) return rc;
   if (int rc = need(U, "U")) return rc;
+  if (p.fp32) {
+    hipError_t e = launch_stage_f32(1, p.g, p.legendre, (const float*)x, (const float*)nullptr,
+                                    (float*)U, false, (hipStream_t)hip_stream);
+    return e == hipSuccess ? WINO_OK : fail_hip(e, "fp32 input launch");
+  }
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(x, 16, "x")) return rc;
   if (int rc = aligned(U, 16, "U")) return rc;
@@ -314,6 +331,11 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
   if (int rc = need(U, "U")) return rc;
   if (int rc = need(V, "V")) return rc;
   if (int rc = need(M, "M")) return rc;
+  if (p.fp32) {
+    hipError_t e = launch_stage_f32(2, p.g, p.legendre, (const float*)U, (const float*)V,
+                                    (float*)M, false, (hipStream_t)hip_stream);
+    return e == hipSuccess ? WINO_OK : fail_hip(e, "fp32 contract launch");
+  }
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(U, 16, "U")) return rc;
   if (int rc = aligned(V, 16, "V")) return rc;
@@ -332,6 +354,11 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
   if (int rc = make_plan(d, &p)) return rc;
   if (int rc = need(M, "M")) return rc;
   if (int rc = need(y, "y")) return rc;
+  if (p.fp32) {
+    hipError_t e = launch_stage_f32(3, p.g, p.legendre, (const float*)M, (const float*)nullptr,
+                                    (float*)y, d->relu != 0, (hipStream_t)hip_stream);
+    return e == hipSuccess ? WINO_OK : fail_hip(e, "fp32 output launch");
+  }
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(M, 16, "M")) return rc;
   if (int rc = aligned(y, 16, "y")) return rc;
@@ -358,10 +385,10 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   if (!d->weights_pretransformed) {
     if (int rc = wino_weight_transform(d, w_or_V, ws, s, hip_stream)) return rc;
     V = ws;
-    ws += round256(n2 * d->K * d->C);
+    ws += round256(n2 * d->K * d->C * (p.fp32 ? 4 : 1));
   }
   void* U = ws;
-  ws += round256(n2 * p.g.T * d->C);
+  ws += round256(n2 * p.g.T * d->C * (p.fp32 ? 4 : 1));
   void* M = ws;
   if (int rc = wino_input_transform(d, x, U, s, hip_stream)) return rc;
   if (int rc = wino_contract(d, U, V, M, s, hip_stream)) return rc;

@@ -58,4 +58,9 @@ hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const
                                    int m_bits, void* y, int out_type, bool relu,
                                    const StageMults& mu, hipStream_t st);
 
+// fp32 path: stage 0 weight (a = w), 1 input (a = x), 2 contraction (a = U, b = V),
+// 3 output (a = M); no casts, float tensors in the int8 path's layouts.
+hipError_t launch_stage_f32(int stage, const Geometry& g, bool legendre, const float* a,
+                            const float* b, float* out, bool relu, hipStream_t st);
+
 }  // namespace wino

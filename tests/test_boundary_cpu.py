@@ -92,7 +92,7 @@ def test_workspace_bytes_and_descriptor_validation():
     d9 = wn.ConvDesc(256, 8, 8, 256, 256, m=4, bits_hadamard=9, weights_pretransformed=1)
     assert wn.wino_workspace_bytes(d9) == r256(n2 * T * 256) + r256(n2 * T * 256 * 2)
     for kw, code in [(dict(m=3), -2), (dict(m=4, r=5), -2), (dict(bits_hadamard=7), -2),
-                     (dict(bits_in=16), -2), (dict(base=5), -1), (dict(out_type=9), -1),
+                     (dict(bits_in=16), -2), (dict(bits_in=32, out_type=wn.OUT_I8), -2), (dict(base=5), -1), (dict(out_type=9), -1),
                      (dict(out_type=wn.OUT_I32), -2),            # Legendre has no integer A_P^T
                      (dict(m=6, base=wn.BASE_CANONICAL, out_type=wn.OUT_I32), -2)]:
         with pytest.raises(wn.WinoError) as e:
@@ -119,5 +119,5 @@ def test_stage_calls_reject_bad_arguments_before_any_launch():
     assert lib.wino_contract(C.byref(d), C.c_void_p(4100), fake, fake, C.byref(s), None) == -1
     assert b"aligned" in lib.wino_last_error()
     assert lib.wino_conv2d(C.byref(d), fake, fake, fake, C.byref(s), fake, 16, None) == -4
-    dfused = wn.ConvDesc(1, 8, 8, 16, 16, bits_in=32)
+    dfused = wn.ConvDesc(1, 8, 8, 16, 16, fused=1)
     assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(s), fake, 1 << 30, None) == -2
