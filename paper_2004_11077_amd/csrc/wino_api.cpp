@@ -278,8 +278,11 @@ int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   const size_t eb = p.fp32 ? 4 : 1;
   size_t total = 0;
   if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C * eb);
-  total += round256(n2 * p.g.T * d->C * eb);
-  total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
+  if (!d->fused) {   // the fused variant keeps U and M on chip
+    total += round256(n2 * p.g.T * d->C * eb);
+    total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
+  }
+  if (total == 0) total = 256;
   *bytes = total;
   return WINO_OK;
 }
@@ -373,7 +376,11 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
                 const wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
-  if (d->fused) return fail(WINO_EUNSUPPORTED, "fused variant not built");
+  if (d->fused) {
+    if (p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32)
+      return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "
+                                     "bits_hadamard 8 or 9 and fp32 or int8 output");
+  }
   size_t want = 0;
   if (int rc = wino_workspace_bytes(d, &want)) return rc;
   if (int rc = need(workspace, "workspace")) return rc;
@@ -386,6 +393,22 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
     if (int rc = wino_weight_transform(d, w_or_V, ws, s, hip_stream)) return rc;
     V = ws;
     ws += round256(n2 * d->K * d->C * (p.fp32 ? 4 : 1));
+  }
+  if (d->fused) {
+    if (int rc = need(x, "x")) return rc;
+    if (int rc = need(y, "y")) return rc;
+    if (int rc = need(s, "scales")) return rc;
+    if (int rc = aligned(V, 16, "V")) return rc;
+    StageMults in_mu, out_mu;
+    float m_mult;
+    double s_m;
+    if (int rc = input_mults(p, s, &in_mu)) return rc;
+    if (int rc = contract_mult(p, s, &m_mult, &s_m)) return rc;
+    if (int rc = output_mults(p, d, s, &out_mu)) return rc;
+    hipError_t e = launch_fused(p.g, p.two_brackets, (const int8_t*)x, (const int8_t*)V, y,
+                                p.m_bits, d->out_type, d->relu != 0, in_mu, out_mu, m_mult,
+                                (hipStream_t)hip_stream);
+    return e == hipSuccess ? WINO_OK : fail_hip(e, "fused launch");
   }
   void* U = ws;
   ws += round256(n2 * p.g.T * d->C * (p.fp32 ? 4 : 1));

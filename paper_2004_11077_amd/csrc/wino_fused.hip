@@ -1,0 +1,251 @@
+// Fused variant: input transform -> per-point contraction -> output transform
+// in ONE kernel; the Winograd-domain tensors U and M never leave the CU
+// (U chunks and the cast M block live in LDS, the int32 accumulators of all
+// n*n points in registers).  Only x, V and y touch HBM.
+//
+// Work group = 4 waves, 16 tiles x KB output channels (KB = 64 for an int8 M,
+// 32 for the 9-bit int16 M), all n*n Winograd points.  Loop over the input
+// channels in chunks of 64:
+//   A  every lane transforms (tile, channel) items of the chunk exactly as the
+//      split input-transform kernel does and drops the n*n codes into LDS as
+//      U_s[point][tile][channel];
+//   B  wave w takes points w, w+4, ...: for each, one 16x16x64 int8 MFMA per
+//      16 output channels, A operand = V rows (k) straight from global / L2,
+//      B operand = the 16 tiles of U_s; accumulators stay in registers.
+// Then the accumulators are cast to bits_hadamard, written to LDS as
+// M_s[point][tile][k] (reusing the U_s storage), and every lane runs the output
+// transform of (tile, k) items and stores y.
+//
+// The input transform is recomputed by each of the K / KB work groups that
+// share a tile block, so the variant pays off for K <= 64 (one k block); for
+// wide layers the split path is the faster one.
+#include "wino_transforms.hpp"
+
+namespace wino {
+
+constexpr int kFT = 16;          // tiles per work group
+constexpr int kFC = 64;          // input channels per chunk
+constexpr int kURow = kFC + 16;  // U_s row (one tile) in bytes, padded
+constexpr int kMRow = 64 + 4;    // M_s row (one tile) in bytes, padded
+
+template <int M, bool LEG, typename MT, int OUT>
+__global__ __launch_bounds__(256) void k_fused(const int8_t* __restrict__ x,
+                                               const int8_t* __restrict__ V,
+                                               void* __restrict__ yv, Geometry g, StageMults in_mu,
+                                               StageMults out_mu, float m_mult, int relu,
+                                               int tblocks) {
+  constexpr int n = M + 2, n2 = n * n;
+  constexpr int KB = sizeof(MT) == 1 ? 64 : 32;      // output channels per work group
+  constexpr int NKB = KB / 16;                       // 16-wide MFMA column blocks
+  constexpr int NPW = n2 / 4;                        // points per wave
+  static_assert(n2 % 4 == 0);
+  constexpr float QM = sizeof(MT) == 1 ? 127.f : 255.f;
+  using TB = Tab<M>;
+  static_assert(n2 * kFT * kMRow <= n2 * kFT * kURow);
+  __shared__ __attribute__((aligned(16))) int8_t smem[n2 * kFT * kURow];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tb = blockIdx.x % tblocks, kblk = blockIdx.x / tblocks;
+  const int t0 = tb * kFT, k0 = kblk * KB;
+  const int jl = lane & 15, seg = lane >> 4;         // MFMA operand row / 16-byte K segment
+
+  v4i acc[NPW][NKB];
+#pragma unroll
+  for (int a = 0; a < NPW; ++a)
+#pragma unroll
+    for (int b = 0; b < NKB; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+
+  for (int c0 = 0; c0 < g.C; c0 += kFC) {
+    if (c0) __syncthreads();                         // U_s of the previous chunk consumed
+    // ---- A: input transform of 16 tiles x 64 channels, 4 items per lane ----
+#pragma unroll 1
+    for (int it = 0; it < kFT / 4; ++it) {
+      const int tl = it * 4 + wave;                  // a wave = one tile, 64 channels
+      const int t = t0 + tl, c = c0 + lane;
+      const bool live = t < g.T && c < g.C;
+      const int tt = live ? t : 0, cc = live ? c : 0;
+      const int tx = tt % g.TW;
+      const int ty = (tt / g.TW) % g.TH;
+      const int b = tt / (g.TW * g.TH);
+      const int8_t* xb = x + (long)b * g.H * g.W * g.C + cc;
+      int xi[n][n];
+      static_for<0, n>([&](auto a) {
+        static_for<0, n>([&](auto bb) {
+          const int h = ty * M - 1 + decltype(a)::value;
+          const int ww = tx * M - 1 + decltype(bb)::value;
+          const bool in = live && h >= 0 && h < g.H && ww >= 0 && ww < g.W;
+          const int hh = min(max(h, 0), g.H - 1), wc = min(max(ww, 0), g.W - 1);
+          const int v = xb[((long)hh * g.W + wc) * g.C];
+          xi[a][bb] = in ? v : 0;
+        });
+      });
+      int q[n][n];
+      if constexpr (LEG) {
+        acc_t<TB::PinvT, 127> num1[n][n];
+        sandwich<TB::PinvT, 127>(xi, num1);
+        int x1[n][n];
+        cast_tile<n>(num1, in_mu.inner, 127.f, x1);
+        acc_t<TB::BPT, 127> num2[n][n];
+        sandwich<TB::BPT, 127>(x1, num2);
+        cast_tile<n>(num2, in_mu.outer, 127.f, q);
+      } else {
+        acc_t<TB::BT, 127> num[n][n];
+        sandwich<TB::BT, 127>(xi, num);
+        cast_tile<n>(num, in_mu.outer, 127.f, q);
+      }
+      static_for<0, n>([&](auto i) {
+        static_for<0, n>([&](auto j) {
+          // a dead item (tile or channel out of range) has all-zero input, hence zero codes
+          smem[((decltype(i)::value * n + decltype(j)::value) * kFT + tl) * kURow + lane] =
+              (int8_t)q[i][j];
+        });
+      });
+    }
+    __syncthreads();
+    // ---- B: contraction of this chunk for the wave's points ----
+    const bool cok = c0 + seg * 16 < g.C;
+    const int ccol = cok ? c0 + seg * 16 : 0;
+#pragma unroll
+    for (int pi = 0; pi < NPW; ++pi) {
+      const int p = pi * 4 + wave;
+      const v4i bu = *reinterpret_cast<const v4i*>(smem + (p * kFT + jl) * kURow + seg * 16);
+#pragma unroll
+      for (int kb = 0; kb < NKB; ++kb) {
+        const int kr = min(k0 + kb * 16 + jl, g.K - 1);          // clamp, masked at the store
+        v4i av = *reinterpret_cast<const v4i*>(V + ((long)p * g.K + kr) * g.C + ccol);
+        if (!cok) av = v4i{0, 0, 0, 0};
+        acc[pi][kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, acc[pi][kb], 0, 0, 0);
+      }
+    }
+  }
+
+  // ---- cast the contraction result and park it in LDS as M_s[p][tile][k] ----
+  __syncthreads();
+  // acc[pi][kb][v] = D[k = 16 kb + 4 seg + v][tile = jl]
+#pragma unroll
+  for (int pi = 0; pi < NPW; ++pi) {
+    const int p = pi * 4 + wave;
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      int q[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)acc[pi][kb][v] * m_mult, QM);
+      int8_t* dst = smem + (p * kFT + jl) * kMRow + (kb * 16 + 4 * seg) * (int)sizeof(MT);
+      if constexpr (sizeof(MT) == 1) {
+        *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
+                                            (((uint32_t)q[2] & 0xffu) << 16) |
+                                            (((uint32_t)q[3] & 0xffu) << 24);
+      } else {
+        reinterpret_cast<uint32_t*>(dst)[0] = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
+        reinterpret_cast<uint32_t*>(dst)[1] = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- output transform of 16 tiles x KB channels ----
+  const MT* ms = reinterpret_cast<const MT*>(smem);
+  constexpr int MROW = kMRow / (int)sizeof(MT);      // M_s row in elements
+#pragma unroll 1
+  for (int it = 0; it < kFT * KB / 256; ++it) {
+    const int item = it * 256 + tid;
+    const int tl = item / KB, kl = item - tl * KB;
+    const int t = t0 + tl, k = k0 + kl;
+    if (t >= g.T || k >= g.K) continue;
+    const int tx = t % g.TW;
+    const int ty = (t / g.TW) % g.TH;
+    const int b = t / (g.TW * g.TH);
+    int mi[n][n];
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) {
+        mi[i][j] = (int)ms[((decltype(i)::value * n + decltype(j)::value) * kFT + tl) * MROW + kl];
+      });
+    });
+    const long ybase = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K + k;
+    const int wk = g.W * g.K;
+    auto to_float_approx = [](auto v) -> float {
+      if constexpr (sizeof(v) == 8) {
+        const uint64_t a = (uint64_t)(v < 0 ? -v : v);
+        const float f = __builtin_fmaf((float)(uint32_t)(a >> 32), 4294967296.0f, (float)(uint32_t)a);
+        return v < 0 ? -f : f;
+      } else {
+        return (float)v;
+      }
+    };
+    auto finish = [&](auto& num) {
+      static_for<0, M>([&](auto i) {
+        static_for<0, M>([&](auto j) {
+          constexpr int idx = decltype(i)::value * M + decltype(j)::value;
+          const int h = ty * M + decltype(i)::value;
+          const int ww = tx * M + decltype(j)::value;
+          if (h < g.H && ww < g.W) {
+            const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
+            if constexpr (OUT == 0) {
+              float v = to_float_approx(num[i][j]) * out_mu.outer.v[idx];
+              (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
+            } else {
+              int v = cast_code((float)num[i][j] * out_mu.outer.v[idx], 127.f);
+              (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
+            }
+          }
+        });
+      });
+    };
+    constexpr int64_t IN_MAX = sizeof(MT) == 1 ? 127 : 255;
+    if constexpr (LEG) {
+      acc_t<TB::PinvT, IN_MAX> num1[n][n];
+      sandwich<TB::PinvT, IN_MAX>(mi, num1);
+      int m1[n][n];
+      cast_tile<n>(num1, out_mu.inner, 127.f, m1);
+      acc_t<TB::APT, 127> num2[M][M];
+      sandwich<TB::APT, 127>(m1, num2);
+      finish(num2);
+    } else {
+      acc_t<TB::AT, IN_MAX> num[M][M];
+      sandwich<TB::AT, IN_MAX>(mi, num);
+      finish(num);
+    }
+  }
+}
+
+template <int M, bool LEG, typename MT>
+static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, void* y, int out_type,
+                           bool relu, const StageMults& in_mu, const StageMults& out_mu,
+                           float m_mult, hipStream_t st) {
+  constexpr int KB = sizeof(MT) == 1 ? 64 : 32;
+  const int tblocks = (g.T + kFT - 1) / kFT, kblocks = (g.K + KB - 1) / KB;
+  dim3 grid((unsigned)(tblocks * kblocks));
+  const int r = relu ? 1 : 0;
+  if (out_type == 0)
+    hipLaunchKernelGGL((k_fused<M, LEG, MT, 0>), grid, dim3(256), 0, st, x, V, y, g, in_mu, out_mu,
+                       m_mult, r, tblocks);
+  else
+    hipLaunchKernelGGL((k_fused<M, LEG, MT, 2>), grid, dim3(256), 0, st, x, V, y, g, in_mu, out_mu,
+                       m_mult, r, tblocks);
+  return hipGetLastError();
+}
+
+template <int M>
+static hipError_t fused_m(const Geometry& g, bool leg, const int8_t* x, const int8_t* V, void* y,
+                          int m_bits, int out_type, bool relu, const StageMults& in_mu,
+                          const StageMults& out_mu, float m_mult, hipStream_t st) {
+  if (leg)
+    return m_bits == 8 ? fused_mt<M, true, int8_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st)
+                       : fused_mt<M, true, int16_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st);
+  return m_bits == 8 ? fused_mt<M, false, int8_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st)
+                     : fused_mt<M, false, int16_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st);
+}
+
+hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x, const int8_t* V,
+                        void* y, int m_bits, int out_type, bool relu, const StageMults& in_mu,
+                        const StageMults& out_mu, float m_mult, hipStream_t st) {
+  if ((long)g.T * g.K == 0) return hipSuccess;
+  if ((m_bits != 8 && m_bits != 9) || (out_type != 0 && out_type != 2)) return hipErrorInvalidValue;
+  switch (g.m) {
+    case 2: return fused_m<2>(g, legendre_inner, x, V, y, m_bits, out_type, relu, in_mu, out_mu, m_mult, st);
+    case 4: return fused_m<4>(g, legendre_inner, x, V, y, m_bits, out_type, relu, in_mu, out_mu, m_mult, st);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace wino

@@ -58,6 +58,12 @@ hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const
                                    int m_bits, void* y, int out_type, bool relu,
                                    const StageMults& mu, hipStream_t st);
 
+// Fused variant (input transform + contraction + output transform in one kernel);
+// V is the transformed filter tensor.  m = 2 or 4, m_bits 8 or 9, out_type 0 or 2.
+hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x, const int8_t* V,
+                        void* y, int m_bits, int out_type, bool relu, const StageMults& in_mu,
+                        const StageMults& out_mu, float m_mult, hipStream_t st);
+
 // fp32 path: stage 0 weight (a = w), 1 input (a = x), 2 contraction (a = U, b = V),
 // 3 output (a = M); no casts, float tensors in the int8 path's layouts.
 hipError_t launch_stage_f32(int stage, const Geometry& g, bool legendre, const float* a,
