@@ -29,7 +29,7 @@ constexpr int kURow = kFC + 16;  // U_s row (one tile) in bytes, padded
 constexpr int kMRow = 64 + 4;    // M_s row (one tile) in bytes, padded
 
 template <int M, bool LEG, typename MT, int OUT>
-__global__ __launch_bounds__(256) void k_fused(const int8_t* __restrict__ x,
+__global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
                                                const int8_t* __restrict__ V,
                                                void* __restrict__ yv, Geometry g, StageMults in_mu,
                                                StageMults out_mu, float m_mult, int relu,
