@@ -22,10 +22,14 @@ num = N Xq N^T are exact integers; the stored code is
     q_ij = clamp( rint( float32(num_ij) * mult_ij ), -qmax, +qmax ),
     mult_ij = float32( s_prev / ( (rho_i*rho_j) * s_next ) )     (double inside)
 
-with int->float32 conversion and rint both round-to-nearest-even, one fp32
-multiply, qmax = 2^(bits-1) - 1.  A stored code q stands for the real q*s.
-This fp32 decision is deliberately the kernel's precision: where floating
-point decides an integer both sides must take the decision the same way.
+where the product of the two fp32 numbers is taken EXACTLY (it has at most 48
+significant bits, so float64 holds it) and rint rounds that exact product to
+the nearest integer, ties to even: one rounding for the int->float32
+conversion (to nearest even), one for the cast.  qmax = 2^(bits-1) - 1.  A
+stored code q stands for the real q*s.  The operands are deliberately the
+kernel's fp32 values: where floating point decides an integer both sides must
+take the decision from the same numbers (a fused multiply-add onto 1.5 * 2^23
+computes exactly this on the GPU).
 
 Layouts: x [N,H,W,C], w [K,C,r,r], U [n*n, T, C], V [n*n, K, C],
 M [n*n, T, K], y [N,H,W,K]; Winograd point p = i*n + j.
@@ -128,9 +132,8 @@ def requant(num, mult, qmax, ij_axes):
     shape = [1] * num.ndim
     shape[ij_axes[0]] = mult.shape[0]
     shape[ij_axes[1]] = mult.shape[1]
-    prod = to_f32(num) * mult.reshape(shape).astype(np.float32)
-    assert prod.dtype == np.float32
-    return np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
+    prod = to_f32(num).astype(np.float64) * mult.reshape(shape).astype(np.float32).astype(np.float64)
+    return np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)    # exact product, one rounding
 
 
 def calibrate(num, rho_i, rho_j, s_prev, qmax, ij_axes):
@@ -231,7 +234,8 @@ def contraction(U, V, cfg, scales, out):
         amax = float(np.max(np.abs(M.astype(np.float64) * s_uv))) if M.size else 0.0
         scales["s_m"] = np.float32(amax / qmax) if amax > 0 else np.float32(1.0)
     mult = np.float32(s_uv / float(scales["s_m"]))
-    Mq = np.clip(np.rint(M.astype(np.float32) * mult), -qmax, qmax).astype(np.int64)
+    prod = M.astype(np.float32).astype(np.float64) * np.float64(mult)   # exact product
+    Mq = np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
     out["M"] = Mq
     return Mq, scales["s_m"]
 

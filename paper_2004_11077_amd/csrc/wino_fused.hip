@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
     for (int kb = 0; kb < NKB; ++kb) {
       int q[4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)acc[pi][kb][v] * m_mult, QM);
+      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)acc[pi][kb][v], m_mult, QM);
       int8_t* dst = smem + (p * kFT + jl) * kMRow + (kb * 16 + 4 * seg) * (int)sizeof(MT);
       if constexpr (sizeof(MT) == 1) {
         *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
@@ -165,9 +165,10 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
     const int wk = g.W * g.K;
     auto to_float_approx = [](auto v) -> float {
       if constexpr (sizeof(v) == 8) {
-        const uint64_t a = (uint64_t)(v < 0 ? -v : v);
-        const float f = __builtin_fmaf((float)(uint32_t)(a >> 32), 4294967296.0f, (float)(uint32_t)a);
-        return v < 0 ? -f : f;
+        // v = hi * 2^32 + lo with a SIGNED low half, so small |v| has hi = 0
+        const int32_t lo = (int32_t)v;
+        const int32_t hi = (int32_t)(v >> 32) + (int32_t)((uint32_t)lo >> 31);
+        return __builtin_fmaf((float)hi, 4294967296.0f, (float)lo);
       } else {
         return (float)v;
       }
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
               float v = to_float_approx(num[i][j]) * out_mu.outer.v[idx];
               (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
             } else {
-              int v = cast_code((float)num[i][j] * out_mu.outer.v[idx], 127.f);
+              int v = cast_code((float)num[i][j], out_mu.outer.v[idx], 127.f);
               (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
             }
           }

@@ -6,11 +6,13 @@ namespace wino {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-// One symmetric cast: round to nearest even, clamp to +-qmax.
-// (clamp first, then the 1.5 * 2^23 trick: the fp32 add rounds to nearest even)
-__device__ __forceinline__ int cast_code(float v, float qmax) {
-  v = __builtin_amdgcn_fmed3f(v, -qmax, qmax);
-  return __float_as_int(v + 12582912.0f) - 0x4B400000;
+// One symmetric cast: q = clamp(rint(v * mult), +-qmax) with the exact product
+// rounded once, ties to even (fma onto 1.5 * 2^23, clamp of the biased float).
+__device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
+  constexpr float kMagic = 12582912.0f;
+  float t = __builtin_fmaf(v, mult, kMagic);
+  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
+  return __float_as_int(t) - 0x4B400000;
 }
 
 // ---------------------------------------------------------------------------
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
           uint32_t pk = 0;
 #pragma unroll
           for (int v = 0; v < 4; ++v) {
-            const int q = cast_code((float)acc[i][j][4 * gq + v] * mult, qmax);
+            const int q = cast_code((float)acc[i][j][4 * gq + v], mult, qmax);
             pk |= ((uint32_t)q & 0xffu) << (8 * v);
           }
           const int tl = wt * 64 + j * 32 + r;
@@ -173,7 +175,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
             if constexpr (sizeof(MT) == 4)
               q[v] = acc[i][j][4 * gq + v];
             else
-              q[v] = cast_code((float)acc[i][j][4 * gq + v] * mult, qmax);
+              q[v] = cast_code((float)acc[i][j][4 * gq + v], mult, qmax);
           }
           if constexpr (sizeof(MT) == 2) {
             uint2 pk;

@@ -61,6 +61,30 @@ __device__ __forceinline__ int32_t mulc(int32_t x) {
   else
     return x * (int32_t)CF;
 }
+// acc + x * c in one instruction.  The compiler would split a multiply-add by
+// a literal into v_mul_i32_i24 (literal form) plus an add; spelling the
+// instruction out with the constant in a scalar register keeps it one op.
+template <int64_t CF, bool S24>
+__device__ __forceinline__ int32_t madc(int32_t x, int32_t acc) {
+  constexpr int64_t a = CF < 0 ? -CF : CF;
+  if constexpr (CF == 1) {
+    return acc + x;
+  } else if constexpr (CF == -1) {
+    return acc - x;
+  } else if constexpr ((a & (a - 1)) == 0) {
+    return acc + x * (int32_t)CF;                // shift-add
+  } else if constexpr (S24 && a < (1 << 23)) {
+    int32_t r;
+    if constexpr (CF >= -16 && CF <= 64)
+      asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(x), "n"((int32_t)CF), "v"(acc));
+    else
+      asm("v_mad_i32_i24 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"((int32_t)CF), "v"(acc));
+    return r;
+  } else {
+    return acc + x * (int32_t)CF;
+  }
+}
+
 // 32-bit operand, 64-bit product (one v_mad_i64_i32 when accumulated).
 template <int64_t CF>
 __device__ __forceinline__ int64_t mulc_wide(int32_t x) {
@@ -70,6 +94,13 @@ __device__ __forceinline__ int64_t mulc_wide(int32_t x) {
 template <int64_t CF>
 __device__ __forceinline__ int64_t mulc_wide(int64_t x) {
   return x * CF;
+}
+
+// Is column `a` the first non-zero coefficient of row `i`?
+constexpr bool first_nz(const IMat& t, int i, int a) {
+  for (int k = 0; k < a; ++k)
+    if (t.N[i][k] != 0) return false;
+  return true;
 }
 
 constexpr bool coef_fit_i32(const IMat& t) {
@@ -100,8 +131,12 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
       static_for<0, T.cols>([&](auto a) {
         constexpr int64_t c = T.N[decltype(i)::value][decltype(a)::value];
         if constexpr (c != 0) {
-          if constexpr (sizeof(TmpT) == 4)
-            acc += mulc<c, s1>((int32_t)x[a][b]);
+          if constexpr (sizeof(TmpT) == 4) {
+            if constexpr (first_nz(T, decltype(i)::value, decltype(a)::value))
+              acc = mulc<c, s1>((int32_t)x[a][b]);
+            else
+              acc = madc<c, s1>((int32_t)x[a][b], acc);
+          }
           else
             acc += mulc_wide<c>((int64_t)x[a][b]);
         }
@@ -115,8 +150,12 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
       static_for<0, T.cols>([&](auto b) {
         constexpr int64_t c = T.N[decltype(j)::value][decltype(b)::value];
         if constexpr (c != 0) {
-          if constexpr (sizeof(AccT) == 4)
-            acc += mulc<c, s2>(tmp[i][b]);
+          if constexpr (sizeof(AccT) == 4) {
+            if constexpr (first_nz(T, decltype(j)::value, decltype(b)::value))
+              acc = mulc<c, s2>(tmp[i][b]);
+            else
+              acc = madc<c, s2>(tmp[i][b], acc);
+          }
           else
             acc += mulc_wide<c>(tmp[i][b]);
         }
@@ -126,13 +165,17 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
   });
 }
 
-// One symmetric cast, q = clamp(rint(v), +-qmax) with rint = round half to
-// even.  Clamping first is equivalent (the bounds are integers and rint is
-// monotone); adding 1.5 * 2^23 then leaves the rounded integer in the low
-// mantissa bits (the fp32 add itself rounds to nearest even), for |v| < 2^22.
-__device__ __forceinline__ int cast_code(float v, float qmax) {
-  v = __builtin_amdgcn_fmed3f(v, -qmax, qmax);
-  return __float_as_int(v + 12582912.0f) - 0x4B400000;
+// One symmetric cast: q = clamp(rint(v * mult), +-qmax), where rint rounds the
+// EXACT product of the two fp32 numbers to the nearest integer, ties to even.
+// One fused multiply-add does it: v * mult + 1.5 * 2^23 is rounded once, to a
+// float whose ulp is 1, so the integer sits in the low mantissa bits.  Products
+// beyond +-2^22 leave that binade but stay on the right side of the clamp,
+// which is applied to the biased float (a cast costs: convert, fma, med3).
+constexpr float kMagic = 12582912.0f;   // 1.5 * 2^23, bit pattern 0x4B400000
+__device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
+  float t = __builtin_fmaf(v, mult, kMagic);
+  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
+  return __float_as_int(t) - 0x4B400000;
 }
 
 template <int R, typename AccT>
@@ -140,7 +183,7 @@ __device__ __forceinline__ void cast_tile(const AccT (&num)[R][R], const MultTab
                                           int (&q)[R][R]) {
   static_for<0, R>([&](auto i) {
     static_for<0, R>([&](auto j) {
-      q[i][j] = cast_code((float)num[i][j] * mu.v[decltype(i)::value * R + decltype(j)::value],
+      q[i][j] = cast_code((float)num[i][j], mu.v[decltype(i)::value * R + decltype(j)::value],
                           qmax);
     });
   });
@@ -343,10 +386,10 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   // int8 output below keeps the exact single-rounding conversion.
   auto to_float_approx = [](auto v) -> float {
     if constexpr (sizeof(v) == 8) {
-      const uint64_t a = (uint64_t)(v < 0 ? -v : v);     // magnitude first: no cancellation
-      const float f = __builtin_fmaf((float)(uint32_t)(a >> 32), 4294967296.0f,
-                                     (float)(uint32_t)a);
-      return v < 0 ? -f : f;
+      // v = hi * 2^32 + lo with a SIGNED low half, so small |v| has hi = 0
+      const int32_t lo = (int32_t)v;
+      const int32_t hi = (int32_t)(v >> 32) + (int32_t)((uint32_t)lo >> 31);
+      return __builtin_fmaf((float)hi, 4294967296.0f, (float)lo);
     } else {
       return (float)v;
     }
@@ -368,7 +411,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
             int v = (int)num[i][j];
             (static_cast<int*>(yv) + ybase)[rel] = relu ? max(v, 0) : v;
           } else {
-            int v = cast_code((float)num[i][j] * mu.outer.v[idx], 127.f);
+            int v = cast_code((float)num[i][j], mu.outer.v[idx], 127.f);
             (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
           }
         }

@@ -119,5 +119,5 @@ def test_stage_calls_reject_bad_arguments_before_any_launch():
     assert lib.wino_contract(C.byref(d), C.c_void_p(4100), fake, fake, C.byref(s), None) == -1
     assert b"aligned" in lib.wino_last_error()
     assert lib.wino_conv2d(C.byref(d), fake, fake, fake, C.byref(s), fake, 16, None) == -4
-    dfused = wn.ConvDesc(1, 8, 8, 16, 16, fused=1)
+    dfused = wn.ConvDesc(1, 8, 8, 16, 16, m=6, fused=1)     # the fused variant has no F(6,3)
     assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(s), fake, 1 << 30, None) == -2
