@@ -25,8 +25,7 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # a plain 64 MiB device copy of the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4a_f4_c256": {"weight_transform": (675.7 + 2304.0) * 1024,
-                      "input_transform": (6525.2 + 9216.0) * 1024,
+    "cfg4a_f4_c256": {"operand_transforms": (675.7 + 2304.0 + 6525.2 + 9216.0) * 1024,
                       "contraction": (20866.0 + 9216.0) * 1024,
                       "output_transform": (9369.9 + 16384.0) * 1024},
 }
@@ -56,6 +55,11 @@ def stage_model(wl, m_bytes, y_bytes, mats):
     model = _stage_bytes(wl, m_bytes, y_bytes, n, T, C, K)
     for k, v in alu.items():
         model[k]["alu_ops"] = v
+    # a1 and a2 run as one launch
+    model["operand_transforms"] = {
+        "bound": "hbm",
+        "work": model["weight_transform"]["work"] + model["input_transform"]["work"],
+        "alu_ops": model["weight_transform"]["alu_ops"] + model["input_transform"]["alu_ops"]}
     return model
 
 
@@ -137,23 +141,21 @@ def main():
     y = torch.empty((wl.N, wl.H, wl.W, wl.K), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
-    names = ["weight_transform", "input_transform", "contraction", "output_transform"]
+    # the three launches wino_conv2d makes for a layer whose filters arrive untransformed
+    names = ["operand_transforms", "contraction", "output_transform"]
 
     def step(events=None):
         if events is not None:
             events[0].record(stream)
-        wn.wino_weight_transform(desc, w, V, sc, stream)
+        wn.wino_transform_operands(desc, x, U, w, V, sc, stream)    # a1 + a2, one launch
         if events is not None:
             events[1].record(stream)
-        wn.wino_input_transform(desc, x, U, sc, stream)
-        if events is not None:
-            events[2].record(stream)
         wn.wino_contract(desc, U, V, M, sc, stream)
         if events is not None:
-            events[3].record(stream)
+            events[2].record(stream)
         wn.wino_output_transform(desc, M, y, sc, stream)
         if events is not None:
-            events[4].record(stream)
+            events[3].record(stream)
 
     for _ in range(args.warmup):
         step()
@@ -169,24 +171,24 @@ def main():
     # itself add a third to the step time).  Each event-to-event interval still
     # carries the marker/dispatch overhead of the two events (about 3 us on
     # this runtime, see profiles/): the stage durations below are therefore
-    # upper bounds and the roofline fractions lower bounds.  A sixth event
-    # directly after the fifth records what an empty interval costs; it is
+    # upper bounds and the roofline fractions lower bounds.  A fifth event
+    # directly after the fourth records what an empty interval costs; it is
     # reported, not subtracted.
     stride = 8
     sampled = list(range(0, args.steps, stride))
-    evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(6)] for i in sampled}
+    evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(5)] for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         if i in evs:
             step(evs[i])
-            evs[i][5].record(stream)
+            evs[i][4].record(stream)
         else:
             step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    null_ms = float(np.median([evs[i][4].elapsed_time(evs[i][5]) for i in sampled]))
+    null_ms = float(np.median([evs[i][3].elapsed_time(evs[i][4]) for i in sampled]))
     raw_ms = {nm: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in sampled]))
               for j, nm in enumerate(names)}
     stage_ms = raw_ms
@@ -242,7 +244,7 @@ def main():
                    "N": wl.N, "H": wl.H, "W": wl.W, "C": wl.C, "K": wl.K,
                    "algorithm": "F(%dx%d,3x3) %s base" % (wl.m, wl.m, wl.base),
                    "bits_hadamard": wl.bits_hadamard, "output": "fp32",
-                   "step": "weight+input transform, contraction, output transform"},
+                   "step": "weight+input transforms (one launch), contraction, output transform"},
         "roofline": roofline,
         "stages": stages,
     }

@@ -126,6 +126,12 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
 /* Input bracket of eq. 3 / eq. 4: x -> U. */
 int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
                          const wino_scales_t* s, void* hip_stream);
+/* Both operand transforms of a layer, x -> U and w -> V (eq. 1 / eq. 2 and the
+ * input bracket of eq. 3 / eq. 4), queued as ONE kernel launch: they are
+ * independent, and a layer that transforms its filters on the fly saves a
+ * launch.  Results are identical to the two separate calls. */
+int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, const void* w,
+                            void* V, const wino_scales_t* s, void* hip_stream);
 /* Hadamard product summed over input channels: M[p][t][k] = sum_c U V, then
  * the cast to bits_hadamard (int8 MFMA, int32 accumulation). */
 int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void* M,

@@ -10,7 +10,7 @@ OUT_F32, OUT_I32, OUT_I8 = 0, 1, 2
 MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
 EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
            "wino_workspace_bytes", "wino_conv2d", "wino_weight_transform",
-           "wino_input_transform", "wino_contract", "wino_output_transform", "wino_last_error")
+           "wino_input_transform", "wino_transform_operands", "wino_contract", "wino_output_transform", "wino_last_error")
 
 
 class WinoError(RuntimeError):
@@ -86,6 +86,7 @@ def _load():
     lib.wino_conv2d.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_weight_transform.argtypes = [dp, vp, vp, sp, vp]
     lib.wino_input_transform.argtypes = [dp, vp, vp, sp, vp]
+    lib.wino_transform_operands.argtypes = [dp, vp, vp, vp, vp, sp, vp]
     lib.wino_contract.argtypes = [dp, vp, vp, vp, sp, vp]
     lib.wino_output_transform.argtypes = [dp, vp, vp, sp, vp]
     _lib = lib
@@ -178,6 +179,13 @@ def wino_input_transform(desc, x, U, scales, stream=None):
     _check(_load().wino_input_transform(C.byref(desc), _ptr(x), _ptr(U), C.byref(sc),
                                         _stream(stream)))
     return U
+
+
+def wino_transform_operands(desc, x, U, w, V, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_transform_operands(C.byref(desc), _ptr(x), _ptr(U), _ptr(w), _ptr(V),
+                                           C.byref(sc), _stream(stream)))
+    return U, V
 
 
 def wino_contract(desc, U, V, M, scales, stream=None):

@@ -327,6 +327,30 @@ int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
   return e == hipSuccess ? WINO_OK : fail_hip(e, "input transform launch");
 }
 
+int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, const void* w,
+                            void* V, const wino_scales_t* s, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (p.fp32) {   // the unquantised path keeps its two separate launches
+    if (int rc = wino_weight_transform(d, w, V, s, hip_stream)) return rc;
+    return wino_input_transform(d, x, U, s, hip_stream);
+  }
+  if (int rc = need(x, "x")) return rc;
+  if (int rc = need(U, "U")) return rc;
+  if (int rc = need(w, "w")) return rc;
+  if (int rc = need(V, "V")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  if (int rc = aligned(x, 16, "x")) return rc;
+  if (int rc = aligned(U, 16, "U")) return rc;
+  StageMults mu_in, mu_w;
+  if (int rc = input_mults(p, s, &mu_in)) return rc;
+  if (int rc = weight_mults(p, s, &mu_w)) return rc;
+  hipError_t e = launch_operand_transforms(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U,
+                                           (const int8_t*)w, (int8_t*)V, mu_in, mu_w,
+                                           (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "operand transforms launch");
+}
+
 int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void* M,
                   const wino_scales_t* s, void* hip_stream) {
   Plan p;
@@ -389,10 +413,15 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   char* ws = static_cast<char*>(workspace);
   const void* V = w_or_V;
+  void* Vws = nullptr;
   if (!d->weights_pretransformed) {
-    if (int rc = wino_weight_transform(d, w_or_V, ws, s, hip_stream)) return rc;
+    Vws = ws;
     V = ws;
     ws += round256(n2 * d->K * d->C * (p.fp32 ? 4 : 1));
+    // the fused variant transforms the filters on their own; the split path
+    // does it together with the input transform, in one launch (below)
+    if (d->fused)
+      if (int rc = wino_weight_transform(d, w_or_V, Vws, s, hip_stream)) return rc;
   }
   if (d->fused) {
     if (int rc = need(x, "x")) return rc;
@@ -413,7 +442,11 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   void* U = ws;
   ws += round256(n2 * p.g.T * d->C * (p.fp32 ? 4 : 1));
   void* M = ws;
-  if (int rc = wino_input_transform(d, x, U, s, hip_stream)) return rc;
+  if (Vws) {
+    if (int rc = wino_transform_operands(d, x, U, w_or_V, Vws, s, hip_stream)) return rc;
+  } else {
+    if (int rc = wino_input_transform(d, x, U, s, hip_stream)) return rc;
+  }
   if (int rc = wino_contract(d, U, V, M, s, hip_stream)) return rc;
   return wino_output_transform(d, M, y, s, hip_stream);
 }

@@ -35,15 +35,20 @@ __device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
 // each with a private L2): the k blocks that share a set of U rows then share
 // one L2, and the number of groups is chosen to spread n*n points evenly.
 // ---------------------------------------------------------------------------
-constexpr int kTT = 128, kKT = 128, kCK = 128, kRow = kCK + 16;
+constexpr int kTT = 128, kKT = 128;
 
-template <typename MT>
+template <typename MT, int kCK>
 __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
                                                   const int8_t* __restrict__ V,
                                                   MT* __restrict__ Mo, int T, int C, int K,
                                                   int tblocks, int kblocks, int tgroups, int tpg,
                                                   int units, float mult, float qmax) {
-  __shared__ __attribute__((aligned(16))) int8_t smem[(kKT + kTT) * kRow];
+  constexpr int kRow = kCK + 16;               // padded LDS row
+  constexpr int LPR = kCK / 16;                // lanes per staged row
+  constexpr int RPP = 256 / LPR;               // rows staged per pass
+  constexpr int NP = 128 / RPP;                // passes per operand
+  constexpr int kSm = (kKT + kTT) * kRow > kTT * (kKT + 4) ? (kKT + kTT) * kRow : kTT * (kKT + 4);
+  __shared__ __attribute__((aligned(16))) int8_t smem[kSm];
   int8_t* sA = smem;                  // V rows (k)
   int8_t* sB = smem + kKT * kRow;     // U rows (t)
 
@@ -65,27 +70,27 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   const int r = lane & 31, h = lane >> 5;
 
   // staging map: 8 lanes cover one 128-byte row chunk, 4 rows per 32 lanes
-  const int srow = tid >> 3, sseg = (tid & 7) * 16;
-  const int8_t* ga[4];
-  const int8_t* gb[4];
+  const int srow = tid / LPR, sseg = (tid % LPR) * 16;
+  const int8_t* ga[NP];
+  const int8_t* gb[NP];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int row = srow + i * 32;
+  for (int i = 0; i < NP; ++i) {
+    const int row = srow + i * RPP;
     const int kr = min(k0 + row, K - 1), tr = min(t0 + row, T - 1);   // clamp, mask later
     ga[i] = V + ((long)p * K + kr) * C + sseg;
     gb[i] = U + ((long)p * T + tr) * C + sseg;
   }
   // one register set: the next chunk is in flight while this one feeds the MFMAs
   // (a second set costs a third of the occupancy and measured slower)
-  v4i ra0[4], rb0[4];
-  auto fetch = [&](v4i (&ra)[4], v4i (&rb)[4], int c0) {
+  v4i ra0[NP], rb0[NP];
+  auto fetch = [&](v4i (&ra)[NP], v4i (&rb)[NP], int c0) {
     // columns past C (last chunk when C is not a multiple of 128) are read
     // from a clamped in-bounds column and zeroed, without branching
     const bool ok = c0 + sseg < C;
     const int cc = ok ? c0 : C - 16 - sseg;
     const int keep = ok ? -1 : 0;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < NP; ++i) {
       ra[i] = *reinterpret_cast<const v4i*>(ga[i] + cc) & keep;
       rb[i] = *reinterpret_cast<const v4i*>(gb[i] + cc) & keep;
     }
@@ -97,12 +102,12 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
 #pragma unroll
     for (int j = 0; j < 2; ++j) acc[i][j] = v16i{};
 
-  auto chunk = [&](v4i (&ra)[4], v4i (&rb)[4], int c0) {
+  auto chunk = [&](v4i (&ra)[NP], v4i (&rb)[NP], int c0) {
     if (c0) __syncthreads();             // previous chunk fully consumed
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<v4i*>(sA + (srow + i * 32) * kRow + sseg) = ra[i];
-      *reinterpret_cast<v4i*>(sB + (srow + i * 32) * kRow + sseg) = rb[i];
+    for (int i = 0; i < NP; ++i) {
+      *reinterpret_cast<v4i*>(sA + (srow + i * RPP) * kRow + sseg) = ra[i];
+      *reinterpret_cast<v4i*>(sB + (srow + i * RPP) * kRow + sseg) = rb[i];
     }
     __syncthreads();
     if (c0 + kCK < C) fetch(ra, rb, c0 + kCK);
@@ -212,6 +217,19 @@ hipError_t launch_input_transform(const Geometry& g, bool leg, const int8_t* x, 
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_operand_transforms(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+                                     const int8_t* w, int8_t* V, const StageMults& mu_in,
+                                     const StageMults& mu_w, hipStream_t st) {
+  if ((long)g.T * g.C == 0) return launch_weight_transform(g, leg, w, V, mu_w, st);
+  if ((long)g.K * g.C == 0) return launch_input_transform(g, leg, x, U, mu_in, st);
+  switch (g.m) {
+    case 2: return PerM<2>::operands(g, leg, x, U, w, V, mu_in, mu_w, st);
+    case 4: return PerM<4>::operands(g, leg, x, U, w, V, mu_in, mu_w, st);
+    case 6: return PerM<6>::operands(g, leg, x, U, w, V, mu_in, mu_w, st);
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,
                            int m_bits, float mult, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
@@ -225,13 +243,13 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   dim3 grid((unsigned)nblocks);
   if (m_bits == 8)
-    hipLaunchKernelGGL((k_contract<int8_t>), grid, dim3(256), 0, st, U, V, (int8_t*)Mo, g.T, g.C,
+    hipLaunchKernelGGL((k_contract<int8_t, 128>), grid, dim3(256), 0, st, U, V, (int8_t*)Mo, g.T, g.C,
                        g.K, tblocks, kblocks, tgroups, tpg, units, mult, 127.f);
   else if (m_bits == 9)
-    hipLaunchKernelGGL((k_contract<int16_t>), grid, dim3(256), 0, st, U, V, (int16_t*)Mo, g.T,
+    hipLaunchKernelGGL((k_contract<int16_t, 128>), grid, dim3(256), 0, st, U, V, (int16_t*)Mo, g.T,
                        g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 255.f);
   else
-    hipLaunchKernelGGL((k_contract<int32_t>), grid, dim3(256), 0, st, U, V, (int32_t*)Mo, g.T,
+    hipLaunchKernelGGL((k_contract<int32_t, 128>), grid, dim3(256), 0, st, U, V, (int32_t*)Mo, g.T,
                        g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 0.f);
   return hipGetLastError();
 }

@@ -35,6 +35,9 @@ struct PerM {
                            const StageMults& mu, hipStream_t st);
   static hipError_t input(const Geometry& g, bool legendre_inner, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st);
+  static hipError_t operands(const Geometry& g, bool legendre_inner, const int8_t* x, int8_t* U,
+                             const int8_t* w, int8_t* V, const StageMults& mu_in,
+                             const StageMults& mu_w, hipStream_t st);
   static hipError_t output(const Geometry& g, bool legendre_inner, const void* M_, int m_bits,
                            void* y, int out_type, bool relu, const StageMults& mu,
                            hipStream_t st);
@@ -49,6 +52,11 @@ hipError_t launch_weight_transform(const Geometry& g, bool legendre_inner, const
                                    int8_t* V, const StageMults& mu, hipStream_t st);
 hipError_t launch_input_transform(const Geometry& g, bool legendre_inner, const int8_t* x,
                                   int8_t* U, const StageMults& mu, hipStream_t st);
+// Input and weight transform in one launch (both outputs non-empty).
+hipError_t launch_operand_transforms(const Geometry& g, bool legendre_inner, const int8_t* x,
+                                     int8_t* U, const int8_t* w, int8_t* V,
+                                     const StageMults& mu_in, const StageMults& mu_w,
+                                     hipStream_t st);
 // m_bits: 8 -> int8 M, 9 -> int16 M, 32 -> int32 M (no cast).
 hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* M,
                            int m_bits, float mult, hipStream_t st);

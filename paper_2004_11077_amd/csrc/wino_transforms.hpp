@@ -193,12 +193,12 @@ __device__ __forceinline__ void cast_tile(const AccT (&num)[R][R], const MultTab
 // Weight transform: one lane per (k, c) filter.
 // ---------------------------------------------------------------------------
 template <int M, bool LEG>
-__global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restrict__ w,
-                                                          int8_t* __restrict__ V, Geometry g,
-                                                          StageMults mu) {
+__device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t* __restrict__ V,
+                                            const Geometry& g, const StageMults& mu,
+                                            unsigned block) {
   constexpr int n = M + 2;
   using TB = Tab<M>;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   const long KC = (long)g.K * g.C;
   if (gid >= KC) return;
   int wi[3][3];
@@ -237,15 +237,15 @@ __global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restri
 // Out-of-image pixels are staged as zeros.
 // ---------------------------------------------------------------------------
 template <int M, bool LEG>
-__global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
-                                                         int8_t* __restrict__ U, Geometry g,
-                                                         StageMults mu) {
+__device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t* __restrict__ U,
+                                           const Geometry& g, const StageMults& mu,
+                                           unsigned block) {
   constexpr int n = M + 2, n2 = n * n;
   using TB = Tab<M>;
   __shared__ __attribute__((aligned(16))) int8_t s_in[n2 * 256];
   __shared__ __attribute__((aligned(16))) int8_t s_out[n2 * 256];
   const int tid = threadIdx.x;
-  const long gid0 = (long)blockIdx.x * 256;
+  const long gid0 = (long)block * 256;
   const long total = (long)g.T * g.C;
 
   // staging role of this lane: 16-byte unit `u` of the block's item range
@@ -307,6 +307,37 @@ __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restric
       *reinterpret_cast<v4i*>(ub + (long)p * total) =
           *reinterpret_cast<const v4i*>(s_out + p * 256 + u * 16);
   }
+}
+
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restrict__ w,
+                                                          int8_t* __restrict__ V, Geometry g,
+                                                          StageMults mu) {
+  weight_body<M, LEG>(w, V, g, mu, blockIdx.x);
+}
+
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
+                                                         int8_t* __restrict__ U, Geometry g,
+                                                         StageMults mu) {
+  input_body<M, LEG>(x, U, g, mu, blockIdx.x);
+}
+
+// Both operand transforms in one launch (they are independent): the first
+// `nb_in` work groups transform input tiles, the rest transform filters.  One
+// launch less per layer, and the small filter transform fills the tail of the
+// input transform instead of paying its own ramp-up and drain.
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_operand_transforms(const int8_t* __restrict__ x,
+                                                            int8_t* __restrict__ U,
+                                                            const int8_t* __restrict__ w,
+                                                            int8_t* __restrict__ V, Geometry g,
+                                                            StageMults mu_in, StageMults mu_w,
+                                                            unsigned nb_in) {
+  if (blockIdx.x < nb_in)
+    input_body<M, LEG>(x, U, g, mu_in, blockIdx.x);
+  else
+    weight_body<M, LEG>(w, V, g, mu_w, blockIdx.x - nb_in);
 }
 
 // ---------------------------------------------------------------------------
@@ -457,6 +488,20 @@ hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* 
     hipLaunchKernelGGL((k_input_transform<M, true>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
   else
     hipLaunchKernelGGL((k_input_transform<M, false>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
+  return hipGetLastError();
+}
+
+template <int M>
+hipError_t PerM<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+                             const int8_t* w, int8_t* V, const StageMults& mu_in,
+                             const StageMults& mu_w, hipStream_t st) {
+  const unsigned nb_in = blocks_for((long)g.T * g.C), nb_w = blocks_for((long)g.K * g.C);
+  if (leg)
+    hipLaunchKernelGGL((k_operand_transforms<M, true>), dim3(nb_in + nb_w), dim3(256), 0, st, x, U,
+                       w, V, g, mu_in, mu_w, nb_in);
+  else
+    hipLaunchKernelGGL((k_operand_transforms<M, false>), dim3(nb_in + nb_w), dim3(256), 0, st, x,
+                       U, w, V, g, mu_in, mu_w, nb_in);
   return hipGetLastError();
 }
 

@@ -92,3 +92,22 @@ def test_full_size_configurations(name):
     L = si.make_layer(wl)
     run_case(L["xq"], L["wq"], L["s_x"], L["s_w"], whole=True, m=wl.m, base=wl.base,
              bits_hadamard=wl.bits_hadamard)
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_operand_transforms_in_one_launch_equal_the_two_calls(m):
+    import torch
+    import paper_2004_11077_amd as wn
+    xq, wq, s_x, s_w = small_layer(3, 9, 7, 48, 80, seed=70 + m)
+    ora, sc = oracle_layer(xq, wq, s_x, s_w, m=m)
+    dev = torch.device("cuda:0")
+    desc = wn.ConvDesc(3, 9, 7, 48, 80, m=m)
+    n2, T = desc.n ** 2, desc.tiles
+    x = torch.from_numpy(xq).to(dev)
+    w = torch.from_numpy(wq).to(dev)
+    U = torch.full((n2, T, 48), 77, dtype=torch.int8, device=dev)
+    V = torch.full((n2, 80, 48), 77, dtype=torch.int8, device=dev)
+    wn.wino_transform_operands(desc, x, U, w, V, wn.Scales.from_dict(sc))
+    torch.cuda.synchronize()
+    assert np.array_equal(U.cpu().numpy().astype(np.int64), ora["U"])
+    assert np.array_equal(V.cpu().numpy().astype(np.int64), ora["V"])
