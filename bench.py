@@ -25,9 +25,9 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # a plain 64 MiB device copy of the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4a_f4_c256": {"operand_transforms": (675.7 + 2304.0 + 6525.2 + 9216.0) * 1024,
-                      "contraction": (20866.0 + 9216.0) * 1024,
-                      "output_transform": (9369.9 + 16384.0) * 1024},
+    "cfg4a_f4_c256": {"operand_transforms": (7191.7 + 11520.1) * 1024,
+                      "contraction": (13934.6 + 9216.0) * 1024,
+                      "output_transform": (9353.7 + 16384.0) * 1024},
 }
 
 
@@ -248,6 +248,23 @@ def main():
         "roofline": roofline,
         "stages": stages,
     }
+    # extra: the single-kernel fused variant on the same workload (same step
+    # definition: filter transform + fused kernel), timed the same way
+    if wl.m in (2, 4) and wl.bits_hadamard in (8, 9):
+        fdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                            bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=1)
+        fws = torch.empty(wn.wino_workspace_bytes(fdesc), dtype=torch.uint8, device=dev)
+        for _ in range(args.warmup):
+            wn.wino_conv2d(fdesc, x, w, y, sc, fws, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            wn.wino_conv2d(fdesc, x, w, y, sc, fws, stream)
+        torch.cuda.synchronize()
+        fdt = (time.perf_counter() - t0) / args.steps
+        out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
+                                "unit": "TOPS",
+                                "note": "input transform recomputed per 64-channel k block"}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si.WORKLOADS[args.workload])
     print(json.dumps(out))
