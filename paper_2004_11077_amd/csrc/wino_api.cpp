@@ -291,6 +291,7 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
                           const wino_scales_t* s, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
+  if ((long)p.g.K * p.g.C == 0) return WINO_OK;   // empty problem: nothing to launch, pointers may be null
   if (int rc = need(w, "w")) return rc;
   if (int rc = need(V, "V")) return rc;
   if (p.fp32) {
@@ -310,6 +311,7 @@ int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
                          const wino_scales_t* s, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
+  if ((long)p.g.T * p.g.C == 0) return WINO_OK;   // empty problem: nothing to launch, pointers may be null
   if (int rc = need(x, "x")) return rc;
   if (int rc = need(U, "U")) return rc;
   if (p.fp32) {
@@ -331,6 +333,7 @@ int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, c
                             void* V, const wino_scales_t* s, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
+  if ((long)p.g.T * p.g.C == 0 && (long)p.g.K * p.g.C == 0) return WINO_OK;   // empty problem: nothing to launch, pointers may be null
   if (p.fp32) {   // the unquantised path keeps its two separate launches
     if (int rc = wino_weight_transform(d, w, V, s, hip_stream)) return rc;
     return wino_input_transform(d, x, U, s, hip_stream);
@@ -355,6 +358,7 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
                   const wino_scales_t* s, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
+  if ((long)p.g.T * p.g.K == 0) return WINO_OK;   // empty problem: nothing to launch, pointers may be null
   if (int rc = need(U, "U")) return rc;
   if (int rc = need(V, "V")) return rc;
   if (int rc = need(M, "M")) return rc;
@@ -379,6 +383,7 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
                           const wino_scales_t* s, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
+  if ((long)p.g.T * p.g.K == 0) return WINO_OK;   // empty problem: nothing to launch, pointers may be null
   if (int rc = need(M, "M")) return rc;
   if (int rc = need(y, "y")) return rc;
   if (p.fp32) {
@@ -400,6 +405,7 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
                 const wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
+  if (p.g.T == 0 || p.g.K == 0) return WINO_OK;   // no output element exists
   if (d->fused) {
     if (p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32)
       return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "

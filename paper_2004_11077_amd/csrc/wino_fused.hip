@@ -6,8 +6,9 @@
 // Work group = 4 waves, 16 tiles x KB output channels (KB = 64 for an int8 M,
 // 32 for the 9-bit int16 M), all n*n Winograd points.  Loop over the input
 // channels in chunks of 64:
-//   A  every lane transforms (tile, channel) items of the chunk exactly as the
-//      split input-transform kernel does and drops the n*n codes into LDS as
+//   A  four tiles at a time: their pixels are staged in LDS with 16-byte loads,
+//      every lane transforms one (tile, channel) item exactly as the split
+//      input-transform kernel does and drops the n*n codes into LDS as
 //      U_s[point][tile][channel];
 //   B  wave w takes points w, w+4, ...: for each, one 16x16x64 int8 MFMA per
 //      16 output channels, A operand = V rows (k) straight from global / L2,
@@ -43,6 +44,7 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
   using TB = Tab<M>;
   static_assert(n2 * kFT * kMRow <= n2 * kFT * kURow);
   __shared__ __attribute__((aligned(16))) int8_t smem[n2 * kFT * kURow];
+  __shared__ __attribute__((aligned(16))) int8_t s_x[4 * n2 * kFC];   // input pixels of one pass
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int tb = blockIdx.x % tblocks, kblk = blockIdx.x / tblocks;
@@ -57,26 +59,38 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
 
   for (int c0 = 0; c0 < g.C; c0 += kFC) {
     if (c0) __syncthreads();                         // U_s of the previous chunk consumed
-    // ---- A: input transform of 16 tiles x 64 channels, 4 items per lane ----
+    // ---- A: input transform of 16 tiles x 64 channels, 4 tiles per pass ----
 #pragma unroll 1
     for (int it = 0; it < kFT / 4; ++it) {
+      // stage the n*n pixels x 64 channels of the pass's 4 tiles with 16-byte
+      // loads (zeros outside the image, past the last tile or channel)
+      if (it) __syncthreads();                       // s_x of the previous pass consumed
+#pragma unroll
+      for (int j = 0; j < (4 * n2 * 4 + 255) / 256; ++j) {
+        const int idx = j * 256 + tid;
+        if (idx < 4 * n2 * 4) {
+          const int tq = idx / (n2 * 4), rem = idx - tq * (n2 * 4);
+          const int pix = rem >> 2, sg = rem & 3;
+          const int t = t0 + it * 4 + tq, c = c0 + sg * 16;
+          v4i v = {0, 0, 0, 0};
+          if (t < g.T && c < g.C) {
+            const int tx = t % g.TW;
+            const int ty = (t / g.TW) % g.TH;
+            const int b = t / (g.TW * g.TH);
+            const int a = pix / n, bb = pix - a * n;
+            const int h = ty * M - 1 + a, ww = tx * M - 1 + bb;
+            if (h >= 0 && h < g.H && ww >= 0 && ww < g.W)
+              v = *reinterpret_cast<const v4i*>(x + (((long)b * g.H + h) * g.W + ww) * g.C + c);
+          }
+          *reinterpret_cast<v4i*>(s_x + (tq * n2 + pix) * kFC + sg * 16) = v;
+        }
+      }
+      __syncthreads();
       const int tl = it * 4 + wave;                  // a wave = one tile, 64 channels
-      const int t = t0 + tl, c = c0 + lane;
-      const bool live = t < g.T && c < g.C;
-      const int tt = live ? t : 0, cc = live ? c : 0;
-      const int tx = tt % g.TW;
-      const int ty = (tt / g.TW) % g.TH;
-      const int b = tt / (g.TW * g.TH);
-      const int8_t* xb = x + (long)b * g.H * g.W * g.C + cc;
       int xi[n][n];
       static_for<0, n>([&](auto a) {
         static_for<0, n>([&](auto bb) {
-          const int h = ty * M - 1 + decltype(a)::value;
-          const int ww = tx * M - 1 + decltype(bb)::value;
-          const bool in = live && h >= 0 && h < g.H && ww >= 0 && ww < g.W;
-          const int hh = min(max(h, 0), g.H - 1), wc = min(max(ww, 0), g.W - 1);
-          const int v = xb[((long)hh * g.W + wc) * g.C];
-          xi[a][bb] = in ? v : 0;
+          xi[a][bb] = s_x[(wave * n2 + decltype(a)::value * n + decltype(bb)::value) * kFC + lane];
         });
       });
       int q[n][n];

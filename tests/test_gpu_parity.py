@@ -111,3 +111,20 @@ def test_operand_transforms_in_one_launch_equal_the_two_calls(m):
     torch.cuda.synchronize()
     assert np.array_equal(U.cpu().numpy().astype(np.int64), ora["U"])
     assert np.array_equal(V.cpu().numpy().astype(np.int64), ora["V"])
+
+
+def test_empty_batch_is_a_no_op():
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    desc = wn.ConvDesc(0, 8, 8, 16, 16, m=4)
+    e8 = torch.empty(0, dtype=torch.int8, device=dev)
+    y = torch.empty((0, 8, 8, 16), dtype=torch.float32, device=dev)
+    w = torch.zeros((16, 16, 3, 3), dtype=torch.int8, device=dev)
+    ws = torch.empty(max(256, wn.wino_workspace_bytes(desc)), dtype=torch.uint8, device=dev)
+    sc = wn.Scales.from_dict({})
+    wn.wino_conv2d(desc, e8, w, y, sc, ws)
+    wn.wino_input_transform(desc, e8, e8, sc)
+    wn.wino_contract(desc, e8, ws, e8, sc)
+    wn.wino_output_transform(desc, e8, y, sc)
+    torch.cuda.synchronize()
