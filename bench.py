@@ -119,7 +119,6 @@ def main():
     import paper_2004_11077_amd as wn
 
     wl = si.WORKLOADS[args.workload]
-    scales = si.workload_scales(wl.name)
     if args.batch_scale != 1:
         wl = si.Workload(**{**wl.__dict__, "N": wl.N * args.batch_scale})
     dev = torch.device("cuda:0")
@@ -132,7 +131,10 @@ def main():
     base = wn.BASE_LEGENDRE if wl.base == "legendre" else wn.BASE_CANONICAL
     desc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
                        bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32)
-    sc = wn.Scales.from_dict(scales)
+    # set-up, outside the timed region: the library chooses the layer's scales itself
+    cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    sc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
+    del cws
     n2, T = desc.n ** 2, desc.tiles
     mdt = {8: torch.int8, 9: torch.int16, 32: torch.int32}[wl.bits_hadamard]
     V = torch.empty((n2, wl.K, wl.C), dtype=torch.int8, device=dev)

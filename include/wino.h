@@ -140,6 +140,23 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
 int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
                           const wino_scales_t* s, void* hip_stream);
 
+/* Chooses the per-tensor scales of a layer on the device, from the tensors it
+ * is given (dynamic quantisation; Section 4.2 casts every stage, the paper
+ * leaves the choice of scales to the training framework).  On entry s->s_x and
+ * s->s_w hold the scales of x and w; on return every other field holds
+ * scale = float(max |real value of that stage| / qmax), computed stage after
+ * stage on the codes the previous stages produce with the scales just chosen
+ * (qmax = 127, or 255 for a 9-bit Hadamard stage; 1.0 for an all-zero tensor;
+ * s_y covers only positive values when relu is set).  As a side effect the
+ * layer is run: V, U, M are left in the workspace and, if y is not null, the
+ * output is written.  This is the one call that synchronises the stream (once
+ * per cast) and it is meant to be used when a layer is set up, not per step.
+ * Needs wino_calibrate_workspace_bytes() of device workspace; int8 path only;
+ * C <= 1040 (the exact int32 contraction result must convert to fp32 exactly). */
+int wino_calibrate_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
+int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void* y,
+                   wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* Text of the last error on this thread ("" if none); valid until the next
  * failing call on the same thread. */
 const char* wino_last_error(void);

@@ -9,7 +9,8 @@ BASE_CANONICAL, BASE_LEGENDRE = 0, 1
 OUT_F32, OUT_I32, OUT_I8 = 0, 1, 2
 MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
 EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
-           "wino_workspace_bytes", "wino_conv2d", "wino_weight_transform",
+           "wino_workspace_bytes", "wino_calibrate_workspace_bytes", "wino_calibrate",
+           "wino_conv2d", "wino_weight_transform",
            "wino_input_transform", "wino_transform_operands", "wino_contract", "wino_output_transform", "wino_last_error")
 
 
@@ -84,6 +85,8 @@ def _load():
     dp, sp = C.POINTER(ConvDesc), C.POINTER(Scales)
     lib.wino_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
     lib.wino_conv2d.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
+    lib.wino_calibrate_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
+    lib.wino_calibrate.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_weight_transform.argtypes = [dp, vp, vp, sp, vp]
     lib.wino_input_transform.argtypes = [dp, vp, vp, sp, vp]
     lib.wino_transform_operands.argtypes = [dp, vp, vp, vp, vp, sp, vp]
@@ -156,6 +159,22 @@ def wino_workspace_bytes(desc):
     out = C.c_size_t()
     _check(_load().wino_workspace_bytes(C.byref(desc), C.byref(out)))
     return out.value
+
+
+def wino_calibrate_workspace_bytes(desc):
+    out = C.c_size_t()
+    _check(_load().wino_calibrate_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def wino_calibrate(desc, x, w, y, s_x, s_w, workspace, stream=None):
+    """Device-side choice of every scale of a layer; returns a Scales struct.
+    Runs the layer as a side effect (y may be None)."""
+    sc = Scales.from_dict({"s_x": s_x, "s_w": s_w})
+    _check(_load().wino_calibrate(C.byref(desc), _ptr(x), _ptr(w), _ptr(y), C.byref(sc),
+                                  _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  _stream(stream)))
+    return sc
 
 
 def wino_conv2d(desc, x, w_or_V, y, scales, workspace, stream=None):

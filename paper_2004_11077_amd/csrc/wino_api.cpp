@@ -401,6 +401,160 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
   return e == hipSuccess ? WINO_OK : fail_hip(e, "output transform launch");
 }
 
+namespace {
+
+// scale = float( max_ij( amax_ij * s_prev / (rho_i rho_j) ) / qmax ), 1 if everything is zero.
+float scale_from(const unsigned long long* amax, const IMat& im, double s_prev, double qmax) {
+  double best = 0.0;
+  for (int i = 0; i < im.rows; ++i)
+    for (int j = 0; j < im.rows; ++j) {
+      const double real = ((double)amax[i * im.rows + j] * s_prev) / (double)(im.rho[i] * im.rho[j]);
+      if (real > best) best = real;
+    }
+  return best > 0.0 ? (float)(best / qmax) : 1.0f;
+}
+
+struct CalCtx {
+  hipStream_t st;
+  unsigned long long* d_amax;
+  unsigned long long h_amax[kMaxPts];
+};
+
+int cal_reset(CalCtx& c) {
+  hipError_t e = hipMemsetAsync(c.d_amax, 0, sizeof c.h_amax, c.st);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "calibration memset");
+}
+
+int cal_read(CalCtx& c) {
+  hipError_t e = hipMemcpyAsync(c.h_amax, c.d_amax, sizeof c.h_amax, hipMemcpyDeviceToHost, c.st);
+  if (e == hipSuccess) e = hipStreamSynchronize(c.st);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "calibration read-back");
+}
+
+// One bracket: zero the maxima, run the calibration kernel, read them back.
+int cal_bracket(CalCtx& c, int stage, const Plan& p, int phase, const void* in, int m_bits,
+                const StageMults& mu, bool relu) {
+  if (int rc = cal_reset(c)) return rc;
+  hipError_t e = launch_calibrate_stage(stage, p.g, p.two_brackets, phase, in, m_bits, c.d_amax,
+                                        mu, relu, c.st);
+  if (e != hipSuccess) return fail_hip(e, "calibration launch");
+  return cal_read(c);
+}
+
+size_t calibrate_layout(const wino_conv_desc_t* d, const Plan& p, size_t* oV, size_t* oU,
+                        size_t* oM, size_t* oM32, size_t* oA) {
+  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  size_t o = 0;
+  *oV = o; o += round256(n2 * d->K * d->C);
+  *oU = o; o += round256(n2 * p.g.T * d->C);
+  *oM = o; o += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
+  *oM32 = o; o += round256(n2 * p.g.T * d->K * 4);
+  *oA = o; o += round256(sizeof(unsigned long long) * kMaxPts);
+  return o;
+}
+
+}  // namespace
+
+int wino_calibrate_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (!bytes) return fail(WINO_EINVAL, "null bytes");
+  if (p.fp32) return fail(WINO_EUNSUPPORTED, "the fp32 path has no scales to calibrate");
+  size_t a, b, c, e, f;
+  *bytes = calibrate_layout(d, p, &a, &b, &c, &e, &f);
+  return WINO_OK;
+}
+
+int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void* y,
+                   wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (p.fp32) return fail(WINO_EUNSUPPORTED, "the fp32 path has no scales to calibrate");
+  if (d->C > kMaxChannelsExact)
+    return fail(WINO_EOVERFLOW, "C = %d: calibration needs the exact int32 contraction result", d->C);
+  if (int rc = need(s, "scales")) return rc;
+  if (!good_scale(s->s_x) || !good_scale(s->s_w)) return fail(WINO_EINVAL, "s_x and s_w must be set");
+  if (int rc = need(workspace, "workspace")) return rc;
+  size_t oV, oU, oM, oM32, oA;
+  const size_t want = calibrate_layout(d, p, &oV, &oU, &oM, &oM32, &oA);
+  if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
+  if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  s->s_x1 = s->s_u = s->s_w1 = s->s_v = s->s_m = s->s_m1 = s->s_y = 1.0f;
+  if (p.g.T == 0 || p.g.K == 0 || p.g.C == 0) return WINO_OK;
+  if (int rc = need(x, "x")) return rc;
+  if (int rc = need(w, "w")) return rc;
+  char* ws = static_cast<char*>(workspace);
+  void *V = ws + oV, *U = ws + oU, *M = ws + oM, *M32 = ws + oM32;
+  CalCtx c{(hipStream_t)hip_stream, reinterpret_cast<unsigned long long*>(ws + oA), {}};
+  wino_conv_desc_t dd = *d;
+  dd.weights_pretransformed = 0;
+  dd.fused = 0;
+  StageMults mu;
+  std::memset(&mu, 0, sizeof mu);
+
+  // filters: s_w1 (Legendre inner bracket), s_v
+  if (p.two_brackets) {
+    if (int rc = cal_bracket(c, 0, p, 1, w, 8, mu, false)) return rc;
+    s->s_w1 = scale_from(c.h_amax, *p.st.GP, s->s_w, 127.0);
+    fill_mults(&mu.inner, *p.st.GP, s->s_w, s->s_w1);
+    if (int rc = cal_bracket(c, 0, p, 2, w, 8, mu, false)) return rc;
+    s->s_v = scale_from(c.h_amax, *p.st.Pinv, s->s_w1, 127.0);
+  } else {
+    if (int rc = cal_bracket(c, 0, p, 2, w, 8, mu, false)) return rc;
+    s->s_v = scale_from(c.h_amax, *p.st.G, s->s_w, 127.0);
+  }
+  if (int rc = wino_weight_transform(&dd, w, V, s, hip_stream)) return rc;
+
+  // activations: s_x1 (Legendre inner bracket), s_u
+  if (p.two_brackets) {
+    if (int rc = cal_bracket(c, 1, p, 1, x, 8, mu, false)) return rc;
+    s->s_x1 = scale_from(c.h_amax, *p.st.PinvT, s->s_x, 127.0);
+    fill_mults(&mu.inner, *p.st.PinvT, s->s_x, s->s_x1);
+    if (int rc = cal_bracket(c, 1, p, 2, x, 8, mu, false)) return rc;
+    s->s_u = scale_from(c.h_amax, *p.st.BPT, s->s_x1, 127.0);
+  } else {
+    if (int rc = cal_bracket(c, 1, p, 2, x, 8, mu, false)) return rc;
+    s->s_u = scale_from(c.h_amax, *p.st.BT, s->s_x, 127.0);
+  }
+  if (int rc = wino_input_transform(&dd, x, U, s, hip_stream)) return rc;
+
+  // contraction: s_m from the exact int32 result
+  const double s_uv = (double)s->s_u * (double)s->s_v;
+  double s_m_eff = s_uv;
+  if (p.m_bits == 32) {
+    if (int rc = wino_contract(&dd, U, V, M, s, hip_stream)) return rc;
+  } else {
+    wino_conv_desc_t d32 = dd;
+    d32.bits_hadamard = 32;
+    if (int rc = wino_contract(&d32, U, V, M32, s, hip_stream)) return rc;
+    if (int rc = cal_reset(c)) return rc;
+    const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+    hipError_t e = launch_absmax_i32((const int32_t*)M32, (long)(n2 * p.g.T * d->K), c.d_amax, c.st);
+    if (e != hipSuccess) return fail_hip(e, "absmax launch");
+    if (int rc = cal_read(c)) return rc;
+    const double real = (double)c.h_amax[0] * s_uv;
+    const double qm = p.m_bits == 8 ? 127.0 : 255.0;
+    s->s_m = real > 0.0 ? (float)(real / qm) : 1.0f;
+    s_m_eff = (double)s->s_m;
+    if (int rc = wino_contract(&dd, U, V, M, s, hip_stream)) return rc;
+  }
+
+  // output: s_m1 (Legendre inner bracket), s_y
+  if (p.two_brackets) {
+    if (int rc = cal_bracket(c, 2, p, 1, M, p.m_bits, mu, false)) return rc;
+    s->s_m1 = scale_from(c.h_amax, *p.st.PinvT, s_m_eff, 127.0);
+    fill_mults(&mu.inner, *p.st.PinvT, s_m_eff, s->s_m1);
+    if (int rc = cal_bracket(c, 2, p, 2, M, p.m_bits, mu, d->relu != 0)) return rc;
+    s->s_y = scale_from(c.h_amax, *p.st.APT, s->s_m1, 127.0);
+  } else {
+    if (int rc = cal_bracket(c, 2, p, 2, M, p.m_bits, mu, d->relu != 0)) return rc;
+    s->s_y = scale_from(c.h_amax, *p.st.AT, s_m_eff, 127.0);
+  }
+  if (y)
+    if (int rc = wino_output_transform(&dd, M, y, s, hip_stream)) return rc;
+  return WINO_OK;
+}
+
 int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, void* y,
                 const wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream) {
   Plan p;

@@ -195,6 +195,48 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   }
 }
 
+__global__ __launch_bounds__(256) void k_absmax_i32(const int32_t* __restrict__ v, long count,
+                                                    unsigned long long* __restrict__ amax) {
+  unsigned int m = 0;
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long)gridDim.x * 256) {
+    const int x = v[i];
+    const unsigned int a = x < 0 ? (unsigned int)(-(long)x) : (unsigned int)x;
+    m = a > m ? a : m;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    const unsigned int o = __shfl_xor(m, off);
+    m = o > m ? o : m;
+  }
+  if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(amax, (unsigned long long)m);
+}
+
+hipError_t launch_absmax_i32(const int32_t* v, long count, unsigned long long* amax,
+                             hipStream_t st) {
+  if (count == 0) return hipSuccess;
+  long nb = (count + 255) / 256;
+  if (nb > 4096) nb = 4096;
+  hipLaunchKernelGGL(k_absmax_i32, dim3((unsigned)nb), dim3(256), 0, st, v, count, amax);
+  return hipGetLastError();
+}
+
+hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool leg, int phase,
+                                  const void* in, int m_bits, unsigned long long* amax,
+                                  const StageMults& mu, bool relu, hipStream_t st) {
+#define WINO_CAL_M(MM)                                                                          \
+  case MM:                                                                                      \
+    return stage == 0   ? PerMCal<MM>::weight(g, leg, phase, (const int8_t*)in, amax, mu, st)   \
+           : stage == 1 ? PerMCal<MM>::input(g, leg, phase, (const int8_t*)in, amax, mu, st)    \
+                        : PerMCal<MM>::output(g, leg, phase, in, m_bits, amax, mu, relu, st);
+  switch (g.m) {
+    WINO_CAL_M(2)
+    WINO_CAL_M(4)
+    WINO_CAL_M(6)
+  }
+#undef WINO_CAL_M
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_weight_transform(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
                                    const StageMults& mu, hipStream_t st) {
   if ((long)g.K * g.C == 0) return hipSuccess;

@@ -46,6 +46,30 @@ extern template struct PerM<2>;
 extern template struct PerM<4>;
 extern template struct PerM<6>;
 
+// Calibration launchers (wino_calibrate.hpp): per-(i, j) maxima of the integer
+// numerators of one bracket, merged into amax[64] (device, zeroed by the caller).
+template <int M>
+struct PerMCal {
+  static hipError_t weight(const Geometry& g, bool legendre_inner, int phase, const int8_t* w,
+                           unsigned long long* amax, const StageMults& mu, hipStream_t st);
+  static hipError_t input(const Geometry& g, bool legendre_inner, int phase, const int8_t* x,
+                          unsigned long long* amax, const StageMults& mu, hipStream_t st);
+  static hipError_t output(const Geometry& g, bool legendre_inner, int phase, const void* M_,
+                           int m_bits, unsigned long long* amax, const StageMults& mu, bool relu,
+                           hipStream_t st);
+};
+extern template struct PerMCal<2>;
+extern template struct PerMCal<4>;
+extern template struct PerMCal<6>;
+
+// stage: 0 weight, 1 input, 2 output; phase 1 = inner bracket, 2 = outer bracket.
+hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool legendre_inner, int phase,
+                                  const void* in, int m_bits, unsigned long long* amax,
+                                  const StageMults& mu, bool relu, hipStream_t st);
+// amax[0] = max |v[i]| over an int32 array (device pointers).
+hipError_t launch_absmax_i32(const int32_t* v, long count, unsigned long long* amax,
+                             hipStream_t st);
+
 // legendre_inner == true selects the two-bracket Legendre pipeline; false the
 // single-bracket (canonical, or Legendre with brackets multiplied out).
 hipError_t launch_weight_transform(const Geometry& g, bool legendre_inner, const int8_t* w,
