@@ -27,9 +27,9 @@ namespace wino {
 constexpr int kFT = 16;          // tiles per work group
 constexpr int kFC = 64;          // input channels per chunk
 constexpr int kURow = kFC + 16;  // U_s row (one tile) in bytes, padded
-constexpr int kMRow = 64 + 4;    // M_s row (one tile) in bytes, padded
+constexpr int kMRow = kURow;     // M_s row (one tile) in bytes: M_s[p] overlays U_s[p] exactly
 
-template <int M, bool LEG, typename MT, int OUT>
+template <int M, bool LEG, typename MT, int OUT, bool SINGLE>
 __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
                                                const int8_t* __restrict__ V,
                                                void* __restrict__ yv, Geometry g, StageMults in_mu,
@@ -51,11 +51,35 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
   const int t0 = tb * kFT, k0 = kblk * KB;
   const int jl = lane & 15, seg = lane >> 4;         // MFMA operand row / 16-byte K segment
 
-  v4i acc[NPW][NKB];
+  // SINGLE (C <= 64, one channel chunk): a point's contraction is complete
+  // after its MFMAs, so it is cast at once and written over that point's own
+  // U_s rows (same wave, same bytes: program order suffices) and no
+  // accumulator outlives a point.  Otherwise the accumulators of all the
+  // wave's points live in registers across the channel loop.
+  v4i acc[SINGLE ? 1 : NPW][NKB];
+  if constexpr (!SINGLE) {
 #pragma unroll
-  for (int a = 0; a < NPW; ++a)
+    for (int a = 0; a < NPW; ++a)
 #pragma unroll
-    for (int b = 0; b < NKB; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+      for (int b = 0; b < NKB; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+  }
+  auto park = [&](const v4i (&av)[NKB], int p) {       // cast one point, store as M_s[p][tile][k]
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      int q[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)av[kb][v], m_mult, QM);
+      int8_t* dst = smem + (p * kFT + jl) * kMRow + (kb * 16 + 4 * seg) * (int)sizeof(MT);
+      if constexpr (sizeof(MT) == 1) {
+        *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
+                                            (((uint32_t)q[2] & 0xffu) << 16) |
+                                            (((uint32_t)q[3] & 0xffu) << 24);
+      } else {
+        reinterpret_cast<uint32_t*>(dst)[0] = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
+        reinterpret_cast<uint32_t*>(dst)[1] = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
+      }
+    }
+  };
 
   for (int c0 = 0; c0 < g.C; c0 += kFC) {
     if (c0) __syncthreads();                         // U_s of the previous chunk consumed
@@ -123,37 +147,27 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
     for (int pi = 0; pi < NPW; ++pi) {
       const int p = pi * 4 + wave;
       const v4i bu = *reinterpret_cast<const v4i*>(smem + (p * kFT + jl) * kURow + seg * 16);
+      v4i (&a4)[NKB] = acc[SINGLE ? 0 : pi];
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) {
         const int kr = min(k0 + kb * 16 + jl, g.K - 1);          // clamp, masked at the store
         v4i av = *reinterpret_cast<const v4i*>(V + ((long)p * g.K + kr) * g.C + ccol);
         if (!cok) av = v4i{0, 0, 0, 0};
-        acc[pi][kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, acc[pi][kb], 0, 0, 0);
+        if constexpr (SINGLE)
+          a4[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, v4i{0, 0, 0, 0}, 0, 0, 0);
+        else
+          a4[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, a4[kb], 0, 0, 0);
       }
+      if constexpr (SINGLE) park(a4, p);
     }
   }
 
   // ---- cast the contraction result and park it in LDS as M_s[p][tile][k] ----
-  __syncthreads();
   // acc[pi][kb][v] = D[k = 16 kb + 4 seg + v][tile = jl]
+  if constexpr (!SINGLE) {
+    __syncthreads();                                 // every wave is done reading U_s
 #pragma unroll
-  for (int pi = 0; pi < NPW; ++pi) {
-    const int p = pi * 4 + wave;
-#pragma unroll
-    for (int kb = 0; kb < NKB; ++kb) {
-      int q[4];
-#pragma unroll
-      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)acc[pi][kb][v], m_mult, QM);
-      int8_t* dst = smem + (p * kFT + jl) * kMRow + (kb * 16 + 4 * seg) * (int)sizeof(MT);
-      if constexpr (sizeof(MT) == 1) {
-        *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
-                                            (((uint32_t)q[2] & 0xffu) << 16) |
-                                            (((uint32_t)q[3] & 0xffu) << 24);
-      } else {
-        reinterpret_cast<uint32_t*>(dst)[0] = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
-        reinterpret_cast<uint32_t*>(dst)[1] = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
-      }
-    }
+    for (int pi = 0; pi < NPW; ++pi) park(acc[pi], pi * 4 + wave);
   }
   __syncthreads();
 
@@ -231,12 +245,19 @@ static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, 
   const int tblocks = (g.T + kFT - 1) / kFT, kblocks = (g.K + KB - 1) / KB;
   dim3 grid((unsigned)(tblocks * kblocks));
   const int r = relu ? 1 : 0;
-  if (out_type == 0)
-    hipLaunchKernelGGL((k_fused<M, LEG, MT, 0>), grid, dim3(256), 0, st, x, V, y, g, in_mu, out_mu,
-                       m_mult, r, tblocks);
+  const bool single = g.C <= kFC;
+  if (out_type == 0 && single)
+    hipLaunchKernelGGL((k_fused<M, LEG, MT, 0, true>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+                       out_mu, m_mult, r, tblocks);
+  else if (out_type == 0)
+    hipLaunchKernelGGL((k_fused<M, LEG, MT, 0, false>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+                       out_mu, m_mult, r, tblocks);
+  else if (single)
+    hipLaunchKernelGGL((k_fused<M, LEG, MT, 2, true>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+                       out_mu, m_mult, r, tblocks);
   else
-    hipLaunchKernelGGL((k_fused<M, LEG, MT, 2>), grid, dim3(256), 0, st, x, V, y, g, in_mu, out_mu,
-                       m_mult, r, tblocks);
+    hipLaunchKernelGGL((k_fused<M, LEG, MT, 2, false>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+                       out_mu, m_mult, r, tblocks);
   return hipGetLastError();
 }
 
