@@ -96,13 +96,6 @@ __device__ __forceinline__ int64_t mulc_wide(int64_t x) {
   return x * CF;
 }
 
-// Is column `a` the first non-zero coefficient of row `i`?
-constexpr bool first_nz(const IMat& t, int i, int a) {
-  for (int k = 0; k < a; ++k)
-    if (t.N[i][k] != 0) return false;
-  return true;
-}
-
 constexpr bool coef_fit_i32(const IMat& t) {
   for (int i = 0; i < t.rows; ++i)
     for (int j = 0; j < t.cols; ++j)
@@ -116,6 +109,72 @@ using tmp_t = std::conditional_t<((__int128)IN_MAX * T.rowsum < ((__int128)1 << 
                                      coef_fit_i32(T),
                                  int32_t, int64_t>;
 
+// Rows of a Toom-Cook matrix built on points +p / -p come in pairs that agree
+// on the even columns and differ by sign on the odd ones: row_j[a] =
+// (-1)^a row_i[a].  Such a pair is evaluated as e + o and e - o from one even
+// part and one odd part.  Returns the partner row of i, or -1.
+constexpr int partner_of(const IMat& t, int i) {
+  bool has_even = false, has_odd = false;
+  for (int a = 0; a < t.cols; ++a)
+    if (t.N[i][a] != 0) (a & 1 ? has_odd : has_even) = true;
+  if (!has_even || !has_odd) return -1;
+  for (int j = 0; j < t.rows; ++j) {
+    if (j == i || t.rho[j] != t.rho[i]) continue;
+    bool ok = true;
+    for (int a = 0; a < t.cols; ++a)
+      if (t.N[j][a] != ((a & 1) ? -t.N[i][a] : t.N[i][a])) ok = false;
+    if (ok) return j;
+  }
+  return -1;
+}
+
+// Is column a the first non-zero of row i among the columns of parity PAR
+// (0 even, 1 odd, 2 all)?
+constexpr bool first_nz_par(const IMat& t, int i, int a, int par) {
+  for (int k = 0; k < a; ++k)
+    if (t.N[i][k] != 0 && (par == 2 || (k & 1) == par)) return false;
+  return true;
+}
+
+// sum over the columns a of parity PAR of T.N[ROW][a] * get(a); S24: |get(a)| < 2^23.
+template <const IMat& T, int ROW, int PAR, bool S24, typename AccT, class Get>
+__device__ __forceinline__ AccT row_dot(Get&& get) {
+  AccT acc = 0;
+  static_for<0, T.cols>([&](auto a) {
+    constexpr int A = decltype(a)::value;
+    constexpr int64_t c = T.N[ROW][A];
+    if constexpr (c != 0 && (PAR == 2 || (A & 1) == PAR)) {
+      if constexpr (sizeof(AccT) == 4) {
+        if constexpr (first_nz_par(T, ROW, A, PAR))
+          acc = mulc<c, S24>((int32_t)get(a));
+        else
+          acc = madc<c, S24>((int32_t)get(a), acc);
+      } else {
+        acc += mulc_wide<c>(get(a));
+      }
+    }
+  });
+  return acc;
+}
+
+// out[i] = sum_a T.N[i][a] * get(a) for every row i, with paired rows sharing
+// their even and odd parts.  put(i, value) receives the results.
+template <const IMat& T, bool S24, typename AccT, class Get, class Put>
+__device__ __forceinline__ void apply_rows(Get&& get, Put&& put) {
+  static_for<0, T.rows>([&](auto i) {
+    constexpr int I = decltype(i)::value;
+    constexpr int PJ = partner_of(T, I);
+    if constexpr (PJ > I) {
+      const AccT e = row_dot<T, I, 0, S24, AccT>(get);
+      const AccT o = row_dot<T, I, 1, S24, AccT>(get);
+      put(i, e + o);
+      put(IC<PJ>{}, e - o);
+    } else if constexpr (PJ < 0) {
+      put(i, row_dot<T, I, 2, S24, AccT>(get));
+    }
+  });
+}
+
 // num = N x N^T with N the compile-time integer matrix T.N (T.rows x T.cols)
 // and |x| <= IN_MAX.  Zero coefficients generate no code.
 template <const IMat& T, int64_t IN_MAX, typename AccT, typename InT>
@@ -125,43 +184,13 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
   constexpr bool s2 = (__int128)IN_MAX * T.rowsum < (1 << 23);
   using TmpT = std::conditional_t<sizeof(AccT) == 4, int32_t, tmp_t<T, IN_MAX>>;
   TmpT tmp[T.rows][T.cols];
-  static_for<0, T.rows>([&](auto i) {
-    static_for<0, T.cols>([&](auto b) {
-      TmpT acc = 0;
-      static_for<0, T.cols>([&](auto a) {
-        constexpr int64_t c = T.N[decltype(i)::value][decltype(a)::value];
-        if constexpr (c != 0) {
-          if constexpr (sizeof(TmpT) == 4) {
-            if constexpr (first_nz(T, decltype(i)::value, decltype(a)::value))
-              acc = mulc<c, s1>((int32_t)x[a][b]);
-            else
-              acc = madc<c, s1>((int32_t)x[a][b], acc);
-          }
-          else
-            acc += mulc_wide<c>((int64_t)x[a][b]);
-        }
-      });
-      tmp[i][b] = acc;
-    });
+  static_for<0, T.cols>([&](auto b) {                      // tmp = N x, column by column
+    apply_rows<T, s1, TmpT>([&](auto a) { return x[a][b]; },
+                            [&](auto i, TmpT v) { tmp[i][b] = v; });
   });
-  static_for<0, T.rows>([&](auto i) {
-    static_for<0, T.rows>([&](auto j) {
-      AccT acc = 0;
-      static_for<0, T.cols>([&](auto b) {
-        constexpr int64_t c = T.N[decltype(j)::value][decltype(b)::value];
-        if constexpr (c != 0) {
-          if constexpr (sizeof(AccT) == 4) {
-            if constexpr (first_nz(T, decltype(j)::value, decltype(b)::value))
-              acc = mulc<c, s2>(tmp[i][b]);
-            else
-              acc = madc<c, s2>(tmp[i][b], acc);
-          }
-          else
-            acc += mulc_wide<c>(tmp[i][b]);
-        }
-      });
-      num[i][j] = acc;
-    });
+  static_for<0, T.rows>([&](auto i) {                      // num = tmp N^T, row by row
+    apply_rows<T, s2, AccT>([&](auto b) { return tmp[i][b]; },
+                            [&](auto j, AccT v) { num[i][j] = v; });
   });
 }
 
