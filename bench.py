@@ -8,6 +8,7 @@ transform of one 3x3 layer, inputs resident in HBM.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 """
 import argparse
+import ctypes
 import json
 import os
 import sys
@@ -75,6 +76,22 @@ def _stage_bytes(wl, m_bytes, y_bytes, n, T, C, K):
         "output_transform": {"bound": "hbm",
                              "work": T * K * (n * n * m_bytes + wl.m * wl.m * y_bytes)},
     }
+
+
+def hip_runtime():
+    """The HIP runtime already loaded into this process (by torch), for plain event calls."""
+    path = None
+    with open("/proc/self/maps") as f:
+        for line in f:
+            if "libamdhip64" in line:
+                path = line.split()[-1]
+                break
+    lib = ctypes.CDLL(path or "libamdhip64.so")
+    lib.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+    lib.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p,
+                                        ctypes.c_void_p]
+    lib.hipEventDestroy.argtypes = [ctypes.c_void_p]
+    return lib
 
 
 def cpu_baseline(wl):
@@ -146,18 +163,33 @@ def main():
     # the three launches wino_conv2d makes for a layer whose filters arrive untransformed
     names = ["operand_transforms", "contraction", "output_transform"]
 
+    # Per-kernel durations: every stage launch of every `stride`-th timed step carries a
+    # pair of HIP events that the library attaches to that very dispatch
+    # (wino_profile_next_launch -> hipExtLaunchKernel), so elapsed(start, stop) is the
+    # kernel's own begin-to-end time on its stream, the same interval rocprofv3 reports,
+    # free of the marker overhead an event recorded between launches would add.
+    hip = hip_runtime()
+
+    def new_event():
+        ev = ctypes.c_void_p()
+        assert hip.hipEventCreate(ctypes.byref(ev)) == 0
+        return ev
+
+    def elapsed_ms(a, b):
+        out = ctypes.c_float()
+        assert hip.hipEventElapsedTime(ctypes.byref(out), a, b) == 0
+        return out.value
+
     def step(events=None):
         if events is not None:
-            events[0].record(stream)
+            wn.wino_profile_next_launch(events[0][0].value, events[0][1].value)
         wn.wino_transform_operands(desc, x, U, w, V, sc, stream)    # a1 + a2, one launch
         if events is not None:
-            events[1].record(stream)
+            wn.wino_profile_next_launch(events[1][0].value, events[1][1].value)
         wn.wino_contract(desc, U, V, M, sc, stream)
         if events is not None:
-            events[2].record(stream)
+            wn.wino_profile_next_launch(events[2][0].value, events[2][1].value)
         wn.wino_output_transform(desc, M, y, sc, stream)
-        if events is not None:
-            events[3].record(stream)
 
     for _ in range(args.warmup):
         step()
@@ -168,32 +200,22 @@ def main():
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
-    # HIP events bracket every stage of every `stride`-th timed step (recording
-    # five events around four microsecond-scale kernels in every step would
-    # itself add a third to the step time).  Each event-to-event interval still
-    # carries the marker/dispatch overhead of the two events (about 3 us on
-    # this runtime, see profiles/): the stage durations below are therefore
-    # upper bounds and the roofline fractions lower bounds.  A fifth event
-    # directly after the fourth records what an empty interval costs; it is
-    # reported, not subtracted.
     stride = 8
     sampled = list(range(0, args.steps, stride))
-    evs = {i: [torch.cuda.Event(enable_timing=True) for _ in range(5)] for i in sampled}
+    evs = {i: [(new_event(), new_event()) for _ in names] for i in sampled}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        if i in evs:
-            step(evs[i])
-            evs[i][4].record(stream)
-        else:
-            step()
+        step(evs.get(i))
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
-    null_ms = float(np.median([evs[i][3].elapsed_time(evs[i][4]) for i in sampled]))
-    raw_ms = {nm: float(np.mean([evs[i][j].elapsed_time(evs[i][j + 1]) for i in sampled]))
-              for j, nm in enumerate(names)}
-    stage_ms = raw_ms
+    stage_ms = {nm: float(np.mean([elapsed_ms(*evs[i][j]) for i in sampled]))
+                for j, nm in enumerate(names)}
+    for i in sampled:
+        for a, b in evs[i]:
+            hip.hipEventDestroy(a)
+            hip.hipEventDestroy(b)
     pts = {2: [0, 1, -1], 4: [0, 1, -1, 2, -2], 6: [0, 1, -1, 2, -2, (1, 2), (-1, 2)]}[wl.m]
     from fractions import Fraction
     mats = wn.wino_make_matrices(wl.m, 3, [Fraction(*p) if isinstance(p, tuple) else p
@@ -230,7 +252,6 @@ def main():
     for k in ("hbm_GBps", "hbm_frac"):
         if k in stages[dominant]:
             roofline[k] = stages[dominant][k]
-    roofline["empty_event_interval_ms"] = null_ms
 
     ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
     ms_per_step = dt / args.steps * 1e3

@@ -157,6 +157,14 @@ int wino_calibrate_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void* y,
                    wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* Measurement hook.  The next kernel that the calling thread launches through
+ * this library records its own begin into `start_event` and its own end into
+ * `stop_event` (hipEvent_t handles created by the caller, either may be null);
+ * after the stream has been synchronised, hipEventElapsedTime(start, stop) is
+ * that dispatch's duration without any launch or marker overhead.  The pair is
+ * consumed by that one launch.  Always returns WINO_OK. */
+int wino_profile_next_launch(void* start_event, void* stop_event);
+
 /* Text of the last error on this thread ("" if none); valid until the next
  * failing call on the same thread. */
 const char* wino_last_error(void);

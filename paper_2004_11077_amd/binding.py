@@ -11,7 +11,8 @@ MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
 EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
            "wino_workspace_bytes", "wino_calibrate_workspace_bytes", "wino_calibrate",
            "wino_conv2d", "wino_weight_transform",
-           "wino_input_transform", "wino_transform_operands", "wino_contract", "wino_output_transform", "wino_last_error")
+           "wino_input_transform", "wino_transform_operands", "wino_contract",
+           "wino_output_transform", "wino_profile_next_launch", "wino_last_error")
 
 
 class WinoError(RuntimeError):
@@ -92,6 +93,7 @@ def _load():
     lib.wino_transform_operands.argtypes = [dp, vp, vp, vp, vp, sp, vp]
     lib.wino_contract.argtypes = [dp, vp, vp, vp, sp, vp]
     lib.wino_output_transform.argtypes = [dp, vp, vp, sp, vp]
+    lib.wino_profile_next_launch.argtypes = [vp, vp]
     _lib = lib
     return lib
 
@@ -153,6 +155,11 @@ def _stream(stream):
 
 def _scales(s):
     return s if isinstance(s, Scales) else Scales.from_dict(s)
+
+
+def wino_profile_next_launch(start_event, stop_event):
+    """Attach two raw hipEvent_t handles (ints) to the next kernel launch of this thread."""
+    _check(_load().wino_profile_next_launch(C.c_void_p(start_event), C.c_void_p(stop_event)))
 
 
 def wino_workspace_bytes(desc):

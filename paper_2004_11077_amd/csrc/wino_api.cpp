@@ -211,6 +211,11 @@ extern "C" {
 
 const char* wino_last_error(void) { return g_err.c_str(); }
 
+int wino_profile_next_launch(void* start_event, void* stop_event) {
+  set_profile_events((hipEvent_t)start_event, (hipEvent_t)stop_event);
+  return WINO_OK;
+}
+
 int wino_make_matrices(int m, int r, const wino_rat_t* points, int n_finite, int base,
                        wino_matrices_t** out) {
   if (!out) return fail(WINO_EINVAL, "null out");

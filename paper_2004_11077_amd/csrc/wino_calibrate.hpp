@@ -171,11 +171,11 @@ hipError_t PerMCal<M>::weight(const Geometry& g, bool leg, int phase, const int8
                               unsigned long long* amax, const StageMults& mu, hipStream_t st) {
   const unsigned nb = (unsigned)(((long)g.K * g.C + 255) / 256);
   if (!leg)
-    hipLaunchKernelGGL((k_cal_weight<M, false, 2>), dim3(nb), dim3(256), 0, st, w, amax, g, mu);
+    wino_launch((k_cal_weight<M, false, 2>), dim3(nb), dim3(256), st, w, amax, g, mu);
   else if (phase == 1)
-    hipLaunchKernelGGL((k_cal_weight<M, true, 1>), dim3(nb), dim3(256), 0, st, w, amax, g, mu);
+    wino_launch((k_cal_weight<M, true, 1>), dim3(nb), dim3(256), st, w, amax, g, mu);
   else
-    hipLaunchKernelGGL((k_cal_weight<M, true, 2>), dim3(nb), dim3(256), 0, st, w, amax, g, mu);
+    wino_launch((k_cal_weight<M, true, 2>), dim3(nb), dim3(256), st, w, amax, g, mu);
   return hipGetLastError();
 }
 
@@ -184,11 +184,11 @@ hipError_t PerMCal<M>::input(const Geometry& g, bool leg, int phase, const int8_
                              unsigned long long* amax, const StageMults& mu, hipStream_t st) {
   const unsigned nb = (unsigned)(((long)g.T * g.C + 255) / 256);
   if (!leg)
-    hipLaunchKernelGGL((k_cal_input<M, false, 2>), dim3(nb), dim3(256), 0, st, x, amax, g, mu);
+    wino_launch((k_cal_input<M, false, 2>), dim3(nb), dim3(256), st, x, amax, g, mu);
   else if (phase == 1)
-    hipLaunchKernelGGL((k_cal_input<M, true, 1>), dim3(nb), dim3(256), 0, st, x, amax, g, mu);
+    wino_launch((k_cal_input<M, true, 1>), dim3(nb), dim3(256), st, x, amax, g, mu);
   else
-    hipLaunchKernelGGL((k_cal_input<M, true, 2>), dim3(nb), dim3(256), 0, st, x, amax, g, mu);
+    wino_launch((k_cal_input<M, true, 2>), dim3(nb), dim3(256), st, x, amax, g, mu);
   return hipGetLastError();
 }
 
@@ -200,11 +200,11 @@ static hipError_t cal_output_mt(const Geometry& g, bool leg, int phase, const vo
   const MT* mp = static_cast<const MT*>(Mq);
   const int r = relu ? 1 : 0;
   if (!leg)
-    hipLaunchKernelGGL((k_cal_output<M, false, MT, 2>), dim3(nb), dim3(256), 0, st, mp, amax, g, mu, r);
+    wino_launch((k_cal_output<M, false, MT, 2>), dim3(nb), dim3(256), st, mp, amax, g, mu, r);
   else if (phase == 1)
-    hipLaunchKernelGGL((k_cal_output<M, true, MT, 1>), dim3(nb), dim3(256), 0, st, mp, amax, g, mu, r);
+    wino_launch((k_cal_output<M, true, MT, 1>), dim3(nb), dim3(256), st, mp, amax, g, mu, r);
   else
-    hipLaunchKernelGGL((k_cal_output<M, true, MT, 2>), dim3(nb), dim3(256), 0, st, mp, amax, g, mu, r);
+    wino_launch((k_cal_output<M, true, MT, 2>), dim3(nb), dim3(256), st, mp, amax, g, mu, r);
   return hipGetLastError();
 }
 

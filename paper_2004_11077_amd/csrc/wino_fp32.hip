@@ -195,27 +195,27 @@ static hipError_t stage_f32(int stage, const Geometry& g, bool leg, const float*
   switch (stage) {
     case 0:
       if (leg)
-        hipLaunchKernelGGL((k_weight_f32<M, true>), dim3(nblk((long)g.K * g.C)), dim3(256), 0, st, a, out, g);
+        wino_launch((k_weight_f32<M, true>), dim3(nblk((long)g.K * g.C)), dim3(256), st, a, out, g);
       else
-        hipLaunchKernelGGL((k_weight_f32<M, false>), dim3(nblk((long)g.K * g.C)), dim3(256), 0, st, a, out, g);
+        wino_launch((k_weight_f32<M, false>), dim3(nblk((long)g.K * g.C)), dim3(256), st, a, out, g);
       break;
     case 1:
       if (leg)
-        hipLaunchKernelGGL((k_input_f32<M, true>), dim3(nblk((long)g.T * g.C)), dim3(256), 0, st, a, out, g);
+        wino_launch((k_input_f32<M, true>), dim3(nblk((long)g.T * g.C)), dim3(256), st, a, out, g);
       else
-        hipLaunchKernelGGL((k_input_f32<M, false>), dim3(nblk((long)g.T * g.C)), dim3(256), 0, st, a, out, g);
+        wino_launch((k_input_f32<M, false>), dim3(nblk((long)g.T * g.C)), dim3(256), st, a, out, g);
       break;
     case 2: {
       const int tblocks = (g.T + 15) / 16, kblocks = (g.K + 15) / 16;
-      hipLaunchKernelGGL(k_contract_f32, dim3((unsigned)(tblocks * kblocks), (unsigned)((M + 2) * (M + 2))),
-                         dim3(256), 0, st, a, b, out, g.T, g.C, g.K, tblocks);
+      wino_launch(k_contract_f32, dim3((unsigned)(tblocks * kblocks), (unsigned)((M + 2) * (M + 2))),
+                         dim3(256), st, a, b, out, g.T, g.C, g.K, tblocks);
       break;
     }
     default:
       if (leg)
-        hipLaunchKernelGGL((k_output_f32<M, true>), dim3(nblk((long)g.T * g.K)), dim3(256), 0, st, a, out, g, relu ? 1 : 0);
+        wino_launch((k_output_f32<M, true>), dim3(nblk((long)g.T * g.K)), dim3(256), st, a, out, g, relu ? 1 : 0);
       else
-        hipLaunchKernelGGL((k_output_f32<M, false>), dim3(nblk((long)g.T * g.K)), dim3(256), 0, st, a, out, g, relu ? 1 : 0);
+        wino_launch((k_output_f32<M, false>), dim3(nblk((long)g.T * g.K)), dim3(256), st, a, out, g, relu ? 1 : 0);
   }
   return hipGetLastError();
 }

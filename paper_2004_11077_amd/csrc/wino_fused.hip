@@ -247,16 +247,16 @@ static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, 
   const int r = relu ? 1 : 0;
   const bool single = g.C <= kFC;
   if (out_type == 0 && single)
-    hipLaunchKernelGGL((k_fused<M, LEG, MT, 0, true>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 0, true>), grid, dim3(256), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   else if (out_type == 0)
-    hipLaunchKernelGGL((k_fused<M, LEG, MT, 0, false>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 0, false>), grid, dim3(256), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   else if (single)
-    hipLaunchKernelGGL((k_fused<M, LEG, MT, 2, true>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 2, true>), grid, dim3(256), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   else
-    hipLaunchKernelGGL((k_fused<M, LEG, MT, 2, false>), grid, dim3(256), 0, st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 2, false>), grid, dim3(256), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   return hipGetLastError();
 }

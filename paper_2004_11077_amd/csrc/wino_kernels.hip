@@ -6,6 +6,16 @@ namespace wino {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
+static thread_local ProfileEvents t_profile = {nullptr, nullptr};
+
+void set_profile_events(hipEvent_t start, hipEvent_t stop) { t_profile = ProfileEvents{start, stop}; }
+
+ProfileEvents take_profile_events() {
+  const ProfileEvents p = t_profile;
+  t_profile = ProfileEvents{nullptr, nullptr};
+  return p;
+}
+
 // One symmetric cast: q = clamp(rint(v * mult), +-qmax) with the exact product
 // rounded once, ties to even (fma onto 1.5 * 2^23, clamp of the biased float).
 __device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
@@ -215,8 +225,8 @@ hipError_t launch_absmax_i32(const int32_t* v, long count, unsigned long long* a
                              hipStream_t st) {
   if (count == 0) return hipSuccess;
   long nb = (count + 255) / 256;
-  if (nb > 4096) nb = 4096;
-  hipLaunchKernelGGL(k_absmax_i32, dim3((unsigned)nb), dim3(256), 0, st, v, count, amax);
+  if (nb > 256) nb = 256;     // one atomic per wave: keep the single target uncontended
+  wino_launch(k_absmax_i32, dim3((unsigned)nb), dim3(256), st, v, count, amax);
   return hipGetLastError();
 }
 
@@ -285,13 +295,13 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   dim3 grid((unsigned)nblocks);
   if (m_bits == 8)
-    hipLaunchKernelGGL((k_contract<int8_t, 128>), grid, dim3(256), 0, st, U, V, (int8_t*)Mo, g.T, g.C,
+    wino_launch((k_contract<int8_t, 128>), grid, dim3(256), st, U, V, (int8_t*)Mo, g.T, g.C,
                        g.K, tblocks, kblocks, tgroups, tpg, units, mult, 127.f);
   else if (m_bits == 9)
-    hipLaunchKernelGGL((k_contract<int16_t, 128>), grid, dim3(256), 0, st, U, V, (int16_t*)Mo, g.T,
+    wino_launch((k_contract<int16_t, 128>), grid, dim3(256), st, U, V, (int16_t*)Mo, g.T,
                        g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 255.f);
   else
-    hipLaunchKernelGGL((k_contract<int32_t, 128>), grid, dim3(256), 0, st, U, V, (int32_t*)Mo, g.T,
+    wino_launch((k_contract<int32_t, 128>), grid, dim3(256), st, U, V, (int32_t*)Mo, g.T,
                        g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 0.f);
   return hipGetLastError();
 }

@@ -2,10 +2,30 @@
 // kernels (wino_kernels.hip).  Not part of the public boundary.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 
 namespace wino {
+
+// Optional per-launch timing: a pair of HIP events handed over with
+// set_profile_events() is attached to the NEXT kernel this thread launches
+// through wino_launch (the events then carry that dispatch's own begin and
+// end timestamps); the pair is consumed by that launch.
+struct ProfileEvents {
+  hipEvent_t start, stop;
+};
+void set_profile_events(hipEvent_t start, hipEvent_t stop);
+ProfileEvents take_profile_events();
+
+template <class K, class... Args>
+inline void wino_launch(K kernel, dim3 grid, dim3 block, hipStream_t st, Args... args) {
+  const ProfileEvents p = take_profile_events();
+  if (p.start || p.stop)
+    hipExtLaunchKernelGGL(kernel, grid, block, 0, st, p.start, p.stop, 0, args...);
+  else
+    hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+}
 
 constexpr int kMaxPts = 64;   // n*n for n = 8
 

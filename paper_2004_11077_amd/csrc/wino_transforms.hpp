@@ -503,9 +503,9 @@ hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t*
                            const StageMults& mu, hipStream_t st) {
   const unsigned nb = blocks_for((long)g.K * g.C);
   if (leg)
-    hipLaunchKernelGGL((k_weight_transform<M, true>), dim3(nb), dim3(256), 0, st, w, V, g, mu);
+    wino_launch((k_weight_transform<M, true>), dim3(nb), dim3(256), st, w, V, g, mu);
   else
-    hipLaunchKernelGGL((k_weight_transform<M, false>), dim3(nb), dim3(256), 0, st, w, V, g, mu);
+    wino_launch((k_weight_transform<M, false>), dim3(nb), dim3(256), st, w, V, g, mu);
   return hipGetLastError();
 }
 
@@ -514,9 +514,9 @@ hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* 
                           const StageMults& mu, hipStream_t st) {
   const unsigned nb = blocks_for((long)g.T * g.C);
   if (leg)
-    hipLaunchKernelGGL((k_input_transform<M, true>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
+    wino_launch((k_input_transform<M, true>), dim3(nb), dim3(256), st, x, U, g, mu);
   else
-    hipLaunchKernelGGL((k_input_transform<M, false>), dim3(nb), dim3(256), 0, st, x, U, g, mu);
+    wino_launch((k_input_transform<M, false>), dim3(nb), dim3(256), st, x, U, g, mu);
   return hipGetLastError();
 }
 
@@ -526,10 +526,10 @@ hipError_t PerM<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_
                              const StageMults& mu_w, hipStream_t st) {
   const unsigned nb_in = blocks_for((long)g.T * g.C), nb_w = blocks_for((long)g.K * g.C);
   if (leg)
-    hipLaunchKernelGGL((k_operand_transforms<M, true>), dim3(nb_in + nb_w), dim3(256), 0, st, x, U,
+    wino_launch((k_operand_transforms<M, true>), dim3(nb_in + nb_w), dim3(256), st, x, U,
                        w, V, g, mu_in, mu_w, nb_in);
   else
-    hipLaunchKernelGGL((k_operand_transforms<M, false>), dim3(nb_in + nb_w), dim3(256), 0, st, x,
+    wino_launch((k_operand_transforms<M, false>), dim3(nb_in + nb_w), dim3(256), st, x,
                        U, w, V, g, mu_in, mu_w, nb_in);
   return hipGetLastError();
 }
@@ -541,17 +541,17 @@ static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_
   const MT* mp = static_cast<const MT*>(Mq);
   const int r = relu ? 1 : 0;
   if (out_type == 0) {
-    hipLaunchKernelGGL((k_output_transform<M, LEG, MT, 0>), dim3(nb), dim3(256), 0, st, mp, y, g,
+    wino_launch((k_output_transform<M, LEG, MT, 0>), dim3(nb), dim3(256), st, mp, y, g,
                        mu, r);
   } else if (out_type == 1) {
     // integer numerators only make sense for a single integer bracket
     if constexpr (LEG)
       return hipErrorInvalidValue;
     else
-      hipLaunchKernelGGL((k_output_transform<M, LEG, MT, 1>), dim3(nb), dim3(256), 0, st, mp, y,
+      wino_launch((k_output_transform<M, LEG, MT, 1>), dim3(nb), dim3(256), st, mp, y,
                          g, mu, r);
   } else {
-    hipLaunchKernelGGL((k_output_transform<M, LEG, MT, 2>), dim3(nb), dim3(256), 0, st, mp, y, g,
+    wino_launch((k_output_transform<M, LEG, MT, 2>), dim3(nb), dim3(256), st, mp, y, g,
                        mu, r);
   }
   return hipGetLastError();
