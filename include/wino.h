@@ -42,6 +42,7 @@ enum {
 
 enum { WINO_BASE_CANONICAL = 0, WINO_BASE_LEGENDRE = 1 };
 enum { WINO_OUT_F32 = 0, WINO_OUT_I32 = 1, WINO_OUT_I8 = 2 };
+enum { WINO_FUSED_OFF = 0, WINO_FUSED_ON = 1, WINO_FUSED_AUTO = 2 };
 enum {
   WINO_MAT_G = 0,     /* n x r  Section 3: filter transform                    */
   WINO_MAT_BT = 1,    /* n x n  Section 3: input transform                     */
@@ -95,7 +96,11 @@ typedef struct {
                                  base, m = 2 or 4)                                */
   int relu;                   /* clamp the output at zero                         */
   int weights_pretransformed; /* wino_conv2d: second pointer is V, not w          */
-  int fused;                  /* wino_conv2d: single-kernel variant               */
+  int fused;                  /* wino_conv2d: WINO_FUSED_*: OFF = one kernel per
+                                 stage; ON = single-kernel variant (U, M stay on
+                                 chip; m = 2 or 4, bits_hadamard 8 or 9, fp32 or
+                                 int8 output); AUTO = ON where it is the faster
+                                 one (C <= 64 and K <= 64), else OFF               */
 } wino_conv_desc_t;
 
 /* Per-tensor symmetric scales, supplied by the caller.  s_x1, s_w1, s_m1 are

@@ -7,6 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 
 BASE_CANONICAL, BASE_LEGENDRE = 0, 1
 OUT_F32, OUT_I32, OUT_I8 = 0, 1, 2
+FUSED_OFF, FUSED_ON, FUSED_AUTO = 0, 1, 2
 MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
 EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
            "wino_workspace_bytes", "wino_calibrate_workspace_bytes", "wino_calibrate",

@@ -283,7 +283,7 @@ int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   const size_t eb = p.fp32 ? 4 : 1;
   size_t total = 0;
   if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C * eb);
-  if (!d->fused) {   // the fused variant keeps U and M on chip
+  if (d->fused != WINO_FUSED_ON) {   // the fused variant keeps U and M on chip (AUTO may pick either)
     total += round256(n2 * p.g.T * d->C * eb);
     total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
   }
@@ -565,13 +565,20 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
   if (p.g.T == 0 || p.g.K == 0) return WINO_OK;   // no output element exists
-  if (d->fused) {
-    if (p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32)
-      return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "
-                                     "bits_hadamard 8 or 9 and fp32 or int8 output");
-  }
-  size_t want = 0;
-  if (int rc = wino_workspace_bytes(d, &want)) return rc;
+  const bool fusable = !(p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32);
+  if (d->fused == WINO_FUSED_ON && !fusable)
+    return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "
+                                   "bits_hadamard 8 or 9 and fp32 or int8 output");
+  if (d->fused != WINO_FUSED_OFF && d->fused != WINO_FUSED_ON && d->fused != WINO_FUSED_AUTO)
+    return fail(WINO_EINVAL, "unknown fused mode %d", d->fused);
+  // AUTO: the fused kernel recomputes the input transform once per 64 output
+  // channels and keeps no accumulators when C <= 64; it wins exactly there.
+  wino_conv_desc_t dsel = *d;
+  dsel.fused = d->fused == WINO_FUSED_ON || (d->fused == WINO_FUSED_AUTO && fusable &&
+                                             d->C <= 64 && d->K <= 64);
+  const size_t ws_want_caller = [&] { size_t b = 0; wino_workspace_bytes(d, &b); return b; }();
+  d = &dsel;
+  const size_t want = ws_want_caller;   // what wino_workspace_bytes told the caller
   if (int rc = need(workspace, "workspace")) return rc;
   if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
   if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");

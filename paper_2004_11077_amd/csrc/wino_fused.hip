@@ -3,14 +3,14 @@
 // (U chunks and the cast M block live in LDS, the int32 accumulators of all
 // n*n points in registers).  Only x, V and y touch HBM.
 //
-// Work group = 4 waves, 16 tiles x KB output channels (KB = 64 for an int8 M,
+// Work group = 4 waves (8 in the single-chunk mode), 16 tiles x KB output channels (KB = 64 for an int8 M,
 // 32 for the 9-bit int16 M), all n*n Winograd points.  Loop over the input
 // channels in chunks of 64:
 //   A  four tiles at a time: their pixels are staged in LDS with 16-byte loads,
 //      every lane transforms one (tile, channel) item exactly as the split
 //      input-transform kernel does and drops the n*n codes into LDS as
 //      U_s[point][tile][channel];
-//   B  wave w takes points w, w+4, ...: for each, one 16x16x64 int8 MFMA per
+//   B  wave w takes points w, w+NW, ...: for each, one 16x16x64 int8 MFMA per
 //      16 output channels, A operand = V rows (k) straight from global / L2,
 //      B operand = the 16 tiles of U_s; accumulators stay in registers.
 // Then the accumulators are cast to bits_hadamard, written to LDS as
@@ -26,11 +26,19 @@ namespace wino {
 
 constexpr int kFT = 16;          // tiles per work group
 constexpr int kFC = 64;          // input channels per chunk
-constexpr int kURow = kFC + 16;  // U_s row (one tile) in bytes, padded
-constexpr int kMRow = kURow;     // M_s row (one tile) in bytes: M_s[p] overlays U_s[p] exactly
+constexpr int kPt = kFT * kFC;   // bytes of one point's block in LDS: 16 tiles x 64 bytes
+
+// Byte offset of (tile, byte) inside a point's 1 KB block.  Rows are 64 bytes
+// with no padding; the 16-byte segment index is XOR-ed with bits 1-2 of the
+// tile so that the eight 16-byte MFMA-operand reads of a pass (8 consecutive
+// tiles, same segment) fall on eight distinct bank groups.  U_s[p] and M_s[p]
+// use the same map, so M_s[p] overlays U_s[p] exactly.
+__device__ __forceinline__ int sw(int tile, int byte) {
+  return tile * kFC + ((((byte >> 4) ^ ((tile >> 1) & 3)) << 4) | (byte & 15));
+}
 
 template <int M, bool LEG, typename MT, int OUT, bool SINGLE>
-__global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
+__global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* __restrict__ x,
                                                const int8_t* __restrict__ V,
                                                void* __restrict__ yv, Geometry g, StageMults in_mu,
                                                StageMults out_mu, float m_mult, int relu,
@@ -38,13 +46,14 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
   constexpr int n = M + 2, n2 = n * n;
   constexpr int KB = sizeof(MT) == 1 ? 64 : 32;      // output channels per work group
   constexpr int NKB = KB / 16;                       // 16-wide MFMA column blocks
-  constexpr int NPW = n2 / 4;                        // points per wave
+  constexpr int NT = SINGLE ? 512 : 256;             // lanes per work group
+  constexpr int NWV = NT / 64;                       // waves: one tile each per pass of phase A
+  constexpr int NPW = (n2 + NWV - 1) / NWV;          // points per wave (the last may be empty)
   static_assert(n2 % 4 == 0);
   constexpr float QM = sizeof(MT) == 1 ? 127.f : 255.f;
   using TB = Tab<M>;
-  static_assert(n2 * kFT * kMRow <= n2 * kFT * kURow);
-  __shared__ __attribute__((aligned(16))) int8_t smem[n2 * kFT * kURow];
-  __shared__ __attribute__((aligned(16))) int8_t s_x[4 * n2 * kFC];   // input pixels of one pass
+  __shared__ __attribute__((aligned(16))) int8_t smem[n2 * kPt];
+  __shared__ __attribute__((aligned(16))) int8_t s_x[NWV * n2 * kFC];   // input pixels of one pass
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int tb = blockIdx.x % tblocks, kblk = blockIdx.x / tblocks;
@@ -69,7 +78,7 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
       int q[4];
 #pragma unroll
       for (int v = 0; v < 4; ++v) q[v] = cast_code((float)av[kb][v], m_mult, QM);
-      int8_t* dst = smem + (p * kFT + jl) * kMRow + (kb * 16 + 4 * seg) * (int)sizeof(MT);
+      int8_t* dst = smem + p * kPt + sw(jl, (kb * 16 + 4 * seg) * (int)sizeof(MT));
       if constexpr (sizeof(MT) == 1) {
         *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
                                             (((uint32_t)q[2] & 0xffu) << 16) |
@@ -83,19 +92,19 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
 
   for (int c0 = 0; c0 < g.C; c0 += kFC) {
     if (c0) __syncthreads();                         // U_s of the previous chunk consumed
-    // ---- A: input transform of 16 tiles x 64 channels, 4 tiles per pass ----
+    // ---- A: input transform of 16 tiles x 64 channels, one tile per wave and pass ----
 #pragma unroll 1
-    for (int it = 0; it < kFT / 4; ++it) {
-      // stage the n*n pixels x 64 channels of the pass's 4 tiles with 16-byte
+    for (int it = 0; it < kFT / NWV; ++it) {
+      // stage the n*n pixels x 64 channels of the pass's NWV tiles with 16-byte
       // loads (zeros outside the image, past the last tile or channel)
       if (it) __syncthreads();                       // s_x of the previous pass consumed
 #pragma unroll
-      for (int j = 0; j < (4 * n2 * 4 + 255) / 256; ++j) {
-        const int idx = j * 256 + tid;
-        if (idx < 4 * n2 * 4) {
+      for (int j = 0; j < (NWV * n2 * 4 + NT - 1) / NT; ++j) {
+        const int idx = j * NT + tid;
+        if (idx < NWV * n2 * 4) {
           const int tq = idx / (n2 * 4), rem = idx - tq * (n2 * 4);
           const int pix = rem >> 2, sg = rem & 3;
-          const int t = t0 + it * 4 + tq, c = c0 + sg * 16;
+          const int t = t0 + it * NWV + tq, c = c0 + sg * 16;
           v4i v = {0, 0, 0, 0};
           if (t < g.T && c < g.C) {
             const int tx = t % g.TW;
@@ -110,7 +119,7 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
         }
       }
       __syncthreads();
-      const int tl = it * 4 + wave;                  // a wave = one tile, 64 channels
+      const int tl = it * NWV + wave;                // a wave = one tile, 64 channels
       int xi[n][n];
       static_for<0, n>([&](auto a) {
         static_for<0, n>([&](auto bb) {
@@ -134,8 +143,7 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
       static_for<0, n>([&](auto i) {
         static_for<0, n>([&](auto j) {
           // a dead item (tile or channel out of range) has all-zero input, hence zero codes
-          smem[((decltype(i)::value * n + decltype(j)::value) * kFT + tl) * kURow + lane] =
-              (int8_t)q[i][j];
+          smem[(decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, lane)] = (int8_t)q[i][j];
         });
       });
     }
@@ -143,10 +151,11 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
     // ---- B: contraction of this chunk for the wave's points ----
     const bool cok = c0 + seg * 16 < g.C;
     const int ccol = cok ? c0 + seg * 16 : 0;
-#pragma unroll
+#pragma unroll(SINGLE ? 3 : NPW)
     for (int pi = 0; pi < NPW; ++pi) {
-      const int p = pi * 4 + wave;
-      const v4i bu = *reinterpret_cast<const v4i*>(smem + (p * kFT + jl) * kURow + seg * 16);
+      const int p = pi * NWV + wave;
+      if (n2 % NWV != 0 && p >= n2) break;           // wave-uniform: this wave has one point less
+      const v4i bu = *reinterpret_cast<const v4i*>(smem + p * kPt + sw(jl, seg * 16));
       v4i (&a4)[NKB] = acc[SINGLE ? 0 : pi];
 #pragma unroll
       for (int kb = 0; kb < NKB; ++kb) {
@@ -167,16 +176,14 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
   if constexpr (!SINGLE) {
     __syncthreads();                                 // every wave is done reading U_s
 #pragma unroll
-    for (int pi = 0; pi < NPW; ++pi) park(acc[pi], pi * 4 + wave);
+    for (int pi = 0; pi < NPW; ++pi) park(acc[pi], pi * NWV + wave);
   }
   __syncthreads();
 
   // ---- output transform of 16 tiles x KB channels ----
-  const MT* ms = reinterpret_cast<const MT*>(smem);
-  constexpr int MROW = kMRow / (int)sizeof(MT);      // M_s row in elements
 #pragma unroll 1
-  for (int it = 0; it < kFT * KB / 256; ++it) {
-    const int item = it * 256 + tid;
+  for (int it = 0; it < kFT * KB / NT; ++it) {
+    const int item = it * NT + tid;
     const int tl = item / KB, kl = item - tl * KB;
     const int t = t0 + tl, k = k0 + kl;
     if (t >= g.T || k >= g.K) continue;
@@ -186,7 +193,8 @@ __global__ __launch_bounds__(256, 2) void k_fused(const int8_t* __restrict__ x,
     int mi[n][n];
     static_for<0, n>([&](auto i) {
       static_for<0, n>([&](auto j) {
-        mi[i][j] = (int)ms[((decltype(i)::value * n + decltype(j)::value) * kFT + tl) * MROW + kl];
+        mi[i][j] = (int)*reinterpret_cast<const MT*>(
+            smem + (decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, kl * (int)sizeof(MT)));
       });
     });
     const long ybase = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K + k;
@@ -247,13 +255,13 @@ static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, 
   const int r = relu ? 1 : 0;
   const bool single = g.C <= kFC;
   if (out_type == 0 && single)
-    wino_launch((k_fused<M, LEG, MT, 0, true>), grid, dim3(256), st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 0, true>), grid, dim3(512), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   else if (out_type == 0)
     wino_launch((k_fused<M, LEG, MT, 0, false>), grid, dim3(256), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   else if (single)
-    wino_launch((k_fused<M, LEG, MT, 2, true>), grid, dim3(256), st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 2, true>), grid, dim3(512), st, x, V, y, g, in_mu,
                        out_mu, m_mult, r, tblocks);
   else
     wino_launch((k_fused<M, LEG, MT, 2, false>), grid, dim3(256), st, x, V, y, g, in_mu,

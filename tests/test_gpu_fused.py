@@ -60,3 +60,25 @@ def test_fused_rejects_what_it_does_not_cover():
             buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
             wn.wino_conv2d(d, buf, buf, buf, wn.Scales.from_dict({}), buf)
         assert e.value.code == -2
+
+
+def test_auto_mode_picks_a_variant_and_matches_the_split_path():
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    for (C, K) in [(64, 64), (128, 64)]:           # fused is chosen for the first, split for the second
+        xq, wq, s_x, s_w = small_layer(4, 8, 8, C, K, seed=95)
+        ora, sc = oracle_layer(xq, wq, s_x, s_w, m=4, base="legendre", out_type="i8")
+        desc = wn.ConvDesc(4, 8, 8, C, K, m=4, out_type=wn.OUT_I8, fused=wn.FUSED_AUTO)
+        x = torch.from_numpy(xq).to(dev)
+        w = torch.from_numpy(wq).to(dev)
+        y = torch.full((4, 8, 8, K), 77, dtype=torch.int8, device=dev)
+        ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        wn.wino_conv2d(desc, x, w, y, wn.Scales.from_dict(sc), ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy().astype(np.int64), ora["y"])
+    with pytest.raises(wn.WinoError):
+        wn.wino_workspace_bytes(wn.ConvDesc(1, 8, 8, 16, 16, fused=7)) and None
+        d = wn.ConvDesc(1, 8, 8, 16, 16, fused=7)
+        buf = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+        wn.wino_conv2d(d, buf, buf, buf, wn.Scales.from_dict({}), buf)
