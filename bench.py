@@ -94,6 +94,38 @@ def hip_runtime():
     return lib
 
 
+def layer_times(wn, si, torch, dev, name, steps):
+    """Step time of one whole layer (filters untransformed) through wino_conv2d."""
+    wl = si.WORKLOADS[name]
+    L = si.make_layer(wl)
+    x = torch.from_numpy(L["xq"]).to(dev)
+    w = torch.from_numpy(L["wq"]).to(dev)
+    y = torch.empty((wl.N, wl.H, wl.W, wl.K), dtype=torch.float32, device=dev)
+    base = wn.BASE_LEGENDRE if wl.base == "legendre" else wn.BASE_CANONICAL
+    ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
+    res = {}
+    sc = None
+    for label, mode in (("split", wn.FUSED_OFF), ("auto", wn.FUSED_AUTO)):
+        desc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                           bits_hadamard=wl.bits_hadamard, fused=mode)
+        if sc is None:
+            cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8,
+                              device=dev)
+            sc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
+            del cws
+        ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        for _ in range(10):
+            wn.wino_conv2d(desc, x, w, y, sc, ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            wn.wino_conv2d(desc, x, w, y, sc, ws)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps
+        res[label] = {"ms_per_step": dt * 1e3, "TOPS_direct_equiv": ops / dt / 1e12}
+    return res
+
+
 def cpu_baseline(wl):
     """The oracle, as it stands, timed once on the host cores on the full workload."""
     import synth_inputs as si
@@ -120,6 +152,8 @@ def main():
     ap.add_argument("--batch-scale", type=int, default=1,
                     help="multiply the batch size N (extra, labelled in config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the extra timings of the other layer configurations")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 64 MiB device copy after warm-up: the known-size "
                          "kernel against which rocprofv3 --pmc byte counters are scaled")
@@ -288,6 +322,14 @@ def main():
         out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
                                 "unit": "TOPS",
                                 "note": "input transform recomputed per 64-channel k block"}
+    # extra: whole-layer call (wino_conv2d) on the other single-layer configurations, split
+    # path and AUTO (which takes the fused kernel where C, K <= 64); not the headline figure
+    if not args.no_extras and reps == 1:
+        out["other_workloads"] = {}
+        for name in ("cfg2_f4_c64", "cfg3_f4_c128_h9", "cfg4b_f4_c512"):
+            if name == wl.name:
+                continue
+            out["other_workloads"][name] = layer_times(wn, si, torch, dev, name, 50)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si.WORKLOADS[args.workload])
     print(json.dumps(out))
