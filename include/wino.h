@@ -40,7 +40,12 @@ enum {
   WINO_EHIP = -5          /* HIP runtime error, text in wino_last_error()       */
 };
 
-enum { WINO_BASE_CANONICAL = 0, WINO_BASE_LEGENDRE = 1 };
+enum {
+  WINO_BASE_CANONICAL = 0,
+  WINO_BASE_LEGENDRE = 1,
+  WINO_BASE_CHEBYSHEV = 2, /* wino_make_matrices only */
+  WINO_BASE_HERMITE = 3    /* wino_make_matrices only */
+};
 enum { WINO_OUT_F32 = 0, WINO_OUT_I32 = 1, WINO_OUT_I8 = 2 };
 enum { WINO_FUSED_OFF = 0, WINO_FUSED_ON = 1, WINO_FUSED_AUTO = 2 };
 enum {
@@ -62,7 +67,10 @@ typedef struct wino_matrices wino_matrices_t;      /* opaque, host memory */
  * points (host array; the point at infinity is implicit and last), plus the
  * base-change factors P^T, P^{-T} and G_P = P G, B_P = P B, A_P = P A.
  * base = WINO_BASE_LEGENDRE: P^T rows are the monic Legendre polynomials;
- * base = WINO_BASE_CANONICAL: P = I.  m+r-1 <= 8.
+ * WINO_BASE_CHEBYSHEV / WINO_BASE_HERMITE: the monic Chebyshev (first kind) /
+ * Hermite (probabilists') polynomials, the alternatives Section 4.1 names;
+ * base = WINO_BASE_CANONICAL: P = I.  m+r-1 <= 8.  (The convolution kernels
+ * are built for the canonical and the Legendre base.)
  * On success *out owns a host handle to be released with wino_free_matrices.
  * Errors: EINVAL (null, sizes, zero denominator, duplicate point),
  * EUNSUPPORTED (m+r-1 > 8), EOVERFLOW (an int64 rational overflowed). */

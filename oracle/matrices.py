@@ -148,6 +148,56 @@ def legendre_PT(n):
     return PT
 
 
+def chebyshev_PT(n):
+    """Row i = ascending coefficients of the monic Chebyshev polynomial of the
+    first kind: t_0 = 1, t_1 = x, t_2 = x^2 - 1/2, t_{k+1} = x t_k - t_{k-1} / 4
+    (the classical T_k divided by its leading coefficient 2^{k-1})."""
+    rows = []
+    for i in range(n):
+        if i == 0:
+            poly = [Fraction(1)]
+        elif i == 1:
+            poly = [Fraction(0), Fraction(1)]
+        else:
+            coef = Fraction(1, 2) if i == 2 else Fraction(1, 4)
+            poly = [Fraction(0)] + rows[i - 1]
+            for d, c in enumerate(rows[i - 2]):
+                poly[d] -= coef * c
+        rows.append(poly)
+    PT = _zeros(n, n)
+    for i, poly in enumerate(rows):
+        for d, c in enumerate(poly):
+            PT[i][d] = c
+    return PT
+
+
+def hermite_PT(n):
+    """Row i = ascending coefficients of the monic (probabilists') Hermite
+    polynomial: he_0 = 1, he_1 = x, he_{k+1} = x he_k - k he_{k-1}."""
+    rows = []
+    for i in range(n):
+        if i == 0:
+            poly = [Fraction(1)]
+        elif i == 1:
+            poly = [Fraction(0), Fraction(1)]
+        else:
+            k = i - 1
+            poly = [Fraction(0)] + rows[i - 1]
+            for d, c in enumerate(rows[i - 2]):
+                poly[d] -= k * c
+        rows.append(poly)
+    PT = _zeros(n, n)
+    for i, poly in enumerate(rows):
+        for d, c in enumerate(poly):
+            PT[i][d] = c
+    return PT
+
+
+def base_PT(n, base):
+    return {"canonical": identity, "legendre": legendre_PT, "chebyshev": chebyshev_PT,
+            "hermite": hermite_PT}[base](n)
+
+
 def inverse(A):
     """Gauss-Jordan inverse in exact rationals."""
     n = len(A)
@@ -173,13 +223,13 @@ def inverse(A):
 class Matrices:
     """All stage matrices of one F(m, r) instance, as lists of Fractions."""
 
-    def __init__(self, m, r, points=None):
+    def __init__(self, m, r, points=None, base="legendre"):
         self.m, self.r, self.n = m, r, m + r - 1
         pts = POINTS[m] if points is None else points
         self.points = [Fraction(p) for p in pts]
         self.AT, self.G, self.BT = toom_cook(m, r, self.points)
         n = self.n
-        self.PT = legendre_PT(n)
+        self.PT = base_PT(n, base)
         self.PinvT = inverse(self.PT)
         self.P = transpose(self.PT)
         self.Pinv = transpose(self.PinvT)

@@ -5,7 +5,7 @@ from fractions import Fraction
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 
-BASE_CANONICAL, BASE_LEGENDRE = 0, 1
+BASE_CANONICAL, BASE_LEGENDRE, BASE_CHEBYSHEV, BASE_HERMITE = 0, 1, 2, 3
 OUT_F32, OUT_I32, OUT_I8 = 0, 1, 2
 FUSED_OFF, FUSED_ON, FUSED_AUTO = 0, 1, 2
 MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")

@@ -224,7 +224,7 @@ int wino_make_matrices(int m, int r, const wino_rat_t* points, int n_finite, int
   if (m + r - 1 > kMaxN) return fail(WINO_EUNSUPPORTED, "m + r - 1 = %d exceeds %d", m + r - 1, kMaxN);
   if (n_finite != m + r - 2) return fail(WINO_EINVAL, "need m + r - 2 = %d finite points, got %d", m + r - 2, n_finite);
   if (n_finite > 0 && !points) return fail(WINO_EINVAL, "null points");
-  if (base != WINO_BASE_CANONICAL && base != WINO_BASE_LEGENDRE)
+  if (base < WINO_BASE_CANONICAL || base > WINO_BASE_HERMITE)
     return fail(WINO_EINVAL, "unknown base %d", base);
   Rat pts[kMaxN];
   for (int i = 0; i < n_finite; ++i) {
@@ -236,7 +236,7 @@ int wino_make_matrices(int m, int r, const wino_rat_t* points, int n_finite, int
   }
   wino_matrices* h = new (std::nothrow) wino_matrices;
   if (!h) return fail(WINO_EINVAL, "out of host memory");
-  h->ms = make_matrix_set(m, r, pts, n_finite, base == WINO_BASE_LEGENDRE);
+  h->ms = make_matrix_set(m, r, pts, n_finite, base);
   if (!h->ms.ok) {
     delete h;
     return fail(WINO_EOVERFLOW, "a rational overflowed int64 while building F(%d,%d)", m, r);

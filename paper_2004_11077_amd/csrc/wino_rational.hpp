@@ -226,10 +226,40 @@ constexpr RMat legendre_PT(int n) {
   return pt;
 }
 
-// points: n-1 finite rationals (infinity implicit and last).  With legendre ==
-// false the base change is the identity (P = I, G_P = G, ...).
+// Other classical orthogonal families, also monic (Section 4.1 names them as
+// the usual alternatives to Legendre).
+//   Chebyshev (first kind): t_0 = 1, t_1 = x, t_2 = x^2 - 1/2, t_{k+1} = x t_k - t_{k-1}/4
+//   Hermite (probabilists'): he_0 = 1, he_1 = x, he_{k+1} = x he_k - k he_{k-1}
+constexpr RMat recurrence_PT(int n, int family) {
+  RMat pt = rmat(n, n);
+  for (int i = 0; i < n; ++i) {
+    if (i == 0) {
+      pt.a[0][0] = make_rat(1, 1);
+    } else if (i == 1) {
+      pt.a[1][1] = make_rat(1, 1);
+    } else {
+      const int64_t k = i - 1;
+      const Rat coef = family == 2 ? (i == 2 ? make_rat(1, 2) : make_rat(1, 4)) : make_rat(k, 1);
+      for (int d = 1; d <= i; ++d) pt.a[i][d] = pt.a[i - 1][d - 1];
+      for (int d = 0; d <= i - 2; ++d)
+        pt.a[i][d] = rat_sub(pt.a[i][d], rat_mul(coef, pt.a[i - 2][d]));
+    }
+  }
+  pt.ok = rmat_ok(pt);
+  return pt;
+}
+
+// base: 0 canonical (P = I), 1 monic Legendre, 2 monic Chebyshev, 3 monic Hermite.
+constexpr RMat base_PT(int n, int base) {
+  if (base == 0) return rmat_identity(n);
+  if (base == 1) return legendre_PT(n);
+  return recurrence_PT(n, base);
+}
+
+// points: n-1 finite rationals (infinity implicit and last).  `base` selects
+// the base-change matrix P (see base_PT; 0 makes it the identity: G_P = G, ...).
 constexpr MatrixSet make_matrix_set(int m, int r, const Rat* points, int n_finite,
-                                    bool legendre = true) {
+                                    int base = 1) {
   MatrixSet s;
   s.m = m;
   s.r = r;
@@ -280,7 +310,7 @@ constexpr MatrixSet make_matrix_set(int m, int r, const Rat* points, int n_finit
     for (int d = 0; d < len && d < n; ++d) s.BT.a[j][d] = poly[d];
   }
 
-  s.PT = legendre ? legendre_PT(n) : rmat_identity(n);
+  s.PT = base_PT(n, base);
   s.PinvT = rmat_inverse(s.PT);
   s.P = rmat_transpose(s.PT);
   s.Pinv = rmat_transpose(s.PinvT);

@@ -56,6 +56,15 @@ def test_make_matrices_canonical_base_has_identity_P():
     assert got.GP == got.G and got.BPT == got.BT and got.APT == got.AT
 
 
+@pytest.mark.parametrize("m", [2, 4, 6])
+@pytest.mark.parametrize("base,name", [(2, "chebyshev"), (3, "hermite")])
+def test_make_matrices_other_bases(m, base, name):
+    got = wn.wino_make_matrices(m, 3, mx.POINTS[m], base)
+    ora = mx.Matrices(m, 3, base=name)
+    for gname, oname in ORACLE_NAMES.items():
+        assert getattr(got, gname) == getattr(ora, oname), gname
+
+
 @pytest.mark.parametrize("m,r,pts", [(3, 2, [0, 1, -1]), (2, 5, [0, 1, -1, 2, -2]),
                                      (4, 3, [0, 1, -1, Fraction(1, 2), -2]), (1, 1, []),
                                      (3, 3, [0, 1, -1, Fraction(3, 2)])])

@@ -186,3 +186,29 @@ def test_int_form_roundtrip_and_row_lcds():
             for v in N[i] + [rho[i]]:
                 g = gcd(g, abs(v))
             assert g == 1                      # rho_i is the *least* common denominator
+
+
+@pytest.mark.parametrize("n", [4, 6, 8])
+def test_chebyshev_and_hermite_rows_against_numpy(n):
+    """The other bases Section 4.1 names, pinned to library conversions."""
+    from numpy.polynomial import chebyshev, hermite_e
+    for rows, conv in ((mx.chebyshev_PT(n), chebyshev.cheb2poly),
+                       (mx.hermite_PT(n), hermite_e.herme2poly)):
+        for i in range(n):
+            coef = conv([0] * i + [1])
+            coef = coef / coef[-1]
+            got = np.array([float(v) for v in rows[i][:i + 1]])
+            assert np.allclose(got, coef, rtol=1e-12, atol=1e-12)
+            assert rows[i][i] == 1 and all(v == 0 for v in rows[i][i + 1:])
+
+
+@pytest.mark.parametrize("base", ["chebyshev", "hermite"])
+def test_other_bases_leave_the_convolution_unchanged(base):
+    M = mx.Matrices(4, 3, base=base)
+    assert mx.matmul(M.Pinv, M.GP) == M.G
+    assert mx.matmul(M.BPT, M.PinvT) == M.BT
+    assert mx.matmul(M.APT, M.PinvT) == M.AT
+    rnd = random.Random(5)
+    X = [[Fraction(rnd.randint(-127, 127)) for _ in range(6)] for _ in range(6)]
+    Wk = [[Fraction(rnd.randint(-127, 127)) for _ in range(3)] for _ in range(3)]
+    assert wg.tile_eq4_fraction(X, Wk, M) == wg.tile_direct_fraction(X, Wk, 4, 3)
