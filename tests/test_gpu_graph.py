@@ -1,0 +1,50 @@
+"""wino_conv2d under HIP graph capture: it allocates nothing, never synchronises
+and queues only kernels, so a captured layer must replay to the eager result.
+The graph is replayed several times with eager work and synchronisations in
+between, and every replay is compared with the eager output."""
+import numpy as np
+import pytest
+
+from helpers import oracle_layer, small_layer
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("fused", [0, 1])
+def test_captured_layer_replays_to_the_eager_result(fused):
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    xq, wq, s_x, s_w = small_layer(4, 8, 8, 64, 64, seed=110)
+    ora, sc = oracle_layer(xq, wq, s_x, s_w, m=4, base="legendre", out_type="i8", relu=True)
+    desc = wn.ConvDesc(4, 8, 8, 64, 64, m=4, out_type=wn.OUT_I8, relu=1, fused=fused)
+    scales = wn.Scales.from_dict(sc)
+    x = torch.from_numpy(xq).to(dev)
+    w = torch.from_numpy(wq).to(dev)
+    y = torch.zeros((4, 8, 8, 64), dtype=torch.int8, device=dev)
+    ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        wn.wino_conv2d(desc, x, w, y, scales, ws, s)             # eager warm-up on the side stream
+        torch.cuda.synchronize()
+        eager = y.clone()
+        assert np.array_equal(eager.cpu().numpy().astype(np.int64), ora["y"])
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            wn.wino_conv2d(desc, x, w, y, scales, ws, s)
+    for rep in range(4):
+        y.fill_(rep + 1)                                         # eager work between replays
+        ws.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, eager), "replay %d differs" % rep
+        # new input values through the same graph
+    x2 = torch.roll(x, 1, dims=0)
+    x.copy_(x2)
+    g.replay()
+    torch.cuda.synchronize()
+    ora2, _ = oracle_layer(np.roll(xq, 1, axis=0), wq, s_x, s_w, m=4, base="legendre",
+                           out_type="i8", relu=True)
+    # the scales were calibrated on the same multiset of images, so they are unchanged
+    assert np.array_equal(y.cpu().numpy().astype(np.int64), ora2["y"])
