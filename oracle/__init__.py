@@ -19,6 +19,11 @@ Parity status of each part (what pins it besides itself):
 * ``quantised`` integer stages   pinned by brute force on tiny inputs, by the
                     inner_quant=0 identity (Legendre == canonical bit for bit),
                     by exact-rational rounding, and by an a-priori error bound.
+* ``flex``          (run-time fp32 matrices, Section 4.2) pinned where fp32 is exact
+                    (must equal ``quantised`` bit for bit), by scalar loops on one
+                    tile, and by convergence to an fp64 evaluation of eq. 3 / eq. 4
+                    with the same arbitrary matrices; outputs for trained
+                    matrices: **parity unpinned** (none are published).
 * ``quantised`` absolute output values: **parity unpinned** by the paper (it
                     prints no worked numeric example; its quantisation figure is
                     missing).  They are pinned oracle <-> GPU only.
