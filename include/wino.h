@@ -170,6 +170,49 @@ int wino_calibrate_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void* y,
                    wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* Section 4.2, "flex" variant: the layer with TRAINED transformation matrices.
+ * G_P, B_P, A_P (G, B, A when d->base is canonical) are fp32 parameters given
+ * at run time; P and P^{-1} stay the fixed rational matrices.  Host arrays,
+ * row-major: GP n x 3, BPT n x n (B_P transposed), APT m x n (A_P transposed);
+ * entries finite, |entry| <= 2^20; they are read during the call and need not
+ * outlive it. */
+typedef struct {
+  const float* GP;
+  const float* BPT;
+  const float* APT;
+} wino_flex_matrices_t;
+
+/* The stages and the layer of the flex variant.  Data flow, layouts, casts and
+ * scales are those of wino_conv2d; wino_contract is shared.  The brackets with
+ * P^{-1} (W1 -> V, x -> X1, M -> M1) keep their exact integer arithmetic.  A
+ * bracket T q T^T with a run-time matrix T is evaluated on the integer codes q
+ * in fp32, in this fixed order, every product and every sum rounded to fp32
+ * and never fused:
+ *     left[i][b] = ((T[i][0] q[0][b] + T[i][1] q[1][b]) + ...)
+ *     out[i][j]  = ((left[i][0] T[j][0] + left[i][1] T[j][1]) + ...)
+ * and is followed by the cast clamp(rint(out * float(s_prev / s_next))), the
+ * exact product rounded once, ties to even; an fp32 output is
+ * out * float(s_prev).  Restrictions: int8 path; Legendre base needs
+ * inner_quant = 1; out_type F32 or I8; no fused variant (d->fused = ON is
+ * EUNSUPPORTED, AUTO runs one kernel per stage).  Workspace of
+ * wino_flex_conv2d: wino_workspace_bytes() with d->fused = OFF.
+ * wino_flex_calibrate is wino_calibrate for this variant (same workspace
+ * size, same rule: scale = float(max |real| / qmax) stage after stage).
+ * Errors as for the static calls, plus EINVAL for a null, non-finite or
+ * too large matrix entry. */
+int wino_flex_weight_transform(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
+                               const void* w, void* V, const wino_scales_t* s, void* hip_stream);
+int wino_flex_input_transform(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
+                              const void* x, void* U, const wino_scales_t* s, void* hip_stream);
+int wino_flex_output_transform(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
+                               const void* M, void* y, const wino_scales_t* s, void* hip_stream);
+int wino_flex_conv2d(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, const void* x,
+                     const void* w_or_V, void* y, const wino_scales_t* s, void* workspace,
+                     size_t ws_bytes, void* hip_stream);
+int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, const void* x,
+                        const void* w, void* y, wino_scales_t* s, void* workspace,
+                        size_t ws_bytes, void* hip_stream);
+
 /* Measurement hook.  The next kernel that the calling thread launches through
  * this library records its own begin into `start_event` and its own end into
  * `stop_event` (hipEvent_t handles created by the caller, either may be null);

@@ -13,7 +13,9 @@ EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_
            "wino_workspace_bytes", "wino_calibrate_workspace_bytes", "wino_calibrate",
            "wino_conv2d", "wino_weight_transform",
            "wino_input_transform", "wino_transform_operands", "wino_contract",
-           "wino_output_transform", "wino_profile_next_launch", "wino_last_error")
+           "wino_output_transform", "wino_flex_weight_transform", "wino_flex_input_transform",
+           "wino_flex_output_transform", "wino_flex_conv2d", "wino_flex_calibrate",
+           "wino_profile_next_launch", "wino_last_error")
 
 
 class WinoError(RuntimeError):
@@ -59,6 +61,16 @@ class Scales(C.Structure):
         return s
 
 
+class FlexMatrices(C.Structure):
+    """Mirror of wino_flex_matrices_t: host fp32 arrays GP [n,3], BPT [n,n], APT [m,n]."""
+    _fields_ = [(n, C.POINTER(C.c_float)) for n in ("GP", "BPT", "APT")]
+
+    def __init__(self, GP, BPT, APT):
+        import numpy as np
+        self._keep = [np.ascontiguousarray(a, dtype=np.float32) for a in (GP, BPT, APT)]
+        super().__init__(*[a.ctypes.data_as(C.POINTER(C.c_float)) for a in self._keep])
+
+
 def lib_path():
     return os.path.join(HERE, "libwino.so")
 
@@ -94,6 +106,12 @@ def _load():
     lib.wino_transform_operands.argtypes = [dp, vp, vp, vp, vp, sp, vp]
     lib.wino_contract.argtypes = [dp, vp, vp, vp, sp, vp]
     lib.wino_output_transform.argtypes = [dp, vp, vp, sp, vp]
+    fp = C.POINTER(FlexMatrices)
+    lib.wino_flex_weight_transform.argtypes = [dp, fp, vp, vp, sp, vp]
+    lib.wino_flex_input_transform.argtypes = [dp, fp, vp, vp, sp, vp]
+    lib.wino_flex_output_transform.argtypes = [dp, fp, vp, vp, sp, vp]
+    lib.wino_flex_conv2d.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
+    lib.wino_flex_calibrate.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_profile_next_launch.argtypes = [vp, vp]
     _lib = lib
     return lib
@@ -227,3 +245,44 @@ def wino_output_transform(desc, M, y, scales, stream=None):
     _check(_load().wino_output_transform(C.byref(desc), _ptr(M), _ptr(y), C.byref(sc),
                                          _stream(stream)))
     return y
+
+
+def wino_flex_weight_transform(desc, fm, w, V, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_flex_weight_transform(C.byref(desc), C.byref(fm), _ptr(w), _ptr(V),
+                                              C.byref(sc), _stream(stream)))
+    return V
+
+
+def wino_flex_input_transform(desc, fm, x, U, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_flex_input_transform(C.byref(desc), C.byref(fm), _ptr(x), _ptr(U),
+                                             C.byref(sc), _stream(stream)))
+    return U
+
+
+def wino_flex_output_transform(desc, fm, M, y, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_flex_output_transform(C.byref(desc), C.byref(fm), _ptr(M), _ptr(y),
+                                              C.byref(sc), _stream(stream)))
+    return y
+
+
+def wino_flex_conv2d(desc, fm, x, w_or_V, y, scales, workspace, stream=None):
+    """Whole layer with run-time fp32 matrices ``fm`` (a FlexMatrices)."""
+    sc = _scales(scales)
+    _check(_load().wino_flex_conv2d(C.byref(desc), C.byref(fm), _ptr(x), _ptr(w_or_V), _ptr(y),
+                                    C.byref(sc), _ptr(workspace),
+                                    workspace.numel() * workspace.element_size(),
+                                    _stream(stream)))
+    return y
+
+
+def wino_flex_calibrate(desc, fm, x, w, y, s_x, s_w, workspace, stream=None):
+    """wino_calibrate for the flex layer; returns a Scales struct."""
+    sc = Scales.from_dict({"s_x": s_x, "s_w": s_w})
+    _check(_load().wino_flex_calibrate(C.byref(desc), C.byref(fm), _ptr(x), _ptr(w), _ptr(y),
+                                       C.byref(sc), _ptr(workspace),
+                                       workspace.numel() * workspace.element_size(),
+                                       _stream(stream)))
+    return sc

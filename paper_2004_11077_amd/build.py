@@ -18,12 +18,14 @@ LIB = os.path.join(HERE, "libwino.so")
 
 HIP_SOURCES = ["wino_kernels.hip", "wino_transforms_f2.hip", "wino_transforms_f4.hip",
                "wino_transforms_f6.hip", "wino_fp32.hip", "wino_fused.hip",
-               "wino_calibrate_f2.hip", "wino_calibrate_f4.hip", "wino_calibrate_f6.hip"]
+               "wino_calibrate_f2.hip", "wino_calibrate_f4.hip", "wino_calibrate_f6.hip",
+               "wino_flex_f2.hip", "wino_flex_f4.hip", "wino_flex_f6.hip"]
 CXX_SOURCES = ["wino_api.cpp"]
 
 COMMON = ["-std=c++20", "-fPIC", "-fconstexpr-steps=200000000", "-Wall", "-Wno-unused-function"]
-# -ffp-contract=off: every cast is one fp32 multiply followed by rint; no FMA
-# may be formed.  Packed fp32 VALU forms are disabled for the device pass.
+# -ffp-contract=off: the only fused multiply-adds are the ones written out (the
+# casts); the fp32 brackets of the flex kernels round every product and sum.
+# Packed fp32 VALU forms are disabled for the device pass.
 DEVICE = ["-O3", "--offload-arch=gfx950", "-ffp-contract=off",
           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -446,6 +446,29 @@ int cal_bracket(CalCtx& c, int stage, const Plan& p, int phase, const void* in, 
   return cal_read(c);
 }
 
+// s_m from the exact int32 contraction result (U, V already in the workspace);
+// leaves M computed with the chosen scale and reports the scale of its codes.
+int calibrate_contraction(CalCtx& c, const wino_conv_desc_t* d, const wino_conv_desc_t& dd,
+                          const Plan& p, const void* U, const void* V, void* M, void* M32,
+                          wino_scales_t* s, double* s_m_eff) {
+  const double s_uv = (double)s->s_u * (double)s->s_v;
+  *s_m_eff = s_uv;
+  if (p.m_bits == 32) return wino_contract(&dd, U, V, M, s, c.st);
+  wino_conv_desc_t d32 = dd;
+  d32.bits_hadamard = 32;
+  if (int rc = wino_contract(&d32, U, V, M32, s, c.st)) return rc;
+  if (int rc = cal_reset(c)) return rc;
+  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  hipError_t e = launch_absmax_i32((const int32_t*)M32, (long)(n2 * p.g.T * d->K), c.d_amax, c.st);
+  if (e != hipSuccess) return fail_hip(e, "absmax launch");
+  if (int rc = cal_read(c)) return rc;
+  const double real = (double)c.h_amax[0] * s_uv;
+  const double qm = p.m_bits == 8 ? 127.0 : 255.0;
+  s->s_m = real > 0.0 ? (float)(real / qm) : 1.0f;
+  *s_m_eff = (double)s->s_m;
+  return wino_contract(&dd, U, V, M, s, c.st);
+}
+
 size_t calibrate_layout(const wino_conv_desc_t* d, const Plan& p, size_t* oV, size_t* oU,
                         size_t* oM, size_t* oM32, size_t* oA) {
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
@@ -523,26 +546,8 @@ int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void
   }
   if (int rc = wino_input_transform(&dd, x, U, s, hip_stream)) return rc;
 
-  // contraction: s_m from the exact int32 result
-  const double s_uv = (double)s->s_u * (double)s->s_v;
-  double s_m_eff = s_uv;
-  if (p.m_bits == 32) {
-    if (int rc = wino_contract(&dd, U, V, M, s, hip_stream)) return rc;
-  } else {
-    wino_conv_desc_t d32 = dd;
-    d32.bits_hadamard = 32;
-    if (int rc = wino_contract(&d32, U, V, M32, s, hip_stream)) return rc;
-    if (int rc = cal_reset(c)) return rc;
-    const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
-    hipError_t e = launch_absmax_i32((const int32_t*)M32, (long)(n2 * p.g.T * d->K), c.d_amax, c.st);
-    if (e != hipSuccess) return fail_hip(e, "absmax launch");
-    if (int rc = cal_read(c)) return rc;
-    const double real = (double)c.h_amax[0] * s_uv;
-    const double qm = p.m_bits == 8 ? 127.0 : 255.0;
-    s->s_m = real > 0.0 ? (float)(real / qm) : 1.0f;
-    s_m_eff = (double)s->s_m;
-    if (int rc = wino_contract(&dd, U, V, M, s, hip_stream)) return rc;
-  }
+  double s_m_eff;
+  if (int rc = calibrate_contraction(c, d, dd, p, U, V, M, M32, s, &s_m_eff)) return rc;
 
   // output: s_m1 (Legendre inner bracket), s_y
   if (p.two_brackets) {
@@ -621,6 +626,261 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   }
   if (int rc = wino_contract(d, U, V, M, s, hip_stream)) return rc;
   return wino_output_transform(d, M, y, s, hip_stream);
+}
+
+// ---------------------------------------------------------------------------
+// Flex layer: run-time fp32 matrices in the G_P / B_P / A_P brackets.
+// ---------------------------------------------------------------------------
+namespace {
+
+struct FlexPlan {
+  Plan p;
+  FlexMats fm;
+};
+
+int make_flex_plan(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, FlexPlan* fp) {
+  if (int rc = make_plan(d, &fp->p)) return rc;
+  const Plan& p = fp->p;
+  if (p.fp32) return fail(WINO_EUNSUPPORTED, "flex layers run on the int8 path (bits_in = 8)");
+  if (p.legendre && !p.two_brackets)
+    return fail(WINO_EUNSUPPORTED, "a flex layer in the Legendre base needs inner_quant = 1 "
+                                   "(run-time matrices cannot be multiplied out with P^{-1})");
+  if (d->out_type == WINO_OUT_I32)
+    return fail(WINO_EUNSUPPORTED, "a flex layer has fp32 or int8 output");
+  if (d->fused == WINO_FUSED_ON)
+    return fail(WINO_EUNSUPPORTED, "the fused variant has no flex form");
+  if (!f || !f->GP || !f->BPT || !f->APT) return fail(WINO_EINVAL, "null flex matrix");
+  const int n = d->m + 2;
+  std::memset(&fp->fm, 0, sizeof fp->fm);
+  struct { const float* src; float* dst; int count; const char* name; } parts[3] = {
+      {f->GP, fp->fm.GP, n * 3, "GP"}, {f->BPT, fp->fm.BPT, n * n, "BPT"},
+      {f->APT, fp->fm.APT, d->m * n, "APT"}};
+  for (auto& part : parts)
+    for (int i = 0; i < part.count; ++i) {
+      const float v = part.src[i];
+      if (!std::isfinite(v) || std::fabs(v) > 1048576.0f)
+        return fail(WINO_EINVAL, "flex matrix %s[%d] = %g: entries must be finite and at most 2^20 "
+                                 "in magnitude", part.name, i, (double)v);
+      part.dst[i] = v;
+    }
+  return WINO_OK;
+}
+
+// Multipliers of the three flex stages.  `first` is the cast after the fp32
+// bracket; the integer P^{-1} brackets use the tables of the static path.
+int flex_weight_mults(const Plan& p, const wino_scales_t* s, StageMults* mu, float* first) {
+  std::memset(mu, 0, sizeof *mu);
+  if (!good_scale(s->s_w) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_w / s_v");
+  if (p.two_brackets) {
+    if (!good_scale(s->s_w1)) return fail(WINO_EINVAL, "bad s_w1");
+    *first = (float)((double)s->s_w / (double)s->s_w1);
+    fill_mults(&mu->outer, *p.st.Pinv, s->s_w1, s->s_v);
+  } else {
+    *first = (float)((double)s->s_w / (double)s->s_v);
+  }
+  return WINO_OK;
+}
+
+int flex_input_mults(const Plan& p, const wino_scales_t* s, StageMults* mu, float* mult_u) {
+  std::memset(mu, 0, sizeof *mu);
+  if (!good_scale(s->s_x) || !good_scale(s->s_u)) return fail(WINO_EINVAL, "bad s_x / s_u");
+  if (p.two_brackets) {
+    if (!good_scale(s->s_x1)) return fail(WINO_EINVAL, "bad s_x1");
+    fill_mults(&mu->inner, *p.st.PinvT, s->s_x, s->s_x1);
+    *mult_u = (float)((double)s->s_x1 / (double)s->s_u);
+  } else {
+    *mult_u = (float)((double)s->s_x / (double)s->s_u);
+  }
+  return WINO_OK;
+}
+
+int flex_output_mults(const Plan& p, const wino_conv_desc_t* d, const wino_scales_t* s,
+                      StageMults* mu, float* mult_out) {
+  std::memset(mu, 0, sizeof *mu);
+  float dummy;
+  double s_prev;
+  if (int rc = contract_mult(p, s, &dummy, &s_prev)) return rc;
+  if (p.two_brackets) {
+    if (!good_scale(s->s_m1)) return fail(WINO_EINVAL, "bad s_m1");
+    fill_mults(&mu->inner, *p.st.PinvT, s_prev, s->s_m1);
+    s_prev = (double)s->s_m1;
+  }
+  if (d->out_type == WINO_OUT_I8) {
+    if (!good_scale(s->s_y)) return fail(WINO_EINVAL, "bad s_y");
+    *mult_out = (float)(s_prev / (double)s->s_y);
+  } else {
+    *mult_out = (float)s_prev;
+  }
+  return WINO_OK;
+}
+
+// scale = float( max |fp32 bracket value| * s_prev / qmax ), 1 if everything is zero.
+float flex_scale_from(unsigned long long amax_bits, double s_prev, double qmax) {
+  const uint32_t bits = (uint32_t)amax_bits;
+  float amax;
+  std::memcpy(&amax, &bits, sizeof amax);
+  const double real = (double)amax * s_prev;
+  return real > 0.0 ? (float)(real / qmax) : 1.0f;
+}
+
+int flex_cal_launch(CalCtx& c, int stage, const FlexPlan& fp, int mode, const void* in,
+                    const StageMults& mu, float mult, bool relu) {
+  if (int rc = cal_reset(c)) return rc;
+  hipError_t e = launch_flex_stage(stage, fp.p.g, fp.p.two_brackets, mode, in, fp.p.m_bits, nullptr,
+                                   0, relu, c.d_amax, fp.fm, mu, mult, c.st);
+  if (e != hipSuccess) return fail_hip(e, "flex calibration launch");
+  return cal_read(c);
+}
+
+}  // namespace
+
+int wino_flex_weight_transform(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
+                               const void* w, void* V, const wino_scales_t* s, void* hip_stream) {
+  FlexPlan fp;
+  if (int rc = make_flex_plan(d, f, &fp)) return rc;
+  if ((long)fp.p.g.K * fp.p.g.C == 0) return WINO_OK;
+  if (int rc = need(w, "w")) return rc;
+  if (int rc = need(V, "V")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  StageMults mu;
+  float first;
+  if (int rc = flex_weight_mults(fp.p, s, &mu, &first)) return rc;
+  hipError_t e = launch_flex_stage(0, fp.p.g, fp.p.two_brackets, 0, w, 8, V, 0, false, nullptr,
+                                   fp.fm, mu, first, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "flex weight transform launch");
+}
+
+int wino_flex_input_transform(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
+                              const void* x, void* U, const wino_scales_t* s, void* hip_stream) {
+  FlexPlan fp;
+  if (int rc = make_flex_plan(d, f, &fp)) return rc;
+  if ((long)fp.p.g.T * fp.p.g.C == 0) return WINO_OK;
+  if (int rc = need(x, "x")) return rc;
+  if (int rc = need(U, "U")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  StageMults mu;
+  float mult_u;
+  if (int rc = flex_input_mults(fp.p, s, &mu, &mult_u)) return rc;
+  hipError_t e = launch_flex_stage(1, fp.p.g, fp.p.two_brackets, 0, x, 8, U, 0, false, nullptr,
+                                   fp.fm, mu, mult_u, (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "flex input transform launch");
+}
+
+int wino_flex_output_transform(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
+                               const void* M, void* y, const wino_scales_t* s, void* hip_stream) {
+  FlexPlan fp;
+  if (int rc = make_flex_plan(d, f, &fp)) return rc;
+  if ((long)fp.p.g.T * fp.p.g.K == 0) return WINO_OK;
+  if (int rc = need(M, "M")) return rc;
+  if (int rc = need(y, "y")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  StageMults mu;
+  float mult_out;
+  if (int rc = flex_output_mults(fp.p, d, s, &mu, &mult_out)) return rc;
+  hipError_t e = launch_flex_stage(2, fp.p.g, fp.p.two_brackets, 0, M, fp.p.m_bits, y, d->out_type,
+                                   d->relu != 0, nullptr, fp.fm, mu, mult_out,
+                                   (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "flex output transform launch");
+}
+
+int wino_flex_conv2d(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, const void* x,
+                     const void* w_or_V, void* y, const wino_scales_t* s, void* workspace,
+                     size_t ws_bytes, void* hip_stream) {
+  FlexPlan fp;
+  if (int rc = make_flex_plan(d, f, &fp)) return rc;
+  const Plan& p = fp.p;
+  if (p.g.T == 0 || p.g.K == 0) return WINO_OK;   // no output element exists
+  wino_conv_desc_t dd = *d;
+  dd.fused = WINO_FUSED_OFF;
+  size_t want = 0;
+  if (int rc = wino_workspace_bytes(&dd, &want)) return rc;
+  if (int rc = need(workspace, "workspace")) return rc;
+  if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
+  if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  char* ws = static_cast<char*>(workspace);
+  const void* V = w_or_V;
+  if (!d->weights_pretransformed) {
+    if (int rc = wino_flex_weight_transform(&dd, f, w_or_V, ws, s, hip_stream)) return rc;
+    V = ws;
+    ws += round256(n2 * d->K * d->C);
+  }
+  void* U = ws;
+  ws += round256(n2 * p.g.T * d->C);
+  void* M = ws;
+  if (int rc = wino_flex_input_transform(&dd, f, x, U, s, hip_stream)) return rc;
+  if (int rc = wino_contract(&dd, U, V, M, s, hip_stream)) return rc;
+  return wino_flex_output_transform(&dd, f, M, y, s, hip_stream);
+}
+
+int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, const void* x,
+                        const void* w, void* y, wino_scales_t* s, void* workspace,
+                        size_t ws_bytes, void* hip_stream) {
+  FlexPlan fp;
+  if (int rc = make_flex_plan(d, f, &fp)) return rc;
+  const Plan& p = fp.p;
+  if (d->C > kMaxChannelsExact)
+    return fail(WINO_EOVERFLOW, "C = %d: calibration needs the exact int32 contraction result", d->C);
+  if (int rc = need(s, "scales")) return rc;
+  if (!good_scale(s->s_x) || !good_scale(s->s_w)) return fail(WINO_EINVAL, "s_x and s_w must be set");
+  if (int rc = need(workspace, "workspace")) return rc;
+  size_t oV, oU, oM, oM32, oA;
+  const size_t want = calibrate_layout(d, p, &oV, &oU, &oM, &oM32, &oA);
+  if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
+  if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  s->s_x1 = s->s_u = s->s_w1 = s->s_v = s->s_m = s->s_m1 = s->s_y = 1.0f;
+  if (p.g.T == 0 || p.g.K == 0 || p.g.C == 0) return WINO_OK;
+  if (int rc = need(x, "x")) return rc;
+  if (int rc = need(w, "w")) return rc;
+  char* ws = static_cast<char*>(workspace);
+  void *V = ws + oV, *U = ws + oU, *M = ws + oM, *M32 = ws + oM32;
+  CalCtx c{(hipStream_t)hip_stream, reinterpret_cast<unsigned long long*>(ws + oA), {}};
+  wino_conv_desc_t dd = *d;
+  dd.weights_pretransformed = 0;
+  dd.fused = 0;
+  StageMults mu;
+  std::memset(&mu, 0, sizeof mu);
+
+  // filters: the fp32 G bracket first, then (Legendre) the integer P^{-1} bracket
+  if (int rc = flex_cal_launch(c, 0, fp, 1, w, mu, 1.f, false)) return rc;
+  if (p.two_brackets) {
+    s->s_w1 = flex_scale_from(c.h_amax[0], s->s_w, 127.0);
+    const float first = (float)((double)s->s_w / (double)s->s_w1);
+    if (int rc = flex_cal_launch(c, 0, fp, 2, w, mu, first, false)) return rc;
+    s->s_v = scale_from(c.h_amax, *p.st.Pinv, s->s_w1, 127.0);
+  } else {
+    s->s_v = flex_scale_from(c.h_amax[0], s->s_w, 127.0);
+  }
+  if (int rc = wino_flex_weight_transform(&dd, f, w, V, s, hip_stream)) return rc;
+
+  // activations: (Legendre) the integer P^{-T} bracket, then the fp32 B bracket
+  double s_prev = s->s_x;
+  if (p.two_brackets) {
+    if (int rc = cal_bracket(c, 1, p, 1, x, 8, mu, false)) return rc;
+    s->s_x1 = scale_from(c.h_amax, *p.st.PinvT, s->s_x, 127.0);
+    fill_mults(&mu.inner, *p.st.PinvT, s->s_x, s->s_x1);
+    s_prev = s->s_x1;
+  }
+  if (int rc = flex_cal_launch(c, 1, fp, 1, x, mu, 1.f, false)) return rc;
+  s->s_u = flex_scale_from(c.h_amax[0], s_prev, 127.0);
+  if (int rc = wino_flex_input_transform(&dd, f, x, U, s, hip_stream)) return rc;
+
+  double s_m_eff;
+  if (int rc = calibrate_contraction(c, d, dd, p, U, V, M, M32, s, &s_m_eff)) return rc;
+
+  // output: (Legendre) the integer P^{-T} bracket, then the fp32 A bracket
+  s_prev = s_m_eff;
+  if (p.two_brackets) {
+    if (int rc = cal_bracket(c, 2, p, 1, M, p.m_bits, mu, false)) return rc;
+    s->s_m1 = scale_from(c.h_amax, *p.st.PinvT, s_m_eff, 127.0);
+    fill_mults(&mu.inner, *p.st.PinvT, s_m_eff, s->s_m1);
+    s_prev = s->s_m1;
+  }
+  if (int rc = flex_cal_launch(c, 2, fp, 1, M, mu, 1.f, d->relu != 0)) return rc;
+  s->s_y = flex_scale_from(c.h_amax[0], s_prev, 127.0);
+  if (y)
+    if (int rc = wino_flex_output_transform(&dd, f, M, y, s, hip_stream)) return rc;
+  return WINO_OK;
 }
 
 }  // extern "C"

@@ -247,6 +247,29 @@ hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool leg, int ph
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_flex_stage(int stage, const Geometry& g, bool leg, int mode, const void* in,
+                             int m_bits, void* out, int out_type, bool relu,
+                             unsigned long long* amax, const FlexMats& fm, const StageMults& mu,
+                             float mult, hipStream_t st) {
+  const long items = stage == 0 ? (long)g.K * g.C : stage == 1 ? (long)g.T * g.C : (long)g.T * g.K;
+  if (items == 0) return hipSuccess;
+#define WINO_FLEX_M(MM)                                                                          \
+  case MM:                                                                                       \
+    return stage == 0   ? PerMFlex<MM>::weight(g, leg, mode, (const int8_t*)in, (int8_t*)out,    \
+                                               amax, fm, mu, mult, st)                           \
+           : stage == 1 ? PerMFlex<MM>::input(g, leg, mode, (const int8_t*)in, (int8_t*)out,     \
+                                              amax, fm, mu, mult, st)                            \
+                        : PerMFlex<MM>::output(g, leg, mode, in, m_bits, out, out_type, relu,    \
+                                               amax, fm, mu, mult, st);
+  switch (g.m) {
+    WINO_FLEX_M(2)
+    WINO_FLEX_M(4)
+    WINO_FLEX_M(6)
+  }
+#undef WINO_FLEX_M
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_weight_transform(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
                                    const StageMults& mu, hipStream_t st) {
   if ((long)g.K * g.C == 0) return hipSuccess;

@@ -82,6 +82,40 @@ extern template struct PerMCal<2>;
 extern template struct PerMCal<4>;
 extern template struct PerMCal<6>;
 
+// Run-time fp32 matrices of the trainable brackets (Section 4.2, "flex"),
+// row-major with their own column counts: GP n x 3, BPT n x n, APT m x n.
+struct FlexMats {
+  float GP[8 * 3];
+  float BPT[8 * 8];
+  float APT[6 * 8];
+};
+
+// Launchers of the flex kernels (wino_flex.hpp).  mode 0 runs the stage, 1
+// reduces max |fp32 bracket value| into amax[0] (float bit pattern), 2 (weights,
+// Legendre) reduces the per-(i, j) numerator maxima of the P^{-1} bracket.
+template <int M>
+struct PerMFlex {
+  static hipError_t weight(const Geometry& g, bool legendre, int mode, const int8_t* w, int8_t* V,
+                           unsigned long long* amax, const FlexMats& fm, const StageMults& mu,
+                           float mult_first, hipStream_t st);
+  static hipError_t input(const Geometry& g, bool legendre, int mode, const int8_t* x, int8_t* U,
+                          unsigned long long* amax, const FlexMats& fm, const StageMults& mu,
+                          float mult_u, hipStream_t st);
+  static hipError_t output(const Geometry& g, bool legendre, int mode, const void* M_, int m_bits,
+                           void* y, int out_type, bool relu, unsigned long long* amax,
+                           const FlexMats& fm, const StageMults& mu, float mult_out,
+                           hipStream_t st);
+};
+extern template struct PerMFlex<2>;
+extern template struct PerMFlex<4>;
+extern template struct PerMFlex<6>;
+
+// stage 0 weight, 1 input, 2 output, dispatched on g.m.
+hipError_t launch_flex_stage(int stage, const Geometry& g, bool legendre, int mode, const void* in,
+                             int m_bits, void* out, int out_type, bool relu,
+                             unsigned long long* amax, const FlexMats& fm, const StageMults& mu,
+                             float mult, hipStream_t st);
+
 // stage: 0 weight, 1 input, 2 output; phase 1 = inner bracket, 2 = outer bracket.
 hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool legendre_inner, int phase,
                                   const void* in, int m_bits, unsigned long long* amax,

@@ -130,3 +130,27 @@ def test_stage_calls_reject_bad_arguments_before_any_launch():
     assert lib.wino_conv2d(C.byref(d), fake, fake, fake, C.byref(s), fake, 16, None) == -4
     dfused = wn.ConvDesc(1, 8, 8, 16, 16, m=6, fused=1)     # the fused variant has no F(6,3)
     assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(s), fake, 1 << 30, None) == -2
+
+
+def test_flex_calls_validate_matrices_and_options_before_any_launch():
+    import numpy as np
+    lib = binding._load()
+    s = wn.Scales.from_dict({})
+    fake = C.c_void_p(4096)      # never dereferenced: validation fails first
+    good = wn.FlexMatrices(np.ones((6, 3)), np.ones((6, 6)), np.ones((4, 6)))
+    d = wn.ConvDesc(1, 8, 8, 16, 16)
+    for mats, text in [(wn.FlexMatrices(np.full((6, 3), np.nan), np.ones((6, 6)), np.ones((4, 6))), b"GP"),
+                       (wn.FlexMatrices(np.ones((6, 3)), np.full((6, 6), 3e6), np.ones((4, 6))), b"BPT"),
+                       (wn.FlexMatrices(np.ones((6, 3)), np.ones((6, 6)), np.full((4, 6), np.inf)), b"APT")]:
+        assert lib.wino_flex_input_transform(C.byref(d), C.byref(mats), fake, fake, C.byref(s), None) == -1
+        assert text in lib.wino_last_error()
+    assert lib.wino_flex_conv2d(C.byref(d), None, fake, fake, fake, C.byref(s), fake, 1 << 30, None) == -1
+    for kw in (dict(inner_quant=0), dict(base=wn.BASE_CANONICAL, out_type=wn.OUT_I32), dict(bits_in=32),
+               dict(fused=1)):
+        dd = wn.ConvDesc(1, 8, 8, 16, 16, **kw)
+        assert lib.wino_flex_conv2d(C.byref(dd), C.byref(good), fake, fake, fake, C.byref(s), fake,
+                                    1 << 30, None) == -2, kw
+    assert lib.wino_flex_conv2d(C.byref(d), C.byref(good), fake, fake, fake, C.byref(s), fake, 16, None) == -4
+    assert lib.wino_flex_weight_transform(C.byref(d), C.byref(good), None, fake, C.byref(s), None) == -1
+    assert lib.wino_flex_output_transform(C.byref(d), C.byref(good), fake, fake,
+                                          C.byref(wn.Scales.from_dict({"s_m1": -1.0})), None) == -1
