@@ -328,6 +328,29 @@ def main():
         out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
                                 "unit": "TOPS",
                                 "note": "input transform recomputed per 64-channel k block"}
+    # extra: the flex layer (run-time fp32 G_P, B_P, A_P; here the static matrices rounded
+    # to fp32, as at the start of training) on the same workload, whole-layer call
+    if not args.no_extras:
+        fm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],
+                                        dtype=np.float32) for nm in ("GP", "BPT", "APT")])
+        xdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                            bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32)
+        cws = torch.empty(wn.wino_calibrate_workspace_bytes(xdesc), dtype=torch.uint8, device=dev)
+        xsc = wn.wino_flex_calibrate(xdesc, fm, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
+        del cws
+        xws = torch.empty(wn.wino_workspace_bytes(xdesc), dtype=torch.uint8, device=dev)
+        for _ in range(args.warmup):
+            wn.wino_flex_conv2d(xdesc, fm, x, w, y, xsc, xws, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            wn.wino_flex_conv2d(xdesc, fm, x, w, y, xsc, xws, stream)
+        torch.cuda.synchronize()
+        xdt = (time.perf_counter() - t0) / args.steps
+        out["flex_variant"] = {"ms_per_step": xdt * 1e3, "value": ops / xdt / 1e12,
+                               "unit": "TOPS",
+                               "note": "fp32 brackets with run-time matrices, four launches"}
+        del xws
     # extra: whole-layer call (wino_conv2d) on the other single-layer configurations, split
     # path and AUTO (which takes the fused kernel where C, K <= 64); not the headline figure
     if not args.no_extras and reps == 1:
