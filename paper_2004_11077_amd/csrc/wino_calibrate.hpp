@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void k_cal_weight(const int8_t* __restrict__ w
       merge_amax<n>(num1, active, false, amax);
     } else {
       int w1[n][n];
-      cast_tile<n>(num1, mu.inner, 127.f, w1);
+      cast_result<TB::GP, 127>(num1, mu.inner, 127.f, w1);
       acc_t<TB::Pinv, 127> num2[n][n];
       sandwich<TB::Pinv, 127>(w1, num2);
       merge_amax<n>(num2, active, false, amax);
@@ -104,7 +104,7 @@ __global__ __launch_bounds__(256) void k_cal_input(const int8_t* __restrict__ x,
       merge_amax<n>(num1, active, false, amax);
     } else {
       int x1[n][n];
-      cast_tile<n>(num1, mu.inner, 127.f, x1);
+      cast_result<TB::PinvT, 127>(num1, mu.inner, 127.f, x1);
       acc_t<TB::BPT, 127> num2[n][n];
       sandwich<TB::BPT, 127>(x1, num2);
       merge_amax<n>(num2, active, false, amax);
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void k_cal_output(const MT* __restrict__ Mq,
       merge_amax<n>(num1, active, false, amax);
     } else {
       int m1[n][n];
-      cast_tile<n>(num1, mu.inner, 127.f, m1);
+      cast_result<TB::PinvT, IN_MAX>(num1, mu.inner, 127.f, m1);
       acc_t<TB::APT, 127> num2[M][M];
       sandwich<TB::APT, 127>(m1, num2);
       crop(num2);

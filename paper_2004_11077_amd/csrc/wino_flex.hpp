@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void k_flex_weight(const int8_t* __restrict__ 
       merge_amax<n>(num2, active, false, amax);
       return;
     }
-    cast_tile<n>(num2, mu.outer, 127.f, q);
+    cast_result<TB::Pinv, 127>(num2, mu.outer, 127.f, q);
   }
   if (!active) return;
   static_for<0, n>([&](auto i) {
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(256) void k_flex_input(const int8_t* __restrict__ x
   if constexpr (LEG) {
     acc_t<TB::PinvT, 127> num1[n][n];
     sandwich<TB::PinvT, 127>(xi, num1);
-    cast_tile<n>(num1, mu.inner, 127.f, xi);
+    cast_result<TB::PinvT, 127>(num1, mu.inner, 127.f, xi);
   }
   float val[n][n];
   fsandwich<n, n>(fm.BPT, xi, val);
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void k_flex_output(const MT* __restrict__ Mq,
   if constexpr (LEG) {
     acc_t<TB::PinvT, IN_MAX> num1[n][n];
     sandwich<TB::PinvT, IN_MAX>(xi, num1);
-    cast_tile<n>(num1, mu.inner, 127.f, xi);
+    cast_result<TB::PinvT, IN_MAX>(num1, mu.inner, 127.f, xi);
   }
   float val[M][M];
   fsandwich<M, n>(fm.APT, xi, val);

@@ -131,14 +131,14 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
         acc_t<TB::PinvT, 127> num1[n][n];
         sandwich<TB::PinvT, 127>(xi, num1);
         int x1[n][n];
-        cast_tile<n>(num1, in_mu.inner, 127.f, x1);
+        cast_result<TB::PinvT, 127>(num1, in_mu.inner, 127.f, x1);
         acc_t<TB::BPT, 127> num2[n][n];
         sandwich<TB::BPT, 127>(x1, num2);
-        cast_tile<n>(num2, in_mu.outer, 127.f, q);
+        cast_result<TB::BPT, 127>(num2, in_mu.outer, 127.f, q);
       } else {
         acc_t<TB::BT, 127> num[n][n];
         sandwich<TB::BT, 127>(xi, num);
-        cast_tile<n>(num, in_mu.outer, 127.f, q);
+        cast_result<TB::BT, 127>(num, in_mu.outer, 127.f, q);
       }
       static_for<0, n>([&](auto i) {
         static_for<0, n>([&](auto j) {
@@ -209,7 +209,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
         return (float)v;
       }
     };
-    auto finish = [&](auto& num) {
+    auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
           constexpr int idx = decltype(i)::value * M + decltype(j)::value;
@@ -218,10 +218,10 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
           if (h < g.H && ww < g.W) {
             const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
             if constexpr (OUT == 0) {
-              float v = to_float_approx(num[i][j]) * out_mu.outer.v[idx];
+              float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * out_mu.outer.v[idx];
               (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
             } else {
-              int v = cast_code((float)num[i][j], out_mu.outer.v[idx], 127.f);
+              int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), out_mu.outer.v[idx], 127.f);
               (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
             }
           }
@@ -233,14 +233,14 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
       acc_t<TB::PinvT, IN_MAX> num1[n][n];
       sandwich<TB::PinvT, IN_MAX>(mi, num1);
       int m1[n][n];
-      cast_tile<n>(num1, out_mu.inner, 127.f, m1);
+      cast_result<TB::PinvT, IN_MAX>(num1, out_mu.inner, 127.f, m1);
       acc_t<TB::APT, 127> num2[M][M];
       sandwich<TB::APT, 127>(m1, num2);
-      finish(num2);
+      finish.template operator()<TB::APT, 127>(num2);
     } else {
       acc_t<TB::AT, IN_MAX> num[M][M];
       sandwich<TB::AT, IN_MAX>(mi, num);
-      finish(num);
+      finish.template operator()<TB::AT, IN_MAX>(num);
     }
   }
 }

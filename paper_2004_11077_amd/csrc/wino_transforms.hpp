@@ -159,18 +159,25 @@ __device__ __forceinline__ AccT row_dot(Get&& get) {
 
 // out[i] = sum_a T.N[i][a] * get(a) for every row i, with paired rows sharing
 // their even and odd parts.  put(i, value) receives the results.
-template <const IMat& T, bool S24, typename AccT, class Get, class Put>
+// LROW >= 0 says that this is the second pass of a sandwich, towards the
+// entries (LROW, i) of N x N^T with |x| <= IN_MAX: a 64-bit AccT is then used
+// only for the entries whose own bound needs it, the others are accumulated in
+// 32 bits (get must then return 32-bit values) and widened at the end.
+template <const IMat& T, bool S24, typename AccT, int64_t IN_MAX = 0, int LROW = -1, class Get,
+          class Put>
 __device__ __forceinline__ void apply_rows(Get&& get, Put&& put) {
   static_for<0, T.rows>([&](auto i) {
     constexpr int I = decltype(i)::value;
     constexpr int PJ = partner_of(T, I);
+    constexpr bool narrow = LROW >= 0 && sizeof(AccT) == 8 && entry_fits_i32<T, IN_MAX>(LROW < 0 ? 0 : LROW, I);
+    using A = std::conditional_t<narrow, int32_t, AccT>;
     if constexpr (PJ > I) {
-      const AccT e = row_dot<T, I, 0, S24, AccT>(get);
-      const AccT o = row_dot<T, I, 1, S24, AccT>(get);
-      put(i, e + o);
-      put(IC<PJ>{}, e - o);
+      const A e = row_dot<T, I, 0, S24, A>(get);
+      const A o = row_dot<T, I, 1, S24, A>(get);
+      put(i, (AccT)(e + o));
+      put(IC<PJ>{}, (AccT)(e - o));
     } else if constexpr (PJ < 0) {
-      put(i, row_dot<T, I, 2, S24, AccT>(get));
+      put(i, (AccT)row_dot<T, I, 2, S24, A>(get));
     }
   });
 }
@@ -189,9 +196,21 @@ __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
                             [&](auto i, TmpT v) { tmp[i][b] = v; });
   });
   static_for<0, T.rows>([&](auto i) {                      // num = tmp N^T, row by row
-    apply_rows<T, s2, AccT>([&](auto b) { return tmp[i][b]; },
-                            [&](auto j, AccT v) { num[i][j] = v; });
+    constexpr int L = sizeof(TmpT) == 4 ? decltype(i)::value : -1;
+    apply_rows<T, s2, AccT, IN_MAX, L>([&](auto b) { return tmp[i][b]; },
+                                       [&](auto j, AccT v) { num[i][j] = v; });
   });
+}
+
+// The value of entry (I, J) of a sandwich result in the narrowest exact type:
+// a 64-bit entry whose own bound fits 32 bits is handed on as int32_t, which
+// makes its conversion to fp32 a single instruction.
+template <const IMat& T, int64_t IN_MAX, int I, int J, typename AccT>
+__device__ __forceinline__ auto entry(AccT v) {
+  if constexpr (sizeof(AccT) == 8 && entry_fits_i32<T, IN_MAX>(I, J))
+    return (int32_t)v;
+  else
+    return v;
 }
 
 // One symmetric cast: q = clamp(rint(v * mult), +-qmax), where rint rounds the
@@ -207,13 +226,15 @@ __device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
   return __float_as_int(t) - 0x4B400000;
 }
 
-template <int R, typename AccT>
-__device__ __forceinline__ void cast_tile(const AccT (&num)[R][R], const MultTable& mu, float qmax,
-                                          int (&q)[R][R]) {
-  static_for<0, R>([&](auto i) {
-    static_for<0, R>([&](auto j) {
-      q[i][j] = cast_code((float)num[i][j], mu.v[decltype(i)::value * R + decltype(j)::value],
-                          qmax);
+// Casts the result of sandwich<T, IN_MAX>, one multiplier per entry; entries
+// that fit 32 bits are converted as such.
+template <const IMat& T, int64_t IN_MAX, typename AccT>
+__device__ __forceinline__ void cast_result(const AccT (&num)[T.rows][T.rows], const MultTable& mu,
+                                            float qmax, int (&q)[T.rows][T.rows]) {
+  static_for<0, T.rows>([&](auto i) {
+    static_for<0, T.rows>([&](auto j) {
+      constexpr int I = decltype(i)::value, J = decltype(j)::value;
+      q[i][j] = cast_code((float)entry<T, IN_MAX, I, J>(num[i][j]), mu.v[I * T.rows + J], qmax);
     });
   });
 }
@@ -239,14 +260,14 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
     acc_t<TB::GP, 127> num1[n][n];
     sandwich<TB::GP, 127>(wi, num1);
     int w1[n][n];
-    cast_tile<n>(num1, mu.inner, 127.f, w1);
+    cast_result<TB::GP, 127>(num1, mu.inner, 127.f, w1);
     acc_t<TB::Pinv, 127> num2[n][n];
     sandwich<TB::Pinv, 127>(w1, num2);
-    cast_tile<n>(num2, mu.outer, 127.f, q);
+    cast_result<TB::Pinv, 127>(num2, mu.outer, 127.f, q);
   } else {
     acc_t<TB::G, 127> num[n][n];
     sandwich<TB::G, 127>(wi, num);
-    cast_tile<n>(num, mu.outer, 127.f, q);
+    cast_result<TB::G, 127>(num, mu.outer, 127.f, q);
   }
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
@@ -312,14 +333,14 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
     acc_t<TB::PinvT, 127> num1[n][n];
     sandwich<TB::PinvT, 127>(xi, num1);
     int x1[n][n];
-    cast_tile<n>(num1, mu.inner, 127.f, x1);
+    cast_result<TB::PinvT, 127>(num1, mu.inner, 127.f, x1);
     acc_t<TB::BPT, 127> num2[n][n];
     sandwich<TB::BPT, 127>(x1, num2);
-    cast_tile<n>(num2, mu.outer, 127.f, q);
+    cast_result<TB::BPT, 127>(num2, mu.outer, 127.f, q);
   } else {
     acc_t<TB::BT, 127> num[n][n];
     sandwich<TB::BT, 127>(xi, num);
-    cast_tile<n>(num, mu.outer, 127.f, q);
+    cast_result<TB::BT, 127>(num, mu.outer, 127.f, q);
   }
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
@@ -456,7 +477,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   };
   const long ybase = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K + k;
   const int wk = g.W * g.K;
-  auto finish = [&](auto& num) {
+  auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
     static_for<0, M>([&](auto i) {
       static_for<0, M>([&](auto j) {
         constexpr int idx = decltype(i)::value * M + decltype(j)::value;
@@ -465,13 +486,13 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
         if (h < g.H && ww < g.W) {
           const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
           if constexpr (OUT == 0) {
-            float v = to_float_approx(num[i][j]) * mu.outer.v[idx];
+            float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * mu.outer.v[idx];
             (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
           } else if constexpr (OUT == 1) {
             int v = (int)num[i][j];
             (static_cast<int*>(yv) + ybase)[rel] = relu ? max(v, 0) : v;
           } else {
-            int v = cast_code((float)num[i][j], mu.outer.v[idx], 127.f);
+            int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), mu.outer.v[idx], 127.f);
             (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
           }
         }
@@ -482,14 +503,14 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     acc_t<TB::PinvT, IN_MAX> num1[n][n];
     sandwich<TB::PinvT, IN_MAX>(xi, num1);
     int m1[n][n];
-    cast_tile<n>(num1, mu.inner, 127.f, m1);
+    cast_result<TB::PinvT, IN_MAX>(num1, mu.inner, 127.f, m1);
     acc_t<TB::APT, 127> num2[M][M];
     sandwich<TB::APT, 127>(m1, num2);
-    finish(num2);
+    finish.template operator()<TB::APT, 127>(num2);
   } else {
     acc_t<TB::AT, IN_MAX> num[M][M];
     sandwich<TB::AT, IN_MAX>(xi, num);
-    finish(num);
+    finish.template operator()<TB::AT, IN_MAX>(num);
   }
 }
 
