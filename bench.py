@@ -231,6 +231,12 @@ def main():
             wn.wino_profile_next_launch(events[2][0].value, events[2][1].value)
         wn.wino_output_transform(desc, M, y, sc, stream)
 
+    # one cold step (first launch of each kernel in this process), reported as an extra
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step()
+    torch.cuda.synchronize()
+    cold_ms = (time.perf_counter() - t0) * 1e3
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -256,6 +262,33 @@ def main():
         for a, b in evs[i]:
             hip.hipEventDestroy(a)
             hip.hipEventDestroy(b)
+    # What this device sustains on the three units the stages are priced against:
+    # register-only int8 MFMA and 24-bit multiply-add loops (library probes, timed per
+    # dispatch like the stages) and a plain 256 MiB device copy (read + write bytes).
+    def probe(kind, blocks, iters):
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        wn.wino_probe_peak(kind, blocks, iters, sink, stream)          # warm-up
+        a, b = new_event(), new_event()
+        wn.wino_profile_next_launch(a.value, b.value)
+        work = wn.wino_probe_peak(kind, blocks, iters, sink, stream)
+        torch.cuda.synchronize()
+        ms = elapsed_ms(a, b)
+        hip.hipEventDestroy(a)
+        hip.hipEventDestroy(b)
+        return work / (ms * 1e-3) / 1e12
+    src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    measured_peaks = {"int8_mfma_TOPs": probe(wn.PROBE_MFMA_I8, 256 * 16, 2048),
+                      "valu_mad24_Tops": probe(wn.PROBE_VALU_MAD24, 256 * 16, 2048),
+                      "copy_GBps": 2 * src.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
+    del src, dst
     pts = {2: [0, 1, -1], 4: [0, 1, -1, 2, -2], 6: [0, 1, -1, 2, -2, (1, 2), (-1, 2)]}[wl.m]
     from fractions import Fraction
     mats = wn.wino_make_matrices(wl.m, 3, [Fraction(*p) if isinstance(p, tuple) else p
@@ -282,6 +315,9 @@ def main():
             ach = model[nm]["work"] / sec / 1e12
             st.update({"bound": "mfma", "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS,
                        "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS})
+        own = {"alu": measured_peaks["valu_mad24_Tops"], "hbm": measured_peaks["copy_GBps"],
+               "mfma": measured_peaks["int8_mfma_TOPs"]}[st["bound"]]
+        st["frac_of_measured_peak"] = st["achieved"] / own
         st["traffic"] = traffic.get(nm)
         st["algorithmic_bytes"] = (model[nm]["work"] if model[nm]["bound"] == "hbm" else None)
         stages[nm] = st
@@ -289,7 +325,7 @@ def main():
     roofline = {k: stages[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac",
                                                    "traffic")}
     roofline["kernel"] = dominant
-    for k in ("hbm_GBps", "hbm_frac"):
+    for k in ("hbm_GBps", "hbm_frac", "frac_of_measured_peak"):
         if k in stages[dominant]:
             roofline[k] = stages[dominant][k]
 
@@ -310,6 +346,8 @@ def main():
                    "step": "weight+input transforms (one launch), contraction, output transform"},
         "roofline": roofline,
         "stages": stages,
+        "measured_peaks": measured_peaks,
+        "cold_step_ms": cold_ms,
     }
     # extra: the single-kernel fused variant on the same workload (same step
     # definition: filter transform + fused kernel), timed the same way

@@ -221,6 +221,17 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
  * consumed by that one launch.  Always returns WINO_OK. */
 int wino_profile_next_launch(void* start_event, void* stop_event);
 
+/* Measurement helper: one register-only kernel that shows what the device
+ * sustains on a unit the hot path is priced against.  WINO_PROBE_MFMA_I8:
+ * every wave issues iters x 4 independent 32x32x32 int8 MFMAs;
+ * WINO_PROBE_VALU_MAD24: every lane issues iters x 8 24-bit multiply-adds.
+ * `blocks` work groups of 256 lanes; *work (host, may be null) receives the
+ * int8 operations (2 per multiply-accumulate) resp. lane-operations of the
+ * launch; `sink` is a device int the kernel may write.  Time it with
+ * wino_profile_next_launch. */
+enum { WINO_PROBE_MFMA_I8 = 0, WINO_PROBE_VALU_MAD24 = 1 };
+int wino_probe_peak(int kind, int blocks, int iters, void* sink, double* work, void* hip_stream);
+
 /* Text of the last error on this thread ("" if none); valid until the next
  * failing call on the same thread. */
 const char* wino_last_error(void);

@@ -15,7 +15,7 @@ EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_
            "wino_input_transform", "wino_transform_operands", "wino_contract",
            "wino_output_transform", "wino_flex_weight_transform", "wino_flex_input_transform",
            "wino_flex_output_transform", "wino_flex_conv2d", "wino_flex_calibrate",
-           "wino_profile_next_launch", "wino_last_error")
+           "wino_profile_next_launch", "wino_probe_peak", "wino_last_error")
 
 
 class WinoError(RuntimeError):
@@ -113,6 +113,7 @@ def _load():
     lib.wino_flex_conv2d.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_flex_calibrate.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_profile_next_launch.argtypes = [vp, vp]
+    lib.wino_probe_peak.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
 
@@ -179,6 +180,16 @@ def _scales(s):
 def wino_profile_next_launch(start_event, stop_event):
     """Attach two raw hipEvent_t handles (ints) to the next kernel launch of this thread."""
     _check(_load().wino_profile_next_launch(C.c_void_p(start_event), C.c_void_p(stop_event)))
+
+
+PROBE_MFMA_I8, PROBE_VALU_MAD24 = 0, 1
+
+
+def wino_probe_peak(kind, blocks, iters, sink, stream=None):
+    """Launch one peak-probe kernel; returns the operations it performs."""
+    work = C.c_double()
+    _check(_load().wino_probe_peak(kind, blocks, iters, _ptr(sink), C.byref(work), _stream(stream)))
+    return work.value
 
 
 def wino_workspace_bytes(desc):

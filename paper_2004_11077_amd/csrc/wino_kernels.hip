@@ -205,6 +205,49 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   }
 }
 
+// ---------------------------------------------------------------------------
+// Peak probes (measurement helpers): register-only loops that show what this
+// device sustains on the two units the hot path is priced against.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_probe_mfma_i8(int iters, int* __restrict__ sink) {
+  const int lane = threadIdx.x;
+  v4i a = {lane, lane + 1, lane + 2, lane + 3}, b = {lane ^ 5, lane ^ 9, lane ^ 17, lane ^ 33};
+  v16i acc[4] = {};
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[k], 0, 0, 0);
+  }
+  int sum = 0;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum ^= acc[k][e];
+  if (sum == 0x7fffffff) sink[0] = sum;      // keeps the loop alive; practically never true
+}
+
+__global__ __launch_bounds__(256) void k_probe_valu_mad24(int iters, int c, int* __restrict__ sink) {
+  int acc[8];
+#pragma unroll
+  for (int k = 0; k < 8; ++k) acc[k] = threadIdx.x + k;
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int k = 0; k < 8; ++k)
+      asm volatile("v_mad_i32_i24 %0, %1, %2, %0" : "+v"(acc[k]) : "v"(acc[(k + 1) & 7]), "s"(c));
+  }
+  int sum = 0;
+#pragma unroll
+  for (int k = 0; k < 8; ++k) sum ^= acc[k];
+  if (sum == 0x7fffffff) sink[0] = sum;
+}
+
+hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t st) {
+  if (kind == 0)
+    wino_launch(k_probe_mfma_i8, dim3((unsigned)blocks), dim3(256), st, iters, sink);
+  else
+    wino_launch(k_probe_valu_mad24, dim3((unsigned)blocks), dim3(256), st, iters, 3, sink);
+  return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void k_absmax_i32(const int32_t* __restrict__ v, long count,
                                                     unsigned long long* __restrict__ amax) {
   unsigned int m = 0;

@@ -150,6 +150,10 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
                         void* y, int m_bits, int out_type, bool relu, const StageMults& in_mu,
                         const StageMults& out_mu, float m_mult, hipStream_t st);
 
+// Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
+// 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8).
+hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t st);
+
 // fp32 path: stage 0 weight (a = w), 1 input (a = x), 2 contraction (a = U, b = V),
 // 3 output (a = M); no casts, float tensors in the int8 path's layouts.
 hipError_t launch_stage_f32(int stage, const Geometry& g, bool legendre, const float* a,
