@@ -26,8 +26,11 @@ COMMON = ["-std=c++20", "-fPIC", "-fconstexpr-steps=200000000", "-Wall", "-Wno-u
 # -ffp-contract=off: the only fused multiply-adds are the ones written out (the
 # casts); the fp32 brackets of the flex kernels round every product and sum.
 # Packed fp32 VALU forms are disabled for the device pass.
+# -amdgpu-mfma-vgpr-form: MFMA accumulators live in ordinary vector registers, so the
+# epilogues read them directly instead of copying them out of the accumulation file.
 DEVICE = ["-O3", "--offload-arch=gfx950", "-ffp-contract=off",
-          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 # host-only translation units still see the HIP runtime API declarations

@@ -110,6 +110,8 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
     return fail(WINO_EINVAL, "negative dimension");
   if (d->C % 16 != 0 || d->K % 16 != 0)
     return fail(WINO_EINVAL, "C (%d) and K (%d) must be multiples of 16", d->C, d->K);
+  if (d->C > (1 << 20) || d->K > (1 << 20))   // kernels keep 128 rows of C or K in 32-bit offsets
+    return fail(WINO_EINVAL, "C and K must not exceed 2^20");
   const long TH = (d->H + d->m - 1) / d->m, TW = (d->W + d->m - 1) / d->m;
   const long T = (long)d->N * TH * TW;
   const long n2 = (long)(d->m + 2) * (d->m + 2);

@@ -16,15 +16,6 @@ ProfileEvents take_profile_events() {
   return p;
 }
 
-// One symmetric cast: q = clamp(rint(v * mult), +-qmax) with the exact product
-// rounded once, ties to even (fma onto 1.5 * 2^23, clamp of the biased float).
-__device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
-  constexpr float kMagic = 12582912.0f;
-  float t = __builtin_fmaf(v, mult, kMagic);
-  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
-  return __float_as_int(t) - 0x4B400000;
-}
-
 // ---------------------------------------------------------------------------
 // Contraction: per Winograd point p, M[p][t][k] = sum_c U[p][t][c] V[p][k][c],
 // a batch of n*n int8 GEMMs (the only dense contraction of the path, hence
@@ -46,6 +37,16 @@ __device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
 // one L2, and the number of groups is chosen to spread n*n points evenly.
 // ---------------------------------------------------------------------------
 constexpr int kTT = 128, kKT = 128;
+
+// One cast kept in its biased float form: the code sits, in two's complement,
+// in the low bits of the returned pattern (0x4B400000 + q), so packing needs
+// only the low byte (or half) of each value.
+__device__ __forceinline__ uint32_t cast_biased(float v, float mult, float qmax) {
+  constexpr float kMagic = 12582912.0f;
+  float t = __builtin_fmaf(v, mult, kMagic);
+  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
+  return __float_as_uint(t);
+}
 
 template <typename MT, int kCK>
 __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
@@ -79,48 +80,59 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   const int wt = wave & 1, wk = wave >> 1;
   const int r = lane & 31, h = lane >> 5;
 
-  // staging map: 8 lanes cover one 128-byte row chunk, 4 rows per 32 lanes
+  // Addresses are a block-uniform 64-bit base (scalar registers) plus a 32-bit
+  // lane offset (the host keeps 128 * C and 128 * K below 2^31).
+  const int8_t* Vp = V + ((long)p * K + k0) * C;
+  const int8_t* Up = U + ((long)p * T + t0) * C;
+  MT* Mp = Mo + ((long)p * T + t0) * K + k0;
+  const int krows = K - k0, trows = T - t0;      // rows of this block that exist (>= 1)
+
+  // staging map: LPR lanes cover one row chunk; rows past the edge are read
+  // from the last existing row (their products land in outputs never stored)
   const int srow = tid / LPR, sseg = (tid % LPR) * 16;
-  const int8_t* ga[NP];
-  const int8_t* gb[NP];
+  uint32_t oa[NP], ob[NP];
 #pragma unroll
   for (int i = 0; i < NP; ++i) {
     const int row = srow + i * RPP;
-    const int kr = min(k0 + row, K - 1), tr = min(t0 + row, T - 1);   // clamp, mask later
-    ga[i] = V + ((long)p * K + kr) * C + sseg;
-    gb[i] = U + ((long)p * T + tr) * C + sseg;
+    oa[i] = (uint32_t)min(row, krows - 1) * (uint32_t)C + sseg;
+    ob[i] = (uint32_t)min(row, trows - 1) * (uint32_t)C + sseg;
   }
   // one register set: the next chunk is in flight while this one feeds the MFMAs
   // (a second set costs a third of the occupancy and measured slower)
-  v4i ra0[NP], rb0[NP];
-  auto fetch = [&](v4i (&ra)[NP], v4i (&rb)[NP], int c0) {
-    // columns past C (last chunk when C is not a multiple of 128) are read
-    // from a clamped in-bounds column and zeroed, without branching
-    const bool ok = c0 + sseg < C;
-    const int cc = ok ? c0 : C - 16 - sseg;
-    const int keep = ok ? -1 : 0;
+  v4i ra[NP], rb[NP];
+  auto fetch = [&](int c0) {
+    if (c0 + kCK <= C) {               // uniform: the whole chunk lies inside C
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      ra[i] = *reinterpret_cast<const v4i*>(ga[i] + cc) & keep;
-      rb[i] = *reinterpret_cast<const v4i*>(gb[i] + cc) & keep;
+      for (int i = 0; i < NP; ++i) {
+        ra[i] = *reinterpret_cast<const v4i*>(Vp + c0 + oa[i]);
+        rb[i] = *reinterpret_cast<const v4i*>(Up + c0 + ob[i]);
+      }
+    } else {
+      // last chunk when C is not a multiple of the chunk: columns past C are
+      // read from a clamped in-bounds column and zeroed, without branching
+      const bool ok = c0 + sseg < C;
+      const int cc = ok ? c0 : C - 16 - sseg;
+      const int keep = ok ? -1 : 0;
+#pragma unroll
+      for (int i = 0; i < NP; ++i) {
+        ra[i] = *reinterpret_cast<const v4i*>(Vp + cc + oa[i]) & keep;
+        rb[i] = *reinterpret_cast<const v4i*>(Up + cc + ob[i]) & keep;
+      }
     }
   };
 
   v16i acc[2][2];
-#pragma unroll
-  for (int i = 0; i < 2; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = v16i{};
-
-  auto chunk = [&](v4i (&ra)[NP], v4i (&rb)[NP], int c0) {
-    if (c0) __syncthreads();             // previous chunk fully consumed
+  // FIRST: the accumulators start from the constant zero operand of the first
+  // MFMA instead of being cleared beforehand.
+  auto chunk = [&]<bool FIRST>(int c0) {
+    if constexpr (!FIRST) __syncthreads();   // previous chunk fully consumed
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
       *reinterpret_cast<v4i*>(sA + (srow + i * RPP) * kRow + sseg) = ra[i];
       *reinterpret_cast<v4i*>(sB + (srow + i * RPP) * kRow + sseg) = rb[i];
     }
     __syncthreads();
-    if (c0 + kCK < C) fetch(ra, rb, c0 + kCK);
+    if (c0 + kCK < C) fetch(c0 + kCK);
 #pragma unroll
     for (int ks = 0; ks < kCK / 32; ++ks) {
       v4i fa[2], fb[2];
@@ -132,13 +144,18 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < 2; ++j) {
+          if (FIRST && ks == 0)
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], v16i{}, 0, 0, 0);
+          else
+            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
     }
   };
 
-  fetch(ra0, rb0, 0);
-  for (int c0 = 0; c0 < C; c0 += kCK) chunk(ra0, rb0, c0);
+  fetch(0);
+  chunk.template operator()<true>(0);
+  for (int c0 = kCK; c0 < C; c0 += kCK) chunk.template operator()<false>(c0);
 
   // acc[i][j][4*g+v] = D[k = 32 i + 8 g + 4 h + v][t = 32 j + r] within the wave's 64 x 64
   if constexpr (sizeof(MT) == 1) {
@@ -151,24 +168,25 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
       for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          uint32_t pk = 0;
+          uint32_t q[4];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            const int q = cast_code((float)acc[i][j][4 * gq + v], mult, qmax);
-            pk |= ((uint32_t)q & 0xffu) << (8 * v);
-          }
+          for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)acc[i][j][4 * gq + v], mult, qmax);
+          // low bytes of q0..q3 -> one dword (v_perm_b32: selectors 0-3 take bytes of the
+          // second operand, 4-7 of the first, 0x0c gives zero)
+          const uint32_t lo = __builtin_amdgcn_perm(q[1], q[0], 0x0c0c0400u);
+          const uint32_t hi = __builtin_amdgcn_perm(q[3], q[2], 0x04000c0cu);
           const int tl = wt * 64 + j * 32 + r;
           const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
-          so[tl * kORow + (kl >> 2)] = pk;
+          so[tl * kORow + (kl >> 2)] = lo | hi;
         }
     __syncthreads();
     const int kq = tid & 31;             // dword within the 128-byte row
-    if (k0 + kq * 4 < K) {
+    if (kq * 4 < krows) {
 #pragma unroll
       for (int it = 0; it < kTT / 8; ++it) {
         const int tl = it * 8 + (tid >> 5);
-        if (t0 + tl < T)
-          *reinterpret_cast<uint32_t*>(Mo + ((long)p * T + t0 + tl) * K + k0 + kq * 4) =
+        if (tl < trows)
+          *reinterpret_cast<uint32_t*>(Mp + ((uint32_t)tl * (uint32_t)K + kq * 4)) =
               so[tl * kORow + kq];
       }
     }
@@ -177,28 +195,24 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
     for (int i = 0; i < 2; ++i)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        const int t = t0 + wt * 64 + j * 32 + r;
-        if (t >= T) continue;
-        MT* mrow = Mo + ((long)p * T + t) * K;
+        const int tl = wt * 64 + j * 32 + r;
+        if (tl >= trows) continue;
+        MT* mrow = Mp + (uint32_t)tl * (uint32_t)K;
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          const int kk = k0 + wk * 64 + i * 32 + 8 * gq + 4 * h;
-          if (kk >= K) continue;
-          int q[4];
-#pragma unroll
-          for (int v = 0; v < 4; ++v) {
-            if constexpr (sizeof(MT) == 4)
-              q[v] = acc[i][j][4 * gq + v];
-            else
-              q[v] = cast_code((float)acc[i][j][4 * gq + v], mult, qmax);
-          }
+          const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
+          if (kl >= krows) continue;
           if constexpr (sizeof(MT) == 2) {
-            uint2 pk;
-            pk.x = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
-            pk.y = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
-            *reinterpret_cast<uint2*>(mrow + kk) = pk;
+            uint32_t q[4];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)acc[i][j][4 * gq + v], mult, qmax);
+            uint2 pk;                    // low halves of q0, q1 and of q2, q3
+            pk.x = __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
+            pk.y = __builtin_amdgcn_perm(q[3], q[2], 0x05040100u);
+            *reinterpret_cast<uint2*>(mrow + kl) = pk;
           } else {
-            *reinterpret_cast<int4*>(mrow + kk) = make_int4(q[0], q[1], q[2], q[3]);
+            *reinterpret_cast<int4*>(mrow + kl) = make_int4(acc[i][j][4 * gq], acc[i][j][4 * gq + 1],
+                                                             acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
           }
         }
       }

@@ -154,3 +154,12 @@ def test_flex_calls_validate_matrices_and_options_before_any_launch():
     assert lib.wino_flex_weight_transform(C.byref(d), C.byref(good), None, fake, C.byref(s), None) == -1
     assert lib.wino_flex_output_transform(C.byref(d), C.byref(good), fake, fake,
                                           C.byref(wn.Scales.from_dict({"s_m1": -1.0})), None) == -1
+
+
+def test_probe_rejects_bad_arguments_before_any_launch():
+    lib = binding._load()
+    fake = C.c_void_p(4096)
+    assert lib.wino_probe_peak(7, 1, 1, fake, None, None) == -1
+    assert lib.wino_probe_peak(0, 0, 1, fake, None, None) == -1
+    assert lib.wino_probe_peak(1, 1, 1 << 30, fake, None, None) == -1
+    assert lib.wino_probe_peak(0, 1, 1, None, None, None) == -1

@@ -48,3 +48,13 @@ def test_captured_layer_replays_to_the_eager_result(fused):
                            out_type="i8", relu=True)
     # the scales were calibrated on the same multiset of images, so they are unchanged
     assert np.array_equal(y.cpu().numpy().astype(np.int64), ora2["y"])
+
+
+def test_peak_probes_run_and_report_their_work():
+    import torch
+    import paper_2004_11077_amd as wn
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    assert wn.wino_probe_peak(wn.PROBE_MFMA_I8, 8, 16, sink) == 8 * 4 * 16 * 4 * 2 * 32 ** 3
+    assert wn.wino_probe_peak(wn.PROBE_VALU_MAD24, 8, 16, sink) == 8 * 256 * 16 * 8
+    torch.cuda.synchronize()
+    assert int(sink.item()) == 0
