@@ -286,7 +286,11 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
 // path see only 16-byte accesses; the byte traffic stays inside LDS.
 // Out-of-image pixels are staged as zeros.
 // ---------------------------------------------------------------------------
-template <int M, bool LEG>
+// WHOLE: C is a multiple of 256, so the 256 items of a work group are 256
+// channels of ONE tile: the tile index and everything derived from it is
+// block-uniform (scalar registers, scalar arithmetic) and no item is out of
+// range.
+template <int M, bool LEG, bool WHOLE>
 __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t* __restrict__ U,
                                            const Geometry& g, const StageMults& mu,
                                            unsigned block) {
@@ -301,9 +305,15 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   // staging role of this lane: 16-byte unit `u` of the block's item range
   const int u = tid & 15, prow = tid >> 4;
   const long ug = gid0 + u * 16;
-  const bool uok = ug < total;
-  const int ut = uok ? (int)(ug / g.C) : 0;
-  const int uc = uok ? (int)(ug - (long)ut * g.C) : 0;
+  const bool uok = WHOLE || ug < total;
+  int ut, uc;
+  if constexpr (WHOLE) {
+    ut = (int)(gid0 / g.C);                       // uniform
+    uc = (int)(gid0 - (long)ut * g.C) + u * 16;
+  } else {
+    ut = uok ? (int)(ug / g.C) : 0;
+    uc = uok ? (int)(ug - (long)ut * g.C) : 0;
+  }
   const int tx = ut % g.TW;
   const int ty = (ut / g.TW) % g.TH;
   const int b = ut / (g.TW * g.TH);
@@ -315,8 +325,12 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
       const int a = pix / n, bb = pix - a * n;
       const int h = ty * M - 1 + a, ww = tx * M - 1 + bb;
       v4i v = {0, 0, 0, 0};
-      if (uok && h >= 0 && h < g.H && ww >= 0 && ww < g.W)
-        v = *reinterpret_cast<const v4i*>(xb + ((long)h * g.W + ww) * g.C);
+      if (uok && h >= 0 && h < g.H && ww >= 0 && ww < g.W) {
+        if constexpr (WHOLE)   // the launcher keeps H * W * C below 2^31 on this path
+          v = *reinterpret_cast<const v4i*>(xb + (uint32_t)((h * g.W + ww) * g.C));
+        else
+          v = *reinterpret_cast<const v4i*>(xb + ((long)h * g.W + ww) * g.C);
+      }
       *reinterpret_cast<v4i*>(s_in + pix * 256 + u * 16) = v;
     }
   }
@@ -366,18 +380,18 @@ __global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restri
   weight_body<M, LEG>(w, V, g, mu, blockIdx.x);
 }
 
-template <int M, bool LEG>
+template <int M, bool LEG, bool WHOLE>
 __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
                                                          int8_t* __restrict__ U, Geometry g,
                                                          StageMults mu) {
-  input_body<M, LEG>(x, U, g, mu, blockIdx.x);
+  input_body<M, LEG, WHOLE>(x, U, g, mu, blockIdx.x);
 }
 
 // Both operand transforms in one launch (they are independent): the first
 // `nb_in` work groups transform input tiles, the rest transform filters.  One
 // launch less per layer, and the small filter transform fills the tail of the
 // input transform instead of paying its own ramp-up and drain.
-template <int M, bool LEG>
+template <int M, bool LEG, bool WHOLE>
 __global__ __launch_bounds__(256) void k_operand_transforms(const int8_t* __restrict__ x,
                                                             int8_t* __restrict__ U,
                                                             const int8_t* __restrict__ w,
@@ -385,7 +399,7 @@ __global__ __launch_bounds__(256) void k_operand_transforms(const int8_t* __rest
                                                             StageMults mu_in, StageMults mu_w,
                                                             unsigned nb_in) {
   if (blockIdx.x < nb_in)
-    input_body<M, LEG>(x, U, g, mu_in, blockIdx.x);
+    input_body<M, LEG, WHOLE>(x, U, g, mu_in, blockIdx.x);
   else
     weight_body<M, LEG>(w, V, g, mu_w, blockIdx.x - nb_in);
 }
@@ -409,7 +423,9 @@ struct MTraits<int32_t> {
   static constexpr int64_t in_max = kMaxAccUnquantised;
 };
 
-template <int M, bool LEG, typename MT, int OUT>
+// WHOLE: K is a multiple of 256, so a work group's items are 256 output
+// channels of ONE tile and the tile arithmetic is block-uniform.
+template <int M, bool LEG, typename MT, int OUT, bool WHOLE>
 __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__ Mq,
                                                           void* __restrict__ yv, Geometry g,
                                                           StageMults mu, int relu) {
@@ -420,9 +436,15 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   const long gid0 = (long)blockIdx.x * 256;
   const long total = (long)g.T * g.K;
   const long gid = gid0 + tid;
-  const bool active = gid < total;
-  const int t = active ? (int)(gid / g.K) : 0;
-  const int k = active ? (int)(gid - (long)t * g.K) : 0;
+  const bool active = WHOLE || gid < total;
+  int t, k;
+  if constexpr (WHOLE) {
+    t = (int)(gid0 / g.K);                        // uniform
+    k = (int)(gid0 - (long)t * g.K) + tid;
+  } else {
+    t = active ? (int)(gid / g.K) : 0;
+    k = active ? (int)(gid - (long)t * g.K) : 0;
+  }
   const int tx = t % g.TW;
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
@@ -434,7 +456,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     __shared__ __attribute__((aligned(16))) int8_t s_in[n2 * 256];
     const int u = tid & 15, prow = tid >> 4;
     const long ug = gid0 + u * 16;
-    const bool uok = ug < total;
+    const bool uok = WHOLE || ug < total;
 #pragma unroll
     for (int it = 0; it < (n2 + 15) / 16; ++it) {
       const int p = it * 16 + prow;
@@ -475,7 +497,8 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
       return (float)v;
     }
   };
-  const long ybase = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K + k;
+  // block-uniform part (WHOLE) kept apart from the lane's channel
+  const long ytile = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K;
   const int wk = g.W * g.K;
   auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
     static_for<0, M>([&](auto i) {
@@ -487,13 +510,13 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
           const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
           if constexpr (OUT == 0) {
             float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * mu.outer.v[idx];
-            (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
+            (static_cast<float*>(yv) + ytile + rel)[k] = relu ? fmaxf(v, 0.f) : v;
           } else if constexpr (OUT == 1) {
             int v = (int)num[i][j];
-            (static_cast<int*>(yv) + ybase)[rel] = relu ? max(v, 0) : v;
+            (static_cast<int*>(yv) + ytile + rel)[k] = relu ? max(v, 0) : v;
           } else {
             int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), mu.outer.v[idx], 127.f);
-            (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
+            (static_cast<int8_t*>(yv) + ytile + rel)[k] = (int8_t)(relu ? max(v, 0) : v);
           }
         }
       });
@@ -519,6 +542,12 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
 // ---------------------------------------------------------------------------
 static inline unsigned blocks_for(long items) { return (unsigned)((items + 255) / 256); }
 
+// A work group's 256 items are the channels of one tile (and offsets inside one
+// image fit 32 bits): the kernels then keep the tile arithmetic in scalar registers.
+static inline bool whole_tiles(int channels, int H, int W) {
+  return channels % 256 == 0 && (long)H * W * channels < (1L << 31);
+}
+
 template <int M>
 hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
                            const StageMults& mu, hipStream_t st) {
@@ -534,10 +563,15 @@ template <int M>
 hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st) {
   const unsigned nb = blocks_for((long)g.T * g.C);
-  if (leg)
-    wino_launch((k_input_transform<M, true>), dim3(nb), dim3(256), st, x, U, g, mu);
+  const bool whole = whole_tiles(g.C, g.H, g.W);
+  if (leg && whole)
+    wino_launch((k_input_transform<M, true, true>), dim3(nb), dim3(256), st, x, U, g, mu);
+  else if (leg)
+    wino_launch((k_input_transform<M, true, false>), dim3(nb), dim3(256), st, x, U, g, mu);
+  else if (whole)
+    wino_launch((k_input_transform<M, false, true>), dim3(nb), dim3(256), st, x, U, g, mu);
   else
-    wino_launch((k_input_transform<M, false>), dim3(nb), dim3(256), st, x, U, g, mu);
+    wino_launch((k_input_transform<M, false, false>), dim3(nb), dim3(256), st, x, U, g, mu);
   return hipGetLastError();
 }
 
@@ -546,36 +580,50 @@ hipError_t PerM<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_
                              const int8_t* w, int8_t* V, const StageMults& mu_in,
                              const StageMults& mu_w, hipStream_t st) {
   const unsigned nb_in = blocks_for((long)g.T * g.C), nb_w = blocks_for((long)g.K * g.C);
-  if (leg)
-    wino_launch((k_operand_transforms<M, true>), dim3(nb_in + nb_w), dim3(256), st, x, U,
-                       w, V, g, mu_in, mu_w, nb_in);
+  const bool whole = whole_tiles(g.C, g.H, g.W);
+  const dim3 grid(nb_in + nb_w), bs(256);
+  if (leg && whole)
+    wino_launch((k_operand_transforms<M, true, true>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
+  else if (leg)
+    wino_launch((k_operand_transforms<M, true, false>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
+  else if (whole)
+    wino_launch((k_operand_transforms<M, false, true>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
   else
-    wino_launch((k_operand_transforms<M, false>), dim3(nb_in + nb_w), dim3(256), st, x,
-                       U, w, V, g, mu_in, mu_w, nb_in);
+    wino_launch((k_operand_transforms<M, false, false>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
   return hipGetLastError();
 }
 
-template <int M, bool LEG, typename MT>
-static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
-                            const StageMults& mu, hipStream_t st) {
+template <int M, bool LEG, typename MT, bool WHOLE>
+static hipError_t output_mtw(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
+                             const StageMults& mu, hipStream_t st) {
   const unsigned nb = blocks_for((long)g.T * g.K);
   const MT* mp = static_cast<const MT*>(Mq);
   const int r = relu ? 1 : 0;
   if (out_type == 0) {
-    wino_launch((k_output_transform<M, LEG, MT, 0>), dim3(nb), dim3(256), st, mp, y, g,
+    wino_launch((k_output_transform<M, LEG, MT, 0, WHOLE>), dim3(nb), dim3(256), st, mp, y, g,
                        mu, r);
   } else if (out_type == 1) {
     // integer numerators only make sense for a single integer bracket
     if constexpr (LEG)
       return hipErrorInvalidValue;
     else
-      wino_launch((k_output_transform<M, LEG, MT, 1>), dim3(nb), dim3(256), st, mp, y,
+      wino_launch((k_output_transform<M, LEG, MT, 1, WHOLE>), dim3(nb), dim3(256), st, mp, y,
                          g, mu, r);
   } else {
-    wino_launch((k_output_transform<M, LEG, MT, 2>), dim3(nb), dim3(256), st, mp, y, g,
+    wino_launch((k_output_transform<M, LEG, MT, 2, WHOLE>), dim3(nb), dim3(256), st, mp, y, g,
                        mu, r);
   }
   return hipGetLastError();
+}
+
+template <int M, bool LEG, typename MT>
+static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
+                            const StageMults& mu, hipStream_t st) {
+  // the fast path is built for the int8 M of the all-8-bit pipeline
+  if constexpr (sizeof(MT) == 1)
+    if (whole_tiles(g.K, g.H, g.W))
+      return output_mtw<M, LEG, MT, true>(g, Mq, y, out_type, relu, mu, st);
+  return output_mtw<M, LEG, MT, false>(g, Mq, y, out_type, relu, mu, st);
 }
 
 template <int M, bool LEG>
