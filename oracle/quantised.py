@@ -52,6 +52,7 @@ class LayerConfig:
     inner_quant: bool = True         # casts on the inner brackets of eq. 4
     out_type: str = "f32"            # "f32" | "i8" | "i32"
     relu: bool = False
+    per_point: bool = False          # one scale per Winograd point for U and for V
 
 
 SCALE_NAMES = ("s_x", "s_x1", "s_u", "s_w", "s_w1", "s_v", "s_m", "s_m1", "s_y")
@@ -119,11 +120,14 @@ def to_f32(num):
 
 
 def mult_table(rho_i, rho_j, s_prev, s_next):
-    """float32 multipliers of one cast; s_prev may be a double (product of scales)."""
+    """float32 multipliers of one cast; s_prev may be a double (product of scales);
+    s_next is one scale or an array [i, j] of per-point scales."""
     tab = np.zeros((len(rho_i), len(rho_j)), dtype=np.float32)
+    per_point = np.ndim(s_next) == 2
     for i, ri in enumerate(rho_i):
         for j, rj in enumerate(rho_j):
-            tab[i, j] = np.float32(float(s_prev) / (float(ri * rj) * float(s_next)))
+            sn = float(s_next[i][j]) if per_point else float(s_next)
+            tab[i, j] = np.float32(float(s_prev) / (float(ri * rj) * sn))
     return tab
 
 
@@ -145,6 +149,21 @@ def calibrate(num, rho_i, rho_j, s_prev, qmax, ij_axes):
     real = (num.astype(np.float64) * float(s_prev)) / rr     # object ints: float() is RNE
     amax = float(np.max(np.abs(real))) if real.size else 0.0
     return np.float32(amax / qmax) if amax > 0 else np.float32(1.0)
+
+
+def calibrate_points(num, rho_i, rho_j, s_prev, qmax, ij_axes):
+    """Per-point variant of calibrate: scale[i, j] = float32(max |real[.., i, j, ..]| / qmax)."""
+    out = np.ones((len(rho_i), len(rho_j)), dtype=np.float32)
+    for i, ri in enumerate(rho_i):
+        for j, rj in enumerate(rho_j):
+            sl = [slice(None)] * num.ndim
+            sl[ij_axes[0]], sl[ij_axes[1]] = i, j
+            part = num[tuple(sl)]
+            real = (part.astype(np.float64) * float(s_prev)) / float(ri * rj)
+            amax = float(np.max(np.abs(real))) if real.size else 0.0
+            if amax > 0:
+                out[i, j] = np.float32(amax / qmax)
+    return out
 
 
 class StageMatrices:
@@ -192,7 +211,8 @@ def weight_transform(wq, s_w, cfg, sm, scales, out):
     Nm, rho = sm.w_outer
     num = sandwich_filters(Nm, cur, _stage_dtype(Nm, qmax))
     if "s_v" not in scales:
-        scales["s_v"] = calibrate(num, rho, rho, s_cur, qmax, (2, 3))
+        cal = calibrate_points if cfg.per_point else calibrate
+        scales["s_v"] = cal(num, rho, rho, s_cur, qmax, (2, 3))
     Vkc = requant(num, mult_table(rho, rho, s_cur, scales["s_v"]), qmax, (2, 3))
     out["V"] = np.ascontiguousarray(Vkc.transpose(2, 3, 0, 1).reshape(n * n, K, C))
     return out["V"]
@@ -215,17 +235,26 @@ def input_transform(xq, s_x, cfg, sm, scales, out):
     Nm, rho = sm.in_outer
     num = sandwich_tiles(Nm, cur, _stage_dtype(Nm, qmax))
     if "s_u" not in scales:
-        scales["s_u"] = calibrate(num, rho, rho, s_cur, qmax, (1, 2))
+        cal = calibrate_points if cfg.per_point else calibrate
+        scales["s_u"] = cal(num, rho, rho, s_cur, qmax, (1, 2))
     Ut = requant(num, mult_table(rho, rho, s_cur, scales["s_u"]), qmax, (1, 2))
     out["U"] = np.ascontiguousarray(Ut.transpose(1, 2, 0, 3).reshape(n * n, T, C))
     return out["U"]
 
 
 def contraction(U, V, cfg, scales, out):
-    """M[p,t,k] = sum_c U[p,t,c] V[p,k,c] (int64), then the Hadamard-stage cast."""
+    """M[p,t,k] = sum_c U[p,t,c] V[p,k,c] (int64), then the Hadamard-stage cast.
+
+    With per-point operand scales the result of point p stands for
+    M * s_u[p] * s_v[p]; the cast brings all points to the one scale s_m."""
     M = np.matmul(U, V.transpose(0, 2, 1))
     out["M_acc"] = M
-    s_uv = float(scales["s_u"]) * float(scales["s_v"])
+    if cfg.per_point:
+        assert cfg.bits_hadamard != 32, "per-point scales need a cast of the contraction result"
+        s_uv = (np.asarray(scales["s_u"], dtype=np.float64) *
+                np.asarray(scales["s_v"], dtype=np.float64)).reshape(-1, 1, 1)     # [p,1,1]
+    else:
+        s_uv = float(scales["s_u"]) * float(scales["s_v"])
     if cfg.bits_hadamard == 32:
         out["M"] = M
         return M, s_uv
@@ -233,8 +262,9 @@ def contraction(U, V, cfg, scales, out):
     if "s_m" not in scales:
         amax = float(np.max(np.abs(M.astype(np.float64) * s_uv))) if M.size else 0.0
         scales["s_m"] = np.float32(amax / qmax) if amax > 0 else np.float32(1.0)
-    mult = np.float32(s_uv / float(scales["s_m"]))
-    prod = M.astype(np.float32).astype(np.float64) * np.float64(mult)   # exact product
+    mult = (s_uv / float(scales["s_m"])).astype(np.float32) if cfg.per_point \
+        else np.float32(s_uv / float(scales["s_m"]))
+    prod = M.astype(np.float32).astype(np.float64) * mult.astype(np.float64)   # exact product
     Mq = np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
     out["M"] = Mq
     return Mq, scales["s_m"]

@@ -94,6 +94,22 @@ def test_full_size_configurations(name):
              bits_hadamard=wl.bits_hadamard)
 
 
+@pytest.mark.parametrize("m,base,shape,bh,out_type,relu", [
+    (2, "canonical", (2, 5, 7, 256, 256), 8, "i8", True),
+    (4, "legendre", (1, 9, 6, 512, 256), 9, "f32", False),
+    (4, "canonical", (2, 6, 6, 256, 512), 8, "i32", True),
+    (6, "legendre", (1, 7, 7, 256, 512), 8, "i8", False),
+])
+def test_channel_counts_that_are_multiples_of_256(m, base, shape, bh, out_type, relu):
+    """Such layers take the transform kernels whose tile arithmetic is block-uniform;
+    ragged images, every output type, split and whole-layer calls."""
+    N, H, W, C, K = shape
+    xq, wq, s_x, s_w = small_layer(N, H, W, C, K, seed=90 + m)
+    for whole in (False, True):
+        run_case(xq, wq, s_x, s_w, whole=whole, m=m, base=base, bits_hadamard=bh,
+                 out_type=out_type, relu=relu)
+
+
 @pytest.mark.parametrize("m", [2, 4, 6])
 def test_operand_transforms_in_one_launch_equal_the_two_calls(m):
     import torch

@@ -259,3 +259,77 @@ def test_error_bounds_and_hadamard_bit_monotonicity(base):
         rms[bh] = np.sqrt(np.mean(err ** 2))
     assert rms[32] <= rms[9] <= rms[8]
     assert np.sqrt(np.mean((yq - yd) ** 2)) < rms[32]       # direct int8 is the more accurate one
+
+
+# ---- per-point operand scales (an option of dynamic quantisation, not in the paper) ------
+
+def test_per_point_scales_all_equal_reproduce_the_per_tensor_layer():
+    _, _, xq, wq, s_x, s_w = tiny_layer(2, 7, 6, 8, 8, seed=8)
+    for base in ("canonical", "legendre"):
+        ref, sc = q.run_layer(xq, wq, s_x, s_w, q.LayerConfig(m=4, base=base, out_type="i8"))
+        flat = dict(sc)
+        flat["s_u"] = np.full((6, 6), sc["s_u"], dtype=np.float32)
+        flat["s_v"] = np.full((6, 6), sc["s_v"], dtype=np.float32)
+        got, _ = q.run_layer(xq, wq, s_x, s_w,
+                             q.LayerConfig(m=4, base=base, out_type="i8", per_point=True), scales=flat)
+        for key in ("U", "V", "M", "y"):
+            assert np.array_equal(got[key], ref[key]), (base, key)
+
+
+def test_per_point_U_against_exact_rational_rounding():
+    """Each point's codes are the exactly rounded real values over that point's own scale."""
+    _, _, xq, wq, s_x, s_w = tiny_layer(1, 8, 8, 8, 8, seed=9)
+    cfg = q.LayerConfig(m=4, base="canonical", per_point=True)
+    out, sc = q.run_layer(xq, wq, s_x, s_w, cfg)
+    assert np.shape(sc["s_u"]) == (6, 6) and np.shape(sc["s_v"]) == (6, 6)
+    assert len(set(np.asarray(sc["s_u"]).ravel().tolist())) > 10      # really per point
+    BT = mx.Matrices(4, 3).BT
+    d = wg.extract_tiles(xq.astype(np.int64), 4, 3)                   # [T,6,6,C]
+    T, C = d.shape[0], d.shape[3]
+    U = out["U"].reshape(6, 6, T, C)
+    near = 0
+    for t in range(0, T, 2):
+        for c in range(0, C, 3):
+            X = [[Fraction(int(d[t, a, b, c])) for b in range(6)] for a in range(6)]
+            R = mx.matmul(mx.matmul(BT, X), mx.transpose(BT))
+            for i in range(6):
+                for j in range(6):
+                    exact = R[i][j] * Fraction(float(s_x)) / Fraction(float(sc["s_u"][i][j]))
+                    want = max(-127, min(127, exact_round_half_even(exact)))
+                    if want != int(U[i, j, t, c]):
+                        frac = exact - (exact.numerator // exact.denominator)
+                        assert abs(frac - Fraction(1, 2)) < Fraction(1, 1000)
+                        near += 1
+    assert near <= 3
+    # every point uses its full range
+    assert np.all(np.abs(out["U"]).reshape(36, -1).max(axis=1) == 127)
+
+
+@pytest.mark.parametrize("base", ["canonical", "legendre"])
+def test_per_point_layer_converges_and_is_at_least_as_accurate(base):
+    x, w = si.make_real(1, 8, 8, 8, 8, seed=1)
+    yd = direct.direct_conv(x, w)
+    rms = np.sqrt(np.mean(yd ** 2))
+    errs = []
+    for bits in (10, 14, 18):
+        xq, s_x = q.quantise_real(x, bits)
+        wq, s_w = q.quantise_real(w, bits)
+        cfg = q.LayerConfig(m=4, base=base, bits=bits, bits_hadamard=bits + 8, per_point=True)
+        out, _ = q.run_layer(xq, wq, s_x, s_w, cfg)
+        errs.append(float(np.sqrt(np.mean((out["y"] - yd) ** 2)) / rms))
+    assert errs[0] > 8 * errs[1] > 64 * errs[2], errs
+    # at 8 bits (9-bit Hadamard stage) per-point scales must not lose to per-tensor ones
+    xq, s_x = q.quantise_real(x, 8)
+    wq, s_w = q.quantise_real(w, 8)
+    e = {}
+    for pp in (False, True):
+        out, _ = q.run_layer(xq, wq, s_x, s_w,
+                             q.LayerConfig(m=4, base=base, bits_hadamard=9, per_point=pp))
+        e[pp] = float(np.sqrt(np.mean((out["y"] - yd) ** 2)) / rms)
+    assert e[True] < e[False], e
+
+
+def test_per_point_needs_a_cast_of_the_contraction_result():
+    _, _, xq, wq, s_x, s_w = tiny_layer(seed=3)
+    with pytest.raises(AssertionError):
+        q.run_layer(xq, wq, s_x, s_w, q.LayerConfig(m=4, bits_hadamard=32, per_point=True))
