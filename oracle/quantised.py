@@ -242,32 +242,65 @@ def input_transform(xq, s_x, cfg, sm, scales, out):
     return out["U"]
 
 
+MAX_M_SHIFT = 8
+
+
 def contraction(U, V, cfg, scales, out):
     """M[p,t,k] = sum_c U[p,t,c] V[p,k,c] (int64), then the Hadamard-stage cast.
 
-    With per-point operand scales the result of point p stands for
-    M * s_u[p] * s_v[p]; the cast brings all points to the one scale s_m."""
+    Per-point mode: U[p], V[p] carry their own scales, so the result of point p
+    stands for M * s_u[p] * s_v[p].  Its codes get the scale s_m / 2^shift[p]:
+    s_m covers the largest point, and a point whose values are smaller by a
+    factor 2^s keeps s more bits, s = shift[p] <= MAX_M_SHIFT being the largest
+    power of two that does not clip it.  Powers of two keep the next bracket in
+    exact integers: it is fed with codes << (smax - shift[p]) at the common
+    scale s_m / 2^smax, smax = max_p shift[p].
+    Returns (what the output bracket is fed with, the scale of those integers)."""
     M = np.matmul(U, V.transpose(0, 2, 1))
     out["M_acc"] = M
-    if cfg.per_point:
-        assert cfg.bits_hadamard != 32, "per-point scales need a cast of the contraction result"
-        s_uv = (np.asarray(scales["s_u"], dtype=np.float64) *
-                np.asarray(scales["s_v"], dtype=np.float64)).reshape(-1, 1, 1)     # [p,1,1]
-    else:
+    if not cfg.per_point:
         s_uv = float(scales["s_u"]) * float(scales["s_v"])
-    if cfg.bits_hadamard == 32:
-        out["M"] = M
-        return M, s_uv
+        if cfg.bits_hadamard == 32:
+            out["M"] = M
+            return M, s_uv
+        qmax = qmax_of(cfg.bits_hadamard)
+        if "s_m" not in scales:
+            amax = float(np.max(np.abs(M.astype(np.float64) * s_uv))) if M.size else 0.0
+            scales["s_m"] = np.float32(amax / qmax) if amax > 0 else np.float32(1.0)
+        mult = np.float32(s_uv / float(scales["s_m"]))
+        prod = M.astype(np.float32).astype(np.float64) * np.float64(mult)   # exact product
+        Mq = np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
+        out["M"] = Mq
+        return Mq, scales["s_m"]
+
+    assert cfg.bits_hadamard != 32, "per-point scales need a cast of the contraction result"
     qmax = qmax_of(cfg.bits_hadamard)
-    if "s_m" not in scales:
-        amax = float(np.max(np.abs(M.astype(np.float64) * s_uv))) if M.size else 0.0
-        scales["s_m"] = np.float32(amax / qmax) if amax > 0 else np.float32(1.0)
-    mult = (s_uv / float(scales["s_m"])).astype(np.float32) if cfg.per_point \
-        else np.float32(s_uv / float(scales["s_m"]))
-    prod = M.astype(np.float32).astype(np.float64) * mult.astype(np.float64)   # exact product
-    Mq = np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
+    n2 = M.shape[0]
+    s_uv = (np.asarray(scales["s_u"], dtype=np.float64) *
+            np.asarray(scales["s_v"], dtype=np.float64)).reshape(n2)
+    if "s_m" not in scales or "m_shift" not in scales:
+        ideal = np.zeros(n2)                       # scale that just covers point p
+        for p in range(n2):
+            amax = float(np.max(np.abs(M[p]))) if M[p].size else 0.0
+            ideal[p] = amax * s_uv[p] / qmax
+        top = float(ideal.max()) if n2 else 0.0
+        scales["s_m"] = np.float32(top) if top > 0 else np.float32(1.0)
+        shift = np.zeros(n2, dtype=np.int64)
+        for p in range(n2):
+            while shift[p] < MAX_M_SHIFT and ideal[p] * 2.0 ** (shift[p] + 1) <= float(scales["s_m"]):
+                shift[p] += 1
+        scales["m_shift"] = shift
+    shift = np.asarray(scales["m_shift"], dtype=np.int64)
+    assert shift.min() >= 0 and shift.max() <= MAX_M_SHIFT
+    Mq = np.empty_like(M)
+    for p in range(n2):
+        mult = np.float32(s_uv[p] * 2.0 ** int(shift[p]) / float(scales["s_m"]))
+        prod = M[p].astype(np.float32).astype(np.float64) * np.float64(mult)
+        Mq[p] = np.clip(np.rint(prod), -qmax, qmax).astype(np.int64)
     out["M"] = Mq
-    return Mq, scales["s_m"]
+    smax = int(shift.max()) if n2 else 0
+    fed = Mq * (2 ** (smax - shift)).reshape(n2, 1, 1)
+    return fed, float(scales["s_m"]) / 2.0 ** smax
 
 
 def output_transform(Mq, s_m, shape, cfg, sm, scales, out):
@@ -277,6 +310,9 @@ def output_transform(Mq, s_m, shape, cfg, sm, scales, out):
     T, K = Mq.shape[1], Mq.shape[2]
     qmax = qmax_of(cfg.bits)
     in_max = qmax_of(cfg.bits_hadamard) if cfg.bits_hadamard != 32 else (1 << 24)
+    if cfg.per_point:
+        in_max <<= MAX_M_SHIFT                                   # codes arrive shifted left
+        assert cfg.out_type != "i32"
     cur = Mq.reshape(n, n, T, K).transpose(2, 0, 1, 3)          # [T,n,n,K]
     s_cur = s_m
     if sm.out_inner is not None:

@@ -270,6 +270,7 @@ def test_per_point_scales_all_equal_reproduce_the_per_tensor_layer():
         flat = dict(sc)
         flat["s_u"] = np.full((6, 6), sc["s_u"], dtype=np.float32)
         flat["s_v"] = np.full((6, 6), sc["s_v"], dtype=np.float32)
+        flat["m_shift"] = np.zeros(36, dtype=np.int64)
         got, _ = q.run_layer(xq, wq, s_x, s_w,
                              q.LayerConfig(m=4, base=base, out_type="i8", per_point=True), scales=flat)
         for key in ("U", "V", "M", "y"):
@@ -327,6 +328,35 @@ def test_per_point_layer_converges_and_is_at_least_as_accurate(base):
                              q.LayerConfig(m=4, base=base, bits_hadamard=9, per_point=pp))
         e[pp] = float(np.sqrt(np.mean((out["y"] - yd) ** 2)) / rms)
     assert e[True] < e[False], e
+    if base == "canonical":
+        assert e[True] < e[False] / 8, e          # the point of it: an order of magnitude
+
+
+def test_per_point_M_shifts_are_the_largest_that_do_not_clip():
+    _, _, xq, wq, s_x, s_w = tiny_layer(2, 8, 8, 16, 16, seed=12)
+    cfg = q.LayerConfig(m=4, base="canonical", per_point=True)
+    out, sc = q.run_layer(xq, wq, s_x, s_w, cfg)
+    shift = np.asarray(sc["m_shift"])
+    assert shift.shape == (36,) and shift.min() == 0 and 0 < shift.max() <= 8
+    s_uv = (np.asarray(sc["s_u"], dtype=np.float64) * np.asarray(sc["s_v"], dtype=np.float64)).reshape(36)
+    for p in range(36):
+        real = np.abs(out["M_acc"][p]).max() * s_uv[p]             # largest real value of point p
+        step = float(sc["s_m"]) / 2.0 ** shift[p]
+        assert real <= 127 * step * (1 + 1e-6)                      # not clipped
+        if shift[p] < 8:
+            assert real > 127 * step / 2 * (1 - 1e-6)               # one more bit would clip
+        # stored codes are the real values over the point's own step, exactly rounded
+        # except at near-ties
+        want = np.clip(np.rint(out["M_acc"][p] * s_uv[p] / step), -127, 127)
+        d = np.abs(want - out["M"][p])
+        assert d.max() <= 1 and np.mean(d != 0) < 0.01
+    # reconstruction: what the output bracket receives, times its scale, is M within half a step
+    smax = shift.max()
+    fed = out["M"] * (2 ** (smax - shift)).reshape(36, 1, 1)
+    real_all = out["M_acc"] * s_uv.reshape(36, 1, 1)
+    err = np.abs(fed * (float(sc["s_m"]) / 2.0 ** smax) - real_all)
+    half = (float(sc["s_m"]) / 2.0 ** shift / 2).reshape(36, 1, 1)
+    assert np.all(err <= half * (1 + 1e-5))
 
 
 def test_per_point_needs_a_cast_of_the_contraction_result():
