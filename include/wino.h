@@ -111,11 +111,30 @@ typedef struct {
                                  one (C <= 64 and K <= 64), else OFF               */
 } wino_conv_desc_t;
 
-/* Per-tensor symmetric scales, supplied by the caller.  s_x1, s_w1, s_m1 are
- * the inner brackets of eq. 4 and are ignored for the canonical base or
- * inner_quant = 0; s_m is ignored for bits_hadamard = 32; s_y only for I8. */
+/* Symmetric scales, supplied by the caller (or chosen by wino_calibrate).
+ * s_x1, s_w1, s_m1 belong to the inner brackets of eq. 4 and are ignored for
+ * the canonical base or inner_quant = 0; s_m is ignored for bits_hadamard = 32;
+ * s_y only matters for I8 output.
+ *
+ * per_point = 0: one scale per tensor (the paper's setting).
+ * per_point = 1 (an option of this library, not in the paper): the three
+ * Winograd-domain tensors around the Hadamard stage get one scale per point
+ * p = i*n + j, because their value ranges differ by orders of magnitude from
+ * point to point:  U[p] has scale s_u_pt[p], V[p] has scale s_v_pt[p] (s_u, s_v
+ * are then ignored), and M[p] has scale s_m / 2^m_shift[p] with
+ * 0 <= m_shift[p] <= WINO_MAX_M_SHIFT.  The powers of two keep the output
+ * bracket in exact integers: it is fed with code << (smax - m_shift[p]) at the
+ * common scale s_m / 2^smax, smax = max_p m_shift[p].  Needs bits_hadamard 8 or
+ * 9 and F32 or I8 output; not available in the fused variant (AUTO then runs
+ * one kernel per stage) or the flex calls.  Only the first n*n entries of the
+ * arrays are read. */
+enum { WINO_MAX_M_SHIFT = 8 };
 typedef struct {
   float s_x, s_x1, s_u, s_w, s_w1, s_v, s_m, s_m1, s_y;
+  int per_point;
+  float s_u_pt[64];
+  float s_v_pt[64];
+  int m_shift[64];
 } wino_scales_t;
 
 /* Bytes of device workspace wino_conv2d needs for this descriptor (V unless
@@ -153,10 +172,13 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
 int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
                           const wino_scales_t* s, void* hip_stream);
 
-/* Chooses the per-tensor scales of a layer on the device, from the tensors it
- * is given (dynamic quantisation; Section 4.2 casts every stage, the paper
- * leaves the choice of scales to the training framework).  On entry s->s_x and
- * s->s_w hold the scales of x and w; on return every other field holds
+/* Chooses the scales of a layer on the device, from the tensors it is given
+ * (dynamic quantisation; Section 4.2 casts every stage, the paper leaves the
+ * choice of scales to the training framework).  On entry s->s_x and s->s_w hold
+ * the scales of x and w and s->per_point selects the mode; with per_point = 1
+ * the per-point arrays are filled as well: s_u_pt[p], s_v_pt[p] from the
+ * maxima of point p alone, s_m from the largest point and m_shift[p] = the
+ * largest shift <= WINO_MAX_M_SHIFT that does not clip point p.  On return every other field holds
  * scale = float(max |real value of that stage| / qmax), computed stage after
  * stage on the codes the previous stages produce with the scales just chosen
  * (qmax = 127, or 255 for a 9-bit Hadamard stage; 1.0 for an all-zero tensor;

@@ -50,15 +50,42 @@ class ConvDesc(C.Structure):
 
 class Scales(C.Structure):
     """Mirror of wino_scales_t."""
-    _fields_ = [(n, C.c_float) for n in (
-        "s_x", "s_x1", "s_u", "s_w", "s_w1", "s_v", "s_m", "s_m1", "s_y")]
+    SCALARS = ("s_x", "s_x1", "s_u", "s_w", "s_w1", "s_v", "s_m", "s_m1", "s_y")
+    _fields_ = ([(n, C.c_float) for n in SCALARS] +
+                [("per_point", C.c_int), ("s_u_pt", C.c_float * 64), ("s_v_pt", C.c_float * 64),
+                 ("m_shift", C.c_int * 64)])
 
     @classmethod
     def from_dict(cls, d):
+        """Scalars by name; a sequence for "s_u" / "s_v" (with "m_shift") selects the
+        per-point mode, as does "per_point": True on its own (for calibration)."""
         s = cls()
-        for name, _ in cls._fields_:
-            setattr(s, name, float(d.get(name, 1.0)))
+        s.per_point = int(bool(d.get("per_point", False)))
+        for name in cls.SCALARS:
+            v = d.get(name, 1.0)
+            if name in ("s_u", "s_v") and hasattr(v, "__len__"):
+                s.per_point = 1
+                flat = [float(e) for row in v for e in (row if hasattr(row, "__len__") else [row])]
+                arr = getattr(s, name + "_pt")
+                for i in range(64):
+                    arr[i] = flat[i] if i < len(flat) else 1.0
+                v = 1.0
+            setattr(s, name, float(v))
+        if not hasattr(d.get("s_u", 1.0), "__len__"):
+            for i in range(64):
+                s.s_u_pt[i] = s.s_v_pt[i] = 1.0
+        for i, v in enumerate(list(d.get("m_shift", []))[:64]):
+            s.m_shift[i] = int(v)
         return s
+
+    def to_dict(self, n):
+        """Back to the oracle's naming; n = m + r - 1 gives the shape of per-point arrays."""
+        out = {name: getattr(self, name) for name in self.SCALARS}
+        if self.per_point:
+            out["s_u"] = [[self.s_u_pt[i * n + j] for j in range(n)] for i in range(n)]
+            out["s_v"] = [[self.s_v_pt[i * n + j] for j in range(n)] for i in range(n)]
+            out["m_shift"] = [self.m_shift[i] for i in range(n * n)]
+        return out
 
 
 class FlexMatrices(C.Structure):
@@ -204,10 +231,10 @@ def wino_calibrate_workspace_bytes(desc):
     return out.value
 
 
-def wino_calibrate(desc, x, w, y, s_x, s_w, workspace, stream=None):
+def wino_calibrate(desc, x, w, y, s_x, s_w, workspace, stream=None, per_point=False):
     """Device-side choice of every scale of a layer; returns a Scales struct.
     Runs the layer as a side effect (y may be None)."""
-    sc = Scales.from_dict({"s_x": s_x, "s_w": s_w})
+    sc = Scales.from_dict({"s_x": s_x, "s_w": s_w, "per_point": per_point})
     _check(_load().wino_calibrate(C.byref(desc), _ptr(x), _ptr(w), _ptr(y), C.byref(sc),
                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
                                   _stream(stream)))

@@ -71,16 +71,29 @@ bool stages_for(int m, Stages* s) {
 }
 
 // mult_ij = float( s_prev / ( (rho_i rho_j) * s_next ) ), evaluated in double.
-void fill_mults(MultTable* t, const IMat& im, double s_prev, double s_next) {
+// s_next_pt != nullptr: one target scale per entry (per-point scales) instead of s_next.
+void fill_mults(MultTable* t, const IMat& im, double s_prev, double s_next,
+                const float* s_next_pt = nullptr) {
   std::memset(t, 0, sizeof *t);
   for (int i = 0; i < im.rows; ++i)
     for (int j = 0; j < im.rows; ++j) {
       const double rr = (double)(im.rho[i] * im.rho[j]);
-      t->v[i * im.rows + j] = (float)(s_prev / (rr * s_next));
+      const double sn = s_next_pt ? (double)s_next_pt[i * im.rows + j] : s_next;
+      t->v[i * im.rows + j] = (float)(s_prev / (rr * sn));
     }
 }
 
+bool good_scales(const float* s, int count) {
+  for (int i = 0; i < count; ++i)
+    if (!(std::isfinite(s[i]) && s[i] > 0.f)) return false;
+  return true;
+}
+
 bool good_scale(float s) { return std::isfinite(s) && s > 0.f; }
+
+// Per-point scales (wino_scales_t.per_point) are an option of the int8 path
+// with a cast Hadamard stage and fp32 or int8 output.
+int check_per_point(const wino_conv_desc_t* d, const wino_scales_t* s);
 
 struct Plan {
   Geometry g;
@@ -149,49 +162,91 @@ size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 size_t m_elem_bytes(int bits) { return bits == 8 ? 1 : bits == 9 ? 2 : 4; }
 
+int check_per_point(const wino_conv_desc_t* d, const wino_scales_t* s) {
+  if (!s || !s->per_point) return WINO_OK;
+  if (s->per_point != 1) return fail(WINO_EINVAL, "per_point must be 0 or 1");
+  if (d->bits_in != 8 || (d->bits_hadamard != 8 && d->bits_hadamard != 9))
+    return fail(WINO_EUNSUPPORTED, "per-point scales need the int8 path with bits_hadamard 8 or 9");
+  if (d->out_type == WINO_OUT_I32)
+    return fail(WINO_EUNSUPPORTED, "per-point scales have fp32 or int8 output");
+  return WINO_OK;
+}
+
 int weight_mults(const Plan& p, const wino_scales_t* s, StageMults* mu) {
-  if (!good_scale(s->s_w) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_w / s_v");
+  const int n2 = (p.g.m + 2) * (p.g.m + 2);
+  const bool pp = s->per_point != 0;
+  if (!good_scale(s->s_w) || !(pp ? good_scales(s->s_v_pt, n2) : good_scale(s->s_v)))
+    return fail(WINO_EINVAL, "bad s_w / s_v");
+  const float* vpt = pp ? s->s_v_pt : nullptr;
   if (p.two_brackets) {
     if (!good_scale(s->s_w1)) return fail(WINO_EINVAL, "bad s_w1");
     fill_mults(&mu->inner, *p.st.GP, s->s_w, s->s_w1);
-    fill_mults(&mu->outer, *p.st.Pinv, s->s_w1, s->s_v);
+    fill_mults(&mu->outer, *p.st.Pinv, s->s_w1, s->s_v, vpt);
   } else {
-    fill_mults(&mu->outer, *p.st.G, s->s_w, s->s_v);
+    fill_mults(&mu->outer, *p.st.G, s->s_w, s->s_v, vpt);
   }
   return WINO_OK;
 }
 
 int input_mults(const Plan& p, const wino_scales_t* s, StageMults* mu) {
-  if (!good_scale(s->s_x) || !good_scale(s->s_u)) return fail(WINO_EINVAL, "bad s_x / s_u");
+  const int n2 = (p.g.m + 2) * (p.g.m + 2);
+  const bool pp = s->per_point != 0;
+  if (!good_scale(s->s_x) || !(pp ? good_scales(s->s_u_pt, n2) : good_scale(s->s_u)))
+    return fail(WINO_EINVAL, "bad s_x / s_u");
+  const float* upt = pp ? s->s_u_pt : nullptr;
   if (p.two_brackets) {
     if (!good_scale(s->s_x1)) return fail(WINO_EINVAL, "bad s_x1");
     fill_mults(&mu->inner, *p.st.PinvT, s->s_x, s->s_x1);
-    fill_mults(&mu->outer, *p.st.BPT, s->s_x1, s->s_u);
+    fill_mults(&mu->outer, *p.st.BPT, s->s_x1, s->s_u, upt);
   } else {
-    fill_mults(&mu->outer, *p.st.BT, s->s_x, s->s_u);
+    fill_mults(&mu->outer, *p.st.BT, s->s_x, s->s_u, upt);
   }
   return WINO_OK;
 }
 
-int contract_mult(const Plan& p, const wino_scales_t* s, float* mult, double* s_m_eff) {
-  if (!good_scale(s->s_u) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_u / s_v");
-  const double s_uv = (double)s->s_u * (double)s->s_v;
-  if (p.m_bits == 32) {
-    *mult = 1.f;
-    *s_m_eff = s_uv;
-  } else {
-    if (!good_scale(s->s_m)) return fail(WINO_EINVAL, "bad s_m");
-    *mult = (float)(s_uv / (double)s->s_m);
-    *s_m_eff = (double)s->s_m;
+// Cast multipliers of the contraction, one per point, the left shifts that
+// bring the codes of M to one scale (per-point mode; null = not wanted) and
+// that scale: what one unit fed to the output bracket stands for.
+int contract_mults(const Plan& p, const wino_scales_t* s, MultTable* mult, ShiftTable* sh,
+                   double* s_fed) {
+  const int n2 = (p.g.m + 2) * (p.g.m + 2);
+  std::memset(mult, 0, sizeof *mult);
+  if (sh) std::memset(sh, 0, sizeof *sh);
+  if (!s->per_point) {
+    if (!good_scale(s->s_u) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_u / s_v");
+    const double s_uv = (double)s->s_u * (double)s->s_v;
+    float m = 1.f;
+    *s_fed = s_uv;
+    if (p.m_bits != 32) {
+      if (!good_scale(s->s_m)) return fail(WINO_EINVAL, "bad s_m");
+      m = (float)(s_uv / (double)s->s_m);
+      *s_fed = (double)s->s_m;
+    }
+    for (int q = 0; q < n2; ++q) mult->v[q] = m;
+    return WINO_OK;
   }
+  if (!good_scales(s->s_u_pt, n2) || !good_scales(s->s_v_pt, n2) || !good_scale(s->s_m))
+    return fail(WINO_EINVAL, "bad per-point s_u / s_v or s_m");
+  int smax = 0;
+  for (int q = 0; q < n2; ++q) {
+    if (s->m_shift[q] < 0 || s->m_shift[q] > kMaxMShift)
+      return fail(WINO_EINVAL, "m_shift[%d] = %d outside 0..%d", q, s->m_shift[q], kMaxMShift);
+    if (s->m_shift[q] > smax) smax = s->m_shift[q];
+  }
+  for (int q = 0; q < n2; ++q) {
+    const double s_uv = (double)s->s_u_pt[q] * (double)s->s_v_pt[q];
+    mult->v[q] = (float)(s_uv * std::ldexp(1.0, s->m_shift[q]) / (double)s->s_m);
+    if (sh) sh->v[q] = smax - s->m_shift[q];
+  }
+  *s_fed = std::ldexp((double)s->s_m, -smax);
   return WINO_OK;
 }
 
 int output_mults(const Plan& p, const wino_conv_desc_t* d, const wino_scales_t* s,
-                 StageMults* mu) {
-  float dummy;
+                 StageMults* mu, ShiftTable* sh) {
+  MultTable dummy;
   double s_m;
-  if (int rc = contract_mult(p, s, &dummy, &s_m)) return rc;
+  if (int rc = contract_mults(p, s, &dummy, sh, &s_m)) return rc;
   double s_next = 1.0;   // fp32 output: the table holds dequantisation factors
   if (d->out_type == WINO_OUT_I8) {
     if (!good_scale(s->s_y)) return fail(WINO_EINVAL, "bad s_y");
@@ -320,6 +375,7 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
     return e == hipSuccess ? WINO_OK : fail_hip(e, "fp32 weight launch");
   }
   if (int rc = need(s, "scales")) return rc;
+  if (int rc = check_per_point(d, s)) return rc;
   StageMults mu;
   if (int rc = weight_mults(p, s, &mu)) return rc;
   hipError_t e = launch_weight_transform(p.g, p.two_brackets, (const int8_t*)w, (int8_t*)V, mu,
@@ -342,6 +398,7 @@ int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(x, 16, "x")) return rc;
   if (int rc = aligned(U, 16, "U")) return rc;
+  if (int rc = check_per_point(d, s)) return rc;
   StageMults mu;
   if (int rc = input_mults(p, s, &mu)) return rc;
   hipError_t e = launch_input_transform(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U, mu,
@@ -365,6 +422,7 @@ int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, c
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(x, 16, "x")) return rc;
   if (int rc = aligned(U, 16, "U")) return rc;
+  if (int rc = check_per_point(d, s)) return rc;
   StageMults mu_in, mu_w;
   if (int rc = input_mults(p, s, &mu_in)) return rc;
   if (int rc = weight_mults(p, s, &mu_w)) return rc;
@@ -391,9 +449,10 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
   if (int rc = aligned(U, 16, "U")) return rc;
   if (int rc = aligned(V, 16, "V")) return rc;
   if (int rc = aligned(M, 16, "M")) return rc;
-  float mult;
+  if (int rc = check_per_point(d, s)) return rc;
+  MultTable mult;
   double s_m;
-  if (int rc = contract_mult(p, s, &mult, &s_m)) return rc;
+  if (int rc = contract_mults(p, s, &mult, nullptr, &s_m)) return rc;
   hipError_t e = launch_contract(p.g, (const int8_t*)U, (const int8_t*)V, M, p.m_bits, mult,
                                  (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "contraction launch");
@@ -414,10 +473,13 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(M, 16, "M")) return rc;
   if (int rc = aligned(y, 16, "y")) return rc;
+  if (int rc = check_per_point(d, s)) return rc;
   StageMults mu;
-  if (int rc = output_mults(p, d, s, &mu)) return rc;
+  ShiftTable sh;
+  if (int rc = output_mults(p, d, s, &mu, &sh)) return rc;
   hipError_t e = launch_output_transform(p.g, p.two_brackets, M, p.m_bits, y, d->out_type,
-                                         d->relu != 0, mu, (hipStream_t)hip_stream);
+                                         d->relu != 0, mu, s->per_point ? &sh : nullptr,
+                                         (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "output transform launch");
 }
 
@@ -432,6 +494,17 @@ float scale_from(const unsigned long long* amax, const IMat& im, double s_prev, 
       if (real > best) best = real;
     }
   return best > 0.0 ? (float)(best / qmax) : 1.0f;
+}
+
+// Per-point variant: out[ij] = float( amax_ij * s_prev / (rho_i rho_j) / qmax ), 1 where zero.
+void scales_from_pt(const unsigned long long* amax, const IMat& im, double s_prev, double qmax,
+                    float* out) {
+  for (int i = 0; i < im.rows; ++i)
+    for (int j = 0; j < im.rows; ++j) {
+      const int q = i * im.rows + j;
+      const double real = ((double)amax[q] * s_prev) / (double)(im.rho[i] * im.rho[j]);
+      out[q] = real > 0.0 ? (float)(real / qmax) : 1.0f;
+    }
 }
 
 struct CalCtx {
@@ -453,34 +526,58 @@ int cal_read(CalCtx& c) {
 
 // One bracket: zero the maxima, run the calibration kernel, read them back.
 int cal_bracket(CalCtx& c, int stage, const Plan& p, int phase, const void* in, int m_bits,
-                const StageMults& mu, bool relu) {
+                const StageMults& mu, bool relu, const ShiftTable* sh = nullptr) {
   if (int rc = cal_reset(c)) return rc;
   hipError_t e = launch_calibrate_stage(stage, p.g, p.two_brackets, phase, in, m_bits, c.d_amax,
-                                        mu, relu, c.st);
+                                        mu, relu, sh, c.st);
   if (e != hipSuccess) return fail_hip(e, "calibration launch");
   return cal_read(c);
 }
 
-// s_m from the exact int32 contraction result (U, V already in the workspace);
-// leaves M computed with the chosen scale and reports the scale of its codes.
+// s_m (and, per point, m_shift) from the exact int32 contraction result (U, V
+// already in the workspace); leaves M computed with the chosen scales and
+// reports what one unit fed to the output bracket stands for, and the shifts.
 int calibrate_contraction(CalCtx& c, const wino_conv_desc_t* d, const wino_conv_desc_t& dd,
                           const Plan& p, const void* U, const void* V, void* M, void* M32,
-                          wino_scales_t* s, double* s_m_eff) {
-  const double s_uv = (double)s->s_u * (double)s->s_v;
-  *s_m_eff = s_uv;
-  if (p.m_bits == 32) return wino_contract(&dd, U, V, M, s, c.st);
-  wino_conv_desc_t d32 = dd;
-  d32.bits_hadamard = 32;
-  if (int rc = wino_contract(&d32, U, V, M32, s, c.st)) return rc;
+                          wino_scales_t* s, double* s_fed, ShiftTable* sh) {
+  const int n2 = (d->m + 2) * (d->m + 2);
+  std::memset(sh, 0, sizeof *sh);
+  MultTable unused;
+  std::memset(&unused, 0, sizeof unused);
+  if (p.m_bits == 32) {
+    *s_fed = (double)s->s_u * (double)s->s_v;
+    return wino_contract(&dd, U, V, M, s, c.st);
+  }
+  hipError_t e = launch_contract(p.g, (const int8_t*)U, (const int8_t*)V, M32, 32, unused, c.st);
+  if (e != hipSuccess) return fail_hip(e, "contraction launch");
   if (int rc = cal_reset(c)) return rc;
-  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
-  hipError_t e = launch_absmax_i32((const int32_t*)M32, (long)(n2 * p.g.T * d->K), c.d_amax, c.st);
+  const long per_point_count = (long)p.g.T * d->K;
+  e = s->per_point ? launch_absmax_i32((const int32_t*)M32, per_point_count, n2, c.d_amax, c.st)
+                   : launch_absmax_i32((const int32_t*)M32, per_point_count * n2, 1, c.d_amax, c.st);
   if (e != hipSuccess) return fail_hip(e, "absmax launch");
   if (int rc = cal_read(c)) return rc;
-  const double real = (double)c.h_amax[0] * s_uv;
   const double qm = p.m_bits == 8 ? 127.0 : 255.0;
-  s->s_m = real > 0.0 ? (float)(real / qm) : 1.0f;
-  *s_m_eff = (double)s->s_m;
+  if (!s->per_point) {
+    const double real = (double)c.h_amax[0] * ((double)s->s_u * (double)s->s_v);
+    s->s_m = real > 0.0 ? (float)(real / qm) : 1.0f;
+    *s_fed = (double)s->s_m;
+  } else {
+    double ideal[kMaxPts], top = 0.0;     // the scale that just covers point q
+    for (int q = 0; q < n2; ++q) {
+      ideal[q] = (double)c.h_amax[q] * ((double)s->s_u_pt[q] * (double)s->s_v_pt[q]) / qm;
+      if (ideal[q] > top) top = ideal[q];
+    }
+    s->s_m = top > 0.0 ? (float)top : 1.0f;
+    int smax = 0;
+    for (int q = 0; q < n2; ++q) {
+      int sft = 0;   // largest shift that does not clip the point
+      while (sft < kMaxMShift && ideal[q] * std::ldexp(1.0, sft + 1) <= (double)s->s_m) ++sft;
+      s->m_shift[q] = sft;
+      if (sft > smax) smax = sft;
+    }
+    for (int q = 0; q < n2; ++q) sh->v[q] = smax - s->m_shift[q];
+    *s_fed = std::ldexp((double)s->s_m, -smax);
+  }
   return wino_contract(&dd, U, V, M, s, c.st);
 }
 
@@ -522,7 +619,13 @@ int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void
   const size_t want = calibrate_layout(d, p, &oV, &oU, &oM, &oM32, &oA);
   if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
   if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  if (int rc = check_per_point(d, s)) return rc;
+  const bool pp = s->per_point != 0;
   s->s_x1 = s->s_u = s->s_w1 = s->s_v = s->s_m = s->s_m1 = s->s_y = 1.0f;
+  for (int q = 0; q < kMaxPts; ++q) {
+    s->s_u_pt[q] = s->s_v_pt[q] = 1.0f;
+    s->m_shift[q] = 0;
+  }
   if (p.g.T == 0 || p.g.K == 0 || p.g.C == 0) return WINO_OK;
   if (int rc = need(x, "x")) return rc;
   if (int rc = need(w, "w")) return rc;
@@ -535,44 +638,54 @@ int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void
   StageMults mu;
   std::memset(&mu, 0, sizeof mu);
 
-  // filters: s_w1 (Legendre inner bracket), s_v
+  // filters: s_w1 (Legendre inner bracket), s_v (one, or one per point)
+  const IMat* w_outer = p.st.G;
+  double w_prev = s->s_w;
   if (p.two_brackets) {
     if (int rc = cal_bracket(c, 0, p, 1, w, 8, mu, false)) return rc;
     s->s_w1 = scale_from(c.h_amax, *p.st.GP, s->s_w, 127.0);
     fill_mults(&mu.inner, *p.st.GP, s->s_w, s->s_w1);
-    if (int rc = cal_bracket(c, 0, p, 2, w, 8, mu, false)) return rc;
-    s->s_v = scale_from(c.h_amax, *p.st.Pinv, s->s_w1, 127.0);
-  } else {
-    if (int rc = cal_bracket(c, 0, p, 2, w, 8, mu, false)) return rc;
-    s->s_v = scale_from(c.h_amax, *p.st.G, s->s_w, 127.0);
+    w_outer = p.st.Pinv;
+    w_prev = s->s_w1;
   }
+  if (int rc = cal_bracket(c, 0, p, 2, w, 8, mu, false)) return rc;
+  if (pp)
+    scales_from_pt(c.h_amax, *w_outer, w_prev, 127.0, s->s_v_pt);
+  else
+    s->s_v = scale_from(c.h_amax, *w_outer, w_prev, 127.0);
   if (int rc = wino_weight_transform(&dd, w, V, s, hip_stream)) return rc;
 
-  // activations: s_x1 (Legendre inner bracket), s_u
+  // activations: s_x1 (Legendre inner bracket), s_u (one, or one per point)
+  const IMat* x_outer = p.st.BT;
+  double x_prev = s->s_x;
   if (p.two_brackets) {
     if (int rc = cal_bracket(c, 1, p, 1, x, 8, mu, false)) return rc;
     s->s_x1 = scale_from(c.h_amax, *p.st.PinvT, s->s_x, 127.0);
     fill_mults(&mu.inner, *p.st.PinvT, s->s_x, s->s_x1);
-    if (int rc = cal_bracket(c, 1, p, 2, x, 8, mu, false)) return rc;
-    s->s_u = scale_from(c.h_amax, *p.st.BPT, s->s_x1, 127.0);
-  } else {
-    if (int rc = cal_bracket(c, 1, p, 2, x, 8, mu, false)) return rc;
-    s->s_u = scale_from(c.h_amax, *p.st.BT, s->s_x, 127.0);
+    x_outer = p.st.BPT;
+    x_prev = s->s_x1;
   }
+  if (int rc = cal_bracket(c, 1, p, 2, x, 8, mu, false)) return rc;
+  if (pp)
+    scales_from_pt(c.h_amax, *x_outer, x_prev, 127.0, s->s_u_pt);
+  else
+    s->s_u = scale_from(c.h_amax, *x_outer, x_prev, 127.0);
   if (int rc = wino_input_transform(&dd, x, U, s, hip_stream)) return rc;
 
   double s_m_eff;
-  if (int rc = calibrate_contraction(c, d, dd, p, U, V, M, M32, s, &s_m_eff)) return rc;
+  ShiftTable sh;
+  if (int rc = calibrate_contraction(c, d, dd, p, U, V, M, M32, s, &s_m_eff, &sh)) return rc;
+  const ShiftTable* shp = pp ? &sh : nullptr;
 
   // output: s_m1 (Legendre inner bracket), s_y
   if (p.two_brackets) {
-    if (int rc = cal_bracket(c, 2, p, 1, M, p.m_bits, mu, false)) return rc;
+    if (int rc = cal_bracket(c, 2, p, 1, M, p.m_bits, mu, false, shp)) return rc;
     s->s_m1 = scale_from(c.h_amax, *p.st.PinvT, s_m_eff, 127.0);
     fill_mults(&mu.inner, *p.st.PinvT, s_m_eff, s->s_m1);
-    if (int rc = cal_bracket(c, 2, p, 2, M, p.m_bits, mu, d->relu != 0)) return rc;
+    if (int rc = cal_bracket(c, 2, p, 2, M, p.m_bits, mu, d->relu != 0, shp)) return rc;
     s->s_y = scale_from(c.h_amax, *p.st.APT, s->s_m1, 127.0);
   } else {
-    if (int rc = cal_bracket(c, 2, p, 2, M, p.m_bits, mu, d->relu != 0)) return rc;
+    if (int rc = cal_bracket(c, 2, p, 2, M, p.m_bits, mu, d->relu != 0, shp)) return rc;
     s->s_y = scale_from(c.h_amax, *p.st.AT, s_m_eff, 127.0);
   }
   if (y)
@@ -585,10 +698,13 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
   if (p.g.T == 0 || p.g.K == 0) return WINO_OK;   // no output element exists
-  const bool fusable = !(p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32);
+  if (int rc = check_per_point(d, s)) return rc;
+  const bool fusable = !(p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32 ||
+                         (s && s->per_point));
   if (d->fused == WINO_FUSED_ON && !fusable)
     return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "
-                                   "bits_hadamard 8 or 9 and fp32 or int8 output");
+                                   "bits_hadamard 8 or 9, fp32 or int8 output and per-tensor "
+                                   "scales");
   if (d->fused != WINO_FUSED_OFF && d->fused != WINO_FUSED_ON && d->fused != WINO_FUSED_AUTO)
     return fail(WINO_EINVAL, "unknown fused mode %d", d->fused);
   // AUTO: the fused kernel recomputes the input transform once per 64 output
@@ -621,13 +737,13 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
     if (int rc = need(s, "scales")) return rc;
     if (int rc = aligned(V, 16, "V")) return rc;
     StageMults in_mu, out_mu;
-    float m_mult;
+    MultTable m_mult;
     double s_m;
     if (int rc = input_mults(p, s, &in_mu)) return rc;
-    if (int rc = contract_mult(p, s, &m_mult, &s_m)) return rc;
-    if (int rc = output_mults(p, d, s, &out_mu)) return rc;
+    if (int rc = contract_mults(p, s, &m_mult, nullptr, &s_m)) return rc;
+    if (int rc = output_mults(p, d, s, &out_mu, nullptr)) return rc;
     hipError_t e = launch_fused(p.g, p.two_brackets, (const int8_t*)x, (const int8_t*)V, y,
-                                p.m_bits, d->out_type, d->relu != 0, in_mu, out_mu, m_mult,
+                                p.m_bits, d->out_type, d->relu != 0, in_mu, out_mu, m_mult.v[0],
                                 (hipStream_t)hip_stream);
     return e == hipSuccess ? WINO_OK : fail_hip(e, "fused launch");
   }
@@ -683,7 +799,12 @@ int make_flex_plan(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, Fle
 
 // Multipliers of the three flex stages.  `first` is the cast after the fp32
 // bracket; the integer P^{-1} brackets use the tables of the static path.
+int flex_no_per_point(const wino_scales_t* s) {
+  return s->per_point ? fail(WINO_EUNSUPPORTED, "the flex calls take per-tensor scales") : WINO_OK;
+}
+
 int flex_weight_mults(const Plan& p, const wino_scales_t* s, StageMults* mu, float* first) {
+  if (int rc = flex_no_per_point(s)) return rc;
   std::memset(mu, 0, sizeof *mu);
   if (!good_scale(s->s_w) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_w / s_v");
   if (p.two_brackets) {
@@ -697,6 +818,7 @@ int flex_weight_mults(const Plan& p, const wino_scales_t* s, StageMults* mu, flo
 }
 
 int flex_input_mults(const Plan& p, const wino_scales_t* s, StageMults* mu, float* mult_u) {
+  if (int rc = flex_no_per_point(s)) return rc;
   std::memset(mu, 0, sizeof *mu);
   if (!good_scale(s->s_x) || !good_scale(s->s_u)) return fail(WINO_EINVAL, "bad s_x / s_u");
   if (p.two_brackets) {
@@ -711,10 +833,11 @@ int flex_input_mults(const Plan& p, const wino_scales_t* s, StageMults* mu, floa
 
 int flex_output_mults(const Plan& p, const wino_conv_desc_t* d, const wino_scales_t* s,
                       StageMults* mu, float* mult_out) {
+  if (int rc = flex_no_per_point(s)) return rc;
   std::memset(mu, 0, sizeof *mu);
-  float dummy;
+  MultTable dummy;
   double s_prev;
-  if (int rc = contract_mult(p, s, &dummy, &s_prev)) return rc;
+  if (int rc = contract_mults(p, s, &dummy, nullptr, &s_prev)) return rc;
   if (p.two_brackets) {
     if (!good_scale(s->s_m1)) return fail(WINO_EINVAL, "bad s_m1");
     fill_mults(&mu->inner, *p.st.PinvT, s_prev, s->s_m1);
@@ -838,6 +961,7 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
     return fail(WINO_EOVERFLOW, "C = %d: calibration needs the exact int32 contraction result", d->C);
   if (int rc = need(s, "scales")) return rc;
   if (!good_scale(s->s_x) || !good_scale(s->s_w)) return fail(WINO_EINVAL, "s_x and s_w must be set");
+  if (int rc = flex_no_per_point(s)) return rc;
   if (int rc = need(workspace, "workspace")) return rc;
   size_t oV, oU, oM, oM32, oA;
   const size_t want = calibrate_layout(d, p, &oV, &oU, &oM, &oM32, &oA);
@@ -881,7 +1005,8 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
   if (int rc = wino_flex_input_transform(&dd, f, x, U, s, hip_stream)) return rc;
 
   double s_m_eff;
-  if (int rc = calibrate_contraction(c, d, dd, p, U, V, M, M32, s, &s_m_eff)) return rc;
+  ShiftTable sh_unused;
+  if (int rc = calibrate_contraction(c, d, dd, p, U, V, M, M32, s, &s_m_eff, &sh_unused)) return rc;
 
   // output: (Legendre) the integer P^{-T} bracket, then the fp32 A bracket
   s_prev = s_m_eff;

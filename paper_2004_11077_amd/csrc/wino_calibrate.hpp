@@ -117,12 +117,13 @@ __global__ __launch_bounds__(256) void k_cal_input(const int8_t* __restrict__ x,
 }
 
 // With relu the output scale only has to cover the positive numerators.
-template <int M, bool LEG, typename MT, int PHASE>
+template <int M, bool LEG, typename MT, int PHASE, bool PP>
 __global__ __launch_bounds__(256) void k_cal_output(const MT* __restrict__ Mq,
                                                     unsigned long long* __restrict__ amax,
-                                                    Geometry g, StageMults mu, int relu) {
+                                                    Geometry g, StageMults mu, int relu,
+                                                    ShiftTable sh) {
   constexpr int n = M + 2;
-  constexpr int64_t IN_MAX = MTraits<MT>::in_max;
+  constexpr int64_t IN_MAX = PP ? (MTraits<MT>::in_max << kMaxMShift) : MTraits<MT>::in_max;
   using TB = Tab<M>;
   const long total = (long)g.T * g.K;
   const long gid = (long)blockIdx.x * 256 + threadIdx.x;
@@ -131,6 +132,7 @@ __global__ __launch_bounds__(256) void k_cal_output(const MT* __restrict__ Mq,
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
       xi[i][j] = active ? (int)Mq[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] : 0;
+      if constexpr (PP) xi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
     });
   });
   // entries of partial tiles that fall outside the image are cropped, so they
@@ -192,29 +194,35 @@ hipError_t PerMCal<M>::input(const Geometry& g, bool leg, int phase, const int8_
   return hipGetLastError();
 }
 
-template <int M, typename MT>
+template <int M, typename MT, bool PP>
 static hipError_t cal_output_mt(const Geometry& g, bool leg, int phase, const void* Mq,
                                 unsigned long long* amax, const StageMults& mu, bool relu,
-                                hipStream_t st) {
-  const unsigned nb = (unsigned)(((long)g.T * g.K + 255) / 256);
+                                const ShiftTable& sh, hipStream_t st) {
+  const dim3 nb((unsigned)(((long)g.T * g.K + 255) / 256)), bs(256);
   const MT* mp = static_cast<const MT*>(Mq);
   const int r = relu ? 1 : 0;
   if (!leg)
-    wino_launch((k_cal_output<M, false, MT, 2>), dim3(nb), dim3(256), st, mp, amax, g, mu, r);
+    wino_launch((k_cal_output<M, false, MT, 2, PP>), nb, bs, st, mp, amax, g, mu, r, sh);
   else if (phase == 1)
-    wino_launch((k_cal_output<M, true, MT, 1>), dim3(nb), dim3(256), st, mp, amax, g, mu, r);
+    wino_launch((k_cal_output<M, true, MT, 1, PP>), nb, bs, st, mp, amax, g, mu, r, sh);
   else
-    wino_launch((k_cal_output<M, true, MT, 2>), dim3(nb), dim3(256), st, mp, amax, g, mu, r);
+    wino_launch((k_cal_output<M, true, MT, 2, PP>), nb, bs, st, mp, amax, g, mu, r, sh);
   return hipGetLastError();
 }
 
 template <int M>
 hipError_t PerMCal<M>::output(const Geometry& g, bool leg, int phase, const void* Mq, int m_bits,
                               unsigned long long* amax, const StageMults& mu, bool relu,
-                              hipStream_t st) {
-  if (m_bits == 8) return cal_output_mt<M, int8_t>(g, leg, phase, Mq, amax, mu, relu, st);
-  if (m_bits == 9) return cal_output_mt<M, int16_t>(g, leg, phase, Mq, amax, mu, relu, st);
-  return cal_output_mt<M, int32_t>(g, leg, phase, Mq, amax, mu, relu, st);
+                              const ShiftTable* sh, hipStream_t st) {
+  if (sh) {
+    if (m_bits == 8) return cal_output_mt<M, int8_t, true>(g, leg, phase, Mq, amax, mu, relu, *sh, st);
+    if (m_bits == 9) return cal_output_mt<M, int16_t, true>(g, leg, phase, Mq, amax, mu, relu, *sh, st);
+    return hipErrorInvalidValue;
+  }
+  const ShiftTable none{};
+  if (m_bits == 8) return cal_output_mt<M, int8_t, false>(g, leg, phase, Mq, amax, mu, relu, none, st);
+  if (m_bits == 9) return cal_output_mt<M, int16_t, false>(g, leg, phase, Mq, amax, mu, relu, none, st);
+  return cal_output_mt<M, int32_t, false>(g, leg, phase, Mq, amax, mu, relu, none, st);
 }
 
 }  // namespace wino

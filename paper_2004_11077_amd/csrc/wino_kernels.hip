@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
                                                   const int8_t* __restrict__ V,
                                                   MT* __restrict__ Mo, int T, int C, int K,
                                                   int tblocks, int kblocks, int tgroups, int tpg,
-                                                  int units, float mult, float qmax) {
+                                                  int units, MultTable mults, float qmax) {
   constexpr int kRow = kCK + 16;               // padded LDS row
   constexpr int LPR = kCK / 16;                // lanes per staged row
   constexpr int RPP = 256 / LPR;               // rows staged per pass
@@ -75,6 +75,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   const int tb = (unit - p * tgroups) * tpg + inner / kblocks;
   if (tb >= tblocks) return;
   const int t0 = tb * kTT, k0 = kb * kKT;
+  const float mult = mults.v[p];               // cast multiplier of this point (uniform)
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int wt = wave & 1, wk = wave >> 1;
@@ -264,9 +265,10 @@ hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t 
 
 __global__ __launch_bounds__(256) void k_absmax_i32(const int32_t* __restrict__ v, long count,
                                                     unsigned long long* __restrict__ amax) {
+  const int32_t* seg = v + (long)blockIdx.y * count;
   unsigned int m = 0;
   for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < count; i += (long)gridDim.x * 256) {
-    const int x = v[i];
+    const int x = seg[i];
     const unsigned int a = x < 0 ? (unsigned int)(-(long)x) : (unsigned int)x;
     m = a > m ? a : m;
   }
@@ -275,26 +277,27 @@ __global__ __launch_bounds__(256) void k_absmax_i32(const int32_t* __restrict__ 
     const unsigned int o = __shfl_xor(m, off);
     m = o > m ? o : m;
   }
-  if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(amax, (unsigned long long)m);
+  if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(amax + blockIdx.y, (unsigned long long)m);
 }
 
-hipError_t launch_absmax_i32(const int32_t* v, long count, unsigned long long* amax,
-                             hipStream_t st) {
-  if (count == 0) return hipSuccess;
+hipError_t launch_absmax_i32(const int32_t* v, long count, int segments,
+                             unsigned long long* amax, hipStream_t st) {
+  if (count == 0 || segments == 0) return hipSuccess;
   long nb = (count + 255) / 256;
-  if (nb > 256) nb = 256;     // one atomic per wave: keep the single target uncontended
-  wino_launch(k_absmax_i32, dim3((unsigned)nb), dim3(256), st, v, count, amax);
+  if (nb > 256) nb = 256;     // one atomic per wave: keep each target uncontended
+  wino_launch(k_absmax_i32, dim3((unsigned)nb, (unsigned)segments), dim3(256), st, v, count, amax);
   return hipGetLastError();
 }
 
 hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool leg, int phase,
                                   const void* in, int m_bits, unsigned long long* amax,
-                                  const StageMults& mu, bool relu, hipStream_t st) {
+                                  const StageMults& mu, bool relu, const ShiftTable* sh,
+                                  hipStream_t st) {
 #define WINO_CAL_M(MM)                                                                          \
   case MM:                                                                                      \
     return stage == 0   ? PerMCal<MM>::weight(g, leg, phase, (const int8_t*)in, amax, mu, st)   \
            : stage == 1 ? PerMCal<MM>::input(g, leg, phase, (const int8_t*)in, amax, mu, st)    \
-                        : PerMCal<MM>::output(g, leg, phase, in, m_bits, amax, mu, relu, st);
+                        : PerMCal<MM>::output(g, leg, phase, in, m_bits, amax, mu, relu, sh, st);
   switch (g.m) {
     WINO_CAL_M(2)
     WINO_CAL_M(4)
@@ -363,7 +366,7 @@ hipError_t launch_operand_transforms(const Geometry& g, bool leg, const int8_t* 
 }
 
 hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,
-                           int m_bits, float mult, hipStream_t st) {
+                           int m_bits, const MultTable& mult, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
   const int n = g.m + 2;
   const int tblocks = (g.T + kTT - 1) / kTT, kblocks = (g.K + kKT - 1) / kKT;
@@ -388,12 +391,12 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
 
 hipError_t launch_output_transform(const Geometry& g, bool leg, const void* Mq, int m_bits,
                                    void* y, int out_type, bool relu, const StageMults& mu,
-                                   hipStream_t st) {
+                                   const ShiftTable* sh, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
   switch (g.m) {
-    case 2: return PerM<2>::output(g, leg, Mq, m_bits, y, out_type, relu, mu, st);
-    case 4: return PerM<4>::output(g, leg, Mq, m_bits, y, out_type, relu, mu, st);
-    case 6: return PerM<6>::output(g, leg, Mq, m_bits, y, out_type, relu, mu, st);
+    case 2: return PerM<2>::output(g, leg, Mq, m_bits, y, out_type, relu, mu, sh, st);
+    case 4: return PerM<4>::output(g, leg, Mq, m_bits, y, out_type, relu, mu, sh, st);
+    case 6: return PerM<6>::output(g, leg, Mq, m_bits, y, out_type, relu, mu, sh, st);
   }
   return hipErrorInvalidValue;
 }

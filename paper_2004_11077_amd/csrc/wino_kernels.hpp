@@ -35,6 +35,13 @@ struct MultTable {
   float v[kMaxPts];
 };
 
+// Left shifts applied to the codes of M before the output bracket when M has
+// per-point power-of-two scales (entry p = i*n + j; all zero otherwise).
+struct ShiftTable {
+  int v[kMaxPts];
+};
+constexpr int kMaxMShift = 8;
+
 struct Geometry {
   int N, H, W, C, K;
   int m;        // output tile edge
@@ -58,9 +65,10 @@ struct PerM {
   static hipError_t operands(const Geometry& g, bool legendre_inner, const int8_t* x, int8_t* U,
                              const int8_t* w, int8_t* V, const StageMults& mu_in,
                              const StageMults& mu_w, hipStream_t st);
+  // sh != nullptr: M carries per-point shifts (8- or 9-bit M only)
   static hipError_t output(const Geometry& g, bool legendre_inner, const void* M_, int m_bits,
                            void* y, int out_type, bool relu, const StageMults& mu,
-                           hipStream_t st);
+                           const ShiftTable* sh, hipStream_t st);
 };
 extern template struct PerM<2>;
 extern template struct PerM<4>;
@@ -76,7 +84,7 @@ struct PerMCal {
                           unsigned long long* amax, const StageMults& mu, hipStream_t st);
   static hipError_t output(const Geometry& g, bool legendre_inner, int phase, const void* M_,
                            int m_bits, unsigned long long* amax, const StageMults& mu, bool relu,
-                           hipStream_t st);
+                           const ShiftTable* sh, hipStream_t st);
 };
 extern template struct PerMCal<2>;
 extern template struct PerMCal<4>;
@@ -119,10 +127,12 @@ hipError_t launch_flex_stage(int stage, const Geometry& g, bool legendre, int mo
 // stage: 0 weight, 1 input, 2 output; phase 1 = inner bracket, 2 = outer bracket.
 hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool legendre_inner, int phase,
                                   const void* in, int m_bits, unsigned long long* amax,
-                                  const StageMults& mu, bool relu, hipStream_t st);
-// amax[0] = max |v[i]| over an int32 array (device pointers).
-hipError_t launch_absmax_i32(const int32_t* v, long count, unsigned long long* amax,
-                             hipStream_t st);
+                                  const StageMults& mu, bool relu, const ShiftTable* sh,
+                                  hipStream_t st);
+// amax[s] = max |v[s * count + i]|, i < count, for each of `segments` consecutive
+// int32 arrays (device pointers).
+hipError_t launch_absmax_i32(const int32_t* v, long count, int segments,
+                             unsigned long long* amax, hipStream_t st);
 
 // legendre_inner == true selects the two-bracket Legendre pipeline; false the
 // single-bracket (canonical, or Legendre with brackets multiplied out).
@@ -136,13 +146,14 @@ hipError_t launch_operand_transforms(const Geometry& g, bool legendre_inner, con
                                      const StageMults& mu_in, const StageMults& mu_w,
                                      hipStream_t st);
 // m_bits: 8 -> int8 M, 9 -> int16 M, 32 -> int32 M (no cast).
+// mult.v[p]: multiplier of the cast of point p (unused for m_bits = 32).
 hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* M,
-                           int m_bits, float mult, hipStream_t st);
+                           int m_bits, const MultTable& mult, hipStream_t st);
 // out_type: 0 fp32 (outer table = dequantisation factors), 1 int32 numerators,
 // 2 int8 codes (outer table = cast multipliers).
 hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const void* M,
                                    int m_bits, void* y, int out_type, bool relu,
-                                   const StageMults& mu, hipStream_t st);
+                                   const StageMults& mu, const ShiftTable* sh, hipStream_t st);
 
 // Fused variant (input transform + contraction + output transform in one kernel);
 // V is the transformed filter tensor.  m = 2 or 4, m_bits 8 or 9, out_type 0 or 2.

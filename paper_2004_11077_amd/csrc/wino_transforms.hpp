@@ -425,12 +425,14 @@ struct MTraits<int32_t> {
 
 // WHOLE: K is a multiple of 256, so a work group's items are 256 output
 // channels of ONE tile and the tile arithmetic is block-uniform.
-template <int M, bool LEG, typename MT, int OUT, bool WHOLE>
+// PP: M carries per-point power-of-two scales; the codes of point p enter the
+// bracket shifted left by sh.v[p] <= kMaxMShift, which the bounds account for.
+template <int M, bool LEG, typename MT, int OUT, bool WHOLE, bool PP>
 __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__ Mq,
                                                           void* __restrict__ yv, Geometry g,
-                                                          StageMults mu, int relu) {
+                                                          StageMults mu, int relu, ShiftTable sh) {
   constexpr int n = M + 2, n2 = n * n;
-  constexpr int64_t IN_MAX = MTraits<MT>::in_max;
+  constexpr int64_t IN_MAX = PP ? (MTraits<MT>::in_max << kMaxMShift) : MTraits<MT>::in_max;
   using TB = Tab<M>;
   const int tid = threadIdx.x;
   const long gid0 = (long)blockIdx.x * 256;
@@ -479,6 +481,14 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     static_for<0, n>([&](auto i) {
       static_for<0, n>([&](auto j) {
         xi[i][j] = (int)mb[(long)(decltype(i)::value * n + decltype(j)::value) * total];
+      });
+    });
+  }
+
+  if constexpr (PP) {
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) {
+        xi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
       });
     });
   }
@@ -593,52 +603,57 @@ hipError_t PerM<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_
   return hipGetLastError();
 }
 
-template <int M, bool LEG, typename MT, bool WHOLE>
+template <int M, bool LEG, typename MT, bool WHOLE, bool PP>
 static hipError_t output_mtw(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
-                             const StageMults& mu, hipStream_t st) {
-  const unsigned nb = blocks_for((long)g.T * g.K);
+                             const StageMults& mu, const ShiftTable& sh, hipStream_t st) {
+  const dim3 nb(blocks_for((long)g.T * g.K)), bs(256);
   const MT* mp = static_cast<const MT*>(Mq);
   const int r = relu ? 1 : 0;
   if (out_type == 0) {
-    wino_launch((k_output_transform<M, LEG, MT, 0, WHOLE>), dim3(nb), dim3(256), st, mp, y, g,
-                       mu, r);
+    wino_launch((k_output_transform<M, LEG, MT, 0, WHOLE, PP>), nb, bs, st, mp, y, g, mu, r, sh);
   } else if (out_type == 1) {
-    // integer numerators only make sense for a single integer bracket
-    if constexpr (LEG)
+    // integer numerators only make sense for a single integer bracket with one scale
+    if constexpr (LEG || PP)
       return hipErrorInvalidValue;
     else
-      wino_launch((k_output_transform<M, LEG, MT, 1, WHOLE>), dim3(nb), dim3(256), st, mp, y,
-                         g, mu, r);
+      wino_launch((k_output_transform<M, LEG, MT, 1, WHOLE, PP>), nb, bs, st, mp, y, g, mu, r, sh);
   } else {
-    wino_launch((k_output_transform<M, LEG, MT, 2, WHOLE>), dim3(nb), dim3(256), st, mp, y, g,
-                       mu, r);
+    wino_launch((k_output_transform<M, LEG, MT, 2, WHOLE, PP>), nb, bs, st, mp, y, g, mu, r, sh);
   }
   return hipGetLastError();
 }
 
 template <int M, bool LEG, typename MT>
 static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_type, bool relu,
-                            const StageMults& mu, hipStream_t st) {
-  // the fast path is built for the int8 M of the all-8-bit pipeline
+                            const StageMults& mu, const ShiftTable* sh, hipStream_t st) {
+  if (sh) {
+    if constexpr (sizeof(MT) == 4)
+      return hipErrorInvalidValue;       // per-point scales need the 8- or 9-bit cast
+    else
+      return output_mtw<M, LEG, MT, false, true>(g, Mq, y, out_type, relu, mu, *sh, st);
+  }
+  const ShiftTable none{};
+  // the block-uniform fast path is built for the int8 M of the all-8-bit pipeline
   if constexpr (sizeof(MT) == 1)
     if (whole_tiles(g.K, g.H, g.W))
-      return output_mtw<M, LEG, MT, true>(g, Mq, y, out_type, relu, mu, st);
-  return output_mtw<M, LEG, MT, false>(g, Mq, y, out_type, relu, mu, st);
+      return output_mtw<M, LEG, MT, true, false>(g, Mq, y, out_type, relu, mu, none, st);
+  return output_mtw<M, LEG, MT, false, false>(g, Mq, y, out_type, relu, mu, none, st);
 }
 
 template <int M, bool LEG>
 static hipError_t output_m(const Geometry& g, const void* Mq, int m_bits, void* y, int out_type,
-                           bool relu, const StageMults& mu, hipStream_t st) {
-  if (m_bits == 8) return output_mt<M, LEG, int8_t>(g, Mq, y, out_type, relu, mu, st);
-  if (m_bits == 9) return output_mt<M, LEG, int16_t>(g, Mq, y, out_type, relu, mu, st);
-  return output_mt<M, LEG, int32_t>(g, Mq, y, out_type, relu, mu, st);
+                           bool relu, const StageMults& mu, const ShiftTable* sh, hipStream_t st) {
+  if (m_bits == 8) return output_mt<M, LEG, int8_t>(g, Mq, y, out_type, relu, mu, sh, st);
+  if (m_bits == 9) return output_mt<M, LEG, int16_t>(g, Mq, y, out_type, relu, mu, sh, st);
+  return output_mt<M, LEG, int32_t>(g, Mq, y, out_type, relu, mu, sh, st);
 }
 
 template <int M>
 hipError_t PerM<M>::output(const Geometry& g, bool leg, const void* Mq, int m_bits, void* y,
-                           int out_type, bool relu, const StageMults& mu, hipStream_t st) {
-  return leg ? output_m<M, true>(g, Mq, m_bits, y, out_type, relu, mu, st)
-             : output_m<M, false>(g, Mq, m_bits, y, out_type, relu, mu, st);
+                           int out_type, bool relu, const StageMults& mu, const ShiftTable* sh,
+                           hipStream_t st) {
+  return leg ? output_m<M, true>(g, Mq, m_bits, y, out_type, relu, mu, sh, st)
+             : output_m<M, false>(g, Mq, m_bits, y, out_type, relu, mu, sh, st);
 }
 
 }  // namespace wino

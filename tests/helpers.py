@@ -8,9 +8,9 @@ M_DTYPES = {8: np.int8, 9: np.int16, 32: np.int32}
 
 
 def oracle_layer(xq, wq, s_x, s_w, m=4, base="legendre", bits_hadamard=8, inner_quant=True,
-                 out_type="f32", relu=False):
+                 out_type="f32", relu=False, per_point=False):
     cfg = q.LayerConfig(m=m, base=base, bits_hadamard=bits_hadamard, inner_quant=inner_quant,
-                        out_type=out_type, relu=relu)
+                        out_type=out_type, relu=relu, per_point=per_point)
     return q.run_layer(xq, wq, s_x, s_w, cfg)
 
 
@@ -22,7 +22,7 @@ def small_layer(N, H, W, C, K, seed, outliers=0.0):
 
 
 def gpu_layer(xq, wq, scales, m=4, base="legendre", bits_hadamard=8, inner_quant=True,
-              out_type="f32", relu=False, whole=False, fused=False):
+              out_type="f32", relu=False, whole=False, fused=False, per_point=False):
     """Runs the library stage by stage (or wino_conv2d when ``whole``) and
     returns numpy copies of V, U, M, y."""
     import torch

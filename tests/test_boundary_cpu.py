@@ -163,3 +163,24 @@ def test_probe_rejects_bad_arguments_before_any_launch():
     assert lib.wino_probe_peak(0, 0, 1, fake, None, None) == -1
     assert lib.wino_probe_peak(1, 1, 1 << 30, fake, None, None) == -1
     assert lib.wino_probe_peak(0, 1, 1, None, None, None) == -1
+
+
+def test_per_point_scales_are_validated_before_any_launch():
+    import numpy as np
+    lib = binding._load()
+    fake = C.c_void_p(4096)
+    pp = wn.Scales.from_dict({"s_u": np.ones((6, 6)), "s_v": np.ones((6, 6)), "m_shift": [0] * 36})
+    assert pp.per_point == 1
+    for kw in (dict(bits_hadamard=32), dict(base=wn.BASE_CANONICAL, out_type=wn.OUT_I32)):
+        d = wn.ConvDesc(1, 8, 8, 16, 16, **kw)
+        assert lib.wino_contract(C.byref(d), fake, fake, fake, C.byref(pp), None) == -2, kw
+    d = wn.ConvDesc(1, 8, 8, 16, 16)
+    bad = wn.Scales.from_dict({"s_u": np.ones((6, 6)), "s_v": np.ones((6, 6)), "m_shift": [9] + [0] * 35})
+    assert lib.wino_contract(C.byref(d), fake, fake, fake, C.byref(bad), None) == -1
+    assert b"m_shift" in lib.wino_last_error()
+    neg = wn.Scales.from_dict({"s_u": -np.ones((6, 6)), "s_v": np.ones((6, 6))})
+    assert lib.wino_input_transform(C.byref(d), fake, fake, C.byref(neg), None) == -1
+    dfused = wn.ConvDesc(1, 8, 8, 16, 16, fused=1)
+    assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(pp), fake, 1 << 30, None) == -2
+    fm = wn.FlexMatrices(np.ones((6, 3)), np.ones((6, 6)), np.ones((4, 6)))
+    assert lib.wino_flex_input_transform(C.byref(d), C.byref(fm), fake, fake, C.byref(pp), None) == -2
