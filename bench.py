@@ -366,6 +366,29 @@ def main():
         out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
                                 "unit": "TOPS",
                                 "note": "input transform recomputed per 64-channel k block"}
+    # extra: the same layer with per-Winograd-point scales (U, V per point, M with
+    # power-of-two refinements), calibrated on the device, same three launches
+    if not args.no_extras:
+        cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        psc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws,
+                                per_point=True)
+        del cws
+
+        def pstep():
+            wn.wino_transform_operands(desc, x, U, w, V, psc, stream)
+            wn.wino_contract(desc, U, V, M, psc, stream)
+            wn.wino_output_transform(desc, M, y, psc, stream)
+        for _ in range(args.warmup):
+            pstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            pstep()
+        torch.cuda.synchronize()
+        pdt = (time.perf_counter() - t0) / args.steps
+        out["per_point_variant"] = {"ms_per_step": pdt * 1e3, "value": ops / pdt / 1e12,
+                                    "unit": "TOPS", "m_shift_max": max(psc.m_shift[:n2]),
+                                    "note": "per-point scales for U, V and M"}
     # extra: the flex layer (run-time fp32 G_P, B_P, A_P; here the static matrices rounded
     # to fp32, as at the start of training) on the same workload, whole-layer call
     if not args.no_extras:
