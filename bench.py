@@ -24,11 +24,11 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
-# a plain 64 MiB device copy of the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
+# a plain device copy of known size in the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4a_f4_c256": {"operand_transforms": (7191.7 + 11520.1) * 1024,
-                      "contraction": (13934.6 + 9216.0) * 1024,
-                      "output_transform": (9353.7 + 16384.0) * 1024},
+    "cfg4a_f4_c256": {"operand_transforms": (7181.3 + 11520.0) * 1024,
+                      "contraction": (13938.2 + 9216.0) * 1024,
+                      "output_transform": (9348.1 + 16384.0) * 1024},
 }
 
 
