@@ -191,7 +191,41 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
               so[tl * kORow + kq];
       }
     }
+  } else if constexpr (sizeof(MT) == 2) {
+    // 9-bit codes (int16): same route as the int8 codes, through LDS as a [t][k]
+    // block of 256-byte rows (+16 B against bank conflicts), stored 16 bytes per lane
+    __syncthreads();
+    constexpr int kORowB = kKT * 2 + 16;
+    static_assert(kTT * kORowB <= kSm);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          uint32_t q[4];
+#pragma unroll
+          for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)acc[i][j][4 * gq + v], mult, qmax);
+          uint2 pk;                      // low halves of q0, q1 and of q2, q3
+          pk.x = __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
+          pk.y = __builtin_amdgcn_perm(q[3], q[2], 0x05040100u);
+          const int tl = wt * 64 + j * 32 + r;
+          const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
+          *reinterpret_cast<uint2*>(smem + tl * kORowB + kl * 2) = pk;
+        }
+    __syncthreads();
+    const int kseg = tid & 15;           // 16-byte segment (8 codes) within the 256-byte row
+    if (kseg * 8 < krows) {
+#pragma unroll
+      for (int it = 0; it < kTT / 16; ++it) {
+        const int tl = it * 16 + (tid >> 4);
+        if (tl < trows)
+          *reinterpret_cast<v4i*>(Mp + ((uint32_t)tl * (uint32_t)K + kseg * 8)) =
+              *reinterpret_cast<const v4i*>(smem + tl * kORowB + kseg * 16);
+      }
+    }
   } else {
+    // unquantised int32 result (calibration, bits_hadamard = 32): stored from registers
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -203,18 +237,8 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
         for (int gq = 0; gq < 4; ++gq) {
           const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
           if (kl >= krows) continue;
-          if constexpr (sizeof(MT) == 2) {
-            uint32_t q[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)acc[i][j][4 * gq + v], mult, qmax);
-            uint2 pk;                    // low halves of q0, q1 and of q2, q3
-            pk.x = __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
-            pk.y = __builtin_amdgcn_perm(q[3], q[2], 0x05040100u);
-            *reinterpret_cast<uint2*>(mrow + kl) = pk;
-          } else {
-            *reinterpret_cast<int4*>(mrow + kl) = make_int4(acc[i][j][4 * gq], acc[i][j][4 * gq + 1],
-                                                             acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
-          }
+          *reinterpret_cast<int4*>(mrow + kl) = make_int4(acc[i][j][4 * gq], acc[i][j][4 * gq + 1],
+                                                           acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]);
         }
       }
   }
