@@ -14,6 +14,7 @@
  *     M [n*n][T][K]  int8 (bits_hadamard 8) | int16 (9) | int32 (32)
  *     y [N][H][W][K] float | int8 | int32 (see out_type)
  *   A stored code q of a tensor with scale s stands for the real value q*s.
+ *   Every device tensor must start on a 16-byte boundary (EINVAL otherwise).
  *
  * Every function returns WINO_OK (0) or a negative error code and never
  * throws or aborts; wino_last_error() gives the text of the last failure on

@@ -375,6 +375,8 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
     return e == hipSuccess ? WINO_OK : fail_hip(e, "fp32 weight launch");
   }
   if (int rc = need(s, "scales")) return rc;
+  if (int rc = aligned(w, 16, "w")) return rc;
+  if (int rc = aligned(V, 16, "V")) return rc;
   if (int rc = check_per_point(d, s)) return rc;
   StageMults mu;
   if (int rc = weight_mults(p, s, &mu)) return rc;
@@ -422,6 +424,8 @@ int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, c
   if (int rc = need(s, "scales")) return rc;
   if (int rc = aligned(x, 16, "x")) return rc;
   if (int rc = aligned(U, 16, "U")) return rc;
+  if (int rc = aligned(w, 16, "w")) return rc;
+  if (int rc = aligned(V, 16, "V")) return rc;
   if (int rc = check_per_point(d, s)) return rc;
   StageMults mu_in, mu_w;
   if (int rc = input_mults(p, s, &mu_in)) return rc;

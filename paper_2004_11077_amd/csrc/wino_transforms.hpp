@@ -240,20 +240,29 @@ __device__ __forceinline__ void cast_result(const AccT (&num)[T.rows][T.rows], c
 }
 
 // ---------------------------------------------------------------------------
-// Weight transform: one lane per (k, c) filter.
+// Weight transform: one lane per (k, c) filter; a work group owns 256
+// consecutive filters (K * C is a multiple of 256, so every block is full).
+// Their 2304 input bytes are contiguous: 144 lanes fetch them with 16-byte
+// loads into LDS and every lane picks its nine taps; the n*n results go back
+// through LDS ([point][filter]) to 16-byte stores, as in the input transform.
 // ---------------------------------------------------------------------------
 template <int M, bool LEG>
 __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t* __restrict__ V,
                                             const Geometry& g, const StageMults& mu,
                                             unsigned block) {
-  constexpr int n = M + 2;
+  constexpr int n = M + 2, n2 = n * n;
   using TB = Tab<M>;
-  const long gid = (long)block * 256 + threadIdx.x;
+  __shared__ __attribute__((aligned(16))) int8_t s_w[256 * 9];
+  __shared__ __attribute__((aligned(16))) int8_t s_v[n2 * 256];
+  const int tid = threadIdx.x;
+  const long gid0 = (long)block * 256;
   const long KC = (long)g.K * g.C;
-  if (gid >= KC) return;
+  if (tid < 144)
+    *reinterpret_cast<v4i*>(s_w + tid * 16) = *reinterpret_cast<const v4i*>(w + gid0 * 9 + tid * 16);
+  __syncthreads();
   int wi[3][3];
   static_for<0, 3>([&](auto a) {
-    static_for<0, 3>([&](auto b) { wi[a][b] = w[gid * 9 + decltype(a)::value * 3 + decltype(b)::value]; });
+    static_for<0, 3>([&](auto b) { wi[a][b] = s_w[tid * 9 + decltype(a)::value * 3 + decltype(b)::value]; });
   });
   int q[n][n];
   if constexpr (LEG) {
@@ -271,9 +280,18 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
   }
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
-      V[(long)(decltype(i)::value * n + decltype(j)::value) * KC + gid] = (int8_t)q[i][j];
+      s_v[(decltype(i)::value * n + decltype(j)::value) * 256 + tid] = (int8_t)q[i][j];
     });
   });
+  __syncthreads();
+  const int u = tid & 15, prow = tid >> 4;
+  int8_t* vb = V + gid0 + u * 16;
+#pragma unroll
+  for (int it = 0; it < (n2 + 15) / 16; ++it) {
+    const int p = it * 16 + prow;
+    if (p < n2)
+      *reinterpret_cast<v4i*>(vb + (long)p * KC) = *reinterpret_cast<const v4i*>(s_v + p * 256 + u * 16);
+  }
 }
 
 // ---------------------------------------------------------------------------
