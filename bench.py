@@ -366,6 +366,24 @@ def main():
         out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
                                 "unit": "TOPS",
                                 "note": "input transform recomputed per 64-channel k block"}
+    # extra: the same layer with its filters transformed ahead of time (a1 is a per-layer,
+    # offline step in deployment): input transform, contraction, output transform
+    if not args.no_extras:
+        def vstep():
+            wn.wino_input_transform(desc, x, U, sc, stream)
+            wn.wino_contract(desc, U, V, M, sc, stream)
+            wn.wino_output_transform(desc, M, y, sc, stream)
+        for _ in range(args.warmup):
+            vstep()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            vstep()
+        torch.cuda.synchronize()
+        vdt = (time.perf_counter() - t0) / args.steps
+        out["pretransformed_weights"] = {"ms_per_step": vdt * 1e3, "value": ops / vdt / 1e12,
+                                         "unit": "TOPS",
+                                         "note": "a2 + a3 + a4 only; V computed once beforehand"}
     # extra: the same layer with per-Winograd-point scales (U, V per point, M with
     # power-of-two refinements), calibrated on the device, same three launches
     if not args.no_extras:
