@@ -55,10 +55,23 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
   __shared__ __attribute__((aligned(16))) int8_t smem[n2 * kPt];
   __shared__ __attribute__((aligned(16))) int8_t s_x[NWV * n2 * kFC];   // input pixels of one pass
 
+  // Image and pixel origin of the block's 16 tiles, worked out once (three
+  // integer divisions per tile) and read back from LDS by the staging loops
+  // and the output transform: ti = {b, ty*M, tx*M, tile exists}.
+  __shared__ int4 s_tile[kFT];
+
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int tb = blockIdx.x % tblocks, kblk = blockIdx.x / tblocks;
   const int t0 = tb * kFT, k0 = kblk * KB;
   const int jl = lane & 15, seg = lane >> 4;         // MFMA operand row / 16-byte K segment
+  if (tid < kFT) {
+    const int t = t0 + tid;
+    const int tx = t % g.TW;
+    const int ty = (t / g.TW) % g.TH;
+    const int b = t / (g.TW * g.TH);
+    s_tile[tid] = make_int4(b, ty * M, tx * M, t < g.T ? 1 : 0);
+  }
+  __syncthreads();
 
   // SINGLE (C <= 64, one channel chunk): a point's contraction is complete
   // after its MFMAs, so it is cast at once and written over that point's own
@@ -104,16 +117,14 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
         if (idx < NWV * n2 * 4) {
           const int tq = idx / (n2 * 4), rem = idx - tq * (n2 * 4);
           const int pix = rem >> 2, sg = rem & 3;
-          const int t = t0 + it * NWV + tq, c = c0 + sg * 16;
+          const int c = c0 + sg * 16;
+          const int4 ti = s_tile[it * NWV + tq];
           v4i v = {0, 0, 0, 0};
-          if (t < g.T && c < g.C) {
-            const int tx = t % g.TW;
-            const int ty = (t / g.TW) % g.TH;
-            const int b = t / (g.TW * g.TH);
+          if (ti.w && c < g.C) {
             const int a = pix / n, bb = pix - a * n;
-            const int h = ty * M - 1 + a, ww = tx * M - 1 + bb;
+            const int h = ti.y - 1 + a, ww = ti.z - 1 + bb;
             if (h >= 0 && h < g.H && ww >= 0 && ww < g.W)
-              v = *reinterpret_cast<const v4i*>(x + (((long)b * g.H + h) * g.W + ww) * g.C + c);
+              v = *reinterpret_cast<const v4i*>(x + (((long)ti.x * g.H + h) * g.W + ww) * g.C + c);
           }
           *reinterpret_cast<v4i*>(s_x + (tq * n2 + pix) * kFC + sg * 16) = v;
         }
@@ -185,11 +196,10 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
   for (int it = 0; it < kFT * KB / NT; ++it) {
     const int item = it * NT + tid;
     const int tl = item / KB, kl = item - tl * KB;
-    const int t = t0 + tl, k = k0 + kl;
-    if (t >= g.T || k >= g.K) continue;
-    const int tx = t % g.TW;
-    const int ty = (t / g.TW) % g.TH;
-    const int b = t / (g.TW * g.TH);
+    const int k = k0 + kl;
+    const int4 ti = s_tile[tl];
+    if (!ti.w || k >= g.K) continue;
+    const int b = ti.x, ty_m = ti.y, tx_m = ti.z;    // image, first output row and column
     int mi[n][n];
     static_for<0, n>([&](auto i) {
       static_for<0, n>([&](auto j) {
@@ -197,7 +207,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
             smem + (decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, kl * (int)sizeof(MT)));
       });
     });
-    const long ybase = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K + k;
+    const long ybase = (((long)b * g.H + ty_m) * g.W + tx_m) * g.K + k;
     const int wk = g.W * g.K;
     auto to_float_approx = [](auto v) -> float {
       if constexpr (sizeof(v) == 8) {
@@ -213,8 +223,8 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
           constexpr int idx = decltype(i)::value * M + decltype(j)::value;
-          const int h = ty * M + decltype(i)::value;
-          const int ww = tx * M + decltype(j)::value;
+          const int h = ty_m + decltype(i)::value;
+          const int ww = tx_m + decltype(j)::value;
           if (h < g.H && ww < g.W) {
             const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
             if constexpr (OUT == 0) {
