@@ -46,7 +46,7 @@ from .winograd import extract_tiles, scatter_tiles
 class LayerConfig:
     m: int = 4
     r: int = 3
-    base: str = "legendre"          # "canonical" | "legendre"
+    base: str = "legendre"          # "canonical" | "legendre" | "chebyshev" | "hermite"
     bits: int = 8                    # every cast except the Hadamard one
     bits_hadamard: int = 8           # 8 | 9 | 32 (32 = contraction result kept as is)
     inner_quant: bool = True         # casts on the inner brackets of eq. 4
@@ -170,9 +170,10 @@ class StageMatrices:
     """Integer forms of the stage matrices one configuration uses."""
 
     def __init__(self, cfg):
-        mats = mx.Matrices(cfg.m, cfg.r)
+        # the canonical matrices G, B^T, A^T do not depend on the base, so any will do there
+        mats = mx.Matrices(cfg.m, cfg.r, base="legendre" if cfg.base == "canonical" else cfg.base)
         self.mats = mats
-        legendre = cfg.base == "legendre"
+        legendre = cfg.base != "canonical"      # a polynomial base: two brackets per stage
         if legendre and cfg.inner_quant:
             self.in_inner = _imat(mats.PinvT)      # P^{-T} X P^{-1}
             self.in_outer = _imat(mats.BPT)        # B_P^T . B_P

@@ -155,6 +155,27 @@ def test_converges_to_direct_convolution_with_bit_width(m, base):
     assert errs[3] < 2e-3 if m < 6 else errs[3] < 5e-2
 
 
+@pytest.mark.parametrize("base", ["chebyshev", "hermite"])
+def test_other_bases_converge_and_collapse_without_inner_casts(base):
+    """The alternatives Section 4.1 names run through the same two-bracket pipeline."""
+    x, w = si.make_real(1, 8, 8, 8, 8, seed=1)
+    yd = direct.direct_conv(x, w)
+    rms = np.sqrt(np.mean(yd ** 2))
+    errs = []
+    for bits in (14, 18, 22):
+        xq, s_x = q.quantise_real(x, bits)
+        wq, s_w = q.quantise_real(w, bits)
+        out, _ = q.run_layer(xq, wq, s_x, s_w,
+                             q.LayerConfig(m=4, base=base, bits=bits, bits_hadamard=bits))
+        errs.append(np.sqrt(np.mean((out["y"] - yd) ** 2)) / rms)
+    assert errs[1] < errs[0] / 8 and errs[2] < errs[1] / 4, errs
+    _, _, xq, wq, s_x, s_w = tiny_layer(1, 8, 8, 4, 4, seed=2)
+    can, _ = q.run_layer(xq, wq, s_x, s_w, q.LayerConfig(m=4, base="canonical"))
+    col, _ = q.run_layer(xq, wq, s_x, s_w, q.LayerConfig(m=4, base=base, inner_quant=False))
+    for key in ("U", "V", "M", "y"):
+        assert np.array_equal(can[key], col[key])
+
+
 @pytest.mark.parametrize("m", [2, 4, 6])
 def test_no_inner_casts_collapses_legendre_to_canonical(m):
     _, _, xq, wq, s_x, s_w = tiny_layer(1, 8, 8, 4, 4, seed=2)
