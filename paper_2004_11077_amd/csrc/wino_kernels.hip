@@ -36,7 +36,7 @@ ProfileEvents take_profile_events() {
 // each with a private L2): the k blocks that share a set of U rows then share
 // one L2, and the number of groups is chosen to spread n*n points evenly.
 // ---------------------------------------------------------------------------
-constexpr int kTT = 128, kKT = 128;
+constexpr int kKT = 128;
 
 // One cast kept in its biased float form: the code sits, in two's complement,
 // in the low bits of the returned pattern (0x4B400000 + q), so packing needs
@@ -48,7 +48,8 @@ __device__ __forceinline__ uint32_t cast_biased(float v, float mult, float qmax)
   return __float_as_uint(t);
 }
 
-template <typename MT, int kCK>
+// kTT: tile rows (t) per work group, 128 or 64 (small problems: twice the work groups).
+template <typename MT, int kCK, int kTT>
 __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
                                                   const int8_t* __restrict__ V,
                                                   MT* __restrict__ Mo, int T, int C, int K,
@@ -57,8 +58,10 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   constexpr int kRow = kCK + 16;               // padded LDS row
   constexpr int LPR = kCK / 16;                // lanes per staged row
   constexpr int RPP = 256 / LPR;               // rows staged per pass
-  constexpr int NP = 128 / RPP;                // passes per operand
-  constexpr int kSm = (kKT + kTT) * kRow > kTT * (kKT + 4) ? (kKT + kTT) * kRow : kTT * (kKT + 4);
+  constexpr int NPA = kKT / RPP;               // staging passes for V
+  constexpr int NPB = kTT / RPP;               // staging passes for U
+  constexpr int JT = kTT / 64;                 // 32-wide t blocks per wave
+  constexpr int kSm = (kKT + kTT) * kRow;      // also holds the [t][k] output block
   __shared__ __attribute__((aligned(16))) int8_t smem[kSm];
   int8_t* sA = smem;                  // V rows (k)
   int8_t* sB = smem + kKT * kRow;     // U rows (t)
@@ -91,23 +94,22 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   // staging map: LPR lanes cover one row chunk; rows past the edge are read
   // from the last existing row (their products land in outputs never stored)
   const int srow = tid / LPR, sseg = (tid % LPR) * 16;
-  uint32_t oa[NP], ob[NP];
+  uint32_t oa[NPA], ob[NPB];
 #pragma unroll
-  for (int i = 0; i < NP; ++i) {
-    const int row = srow + i * RPP;
-    oa[i] = (uint32_t)min(row, krows - 1) * (uint32_t)C + sseg;
-    ob[i] = (uint32_t)min(row, trows - 1) * (uint32_t)C + sseg;
-  }
+  for (int i = 0; i < NPA; ++i)
+    oa[i] = (uint32_t)min(srow + i * RPP, krows - 1) * (uint32_t)C + sseg;
+#pragma unroll
+  for (int i = 0; i < NPB; ++i)
+    ob[i] = (uint32_t)min(srow + i * RPP, trows - 1) * (uint32_t)C + sseg;
   // one register set: the next chunk is in flight while this one feeds the MFMAs
   // (a second set costs a third of the occupancy and measured slower)
-  v4i ra[NP], rb[NP];
+  v4i ra[NPA], rb[NPB];
   auto fetch = [&](int c0) {
     if (c0 + kCK <= C) {               // uniform: the whole chunk lies inside C
 #pragma unroll
-      for (int i = 0; i < NP; ++i) {
-        ra[i] = *reinterpret_cast<const v4i*>(Vp + c0 + oa[i]);
-        rb[i] = *reinterpret_cast<const v4i*>(Up + c0 + ob[i]);
-      }
+      for (int i = 0; i < NPA; ++i) ra[i] = *reinterpret_cast<const v4i*>(Vp + c0 + oa[i]);
+#pragma unroll
+      for (int i = 0; i < NPB; ++i) rb[i] = *reinterpret_cast<const v4i*>(Up + c0 + ob[i]);
     } else {
       // last chunk when C is not a multiple of the chunk: columns past C are
       // read from a clamped in-bounds column and zeroed, without branching
@@ -115,37 +117,36 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
       const int cc = ok ? c0 : C - 16 - sseg;
       const int keep = ok ? -1 : 0;
 #pragma unroll
-      for (int i = 0; i < NP; ++i) {
-        ra[i] = *reinterpret_cast<const v4i*>(Vp + cc + oa[i]) & keep;
-        rb[i] = *reinterpret_cast<const v4i*>(Up + cc + ob[i]) & keep;
-      }
+      for (int i = 0; i < NPA; ++i) ra[i] = *reinterpret_cast<const v4i*>(Vp + cc + oa[i]) & keep;
+#pragma unroll
+      for (int i = 0; i < NPB; ++i) rb[i] = *reinterpret_cast<const v4i*>(Up + cc + ob[i]) & keep;
     }
   };
 
-  v16i acc[2][2];
+  v16i acc[2][JT];
   // FIRST: the accumulators start from the constant zero operand of the first
   // MFMA instead of being cleared beforehand.
   auto chunk = [&]<bool FIRST>(int c0) {
     if constexpr (!FIRST) __syncthreads();   // previous chunk fully consumed
 #pragma unroll
-    for (int i = 0; i < NP; ++i) {
-      *reinterpret_cast<v4i*>(sA + (srow + i * RPP) * kRow + sseg) = ra[i];
-      *reinterpret_cast<v4i*>(sB + (srow + i * RPP) * kRow + sseg) = rb[i];
-    }
+    for (int i = 0; i < NPA; ++i) *reinterpret_cast<v4i*>(sA + (srow + i * RPP) * kRow + sseg) = ra[i];
+#pragma unroll
+    for (int i = 0; i < NPB; ++i) *reinterpret_cast<v4i*>(sB + (srow + i * RPP) * kRow + sseg) = rb[i];
     __syncthreads();
     if (c0 + kCK < C) fetch(c0 + kCK);
 #pragma unroll
     for (int ks = 0; ks < kCK / 32; ++ks) {
-      v4i fa[2], fb[2];
+      v4i fa[2], fb[JT];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < 2; ++i)
         fa[i] = *reinterpret_cast<const v4i*>(sA + (wk * 64 + i * 32 + r) * kRow + ks * 32 + h * 16);
-        fb[i] = *reinterpret_cast<const v4i*>(sB + (wt * 64 + i * 32 + r) * kRow + ks * 32 + h * 16);
-      }
+#pragma unroll
+      for (int j = 0; j < JT; ++j)
+        fb[j] = *reinterpret_cast<const v4i*>(sB + (wt * (kTT / 2) + j * 32 + r) * kRow + ks * 32 + h * 16);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
+        for (int j = 0; j < JT; ++j) {
           if (FIRST && ks == 0)
             acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], v16i{}, 0, 0, 0);
           else
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
   chunk.template operator()<true>(0);
   for (int c0 = kCK; c0 < C; c0 += kCK) chunk.template operator()<false>(c0);
 
-  // acc[i][j][4*g+v] = D[k = 32 i + 8 g + 4 h + v][t = 32 j + r] within the wave's 64 x 64
+  // acc[i][j][4*g+v] = D[k = 32 i + 8 g + 4 h + v][t = 32 j + r] within the wave's 64 (k) x kTT/2 (t)
   if constexpr (sizeof(MT) == 1) {
     __syncthreads();                     // LDS is reused as the [t][k] output block
     uint32_t* so = reinterpret_cast<uint32_t*>(smem);
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < JT; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
           uint32_t q[4];
@@ -176,7 +177,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
           // second operand, 4-7 of the first, 0x0c gives zero)
           const uint32_t lo = __builtin_amdgcn_perm(q[1], q[0], 0x0c0c0400u);
           const uint32_t hi = __builtin_amdgcn_perm(q[3], q[2], 0x04000c0cu);
-          const int tl = wt * 64 + j * 32 + r;
+          const int tl = wt * (kTT / 2) + j * 32 + r;
           const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
           so[tl * kORow + (kl >> 2)] = lo | hi;
         }
@@ -197,10 +198,11 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
     __syncthreads();
     constexpr int kORowB = kKT * 2 + 16;
     static_assert(kTT * kORowB <= kSm);
+    static_assert(kTT * (kKT + 4) <= kSm);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < JT; ++j)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
           uint32_t q[4];
@@ -209,7 +211,7 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
           uint2 pk;                      // low halves of q0, q1 and of q2, q3
           pk.x = __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
           pk.y = __builtin_amdgcn_perm(q[3], q[2], 0x05040100u);
-          const int tl = wt * 64 + j * 32 + r;
+          const int tl = wt * (kTT / 2) + j * 32 + r;
           const int kl = wk * 64 + i * 32 + 8 * gq + 4 * h;
           *reinterpret_cast<uint2*>(smem + tl * kORowB + kl * 2) = pk;
         }
@@ -229,8 +231,8 @@ __global__ __launch_bounds__(256) void k_contract(const int8_t* __restrict__ U,
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int tl = wt * 64 + j * 32 + r;
+      for (int j = 0; j < JT; ++j) {
+        const int tl = wt * (kTT / 2) + j * 32 + r;
         if (tl >= trows) continue;
         MT* mrow = Mp + (uint32_t)tl * (uint32_t)K;
 #pragma unroll
@@ -389,9 +391,9 @@ hipError_t launch_operand_transforms(const Geometry& g, bool leg, const int8_t* 
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,
-                           int m_bits, const MultTable& mult, hipStream_t st) {
-  if ((long)g.T * g.K == 0) return hipSuccess;
+template <int kTT>
+static hipError_t contract_tt(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,
+                              int m_bits, const MultTable& mult, hipStream_t st) {
   const int n = g.m + 2;
   const int tblocks = (g.T + kTT - 1) / kTT, kblocks = (g.K + kKT - 1) / kKT;
   int tgroups = 1;                                   // smallest split that fills 8 XCDs evenly
@@ -402,15 +404,28 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
   if (nblocks > 0x7fffffffL) return hipErrorInvalidValue;
   dim3 grid((unsigned)nblocks);
   if (m_bits == 8)
-    wino_launch((k_contract<int8_t, 128>), grid, dim3(256), st, U, V, (int8_t*)Mo, g.T, g.C,
+    wino_launch((k_contract<int8_t, 128, kTT>), grid, dim3(256), st, U, V, (int8_t*)Mo, g.T, g.C,
                        g.K, tblocks, kblocks, tgroups, tpg, units, mult, 127.f);
   else if (m_bits == 9)
-    wino_launch((k_contract<int16_t, 128>), grid, dim3(256), st, U, V, (int16_t*)Mo, g.T,
+    wino_launch((k_contract<int16_t, 128, kTT>), grid, dim3(256), st, U, V, (int16_t*)Mo, g.T,
                        g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 255.f);
   else
-    wino_launch((k_contract<int32_t, 128>), grid, dim3(256), st, U, V, (int32_t*)Mo, g.T,
+    wino_launch((k_contract<int32_t, 128, kTT>), grid, dim3(256), st, U, V, (int32_t*)Mo, g.T,
                        g.C, g.K, tblocks, kblocks, tgroups, tpg, units, mult, 0.f);
   return hipGetLastError();
+}
+
+hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,
+                           int m_bits, const MultTable& mult, hipStream_t st) {
+  if ((long)g.T * g.K == 0) return hipSuccess;
+  // Fewer than two 128-row tiles per compute unit: halve the tile, so that twice as many,
+  // shorter, work groups share each compute unit (measured: 7 % on a 4x4 x 512-channel
+  // layer with 256 tiles; no gain from about two tiles per compute unit on).
+  const int n = g.m + 2;
+  const long big_tiles = (long)n * n * ((g.T + 127) / 128) * ((g.K + kKT - 1) / kKT);
+  const bool small = big_tiles < 2 * 256;
+  return small ? contract_tt<64>(g, U, V, Mo, m_bits, mult, st)
+               : contract_tt<128>(g, U, V, Mo, m_bits, mult, st);
 }
 
 hipError_t launch_output_transform(const Geometry& g, bool leg, const void* Mq, int m_bits,
