@@ -126,6 +126,56 @@ def layer_times(wn, si, torch, dev, name, steps):
     return res
 
 
+def resnet18_stack(wn, si, torch, dev, steps, N=256):
+    """The 14 stride-1 3x3 layers of the CIFAR ResNet18 (stem 3->64 at 32x32, 4 x 64 at 32x32,
+    3 x 128 at 16x16, 3 x 256 at 8x8, 3 x 512 at 4x4), F(4x4,3x3) Legendre int8 with ReLU,
+    int8 activations handed from layer to layer inside a resolution stage, filters transformed
+    ahead of time, scales chosen by wino_calibrate, fused = AUTO.  Returns the time of one pass
+    over all 14 layers."""
+    import numpy as np
+    layers, stage_in, ops = [], {}, 0.0
+    for li, (C, K, HW) in enumerate(si.RESNET18_STACK):
+        Cp = (C + 15) // 16 * 16                          # the stem's 3 channels are zero-padded
+        if HW not in stage_in:                            # a stage starts from a fresh seeded tensor
+            x0, _ = si.make_real(N, HW, HW, C, 1, seed=4)
+            if Cp != C:
+                x0 = np.concatenate([x0, np.zeros(x0.shape[:3] + (Cp - C,), np.float32)], axis=3)
+            xq, s_x = si.cast_int8(x0)
+            stage_in[HW] = (torch.from_numpy(xq).to(dev), float(s_x))
+            x, s_in = stage_in[HW]
+        _, w0 = si.make_real(1, 1, 1, C, K, seed=400 + HW + li)
+        if Cp != C:
+            w0 = np.concatenate([w0, np.zeros((K, Cp - C, 3, 3), np.float32)], axis=1)
+        wq, s_w = si.cast_int8(w0)
+        w = torch.from_numpy(wq).to(dev)
+        desc = wn.ConvDesc(N, HW, HW, Cp, K, m=4, out_type=wn.OUT_I8, relu=1)
+        y = torch.empty((N, HW, HW, K), dtype=torch.int8, device=dev)
+        cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        sc = wn.wino_calibrate(desc, x, w, y, s_in, float(s_w), cws)
+        del cws
+        V = torch.empty((36, K, Cp), dtype=torch.int8, device=dev)
+        wn.wino_weight_transform(desc, w, V, sc)
+        run = wn.ConvDesc(N, HW, HW, Cp, K, m=4, out_type=wn.OUT_I8, relu=1,
+                          weights_pretransformed=1, fused=wn.FUSED_AUTO)
+        ws = torch.empty(wn.wino_workspace_bytes(run), dtype=torch.uint8, device=dev)
+        layers.append((run, x, V, y, sc, ws))
+        ops += 2.0 * N * HW * HW * C * K * 9
+        x, s_in = y, sc.s_y                               # this layer's codes feed the next one
+    def once():
+        for run, xi, V, y, sc, ws in layers:
+            wn.wino_conv2d(run, xi, V, y, sc, ws)
+    for _ in range(5):
+        once()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        once()
+    torch.cuda.synchronize()
+    dt = (time.perf_counter() - t0) / steps
+    return {"ms_per_pass": dt * 1e3, "TOPS_direct_equiv": ops / dt / 1e12, "layers": len(layers),
+            "N": N, "note": "int8 in, int8 + ReLU out, filters pretransformed, fused = AUTO"}
+
+
 def cpu_baseline(wl, min_seconds=12.0):
     """The oracle, as it stands, timed on the host cores: whole passes over the full
     workload, repeated until about min_seconds of CPU work have been spent."""
@@ -438,6 +488,7 @@ def main():
             if name == wl.name:
                 continue
             out["other_workloads"][name] = layer_times(wn, si, torch, dev, name, 50)
+        out["resnet18_stack"] = resnet18_stack(wn, si, torch, dev, 20)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(si.WORKLOADS[args.workload])
     print(json.dumps(out))
