@@ -126,9 +126,8 @@ typedef struct {
  * 0 <= m_shift[p] <= WINO_MAX_M_SHIFT.  The powers of two keep the output
  * bracket in exact integers: it is fed with code << (smax - m_shift[p]) at the
  * common scale s_m / 2^smax, smax = max_p m_shift[p].  Needs bits_hadamard 8 or
- * 9 and F32 or I8 output; not available in the fused variant (AUTO then runs
- * one kernel per stage) or the flex calls.  Only the first n*n entries of the
- * arrays are read. */
+ * 9 and F32 or I8 output; not available in the flex calls.  Only the first
+ * n*n entries of the arrays are read. */
 enum { WINO_MAX_M_SHIFT = 8 };
 typedef struct {
   float s_x, s_x1, s_u, s_w, s_w1, s_v, s_m, s_m1, s_y;

@@ -703,12 +703,10 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   if (int rc = make_plan(d, &p)) return rc;
   if (p.g.T == 0 || p.g.K == 0) return WINO_OK;   // no output element exists
   if (int rc = check_per_point(d, s)) return rc;
-  const bool fusable = !(p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32 ||
-                         (s && s->per_point));
+  const bool fusable = !(p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32);
   if (d->fused == WINO_FUSED_ON && !fusable)
     return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "
-                                   "bits_hadamard 8 or 9, fp32 or int8 output and per-tensor "
-                                   "scales");
+                                   "bits_hadamard 8 or 9 and fp32 or int8 output");
   if (d->fused != WINO_FUSED_OFF && d->fused != WINO_FUSED_ON && d->fused != WINO_FUSED_AUTO)
     return fail(WINO_EINVAL, "unknown fused mode %d", d->fused);
   // AUTO: the fused kernel recomputes the input transform once per 64 output
@@ -742,13 +740,14 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
     if (int rc = aligned(V, 16, "V")) return rc;
     StageMults in_mu, out_mu;
     MultTable m_mult;
+    ShiftTable sh;
     double s_m;
     if (int rc = input_mults(p, s, &in_mu)) return rc;
-    if (int rc = contract_mults(p, s, &m_mult, nullptr, &s_m)) return rc;
+    if (int rc = contract_mults(p, s, &m_mult, &sh, &s_m)) return rc;
     if (int rc = output_mults(p, d, s, &out_mu, nullptr)) return rc;
     hipError_t e = launch_fused(p.g, p.two_brackets, (const int8_t*)x, (const int8_t*)V, y,
-                                p.m_bits, d->out_type, d->relu != 0, in_mu, out_mu, m_mult.v[0],
-                                (hipStream_t)hip_stream);
+                                p.m_bits, d->out_type, d->relu != 0, in_mu, out_mu, m_mult,
+                                s->per_point ? &sh : nullptr, (hipStream_t)hip_stream);
     return e == hipSuccess ? WINO_OK : fail_hip(e, "fused launch");
   }
   void* U = ws;

@@ -37,12 +37,15 @@ __device__ __forceinline__ int sw(int tile, int byte) {
   return tile * kFC + ((((byte >> 4) ^ ((tile >> 1) & 3)) << 4) | (byte & 15));
 }
 
-template <int M, bool LEG, typename MT, int OUT, bool SINGLE>
+// PP: per-point scales -- the cast of point p uses mm.v[p], and its codes enter
+// the output bracket shifted left by sh.v[p] (<= kMaxMShift, priced into the
+// bounds).  Without PP every entry of mm is the same and sh is not read.
+template <int M, bool LEG, typename MT, int OUT, bool SINGLE, bool PP>
 __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* __restrict__ x,
                                                const int8_t* __restrict__ V,
                                                void* __restrict__ yv, Geometry g, StageMults in_mu,
-                                               StageMults out_mu, float m_mult, int relu,
-                                               int tblocks) {
+                                               StageMults out_mu, MultTable mm, ShiftTable sh,
+                                               int relu, int tblocks) {
   constexpr int n = M + 2, n2 = n * n;
   constexpr int KB = sizeof(MT) == 1 ? 64 : 32;      // output channels per work group
   constexpr int NKB = KB / 16;                       // 16-wide MFMA column blocks
@@ -86,6 +89,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
       for (int b = 0; b < NKB; ++b) acc[a][b] = v4i{0, 0, 0, 0};
   }
   auto park = [&](const v4i (&av)[NKB], int p) {       // cast one point, store as M_s[p][tile][k]
+    const float m_mult = PP ? mm.v[p] : mm.v[0];       // p is wave-uniform
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) {
       int q[4];
@@ -205,6 +209,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
       static_for<0, n>([&](auto j) {
         mi[i][j] = (int)*reinterpret_cast<const MT*>(
             smem + (decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, kl * (int)sizeof(MT)));
+        if constexpr (PP) mi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
       });
     });
     const long ybase = (((long)b * g.H + ty_m) * g.W + tx_m) * g.K + k;
@@ -238,7 +243,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
         });
       });
     };
-    constexpr int64_t IN_MAX = sizeof(MT) == 1 ? 127 : 255;
+    constexpr int64_t IN_MAX = (sizeof(MT) == 1 ? 127 : 255) << (PP ? kMaxMShift : 0);
     if constexpr (LEG) {
       acc_t<TB::PinvT, IN_MAX> num1[n][n];
       sandwich<TB::PinvT, IN_MAX>(mi, num1);
@@ -255,49 +260,63 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
   }
 }
 
-template <int M, bool LEG, typename MT>
+template <int M, bool LEG, typename MT, bool PP>
 static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, void* y, int out_type,
                            bool relu, const StageMults& in_mu, const StageMults& out_mu,
-                           float m_mult, hipStream_t st) {
+                           const MultTable& mm, const ShiftTable& sh, hipStream_t st) {
   constexpr int KB = sizeof(MT) == 1 ? 64 : 32;
   const int tblocks = (g.T + kFT - 1) / kFT, kblocks = (g.K + KB - 1) / KB;
   dim3 grid((unsigned)(tblocks * kblocks));
   const int r = relu ? 1 : 0;
   const bool single = g.C <= kFC;
   if (out_type == 0 && single)
-    wino_launch((k_fused<M, LEG, MT, 0, true>), grid, dim3(512), st, x, V, y, g, in_mu,
-                       out_mu, m_mult, r, tblocks);
+    wino_launch((k_fused<M, LEG, MT, 0, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
+                       out_mu, mm, sh, r, tblocks);
   else if (out_type == 0)
-    wino_launch((k_fused<M, LEG, MT, 0, false>), grid, dim3(256), st, x, V, y, g, in_mu,
-                       out_mu, m_mult, r, tblocks);
+    wino_launch((k_fused<M, LEG, MT, 0, false, PP>), grid, dim3(256), st, x, V, y, g, in_mu,
+                       out_mu, mm, sh, r, tblocks);
   else if (single)
-    wino_launch((k_fused<M, LEG, MT, 2, true>), grid, dim3(512), st, x, V, y, g, in_mu,
-                       out_mu, m_mult, r, tblocks);
+    wino_launch((k_fused<M, LEG, MT, 2, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
+                       out_mu, mm, sh, r, tblocks);
   else
-    wino_launch((k_fused<M, LEG, MT, 2, false>), grid, dim3(256), st, x, V, y, g, in_mu,
-                       out_mu, m_mult, r, tblocks);
+    wino_launch((k_fused<M, LEG, MT, 2, false, PP>), grid, dim3(256), st, x, V, y, g, in_mu,
+                       out_mu, mm, sh, r, tblocks);
   return hipGetLastError();
+}
+
+template <int M, bool LEG>
+static hipError_t fused_ml(const Geometry& g, const int8_t* x, const int8_t* V, void* y, int m_bits,
+                           int out_type, bool relu, const StageMults& in_mu,
+                           const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
+                           hipStream_t st) {
+  const ShiftTable none{};
+  if (sh)
+    return m_bits == 8
+               ? fused_mt<M, LEG, int8_t, true>(g, x, V, y, out_type, relu, in_mu, out_mu, mm, *sh, st)
+               : fused_mt<M, LEG, int16_t, true>(g, x, V, y, out_type, relu, in_mu, out_mu, mm, *sh, st);
+  return m_bits == 8
+             ? fused_mt<M, LEG, int8_t, false>(g, x, V, y, out_type, relu, in_mu, out_mu, mm, none, st)
+             : fused_mt<M, LEG, int16_t, false>(g, x, V, y, out_type, relu, in_mu, out_mu, mm, none, st);
 }
 
 template <int M>
 static hipError_t fused_m(const Geometry& g, bool leg, const int8_t* x, const int8_t* V, void* y,
                           int m_bits, int out_type, bool relu, const StageMults& in_mu,
-                          const StageMults& out_mu, float m_mult, hipStream_t st) {
-  if (leg)
-    return m_bits == 8 ? fused_mt<M, true, int8_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st)
-                       : fused_mt<M, true, int16_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st);
-  return m_bits == 8 ? fused_mt<M, false, int8_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st)
-                     : fused_mt<M, false, int16_t>(g, x, V, y, out_type, relu, in_mu, out_mu, m_mult, st);
+                          const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
+                          hipStream_t st) {
+  return leg ? fused_ml<M, true>(g, x, V, y, m_bits, out_type, relu, in_mu, out_mu, mm, sh, st)
+             : fused_ml<M, false>(g, x, V, y, m_bits, out_type, relu, in_mu, out_mu, mm, sh, st);
 }
 
 hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x, const int8_t* V,
                         void* y, int m_bits, int out_type, bool relu, const StageMults& in_mu,
-                        const StageMults& out_mu, float m_mult, hipStream_t st) {
+                        const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
+                        hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
   if ((m_bits != 8 && m_bits != 9) || (out_type != 0 && out_type != 2)) return hipErrorInvalidValue;
   switch (g.m) {
-    case 2: return fused_m<2>(g, legendre_inner, x, V, y, m_bits, out_type, relu, in_mu, out_mu, m_mult, st);
-    case 4: return fused_m<4>(g, legendre_inner, x, V, y, m_bits, out_type, relu, in_mu, out_mu, m_mult, st);
+    case 2: return fused_m<2>(g, legendre_inner, x, V, y, m_bits, out_type, relu, in_mu, out_mu, mm, sh, st);
+    case 4: return fused_m<4>(g, legendre_inner, x, V, y, m_bits, out_type, relu, in_mu, out_mu, mm, sh, st);
   }
   return hipErrorInvalidValue;
 }

@@ -157,9 +157,11 @@ hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const
 
 // Fused variant (input transform + contraction + output transform in one kernel);
 // V is the transformed filter tensor.  m = 2 or 4, m_bits 8 or 9, out_type 0 or 2.
+// mm: cast multiplier of the contraction per point; sh: per-point shifts or null.
 hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x, const int8_t* V,
                         void* y, int m_bits, int out_type, bool relu, const StageMults& in_mu,
-                        const StageMults& out_mu, float m_mult, hipStream_t st);
+                        const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
+                        hipStream_t st);
 
 // Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
 // 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8).

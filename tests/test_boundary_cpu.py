@@ -180,7 +180,5 @@ def test_per_point_scales_are_validated_before_any_launch():
     assert b"m_shift" in lib.wino_last_error()
     neg = wn.Scales.from_dict({"s_u": -np.ones((6, 6)), "s_v": np.ones((6, 6))})
     assert lib.wino_input_transform(C.byref(d), fake, fake, C.byref(neg), None) == -1
-    dfused = wn.ConvDesc(1, 8, 8, 16, 16, fused=1)
-    assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(pp), fake, 1 << 30, None) == -2
     fm = wn.FlexMatrices(np.ones((6, 3)), np.ones((6, 6)), np.ones((4, 6)))
     assert lib.wino_flex_input_transform(C.byref(d), C.byref(fm), fake, fake, C.byref(pp), None) == -2

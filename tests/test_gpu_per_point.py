@@ -34,6 +34,21 @@ def test_per_point_layer_matches_the_oracle(m, base, shape, bh, out_type, relu, 
     assert_layer_parity(ora, got, out_type)
 
 
+@pytest.mark.parametrize("m,base,shape,bh,out_type,relu", [
+    (4, "canonical", (2, 8, 8, 64, 64), 8, "f32", False),      # one channel chunk
+    (4, "legendre", (3, 9, 7, 48, 80), 9, "i8", True),
+    (4, "canonical", (1, 8, 8, 144, 32), 8, "i8", True),        # several channel chunks
+    (2, "legendre", (2, 6, 6, 32, 16), 8, "f32", False),
+])
+def test_fused_variant_with_per_point_scales(m, base, shape, bh, out_type, relu):
+    N, H, W, C, K = shape
+    xq, wq, s_x, s_w = small_layer(N, H, W, C, K, seed=600 + m + C, outliers=0.01)
+    kw = dict(m=m, base=base, bits_hadamard=bh, out_type=out_type, relu=relu, per_point=True)
+    ora, sc = oracle_layer(xq, wq, s_x, s_w, **kw)
+    got = gpu_layer(xq, wq, sc, fused=True, **kw)
+    assert_layer_parity(ora, got, out_type)
+
+
 def test_per_point_on_the_benchmark_layer_is_far_more_accurate():
     """cfg4a shape with a smaller batch, canonical base: the reason the option exists."""
     from oracle import direct
