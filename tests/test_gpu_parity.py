@@ -110,6 +110,15 @@ def test_channel_counts_that_are_multiples_of_256(m, base, shape, bh, out_type, 
                  out_type=out_type, relu=relu)
 
 
+@pytest.mark.parametrize("m,shape", [(4, (1, 113, 57, 32, 16)), (6, (1, 64, 200, 16, 32)),
+                                     (2, (2, 75, 75, 16, 16))])
+def test_large_ragged_images(m, shape):
+    """Many tiles per image, edges that are not multiples of m in either direction."""
+    N, H, W, C, K = shape
+    xq, wq, s_x, s_w = small_layer(N, H, W, C, K, seed=130 + m)
+    run_case(xq, wq, s_x, s_w, whole=True, m=m, base="legendre", out_type="i8", relu=True)
+
+
 @pytest.mark.parametrize("m", [2, 4, 6])
 def test_operand_transforms_in_one_launch_equal_the_two_calls(m):
     import torch
@@ -144,3 +153,37 @@ def test_empty_batch_is_a_no_op():
     wn.wino_contract(desc, e8, ws, e8, sc)
     wn.wino_output_transform(desc, e8, y, sc)
     torch.cuda.synchronize()
+
+
+def test_largest_exact_contraction_result():
+    """bits_hadamard = 32 at the channel limit (C = 1040): saturated codes give
+    127 * 127 * 1040 = 16 774 160 < 2^24, the largest value that the output bracket
+    still converts to fp32 exactly."""
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    N, H, W, C, K, m = 1, 4, 8, 1040, 16, 4
+    desc = wn.ConvDesc(N, H, W, C, K, m=m, base=wn.BASE_CANONICAL, bits_hadamard=32)
+    n2, T = 36, desc.tiles
+    rng = np.random.default_rng(5)
+    sign_u = rng.choice([-127, 127], size=(n2, T, 1)).astype(np.int8)
+    sign_v = rng.choice([-127, 127], size=(n2, K, 1)).astype(np.int8)
+    Uq = np.broadcast_to(sign_u, (n2, T, C)).copy()
+    Vq = np.broadcast_to(sign_v, (n2, K, C)).copy()
+    sc = {"s_x": 1.0, "s_w": 1.0, "s_u": 0.5, "s_v": 0.25}
+    cfg = oq.LayerConfig(m=m, base="canonical", bits_hadamard=32)
+    out = {}
+    Mq, s_m = oq.contraction(Uq.astype(np.int64), Vq.astype(np.int64), cfg, dict(sc), out)
+    assert np.abs(Mq).max() == 127 * 127 * 1040
+    y_ref = oq.output_transform(Mq, s_m, (N, H, W), cfg, oq.StageMatrices(cfg), dict(sc), out)
+    U = torch.from_numpy(Uq).to(dev)
+    V = torch.from_numpy(Vq).to(dev)
+    M = torch.zeros((n2, T, K), dtype=torch.int32, device=dev)
+    y = torch.zeros((N, H, W, K), dtype=torch.float32, device=dev)
+    gsc = wn.Scales.from_dict(sc)
+    wn.wino_contract(desc, U, V, M, gsc)
+    wn.wino_output_transform(desc, M, y, gsc)
+    torch.cuda.synchronize()
+    assert np.array_equal(M.cpu().numpy().astype(np.int64), Mq)
+    err = np.abs(y.cpu().numpy().astype(np.float64) - y_ref).max()
+    assert err <= 1e-5 * np.abs(y_ref).max()
