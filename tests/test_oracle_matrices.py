@@ -33,6 +33,48 @@ def read_counts():
     return out
 
 
+def read_blocks(name):
+    blocks, cur = {}, None
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            if line.startswith("["):
+                cur = blocks.setdefault(line.strip("[]"), [])
+            else:
+                cur.append([Fraction(tok) for tok in line.split()])
+    return blocks
+
+
+def test_F43_equals_the_published_matrix_set():
+    """The construction (all Lagrange denominators in G, no sign normalisation) reproduces
+    the widely used F(4x4,3x3) matrices entry for entry."""
+    pub = read_blocks("toomcook_F43_published.txt")
+    M = mx.Matrices(4, 3)
+    assert M.BT == pub["BT"] and M.G == pub["G"] and M.AT == pub["AT"]
+
+
+def test_F23_equals_the_published_set_up_to_row_signs():
+    """For F(2x2,3x3) the published matrices (B^T rows [1,0,-1,0], [0,1,1,0], [0,-1,1,0],
+    [0,1,0,-1]; G rows [1,0,0], [1/2,1/2,1/2], [1/2,-1/2,1/2], [0,0,1]; A^T rows [1,1,1,0],
+    [0,1,-1,-1]) differ from this construction only by a sign on the rows of points 0 and
+    infinity, applied to G (or A^T) and B^T together, which leaves every product unchanged."""
+    F = Fraction
+    pub_BT = [[1, 0, -1, 0], [0, 1, 1, 0], [0, -1, 1, 0], [0, 1, 0, -1]]
+    pub_G = [[F(1), 0, 0], [F(1, 2), F(1, 2), F(1, 2)], [F(1, 2), F(-1, 2), F(1, 2)], [0, 0, F(1)]]
+    pub_AT = [[1, 1, 1, 0], [0, 1, -1, -1]]
+    M = mx.Matrices(2, 3)
+    for j in range(4):
+        sb = 1 if M.BT[j] == [F(v) for v in pub_BT[j]] else -1
+        assert M.BT[j] == [sb * F(v) for v in pub_BT[j]]
+        sg = 1 if M.G[j] == [F(v) for v in pub_G[j]] else -1
+        assert M.G[j] == [sg * F(v) for v in pub_G[j]]
+        sa = 1 if [M.AT[i][j] for i in range(2)] == [F(pub_AT[i][j]) for i in range(2)] else -1
+        assert [M.AT[i][j] for i in range(2)] == [sa * F(pub_AT[i][j]) for i in range(2)]
+        assert sb * sg * sa == 1                   # the three signs of a point cancel
+
+
 def test_PT_equals_printed_matrix():
     # Section 4.1, first displayed matrix.
     assert mx.legendre_PT(6) == read_matrix("legendre_PT_6x6.txt")
