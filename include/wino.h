@@ -98,7 +98,7 @@ typedef struct {
                                  U, V, M, y are float in the same layouts, scales
                                  are ignored (may be null), output is fp32        */
   int bits_hadamard;          /* 8 | 9 | 32: width kept for the contraction result
-                                 (Section 5: "Hadamard product on 9 bits")        */
+                                 (Section 5: the Hadamard stage kept on 9 bits)   */
   int inner_quant;            /* Legendre only: casts on the inner brackets of
                                  eq. 4 (1) or brackets multiplied out (0)         */
   int out_type;               /* WINO_OUT_*; I32 needs an integer A^T (canonical

@@ -1,7 +1,7 @@
 """Quantised Winograd convolution layer, stage by stage (canonical and Legendre).
 
 Oracle code (test infrastructure).  It follows the data flow of eq. 3 / eq. 4
-with a symmetric per-tensor cast "before and after all transformations"
+with a symmetric per-tensor cast on both sides of every transformation
 (Section 4.2): a cast sits after every bracket of eq. 4, i.e. on
 
     x, w                                   (inputs of the layer)
