@@ -234,10 +234,11 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
             const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
             if constexpr (OUT == 0) {
               float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * out_mu.outer.v[idx];
-              (static_cast<float*>(yv) + ybase)[rel] = relu ? fmaxf(v, 0.f) : v;
+              __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ybase + rel);
             } else {
               int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), out_mu.outer.v[idx], 127.f);
-              (static_cast<int8_t*>(yv) + ybase)[rel] = (int8_t)(relu ? max(v, 0) : v);
+              __builtin_nontemporal_store((int8_t)(relu ? max(v, 0) : v),
+                                          static_cast<int8_t*>(yv) + ybase + rel);
             }
           }
         });

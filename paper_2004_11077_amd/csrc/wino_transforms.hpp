@@ -290,7 +290,8 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
   for (int it = 0; it < (n2 + 15) / 16; ++it) {
     const int p = it * 16 + prow;
     if (p < n2)
-      *reinterpret_cast<v4i*>(vb + (long)p * KC) = *reinterpret_cast<const v4i*>(s_v + p * 256 + u * 16);
+      __builtin_nontemporal_store(*reinterpret_cast<const v4i*>(s_v + p * 256 + u * 16),
+                                  reinterpret_cast<v4i*>(vb + (long)p * KC));
   }
 }
 
@@ -386,8 +387,8 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   for (int it = 0; it < (n2 + 15) / 16; ++it) {
     const int p = it * 16 + prow;
     if (p < n2 && uok)
-      *reinterpret_cast<v4i*>(ub + (long)p * total) =
-          *reinterpret_cast<const v4i*>(s_out + p * 256 + u * 16);
+      __builtin_nontemporal_store(*reinterpret_cast<const v4i*>(s_out + p * 256 + u * 16),
+                                  reinterpret_cast<v4i*>(ub + (long)p * total));
   }
 }
 
@@ -482,7 +483,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
       const int p = it * 16 + prow;
       if (p < n2) {
         v4i v = {0, 0, 0, 0};
-        if (uok) v = *reinterpret_cast<const v4i*>(Mq + (long)p * total + ug);
+        if (uok) v = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(Mq + (long)p * total + ug));
         *reinterpret_cast<v4i*>(s_in + p * 256 + u * 16) = v;
       }
     }
@@ -538,13 +539,14 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
           const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
           if constexpr (OUT == 0) {
             float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * mu.outer.v[idx];
-            (static_cast<float*>(yv) + ytile + rel)[k] = relu ? fmaxf(v, 0.f) : v;
+            __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ytile + rel + k);
           } else if constexpr (OUT == 1) {
             int v = (int)num[i][j];
-            (static_cast<int*>(yv) + ytile + rel)[k] = relu ? max(v, 0) : v;
+            __builtin_nontemporal_store(relu ? max(v, 0) : v, static_cast<int*>(yv) + ytile + rel + k);
           } else {
             int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), mu.outer.v[idx], 127.f);
-            (static_cast<int8_t*>(yv) + ytile + rel)[k] = (int8_t)(relu ? max(v, 0) : v);
+            __builtin_nontemporal_store((int8_t)(relu ? max(v, 0) : v),
+                                        static_cast<int8_t*>(yv) + ytile + rel + k);
           }
         }
       });
