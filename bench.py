@@ -26,9 +26,9 @@ VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
 # a plain device copy of known size in the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
 MEASURED_TRAFFIC_BYTES = {
-    "cfg4a_f4_c256": {"operand_transforms": (7181.3 + 11520.0) * 1024,
-                      "contraction": (13938.2 + 9216.0) * 1024,
-                      "output_transform": (9348.1 + 16384.0) * 1024},
+    "cfg4a_f4_c256": {"operand_transforms": (7175.3 + 11520.0) * 1024,
+                      "contraction": (13936.2 + 9216.0) * 1024,
+                      "output_transform": (9334.1 + 16384.0) * 1024},
 }
 
 
