@@ -499,7 +499,8 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     const MT* mb = Mq + (long)t * g.K + k;
     static_for<0, n>([&](auto i) {
       static_for<0, n>([&](auto j) {
-        xi[i][j] = (int)mb[(long)(decltype(i)::value * n + decltype(j)::value) * total];
+        xi[i][j] = (int)__builtin_nontemporal_load(
+            mb + (long)(decltype(i)::value * n + decltype(j)::value) * total);
       });
     });
   }
