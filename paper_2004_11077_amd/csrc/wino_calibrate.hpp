@@ -9,17 +9,19 @@
 
 namespace wino {
 
-// Block-wide maximum of v for each of R*R slots, merged into amax[] (global).
-template <int R, typename AccT>
-__device__ __forceinline__ void merge_amax(const AccT (&num)[R][R], bool active,
+// Block-wide maximum of |v| for each of the R*R entries of a result of
+// sandwich<T, IN_MAX>, merged into amax[] (global).
+template <const IMat& T, int64_t IN_MAX, typename AccT>
+__device__ __forceinline__ void merge_amax(const AccT (&num)[T.rows][T.rows], bool active,
                                            bool positive_only,
                                            unsigned long long* __restrict__ amax) {
   __shared__ unsigned long long s_max[kMaxPts];
   if (threadIdx.x < kMaxPts) s_max[threadIdx.x] = 0;
   __syncthreads();
+  constexpr int R = T.rows;
   static_for<0, R>([&](auto i) {
     static_for<0, R>([&](auto j) {
-      long long v = (long long)num[i][j];
+      long long v = (long long)entry<T, IN_MAX, decltype(i)::value, decltype(j)::value>(num[i][j]);
       if (positive_only)
         v = v > 0 ? v : 0;
       else
@@ -58,18 +60,18 @@ __global__ __launch_bounds__(256) void k_cal_weight(const int8_t* __restrict__ w
     acc_t<TB::GP, 127> num1[n][n];
     sandwich<TB::GP, 127>(wi, num1);
     if constexpr (PHASE == 1) {
-      merge_amax<n>(num1, active, false, amax);
+      merge_amax<TB::GP, 127>(num1, active, false, amax);
     } else {
       int w1[n][n];
       cast_result<TB::GP, 127>(num1, mu.inner, 127.f, w1);
       acc_t<TB::Pinv, 127> num2[n][n];
       sandwich<TB::Pinv, 127>(w1, num2);
-      merge_amax<n>(num2, active, false, amax);
+      merge_amax<TB::Pinv, 127>(num2, active, false, amax);
     }
   } else {
     acc_t<TB::G, 127> num[n][n];
     sandwich<TB::G, 127>(wi, num);
-    merge_amax<n>(num, active, false, amax);
+    merge_amax<TB::G, 127>(num, active, false, amax);
   }
 }
 
@@ -101,18 +103,18 @@ __global__ __launch_bounds__(256) void k_cal_input(const int8_t* __restrict__ x,
     acc_t<TB::PinvT, 127> num1[n][n];
     sandwich<TB::PinvT, 127>(xi, num1);
     if constexpr (PHASE == 1) {
-      merge_amax<n>(num1, active, false, amax);
+      merge_amax<TB::PinvT, 127>(num1, active, false, amax);
     } else {
       int x1[n][n];
       cast_result<TB::PinvT, 127>(num1, mu.inner, 127.f, x1);
       acc_t<TB::BPT, 127> num2[n][n];
       sandwich<TB::BPT, 127>(x1, num2);
-      merge_amax<n>(num2, active, false, amax);
+      merge_amax<TB::BPT, 127>(num2, active, false, amax);
     }
   } else {
     acc_t<TB::BT, 127> num[n][n];
     sandwich<TB::BT, 127>(xi, num);
-    merge_amax<n>(num, active, false, amax);
+    merge_amax<TB::BT, 127>(num, active, false, amax);
   }
 }
 
@@ -151,20 +153,20 @@ __global__ __launch_bounds__(256) void k_cal_output(const MT* __restrict__ Mq,
     acc_t<TB::PinvT, IN_MAX> num1[n][n];
     sandwich<TB::PinvT, IN_MAX>(xi, num1);
     if constexpr (PHASE == 1) {
-      merge_amax<n>(num1, active, false, amax);
+      merge_amax<TB::PinvT, IN_MAX>(num1, active, false, amax);
     } else {
       int m1[n][n];
       cast_result<TB::PinvT, IN_MAX>(num1, mu.inner, 127.f, m1);
       acc_t<TB::APT, 127> num2[M][M];
       sandwich<TB::APT, 127>(m1, num2);
       crop(num2);
-      merge_amax<M>(num2, active, relu != 0, amax);
+      merge_amax<TB::APT, 127>(num2, active, relu != 0, amax);
     }
   } else {
     acc_t<TB::AT, IN_MAX> num[M][M];
     sandwich<TB::AT, IN_MAX>(xi, num);
     crop(num);
-    merge_amax<M>(num, active, relu != 0, amax);
+    merge_amax<TB::AT, IN_MAX>(num, active, relu != 0, amax);
   }
 }
 

@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void k_flex_weight(const int8_t* __restrict__ 
     acc_t<TB::Pinv, 127> num2[n][n];
     sandwich<TB::Pinv, 127>(q, num2);
     if constexpr (MODE == kFlexCalInt) {
-      merge_amax<n>(num2, active, false, amax);
+      merge_amax<TB::Pinv, 127>(num2, active, false, amax);
       return;
     }
     cast_result<TB::Pinv, 127>(num2, mu.outer, 127.f, q);

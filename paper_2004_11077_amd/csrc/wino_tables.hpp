@@ -45,21 +45,16 @@ constexpr bool fits_bits(const IMat& t, int64_t in_max, int bits) {
   return b < ((__int128)1 << (bits - 1));
 }
 
+// Storage of a stage's results: int32_t where every entry fits, else 8-byte
+// slots (the transforms pick the arithmetic of each entry by its own bound).
 template <const IMat& T, int64_t IN_MAX>
 using acc_t = std::conditional_t<fits_bits(T, IN_MAX, 32), int32_t, int64_t>;
 
-// The bound holds entry by entry: |(N x N^T)[i][j]| <= in_max * |row i| * |row j|
-// (sums of absolute values), and so does every partial sum towards that entry.
-// Where the matrix as a whole needs 64-bit accumulators, most entries still fit
-// 32 bits (F(4,3) Legendre output bracket: all but the last one).
+// Sum of the absolute values of row i: |(N x)[i]| <= in_max * row_abs(i).
 constexpr int64_t row_abs(const IMat& t, int i) {
   int64_t s = 0;
   for (int a = 0; a < t.cols; ++a) s += t.N[i][a] < 0 ? -t.N[i][a] : t.N[i][a];
   return s;
-}
-template <const IMat& T, int64_t IN_MAX>
-constexpr bool entry_fits_i32(int i, int j) {
-  return (__int128)IN_MAX * row_abs(T, i) * row_abs(T, j) < ((__int128)1 << 31);
 }
 
 // Largest |M| the contraction may produce when it is passed on unquantised

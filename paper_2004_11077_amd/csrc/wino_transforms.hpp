@@ -103,11 +103,73 @@ constexpr bool coef_fit_i32(const IMat& t) {
   return true;
 }
 
-// Accumulator of the first (left) pass: |N x| <= IN_MAX * rowsum.
+// ---------------------------------------------------------------------------
+// Arithmetic kinds.  Every value of a sandwich N x N^T is an integer with a
+// compile-time bound; it is held in the cheapest type that is exact for it:
+//   kI32  below 2^31: 32-bit integer multiply-adds;
+//   kF64  below 2^53: a double.  Products and partial sums are integers below
+//         2^53, so fp64 fused multiply-adds are exact, cost half a 64-bit
+//         integer multiply-add, and the result converts to fp32 (round to
+//         nearest even, what the cast needs) in one instruction;
+//   kI64  the rest: 64-bit integers.
+// The bound holds entry by entry: |(N x N^T)[i][j]| <= in_max |row i| |row j|
+// (sums of absolute values) and |(N x)[i][b]| <= in_max |row i|, and so does
+// every partial sum towards them.
+// ---------------------------------------------------------------------------
+enum { kI32 = 0, kF64 = 1, kI64 = 2 };
+template <int KIND>
+using kind_t = std::conditional_t<KIND == kI32, int32_t, std::conditional_t<KIND == kF64, double, int64_t>>;
+
 template <const IMat& T, int64_t IN_MAX>
-using tmp_t = std::conditional_t<((__int128)IN_MAX * T.rowsum < ((__int128)1 << 31)) &&
-                                     coef_fit_i32(T),
-                                 int32_t, int64_t>;
+constexpr int raw_entry_kind(int i, int j) {
+  const __int128 b = (__int128)IN_MAX * row_abs(T, i) * row_abs(T, j);
+  return b < ((__int128)1 << 31) ? kI32 : b < ((__int128)1 << 53) ? kF64 : kI64;
+}
+// First pass, row i of N x.  A row that feeds a 64-bit entry stays integer (a
+// double would have to be converted back); 32 bits need 32-bit coefficients.
+template <const IMat& T, int64_t IN_MAX>
+constexpr int tmp_kind(int i) {
+  const __int128 b = (__int128)IN_MAX * row_abs(T, i);
+  if (b < ((__int128)1 << 31) && coef_fit_i32(T)) return kI32;
+  for (int j = 0; j < T.rows; ++j)
+    if (raw_entry_kind<T, IN_MAX>(i, j) == kI64) return kI64;
+  return b < ((__int128)1 << 53) ? kF64 : kI64;
+}
+// Second pass, entry (i, j): 32-bit arithmetic needs a 32-bit row i of N x.
+template <const IMat& T, int64_t IN_MAX>
+constexpr int entry_kind(int i, int j) {
+  const int k = raw_entry_kind<T, IN_MAX>(i, j);
+  return (k == kI32 && tmp_kind<T, IN_MAX>(i) != kI32) ? kF64 : k;
+}
+template <const IMat& T, int64_t IN_MAX>
+constexpr bool all_tmp_i32() {
+  for (int i = 0; i < T.rows; ++i)
+    if (tmp_kind<T, IN_MAX>(i) != kI32) return false;
+  return true;
+}
+
+// Storage: an array of int32_t where every value is kI32, else of 8-byte
+// slots that hold an int32 (sign-extended), the bits of a double, or an int64.
+template <typename Slot, typename V>
+__device__ __forceinline__ Slot to_slot(V v) {
+  if constexpr (sizeof(Slot) == 4)
+    return (int32_t)v;
+  else if constexpr (std::is_same_v<V, double>)
+    return __builtin_bit_cast(int64_t, v);
+  else
+    return (int64_t)v;
+}
+template <int KIND, typename Slot>
+__device__ __forceinline__ auto from_slot(Slot s) {
+  if constexpr (sizeof(Slot) == 4 || KIND == kI64)
+    return s;
+  else if constexpr (KIND == kF64)
+    return __builtin_bit_cast(double, s);
+  else
+    return (int32_t)s;
+}
+template <const IMat& T, int64_t IN_MAX>
+using tmp_slot_t = std::conditional_t<all_tmp_i32<T, IN_MAX>(), int32_t, int64_t>;
 
 // Rows of a Toom-Cook matrix built on points +p / -p come in pairs that agree
 // on the even columns and differ by sign on the odd ones: row_j[a] =
@@ -136,81 +198,86 @@ constexpr bool first_nz_par(const IMat& t, int i, int a, int par) {
   return true;
 }
 
-// sum over the columns a of parity PAR of T.N[ROW][a] * get(a); S24: |get(a)| < 2^23.
-template <const IMat& T, int ROW, int PAR, bool S24, typename AccT, class Get>
-__device__ __forceinline__ AccT row_dot(Get&& get) {
-  AccT acc = 0;
+// sum over the columns a of parity PAR of T.N[ROW][a] * get(a), accumulated in
+// kind KIND; get(a) yields an int32_t, a double or an int64_t.
+// S24: |get(a)| < 2^23 (32-bit kind only).
+template <const IMat& T, int ROW, int PAR, bool S24, int KIND, class Get>
+__device__ __forceinline__ kind_t<KIND> row_dot(Get&& get) {
+  kind_t<KIND> acc = 0;
   static_for<0, T.cols>([&](auto a) {
     constexpr int A = decltype(a)::value;
     constexpr int64_t c = T.N[ROW][A];
     if constexpr (c != 0 && (PAR == 2 || (A & 1) == PAR)) {
-      if constexpr (sizeof(AccT) == 4) {
-        if constexpr (first_nz_par(T, ROW, A, PAR))
-          acc = mulc<c, S24>((int32_t)get(a));
+      constexpr bool first = first_nz_par(T, ROW, A, PAR);
+      const auto v = get(a);
+      if constexpr (KIND == kI32) {
+        if constexpr (first)
+          acc = mulc<c, S24>((int32_t)v);
         else
-          acc = madc<c, S24>((int32_t)get(a), acc);
+          acc = madc<c, S24>((int32_t)v, acc);
+      } else if constexpr (KIND == kF64) {
+        if constexpr (first)
+          acc = (double)v * (double)c;
+        else
+          acc = __builtin_fma((double)v, (double)c, acc);
       } else {
-        acc += mulc_wide<c>(get(a));
+        static_assert(!std::is_same_v<std::decay_t<decltype(v)>, double>);
+        acc += mulc_wide<c>(v);
       }
     }
   });
   return acc;
 }
 
-// out[i] = sum_a T.N[i][a] * get(a) for every row i, with paired rows sharing
-// their even and odd parts.  put(i, value) receives the results.
-// LROW >= 0 says that this is the second pass of a sandwich, towards the
-// entries (LROW, i) of N x N^T with |x| <= IN_MAX: a 64-bit AccT is then used
-// only for the entries whose own bound needs it, the others are accumulated in
-// 32 bits (get must then return 32-bit values) and widened at the end.
-template <const IMat& T, bool S24, typename AccT, int64_t IN_MAX = 0, int LROW = -1, class Get,
-          class Put>
+// One pass of a sandwich with |x| <= IN_MAX: out[i] = sum_a T.N[i][a] * get(a)
+// for every row i, with paired rows sharing their even and odd parts (the rows
+// of a pair have equal bounds, hence one kind).  put(i, value) receives the
+// results.  LROW < 0: first pass, row i of N x, in tmp_kind(i).  LROW >= 0:
+// second pass, entry (LROW, i) of N x N^T, in entry_kind(LROW, i).
+template <const IMat& T, bool S24, int64_t IN_MAX, int LROW, class Get, class Put>
 __device__ __forceinline__ void apply_rows(Get&& get, Put&& put) {
   static_for<0, T.rows>([&](auto i) {
     constexpr int I = decltype(i)::value;
     constexpr int PJ = partner_of(T, I);
-    constexpr bool narrow = LROW >= 0 && sizeof(AccT) == 8 && entry_fits_i32<T, IN_MAX>(LROW < 0 ? 0 : LROW, I);
-    using A = std::conditional_t<narrow, int32_t, AccT>;
+    constexpr int KIND = LROW < 0 ? tmp_kind<T, IN_MAX>(I) : entry_kind<T, IN_MAX>(LROW < 0 ? 0 : LROW, I);
     if constexpr (PJ > I) {
-      const A e = row_dot<T, I, 0, S24, A>(get);
-      const A o = row_dot<T, I, 1, S24, A>(get);
-      put(i, (AccT)(e + o));
-      put(IC<PJ>{}, (AccT)(e - o));
+      const auto e = row_dot<T, I, 0, S24, KIND>(get);
+      const auto o = row_dot<T, I, 1, S24, KIND>(get);
+      put(i, e + o);
+      put(IC<PJ>{}, e - o);
     } else if constexpr (PJ < 0) {
-      put(i, (AccT)row_dot<T, I, 2, S24, A>(get));
+      put(i, row_dot<T, I, 2, S24, KIND>(get));
     }
   });
 }
 
 // num = N x N^T with N the compile-time integer matrix T.N (T.rows x T.cols)
-// and |x| <= IN_MAX.  Zero coefficients generate no code.
+// and |x| <= IN_MAX.  Zero coefficients generate no code.  The entries of num
+// are read back with entry<T, IN_MAX, I, J>().
 template <const IMat& T, int64_t IN_MAX, typename AccT, typename InT>
 __device__ __forceinline__ void sandwich(const InT (&x)[T.cols][T.cols],
                                          AccT (&num)[T.rows][T.rows]) {
+  static_assert(std::is_same_v<AccT, acc_t<T, IN_MAX>>);
   constexpr bool s1 = IN_MAX < (1 << 23);
   constexpr bool s2 = (__int128)IN_MAX * T.rowsum < (1 << 23);
-  using TmpT = std::conditional_t<sizeof(AccT) == 4, int32_t, tmp_t<T, IN_MAX>>;
+  using TmpT = tmp_slot_t<T, IN_MAX>;
   TmpT tmp[T.rows][T.cols];
   static_for<0, T.cols>([&](auto b) {                      // tmp = N x, column by column
-    apply_rows<T, s1, TmpT>([&](auto a) { return x[a][b]; },
-                            [&](auto i, TmpT v) { tmp[i][b] = v; });
+    apply_rows<T, s1, IN_MAX, -1>([&](auto a) { return x[a][b]; },
+                                  [&](auto i, auto v) { tmp[i][b] = to_slot<TmpT>(v); });
   });
   static_for<0, T.rows>([&](auto i) {                      // num = tmp N^T, row by row
-    constexpr int L = sizeof(TmpT) == 4 ? decltype(i)::value : -1;
-    apply_rows<T, s2, AccT, IN_MAX, L>([&](auto b) { return tmp[i][b]; },
-                                       [&](auto j, AccT v) { num[i][j] = v; });
+    constexpr int I = decltype(i)::value;
+    apply_rows<T, s2, IN_MAX, I>(
+        [&](auto b) { return from_slot<tmp_kind<T, IN_MAX>(I)>(tmp[i][b]); },
+        [&](auto j, auto v) { num[i][j] = to_slot<AccT>(v); });
   });
 }
 
-// The value of entry (I, J) of a sandwich result in the narrowest exact type:
-// a 64-bit entry whose own bound fits 32 bits is handed on as int32_t, which
-// makes its conversion to fp32 a single instruction.
+// The value of entry (I, J) of a sandwich result, in the type of its kind.
 template <const IMat& T, int64_t IN_MAX, int I, int J, typename AccT>
 __device__ __forceinline__ auto entry(AccT v) {
-  if constexpr (sizeof(AccT) == 8 && entry_fits_i32<T, IN_MAX>(I, J))
-    return (int32_t)v;
-  else
-    return v;
+  return from_slot<entry_kind<T, IN_MAX>(I, J)>(v);
 }
 
 // One symmetric cast: q = clamp(rint(v * mult), +-qmax), where rint rounds the
@@ -518,7 +585,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   // rounded conversion, but within 2 ulp, which the fp32 output tolerates; the
   // int8 output below keeps the exact single-rounding conversion.
   auto to_float_approx = [](auto v) -> float {
-    if constexpr (sizeof(v) == 8) {
+    if constexpr (std::is_same_v<decltype(v), int64_t>) {
       // v = hi * 2^32 + lo with a SIGNED low half, so small |v| has hi = 0
       const int32_t lo = (int32_t)v;
       const int32_t hi = (int32_t)(v >> 32) + (int32_t)((uint32_t)lo >> 31);
@@ -542,7 +609,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
             float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * mu.outer.v[idx];
             __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ytile + rel + k);
           } else if constexpr (OUT == 1) {
-            int v = (int)num[i][j];
+            int v = (int)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]);
             __builtin_nontemporal_store(relu ? max(v, 0) : v, static_cast<int*>(yv) + ytile + rel + k);
           } else {
             int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), mu.outer.v[idx], 127.f);
