@@ -24,6 +24,12 @@ Parity status of each part (what pins it besides itself):
                     tile, and by convergence to an fp64 evaluation of eq. 3 / eq. 4
                     with the same arbitrary matrices; outputs for trained
                     matrices: **parity unpinned** (none are published).
+* ``backward``      (gradients of one layer, straight-through casts) pinned: with
+                    unquantised operands it must equal the gradients of direct
+                    convolution written from the definition; adjoint identities
+                    against the forward oracle; exact finite differences; scalar
+                    loops.  The treatment of a cast in the backward pass is a
+                    reading (the paper gives none).
 * ``quantised`` absolute output values: **parity unpinned** by the paper (it
                     prints no worked numeric example; its quantisation figure is
                     missing).  They are pinned oracle <-> GPU only.

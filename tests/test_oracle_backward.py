@@ -1,0 +1,133 @@
+"""Pins of the backward-pass oracle (CPU only).
+
+The gradients of direct convolution, written out below from its definition
+y[n,h,w,k] = sum x[n,h+a-1,w+b-1,c] w[k,c,a,b], are the independent reference:
+with unquantised operands the Winograd backward pass must reproduce them.
+"""
+import numpy as np
+import pytest
+
+from oracle import backward as bw
+from oracle import matrices as mx
+from oracle import winograd as wg
+
+
+def direct_grads(x, w, dy):
+    """dx and dw of zero-padded stride-1 cross-correlation, by shifted slices."""
+    N, H, W, C = x.shape
+    K = w.shape[0]
+    xp = np.zeros((N, H + 2, W + 2, C))
+    xp[:, 1:H + 1, 1:W + 1, :] = x
+    dxp = np.zeros_like(xp)
+    dw = np.zeros_like(w)
+    for a in range(3):
+        for b in range(3):
+            # y[:, h, w, k] += xp[:, h + a, w + b, c] * w[k, c, a, b]
+            dw[:, :, a, b] = np.einsum("nhwc,nhwk->kc", xp[:, a:a + H, b:b + W, :], dy)
+            dxp[:, a:a + H, b:b + W, :] += np.einsum("nhwk,kc->nhwc", dy, w[:, :, a, b])
+    return dxp[:, 1:H + 1, 1:W + 1, :], dw
+
+
+def exact_operands(x, w, mats):
+    G, BT = bw._f64(mats.G), bw._f64(mats.BT)
+    n = mats.n
+    d = wg.extract_tiles(x, mats.m, mats.r)                         # [T,n,n,C]
+    U = np.einsum("ia,tabc,jb->ijtc", BT, d, BT).reshape(n * n, d.shape[0], x.shape[3])
+    V = np.einsum("ia,kcab,jb->ijkc", G, w, G).reshape(n * n, w.shape[0], w.shape[1])
+    return U, V
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+@pytest.mark.parametrize("shape", [(2, 8, 8, 3, 2), (1, 7, 9, 2, 3), (2, 5, 13, 1, 2)])
+def test_unquantised_backward_equals_direct_gradients(m, shape):
+    N, H, W, C, K = shape
+    rng = np.random.default_rng(100 * m + H)
+    x = rng.standard_normal((N, H, W, C))
+    w = rng.standard_normal((K, C, 3, 3))
+    dy = rng.standard_normal((N, H, W, K))
+    mats = mx.Matrices(m, 3)
+    U, V = exact_operands(x, w, mats)
+    got = bw.backward_layer(dy, U, V, x.shape, m)
+    dx, dw = direct_grads(x, w, dy)
+    scale = 10.0 ** {2: 0, 4: 1, 6: 3}[m]          # conditioning of the F(m,3) matrices in fp64
+    assert np.abs(got["dx"] - dx).max() <= 1e-12 * scale * np.abs(dx).max()
+    assert np.abs(got["dw"] - dw).max() <= 1e-12 * scale * np.abs(dw).max()
+
+
+@pytest.mark.parametrize("m", [2, 4, 6])
+def test_each_step_is_the_adjoint_of_its_forward_step(m):
+    rng = np.random.default_rng(7 + m)
+    mats = mx.Matrices(m, 3)
+    n = mats.n
+    N, H, W, C, K = 2, 9, 6, 3, 2
+    TH, TW = wg.tile_counts(H, W, m)
+    T = N * TH * TW
+    AT, BT, G = bw._f64(mats.AT), bw._f64(mats.BT), bw._f64(mats.G)
+    # output bracket + crop
+    M = rng.standard_normal((n * n, T, K))
+    dy = rng.standard_normal((N, H, W, K))
+    Y = np.einsum("ia,abtk,jb->tijk", AT, M.reshape(n, n, T, K), AT)
+    y = wg.scatter_tiles(Y, N, H, W, m)
+    assert np.isclose((y * dy).sum(), (M * bw.grad_M(dy, mats)).sum(), rtol=1e-11)
+    # tiling + input bracket
+    x = rng.standard_normal((N, H, W, C))
+    dU = rng.standard_normal((n * n, T, C))
+    d = wg.extract_tiles(x, m, 3)
+    U = np.einsum("ia,tabc,jb->ijtc", BT, d, BT).reshape(n * n, T, C)
+    assert np.isclose((U * dU).sum(), (x * bw.grad_x(dU, x.shape, mats)).sum(), rtol=1e-11)
+    # filter bracket
+    w = rng.standard_normal((K, C, 3, 3))
+    dV = rng.standard_normal((n * n, K, C))
+    V = np.einsum("ia,kcab,jb->ijkc", G, w, G).reshape(n * n, K, C)
+    assert np.isclose((V * dV).sum(), (w * bw.grad_w(dV, mats)).sum(), rtol=1e-11)
+
+
+def test_finite_differences_of_the_forward_oracle():
+    m = 4
+    rng = np.random.default_rng(11)
+    mats = mx.Matrices(m, 3)
+    x = rng.standard_normal((1, 6, 7, 2))
+    w = rng.standard_normal((3, 2, 3, 3))
+    dy = rng.standard_normal((1, 6, 7, 3))
+    U, V = exact_operands(x, w, mats)
+    g = bw.backward_layer(dy, U, V, x.shape, m)
+    loss = lambda xx, ww: float((wg.conv_eq3(xx, ww, mats) * dy).sum())
+    h = 1e-3                                       # the loss is bilinear: central differences are exact
+    for idx in [(0, 0, 0, 0), (0, 5, 6, 1), (0, 3, 2, 1)]:
+        e = np.zeros_like(x); e[idx] = h
+        assert np.isclose((loss(x + e, w) - loss(x - e, w)) / (2 * h), g["dx"][idx], rtol=1e-8, atol=1e-9)
+    for idx in [(0, 0, 0, 0), (2, 1, 2, 2), (1, 0, 1, 2)]:
+        e = np.zeros_like(w); e[idx] = h
+        assert np.isclose((loss(x, w + e) - loss(x, w - e)) / (2 * h), g["dw"][idx], rtol=1e-8, atol=1e-9)
+
+
+def test_contraction_gradients_by_scalar_loops_on_quantised_operands():
+    rng = np.random.default_rng(3)
+    n2, T, C, K = 16, 3, 2, 4
+    Uq = rng.integers(-127, 128, (n2, T, C))
+    Vq = rng.integers(-127, 128, (n2, K, C))
+    s_u_pt = rng.uniform(0.01, 0.1, n2)
+    s_v = 0.03
+    U = bw.dequantise(Uq, None, s_u_pt)
+    V = bw.dequantise(Vq, s_v)
+    dM = rng.standard_normal((n2, T, K))
+    dU, dV = bw.grad_U(dM, V), bw.grad_V(dM, U)
+    for p in range(n2):
+        for c in range(C):
+            for t in range(T):
+                ref = sum(dM[p, t, k] * (s_v * Vq[p, k, c]) for k in range(K))
+                assert abs(dU[p, t, c] - ref) < 1e-12 * max(1.0, abs(ref))
+            for k in range(K):
+                ref = sum(dM[p, t, k] * (s_u_pt[p] * Uq[p, t, c]) for t in range(T))
+                assert abs(dV[p, k, c] - ref) < 1e-12 * max(1.0, abs(ref))
+
+
+def test_gradient_outside_the_cropped_output_is_dropped():
+    # H = 5 with m = 4: the second tile row owns output rows 4..7, of which only
+    # row 4 exists.  Changing nothing but the tile padding must not change dM.
+    mats = mx.Matrices(4, 3)
+    rng = np.random.default_rng(5)
+    dy = rng.standard_normal((1, 5, 4, 1))
+    t = bw.output_grad_tiles(dy, 4)
+    assert t.shape == (2, 4, 4, 1)
+    assert np.array_equal(t[1, 0], dy[0, 4]) and not t[1, 1:].any()
