@@ -235,6 +235,34 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
                         const void* w, void* y, wino_scales_t* s, void* workspace,
                         size_t ws_bytes, void* hip_stream);
 
+/* Backward pass of one layer, for Winograd-aware training with fixed matrices
+ * (Sections 2 and 4.2 adopt that training method; the derivative of a cast is
+ * not given there and is taken as the identity, "straight-through").  Every
+ * step is then the adjoint of the matching step of eq. 3, and the base change
+ * of eq. 4 cancels, so d->base and d->inner_quant do not matter:
+ *     dM = A dY_t A^T                      per (tile, k), A = (A^T)^T, n x m
+ *     dU[p][t][c] = sum_k dM[p][t][k] * (s_v V[p][k][c])
+ *     dV[p][k][c] = sum_t dM[p][t][k] * (s_u U[p][t][c])
+ *     dx = sum over overlapping tiles of B dU_t B^T   (B = (B^T)^T)
+ *     dw = G^T dV G
+ * dy [N][H][W][K], dx [N][H][W][C], dw [K][C][3][3]: fp32 device tensors,
+ * gradients with respect to the REAL output, input (s_x * code) and weights
+ * (s_w * code).  U [n*n][T][C], V [n*n][K][C]: the int8 codes the forward pass
+ * contracted (device).  s (host): only s_u, s_v (or, with per_point, s_u_pt,
+ * s_v_pt) are read.  All arithmetic is fp32 (fp32 matrix instructions for the
+ * two contractions); sums over tiles are taken in a fixed order, so results
+ * are reproducible.  Int8 path only (d->bits_in = 8).  Pixels of partial tiles
+ * outside H x W receive no gradient.
+ * Workspace (device, 256-byte aligned), wino_backward_workspace_bytes(): four
+ * fp32 tensors in this order, each rounded up to 256 bytes:
+ * dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C], per-tile dX [n*n][T][C];
+ * they hold those intermediate gradients when the call returns.
+ * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
+int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
+int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, const void* V,
+                  const wino_scales_t* s, void* dx, void* dw, void* workspace, size_t ws_bytes,
+                  void* hip_stream);
+
 /* Measurement hook.  The next kernel that the calling thread launches through
  * this library records its own begin into `start_event` and its own end into
  * `stop_event` (hipEvent_t handles created by the caller, either may be null);

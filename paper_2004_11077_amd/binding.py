@@ -15,6 +15,7 @@ EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_
            "wino_input_transform", "wino_transform_operands", "wino_contract",
            "wino_output_transform", "wino_flex_weight_transform", "wino_flex_input_transform",
            "wino_flex_output_transform", "wino_flex_conv2d", "wino_flex_calibrate",
+           "wino_backward_workspace_bytes", "wino_backward",
            "wino_profile_next_launch", "wino_probe_peak", "wino_last_error")
 
 
@@ -140,6 +141,8 @@ def _load():
     lib.wino_flex_conv2d.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_flex_calibrate.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_profile_next_launch.argtypes = [vp, vp]
+    lib.wino_backward_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
+    lib.wino_backward.argtypes = [dp, vp, vp, vp, sp, vp, vp, vp, C.c_size_t, vp]
     lib.wino_probe_peak.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
@@ -223,6 +226,22 @@ def wino_workspace_bytes(desc):
     out = C.c_size_t()
     _check(_load().wino_workspace_bytes(C.byref(desc), C.byref(out)))
     return out.value
+
+
+def wino_backward_workspace_bytes(desc):
+    out = C.c_size_t()
+    _check(_load().wino_backward_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def wino_backward(desc, dy, U, V, scales, dx, dw, workspace, stream=None):
+    """Gradients of one layer w.r.t. its real input and weights (fp32); the
+    workspace keeps dM, dU, dV and the per-tile dX."""
+    sc = _scales(scales)
+    _check(_load().wino_backward(C.byref(desc), _ptr(dy), _ptr(U), _ptr(V), C.byref(sc), _ptr(dx),
+                                 _ptr(dw), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+    return dx, dw
 
 
 def wino_calibrate_workspace_bytes(desc):

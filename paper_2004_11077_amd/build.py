@@ -19,7 +19,8 @@ LIB = os.path.join(HERE, "libwino.so")
 HIP_SOURCES = ["wino_kernels.hip", "wino_transforms_f2.hip", "wino_transforms_f4.hip",
                "wino_transforms_f6.hip", "wino_fp32.hip", "wino_fused.hip",
                "wino_calibrate_f2.hip", "wino_calibrate_f4.hip", "wino_calibrate_f6.hip",
-               "wino_flex_f2.hip", "wino_flex_f4.hip", "wino_flex_f6.hip"]
+               "wino_flex_f2.hip", "wino_flex_f4.hip", "wino_flex_f6.hip",
+               "wino_backward.hip"]
 CXX_SOURCES = ["wino_api.cpp"]
 
 COMMON = ["-std=c++20", "-fPIC", "-fconstexpr-steps=200000000", "-Wall", "-Wno-unused-function"]

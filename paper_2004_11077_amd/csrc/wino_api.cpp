@@ -268,6 +268,84 @@ extern "C" {
 
 const char* wino_last_error(void) { return g_err.c_str(); }
 
+int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (p.fp32) return fail(WINO_EUNSUPPORTED, "the backward pass takes the int8 path's U and V");
+  if (!bytes) return fail(WINO_EINVAL, "null bytes");
+  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
+  const size_t T = (size_t)p.g.T, C = (size_t)d->C, K = (size_t)d->K;
+  size_t total = round256(n2 * T * K * 4) + 2 * round256(n2 * T * C * 4) + round256(n2 * K * C * 4);
+  if (total == 0) total = 256;
+  *bytes = total;
+  return WINO_OK;
+}
+
+int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, const void* V,
+                  const wino_scales_t* s, void* dx, void* dw, void* workspace, size_t ws_bytes,
+                  void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  size_t want = 0;
+  if (int rc = wino_backward_workspace_bytes(d, &want)) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  const int n2 = (d->m + 2) * (d->m + 2);
+  MultTable su, sv;
+  std::memset(&su, 0, sizeof su);
+  std::memset(&sv, 0, sizeof sv);
+  if (s->per_point) {
+    if (s->per_point != 1) return fail(WINO_EINVAL, "per_point must be 0 or 1");
+    if (!good_scales(s->s_u_pt, n2) || !good_scales(s->s_v_pt, n2))
+      return fail(WINO_EINVAL, "bad per-point s_u / s_v");
+    for (int q = 0; q < n2; ++q) su.v[q] = s->s_u_pt[q], sv.v[q] = s->s_v_pt[q];
+  } else {
+    if (!good_scale(s->s_u) || !good_scale(s->s_v)) return fail(WINO_EINVAL, "bad s_u / s_v");
+    for (int q = 0; q < n2; ++q) su.v[q] = s->s_u, sv.v[q] = s->s_v;
+  }
+  const Geometry& g = p.g;
+  const long x_items = (long)g.N * g.H * g.W * g.C, w_items = (long)g.K * g.C;
+  if (x_items == 0 && w_items == 0) return WINO_OK;   // nothing to write
+  if (int rc = need(workspace, "workspace")) return rc;
+  if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
+  if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  if (x_items) if (int rc = need(dx, "dx")) return rc;
+  if (w_items) if (int rc = need(dw, "dw")) return rc;
+  const long y_items = (long)g.N * g.H * g.W * g.K;
+  if (y_items) if (int rc = need(dy, "dy")) return rc;
+  if ((long)g.T * g.C) if (int rc = need(U, "U")) return rc;
+  if (w_items) if (int rc = need(V, "V")) return rc;
+  if (int rc = aligned(dy, 16, "dy")) return rc;
+  if (int rc = aligned(U, 16, "U")) return rc;
+  if (int rc = aligned(V, 16, "V")) return rc;
+  const size_t T = (size_t)g.T, C = (size_t)g.C, K = (size_t)g.K;
+  char* ws = static_cast<char*>(workspace);
+  float* dM = reinterpret_cast<float*>(ws);  ws += round256((size_t)n2 * T * K * 4);
+  float* dU = reinterpret_cast<float*>(ws);  ws += round256((size_t)n2 * T * C * 4);
+  float* dV = reinterpret_cast<float*>(ws);  ws += round256((size_t)n2 * K * C * 4);
+  float* dXt = reinterpret_cast<float*>(ws);
+  hipStream_t st = (hipStream_t)hip_stream;
+  hipError_t e = launch_backward_transform(0, g, (const float*)dy, dM, st);
+  if (e != hipSuccess) return fail_hip(e, "backward dM launch");
+  // An empty reduction (K = 0 resp. T = 0) makes the contraction kernels store zeros.
+  if ((long)g.T * g.C) {
+    e = launch_backward_gemm(false, g, dM, (const int8_t*)V, dU, sv, st);
+    if (e != hipSuccess) return fail_hip(e, "backward dU launch");
+  }
+  if (w_items) {
+    e = launch_backward_gemm(true, g, dM, (const int8_t*)U, dV, su, st);
+    if (e != hipSuccess) return fail_hip(e, "backward dV launch");
+    e = launch_backward_transform(3, g, dV, (float*)dw, st);
+    if (e != hipSuccess) return fail_hip(e, "backward dw launch");
+  }
+  if (x_items) {
+    e = launch_backward_transform(1, g, dU, dXt, st);
+    if (e != hipSuccess) return fail_hip(e, "backward per-tile dX launch");
+    e = launch_backward_transform(2, g, dXt, (float*)dx, st);
+    if (e != hipSuccess) return fail_hip(e, "backward dx launch");
+  }
+  return WINO_OK;
+}
+
 int wino_profile_next_launch(void* start_event, void* stop_event) {
   set_profile_events((hipEvent_t)start_event, (hipEvent_t)stop_event);
   return WINO_OK;

@@ -1,0 +1,367 @@
+// Backward pass of one layer (Winograd-aware training with fixed matrices,
+// Sections 2 and 4.2), fp32.  A cast passes its gradient on unchanged
+// (straight-through), so every step is the adjoint of the matching step of
+// eq. 3 and the base change of eq. 4 cancels (A_P^T P^{-T} = A^T, ...): the
+// canonical matrices serve both bases.  The forward pass enters through the
+// int8 codes U and V that it contracted, dequantised here by their scales.
+//
+//   dM[p][t][k]  = (A dY_t A^T)[p]                   k_bwd_dm
+//   dU[p][t][c]  = s_v[p] sum_k dM[p][t][k] V[p][k][c]   k_bwd_gemm<true>
+//   dV[p][k][c]  = s_u[p] sum_t dM[p][t][k] U[p][t][c]   k_bwd_gemm<false>
+//   dXt[q][t][c] = (B dU_t B^T)[q]                   k_bwd_dxt
+//   dx[b][h][w][c] = sum of the <= 4 tiles covering the pixel   k_bwd_dx
+//   dw[k][c]     = G^T dV G                          k_bwd_dw
+//
+// Layouts as in the forward pass: point-major [n*n][items][channels] for
+// everything in the transform domain, NHWC for dy and dx, KCRS for dw.
+#include "wino_kernels.hpp"
+#include "wino_tables.hpp"
+
+namespace wino {
+namespace {
+
+template <int I>
+using ICb = std::integral_constant<int, I>;
+
+template <int B, int E, class F>
+__device__ __forceinline__ void bfor(F&& f) {
+  if constexpr (B < E) {
+    f(ICb<B>{});
+    bfor<B + 1, E>(f);
+  }
+}
+
+template <int M>
+struct TabB {
+  static constexpr MatrixSet ms = standard_matrix_set(M);
+  static constexpr RMat G = ms.G, BT = ms.BT, AT = ms.AT;
+};
+
+// out = Q x Q^T with Q = T^T (T.cols x T.rows): the adjoint of the bracket
+// T x T^T.  Coefficients are the rationals of T rounded to fp32 at compile
+// time; zero coefficients generate no code.
+template <const RMat& T>
+__device__ __forceinline__ void adjoint_sandwich(const float (&x)[T.rows][T.rows],
+                                                 float (&out)[T.cols][T.cols]) {
+  float tmp[T.cols][T.rows];
+  bfor<0, T.cols>([&](auto i) {                  // tmp = T^T x
+    bfor<0, T.rows>([&](auto b) {
+      float acc = 0.f;
+      bfor<0, T.rows>([&](auto a) {
+        constexpr Rat c = T.a[decltype(a)::value][decltype(i)::value];
+        if constexpr (c.num != 0)
+          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), x[a][b], acc);
+      });
+      tmp[i][b] = acc;
+    });
+  });
+  bfor<0, T.cols>([&](auto i) {                  // out = tmp T
+    bfor<0, T.cols>([&](auto j) {
+      float acc = 0.f;
+      bfor<0, T.rows>([&](auto b) {
+        constexpr Rat c = T.a[decltype(b)::value][decltype(j)::value];
+        if constexpr (c.num != 0)
+          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), tmp[i][b], acc);
+      });
+      out[i][j] = acc;
+    });
+  });
+}
+
+// dY -> dM.  One lane per (tile, k); output pixels beyond H x W (partial tiles)
+// carry no gradient.
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dm(const float* __restrict__ dy,
+                                                float* __restrict__ dM, Geometry g) {
+  constexpr int n = M + 2;
+  const long total = (long)g.T * g.K;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  const int t = (int)(gid / g.K);
+  const int k = (int)(gid - (long)t * g.K);
+  const int tx = t % g.TW;
+  const int ty = (t / g.TW) % g.TH;
+  const int b = t / (g.TW * g.TH);
+  float v[M][M];
+  bfor<0, M>([&](auto i) {
+    bfor<0, M>([&](auto j) {
+      const int h = ty * M + decltype(i)::value, w = tx * M + decltype(j)::value;
+      v[i][j] = (h < g.H && w < g.W) ? dy[(((long)b * g.H + h) * g.W + w) * g.K + k] : 0.f;
+    });
+  });
+  float out[n][n];
+  adjoint_sandwich<TabB<M>::AT>(v, out);
+  bfor<0, n>([&](auto i) {
+    bfor<0, n>([&](auto j) {
+      dM[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = out[i][j];
+    });
+  });
+}
+
+// dU -> per-tile input gradients dXt[a*n+b][t][c] (tiles not yet summed).
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dxt(const float* __restrict__ dU,
+                                                 float* __restrict__ dXt, Geometry g) {
+  constexpr int n = M + 2;
+  const long total = (long)g.T * g.C;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  float v[n][n];
+  bfor<0, n>([&](auto i) {
+    bfor<0, n>([&](auto j) {
+      v[i][j] = dU[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid];
+    });
+  });
+  float out[n][n];
+  adjoint_sandwich<TabB<M>::BT>(v, out);
+  bfor<0, n>([&](auto i) {
+    bfor<0, n>([&](auto j) {
+      dXt[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = out[i][j];
+    });
+  });
+}
+
+// dx[b][h][w][c]: tile ty reads input rows ty*M - 1 ... ty*M + M, so pixel row h
+// is local row (h+1) % M of tile (h+1) / M and, when that is 0 or 1, also local
+// row M + (h+1) % M of the tile above; columns alike.  The (at most four)
+// contributions are added in a fixed order.
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dXt,
+                                                float* __restrict__ dx, Geometry g) {
+  constexpr int n = M + 2;
+  const long total = (long)g.N * g.H * g.W * g.C;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  const int c = (int)(gid % g.C);
+  const long pix = gid / g.C;
+  const int w = (int)(pix % g.W);
+  const int h = (int)((pix / g.W) % g.H);
+  const int b = (int)(pix / ((long)g.W * g.H));
+  const long TC = (long)g.T * g.C;
+  const int ty1 = (h + 1) / M, i1 = (h + 1) % M;
+  const int tx1 = (w + 1) / M, j1 = (w + 1) % M;
+  float acc = 0.f;
+#pragma unroll
+  for (int dyv = 0; dyv < 2; ++dyv) {
+    const int ty = ty1 - dyv, i = i1 + dyv * M;
+    if (ty < 0 || ty >= g.TH || i >= n) continue;
+#pragma unroll
+    for (int dxv = 0; dxv < 2; ++dxv) {
+      const int tx = tx1 - dxv, j = j1 + dxv * M;
+      if (tx < 0 || tx >= g.TW || j >= n) continue;
+      const long t = ((long)b * g.TH + ty) * g.TW + tx;
+      acc += dXt[(long)(i * n + j) * TC + t * g.C + c];
+    }
+  }
+  dx[gid] = acc;
+}
+
+// dV -> dw[k][c][3][3].
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dw(const float* __restrict__ dV,
+                                                float* __restrict__ dw, Geometry g) {
+  constexpr int n = M + 2;
+  const long total = (long)g.K * g.C;
+  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  if (gid >= total) return;
+  float v[n][n];
+  bfor<0, n>([&](auto i) {
+    bfor<0, n>([&](auto j) {
+      v[i][j] = dV[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid];
+    });
+  });
+  float out[3][3];
+  adjoint_sandwich<TabB<M>::G>(v, out);
+  bfor<0, 3>([&](auto a) {
+    bfor<0, 3>([&](auto bb) {
+      dw[gid * 9 + decltype(a)::value * 3 + decltype(bb)::value] = out[a][bb];
+    });
+  });
+}
+
+// ---------------------------------------------------------------------------
+// Contraction gradients: n*n GEMMs  C[p][row][col] = scale[p] * sum_red
+// A(p, row, red) * B[p][red][col]  with fp32 A (dM), int8 B (codes, converted
+// to fp32 when staged) and fp32 accumulation on v_mfma_f32_32x32x2_f32.
+//   ARED = true : A is [p][row][red]  (dU: row = t, red = k, col = c, B = V)
+//   ARED = false: A is [p][red][row]  (dV: row = k, red = t, col = c, B = U)
+// Work group = 4 waves = 64 x 64 outputs, one 32 x 32 block per wave; the
+// reduction runs in chunks of 32 staged through LDS, the next chunk's global
+// loads in flight during the MFMAs.  LDS rows are padded so that the
+// per-lane fragment reads (lane -> row or column = lane % 32, red = lane / 32)
+// hit distinct banks.  red and cols are multiples of 4 resp. 16 (K and C are
+// multiples of 16), rows and red are otherwise arbitrary: out-of-range
+// elements are staged as zeros, out-of-range outputs are not stored.
+// ---------------------------------------------------------------------------
+using v4f = __attribute__((ext_vector_type(4))) float;
+using v4ib = __attribute__((ext_vector_type(4))) int;
+using v16f = __attribute__((ext_vector_type(16))) float;
+
+constexpr int kGT = 64;        // outputs per work group edge
+constexpr int kGR = 32;        // reduction chunk
+constexpr int kLdA = 33;       // ARED: As[row][red], odd stride
+constexpr int kLdT = 68;       // As[red][row] / Bs[red][col], 16-byte aligned rows
+
+template <bool ARED>
+__global__ __launch_bounds__(256) void k_bwd_gemm(const float* __restrict__ A,
+                                                  const int8_t* __restrict__ B,
+                                                  float* __restrict__ Cout, int rows, int red,
+                                                  int cols, MultTable scale, int row_blocks) {
+  __shared__ __attribute__((aligned(16))) float As[ARED ? kGT * kLdA : kGR * kLdT];
+  __shared__ __attribute__((aligned(16))) float Bs[kGR * kLdT];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int p = blockIdx.y;
+  const int rb = blockIdx.x % row_blocks, cb = blockIdx.x / row_blocks;
+  const int row0 = rb * kGT, col0 = cb * kGT;
+  const float* Ap = A + (long)p * rows * red;
+  const int8_t* Bp = B + (long)p * red * cols;
+
+  v4f ra[2];
+  v4ib rbv;
+  auto fetch = [&](int r0) {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int idx = tid + it * 256;
+      v4f v = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (ARED) {
+        const int row = idx >> 3, q = idx & 7;
+        if (row0 + row < rows && r0 + 4 * q < red)
+          v = *reinterpret_cast<const v4f*>(Ap + (long)(row0 + row) * red + r0 + 4 * q);
+      } else {
+        const int rr = idx >> 4, q = idx & 15;
+        if (r0 + rr < red && row0 + 4 * q < rows)
+          v = *reinterpret_cast<const v4f*>(Ap + (long)(r0 + rr) * rows + row0 + 4 * q);
+      }
+      ra[it] = v;
+    }
+    rbv = v4ib{0, 0, 0, 0};
+    if (tid < 128) {
+      const int rr = tid >> 2, q = tid & 3;
+      if (r0 + rr < red && col0 + 16 * q < cols)
+        rbv = *reinterpret_cast<const v4ib*>(Bp + (long)(r0 + rr) * cols + col0 + 16 * q);
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+      const int idx = tid + it * 256;
+      if constexpr (ARED) {
+        const int row = idx >> 3, q = idx & 7;
+        float* d = As + row * kLdA + 4 * q;
+        d[0] = ra[it].x; d[1] = ra[it].y; d[2] = ra[it].z; d[3] = ra[it].w;
+      } else {
+        const int rr = idx >> 4, q = idx & 15;
+        *reinterpret_cast<v4f*>(As + rr * kLdT + 4 * q) = ra[it];
+      }
+    }
+    if (tid < 128) {
+      const int rr = tid >> 2, q = tid & 3;
+      float* d = Bs + rr * kLdT + 16 * q;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int word = rbv[e];
+        v4f f;
+        f.x = (float)(int8_t)(word & 0xff);
+        f.y = (float)(int8_t)((word >> 8) & 0xff);
+        f.z = (float)(int8_t)((word >> 16) & 0xff);
+        f.w = (float)(word >> 24);
+        *reinterpret_cast<v4f*>(d + 4 * e) = f;
+      }
+    }
+  };
+
+  v16f acc;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
+  const int l32 = lane & 31, lk = lane >> 5;
+
+  fetch(0);
+  for (int r0 = 0; r0 < red; r0 += kGR) {
+    __syncthreads();                  // the previous chunk's fragment reads are done
+    stage();
+    __syncthreads();
+    if (r0 + kGR < red) fetch(r0 + kGR);
+#pragma unroll
+    for (int kk = 0; kk < kGR; kk += 2) {
+      float a;
+      if constexpr (ARED)
+        a = As[(wr + l32) * kLdA + kk + lk];
+      else
+        a = As[(kk + lk) * kLdT + wr + l32];
+      const float b = Bs[(kk + lk) * kLdT + wc + l32];
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    }
+  }
+
+  // acc[i] holds output (row = (i / 4) * 8 + (lane / 32) * 4 + i % 4, col = lane % 32)
+  const float s = scale.v[p];
+  const int col = col0 + wc + l32;
+  if (col < cols) {
+    float* Cp = Cout + (long)p * rows * cols;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int row = row0 + wr + (i >> 2) * 8 + lk * 4 + (i & 3);
+      if (row < rows) Cp[(long)row * cols + col] = acc[i] * s;
+    }
+  }
+}
+
+inline unsigned blocks256(long items) { return (unsigned)((items + 255) / 256); }
+
+template <int M>
+hipError_t bwd_transform(int which, const Geometry& g, const float* in, float* out,
+                         hipStream_t st) {
+  switch (which) {
+    case 0:
+      wino_launch((k_bwd_dm<M>), dim3(blocks256((long)g.T * g.K)), dim3(256), st, in, out, g);
+      break;
+    case 1:
+      wino_launch((k_bwd_dxt<M>), dim3(blocks256((long)g.T * g.C)), dim3(256), st, in, out, g);
+      break;
+    case 2:
+      wino_launch((k_bwd_dx<M>), dim3(blocks256((long)g.N * g.H * g.W * g.C)), dim3(256), st, in,
+                  out, g);
+      break;
+    default:
+      wino_launch((k_bwd_dw<M>), dim3(blocks256((long)g.K * g.C)), dim3(256), st, in, out, g);
+      break;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
+                                     hipStream_t st) {
+  const long items = which == 0   ? (long)g.T * g.K
+                     : which == 1 ? (long)g.T * g.C
+                     : which == 2 ? (long)g.N * g.H * g.W * g.C
+                                  : (long)g.K * g.C;
+  if (items == 0) return hipSuccess;
+  switch (g.m) {
+    case 2: return bwd_transform<2>(which, g, in, out, st);
+    case 4: return bwd_transform<4>(which, g, in, out, st);
+    case 6: return bwd_transform<6>(which, g, in, out, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float* dM,
+                                const int8_t* codes, float* out, const MultTable& scale,
+                                hipStream_t st) {
+  const int n2 = (g.m + 2) * (g.m + 2);
+  const int rows = for_weights ? g.K : g.T;
+  const int red = for_weights ? g.T : g.K;
+  const int cols = g.C;
+  if (rows == 0 || cols == 0) return hipSuccess;
+  const int rbk = (rows + kGT - 1) / kGT, cbk = (cols + kGT - 1) / kGT;
+  const dim3 grid((unsigned)(rbk * cbk), (unsigned)n2);
+  if (for_weights)
+    wino_launch((k_bwd_gemm<false>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale, rbk);
+  else
+    wino_launch((k_bwd_gemm<true>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale, rbk);
+  return hipGetLastError();
+}
+
+}  // namespace wino

@@ -163,6 +163,16 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
                         const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
                         hipStream_t st);
 
+// Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> per-tile
+// dX, 2 per-tile dX -> dx, 3 dV -> dw.
+hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
+                                     hipStream_t st);
+// for_weights = false: out = dU[p][t][c] = scale[p] sum_k dM[p][t][k] codes[p][k][c] (codes = V);
+// for_weights = true:  out = dV[p][k][c] = scale[p] sum_t dM[p][t][k] codes[p][t][c] (codes = U).
+hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float* dM,
+                                const int8_t* codes, float* out, const MultTable& scale,
+                                hipStream_t st);
+
 // Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
 // 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8).
 hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t st);

@@ -1,0 +1,124 @@
+"""Backward pass of one layer: library (fp32, through the C ABI) against the fp64 oracle.
+
+Tolerance.  Every result is a chain of fp32 sums of products: two short
+brackets (at most 8 terms each) around one contraction of length L (K for the
+input gradient, T for the weight gradient).  With unit roundoff u = 2^-24 the
+error of such a sum is at most about (L + 16) u sum|terms|, and for the
+zero-mean synthetic gradients used here it behaves like sqrt(L) u times the
+largest result.  The tests allow 1e-5 of the largest reference value for the
+brackets and contractions with L <= 512, and 3e-5 at L = T = 1024 (the headline
+shape), i.e. a few sqrt(L) u.
+"""
+import numpy as np
+import pytest
+
+from oracle import backward as bw
+
+pytestmark = pytest.mark.gpu
+
+
+def run_backward(dy, Uq, Vq, shape, m, scales):
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    N, H, W, C, K = shape
+    desc = wn.ConvDesc(N, H, W, C, K, m=m)
+    n2, T = desc.n ** 2, desc.tiles
+    nbytes = wn.wino_backward_workspace_bytes(desc)
+    ws = torch.full((nbytes // 4,), float("nan"), dtype=torch.float32, device=dev)
+    dx = torch.full((N, H, W, C), float("nan"), dtype=torch.float32, device=dev)
+    dw = torch.full((K, C, 3, 3), float("nan"), dtype=torch.float32, device=dev)
+    t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(dev)
+    wn.wino_backward(desc, t(dy, np.float32), t(Uq, np.int8), t(Vq, np.int8),
+                     wn.Scales.from_dict(scales), dx, dw, ws)
+    torch.cuda.synchronize()
+    r64 = lambda v: (v + 63) // 64 * 64            # 256-byte rounding, in floats
+    out, o = {}, 0
+    for name, shp in (("dM", (n2, T, K)), ("dU", (n2, T, C)), ("dV", (n2, K, C))):
+        cnt = int(np.prod(shp))
+        out[name] = ws[o:o + cnt].reshape(shp).cpu().numpy()
+        o += r64(cnt)
+    out["dx"], out["dw"] = dx.cpu().numpy(), dw.cpu().numpy()
+    return out
+
+
+def reference(dy, Uq, Vq, shape, m, scales):
+    if hasattr(scales["s_u"], "__len__"):             # per-point scales
+        U = bw.dequantise(Uq, None, scales["s_u"])
+        V = bw.dequantise(Vq, None, scales["s_v"])
+    else:
+        U, V = bw.dequantise(Uq, scales["s_u"]), bw.dequantise(Vq, scales["s_v"])
+    return bw.backward_layer(dy.astype(np.float64), U, V, shape[:4], m)
+
+
+def make_case(shape, m, seed, per_point):
+    N, H, W, C, K = shape
+    rng = np.random.default_rng(seed)
+    n2 = (m + 2) ** 2
+    T = N * (-(-H // m)) * (-(-W // m))
+    dy = rng.standard_normal((N, H, W, K)).astype(np.float32)
+    Uq = rng.integers(-127, 128, (n2, T, C)).astype(np.int8)
+    Vq = rng.integers(-127, 128, (n2, K, C)).astype(np.int8)
+    if per_point:
+        pt = lambda: [float(v) for v in rng.uniform(0.005, 0.05, n2).astype(np.float32)]
+        scales = {"s_u": pt(), "s_v": pt()}
+    else:
+        scales = {"s_u": 0.02, "s_v": 0.011}
+    return dy, Uq, Vq, scales
+
+
+def check(ref, got, tol):
+    for key in ("dM", "dU", "dV", "dx", "dw"):
+        assert got[key].shape == ref[key].shape, key
+        assert np.isfinite(got[key]).all(), key + " holds values the kernels did not write"
+        if ref[key].size == 0:
+            continue
+        bound = tol * max(float(np.abs(ref[key]).max()), 1e-30)
+        err = float(np.abs(got[key].astype(np.float64) - ref[key]).max())
+        assert err <= bound, "%s: max abs err %g > %g" % (key, err, bound)
+
+
+CASES = [
+    # m, (N, H, W, C, K), per_point
+    (4, (2, 8, 8, 16, 16), False),
+    (4, (3, 11, 6, 48, 80), True),          # ragged image, ragged 64-blocks in every GEMM dimension
+    (4, (1, 13, 5, 256, 64), False),
+    (2, (2, 7, 9, 32, 16), True),
+    (2, (5, 6, 6, 64, 144), False),
+    (6, (1, 12, 12, 16, 32), False),
+    (6, (2, 7, 8, 32, 16), True),
+    (4, (40, 4, 4, 16, 32), False),         # T = 40: reduction over tiles not a multiple of 32
+]
+
+
+@pytest.mark.parametrize("m,shape,per_point", CASES)
+def test_backward_matches_oracle(m, shape, per_point):
+    dy, Uq, Vq, scales = make_case(shape, m, seed=900 + m + shape[3], per_point=per_point)
+    got = run_backward(dy, Uq, Vq, shape, m, scales)
+    check(reference(dy, Uq, Vq, shape, m, scales), got, 1e-5)
+
+
+@pytest.mark.parametrize("shape", [(0, 8, 8, 16, 16), (2, 8, 8, 16, 0), (2, 8, 8, 0, 16), (2, 0, 8, 16, 16)])
+def test_backward_empty_problems(shape):
+    dy, Uq, Vq, scales = make_case(shape, 4, seed=1, per_point=False)
+    got = run_backward(dy, Uq, Vq, shape, 4, scales)
+    ref = reference(dy, Uq, Vq, shape, 4, scales)
+    for key in ("dx", "dw"):
+        assert got[key].shape == ref[key].shape
+        assert np.array_equal(got[key], ref[key].astype(np.float32))   # all zero, or empty
+
+
+def test_backward_after_the_library_forward_pass_headline_shape():
+    """U and V produced by the forward kernels of the headline workload."""
+    import synth_inputs as si
+    from helpers import gpu_layer
+    wl = si.WORKLOADS["cfg4a_f4_c256"]
+    L = si.make_layer(wl)
+    scales = si.workload_scales(wl.name)
+    fwd = gpu_layer(L["xq"], L["wq"], scales, m=4, base="legendre")
+    rng = np.random.default_rng(77)
+    shape = (wl.N, wl.H, wl.W, wl.C, wl.K)
+    dy = rng.standard_normal((wl.N, wl.H, wl.W, wl.K)).astype(np.float32)
+    got = run_backward(dy, fwd["U"], fwd["V"], shape, 4, scales)
+    ref = reference(dy, fwd["U"], fwd["V"], shape, 4, scales)
+    check(ref, got, 3e-5)
