@@ -210,6 +210,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra timings of the other layer configurations")
+    ap.add_argument("--only-extra", default=None,
+                    choices=("fused", "pretransformed", "per_point", "flex", "backward", "others"),
+                    help="run just this one of the extra measurements (for profiling it)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 64 MiB device copy after warm-up: the known-size "
                          "kernel against which rocprofv3 --pmc byte counters are scaled")
@@ -401,7 +404,12 @@ def main():
     }
     # extra: the single-kernel fused variant on the same workload (same step
     # definition: filter transform + fused kernel), timed the same way
-    if wl.m in (2, 4) and wl.bits_hadamard in (8, 9):
+    def want(name, always=False):
+        if args.only_extra is not None:
+            return args.only_extra == name
+        return always or not args.no_extras
+
+    if want("fused", always=True) and wl.m in (2, 4) and wl.bits_hadamard in (8, 9):
         fdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
                             bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=1)
         fws = torch.empty(wn.wino_workspace_bytes(fdesc), dtype=torch.uint8, device=dev)
@@ -418,7 +426,7 @@ def main():
                                 "note": "input transform recomputed per 64-channel k block"}
     # extra: the same layer with its filters transformed ahead of time (a1 is a per-layer,
     # offline step in deployment): input transform, contraction, output transform
-    if not args.no_extras:
+    if want("pretransformed"):
         def vstep():
             wn.wino_input_transform(desc, x, U, sc, stream)
             wn.wino_contract(desc, U, V, M, sc, stream)
@@ -436,7 +444,7 @@ def main():
                                          "note": "a2 + a3 + a4 only; V computed once beforehand"}
     # extra: the same layer with per-Winograd-point scales (U, V per point, M with
     # power-of-two refinements), calibrated on the device, same three launches
-    if not args.no_extras:
+    if want("per_point"):
         cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
         psc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws,
                                 per_point=True)
@@ -459,7 +467,7 @@ def main():
                                     "note": "per-point scales for U, V and M"}
     # extra: the flex layer (run-time fp32 G_P, B_P, A_P; here the static matrices rounded
     # to fp32, as at the start of training) on the same workload, whole-layer call
-    if not args.no_extras:
+    if want("flex"):
         fm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],
                                         dtype=np.float32) for nm in ("GP", "BPT", "APT")])
         xdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
@@ -480,9 +488,48 @@ def main():
                                "unit": "TOPS",
                                "note": "fp32 brackets with run-time matrices, four launches"}
         del xws
+    # extra: backward pass of the same layer (gradients w.r.t. input and weights from a
+    # synthetic output gradient, U and V as the forward pass left them), fp32; each of its
+    # five launches timed by its own event pair
+    if want("backward") and reps == 1:
+        bnames = ("dY_to_dM", "gemm_dU", "gemm_dV", "dV_to_dw", "dU_to_dx")
+        g = torch.Generator(device="cpu").manual_seed(wl.seed + 1)
+        dy = torch.randn((wl.N, wl.H, wl.W, wl.K), generator=g, dtype=torch.float32).to(dev)
+        dx = torch.empty((wl.N, wl.H, wl.W, wl.C), dtype=torch.float32, device=dev)
+        dw = torch.empty((wl.K, wl.C, 3, 3), dtype=torch.float32, device=dev)
+        bws = torch.empty(wn.wino_backward_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        for _ in range(args.warmup):
+            wn.wino_backward(desc, dy, U, V, sc, dx, dw, bws, stream)
+        torch.cuda.synchronize()
+        bsteps = max(10, args.steps // 10)
+        bev = [(new_event(), new_event()) for _ in bnames]
+        t0 = time.perf_counter()
+        for i in range(bsteps):
+            if i == bsteps - 1:
+                for a, b in bev:
+                    wn.wino_profile_next_launch(a.value, b.value)
+            wn.wino_backward(desc, dy, U, V, sc, dx, dw, bws, stream)
+        torch.cuda.synchronize()
+        bdt = (time.perf_counter() - t0) / bsteps
+        kus = {nm: elapsed_ms(a, b) * 1e3 for nm, (a, b) in zip(bnames, bev)}
+        for a, b in bev:
+            hip.hipEventDestroy(a)
+            hip.hipEventDestroy(b)
+        gemm_flops = 2.0 * n2 * T * wl.C * wl.K
+        gemm_tf = 2 * gemm_flops / ((kus["gemm_dU"] + kus["gemm_dV"]) * 1e-6) / 1e12
+        f32_peak = probe(wn.PROBE_MFMA_F32, 4096, 2048)
+        out["backward_variant"] = {
+            "ms_per_step": bdt * 1e3, "dtype": "f32", "kernel_us": kus,
+            "roofline": {"bound": "mfma", "kernel": "gemm_dU + gemm_dV", "achieved": gemm_tf,
+                         "peak": 157.3, "unit": "TFLOP/s", "frac": gemm_tf / 157.3,
+                         "traffic": None, "measured_mfma_f32_TFLOPs": f32_peak,
+                         "frac_of_measured_peak": gemm_tf / f32_peak},
+            "note": "straight-through gradients; the two contraction gradients are fp32 MFMA GEMMs "
+                    "of 2*n^2*T*C*K flops each"}
+        del dy, dx, dw, bws
     # extra: whole-layer call (wino_conv2d) on the other single-layer configurations, split
     # path and AUTO (which takes the fused kernel where C, K <= 64); not the headline figure
-    if not args.no_extras and reps == 1:
+    if want("others") and reps == 1:
         out["other_workloads"] = {}
         for name in ("cfg2_f4_c64", "cfg3_f4_c128_h9", "cfg4b_f4_c512"):
             if name == wl.name:

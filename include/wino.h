@@ -253,10 +253,10 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
  * two contractions); sums over tiles are taken in a fixed order, so results
  * are reproducible.  Int8 path only (d->bits_in = 8).  Pixels of partial tiles
  * outside H x W receive no gradient.
- * Workspace (device, 256-byte aligned), wino_backward_workspace_bytes(): four
+ * Workspace (device, 256-byte aligned), wino_backward_workspace_bytes(): three
  * fp32 tensors in this order, each rounded up to 256 bytes:
- * dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C], per-tile dX [n*n][T][C];
- * they hold those intermediate gradients when the call returns.
+ * dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C]; they hold those intermediate
+ * gradients when the call returns.
  * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
 int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, const void* V,
@@ -268,18 +268,22 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
  * `stop_event` (hipEvent_t handles created by the caller, either may be null);
  * after the stream has been synchronised, hipEventElapsedTime(start, stop) is
  * that dispatch's duration without any launch or marker overhead.  The pair is
- * consumed by that one launch.  Always returns WINO_OK. */
+ * consumed by that one launch.  Calls queue up, oldest first, at most 8 pending
+ * pairs per thread (a ninth replaces the eighth): before a call that launches
+ * several kernels, k calls time its first k launches.  Always returns WINO_OK. */
 int wino_profile_next_launch(void* start_event, void* stop_event);
 
 /* Measurement helper: one register-only kernel that shows what the device
  * sustains on a unit the hot path is priced against.  WINO_PROBE_MFMA_I8:
  * every wave issues iters x 4 independent 32x32x32 int8 MFMAs;
- * WINO_PROBE_VALU_MAD24: every lane issues iters x 8 24-bit multiply-adds.
+ * WINO_PROBE_VALU_MAD24: every lane issues iters x 8 24-bit multiply-adds;
+ * WINO_PROBE_MFMA_F32: every wave issues iters x 4 independent 32x32x2 fp32
+ * MFMAs (the instruction of the backward pass's contractions).
  * `blocks` work groups of 256 lanes; *work (host, may be null) receives the
- * int8 operations (2 per multiply-accumulate) resp. lane-operations of the
- * launch; `sink` is a device int the kernel may write.  Time it with
+ * int8 operations resp. flops (2 per multiply-accumulate) resp. lane-operations
+ * of the launch; `sink` is a device int the kernel may write.  Time it with
  * wino_profile_next_launch. */
-enum { WINO_PROBE_MFMA_I8 = 0, WINO_PROBE_VALU_MAD24 = 1 };
+enum { WINO_PROBE_MFMA_I8 = 0, WINO_PROBE_VALU_MAD24 = 1, WINO_PROBE_MFMA_F32 = 2 };
 int wino_probe_peak(int kind, int blocks, int iters, void* sink, double* work, void* hip_stream);
 
 /* Text of the last error on this thread ("" if none); valid until the next

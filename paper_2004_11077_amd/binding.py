@@ -212,7 +212,7 @@ def wino_profile_next_launch(start_event, stop_event):
     _check(_load().wino_profile_next_launch(C.c_void_p(start_event), C.c_void_p(stop_event)))
 
 
-PROBE_MFMA_I8, PROBE_VALU_MAD24 = 0, 1
+PROBE_MFMA_I8, PROBE_VALU_MAD24, PROBE_MFMA_F32 = 0, 1, 2
 
 
 def wino_probe_peak(kind, blocks, iters, sink, stream=None):
@@ -236,7 +236,7 @@ def wino_backward_workspace_bytes(desc):
 
 def wino_backward(desc, dy, U, V, scales, dx, dw, workspace, stream=None):
     """Gradients of one layer w.r.t. its real input and weights (fp32); the
-    workspace keeps dM, dU, dV and the per-tile dX."""
+    workspace keeps dM, dU and dV."""
     sc = _scales(scales)
     _check(_load().wino_backward(C.byref(desc), _ptr(dy), _ptr(U), _ptr(V), C.byref(sc), _ptr(dx),
                                  _ptr(dw), _ptr(workspace),

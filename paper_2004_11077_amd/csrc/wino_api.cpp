@@ -275,7 +275,7 @@ int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   const size_t T = (size_t)p.g.T, C = (size_t)d->C, K = (size_t)d->K;
-  size_t total = round256(n2 * T * K * 4) + 2 * round256(n2 * T * C * 4) + round256(n2 * K * C * 4);
+  size_t total = round256(n2 * T * K * 4) + round256(n2 * T * C * 4) + round256(n2 * K * C * 4);
   if (total == 0) total = 256;
   *bytes = total;
   return WINO_OK;
@@ -321,8 +321,7 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
   char* ws = static_cast<char*>(workspace);
   float* dM = reinterpret_cast<float*>(ws);  ws += round256((size_t)n2 * T * K * 4);
   float* dU = reinterpret_cast<float*>(ws);  ws += round256((size_t)n2 * T * C * 4);
-  float* dV = reinterpret_cast<float*>(ws);  ws += round256((size_t)n2 * K * C * 4);
-  float* dXt = reinterpret_cast<float*>(ws);
+  float* dV = reinterpret_cast<float*>(ws);
   hipStream_t st = (hipStream_t)hip_stream;
   hipError_t e = launch_backward_transform(0, g, (const float*)dy, dM, st);
   if (e != hipSuccess) return fail_hip(e, "backward dM launch");
@@ -338,9 +337,7 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
     if (e != hipSuccess) return fail_hip(e, "backward dw launch");
   }
   if (x_items) {
-    e = launch_backward_transform(1, g, dU, dXt, st);
-    if (e != hipSuccess) return fail_hip(e, "backward per-tile dX launch");
-    e = launch_backward_transform(2, g, dXt, (float*)dx, st);
+    e = launch_backward_transform(1, g, dU, (float*)dx, st);
     if (e != hipSuccess) return fail_hip(e, "backward dx launch");
   }
   return WINO_OK;
@@ -352,14 +349,15 @@ int wino_profile_next_launch(void* start_event, void* stop_event) {
 }
 
 int wino_probe_peak(int kind, int blocks, int iters, void* sink, double* work, void* hip_stream) {
-  if (kind != WINO_PROBE_MFMA_I8 && kind != WINO_PROBE_VALU_MAD24)
+  if (kind != WINO_PROBE_MFMA_I8 && kind != WINO_PROBE_VALU_MAD24 && kind != WINO_PROBE_MFMA_F32)
     return fail(WINO_EINVAL, "unknown probe %d", kind);
   if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > (1 << 24))
     return fail(WINO_EINVAL, "probe size out of range");
   if (int rc = need(sink, "sink")) return rc;
   if (work)
-    *work = kind == WINO_PROBE_MFMA_I8 ? (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 32)
-                                       : (double)blocks * 256.0 * iters * 8.0;
+    *work = kind == WINO_PROBE_MFMA_I8    ? (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 32)
+            : kind == WINO_PROBE_MFMA_F32 ? (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 2)
+                                          : (double)blocks * 256.0 * iters * 8.0;
   hipError_t e = launch_probe(kind, blocks, iters, (int*)sink, (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "probe launch");
 }

@@ -8,8 +8,8 @@
 //   dM[p][t][k]  = (A dY_t A^T)[p]                   k_bwd_dm
 //   dU[p][t][c]  = s_v[p] sum_k dM[p][t][k] V[p][k][c]   k_bwd_gemm<true>
 //   dV[p][k][c]  = s_u[p] sum_t dM[p][t][k] U[p][t][c]   k_bwd_gemm<false>
-//   dXt[q][t][c] = (B dU_t B^T)[q]                   k_bwd_dxt
-//   dx[b][h][w][c] = sum of the <= 4 tiles covering the pixel   k_bwd_dx
+//   dx[b][h][w][c] = sum over the <= 4 tiles t covering the pixel of
+//                    (B dU_t B^T)[its local position in t]       k_bwd_dx
 //   dw[k][c]     = G^T dV G                          k_bwd_dw
 //
 // Layouts as in the forward pass: point-major [n*n][items][channels] for
@@ -98,62 +98,100 @@ __global__ __launch_bounds__(256) void k_bwd_dm(const float* __restrict__ dy,
   });
 }
 
-// dU -> per-tile input gradients dXt[a*n+b][t][c] (tiles not yet summed).
-template <int M>
-__global__ __launch_bounds__(256) void k_bwd_dxt(const float* __restrict__ dU,
-                                                 float* __restrict__ dXt, Geometry g) {
-  constexpr int n = M + 2;
-  const long total = (long)g.T * g.C;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  if (gid >= total) return;
-  float v[n][n];
-  bfor<0, n>([&](auto i) {
-    bfor<0, n>([&](auto j) {
-      v[i][j] = dU[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid];
-    });
+// Entries [A0, A1] x [B0, B1] of B dU B^T for one tile, added to acc[a - A0 + AO][b - B0 + BO]:
+//   (B dU B^T)[a][b] = sum_i sum_j BT[i][a] dU[i][j] BT[j][b].
+// load(i, j) is called only for the (i, j) that a non-zero coefficient needs.
+template <const RMat& BT, int A0, int A1, int B0, int B1, int AO, int BO, int ACC, class Load>
+__device__ __forceinline__ void dx_entries(Load&& load, float (&acc)[ACC][ACC]) {
+  constexpr int n = BT.rows;
+  constexpr auto row_used = [](int i) {
+    for (int a = A0; a <= A1; ++a)
+      if (BT.a[i][a].num != 0) return true;
+    return false;
+  };
+  constexpr auto col_used = [](int j) {
+    for (int b = B0; b <= B1; ++b)
+      if (BT.a[j][b].num != 0) return true;
+    return false;
+  };
+  float part[A1 - A0 + 1][n];                    // part[a][j] = sum_i BT[i][a] dU[i][j]
+  bfor<0, n>([&](auto j) {
+    constexpr int J = decltype(j)::value;
+    if constexpr (col_used(J)) {
+      bfor<A0, A1 + 1>([&](auto a) { part[decltype(a)::value - A0][J] = 0.f; });
+      bfor<0, n>([&](auto i) {
+        constexpr int I = decltype(i)::value;
+        if constexpr (row_used(I)) {
+          const float v = load(i, j);
+          bfor<A0, A1 + 1>([&](auto a) {
+            constexpr Rat c = BT.a[I][decltype(a)::value];
+            if constexpr (c.num != 0)
+              part[decltype(a)::value - A0][J] = __builtin_fmaf(
+                  (float)((double)c.num / (double)c.den), v, part[decltype(a)::value - A0][J]);
+          });
+        }
+      });
+    }
   });
-  float out[n][n];
-  adjoint_sandwich<TabB<M>::BT>(v, out);
-  bfor<0, n>([&](auto i) {
-    bfor<0, n>([&](auto j) {
-      dXt[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = out[i][j];
+  bfor<A0, A1 + 1>([&](auto a) {
+    bfor<B0, B1 + 1>([&](auto b) {
+      float sum = 0.f;
+      bfor<0, n>([&](auto j) {
+        constexpr Rat c = BT.a[decltype(j)::value][decltype(b)::value];
+        if constexpr (c.num != 0)
+          sum = __builtin_fmaf((float)((double)c.num / (double)c.den),
+                               part[decltype(a)::value - A0][decltype(j)::value], sum);
+      });
+      acc[decltype(a)::value - A0 + AO][decltype(b)::value - B0 + BO] += sum;
     });
   });
 }
 
-// dx[b][h][w][c]: tile ty reads input rows ty*M - 1 ... ty*M + M, so pixel row h
-// is local row (h+1) % M of tile (h+1) / M and, when that is 0 or 1, also local
-// row M + (h+1) % M of the tile above; columns alike.  The (at most four)
-// contributions are added in a fixed order.
+// dU -> dx.  Tile (ty, tx) reads input rows ty*M - 1 ... ty*M + M (local rows
+// 0 ... M + 1), so the M x M pixels starting at (ty*M, tx*M) are its local rows and
+// columns 1 ... M, local row M + 1 of the tile above (on the first of them) and
+// local row 0 of the tile below (on the last), columns and corners alike.  One
+// lane per (tile, channel) gathers those nine contributions for its M x M pixels,
+// in a fixed order; no tile ever writes a pixel of another.
 template <int M>
-__global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dXt,
+__global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dU,
                                                 float* __restrict__ dx, Geometry g) {
   constexpr int n = M + 2;
-  const long total = (long)g.N * g.H * g.W * g.C;
+  static constexpr RMat BT = TabB<M>::BT;
+  const long total = (long)g.T * g.C;
   const long gid = (long)blockIdx.x * 256 + threadIdx.x;
   if (gid >= total) return;
-  const int c = (int)(gid % g.C);
-  const long pix = gid / g.C;
-  const int w = (int)(pix % g.W);
-  const int h = (int)((pix / g.W) % g.H);
-  const int b = (int)(pix / ((long)g.W * g.H));
-  const long TC = (long)g.T * g.C;
-  const int ty1 = (h + 1) / M, i1 = (h + 1) % M;
-  const int tx1 = (w + 1) / M, j1 = (w + 1) % M;
-  float acc = 0.f;
-#pragma unroll
-  for (int dyv = 0; dyv < 2; ++dyv) {
-    const int ty = ty1 - dyv, i = i1 + dyv * M;
-    if (ty < 0 || ty >= g.TH || i >= n) continue;
-#pragma unroll
-    for (int dxv = 0; dxv < 2; ++dxv) {
-      const int tx = tx1 - dxv, j = j1 + dxv * M;
-      if (tx < 0 || tx >= g.TW || j >= n) continue;
-      const long t = ((long)b * g.TH + ty) * g.TW + tx;
-      acc += dXt[(long)(i * n + j) * TC + t * g.C + c];
-    }
-  }
-  dx[gid] = acc;
+  const int t = (int)(gid / g.C);
+  const int c = (int)(gid - (long)t * g.C);
+  const int tx = t % g.TW;
+  const int ty = (t / g.TW) % g.TH;
+  const int b = t / (g.TW * g.TH);
+  float acc[M][M];
+  bfor<0, M>([&](auto i) { bfor<0, M>([&](auto j) { acc[i][j] = 0.f; }); });
+  // neighbour (DY, DX): its local rows [A0, A1] land on my pixel rows AO ...
+  auto neighbour = [&](auto dyc, auto dxc) {
+    constexpr int DY = decltype(dyc)::value, DX = decltype(dxc)::value;
+    constexpr int A0 = DY < 0 ? M + 1 : DY > 0 ? 0 : 1, A1 = DY < 0 ? M + 1 : DY > 0 ? 0 : M;
+    constexpr int B0 = DX < 0 ? M + 1 : DX > 0 ? 0 : 1, B1 = DX < 0 ? M + 1 : DX > 0 ? 0 : M;
+    constexpr int AO = DY > 0 ? M - 1 : 0, BO = DX > 0 ? M - 1 : 0;
+    const int nty = ty + DY, ntx = tx + DX;
+    if (nty < 0 || nty >= g.TH || ntx < 0 || ntx >= g.TW) return;
+    const float* src = dU + (((long)b * g.TH + nty) * g.TW + ntx) * g.C + c;
+    dx_entries<BT, A0, A1, B0, B1, AO, BO>(
+        [&](auto i, auto j) { return src[(long)(decltype(i)::value * n + decltype(j)::value) * total]; },
+        acc);
+  };
+  bfor<0, 3>([&](auto dyi) {
+    bfor<0, 3>([&](auto dxi) {
+      neighbour(ICb<decltype(dyi)::value - 1>{}, ICb<decltype(dxi)::value - 1>{});
+    });
+  });
+  bfor<0, M>([&](auto i) {
+    bfor<0, M>([&](auto j) {
+      const int h = ty * M + decltype(i)::value, w = tx * M + decltype(j)::value;
+      if (h < g.H && w < g.W) dx[(((long)b * g.H + h) * g.W + w) * g.C + c] = acc[i][j];
+    });
+  });
 }
 
 // dV -> dw[k][c][3][3].
@@ -317,11 +355,7 @@ hipError_t bwd_transform(int which, const Geometry& g, const float* in, float* o
       wino_launch((k_bwd_dm<M>), dim3(blocks256((long)g.T * g.K)), dim3(256), st, in, out, g);
       break;
     case 1:
-      wino_launch((k_bwd_dxt<M>), dim3(blocks256((long)g.T * g.C)), dim3(256), st, in, out, g);
-      break;
-    case 2:
-      wino_launch((k_bwd_dx<M>), dim3(blocks256((long)g.N * g.H * g.W * g.C)), dim3(256), st, in,
-                  out, g);
+      wino_launch((k_bwd_dx<M>), dim3(blocks256((long)g.T * g.C)), dim3(256), st, in, out, g);
       break;
     default:
       wino_launch((k_bwd_dw<M>), dim3(blocks256((long)g.K * g.C)), dim3(256), st, in, out, g);
@@ -334,10 +368,7 @@ hipError_t bwd_transform(int which, const Geometry& g, const float* in, float* o
 
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st) {
-  const long items = which == 0   ? (long)g.T * g.K
-                     : which == 1 ? (long)g.T * g.C
-                     : which == 2 ? (long)g.N * g.H * g.W * g.C
-                                  : (long)g.K * g.C;
+  const long items = which == 0 ? (long)g.T * g.K : which == 1 ? (long)g.T * g.C : (long)g.K * g.C;
   if (items == 0) return hipSuccess;
   switch (g.m) {
     case 2: return bwd_transform<2>(which, g, in, out, st);

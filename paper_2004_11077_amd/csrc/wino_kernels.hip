@@ -6,13 +6,21 @@ namespace wino {
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
-static thread_local ProfileEvents t_profile = {nullptr, nullptr};
+// Pending event pairs of this thread, oldest first; every launch takes one.
+constexpr int kMaxPendingProfiles = 8;
+static thread_local ProfileEvents t_profile[kMaxPendingProfiles];
+static thread_local int t_profile_count = 0;
 
-void set_profile_events(hipEvent_t start, hipEvent_t stop) { t_profile = ProfileEvents{start, stop}; }
+void set_profile_events(hipEvent_t start, hipEvent_t stop) {
+  if (t_profile_count == kMaxPendingProfiles) --t_profile_count;   // full: replace the newest
+  t_profile[t_profile_count++] = ProfileEvents{start, stop};
+}
 
 ProfileEvents take_profile_events() {
-  const ProfileEvents p = t_profile;
-  t_profile = ProfileEvents{nullptr, nullptr};
+  if (t_profile_count == 0) return ProfileEvents{nullptr, nullptr};
+  const ProfileEvents p = t_profile[0];
+  for (int i = 1; i < t_profile_count; ++i) t_profile[i - 1] = t_profile[i];
+  --t_profile_count;
   return p;
 }
 
@@ -269,6 +277,22 @@ __global__ __launch_bounds__(256) void k_probe_mfma_i8(int iters, int* __restric
   if (sum == 0x7fffffff) sink[0] = sum;      // keeps the loop alive; practically never true
 }
 
+__global__ __launch_bounds__(256) void k_probe_mfma_f32(int iters, int* __restrict__ sink) {
+  using v16f = __attribute__((ext_vector_type(16))) float;
+  const float a = (float)(threadIdx.x & 7) * 0.25f, b = (float)(threadIdx.x & 3) - 1.5f;
+  v16f acc[4] = {};
+  for (int i = 0; i < iters; ++i) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[k], 0, 0, 0);
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) sum += acc[k][e];
+  if (sum == 12345.678f) sink[0] = 1;        // keeps the loop alive; practically never true
+}
+
 __global__ __launch_bounds__(256) void k_probe_valu_mad24(int iters, int c, int* __restrict__ sink) {
   int acc[8];
 #pragma unroll
@@ -287,6 +311,8 @@ __global__ __launch_bounds__(256) void k_probe_valu_mad24(int iters, int c, int*
 hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t st) {
   if (kind == 0)
     wino_launch(k_probe_mfma_i8, dim3((unsigned)blocks), dim3(256), st, iters, sink);
+  else if (kind == 2)
+    wino_launch(k_probe_mfma_f32, dim3((unsigned)blocks), dim3(256), st, iters, sink);
   else
     wino_launch(k_probe_valu_mad24, dim3((unsigned)blocks), dim3(256), st, iters, 3, sink);
   return hipGetLastError();

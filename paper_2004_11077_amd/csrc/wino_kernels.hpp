@@ -11,7 +11,8 @@ namespace wino {
 // Optional per-launch timing: a pair of HIP events handed over with
 // set_profile_events() is attached to the NEXT kernel this thread launches
 // through wino_launch (the events then carry that dispatch's own begin and
-// end timestamps); the pair is consumed by that launch.
+// end timestamps); the pair is consumed by that launch.  Pairs queue up (at
+// most 8 pending): the k-th pending pair goes to the k-th launch from now.
 struct ProfileEvents {
   hipEvent_t start, stop;
 };
@@ -163,8 +164,7 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
                         const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
                         hipStream_t st);
 
-// Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> per-tile
-// dX, 2 per-tile dX -> dx, 3 dV -> dw.
+// Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> dx, 3 dV -> dw.
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st);
 // for_weights = false: out = dU[p][t][c] = scale[p] sum_k dM[p][t][k] codes[p][k][c] (codes = V);
@@ -174,7 +174,8 @@ hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float
                                 hipStream_t st);
 
 // Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
-// 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8).
+// 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8),
+// kind 2 = fp32 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of 32x32x2).
 hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t st);
 
 // fp32 path: stage 0 weight (a = w), 1 input (a = x), 2 contraction (a = U, b = V),
