@@ -239,17 +239,26 @@ constexpr int kGT = 64;        // outputs per work group edge
 constexpr int kGR = 32;        // reduction chunk
 constexpr int kLdA = 33;       // ARED: As[row][red], odd stride
 constexpr int kLdT = 68;       // As[red][row] / Bs[red][col], 16-byte aligned rows
+constexpr int kXcds = 8;
 
 template <bool ARED>
 __global__ __launch_bounds__(256) void k_bwd_gemm(const float* __restrict__ A,
                                                   const int8_t* __restrict__ B,
                                                   float* __restrict__ Cout, int rows, int red,
-                                                  int cols, MultTable scale, int row_blocks) {
+                                                  int cols, MultTable scale, int row_blocks,
+                                                  int col_blocks, int units) {
   __shared__ __attribute__((aligned(16))) float As[ARED ? kGT * kLdA : kGR * kLdT];
   __shared__ __attribute__((aligned(16))) float Bs[kGR * kLdT];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int p = blockIdx.y;
-  const int rb = blockIdx.x % row_blocks, cb = blockIdx.x / row_blocks;
+  // Consecutive blocks are spread round-robin over the 8 XCDs, so block L runs on
+  // XCD L % 8.  The column blocks that share one A panel (point p, row block rb: a
+  // "unit") are given to consecutive blocks of ONE XCD, whose L2 then serves the
+  // panel to all of them.
+  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int unit = (slot / col_blocks) * kXcds + xcd;
+  if (unit >= units) return;                     // padding blocks (uniform exit, no barrier yet)
+  const int cb = slot % col_blocks;
+  const int p = unit / row_blocks, rb = unit - p * row_blocks;
   const int row0 = rb * kGT, col0 = cb * kGT;
   const float* Ap = A + (long)p * rows * red;
   const int8_t* Bp = B + (long)p * red * cols;
@@ -387,11 +396,16 @@ hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float
   const int cols = g.C;
   if (rows == 0 || cols == 0) return hipSuccess;
   const int rbk = (rows + kGT - 1) / kGT, cbk = (cols + kGT - 1) / kGT;
-  const dim3 grid((unsigned)(rbk * cbk), (unsigned)n2);
+  const long units = (long)n2 * rbk;
+  const long blocks = (units + kXcds - 1) / kXcds * kXcds * cbk;
+  if (blocks > (1L << 30)) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)blocks);
   if (for_weights)
-    wino_launch((k_bwd_gemm<false>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale, rbk);
+    wino_launch((k_bwd_gemm<false>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale,
+                rbk, cbk, (int)units);
   else
-    wino_launch((k_bwd_gemm<true>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale, rbk);
+    wino_launch((k_bwd_gemm<true>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale,
+                rbk, cbk, (int)units);
   return hipGetLastError();
 }
 
