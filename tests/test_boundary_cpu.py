@@ -182,3 +182,24 @@ def test_per_point_scales_are_validated_before_any_launch():
     assert lib.wino_input_transform(C.byref(d), fake, fake, C.byref(neg), None) == -1
     fm = wn.FlexMatrices(np.ones((6, 3)), np.ones((6, 6)), np.ones((4, 6)))
     assert lib.wino_flex_input_transform(C.byref(d), C.byref(fm), fake, fake, C.byref(pp), None) == -2
+
+
+def test_backward_workspace_and_argument_checks_before_any_launch():
+    lib = binding._load()
+    fake = C.c_void_p(4096)
+    r256 = lambda v: (v + 255) // 256 * 256
+    d = wn.ConvDesc(2, 8, 8, 32, 48)                     # F(4,3): n*n = 36, T = 8
+    want = r256(36 * 8 * 48 * 4) + r256(36 * 8 * 32 * 4) + r256(36 * 48 * 32 * 4)
+    assert wn.wino_backward_workspace_bytes(d) == want
+    s = wn.Scales.from_dict({"s_u": 0.1, "s_v": 0.2})
+    args = lambda desc, sc, ws=fake, nbytes=1 << 30: (
+        C.byref(desc), fake, fake, fake, sc, fake, fake, ws, nbytes, None)
+    assert lib.wino_backward(*args(wn.ConvDesc(2, 8, 8, 32, 48, bits_in=32), C.byref(s))) == -2
+    assert lib.wino_backward(*args(d, None)) == -1                              # no scales
+    assert lib.wino_backward(*args(d, C.byref(wn.Scales.from_dict({"s_u": 0.0, "s_v": 0.2})))) == -1
+    assert lib.wino_backward(*args(d, C.byref(s), nbytes=want - 1)) == -4       # workspace too small
+    assert lib.wino_backward(*args(d, C.byref(s), ws=C.c_void_p(4096 + 64))) == -4   # misaligned
+    assert lib.wino_backward(*args(d, C.byref(s), ws=None)) == -1
+    assert lib.wino_backward(C.byref(d), fake, C.c_void_p(4096 + 4), fake, C.byref(s), fake, fake, fake,
+                             1 << 30, None) == -1                               # U not 16-byte aligned
+    assert lib.wino_backward(C.byref(d), fake, fake, fake, C.byref(s), None, fake, fake, 1 << 30, None) == -1
