@@ -28,8 +28,10 @@ Parity status of each part (what pins it besides itself):
                     unquantised operands it must equal the gradients of direct
                     convolution written from the definition; adjoint identities
                     against the forward oracle; exact finite differences; scalar
-                    loops.  The treatment of a cast in the backward pass is a
-                    reading (the paper gives none).
+                    loops; the flex part (gradients of the trained matrices) also
+                    by finite differences of an unquantised flex forward pass.
+                    The treatment of a cast in the backward pass is a reading
+                    (the paper gives none).
 * ``quantised`` absolute output values: **parity unpinned** by the paper (it
                     prints no worked numeric example; its quantisation figure is
                     missing).  They are pinned oracle <-> GPU only.

@@ -131,3 +131,103 @@ def test_gradient_outside_the_cropped_output_is_dropped():
     t = bw.output_grad_tiles(dy, 4)
     assert t.shape == (2, 4, 4, 1)
     assert np.array_equal(t[1, 0], dy[0, 4]) and not t[1, 1:].any()
+
+
+# ---------------------------------------------------------------------------
+# flex variant: gradients of the trained matrices
+# ---------------------------------------------------------------------------
+def flex_forward_real(x, w, GP, BPT, APT, mats, base):
+    """Unquantised flex layer (casts as identities), plus the tensors the backward pass needs."""
+    n, m = mats.n, mats.m
+    L = bw._f64(mats.PinvT) if base == "legendre" else np.eye(n)
+    Pinv = bw._f64(mats.Pinv) if base == "legendre" else np.eye(n)
+    d = wg.extract_tiles(x, m, 3)                                        # [T,n,n,C]
+    X1 = np.einsum("ia,tabc,jb->tijc", L, d, L)
+    Ut = np.einsum("ia,tabc,jb->tijc", BPT, X1, BPT)
+    W1 = np.einsum("ia,kcab,jb->kijc", GP, w, GP)                         # [K,n,n,C]
+    Vt = np.einsum("ia,kabc,jb->kijc", Pinv, W1, Pinv)
+    M = np.einsum("tijc,kijc->tijk", Ut, Vt)
+    M1 = np.einsum("ia,tabk,jb->tijk", L, M, L)
+    Y = np.einsum("ia,tabk,jb->tijk", APT, M1, APT)
+    N, H, W, _ = x.shape
+    T, C, K = d.shape[0], x.shape[3], w.shape[0]
+    U = Ut.transpose(1, 2, 0, 3).reshape(n * n, T, C)
+    V = Vt.transpose(1, 2, 0, 3).reshape(n * n, K, C)
+    return wg.scatter_tiles(Y, N, H, W, m), X1, M1, U, V
+
+
+def flex_case(m, base, seed, perturb):
+    from oracle.flex import FlexMatrices
+    rng = np.random.default_rng(seed)
+    mats = mx.Matrices(m, 3)
+    fm = FlexMatrices.from_exact(m, 3, base)
+    GP, BPT, APT = (np.asarray(a, dtype=np.float64) for a in (fm.GP, fm.BPT, fm.APT))
+    if perturb:                                   # "trained" matrices: no longer a convolution
+        GP = GP + 0.05 * rng.standard_normal(GP.shape)
+        BPT = BPT + 0.05 * rng.standard_normal(BPT.shape)
+        APT = APT + 0.05 * rng.standard_normal(APT.shape)
+    x = rng.standard_normal((2, 7, 6, 2))
+    w = rng.standard_normal((3, 2, 3, 3))
+    dy = rng.standard_normal((2, 7, 6, 3))
+    return mats, FlexMatrices(GP, BPT, APT), x, w, dy
+
+
+@pytest.mark.parametrize("m,base", [(2, "legendre"), (4, "legendre"), (4, "canonical"), (6, "legendre")])
+def test_flex_backward_with_static_matrices_equals_the_static_backward(m, base):
+    mats, fm, x, w, dy = flex_case(m, base, 21 + m, perturb=False)
+    # exact static matrices in fp64 (from_exact rounds to fp32, which would blur the comparison)
+    pick = (mats.GP, mats.BPT, mats.APT) if base == "legendre" else (mats.G, mats.BT, mats.AT)
+    fm.GP, fm.BPT, fm.APT = (bw._f64(a) for a in pick)
+    y, X1, M1, U, V = flex_forward_real(x, w, fm.GP, fm.BPT, fm.APT, mats, base)
+    assert np.allclose(y, wg.conv_eq3(x, w, mats), rtol=0, atol=1e-7 * 10.0 ** m)
+    got = bw.flex_backward(dy, w, X1, M1, U, V, fm, x.shape, m, base)
+    dx, dw = direct_grads(x, w, dy)
+    scale = 10.0 ** {2: 1, 4: 3, 6: 6}[m]          # conditioning of the Legendre brackets in fp64
+    assert np.abs(got["dx"] - dx).max() <= 1e-12 * scale * np.abs(dx).max()
+    assert np.abs(got["dw"] - dw).max() <= 1e-12 * scale * np.abs(dw).max()
+
+
+@pytest.mark.parametrize("m,base", [(2, "legendre"), (4, "legendre"), (4, "canonical")])
+def test_flex_matrix_gradients_by_finite_differences(m, base):
+    mats, fm, x, w, dy = flex_case(m, base, 5 + m, perturb=True)
+    y, X1, M1, U, V = flex_forward_real(x, w, fm.GP, fm.BPT, fm.APT, mats, base)
+    g = bw.flex_backward(dy, w, X1, M1, U, V, fm, x.shape, m, base)
+
+    def loss(GP, BPT, APT, xx=x, ww=w):
+        return float((flex_forward_real(xx, ww, GP, BPT, APT, mats, base)[0] * dy).sum())
+    h = 1e-5
+    rng = np.random.default_rng(0)
+    for name in ("GP", "BPT", "APT"):
+        Tm = getattr(fm, name)
+        for _ in range(4):
+            i, j = rng.integers(Tm.shape[0]), rng.integers(Tm.shape[1])
+            args = {k: getattr(fm, k).copy() for k in ("GP", "BPT", "APT")}
+            args[name][i, j] += h
+            up = loss(**args)
+            args[name][i, j] -= 2 * h
+            dn = loss(**args)
+            fd = (up - dn) / (2 * h)               # the loss is quadratic in each matrix: O(h^2) error
+            ref = g["d" + name][i, j]
+            assert abs(fd - ref) <= 1e-6 * max(1.0, abs(ref)), (name, i, j, fd, ref)
+    # and the data gradients with perturbed matrices (the layer is still bilinear in x and w)
+    e = np.zeros_like(x); e[1, 3, 2, 1] = 1e-3
+    fd = (loss(fm.GP, fm.BPT, fm.APT, xx=x + e) - loss(fm.GP, fm.BPT, fm.APT, xx=x - e)) / 2e-3
+    assert np.isclose(fd, g["dx"][1, 3, 2, 1], rtol=1e-8, atol=1e-8)
+    e = np.zeros_like(w); e[2, 1, 0, 2] = 1e-3
+    fd = (loss(fm.GP, fm.BPT, fm.APT, ww=w + e) - loss(fm.GP, fm.BPT, fm.APT, ww=w - e)) / 2e-3
+    assert np.isclose(fd, g["dw"][2, 1, 0, 2], rtol=1e-8, atol=1e-8)
+
+
+def test_bracket_gradient_by_scalar_loops():
+    rng = np.random.default_rng(9)
+    Tm = rng.standard_normal((2, 3))
+    S = rng.standard_normal((4, 3, 3, 2))          # [tile, a, b, ch]
+    dR = rng.standard_normal((4, 2, 2, 2))
+    dT, dS = bw._bracket_grads(Tm, S, dR)
+    ref = np.zeros_like(Tm)
+    for t in range(4):
+        for c in range(2):
+            s, g = S[t, :, :, c], dR[t, :, :, c]
+            ref += g @ (Tm @ s.T) + g.T @ (Tm @ s)
+            assert np.allclose(dS[t, :, :, c], Tm.T @ g @ Tm)
+    assert np.allclose(dT, ref)
