@@ -263,6 +263,37 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
                   const wino_scales_t* s, void* dx, void* dw, void* workspace, size_t ws_bytes,
                   void* hip_stream);
 
+/* Backward pass of the flex layer (Section 4.2: G_P, B_P, A_P trained, P and
+ * P^{-1} fixed; casts straight-through as in wino_backward).  Besides dx and dw,
+ * now taken through the run-time matrices, it returns the gradients of the three
+ * matrices.  For a bracket R = T S T^T with trained T, summed over all tiles (or
+ * filters) and channels:  dT = sum dR (T S^T) + dR^T (T S),  dS = T^T dR T;
+ * through a fixed bracket S1 = L S L^T:  dS = L^T dS1 L.  The inputs of the
+ * trained brackets are recomputed from the forward pass's integer tensors with
+ * its exact arithmetic (X1 from x, M1 from M) and dequantised (s_x1, s_m1; in the
+ * canonical base x, M and s_x, s_m).
+ * x [N][H][W][C], w [K][C][3][3], U, V: int8 as in the forward pass; M
+ * [n*n][T][K] with the element type of d->bits_hadamard; dy, dx, dw as in
+ * wino_backward; grads: device fp32 arrays, row-major, dGP n x 3, dBPT n x n,
+ * dAPT m x n (gradients with respect to the entries of f->GP, f->BPT, f->APT).
+ * s: the scales of the forward pass (per-tensor).  Restrictions of the flex
+ * calls apply; every dimension must be positive; d->relu is ignored (mask dy
+ * beforehand).  All sums are taken in a fixed order.
+ * Workspace (device, 256-byte aligned), wino_flex_backward_workspace_bytes():
+ * fp32 dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C], per-tile dX [n*n][T][C]
+ * (each rounded up to 256 bytes), then partial sums.
+ * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
+typedef struct {
+  void* dGP;
+  void* dBPT;
+  void* dAPT;
+} wino_flex_grads_t;
+int wino_flex_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
+int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, const void* dy,
+                       const void* x, const void* w, const void* U, const void* V, const void* M,
+                       const wino_scales_t* s, void* dx, void* dw, const wino_flex_grads_t* grads,
+                       void* workspace, size_t ws_bytes, void* hip_stream);
+
 /* Measurement hook.  The next kernel that the calling thread launches through
  * this library records its own begin into `start_event` and its own end into
  * `stop_event` (hipEvent_t handles created by the caller, either may be null);

@@ -16,6 +16,7 @@ EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_
            "wino_output_transform", "wino_flex_weight_transform", "wino_flex_input_transform",
            "wino_flex_output_transform", "wino_flex_conv2d", "wino_flex_calibrate",
            "wino_backward_workspace_bytes", "wino_backward",
+           "wino_flex_backward_workspace_bytes", "wino_flex_backward",
            "wino_profile_next_launch", "wino_probe_peak", "wino_last_error")
 
 
@@ -99,6 +100,11 @@ class FlexMatrices(C.Structure):
         super().__init__(*[a.ctypes.data_as(C.POINTER(C.c_float)) for a in self._keep])
 
 
+class FlexGrads(C.Structure):
+    """Mirror of wino_flex_grads_t: device fp32 arrays dGP [n,3], dBPT [n,n], dAPT [m,n]."""
+    _fields_ = [(n, C.c_void_p) for n in ("dGP", "dBPT", "dAPT")]
+
+
 def lib_path():
     return os.path.join(HERE, "libwino.so")
 
@@ -143,6 +149,9 @@ def _load():
     lib.wino_profile_next_launch.argtypes = [vp, vp]
     lib.wino_backward_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
     lib.wino_backward.argtypes = [dp, vp, vp, vp, sp, vp, vp, vp, C.c_size_t, vp]
+    lib.wino_flex_backward_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
+    lib.wino_flex_backward.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, sp, vp, vp,
+                                       C.POINTER(FlexGrads), vp, C.c_size_t, vp]
     lib.wino_probe_peak.argtypes = [C.c_int, C.c_int, C.c_int, vp, C.POINTER(C.c_double), vp]
     _lib = lib
     return lib
@@ -242,6 +251,26 @@ def wino_backward(desc, dy, U, V, scales, dx, dw, workspace, stream=None):
                                  _ptr(dw), _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)))
     return dx, dw
+
+
+def wino_flex_backward_workspace_bytes(desc):
+    out = C.c_size_t()
+    _check(_load().wino_flex_backward_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def wino_flex_backward(desc, fm, dy, x, w, U, V, M, scales, dx, dw, dGP, dBPT, dAPT, workspace,
+                       stream=None):
+    """Gradients of one flex layer: dx, dw and the gradients of the three trained
+    matrices (device fp32 tensors dGP [n,3], dBPT [n,n], dAPT [m,n])."""
+    sc = _scales(scales)
+    grads = FlexGrads(dGP.data_ptr(), dBPT.data_ptr(), dAPT.data_ptr())
+    _check(_load().wino_flex_backward(C.byref(desc), C.byref(fm), _ptr(dy), _ptr(x), _ptr(w),
+                                      _ptr(U), _ptr(V), _ptr(M), C.byref(sc), _ptr(dx), _ptr(dw),
+                                      C.byref(grads), _ptr(workspace),
+                                      workspace.numel() * workspace.element_size(),
+                                      _stream(stream)))
+    return dx, dw, dGP, dBPT, dAPT
 
 
 def wino_calibrate_workspace_bytes(desc):

@@ -20,7 +20,8 @@ HIP_SOURCES = ["wino_kernels.hip", "wino_transforms_f2.hip", "wino_transforms_f4
                "wino_transforms_f6.hip", "wino_fp32.hip", "wino_fused.hip",
                "wino_calibrate_f2.hip", "wino_calibrate_f4.hip", "wino_calibrate_f6.hip",
                "wino_flex_f2.hip", "wino_flex_f4.hip", "wino_flex_f6.hip",
-               "wino_backward.hip"]
+               "wino_backward.hip", "wino_flex_backward_f2.hip", "wino_flex_backward_f4.hip",
+               "wino_flex_backward_f6.hip"]
 CXX_SOURCES = ["wino_api.cpp"]
 
 COMMON = ["-std=c++20", "-fPIC", "-fconstexpr-steps=200000000", "-Wall", "-Wno-unused-function"]

@@ -1102,4 +1102,106 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
   return WINO_OK;
 }
 
+namespace {
+struct FlexBwdLayout {
+  size_t dM, dU, dV, dXt, part_out, part_in, part_w, total;
+  long out_blocks, in_blocks, w_blocks;
+};
+FlexBwdLayout flex_bwd_layout(const Geometry& g) {
+  const size_t n2 = (size_t)(g.m + 2) * (g.m + 2);
+  const size_t T = (size_t)g.T, C = (size_t)g.C, K = (size_t)g.K;
+  FlexBwdLayout l;
+  l.out_blocks = (long)((T * K + 255) / 256);
+  l.in_blocks = (long)((T * C + 255) / 256);
+  l.w_blocks = (long)((K * C + 255) / 256);
+  size_t o = 0;
+  l.dM = o;  o += round256(n2 * T * K * 4);
+  l.dU = o;  o += round256(n2 * T * C * 4);
+  l.dV = o;  o += round256(n2 * K * C * 4);
+  l.dXt = o; o += round256(n2 * T * C * 4);
+  l.part_out = o; o += (size_t)l.out_blocks * 256;
+  l.part_in = o;  o += (size_t)l.in_blocks * 256;
+  l.part_w = o;   o += (size_t)l.w_blocks * 256;
+  l.total = o;
+  return l;
+}
+}  // namespace
+
+int wino_flex_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (p.fp32) return fail(WINO_EUNSUPPORTED, "flex layers run on the int8 path (bits_in = 8)");
+  if (!bytes) return fail(WINO_EINVAL, "null bytes");
+  *bytes = flex_bwd_layout(p.g).total;
+  if (*bytes == 0) *bytes = 256;
+  return WINO_OK;
+}
+
+int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, const void* dy,
+                       const void* x, const void* w, const void* U, const void* V, const void* M,
+                       const wino_scales_t* s, void* dx, void* dw, const wino_flex_grads_t* grads,
+                       void* workspace, size_t ws_bytes, void* hip_stream) {
+  FlexPlan fp;
+  if (int rc = make_flex_plan(d, f, &fp)) return rc;
+  const Plan& p = fp.p;
+  const Geometry& g = p.g;
+  if (g.N <= 0 || g.H <= 0 || g.W <= 0 || g.C <= 0 || g.K <= 0)
+    return fail(WINO_EINVAL, "the flex backward pass needs positive dimensions");
+  if (int rc = need(s, "scales")) return rc;
+  if (!grads || !grads->dGP || !grads->dBPT || !grads->dAPT)
+    return fail(WINO_EINVAL, "null matrix gradient");
+  const struct { const void* ptr; const char* name; } ptrs[] = {
+      {dy, "dy"}, {x, "x"}, {w, "w"}, {U, "U"}, {V, "V"}, {M, "M"}, {dx, "dx"}, {dw, "dw"}};
+  for (const auto& q : ptrs)
+    if (int rc = need(q.ptr, q.name)) return rc;
+  for (const auto& q : {ptrs[0], ptrs[3], ptrs[4]})
+    if (int rc = aligned(q.ptr, 16, q.name)) return rc;
+  StageMults mu_in, mu_out;
+  float mult_unused, s_in_m;
+  if (int rc = flex_input_mults(p, s, &mu_in, &mult_unused)) return rc;
+  wino_conv_desc_t dreal = *d;
+  dreal.out_type = WINO_OUT_F32;          // asks flex_output_mults for the scale of the A_P bracket's input
+  if (int rc = flex_output_mults(p, &dreal, s, &mu_out, &s_in_m)) return rc;
+  if (!good_scale(s->s_w)) return fail(WINO_EINVAL, "bad s_w");
+  const float s_in_x = p.two_brackets ? s->s_x1 : s->s_x;
+  const FlexBwdLayout l = flex_bwd_layout(g);
+  if (int rc = need(workspace, "workspace")) return rc;
+  if (ws_bytes < l.total) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, l.total);
+  if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
+  char* ws = static_cast<char*>(workspace);
+  float* dM = reinterpret_cast<float*>(ws + l.dM);
+  float* dU = reinterpret_cast<float*>(ws + l.dU);
+  float* dV = reinterpret_cast<float*>(ws + l.dV);
+  float* dXt = reinterpret_cast<float*>(ws + l.dXt);
+  float* part_out = reinterpret_cast<float*>(ws + l.part_out);
+  float* part_in = reinterpret_cast<float*>(ws + l.part_in);
+  float* part_w = reinterpret_cast<float*>(ws + l.part_w);
+  const int n = g.m + 2, n2 = n * n;
+  MultTable su, sv;
+  std::memset(&su, 0, sizeof su);
+  std::memset(&sv, 0, sizeof sv);
+  for (int q = 0; q < n2; ++q) su.v[q] = s->s_u, sv.v[q] = s->s_v;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const StageMults none{};
+  hipError_t e = launch_flex_backward_stage(0, g, p.legendre, M, p.m_bits, (const float*)dy, dM,
+                                            part_out, fp.fm, mu_out, s_in_m, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward output-bracket launch");
+  e = launch_backward_gemm(false, g, dM, (const int8_t*)V, dU, sv, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward dU launch");
+  e = launch_backward_gemm(true, g, dM, (const int8_t*)U, dV, su, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward dV launch");
+  e = launch_flex_backward_stage(2, g, p.legendre, w, 0, dV, (float*)dw, part_w, fp.fm, none,
+                                 s->s_w, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward filter-bracket launch");
+  e = launch_flex_backward_stage(1, g, p.legendre, x, 0, dU, dXt, part_in, fp.fm, mu_in, s_in_x, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward input-bracket launch");
+  e = launch_flex_backward_stage(3, g, p.legendre, nullptr, 0, dXt, (float*)dx, nullptr, fp.fm,
+                                 none, 0.f, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward tile-sum launch");
+  e = launch_sum_partials(part_out, l.out_blocks, g.m * n, (float*)grads->dAPT, st);
+  if (e == hipSuccess) e = launch_sum_partials(part_in, l.in_blocks, n2, (float*)grads->dBPT, st);
+  if (e == hipSuccess) e = launch_sum_partials(part_w, l.w_blocks, n * 3, (float*)grads->dGP, st);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "flex backward matrix-gradient launch");
+}
+
 }  // extern "C"

@@ -387,6 +387,55 @@ hipError_t launch_backward_transform(int which, const Geometry& g, const float* 
   }
 }
 
+// Column sums of the per-work-group partial sums: one work group per column, every lane
+// adds its rows in ascending order, then a fixed tree over the 256 lanes.
+__global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, long rows,
+                                                      float* __restrict__ out) {
+  __shared__ float s_sum[256];
+  const int v = blockIdx.x;
+  float acc = 0.f;
+  for (long r = threadIdx.x; r < rows; r += 256) acc += part[r * 64 + v];
+  s_sum[threadIdx.x] = acc;
+  __syncthreads();
+#pragma unroll
+  for (int half = 128; half > 0; half >>= 1) {
+    if ((int)threadIdx.x < half) s_sum[threadIdx.x] += s_sum[threadIdx.x + half];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) out[v] = s_sum[0];
+}
+
+hipError_t launch_sum_partials(const float* part, long rows, int count, float* out,
+                               hipStream_t st) {
+  if (count <= 0) return hipSuccess;
+  wino_launch(k_sum_partials, dim3((unsigned)count), dim3(256), st, part, rows, out);
+  return hipGetLastError();
+}
+
+template <int M>
+static hipError_t flex_bwd_stage(int stage, const Geometry& g, bool leg, const void* in, int m_bits,
+                                 const float* grad, float* out, float* part, const FlexMats& fm,
+                                 const StageMults& mu, float s_in, hipStream_t st) {
+  switch (stage) {
+    case 0: return PerMFlexBwd<M>::output(g, leg, in, m_bits, grad, out, part, fm, mu, s_in, st);
+    case 1: return PerMFlexBwd<M>::input(g, leg, (const int8_t*)in, grad, out, part, fm, mu, s_in, st);
+    case 2: return PerMFlexBwd<M>::weight(g, leg, (const int8_t*)in, grad, out, part, fm, s_in, st);
+    default: return PerMFlexBwd<M>::tile_sum(g, grad, out, st);
+  }
+}
+
+hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendre, const void* in,
+                                      int m_bits, const float* grad, float* out, float* part,
+                                      const FlexMats& fm, const StageMults& mu, float s_in,
+                                      hipStream_t st) {
+  switch (g.m) {
+    case 2: return flex_bwd_stage<2>(stage, g, legendre, in, m_bits, grad, out, part, fm, mu, s_in, st);
+    case 4: return flex_bwd_stage<4>(stage, g, legendre, in, m_bits, grad, out, part, fm, mu, s_in, st);
+    case 6: return flex_bwd_stage<6>(stage, g, legendre, in, m_bits, grad, out, part, fm, mu, s_in, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float* dM,
                                 const int8_t* codes, float* out, const MultTable& scale,
                                 hipStream_t st) {

@@ -173,6 +173,33 @@ hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float
                                 const int8_t* codes, float* out, const MultTable& scale,
                                 hipStream_t st);
 
+// Backward pass of the flex layer (wino_flex_backward.hpp).  `part` receives one row
+// of 64 floats per work group (the group's share of the matrix gradient).
+template <int M>
+struct PerMFlexBwd {
+  static hipError_t output(const Geometry& g, bool legendre, const void* M_, int m_bits,
+                           const float* dy, float* dM, float* part, const FlexMats& fm,
+                           const StageMults& mu, float s_in, hipStream_t st);
+  static hipError_t input(const Geometry& g, bool legendre, const int8_t* x, const float* dU,
+                          float* dXt, float* part, const FlexMats& fm, const StageMults& mu,
+                          float s_in, hipStream_t st);
+  static hipError_t weight(const Geometry& g, bool legendre, const int8_t* w, const float* dV,
+                           float* dw, float* part, const FlexMats& fm, float s_w, hipStream_t st);
+  static hipError_t tile_sum(const Geometry& g, const float* dXt, float* dx, hipStream_t st);
+};
+extern template struct PerMFlexBwd<2>;
+extern template struct PerMFlexBwd<4>;
+extern template struct PerMFlexBwd<6>;
+// stage 0 output (in = M, grad = dy, out = dM), 1 input (in = x, grad = dU, out = per-tile
+// dX), 2 weight (in = w, grad = dV, out = dw), 3 tile sum (grad = per-tile dX, out = dx).
+hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendre, const void* in,
+                                      int m_bits, const float* grad, float* out, float* part,
+                                      const FlexMats& fm, const StageMults& mu, float s_in,
+                                      hipStream_t st);
+// out[v] = sum over r < rows of part[r * 64 + v], v < count, in a fixed order.
+hipError_t launch_sum_partials(const float* part, long rows, int count, float* out,
+                               hipStream_t st);
+
 // Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
 // 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8),
 // kind 2 = fp32 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of 32x32x2).
