@@ -526,7 +526,42 @@ def main():
                          "frac_of_measured_peak": gemm_tf / f32_peak},
             "note": "straight-through gradients; the two contraction gradients are fp32 MFMA GEMMs "
                     "of 2*n^2*T*C*K flops each"}
-        del dy, dx, dw, bws
+        # the same for the flex layer (run-time matrices: here the static ones rounded to
+        # fp32), which also returns the gradients of G_P, B_P, A_P; first six of its nine
+        # launches timed (the last three are the column sums of the matrix gradients)
+        fnames = ("dY_M_to_dM_dAPT", "gemm_dU", "gemm_dV", "dV_w_to_dw_dGP", "dU_x_to_tile_dX_dBPT",
+                  "tile_dX_to_dx")
+        bfm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],
+                                         dtype=np.float32) for nm in ("GP", "BPT", "APT")])
+        nn = desc.n
+        dGP = torch.empty((nn, 3), dtype=torch.float32, device=dev)
+        dBPT = torch.empty((nn, nn), dtype=torch.float32, device=dev)
+        dAPT = torch.empty((wl.m, nn), dtype=torch.float32, device=dev)
+        fws = torch.empty(wn.wino_flex_backward_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+
+        def fstep():
+            wn.wino_flex_backward(desc, bfm, dy, x, w, U, V, M, sc, dx, dw, dGP, dBPT, dAPT, fws,
+                                  stream)
+        for _ in range(args.warmup):
+            fstep()
+        torch.cuda.synchronize()
+        fev = [(new_event(), new_event()) for _ in fnames]
+        t0 = time.perf_counter()
+        for i in range(bsteps):
+            if i == bsteps - 1:
+                for a, b in fev:
+                    wn.wino_profile_next_launch(a.value, b.value)
+            fstep()
+        torch.cuda.synchronize()
+        fdt = (time.perf_counter() - t0) / bsteps
+        out["flex_backward_variant"] = {
+            "ms_per_step": fdt * 1e3, "dtype": "f32",
+            "kernel_us": {nm: elapsed_ms(a, b) * 1e3 for nm, (a, b) in zip(fnames, fev)},
+            "note": "dx, dw and the gradients of the three trained matrices"}
+        for a, b in fev:
+            hip.hipEventDestroy(a)
+            hip.hipEventDestroy(b)
+        del dy, dx, dw, bws, fws
     # extra: whole-layer call (wino_conv2d) on the other single-layer configurations, split
     # path and AUTO (which takes the fused kernel where C, K <= 64); not the headline figure
     if want("others") and reps == 1:

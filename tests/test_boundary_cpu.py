@@ -203,3 +203,34 @@ def test_backward_workspace_and_argument_checks_before_any_launch():
     assert lib.wino_backward(C.byref(d), fake, C.c_void_p(4096 + 4), fake, C.byref(s), fake, fake, fake,
                              1 << 30, None) == -1                               # U not 16-byte aligned
     assert lib.wino_backward(C.byref(d), fake, fake, fake, C.byref(s), None, fake, fake, 1 << 30, None) == -1
+
+
+def test_flex_backward_argument_checks_before_any_launch():
+    import numpy as np
+    lib = binding._load()
+    fake = C.c_void_p(4096)
+    r256 = lambda v: (v + 255) // 256 * 256
+    d = wn.ConvDesc(2, 8, 8, 32, 48)                     # n*n = 36, T = 8
+    tensors = r256(36 * 8 * 48 * 4) + 2 * r256(36 * 8 * 32 * 4) + r256(36 * 48 * 32 * 4)
+    blocks = -(-8 * 48 // 256) + -(-8 * 32 // 256) + -(-48 * 32 // 256)
+    assert wn.wino_flex_backward_workspace_bytes(d) == tensors + blocks * 256
+    good = wn.FlexMatrices(np.ones((6, 3)), np.ones((6, 6)), np.ones((4, 6)))
+    s = wn.Scales.from_dict({})
+    grads = binding.FlexGrads(4096, 4096, 4096)
+
+    def call(desc=d, fm=good, sc=s, gr=grads, ws=fake, nbytes=1 << 30, x=fake):
+        return lib.wino_flex_backward(C.byref(desc), C.byref(fm) if fm is not None else None, fake, x,
+                                      fake, fake, fake, fake, C.byref(sc) if sc is not None else None,
+                                      fake, fake, C.byref(gr) if gr is not None else None, ws, nbytes, None)
+    assert call(desc=wn.ConvDesc(2, 8, 8, 32, 48, bits_in=32)) == -2
+    assert call(desc=wn.ConvDesc(2, 8, 8, 32, 48, inner_quant=0)) == -2       # Legendre flex needs the inner casts
+    assert call(desc=wn.ConvDesc(0, 8, 8, 32, 48)) == -1                       # empty problem
+    assert call(fm=None) == -1
+    assert call(sc=None) == -1
+    assert call(gr=None) == -1
+    assert call(gr=binding.FlexGrads(4096, 0, 4096)) == -1
+    assert call(x=None) == -1
+    assert call(sc=wn.Scales.from_dict({"s_x1": 0.0})) == -1
+    assert call(sc=wn.Scales.from_dict({"s_u": np.ones((6, 6)), "s_v": np.ones((6, 6))})) == -2   # per-point
+    assert call(nbytes=tensors) == -4
+    assert call(ws=C.c_void_p(4096 + 128)) == -4
