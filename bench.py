@@ -490,9 +490,9 @@ def main():
         del xws
     # extra: backward pass of the same layer (gradients w.r.t. input and weights from a
     # synthetic output gradient, U and V as the forward pass left them), fp32; each of its
-    # five launches timed by its own event pair
+    # four launches timed by its own event pair
     if want("backward") and reps == 1:
-        bnames = ("dY_to_dM", "gemm_dU", "gemm_dV", "dV_to_dw", "dU_to_dx")
+        bnames = ("dY_to_dM", "gemm_dV_and_dU", "dV_to_dw", "dU_to_dx")
         g = torch.Generator(device="cpu").manual_seed(wl.seed + 1)
         dy = torch.randn((wl.N, wl.H, wl.W, wl.K), generator=g, dtype=torch.float32).to(dev)
         dx = torch.empty((wl.N, wl.H, wl.W, wl.C), dtype=torch.float32, device=dev)
@@ -516,20 +516,20 @@ def main():
             hip.hipEventDestroy(a)
             hip.hipEventDestroy(b)
         gemm_flops = 2.0 * n2 * T * wl.C * wl.K
-        gemm_tf = 2 * gemm_flops / ((kus["gemm_dU"] + kus["gemm_dV"]) * 1e-6) / 1e12
+        gemm_tf = 2 * gemm_flops / (kus["gemm_dV_and_dU"] * 1e-6) / 1e12
         f32_peak = probe(wn.PROBE_MFMA_F32, 4096, 2048)
         out["backward_variant"] = {
             "ms_per_step": bdt * 1e3, "dtype": "f32", "kernel_us": kus,
-            "roofline": {"bound": "mfma", "kernel": "gemm_dU + gemm_dV", "achieved": gemm_tf,
+            "roofline": {"bound": "mfma", "kernel": "gemm_dV_and_dU (both contractions, one launch)", "achieved": gemm_tf,
                          "peak": 157.3, "unit": "TFLOP/s", "frac": gemm_tf / 157.3,
                          "traffic": None, "measured_mfma_f32_TFLOPs": f32_peak,
                          "frac_of_measured_peak": gemm_tf / f32_peak},
             "note": "straight-through gradients; the two contraction gradients are fp32 MFMA GEMMs "
                     "of 2*n^2*T*C*K flops each"}
         # the same for the flex layer (run-time matrices: here the static ones rounded to
-        # fp32), which also returns the gradients of G_P, B_P, A_P; first six of its nine
+        # fp32), which also returns the gradients of G_P, B_P, A_P; first five of its eight
         # launches timed (the last three are the column sums of the matrix gradients)
-        fnames = ("dY_M_to_dM_dAPT", "gemm_dU", "gemm_dV", "dV_w_to_dw_dGP", "dU_x_to_tile_dX_dBPT",
+        fnames = ("dY_M_to_dM_dAPT", "gemm_dV_and_dU", "dV_w_to_dw_dGP", "dU_x_to_tile_dX_dBPT",
                   "tile_dX_to_dx")
         bfm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],
                                          dtype=np.float32) for nm in ("GP", "BPT", "APT")])

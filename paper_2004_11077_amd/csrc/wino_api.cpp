@@ -326,13 +326,20 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
   hipError_t e = launch_backward_transform(0, g, (const float*)dy, dM, st);
   if (e != hipSuccess) return fail_hip(e, "backward dM launch");
   // An empty reduction (K = 0 resp. T = 0) makes the contraction kernels store zeros.
-  if ((long)g.T * g.C) {
-    e = launch_backward_gemm(false, g, dM, (const int8_t*)V, dU, sv, st);
-    if (e != hipSuccess) return fail_hip(e, "backward dU launch");
+  if ((long)g.T * g.C && w_items && g.K) {
+    e = launch_backward_gemms(g, dM, (const int8_t*)U, (const int8_t*)V, dU, dV, su, sv, st);
+    if (e != hipSuccess) return fail_hip(e, "backward contraction launch");
+  } else {
+    if ((long)g.T * g.C) {
+      e = launch_backward_gemm(false, g, dM, (const int8_t*)V, dU, sv, st);
+      if (e != hipSuccess) return fail_hip(e, "backward dU launch");
+    }
+    if (w_items) {
+      e = launch_backward_gemm(true, g, dM, (const int8_t*)U, dV, su, st);
+      if (e != hipSuccess) return fail_hip(e, "backward dV launch");
+    }
   }
   if (w_items) {
-    e = launch_backward_gemm(true, g, dM, (const int8_t*)U, dV, su, st);
-    if (e != hipSuccess) return fail_hip(e, "backward dV launch");
     e = launch_backward_transform(3, g, dV, (float*)dw, st);
     if (e != hipSuccess) return fail_hip(e, "backward dw launch");
   }
@@ -1186,10 +1193,8 @@ int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
   hipError_t e = launch_flex_backward_stage(0, g, p.legendre, M, p.m_bits, (const float*)dy, dM,
                                             part_out, fp.fm, mu_out, s_in_m, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward output-bracket launch");
-  e = launch_backward_gemm(false, g, dM, (const int8_t*)V, dU, sv, st);
-  if (e != hipSuccess) return fail_hip(e, "flex backward dU launch");
-  e = launch_backward_gemm(true, g, dM, (const int8_t*)U, dV, su, st);
-  if (e != hipSuccess) return fail_hip(e, "flex backward dV launch");
+  e = launch_backward_gemms(g, dM, (const int8_t*)U, (const int8_t*)V, dU, dV, su, sv, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward contraction launch");
   e = launch_flex_backward_stage(2, g, p.legendre, w, 0, dV, (float*)dw, part_w, fp.fm, none,
                                  s->s_w, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward filter-bracket launch");

@@ -241,20 +241,33 @@ constexpr int kLdA = 33;       // ARED: As[row][red], odd stride
 constexpr int kLdT = 68;       // As[red][row] / Bs[red][col], 16-byte aligned rows
 constexpr int kXcds = 8;
 
+struct GemmArgs {
+  const float* A;
+  const int8_t* B;
+  float* C;
+  int rows, red, cols;
+  int row_blocks, col_blocks, units;
+  int blocks;                  // ceil(units / 8) * 8 * col_blocks
+};
+
+constexpr int kGemmLds = (kGT * kLdA > kGR * kLdT ? kGT * kLdA : kGR * kLdT) + kGR * kLdT;
+
 template <bool ARED>
-__global__ __launch_bounds__(256) void k_bwd_gemm(const float* __restrict__ A,
-                                                  const int8_t* __restrict__ B,
-                                                  float* __restrict__ Cout, int rows, int red,
-                                                  int cols, MultTable scale, int row_blocks,
-                                                  int col_blocks, int units) {
-  __shared__ __attribute__((aligned(16))) float As[ARED ? kGT * kLdA : kGR * kLdT];
-  __shared__ __attribute__((aligned(16))) float Bs[kGR * kLdT];
+__device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& scale,
+                                          unsigned block, float* __restrict__ smem) {
+  const float* __restrict__ A = ga.A;
+  const int8_t* __restrict__ B = ga.B;
+  float* __restrict__ Cout = ga.C;
+  const int rows = ga.rows, red = ga.red, cols = ga.cols;
+  const int row_blocks = ga.row_blocks, col_blocks = ga.col_blocks, units = ga.units;
+  float* As = smem;
+  float* Bs = smem + (ARED ? kGT * kLdA : kGR * kLdT);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // Consecutive blocks are spread round-robin over the 8 XCDs, so block L runs on
   // XCD L % 8.  The column blocks that share one A panel (point p, row block rb: a
   // "unit") are given to consecutive blocks of ONE XCD, whose L2 then serves the
   // panel to all of them.
-  const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+  const int xcd = block % kXcds, slot = block / kXcds;
   const int unit = (slot / col_blocks) * kXcds + xcd;
   if (unit >= units) return;                     // padding blocks (uniform exit, no barrier yet)
   const int cb = slot % col_blocks;
@@ -354,6 +367,25 @@ __global__ __launch_bounds__(256) void k_bwd_gemm(const float* __restrict__ A,
   }
 }
 
+// One contraction per launch.
+template <bool ARED>
+__global__ __launch_bounds__(256) void k_bwd_gemm(GemmArgs ga, MultTable scale) {
+  __shared__ __attribute__((aligned(16))) float smem[kGemmLds];
+  gemm_body<ARED>(ga, scale, blockIdx.x, smem);
+}
+
+// Both contractions in one launch (they only share their input dM): the blocks of
+// the dV contraction, whose reduction over the tiles is the longer one, come first,
+// the blocks of dU fill the compute units as those drain.
+__global__ __launch_bounds__(256) void k_bwd_gemm_both(GemmArgs for_dv, MultTable s_u,
+                                                        GemmArgs for_du, MultTable s_v) {
+  __shared__ __attribute__((aligned(16))) float smem[kGemmLds];
+  if (blockIdx.x < (unsigned)for_dv.blocks)
+    gemm_body<false>(for_dv, s_u, blockIdx.x, smem);
+  else
+    gemm_body<true>(for_du, s_v, blockIdx.x - (unsigned)for_dv.blocks, smem);
+}
+
 inline unsigned blocks256(long items) { return (unsigned)((items + 255) / 256); }
 
 template <int M>
@@ -436,25 +468,50 @@ hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendr
   }
 }
 
+static bool gemm_args(bool for_weights, const Geometry& g, const float* dM, const int8_t* codes,
+                      float* out, GemmArgs* ga) {
+  const int n2 = (g.m + 2) * (g.m + 2);
+  ga->A = dM;
+  ga->B = codes;
+  ga->C = out;
+  ga->rows = for_weights ? g.K : g.T;
+  ga->red = for_weights ? g.T : g.K;
+  ga->cols = g.C;
+  ga->row_blocks = (ga->rows + kGT - 1) / kGT;
+  ga->col_blocks = (ga->cols + kGT - 1) / kGT;
+  const long units = (long)n2 * ga->row_blocks;
+  const long blocks = (units + kXcds - 1) / kXcds * kXcds * ga->col_blocks;
+  ga->units = (int)units;
+  ga->blocks = (int)blocks;
+  return blocks <= (1L << 30);
+}
+
 hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float* dM,
                                 const int8_t* codes, float* out, const MultTable& scale,
                                 hipStream_t st) {
-  const int n2 = (g.m + 2) * (g.m + 2);
-  const int rows = for_weights ? g.K : g.T;
-  const int red = for_weights ? g.T : g.K;
-  const int cols = g.C;
-  if (rows == 0 || cols == 0) return hipSuccess;
-  const int rbk = (rows + kGT - 1) / kGT, cbk = (cols + kGT - 1) / kGT;
-  const long units = (long)n2 * rbk;
-  const long blocks = (units + kXcds - 1) / kXcds * kXcds * cbk;
-  if (blocks > (1L << 30)) return hipErrorInvalidValue;
-  const dim3 grid((unsigned)blocks);
+  GemmArgs ga;
+  if (!gemm_args(for_weights, g, dM, codes, out, &ga)) return hipErrorInvalidValue;
+  if (ga.rows == 0 || ga.cols == 0) return hipSuccess;
   if (for_weights)
-    wino_launch((k_bwd_gemm<false>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale,
-                rbk, cbk, (int)units);
+    wino_launch((k_bwd_gemm<false>), dim3((unsigned)ga.blocks), dim3(256), st, ga, scale);
   else
-    wino_launch((k_bwd_gemm<true>), grid, dim3(256), st, dM, codes, out, rows, red, cols, scale,
-                rbk, cbk, (int)units);
+    wino_launch((k_bwd_gemm<true>), dim3((unsigned)ga.blocks), dim3(256), st, ga, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_backward_gemms(const Geometry& g, const float* dM, const int8_t* U,
+                                 const int8_t* V, float* dU, float* dV, const MultTable& s_u,
+                                 const MultTable& s_v, hipStream_t st) {
+  GemmArgs for_dv, for_du;
+  if (!gemm_args(true, g, dM, U, dV, &for_dv) || !gemm_args(false, g, dM, V, dU, &for_du))
+    return hipErrorInvalidValue;
+  const bool has_dv = for_dv.rows > 0 && for_dv.cols > 0, has_du = for_du.rows > 0 && for_du.cols > 0;
+  if (!has_dv || !has_du || (long)for_dv.blocks + for_du.blocks > (1L << 30)) {
+    hipError_t e = launch_backward_gemm(false, g, dM, V, dU, s_v, st);
+    return e == hipSuccess ? launch_backward_gemm(true, g, dM, U, dV, s_u, st) : e;
+  }
+  wino_launch(k_bwd_gemm_both, dim3((unsigned)(for_dv.blocks + for_du.blocks)), dim3(256), st, for_dv,
+              s_u, for_du, s_v);
   return hipGetLastError();
 }
 

@@ -200,6 +200,11 @@ hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendr
 hipError_t launch_sum_partials(const float* part, long rows, int count, float* out,
                                hipStream_t st);
 
+// Both contraction gradients in one launch (falls back to two when one is empty).
+hipError_t launch_backward_gemms(const Geometry& g, const float* dM, const int8_t* U,
+                                 const int8_t* V, float* dU, float* dV, const MultTable& s_u,
+                                 const MultTable& s_v, hipStream_t st);
+
 // Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
 // 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8),
 // kind 2 = fp32 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of 32x32x2).
