@@ -322,19 +322,20 @@ __global__ __launch_bounds__(256) void k_fbwd_weight(const int8_t* __restrict__ 
 template <int M>
 __global__ __launch_bounds__(256) void k_bwd_tile_sum(const float* __restrict__ dXt,
                                                       float* __restrict__ dx, Geometry g) {
+  using v4f = __attribute__((ext_vector_type(4))) float;
   constexpr int n = M + 2;
-  const long total = (long)g.N * g.H * g.W * g.C;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
-  if (gid >= total) return;
-  const int c = (int)(gid % g.C);
-  const long pix = gid / g.C;
-  const int w = (int)(pix % g.W);
-  const int h = (int)((pix / g.W) % g.H);
-  const int b = (int)(pix / ((long)g.W * g.H));
+  // one lane per four channels of a pixel (C is a multiple of 16); blockIdx.y = image row
+  const int c4s = g.C / 4;
+  const unsigned e = blockIdx.x * 256 + threadIdx.x;       // index in the row: w * c4s + c4
+  if (e >= (unsigned)(g.W * c4s)) return;
+  const int w = (int)(e / (unsigned)c4s), c = 4 * (int)(e - (unsigned)w * c4s);
+  const long row = (long)blockIdx.y + (long)blockIdx.z * 65535;   // b * H + h
+  if (row >= (long)g.N * g.H) return;
+  const int b = (int)(row / g.H), h = (int)(row - (long)b * g.H);
   const long TC = (long)g.T * g.C;
   const int ty1 = (h + 1) / M, i1 = (h + 1) % M;
   const int tx1 = (w + 1) / M, j1 = (w + 1) % M;
-  float acc = 0.f;
+  v4f acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int dyv = 0; dyv < 2; ++dyv) {
     const int ty = ty1 - dyv, i = i1 + dyv * M;
@@ -344,10 +345,10 @@ __global__ __launch_bounds__(256) void k_bwd_tile_sum(const float* __restrict__ 
       const int tx = tx1 - dxv, j = j1 + dxv * M;
       if (tx < 0 || tx >= g.TW || j >= n) continue;
       const long t = ((long)b * g.TH + ty) * g.TW + tx;
-      acc += dXt[(long)(i * n + j) * TC + t * g.C + c];
+      acc += *reinterpret_cast<const v4f*>(dXt + (long)(i * n + j) * TC + t * g.C + c);
     }
   }
-  dx[gid] = acc;
+  *reinterpret_cast<v4f*>(dx + (row * g.W + w) * g.C + c) = acc;
 }
 
 template <int M>
@@ -398,8 +399,13 @@ hipError_t PerMFlexBwd<M>::weight(const Geometry& g, bool leg, const int8_t* w, 
 template <int M>
 hipError_t PerMFlexBwd<M>::tile_sum(const Geometry& g, const float* dXt, float* dx,
                                     hipStream_t st) {
-  const long items = (long)g.N * g.H * g.W * g.C;
-  wino_launch((k_bwd_tile_sum<M>), dim3((unsigned)((items + 255) / 256)), dim3(256), st, dXt, dx, g);
+  const long rows = (long)g.N * g.H, per_row = (long)g.W * (g.C / 4);
+  if (rows == 0 || per_row == 0) return hipSuccess;
+  // grid: x over a row's (pixel, 4 channels) items, y and z over the image rows
+  const long zs = (rows + 65534) / 65535;
+  if (zs > 65535 || per_row >= (1L << 31)) return hipErrorInvalidValue;
+  const dim3 grid((unsigned)((per_row + 255) / 256), (unsigned)(rows < 65535 ? rows : 65535), (unsigned)zs);
+  wino_launch((k_bwd_tile_sum<M>), grid, dim3(256), st, dXt, dx, g);
   return hipGetLastError();
 }
 
