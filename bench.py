@@ -486,7 +486,7 @@ def main():
         xdt = (time.perf_counter() - t0) / args.steps
         out["flex_variant"] = {"ms_per_step": xdt * 1e3, "value": ops / xdt / 1e12,
                                "unit": "TOPS",
-                               "note": "fp32 brackets with run-time matrices, four launches"}
+                               "note": "fp32 brackets with run-time matrices, three launches"}
         del xws
     # extra: backward pass of the same layer (gradients w.r.t. input and weights from a
     # synthetic output gradient, U and V as the forward pass left them), fp32; each of its

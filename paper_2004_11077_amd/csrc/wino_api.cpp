@@ -1024,15 +1024,33 @@ int wino_flex_conv2d(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, c
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   char* ws = static_cast<char*>(workspace);
   const void* V = w_or_V;
+  void* Vws = nullptr;
   if (!d->weights_pretransformed) {
-    if (int rc = wino_flex_weight_transform(&dd, f, w_or_V, ws, s, hip_stream)) return rc;
+    Vws = ws;
     V = ws;
     ws += round256(n2 * d->K * d->C);
   }
   void* U = ws;
   ws += round256(n2 * p.g.T * d->C);
   void* M = ws;
-  if (int rc = wino_flex_input_transform(&dd, f, x, U, s, hip_stream)) return rc;
+  if (Vws && (long)p.g.T * p.g.C && (long)p.g.K * p.g.C) {
+    // both operand transforms are independent: one launch
+    if (int rc = need(x, "x")) return rc;
+    if (int rc = need(w_or_V, "w")) return rc;
+    if (int rc = need(s, "scales")) return rc;
+    StageMults mu_in, mu_w;
+    float mult_u, mult_first;
+    if (int rc = flex_input_mults(p, s, &mu_in, &mult_u)) return rc;
+    if (int rc = flex_weight_mults(p, s, &mu_w, &mult_first)) return rc;
+    hipError_t e = launch_flex_operands(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U,
+                                        (const int8_t*)w_or_V, (int8_t*)Vws, fp.fm, mu_in, mult_u,
+                                        mu_w, mult_first, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail_hip(e, "flex operand-transform launch");
+  } else {
+    if (Vws)
+      if (int rc = wino_flex_weight_transform(&dd, f, w_or_V, Vws, s, hip_stream)) return rc;
+    if (int rc = wino_flex_input_transform(&dd, f, x, U, s, hip_stream)) return rc;
+  }
   if (int rc = wino_contract(&dd, U, V, M, s, hip_stream)) return rc;
   return wino_flex_output_transform(&dd, f, M, y, s, hip_stream);
 }

@@ -68,14 +68,15 @@ __device__ __forceinline__ float tile_absmax(const float (&v)[R][R]) {
 }
 
 template <int M, bool LEG, int MODE>
-__global__ __launch_bounds__(256) void k_flex_weight(const int8_t* __restrict__ w,
-                                                     int8_t* __restrict__ V,
-                                                     unsigned long long* __restrict__ amax,
-                                                     Geometry g, FlexMats fm, StageMults mu,
-                                                     float mult_first) {
+__device__ __forceinline__ void flex_weight_body(const int8_t* __restrict__ w,
+                                                 int8_t* __restrict__ V,
+                                                 unsigned long long* __restrict__ amax,
+                                                 const Geometry& g, const FlexMats& fm,
+                                                 const StageMults& mu, float mult_first,
+                                                 unsigned block) {
   constexpr int n = M + 2;
   using TB = Tab<M>;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   const long KC = (long)g.K * g.C;
   const bool active = gid < KC;
   int wi[3][3];
@@ -112,14 +113,24 @@ __global__ __launch_bounds__(256) void k_flex_weight(const int8_t* __restrict__ 
 }
 
 template <int M, bool LEG, int MODE>
-__global__ __launch_bounds__(256) void k_flex_input(const int8_t* __restrict__ x,
-                                                    int8_t* __restrict__ U,
-                                                    unsigned long long* __restrict__ amax,
-                                                    Geometry g, FlexMats fm, StageMults mu,
-                                                    float mult_u) {
+__global__ __launch_bounds__(256) void k_flex_weight(const int8_t* __restrict__ w,
+                                                     int8_t* __restrict__ V,
+                                                     unsigned long long* __restrict__ amax,
+                                                     Geometry g, FlexMats fm, StageMults mu,
+                                                     float mult_first) {
+  flex_weight_body<M, LEG, MODE>(w, V, amax, g, fm, mu, mult_first, blockIdx.x);
+}
+
+template <int M, bool LEG, int MODE>
+__device__ __forceinline__ void flex_input_body(const int8_t* __restrict__ x,
+                                                int8_t* __restrict__ U,
+                                                unsigned long long* __restrict__ amax,
+                                                const Geometry& g, const FlexMats& fm,
+                                                const StageMults& mu, float mult_u,
+                                                unsigned block) {
   constexpr int n = M + 2;
   using TB = Tab<M>;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   const long total = (long)g.T * g.C;
   const bool active = gid < total;
   const int t = active ? (int)(gid / g.C) : 0;
@@ -160,6 +171,31 @@ __global__ __launch_bounds__(256) void k_flex_input(const int8_t* __restrict__ x
 
 // OUT: 0 fp32 (mult_out = scale of the bracket's input), 2 int8 codes
 // (mult_out = that scale / s_y).
+template <int M, bool LEG, int MODE>
+__global__ __launch_bounds__(256) void k_flex_input(const int8_t* __restrict__ x,
+                                                    int8_t* __restrict__ U,
+                                                    unsigned long long* __restrict__ amax,
+                                                    Geometry g, FlexMats fm, StageMults mu,
+                                                    float mult_u) {
+  flex_input_body<M, LEG, MODE>(x, U, amax, g, fm, mu, mult_u, blockIdx.x);
+}
+
+// Both operand transforms of a layer in one launch (they are independent): the
+// first nb_in work groups transform input tiles, the rest filters.
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_flex_operands(const int8_t* __restrict__ x,
+                                                       int8_t* __restrict__ U,
+                                                       const int8_t* __restrict__ w,
+                                                       int8_t* __restrict__ V, Geometry g,
+                                                       FlexMats fm, StageMults mu_in, float mult_u,
+                                                       StageMults mu_w, float mult_first,
+                                                       unsigned nb_in) {
+  if (blockIdx.x < nb_in)
+    flex_input_body<M, LEG, kFlexRun>(x, U, nullptr, g, fm, mu_in, mult_u, blockIdx.x);
+  else
+    flex_weight_body<M, LEG, kFlexRun>(w, V, nullptr, g, fm, mu_w, mult_first, blockIdx.x - nb_in);
+}
+
 template <int M, bool LEG, typename MT, int OUT, int MODE>
 __global__ __launch_bounds__(256) void k_flex_output(const MT* __restrict__ Mq,
                                                      void* __restrict__ yv,
@@ -257,6 +293,22 @@ hipError_t PerMFlex<M>::input(const Geometry& g, bool leg, int mode, const int8_
     if (leg) WINO_FLEX_I(true, kFlexCalFloat); else WINO_FLEX_I(false, kFlexCalFloat);
   }
 #undef WINO_FLEX_I
+  return hipGetLastError();
+}
+
+template <int M>
+hipError_t PerMFlex<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+                                 const int8_t* w, int8_t* V, const FlexMats& fm,
+                                 const StageMults& mu_in, float mult_u, const StageMults& mu_w,
+                                 float mult_first, hipStream_t st) {
+  const unsigned nb_in = blocks_for((long)g.T * g.C), nb_w = blocks_for((long)g.K * g.C);
+  const dim3 grid(nb_in + nb_w), bs(256);
+  if (leg)
+    wino_launch((k_flex_operands<M, true>), grid, bs, st, x, U, w, V, g, fm, mu_in, mult_u, mu_w,
+                mult_first, nb_in);
+  else
+    wino_launch((k_flex_operands<M, false>), grid, bs, st, x, U, w, V, g, fm, mu_in, mult_u, mu_w,
+                mult_first, nb_in);
   return hipGetLastError();
 }
 

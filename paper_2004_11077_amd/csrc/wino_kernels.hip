@@ -385,6 +385,18 @@ hipError_t launch_flex_stage(int stage, const Geometry& g, bool leg, int mode, c
   return hipErrorInvalidValue;
 }
 
+hipError_t launch_flex_operands(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+                                const int8_t* w, int8_t* V, const FlexMats& fm,
+                                const StageMults& mu_in, float mult_u, const StageMults& mu_w,
+                                float mult_first, hipStream_t st) {
+  switch (g.m) {
+    case 2: return PerMFlex<2>::operands(g, leg, x, U, w, V, fm, mu_in, mult_u, mu_w, mult_first, st);
+    case 4: return PerMFlex<4>::operands(g, leg, x, U, w, V, fm, mu_in, mult_u, mu_w, mult_first, st);
+    case 6: return PerMFlex<6>::operands(g, leg, x, U, w, V, fm, mu_in, mult_u, mu_w, mult_first, st);
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_weight_transform(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
                                    const StageMults& mu, hipStream_t st) {
   if ((long)g.K * g.C == 0) return hipSuccess;

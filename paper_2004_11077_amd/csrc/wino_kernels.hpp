@@ -114,6 +114,11 @@ struct PerMFlex {
                            void* y, int out_type, bool relu, unsigned long long* amax,
                            const FlexMats& fm, const StageMults& mu, float mult_out,
                            hipStream_t st);
+  // input and weight stage (mode 0) in one launch
+  static hipError_t operands(const Geometry& g, bool legendre, const int8_t* x, int8_t* U,
+                             const int8_t* w, int8_t* V, const FlexMats& fm,
+                             const StageMults& mu_in, float mult_u, const StageMults& mu_w,
+                             float mult_first, hipStream_t st);
 };
 extern template struct PerMFlex<2>;
 extern template struct PerMFlex<4>;
@@ -124,6 +129,12 @@ hipError_t launch_flex_stage(int stage, const Geometry& g, bool legendre, int mo
                              int m_bits, void* out, int out_type, bool relu,
                              unsigned long long* amax, const FlexMats& fm, const StageMults& mu,
                              float mult, hipStream_t st);
+
+// Input and weight stage of a flex layer in one launch (both outputs non-empty).
+hipError_t launch_flex_operands(const Geometry& g, bool legendre, const int8_t* x, int8_t* U,
+                                const int8_t* w, int8_t* V, const FlexMats& fm,
+                                const StageMults& mu_in, float mult_u, const StageMults& mu_w,
+                                float mult_first, hipStream_t st);
 
 // stage: 0 weight, 1 input, 2 output; phase 1 = inner bracket, 2 = outer bracket.
 hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool legendre_inner, int phase,
