@@ -527,8 +527,8 @@ def main():
             "note": "straight-through gradients; the two contraction gradients are fp32 MFMA GEMMs "
                     "of 2*n^2*T*C*K flops each"}
         # the same for the flex layer (run-time matrices: here the static ones rounded to
-        # fp32), which also returns the gradients of G_P, B_P, A_P; first five of its eight
-        # launches timed (the last three are the column sums of the matrix gradients)
+        # fp32), which also returns the gradients of G_P, B_P, A_P; first five of its six
+        # launches timed (the last one sums the partial matrix gradients)
         fnames = ("dY_M_to_dM_dAPT", "gemm_dV_and_dU", "dV_w_to_dw_dGP", "dU_x_to_tile_dX_dBPT",
                   "tile_dX_to_dx")
         bfm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],

@@ -1221,9 +1221,11 @@ int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
   e = launch_flex_backward_stage(3, g, p.legendre, nullptr, 0, dXt, (float*)dx, nullptr, fp.fm,
                                  none, 0.f, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward tile-sum launch");
-  e = launch_sum_partials(part_out, l.out_blocks, g.m * n, (float*)grads->dAPT, st);
-  if (e == hipSuccess) e = launch_sum_partials(part_in, l.in_blocks, n2, (float*)grads->dBPT, st);
-  if (e == hipSuccess) e = launch_sum_partials(part_w, l.w_blocks, n * 3, (float*)grads->dGP, st);
+  const float* const parts[3] = {part_out, part_in, part_w};
+  const long part_rows[3] = {l.out_blocks, l.in_blocks, l.w_blocks};
+  const int part_counts[3] = {g.m * n, n2, n * 3};
+  float* const sums[3] = {(float*)grads->dAPT, (float*)grads->dBPT, (float*)grads->dGP};
+  e = launch_sum_partials(parts, part_rows, part_counts, sums, st);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "flex backward matrix-gradient launch");
 }
 

@@ -419,12 +419,22 @@ hipError_t launch_backward_transform(int which, const Geometry& g, const float* 
   }
 }
 
-// Column sums of the per-work-group partial sums: one work group per column, every lane
-// adds its rows in ascending order, then a fixed tree over the 256 lanes.
-__global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, long rows,
-                                                      float* __restrict__ out) {
+// Column sums of per-work-group partial sums (rows of 64 floats), for up to three
+// arrays in one launch: one work group per column, every lane adds its rows in
+// ascending order, then a fixed tree over the 256 lanes.
+struct PartialSums {
+  const float* part[3];
+  float* out[3];
+  long rows[3];
+  int count[3];
+};
+
+__global__ __launch_bounds__(256) void k_sum_partials(PartialSums ps) {
   __shared__ float s_sum[256];
-  const int v = blockIdx.x;
+  int v = blockIdx.x, which = 0;
+  while (which < 2 && v >= ps.count[which]) v -= ps.count[which++];
+  const float* part = ps.part[which];
+  const long rows = ps.rows[which];
   float acc = 0.f;
   for (long r = threadIdx.x; r < rows; r += 256) acc += part[r * 64 + v];
   s_sum[threadIdx.x] = acc;
@@ -434,13 +444,22 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
     if ((int)threadIdx.x < half) s_sum[threadIdx.x] += s_sum[threadIdx.x + half];
     __syncthreads();
   }
-  if (threadIdx.x == 0) out[v] = s_sum[0];
+  if (threadIdx.x == 0) ps.out[which][v] = s_sum[0];
 }
 
-hipError_t launch_sum_partials(const float* part, long rows, int count, float* out,
-                               hipStream_t st) {
-  if (count <= 0) return hipSuccess;
-  wino_launch(k_sum_partials, dim3((unsigned)count), dim3(256), st, part, rows, out);
+hipError_t launch_sum_partials(const float* const part[3], const long rows[3], const int count[3],
+                               float* const out[3], hipStream_t st) {
+  PartialSums ps;
+  int total = 0;
+  for (int i = 0; i < 3; ++i) {
+    ps.part[i] = part[i];
+    ps.out[i] = out[i];
+    ps.rows[i] = rows[i];
+    ps.count[i] = count[i];
+    total += count[i];
+  }
+  if (total <= 0) return hipSuccess;
+  wino_launch(k_sum_partials, dim3((unsigned)total), dim3(256), st, ps);
   return hipGetLastError();
 }
 

@@ -207,9 +207,10 @@ hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendr
                                       int m_bits, const float* grad, float* out, float* part,
                                       const FlexMats& fm, const StageMults& mu, float s_in,
                                       hipStream_t st);
-// out[v] = sum over r < rows of part[r * 64 + v], v < count, in a fixed order.
-hipError_t launch_sum_partials(const float* part, long rows, int count, float* out,
-                               hipStream_t st);
+// For each of three arrays: out[i][v] = sum over r < rows[i] of part[i][r * 64 + v],
+// v < count[i], in a fixed order; one launch.
+hipError_t launch_sum_partials(const float* const part[3], const long rows[3], const int count[3],
+                               float* const out[3], hipStream_t st);
 
 // Both contraction gradients in one launch (falls back to two when one is empty).
 hipError_t launch_backward_gemms(const Geometry& g, const float* dM, const int8_t* U,
