@@ -122,3 +122,23 @@ def test_backward_after_the_library_forward_pass_headline_shape():
     got = run_backward(dy, fwd["U"], fwd["V"], shape, 4, scales)
     ref = reference(dy, fwd["U"], fwd["V"], shape, 4, scales)
     check(ref, got, 3e-5)
+
+
+def random_cases():
+    rng = np.random.default_rng(4242)
+    out = []
+    for i in range(16):
+        out.append((int(rng.choice([2, 4, 6])),
+                    (int(rng.integers(1, 6)), int(rng.integers(1, 14)), int(rng.integers(1, 14)),
+                     int(rng.choice([16, 32, 48, 80, 144, 272])), int(rng.choice([16, 32, 48, 80, 144]))),
+                    bool(rng.integers(0, 2)), 7000 + i))
+    return out
+
+
+@pytest.mark.parametrize("m,shape,per_point,seed", random_cases(),
+                         ids=lambda v: "x".join(map(str, v)) if isinstance(v, tuple) else str(v))
+def test_backward_random_shapes(m, shape, per_point, seed):
+    """Seeded random shapes: ragged images, 64-blocks and 32-chunks with tails in every dimension."""
+    dy, Uq, Vq, scales = make_case(shape, m, seed=seed, per_point=per_point)
+    got = run_backward(dy, Uq, Vq, shape, m, scales)
+    check(reference(dy, Uq, Vq, shape, m, scales), got, 1e-5)

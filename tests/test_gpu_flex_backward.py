@@ -142,3 +142,26 @@ def test_flex_backward_with_static_matrices_matches_static_backward():
     for name, a, b in (("dx", got["dx"], dx.cpu().numpy()), ("dw", got["dw"], dw.cpu().numpy())):
         err, top = float(np.abs(a - b).max()), float(np.abs(b).max())
         assert err <= 2e-4 * top, "%s: %g vs %g" % (name, err, 2e-4 * top)
+
+
+def random_cases():
+    rng = np.random.default_rng(777)
+    out = []
+    for i in range(10):
+        m = int(rng.choice([2, 4, 6]))
+        out.append((m, str(rng.choice(["canonical", "legendre"])),
+                    (int(rng.integers(1, 4)), int(rng.integers(1, 13)), int(rng.integers(1, 13)),
+                     int(rng.choice([16, 32, 48, 80])), int(rng.choice([16, 32, 48, 80]))),
+                    int(rng.choice([8, 9, 32]))))
+    return out
+
+
+@pytest.mark.parametrize("m,base,shape,bits_hadamard", random_cases())
+def test_flex_backward_random_shapes(m, base, shape, bits_hadamard):
+    N, H, W, C, K = shape
+    xq, wq, s_x, s_w = small_layer(N, H, W, C, K, seed=2100 + m + C + H)
+    fm = noisy_matrices(m, base, seed=29 + m)
+    fwd, sc = oracle_forward(xq, wq, s_x, s_w, fm, m, base, bits_hadamard)
+    dy = np.random.default_rng(11 + K + W).standard_normal((N, H, W, K)).astype(np.float32)
+    got = run_gpu(dy, xq, wq, fwd, sc, fm, m, base, bits_hadamard)
+    check(reference(dy, xq, wq, fwd, sc, fm, m, base), got)
