@@ -6,14 +6,16 @@
 // int8 codes U and V that it contracted, dequantised here by their scales.
 //
 //   dM[p][t][k]  = (A dY_t A^T)[p]                   k_bwd_dm
-//   dU[p][t][c]  = s_v[p] sum_k dM[p][t][k] V[p][k][c]   k_bwd_gemm<true>
-//   dV[p][k][c]  = s_u[p] sum_t dM[p][t][k] U[p][t][c]   k_bwd_gemm<false>
+//   dU[p][t][c]  = s_v[p] sum_k dM[p][t][k] V[p][k][c]   gemm_body<true>   \ one launch,
+//   dV[p][k][c]  = s_u[p] sum_t dM[p][t][k] U[p][t][c]   gemm_body<false>  / k_bwd_gemm_both
 //   dx[b][h][w][c] = sum over the <= 4 tiles t covering the pixel of
 //                    (B dU_t B^T)[its local position in t]       k_bwd_dx
 //   dw[k][c]     = G^T dV G                          k_bwd_dw
 //
 // Layouts as in the forward pass: point-major [n*n][items][channels] for
 // everything in the transform domain, NHWC for dy and dx, KCRS for dw.
+// The launchers of the flex layer's backward kernels (wino_flex_backward.hpp) and
+// the column sums of its matrix gradients are at the end of this file.
 #include "wino_kernels.hpp"
 #include "wino_tables.hpp"
 
