@@ -58,3 +58,37 @@ def test_peak_probes_run_and_report_their_work():
     assert wn.wino_probe_peak(wn.PROBE_VALU_MAD24, 8, 16, sink) == 8 * 256 * 16 * 8
     torch.cuda.synchronize()
     assert int(sink.item()) == 0
+
+
+def test_captured_backward_replays_to_the_eager_result():
+    """wino_backward queues kernels only (no allocation, no memset, no synchronisation)."""
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    N, H, W, C, K, m = 3, 9, 8, 48, 80, 4
+    rng = np.random.default_rng(31)
+    desc = wn.ConvDesc(N, H, W, C, K, m=m)
+    n2, T = desc.n ** 2, desc.tiles
+    dy = torch.from_numpy(rng.standard_normal((N, H, W, K)).astype(np.float32)).to(dev)
+    U = torch.from_numpy(rng.integers(-127, 128, (n2, T, C)).astype(np.int8)).to(dev)
+    V = torch.from_numpy(rng.integers(-127, 128, (n2, K, C)).astype(np.int8)).to(dev)
+    sc = wn.Scales.from_dict({"s_u": 0.02, "s_v": 0.01})
+    dx = torch.zeros((N, H, W, C), dtype=torch.float32, device=dev)
+    dw = torch.zeros((K, C, 3, 3), dtype=torch.float32, device=dev)
+    ws = torch.empty(wn.wino_backward_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        wn.wino_backward(desc, dy, U, V, sc, dx, dw, ws, s)
+        torch.cuda.synchronize()
+        eager_dx, eager_dw = dx.clone(), dw.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            wn.wino_backward(desc, dy, U, V, sc, dx, dw, ws, s)
+    for rep in range(3):
+        dx.fill_(float(rep + 1))
+        dw.fill_(-1.0)
+        ws.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dx, eager_dx) and torch.equal(dw, eager_dw), "replay %d differs" % rep
