@@ -253,6 +253,7 @@ struct GemmArgs {
 };
 
 constexpr int kGemmLds = (kGT * kLdA > kGR * kLdT ? kGT * kLdA : kGR * kLdT) + kGR * kLdT;
+static_assert(kGemmLds >= kGT * kLdT, "the output block is staged in the same LDS");
 
 template <bool ARED>
 __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& scale,
@@ -356,16 +357,25 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
     }
   }
 
-  // acc[i] holds output (row = (i / 4) * 8 + (lane / 32) * 4 + i % 4, col = lane % 32)
+  // acc[i] holds output (row = (i / 4) * 8 + (lane / 32) * 4 + i % 4, col = lane % 32).
+  // The 64 x 64 block goes through LDS (rows of kLdT floats) so that it leaves in
+  // 16-byte stores, a wave writing four 256-byte row segments per instruction.
   const float s = scale.v[p];
-  const int col = col0 + wc + l32;
-  if (col < cols) {
-    float* Cp = Cout + (long)p * rows * cols;
+  __syncthreads();                    // every wave is done with the last chunk's fragments
+  float* Cs = smem;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int row = row0 + wr + (i >> 2) * 8 + lk * 4 + (i & 3);
-      if (row < rows) Cp[(long)row * cols + col] = acc[i] * s;
-    }
+  for (int i = 0; i < 16; ++i)
+    Cs[(wr + (i >> 2) * 8 + lk * 4 + (i & 3)) * kLdT + wc + l32] = acc[i] * s;
+  __syncthreads();
+  float* Cp = Cout + (long)p * rows * cols;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int idx = tid + it * 256;
+    const int r = idx >> 4, q = idx & 15;
+    const int row = row0 + r, col = col0 + 4 * q;
+    if (row < rows && col < cols)     // cols is a multiple of 16: a quad is inside or outside
+      *reinterpret_cast<v4f*>(Cp + (long)row * cols + col) =
+          *reinterpret_cast<const v4f*>(Cs + r * kLdT + 4 * q);
   }
 }
 
