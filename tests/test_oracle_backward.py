@@ -231,3 +231,38 @@ def test_bracket_gradient_by_scalar_loops():
             ref += g @ (Tm @ s.T) + g.T @ (Tm @ s)
             assert np.allclose(dS[t, :, :, c], Tm.T @ g @ Tm)
     assert np.allclose(dT, ref)
+
+
+def test_straight_through_gradients_reduce_the_error_of_a_quantised_flex_layer():
+    """The reading of the cast derivative is only useful if descending along the gradients it
+    gives improves the QUANTISED layer.  Starting from perturbed matrices, a few normalised
+    gradient steps on G_P, B_P, A_P (scales re-calibrated each step, 9-bit Hadamard stage)
+    must bring the output closer to direct convolution of the same dequantised inputs."""
+    from helpers import small_layer
+    from oracle import direct, flex, quantised as q
+    m, base = 4, "legendre"
+    N, H, W, C, K = 2, 8, 8, 16, 16
+    xq, wq, s_x, s_w = small_layer(N, H, W, C, K, seed=5)
+    y_ref = direct.direct_conv(xq.astype(np.float64) * float(s_x), wq.astype(np.float64) * float(s_w))
+    rng = np.random.default_rng(0)
+    fm = flex.FlexMatrices.from_exact(m, base=base)
+    for name in ("GP", "BPT", "APT"):
+        a = getattr(fm, name)
+        setattr(fm, name, (a + 0.03 * rng.standard_normal(a.shape) * np.abs(a).max()).astype(np.float32))
+    cfg = q.LayerConfig(m=m, base=base, bits_hadamard=9, inner_quant=True, out_type="f32")
+    losses = []
+    for _ in range(7):
+        fwd, sc = flex.run_layer_flex(xq, wq, s_x, s_w, cfg, fm)
+        y = fwd["y"].astype(np.float64)
+        losses.append(0.5 * float(((y - y_ref) ** 2).mean()))
+        f = lambda name: float(sc[name])
+        g = bw.flex_backward((y - y_ref) / y_ref.size, wq.astype(np.float64) * f("s_w"),
+                             fwd["X1"].astype(np.float64) * f("s_x1"),
+                             fwd["M1"].astype(np.float64) * f("s_m1"),
+                             bw.dequantise(fwd["U"], f("s_u")), bw.dequantise(fwd["V"], f("s_v")),
+                             fm, xq.shape, m, base)
+        for name in ("GP", "BPT", "APT"):
+            a, d = getattr(fm, name).astype(np.float64), g["d" + name]
+            step = 0.05 * np.abs(a).max() / max(np.abs(d).max(), 1e-30)
+            setattr(fm, name, (a - step * d).astype(np.float32))
+    assert min(losses[3:]) < 0.6 * losses[0], losses
