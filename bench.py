@@ -490,9 +490,9 @@ def main():
         del xws
     # extra: backward pass of the same layer (gradients w.r.t. input and weights from a
     # synthetic output gradient, U and V as the forward pass left them), fp32; each of its
-    # four launches timed by its own event pair
+    # three launches timed by its own event pair
     if want("backward") and reps == 1:
-        bnames = ("dY_to_dM", "gemm_dV_and_dU", "dV_to_dw", "dU_to_dx")
+        bnames = ("dY_to_dM", "gemm_dV_and_dU", "dU_to_dx_and_dV_to_dw")
         g = torch.Generator(device="cpu").manual_seed(wl.seed + 1)
         dy = torch.randn((wl.N, wl.H, wl.W, wl.K), generator=g, dtype=torch.float32).to(dev)
         dx = torch.empty((wl.N, wl.H, wl.W, wl.C), dtype=torch.float32, device=dev)

@@ -339,11 +339,13 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
       if (e != hipSuccess) return fail_hip(e, "backward dV launch");
     }
   }
-  if (w_items) {
+  if (w_items && x_items) {
+    e = launch_backward_dx_dw(g, dU, (float*)dx, dV, (float*)dw, st);
+    if (e != hipSuccess) return fail_hip(e, "backward dx / dw launch");
+  } else if (w_items) {
     e = launch_backward_transform(3, g, dV, (float*)dw, st);
     if (e != hipSuccess) return fail_hip(e, "backward dw launch");
-  }
-  if (x_items) {
+  } else if (x_items) {
     e = launch_backward_transform(1, g, dU, (float*)dx, st);
     if (e != hipSuccess) return fail_hip(e, "backward dx launch");
   }

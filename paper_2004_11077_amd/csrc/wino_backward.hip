@@ -9,8 +9,8 @@
 //   dU[p][t][c]  = s_v[p] sum_k dM[p][t][k] V[p][k][c]   gemm_body<true>   \ one launch,
 //   dV[p][k][c]  = s_u[p] sum_t dM[p][t][k] U[p][t][c]   gemm_body<false>  / k_bwd_gemm_both
 //   dx[b][h][w][c] = sum over the <= 4 tiles t covering the pixel of
-//                    (B dU_t B^T)[its local position in t]       k_bwd_dx
-//   dw[k][c]     = G^T dV G                          k_bwd_dw
+//                    (B dU_t B^T)[its local position in t]       bwd_dx_body  \ one launch,
+//   dw[k][c]     = G^T dV G                          bwd_dw_body  / k_bwd_dx_dw
 //
 // Layouts as in the forward pass: point-major [n*n][items][channels] for
 // everything in the transform domain, NHWC for dy and dx, KCRS for dw.
@@ -156,12 +156,12 @@ __device__ __forceinline__ void dx_entries(Load&& load, float (&acc)[ACC][ACC]) 
 // lane per (tile, channel) gathers those nine contributions for its M x M pixels,
 // in a fixed order; no tile ever writes a pixel of another.
 template <int M>
-__global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dU,
-                                                float* __restrict__ dx, Geometry g) {
+__device__ __forceinline__ void bwd_dx_body(const float* __restrict__ dU, float* __restrict__ dx,
+                                            const Geometry& g, unsigned block) {
   constexpr int n = M + 2;
   static constexpr RMat BT = TabB<M>::BT;
   const long total = (long)g.T * g.C;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   if (gid >= total) return;
   const int t = (int)(gid / g.C);
   const int c = (int)(gid - (long)t * g.C);
@@ -196,13 +196,19 @@ __global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dU,
   });
 }
 
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dU,
+                                                float* __restrict__ dx, Geometry g) {
+  bwd_dx_body<M>(dU, dx, g, blockIdx.x);
+}
+
 // dV -> dw[k][c][3][3].
 template <int M>
-__global__ __launch_bounds__(256) void k_bwd_dw(const float* __restrict__ dV,
-                                                float* __restrict__ dw, Geometry g) {
+__device__ __forceinline__ void bwd_dw_body(const float* __restrict__ dV, float* __restrict__ dw,
+                                            const Geometry& g, unsigned block) {
   constexpr int n = M + 2;
   const long total = (long)g.K * g.C;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   if (gid >= total) return;
   float v[n][n];
   bfor<0, n>([&](auto i) {
@@ -217,6 +223,26 @@ __global__ __launch_bounds__(256) void k_bwd_dw(const float* __restrict__ dV,
       dw[gid * 9 + decltype(a)::value * 3 + decltype(bb)::value] = out[a][bb];
     });
   });
+}
+
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dw(const float* __restrict__ dV,
+                                                float* __restrict__ dw, Geometry g) {
+  bwd_dw_body<M>(dV, dw, g, blockIdx.x);
+}
+
+// The last two steps are independent of each other: one launch, the first nb_dx
+// work groups gather dx, the rest transform dV into dw.
+template <int M>
+__global__ __launch_bounds__(256) void k_bwd_dx_dw(const float* __restrict__ dU,
+                                                   float* __restrict__ dx,
+                                                   const float* __restrict__ dV,
+                                                   float* __restrict__ dw, Geometry g,
+                                                   unsigned nb_dx) {
+  if (blockIdx.x < nb_dx)
+    bwd_dx_body<M>(dU, dx, g, blockIdx.x);
+  else
+    bwd_dw_body<M>(dV, dw, g, blockIdx.x - nb_dx);
 }
 
 // ---------------------------------------------------------------------------
@@ -417,7 +443,25 @@ hipError_t bwd_transform(int which, const Geometry& g, const float* in, float* o
   return hipGetLastError();
 }
 
+template <int M>
+hipError_t bwd_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV, float* dw,
+                     hipStream_t st) {
+  const unsigned nb_dx = blocks256((long)g.T * g.C), nb_dw = blocks256((long)g.K * g.C);
+  wino_launch((k_bwd_dx_dw<M>), dim3(nb_dx + nb_dw), dim3(256), st, dU, dx, dV, dw, g, nb_dx);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV,
+                                 float* dw, hipStream_t st) {
+  switch (g.m) {
+    case 2: return bwd_dx_dw<2>(g, dU, dx, dV, dw, st);
+    case 4: return bwd_dx_dw<4>(g, dU, dx, dV, dw, st);
+    case 6: return bwd_dx_dw<6>(g, dU, dx, dV, dw, st);
+    default: return hipErrorInvalidValue;
+  }
+}
 
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st) {

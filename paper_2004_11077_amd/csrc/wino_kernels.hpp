@@ -178,6 +178,9 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
 // Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> dx, 3 dV -> dw.
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st);
+// dU -> dx and dV -> dw in one launch (both non-empty).
+hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV,
+                                 float* dw, hipStream_t st);
 // for_weights = false: out = dU[p][t][c] = scale[p] sum_k dM[p][t][k] codes[p][k][c] (codes = V);
 // for_weights = true:  out = dV[p][k][c] = scale[p] sum_t dM[p][t][k] codes[p][t][c] (codes = U).
 hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float* dM,
