@@ -527,10 +527,9 @@ def main():
             "note": "straight-through gradients; the two contraction gradients are fp32 MFMA GEMMs "
                     "of 2*n^2*T*C*K flops each"}
         # the same for the flex layer (run-time matrices: here the static ones rounded to
-        # fp32), which also returns the gradients of G_P, B_P, A_P; first five of its six
+        # fp32), which also returns the gradients of G_P, B_P, A_P; first four of its five
         # launches timed (the last one sums the partial matrix gradients)
-        fnames = ("dY_M_to_dM_dAPT", "gemm_dV_and_dU", "dV_w_to_dw_dGP", "dU_x_to_tile_dX_dBPT",
-                  "tile_dX_to_dx")
+        fnames = ("dY_M_to_dM_dAPT", "gemm_dV_and_dU", "input_and_filter_brackets", "tile_dX_to_dx")
         bfm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],
                                          dtype=np.float32) for nm in ("GP", "BPT", "APT")])
         nn = desc.n

@@ -1209,19 +1209,16 @@ int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
   std::memset(&sv, 0, sizeof sv);
   for (int q = 0; q < n2; ++q) su.v[q] = s->s_u, sv.v[q] = s->s_v;
   hipStream_t st = (hipStream_t)hip_stream;
-  const StageMults none{};
-  hipError_t e = launch_flex_backward_stage(0, g, p.legendre, M, p.m_bits, (const float*)dy, dM,
-                                            part_out, fp.fm, mu_out, s_in_m, st);
+  hipError_t e = launch_flex_backward_output(g, p.legendre, M, p.m_bits, (const float*)dy, dM,
+                                             part_out, fp.fm, mu_out, s_in_m, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward output-bracket launch");
   e = launch_backward_gemms(g, dM, (const int8_t*)U, (const int8_t*)V, dU, dV, su, sv, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward contraction launch");
-  e = launch_flex_backward_stage(2, g, p.legendre, w, 0, dV, (float*)dw, part_w, fp.fm, none,
-                                 s->s_w, st);
-  if (e != hipSuccess) return fail_hip(e, "flex backward filter-bracket launch");
-  e = launch_flex_backward_stage(1, g, p.legendre, x, 0, dU, dXt, part_in, fp.fm, mu_in, s_in_x, st);
-  if (e != hipSuccess) return fail_hip(e, "flex backward input-bracket launch");
-  e = launch_flex_backward_stage(3, g, p.legendre, nullptr, 0, dXt, (float*)dx, nullptr, fp.fm,
-                                 none, 0.f, st);
+  e = launch_flex_backward_input_weight(g, p.legendre, (const int8_t*)x, dU, dXt, part_in,
+                                        (const int8_t*)w, dV, (float*)dw, part_w, fp.fm, mu_in,
+                                        s_in_x, s->s_w, st);
+  if (e != hipSuccess) return fail_hip(e, "flex backward input / filter bracket launch");
+  e = launch_flex_backward_tile_sum(g, dXt, (float*)dx, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward tile-sum launch");
   const float* const parts[3] = {part_out, part_in, part_w};
   const long part_rows[3] = {l.out_blocks, l.in_blocks, l.w_blocks};

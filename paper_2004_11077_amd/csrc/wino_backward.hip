@@ -519,29 +519,34 @@ hipError_t launch_sum_partials(const float* const part[3], const long rows[3], c
   return hipGetLastError();
 }
 
-template <int M>
-static hipError_t flex_bwd_stage(int stage, const Geometry& g, bool leg, const void* in, int m_bits,
-                                 const float* grad, float* out, float* part, const FlexMats& fm,
-                                 const StageMults& mu, float s_in, hipStream_t st) {
-  switch (stage) {
-    case 0: return PerMFlexBwd<M>::output(g, leg, in, m_bits, grad, out, part, fm, mu, s_in, st);
-    case 1: return PerMFlexBwd<M>::input(g, leg, (const int8_t*)in, grad, out, part, fm, mu, s_in, st);
-    case 2: return PerMFlexBwd<M>::weight(g, leg, (const int8_t*)in, grad, out, part, fm, s_in, st);
-    default: return PerMFlexBwd<M>::tile_sum(g, grad, out, st);
+#define WINO_BY_M(CALL)            \
+  switch (g.m) {                   \
+    case 2: return PerMFlexBwd<2>::CALL; \
+    case 4: return PerMFlexBwd<4>::CALL; \
+    case 6: return PerMFlexBwd<6>::CALL; \
+    default: return hipErrorInvalidValue; \
   }
+
+hipError_t launch_flex_backward_output(const Geometry& g, bool legendre, const void* M_, int m_bits,
+                                       const float* dy, float* dM, float* part, const FlexMats& fm,
+                                       const StageMults& mu, float s_in, hipStream_t st) {
+  WINO_BY_M(output(g, legendre, M_, m_bits, dy, dM, part, fm, mu, s_in, st))
 }
 
-hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendre, const void* in,
-                                      int m_bits, const float* grad, float* out, float* part,
-                                      const FlexMats& fm, const StageMults& mu, float s_in,
-                                      hipStream_t st) {
-  switch (g.m) {
-    case 2: return flex_bwd_stage<2>(stage, g, legendre, in, m_bits, grad, out, part, fm, mu, s_in, st);
-    case 4: return flex_bwd_stage<4>(stage, g, legendre, in, m_bits, grad, out, part, fm, mu, s_in, st);
-    case 6: return flex_bwd_stage<6>(stage, g, legendre, in, m_bits, grad, out, part, fm, mu, s_in, st);
-    default: return hipErrorInvalidValue;
-  }
+hipError_t launch_flex_backward_input_weight(const Geometry& g, bool legendre, const int8_t* x,
+                                             const float* dU, float* dXt, float* part_in,
+                                             const int8_t* w, const float* dV, float* dw,
+                                             float* part_w, const FlexMats& fm,
+                                             const StageMults& mu, float s_in, float s_w,
+                                             hipStream_t st) {
+  WINO_BY_M(input_weight(g, legendre, x, dU, dXt, part_in, w, dV, dw, part_w, fm, mu, s_in, s_w, st))
 }
+
+hipError_t launch_flex_backward_tile_sum(const Geometry& g, const float* dXt, float* dx,
+                                         hipStream_t st) {
+  WINO_BY_M(tile_sum(g, dXt, dx, st))
+}
+#undef WINO_BY_M
 
 static bool gemm_args(bool for_weights, const Geometry& g, const float* dM, const int8_t* codes,
                       float* out, GemmArgs* ga) {

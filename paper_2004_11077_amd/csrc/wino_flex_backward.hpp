@@ -7,8 +7,8 @@
 // forward pass's exact arithmetic (X1 from x, M1 from M) and dequantised.
 //
 //   k_fbwd_output   dY, M  -> dM, per-block partial sums of dA_P^T
-//   k_fbwd_input    dU, x  -> per-tile dX, per-block partial sums of dB_P^T
-//   k_fbwd_weight   dV, w  -> dw, per-block partial sums of dG_P
+//   fbwd_input_body   dU, x  -> per-tile dX, per-block partial sums of dB_P^T   \ one launch,
+//   fbwd_weight_body  dV, w  -> dw, per-block partial sums of dG_P              / k_fbwd_input_weight
 //   k_bwd_tile_sum  per-tile dX -> dx (fixed order over the <= 4 covering tiles)
 //   k_sum_partials  partial sums -> the three matrix gradients (fixed order)
 // The two contraction gradients between them are those of the static layer.
@@ -203,15 +203,15 @@ __global__ __launch_bounds__(256) void k_fbwd_output(const MT* __restrict__ Mq,
 // dU, x -> per-tile dX [a*n+b][t][c] and the partial sums of dBPT (n x n).
 // s_in: what one code of the B_P bracket's input stands for (s_x1, or s_x).
 template <int M, bool LEG>
-__global__ __launch_bounds__(256) void k_fbwd_input(const int8_t* __restrict__ x,
-                                                    const float* __restrict__ dU,
-                                                    float* __restrict__ dXt,
-                                                    float* __restrict__ part, Geometry g,
-                                                    FlexMats fm, StageMults mu, float s_in) {
+__device__ __forceinline__ void fbwd_input_body(const int8_t* __restrict__ x,
+                                                const float* __restrict__ dU,
+                                                float* __restrict__ dXt, float* __restrict__ part,
+                                                const Geometry& g, const FlexMats& fm,
+                                                const StageMults& mu, float s_in, unsigned block) {
   constexpr int n = M + 2;
   using TB = Tab<M>;
   const long total = (long)g.T * g.C;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   const bool active = gid < total;
   const int t = active ? (int)(gid / g.C) : 0;
   const int c = active ? (int)(gid - (long)t * g.C) : 0;
@@ -266,19 +266,19 @@ __global__ __launch_bounds__(256) void k_fbwd_input(const int8_t* __restrict__ x
       });
     }
   }
-  block_sum_to_row<n * n>(dT, part + (long)blockIdx.x * kPartialStride);
+  block_sum_to_row<n * n>(dT, part + (long)block * kPartialStride);
 }
 
 // dV, w -> dw [k][c][3][3] and the partial sums of dGP (n x 3).
 template <int M, bool LEG>
-__global__ __launch_bounds__(256) void k_fbwd_weight(const int8_t* __restrict__ w,
-                                                     const float* __restrict__ dV,
-                                                     float* __restrict__ dw,
-                                                     float* __restrict__ part, Geometry g,
-                                                     FlexMats fm, float s_w) {
+__device__ __forceinline__ void fbwd_weight_body(const int8_t* __restrict__ w,
+                                                 const float* __restrict__ dV,
+                                                 float* __restrict__ dw, float* __restrict__ part,
+                                                 const Geometry& g, const FlexMats& fm, float s_w,
+                                                 unsigned block) {
   constexpr int n = M + 2;
   const long total = (long)g.K * g.C;
-  const long gid = (long)blockIdx.x * 256 + threadIdx.x;
+  const long gid = (long)block * 256 + threadIdx.x;
   const bool active = gid < total;
   float S[3][3];
   static_for<0, 3>([&](auto a) {
@@ -312,7 +312,21 @@ __global__ __launch_bounds__(256) void k_fbwd_weight(const int8_t* __restrict__ 
       });
     });
   }
-  block_sum_to_row<n * 3>(dT, part + (long)blockIdx.x * kPartialStride);
+  block_sum_to_row<n * 3>(dT, part + (long)block * kPartialStride);
+}
+
+// The input and the filter bracket are independent of each other: one launch, the first
+// nb_in work groups take (tile, channel) items, the rest filters.
+template <int M, bool LEG>
+__global__ __launch_bounds__(256) void k_fbwd_input_weight(
+    const int8_t* __restrict__ x, const float* __restrict__ dU, float* __restrict__ dXt,
+    float* __restrict__ part_in, const int8_t* __restrict__ w, const float* __restrict__ dV,
+    float* __restrict__ dw, float* __restrict__ part_w, Geometry g, FlexMats fm, StageMults mu,
+    float s_in, float s_w, unsigned nb_in) {
+  if (blockIdx.x < nb_in)
+    fbwd_input_body<M, LEG>(x, dU, dXt, part_in, g, fm, mu, s_in, blockIdx.x);
+  else
+    fbwd_weight_body<M, LEG>(w, dV, dw, part_w, g, fm, s_w, blockIdx.x - nb_in);
 }
 
 // dx[b][h][w][c] from per-tile gradients: tile ty reads input rows ty*M - 1 ... ty*M + M,
@@ -373,26 +387,20 @@ hipError_t PerMFlexBwd<M>::output(const Geometry& g, bool leg, const void* Mq, i
 }
 
 template <int M>
-hipError_t PerMFlexBwd<M>::input(const Geometry& g, bool leg, const int8_t* x, const float* dU,
-                                 float* dXt, float* part, const FlexMats& fm,
-                                 const StageMults& mu, float s_in, hipStream_t st) {
-  const dim3 grid((unsigned)(((long)g.T * g.C + 255) / 256)), bs(256);
+hipError_t PerMFlexBwd<M>::input_weight(const Geometry& g, bool leg, const int8_t* x,
+                                        const float* dU, float* dXt, float* part_in,
+                                        const int8_t* w, const float* dV, float* dw,
+                                        float* part_w, const FlexMats& fm, const StageMults& mu,
+                                        float s_in, float s_w, hipStream_t st) {
+  const unsigned nb_in = (unsigned)(((long)g.T * g.C + 255) / 256);
+  const unsigned nb_w = (unsigned)(((long)g.K * g.C + 255) / 256);
+  const dim3 grid(nb_in + nb_w), bs(256);
   if (leg)
-    wino_launch((k_fbwd_input<M, true>), grid, bs, st, x, dU, dXt, part, g, fm, mu, s_in);
+    wino_launch((k_fbwd_input_weight<M, true>), grid, bs, st, x, dU, dXt, part_in, w, dV, dw, part_w,
+                g, fm, mu, s_in, s_w, nb_in);
   else
-    wino_launch((k_fbwd_input<M, false>), grid, bs, st, x, dU, dXt, part, g, fm, mu, s_in);
-  return hipGetLastError();
-}
-
-template <int M>
-hipError_t PerMFlexBwd<M>::weight(const Geometry& g, bool leg, const int8_t* w, const float* dV,
-                                  float* dw, float* part, const FlexMats& fm, float s_w,
-                                  hipStream_t st) {
-  const dim3 grid((unsigned)(((long)g.K * g.C + 255) / 256)), bs(256);
-  if (leg)
-    wino_launch((k_fbwd_weight<M, true>), grid, bs, st, w, dV, dw, part, g, fm, s_w);
-  else
-    wino_launch((k_fbwd_weight<M, false>), grid, bs, st, w, dV, dw, part, g, fm, s_w);
+    wino_launch((k_fbwd_input_weight<M, false>), grid, bs, st, x, dU, dXt, part_in, w, dV, dw,
+                part_w, g, fm, mu, s_in, s_w, nb_in);
   return hipGetLastError();
 }
 

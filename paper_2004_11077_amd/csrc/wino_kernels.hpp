@@ -194,22 +194,27 @@ struct PerMFlexBwd {
   static hipError_t output(const Geometry& g, bool legendre, const void* M_, int m_bits,
                            const float* dy, float* dM, float* part, const FlexMats& fm,
                            const StageMults& mu, float s_in, hipStream_t st);
-  static hipError_t input(const Geometry& g, bool legendre, const int8_t* x, const float* dU,
-                          float* dXt, float* part, const FlexMats& fm, const StageMults& mu,
-                          float s_in, hipStream_t st);
-  static hipError_t weight(const Geometry& g, bool legendre, const int8_t* w, const float* dV,
-                           float* dw, float* part, const FlexMats& fm, float s_w, hipStream_t st);
+  static hipError_t input_weight(const Geometry& g, bool legendre, const int8_t* x,
+                                 const float* dU, float* dXt, float* part_in, const int8_t* w,
+                                 const float* dV, float* dw, float* part_w, const FlexMats& fm,
+                                 const StageMults& mu, float s_in, float s_w, hipStream_t st);
   static hipError_t tile_sum(const Geometry& g, const float* dXt, float* dx, hipStream_t st);
 };
 extern template struct PerMFlexBwd<2>;
 extern template struct PerMFlexBwd<4>;
 extern template struct PerMFlexBwd<6>;
-// stage 0 output (in = M, grad = dy, out = dM), 1 input (in = x, grad = dU, out = per-tile
-// dX), 2 weight (in = w, grad = dV, out = dw), 3 tile sum (grad = per-tile dX, out = dx).
-hipError_t launch_flex_backward_stage(int stage, const Geometry& g, bool legendre, const void* in,
-                                      int m_bits, const float* grad, float* out, float* part,
-                                      const FlexMats& fm, const StageMults& mu, float s_in,
-                                      hipStream_t st);
+// The launches of the flex backward pass besides the contractions, dispatched on g.m.
+hipError_t launch_flex_backward_output(const Geometry& g, bool legendre, const void* M_, int m_bits,
+                                       const float* dy, float* dM, float* part, const FlexMats& fm,
+                                       const StageMults& mu, float s_in, hipStream_t st);
+hipError_t launch_flex_backward_input_weight(const Geometry& g, bool legendre, const int8_t* x,
+                                             const float* dU, float* dXt, float* part_in,
+                                             const int8_t* w, const float* dV, float* dw,
+                                             float* part_w, const FlexMats& fm,
+                                             const StageMults& mu, float s_in, float s_w,
+                                             hipStream_t st);
+hipError_t launch_flex_backward_tile_sum(const Geometry& g, const float* dXt, float* dx,
+                                         hipStream_t st);
 // For each of three arrays: out[i][v] = sum over r < rows[i] of part[i][r * 64 + v],
 // v < count[i], in a fixed order; one launch.
 hipError_t launch_sum_partials(const float* const part[3], const long rows[3], const int count[3],
