@@ -252,7 +252,10 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
  * s_v_pt) are read.  All arithmetic is fp32 (fp32 matrix instructions for the
  * two contractions); sums over tiles are taken in a fixed order, so results
  * are reproducible.  Int8 path only (d->bits_in = 8).  Pixels of partial tiles
- * outside H x W receive no gradient.
+ * outside H x W receive no gradient.  d->relu, d->out_type, d->bits_hadamard
+ * and d->fused are ignored: dy is the gradient at the layer's real output, a
+ * ReLU or an output cast behind it is the caller's to apply to dy beforehand.
+ * Inputs are only read; dx, dw and the workspace are overwritten.
  * Workspace (device, 256-byte aligned), wino_backward_workspace_bytes(): three
  * fp32 tensors in this order, each rounded up to 256 bytes:
  * dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C]; they hold those intermediate
