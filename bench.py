@@ -492,7 +492,9 @@ def main():
     # synthetic output gradient, U and V as the forward pass left them), fp32; each of its
     # three launches timed by its own event pair
     if want("backward") and reps == 1:
-        bnames = ("dY_to_dM", "gemm_dV_and_dU", "dU_to_dx_and_dV_to_dw")
+        parts = wn.wino_backward_dv_parts(desc)      # > 1: one more launch, which adds the parts of dV
+        extra_launch = ("sum_dV_parts",) if parts > 1 else ()
+        bnames = ("dY_to_dM", "gemm_dV_and_dU") + extra_launch + ("dU_to_dx_and_dV_to_dw",)
         g = torch.Generator(device="cpu").manual_seed(wl.seed + 1)
         dy = torch.randn((wl.N, wl.H, wl.W, wl.K), generator=g, dtype=torch.float32).to(dev)
         dx = torch.empty((wl.N, wl.H, wl.W, wl.C), dtype=torch.float32, device=dev)
@@ -529,7 +531,8 @@ def main():
         # the same for the flex layer (run-time matrices: here the static ones rounded to
         # fp32), which also returns the gradients of G_P, B_P, A_P; first four of its five
         # launches timed (the last one sums the partial matrix gradients)
-        fnames = ("dY_M_to_dM_dAPT", "gemm_dV_and_dU", "input_and_filter_brackets", "tile_dX_to_dx")
+        fnames = ("dY_M_to_dM_dAPT", "gemm_dV_and_dU") + extra_launch + ("input_and_filter_brackets",
+                                                                         "tile_dX_to_dx")
         bfm = wn.FlexMatrices(*[np.array([[float(v) for v in row] for row in getattr(mats, nm)],
                                          dtype=np.float32) for nm in ("GP", "BPT", "APT")])
         nn = desc.n

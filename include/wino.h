@@ -257,11 +257,17 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
  * ReLU or an output cast behind it is the caller's to apply to dy beforehand.
  * Inputs are only read; dx, dw and the workspace are overwritten.
  * Workspace (device, 256-byte aligned), wino_backward_workspace_bytes(): three
- * fp32 tensors in this order, each rounded up to 256 bytes:
- * dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C]; they hold those intermediate
- * gradients when the call returns.
+ * fp32 regions in this order, each rounded up to 256 bytes:
+ * dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C] (followed, for shapes with few
+ * output channels and many tiles, by partial sums of dV over ranges of tiles);
+ * dM, dU and dV hold those intermediate gradients when the call returns.
  * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
 int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
+/* *parts (host) = number of partial sums over ranges of tiles in which the dV
+ * contraction of this shape is computed (a power of two, 1 ... 32).  With more
+ * than one, both backward calls launch one more kernel that adds them up, and
+ * the dV region of the workspace holds that many tensors. */
+int wino_backward_dv_parts(const wino_conv_desc_t* d, int* parts);
 int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, const void* V,
                   const wino_scales_t* s, void* dx, void* dw, void* workspace, size_t ws_bytes,
                   void* hip_stream);
@@ -283,8 +289,9 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
  * calls apply; every dimension must be positive; d->relu is ignored (mask dy
  * beforehand).  All sums are taken in a fixed order.
  * Workspace (device, 256-byte aligned), wino_flex_backward_workspace_bytes():
- * fp32 dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C], per-tile dX [n*n][T][C]
- * (each rounded up to 256 bytes), then partial sums.
+ * fp32 dM [n*n][T][K], dU [n*n][T][C], dV [n*n][K][C] (plus its partial sums, as
+ * in wino_backward), per-tile dX [n*n][T][C] (each region rounded up to 256
+ * bytes), then the partial sums of the matrix gradients.
  * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
 typedef struct {
   void* dGP;

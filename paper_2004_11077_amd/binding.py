@@ -15,7 +15,7 @@ EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_
            "wino_input_transform", "wino_transform_operands", "wino_contract",
            "wino_output_transform", "wino_flex_weight_transform", "wino_flex_input_transform",
            "wino_flex_output_transform", "wino_flex_conv2d", "wino_flex_calibrate",
-           "wino_backward_workspace_bytes", "wino_backward",
+           "wino_backward_workspace_bytes", "wino_backward_dv_parts", "wino_backward",
            "wino_flex_backward_workspace_bytes", "wino_flex_backward",
            "wino_profile_next_launch", "wino_probe_peak", "wino_last_error")
 
@@ -148,6 +148,7 @@ def _load():
     lib.wino_flex_calibrate.argtypes = [dp, fp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_profile_next_launch.argtypes = [vp, vp]
     lib.wino_backward_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
+    lib.wino_backward_dv_parts.argtypes = [dp, ip]
     lib.wino_backward.argtypes = [dp, vp, vp, vp, sp, vp, vp, vp, C.c_size_t, vp]
     lib.wino_flex_backward_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
     lib.wino_flex_backward.argtypes = [dp, fp, vp, vp, vp, vp, vp, vp, sp, vp, vp,
@@ -240,6 +241,12 @@ def wino_workspace_bytes(desc):
 def wino_backward_workspace_bytes(desc):
     out = C.c_size_t()
     _check(_load().wino_backward_workspace_bytes(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def wino_backward_dv_parts(desc):
+    out = C.c_int()
+    _check(_load().wino_backward_dv_parts(C.byref(desc), C.byref(out)))
     return out.value
 
 

@@ -275,9 +275,18 @@ int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   const size_t T = (size_t)p.g.T, C = (size_t)d->C, K = (size_t)d->K;
-  size_t total = round256(n2 * T * K * 4) + round256(n2 * T * C * 4) + round256(n2 * K * C * 4);
+  const size_t splits = (size_t)backward_dv_splits(p.g);
+  size_t total = round256(n2 * T * K * 4) + round256(n2 * T * C * 4) + round256(splits * n2 * K * C * 4);
   if (total == 0) total = 256;
   *bytes = total;
+  return WINO_OK;
+}
+
+int wino_backward_dv_parts(const wino_conv_desc_t* d, int* parts) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (!parts) return fail(WINO_EINVAL, "null parts");
+  *parts = backward_dv_splits(p.g);
   return WINO_OK;
 }
 
@@ -338,6 +347,10 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
       e = launch_backward_gemm(true, g, dM, (const int8_t*)U, dV, su, st);
       if (e != hipSuccess) return fail_hip(e, "backward dV launch");
     }
+  }
+  if (w_items) {
+    e = launch_backward_sum_splits(g, dV, st);          // no launch unless dV came in several parts
+    if (e != hipSuccess) return fail_hip(e, "backward partial-sum launch");
   }
   if (w_items && x_items) {
     e = launch_backward_dx_dw(g, dU, (float*)dx, dV, (float*)dw, st);
@@ -1144,7 +1157,7 @@ FlexBwdLayout flex_bwd_layout(const Geometry& g) {
   size_t o = 0;
   l.dM = o;  o += round256(n2 * T * K * 4);
   l.dU = o;  o += round256(n2 * T * C * 4);
-  l.dV = o;  o += round256(n2 * K * C * 4);
+  l.dV = o;  o += round256((size_t)backward_dv_splits(g) * n2 * K * C * 4);
   l.dXt = o; o += round256(n2 * T * C * 4);
   l.part_out = o; o += (size_t)l.out_blocks * 256;
   l.part_in = o;  o += (size_t)l.in_blocks * 256;
@@ -1214,6 +1227,8 @@ int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
   if (e != hipSuccess) return fail_hip(e, "flex backward output-bracket launch");
   e = launch_backward_gemms(g, dM, (const int8_t*)U, (const int8_t*)V, dU, dV, su, sv, st);
   if (e != hipSuccess) return fail_hip(e, "flex backward contraction launch");
+  e = launch_backward_sum_splits(g, dV, st);            // no launch unless dV came in several parts
+  if (e != hipSuccess) return fail_hip(e, "flex backward partial-sum launch");
   e = launch_flex_backward_input_weight(g, p.legendre, (const int8_t*)x, dU, dXt, part_in,
                                         (const int8_t*)w, dV, (float*)dw, part_w, fp.fm, mu_in,
                                         s_in_x, s->s_w, st);

@@ -275,7 +275,10 @@ struct GemmArgs {
   float* C;
   int rows, red, cols;
   int row_blocks, col_blocks, units;
-  int blocks;                  // ceil(units / 8) * 8 * col_blocks
+  int blocks;                  // splits * ceil(units / 8) * 8 * col_blocks
+  int splits, red_split;       // the reduction is cut into `splits` ranges of red_split (a multiple
+                               // of the chunk); range s writes its partial sum to C + s * n*n*rows*cols
+  long out_stride;             // n*n * rows * cols
 };
 
 constexpr int kGemmLds = (kGT * kLdA > kGR * kLdT ? kGT * kLdA : kGR * kLdT) + kGR * kLdT;
@@ -292,6 +295,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   float* As = smem;
   float* Bs = smem + (ARED ? kGT * kLdA : kGR * kLdT);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per_split = ga.blocks / ga.splits;
+  const int split = (int)(block / (unsigned)per_split);
+  block -= (unsigned)split * (unsigned)per_split;
+  const int r_begin = split * ga.red_split, r_end = min(red, r_begin + ga.red_split);
+  Cout += (long)split * ga.out_stride;
   // Consecutive blocks are spread round-robin over the 8 XCDs, so block L runs on
   // XCD L % 8.  The column blocks that share one A panel (point p, row block rb: a
   // "unit") are given to consecutive blocks of ONE XCD, whose L2 then serves the
@@ -314,11 +322,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
       v4f v = {0.f, 0.f, 0.f, 0.f};
       if constexpr (ARED) {
         const int row = idx >> 3, q = idx & 7;
-        if (row0 + row < rows && r0 + 4 * q < red)
+        if (row0 + row < rows && r0 + 4 * q < r_end)
           v = *reinterpret_cast<const v4f*>(Ap + (long)(row0 + row) * red + r0 + 4 * q);
       } else {
         const int rr = idx >> 4, q = idx & 15;
-        if (r0 + rr < red && row0 + 4 * q < rows)
+        if (r0 + rr < r_end && row0 + 4 * q < rows)
           v = *reinterpret_cast<const v4f*>(Ap + (long)(r0 + rr) * rows + row0 + 4 * q);
       }
       ra[it] = v;
@@ -326,7 +334,7 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
     rbv = v4ib{0, 0, 0, 0};
     if (tid < 128) {
       const int rr = tid >> 2, q = tid & 3;
-      if (r0 + rr < red && col0 + 16 * q < cols)
+      if (r0 + rr < r_end && col0 + 16 * q < cols)
         rbv = *reinterpret_cast<const v4ib*>(Bp + (long)(r0 + rr) * cols + col0 + 16 * q);
     }
   };
@@ -365,12 +373,12 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
   const int l32 = lane & 31, lk = lane >> 5;
 
-  fetch(0);
-  for (int r0 = 0; r0 < red; r0 += kGR) {
+  fetch(r_begin);
+  for (int r0 = r_begin; r0 < r_end; r0 += kGR) {
     __syncthreads();                  // the previous chunk's fragment reads are done
     stage();
     __syncthreads();
-    if (r0 + kGR < red) fetch(r0 + kGR);
+    if (r0 + kGR < r_end) fetch(r0 + kGR);
 #pragma unroll
     for (int kk = 0; kk < kGR; kk += 2) {
       float a;
@@ -452,6 +460,24 @@ hipError_t bwd_dx_dw(const Geometry& g, const float* dU, float* dx, const float*
 }
 
 }  // namespace
+
+// dV[i] = sum over s < splits of dV[s * count + i], ascending s, i < count.
+__global__ __launch_bounds__(256) void k_sum_splits(float* __restrict__ dV, long count, int splits) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= count) return;
+  float acc = dV[i];
+#pragma unroll 4
+  for (int sp = 1; sp < splits; ++sp) acc += dV[(long)sp * count + i];
+  dV[i] = acc;
+}
+
+hipError_t launch_backward_sum_splits(const Geometry& g, float* dV, hipStream_t st) {
+  const int splits = backward_dv_splits(g);
+  const long count = (long)(g.m + 2) * (g.m + 2) * g.K * g.C;
+  if (splits <= 1 || count == 0) return hipSuccess;
+  wino_launch(k_sum_splits, dim3(blocks256(count)), dim3(256), st, dV, count, splits);
+  return hipGetLastError();
+}
 
 hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV,
                                  float* dw, hipStream_t st) {
@@ -548,6 +574,22 @@ hipError_t launch_flex_backward_tile_sum(const Geometry& g, const float* dXt, fl
 }
 #undef WINO_BY_M
 
+// The dV contraction has few outputs (n*n x K x C) and a long reduction (all tiles): where its
+// 64 x 64 tiles would leave most compute units idle, the reduction is cut into 2^j ranges that
+// run as separate work groups and leave partial sums, added up (in ascending order) by
+// k_sum_splits before the filter bracket.  Ranges hold at least four chunks; at most 32, and at most 64 MB of
+// partial sums.
+int backward_dv_splits(const Geometry& g) {
+  const long n2 = (long)(g.m + 2) * (g.m + 2);
+  const long tiles = n2 * ((g.K + kGT - 1) / kGT) * ((g.C + kGT - 1) / kGT);
+  const long chunks = ((long)g.T + kGR - 1) / kGR;
+  const long bytes = n2 * g.K * g.C * 4;
+  int s = 1;
+  while (tiles * s < 512 && (long)s * 2 * 4 <= chunks && s < 32 && (long)s * 2 * bytes <= (64L << 20))
+    s *= 2;
+  return s;
+}
+
 static bool gemm_args(bool for_weights, const Geometry& g, const float* dM, const int8_t* codes,
                       float* out, GemmArgs* ga) {
   const int n2 = (g.m + 2) * (g.m + 2);
@@ -560,7 +602,11 @@ static bool gemm_args(bool for_weights, const Geometry& g, const float* dM, cons
   ga->row_blocks = (ga->rows + kGT - 1) / kGT;
   ga->col_blocks = (ga->cols + kGT - 1) / kGT;
   const long units = (long)n2 * ga->row_blocks;
-  const long blocks = (units + kXcds - 1) / kXcds * kXcds * ga->col_blocks;
+  ga->splits = for_weights ? backward_dv_splits(g) : 1;
+  const long chunks = ((long)ga->red + kGR - 1) / kGR;
+  ga->red_split = (int)((chunks + ga->splits - 1) / ga->splits) * kGR;
+  ga->out_stride = (long)n2 * ga->rows * ga->cols;
+  const long blocks = (units + kXcds - 1) / kXcds * kXcds * ga->col_blocks * ga->splits;
   ga->units = (int)units;
   ga->blocks = (int)blocks;
   return blocks <= (1L << 30);

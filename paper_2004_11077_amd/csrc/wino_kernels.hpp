@@ -178,6 +178,11 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
 // Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> dx, 3 dV -> dw.
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st);
+// Number of partial sums (a power of two, 1 ... 32) the dV contraction leaves for this
+// shape; the dV buffer holds that many [n*n][K][C] tensors, and launch_backward_sum_splits
+// adds them into the first one (no launch when there is only one).
+int backward_dv_splits(const Geometry& g);
+hipError_t launch_backward_sum_splits(const Geometry& g, float* dV, hipStream_t st);
 // dU -> dx and dV -> dw in one launch (both non-empty).
 hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV,
                                  float* dw, hipStream_t st);

@@ -88,6 +88,9 @@ CASES = [
     (6, (1, 12, 12, 16, 32), False),
     (6, (2, 7, 8, 32, 16), True),
     (4, (40, 4, 4, 16, 32), False),         # T = 40: reduction over tiles not a multiple of 32
+    (4, (64, 16, 16, 16, 16), False),       # T = 1024, few outputs: dV summed from 8 ranges of tiles
+    (2, (37, 12, 12, 32, 16), True),        # T = 1332: 8 ranges, the last one ragged
+    (4, (37, 12, 12, 16, 32), False),       # T = 333: 2 ranges of 6 and 5 chunks, the last chunk ragged
 ]
 
 
@@ -95,7 +98,16 @@ CASES = [
 def test_backward_matches_oracle(m, shape, per_point):
     dy, Uq, Vq, scales = make_case(shape, m, seed=900 + m + shape[3], per_point=per_point)
     got = run_backward(dy, Uq, Vq, shape, m, scales)
-    check(reference(dy, Uq, Vq, shape, m, scales), got, 1e-5)
+    # 1e-5 up to reductions of 512 terms, sqrt(L)-scaled beyond (docstring)
+    T = shape[0] * (-(-shape[1] // m)) * (-(-shape[2] // m))
+    check(reference(dy, Uq, Vq, shape, m, scales), got, 1e-5 * max(1.0, (T / 512.0) ** 0.5))
+
+
+def test_dv_parts_of_the_shapes_above():
+    import paper_2004_11077_amd as wn
+    parts = lambda m, s: wn.wino_backward_dv_parts(wn.ConvDesc(*s, m=m))
+    assert parts(4, (64, 16, 16, 16, 16)) == 8 and parts(2, (37, 12, 12, 32, 16)) == 8
+    assert parts(4, (37, 12, 12, 16, 32)) == 2 and parts(4, (256, 8, 8, 256, 256)) == 1
 
 
 @pytest.mark.parametrize("shape", [(0, 8, 8, 16, 16), (2, 8, 8, 16, 0), (2, 8, 8, 0, 16), (2, 0, 8, 16, 16)])

@@ -103,6 +103,8 @@ CASES = [
     (6, "legendre", (1, 12, 12, 16, 32), 8),
     (6, "canonical", (2, 7, 8, 32, 16), 8),
     (4, "legendre", (8, 16, 16, 64, 64), 8),      # 128 tiles: several work groups per partial-sum array
+    (4, "legendre", (40, 12, 12, 16, 16), 8),     # 360 tiles, few outputs: dV summed from 2 ranges of tiles
+    (4, "canonical", (64, 16, 16, 16, 16), 9),    # 1024 tiles: 8 ranges
 ]
 
 
