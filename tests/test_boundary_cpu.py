@@ -234,3 +234,20 @@ def test_flex_backward_argument_checks_before_any_launch():
     assert call(sc=wn.Scales.from_dict({"s_u": np.ones((6, 6)), "s_v": np.ones((6, 6))})) == -2   # per-point
     assert call(nbytes=tensors) == -4
     assert call(ws=C.c_void_p(4096 + 128)) == -4
+
+
+def test_backward_dv_parts_and_their_workspace():
+    r256 = lambda v: (v + 255) // 256 * 256
+    # (shape, m) -> parts: fewer than 512 tiles of 64 x 64 outputs, ranges of at least four 32-tile chunks
+    cases = [((256, 8, 8, 256, 256), 4, 1), ((128, 32, 32, 64, 64), 4, 16), ((128, 16, 16, 128, 128), 4, 4),
+             ((1, 8, 8, 16, 16), 4, 1), ((64, 16, 16, 16, 16), 4, 8), ((37, 12, 12, 16, 32), 4, 2),
+             ((512, 16, 16, 16, 16), 2, 32)]
+    for shape, m, parts in cases:
+        d = wn.ConvDesc(*shape, m=m)
+        assert wn.wino_backward_dv_parts(d) == parts, shape
+        n2, T, (Cc, Kk) = d.n ** 2, d.tiles, shape[3:]
+        assert wn.wino_backward_workspace_bytes(d) == (r256(n2 * T * Kk * 4) + r256(n2 * T * Cc * 4) +
+                                                       r256(parts * n2 * Kk * Cc * 4))
+    lib = binding._load()
+    assert lib.wino_backward_dv_parts(C.byref(wn.ConvDesc(1, 8, 8, 16, 16)), None) == -1
+    assert lib.wino_backward_dv_parts(C.byref(wn.ConvDesc(1, 8, 8, 17, 16)), C.byref(C.c_int())) == -1
