@@ -17,58 +17,13 @@
 // The launchers of the flex layer's backward kernels (wino_flex_backward.hpp) and
 // the column sums of its matrix gradients are at the end of this file.
 #include "wino_kernels.hpp"
-#include "wino_tables.hpp"
+#include "wino_real_brackets.hpp"
 
 namespace wino {
 namespace {
 
 template <int I>
 using ICb = std::integral_constant<int, I>;
-
-template <int B, int E, class F>
-__device__ __forceinline__ void bfor(F&& f) {
-  if constexpr (B < E) {
-    f(ICb<B>{});
-    bfor<B + 1, E>(f);
-  }
-}
-
-template <int M>
-struct TabB {
-  static constexpr MatrixSet ms = standard_matrix_set(M);
-  static constexpr RMat G = ms.G, BT = ms.BT, AT = ms.AT;
-};
-
-// out = Q x Q^T with Q = T^T (T.cols x T.rows): the adjoint of the bracket
-// T x T^T.  Coefficients are the rationals of T rounded to fp32 at compile
-// time; zero coefficients generate no code.
-template <const RMat& T>
-__device__ __forceinline__ void adjoint_sandwich(const float (&x)[T.rows][T.rows],
-                                                 float (&out)[T.cols][T.cols]) {
-  float tmp[T.cols][T.rows];
-  bfor<0, T.cols>([&](auto i) {                  // tmp = T^T x
-    bfor<0, T.rows>([&](auto b) {
-      float acc = 0.f;
-      bfor<0, T.rows>([&](auto a) {
-        constexpr Rat c = T.a[decltype(a)::value][decltype(i)::value];
-        if constexpr (c.num != 0)
-          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), x[a][b], acc);
-      });
-      tmp[i][b] = acc;
-    });
-  });
-  bfor<0, T.cols>([&](auto i) {                  // out = tmp T
-    bfor<0, T.cols>([&](auto j) {
-      float acc = 0.f;
-      bfor<0, T.rows>([&](auto b) {
-        constexpr Rat c = T.a[decltype(b)::value][decltype(j)::value];
-        if constexpr (c.num != 0)
-          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), tmp[i][b], acc);
-      });
-      out[i][j] = acc;
-    });
-  });
-}
 
 // dY -> dM.  One lane per (tile, k); output pixels beyond H x W (partial tiles)
 // carry no gradient.
@@ -85,16 +40,16 @@ __global__ __launch_bounds__(256) void k_bwd_dm(const float* __restrict__ dy,
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
   float v[M][M];
-  bfor<0, M>([&](auto i) {
-    bfor<0, M>([&](auto j) {
+  rfor<0, M>([&](auto i) {
+    rfor<0, M>([&](auto j) {
       const int h = ty * M + decltype(i)::value, w = tx * M + decltype(j)::value;
       v[i][j] = (h < g.H && w < g.W) ? dy[(((long)b * g.H + h) * g.W + w) * g.K + k] : 0.f;
     });
   });
   float out[n][n];
-  adjoint_sandwich<TabB<M>::AT>(v, out);
-  bfor<0, n>([&](auto i) {
-    bfor<0, n>([&](auto j) {
+  adjoint_bracket_f<TabF<M>::AT>(v, out);
+  rfor<0, n>([&](auto i) {
+    rfor<0, n>([&](auto j) {
       dM[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = out[i][j];
     });
   });
@@ -117,15 +72,15 @@ __device__ __forceinline__ void dx_entries(Load&& load, float (&acc)[ACC][ACC]) 
     return false;
   };
   float part[A1 - A0 + 1][n];                    // part[a][j] = sum_i BT[i][a] dU[i][j]
-  bfor<0, n>([&](auto j) {
+  rfor<0, n>([&](auto j) {
     constexpr int J = decltype(j)::value;
     if constexpr (col_used(J)) {
-      bfor<A0, A1 + 1>([&](auto a) { part[decltype(a)::value - A0][J] = 0.f; });
-      bfor<0, n>([&](auto i) {
+      rfor<A0, A1 + 1>([&](auto a) { part[decltype(a)::value - A0][J] = 0.f; });
+      rfor<0, n>([&](auto i) {
         constexpr int I = decltype(i)::value;
         if constexpr (row_used(I)) {
           const float v = load(i, j);
-          bfor<A0, A1 + 1>([&](auto a) {
+          rfor<A0, A1 + 1>([&](auto a) {
             constexpr Rat c = BT.a[I][decltype(a)::value];
             if constexpr (c.num != 0)
               part[decltype(a)::value - A0][J] = __builtin_fmaf(
@@ -135,10 +90,10 @@ __device__ __forceinline__ void dx_entries(Load&& load, float (&acc)[ACC][ACC]) 
       });
     }
   });
-  bfor<A0, A1 + 1>([&](auto a) {
-    bfor<B0, B1 + 1>([&](auto b) {
+  rfor<A0, A1 + 1>([&](auto a) {
+    rfor<B0, B1 + 1>([&](auto b) {
       float sum = 0.f;
-      bfor<0, n>([&](auto j) {
+      rfor<0, n>([&](auto j) {
         constexpr Rat c = BT.a[decltype(j)::value][decltype(b)::value];
         if constexpr (c.num != 0)
           sum = __builtin_fmaf((float)((double)c.num / (double)c.den),
@@ -159,7 +114,7 @@ template <int M>
 __device__ __forceinline__ void bwd_dx_body(const float* __restrict__ dU, float* __restrict__ dx,
                                             const Geometry& g, unsigned block) {
   constexpr int n = M + 2;
-  static constexpr RMat BT = TabB<M>::BT;
+  static constexpr RMat BT = TabF<M>::BT;
   const long total = (long)g.T * g.C;
   const long gid = (long)block * 256 + threadIdx.x;
   if (gid >= total) return;
@@ -169,7 +124,7 @@ __device__ __forceinline__ void bwd_dx_body(const float* __restrict__ dU, float*
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
   float acc[M][M];
-  bfor<0, M>([&](auto i) { bfor<0, M>([&](auto j) { acc[i][j] = 0.f; }); });
+  rfor<0, M>([&](auto i) { rfor<0, M>([&](auto j) { acc[i][j] = 0.f; }); });
   // neighbour (DY, DX): its local rows [A0, A1] land on my pixel rows AO ...
   auto neighbour = [&](auto dyc, auto dxc) {
     constexpr int DY = decltype(dyc)::value, DX = decltype(dxc)::value;
@@ -183,13 +138,13 @@ __device__ __forceinline__ void bwd_dx_body(const float* __restrict__ dU, float*
         [&](auto i, auto j) { return src[(long)(decltype(i)::value * n + decltype(j)::value) * total]; },
         acc);
   };
-  bfor<0, 3>([&](auto dyi) {
-    bfor<0, 3>([&](auto dxi) {
+  rfor<0, 3>([&](auto dyi) {
+    rfor<0, 3>([&](auto dxi) {
       neighbour(ICb<decltype(dyi)::value - 1>{}, ICb<decltype(dxi)::value - 1>{});
     });
   });
-  bfor<0, M>([&](auto i) {
-    bfor<0, M>([&](auto j) {
+  rfor<0, M>([&](auto i) {
+    rfor<0, M>([&](auto j) {
       const int h = ty * M + decltype(i)::value, w = tx * M + decltype(j)::value;
       if (h < g.H && w < g.W) dx[(((long)b * g.H + h) * g.W + w) * g.C + c] = acc[i][j];
     });
@@ -211,15 +166,15 @@ __device__ __forceinline__ void bwd_dw_body(const float* __restrict__ dV, float*
   const long gid = (long)block * 256 + threadIdx.x;
   if (gid >= total) return;
   float v[n][n];
-  bfor<0, n>([&](auto i) {
-    bfor<0, n>([&](auto j) {
+  rfor<0, n>([&](auto i) {
+    rfor<0, n>([&](auto j) {
       v[i][j] = dV[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid];
     });
   });
   float out[3][3];
-  adjoint_sandwich<TabB<M>::G>(v, out);
-  bfor<0, 3>([&](auto a) {
-    bfor<0, 3>([&](auto bb) {
+  adjoint_bracket_f<TabF<M>::G>(v, out);
+  rfor<0, 3>([&](auto a) {
+    rfor<0, 3>([&](auto bb) {
       dw[gid * 9 + decltype(a)::value * 3 + decltype(bb)::value] = out[a][bb];
     });
   });

@@ -14,6 +14,7 @@
 // The two contraction gradients between them are those of the static layer.
 #pragma once
 #include "wino_flex.hpp"
+#include "wino_real_brackets.hpp"
 
 namespace wino {
 
@@ -78,42 +79,6 @@ __device__ __forceinline__ void flex_input_grad(const float* __restrict__ Tm,
     });
   });
 }
-
-// out = T^T x T for a fixed rational matrix T (square), coefficients rounded to fp32
-// at compile time: the adjoint of the bracket T x T^T.
-template <const RMat& T>
-__device__ __forceinline__ void fixed_adjoint(const float (&x)[T.rows][T.rows],
-                                              float (&out)[T.cols][T.cols]) {
-  float tmp[T.cols][T.rows];
-  static_for<0, T.cols>([&](auto i) {
-    static_for<0, T.rows>([&](auto b) {
-      float acc = 0.f;
-      static_for<0, T.rows>([&](auto a) {
-        constexpr Rat c = T.a[decltype(a)::value][decltype(i)::value];
-        if constexpr (c.num != 0)
-          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), x[a][b], acc);
-      });
-      tmp[i][b] = acc;
-    });
-  });
-  static_for<0, T.cols>([&](auto i) {
-    static_for<0, T.cols>([&](auto j) {
-      float acc = 0.f;
-      static_for<0, T.rows>([&](auto b) {
-        constexpr Rat c = T.a[decltype(b)::value][decltype(j)::value];
-        if constexpr (c.num != 0)
-          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), tmp[i][b], acc);
-      });
-      out[i][j] = acc;
-    });
-  });
-}
-
-template <int M>
-struct TabR {
-  static constexpr MatrixSet ms = standard_matrix_set(M);
-  static constexpr RMat PinvT = ms.PinvT, Pinv = ms.Pinv;
-};
 
 // Sum of v[i] over the 256 lanes of the work group, in a fixed order (xor tree
 // inside a wave, then wave 0 + 1 + 2 + 3), written to row[i] by lane i.
@@ -183,7 +148,7 @@ __global__ __launch_bounds__(256) void k_fbwd_output(const MT* __restrict__ Mq,
   if (active) {
     if constexpr (LEG) {
       float out[n][n];
-      fixed_adjoint<TabR<M>::PinvT>(dS, out);
+      adjoint_bracket_f<TabF<M>::PinvT>(dS, out);
       static_for<0, n>([&](auto i) {
         static_for<0, n>([&](auto j) {
           dM[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = out[i][j];
@@ -252,7 +217,7 @@ __device__ __forceinline__ void fbwd_input_body(const int8_t* __restrict__ x,
   if (active) {
     if constexpr (LEG) {
       float out[n][n];
-      fixed_adjoint<TabR<M>::PinvT>(dS, out);
+      adjoint_bracket_f<TabF<M>::PinvT>(dS, out);
       static_for<0, n>([&](auto i) {
         static_for<0, n>([&](auto j) {
           dXt[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = out[i][j];
@@ -295,7 +260,7 @@ __device__ __forceinline__ void fbwd_weight_body(const int8_t* __restrict__ w,
       });
     });
     if constexpr (LEG) {
-      fixed_adjoint<TabR<M>::Pinv>(v, dR);      // V = P^{-1} W1 P^{-T}
+      adjoint_bracket_f<TabF<M>::Pinv>(v, dR);      // V = P^{-1} W1 P^{-T}
     } else {
       static_for<0, n>([&](auto i) { static_for<0, n>([&](auto j) { dR[i][j] = v[i][j]; }); });
     }

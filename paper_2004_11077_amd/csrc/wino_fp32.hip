@@ -5,57 +5,9 @@
 // not tuned: one lane per item in the transforms, one lane per output in the
 // contraction.
 #include "wino_kernels.hpp"
-#include "wino_tables.hpp"
+#include "wino_real_brackets.hpp"
 
 namespace wino {
-
-template <int I>
-using ICf = std::integral_constant<int, I>;
-
-template <int B, int E, class F>
-__device__ __forceinline__ void sfor(F&& f) {
-  if constexpr (B < E) {
-    f(ICf<B>{});
-    sfor<B + 1, E>(f);
-  }
-}
-
-// out = T x T^T with the rational matrix T evaluated to fp32 coefficients at
-// compile time; explicit fused multiply-adds.
-template <const RMat& T>
-__device__ __forceinline__ void sandwich_f(const float (&x)[T.cols][T.cols],
-                                           float (&out)[T.rows][T.rows]) {
-  float tmp[T.rows][T.cols];
-  sfor<0, T.rows>([&](auto i) {
-    sfor<0, T.cols>([&](auto b) {
-      float acc = 0.f;
-      sfor<0, T.cols>([&](auto a) {
-        constexpr Rat c = T.a[decltype(i)::value][decltype(a)::value];
-        if constexpr (c.num != 0)
-          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), x[a][b], acc);
-      });
-      tmp[i][b] = acc;
-    });
-  });
-  sfor<0, T.rows>([&](auto i) {
-    sfor<0, T.rows>([&](auto j) {
-      float acc = 0.f;
-      sfor<0, T.cols>([&](auto b) {
-        constexpr Rat c = T.a[decltype(j)::value][decltype(b)::value];
-        if constexpr (c.num != 0)
-          acc = __builtin_fmaf((float)((double)c.num / (double)c.den), tmp[i][b], acc);
-      });
-      out[i][j] = acc;
-    });
-  });
-}
-
-template <int M>
-struct TabF {
-  static constexpr MatrixSet ms = standard_matrix_set(M);
-  static constexpr RMat G = ms.G, BT = ms.BT, AT = ms.AT, PinvT = ms.PinvT, Pinv = ms.Pinv,
-                        GP = ms.GP, BPT = ms.BPT, APT = ms.APT;
-};
 
 template <int M, bool LEG>
 __global__ __launch_bounds__(256) void k_weight_f32(const float* __restrict__ w,
@@ -66,19 +18,19 @@ __global__ __launch_bounds__(256) void k_weight_f32(const float* __restrict__ w,
   const long KC = (long)g.K * g.C;
   if (gid >= KC) return;
   float wi[3][3];
-  sfor<0, 3>([&](auto a) {
-    sfor<0, 3>([&](auto b) { wi[a][b] = w[gid * 9 + decltype(a)::value * 3 + decltype(b)::value]; });
+  rfor<0, 3>([&](auto a) {
+    rfor<0, 3>([&](auto b) { wi[a][b] = w[gid * 9 + decltype(a)::value * 3 + decltype(b)::value]; });
   });
   float v[n][n];
   if constexpr (LEG) {
     float w1[n][n];
-    sandwich_f<TB::GP>(wi, w1);       // G_P W G_P^T
-    sandwich_f<TB::Pinv>(w1, v);      // P^{-1} ( . ) P^{-T}
+    bracket_f<TB::GP>(wi, w1);       // G_P W G_P^T
+    bracket_f<TB::Pinv>(w1, v);      // P^{-1} ( . ) P^{-T}
   } else {
-    sandwich_f<TB::G>(wi, v);
+    bracket_f<TB::G>(wi, v);
   }
-  sfor<0, n>([&](auto i) {
-    sfor<0, n>([&](auto j) {
+  rfor<0, n>([&](auto i) {
+    rfor<0, n>([&](auto j) {
       V[(long)(decltype(i)::value * n + decltype(j)::value) * KC + gid] = v[i][j];
     });
   });
@@ -98,8 +50,8 @@ __global__ __launch_bounds__(256) void k_input_f32(const float* __restrict__ x,
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
   float xi[n][n];
-  sfor<0, n>([&](auto a) {
-    sfor<0, n>([&](auto bb) {
+  rfor<0, n>([&](auto a) {
+    rfor<0, n>([&](auto bb) {
       const int h = ty * M - 1 + decltype(a)::value;
       const int ww = tx * M - 1 + decltype(bb)::value;
       float v = 0.f;
@@ -111,13 +63,13 @@ __global__ __launch_bounds__(256) void k_input_f32(const float* __restrict__ x,
   float u[n][n];
   if constexpr (LEG) {
     float x1[n][n];
-    sandwich_f<TB::PinvT>(xi, x1);    // P^{-T} X P^{-1}
-    sandwich_f<TB::BPT>(x1, u);       // B_P^T ( . ) B_P
+    bracket_f<TB::PinvT>(xi, x1);    // P^{-T} X P^{-1}
+    bracket_f<TB::BPT>(x1, u);       // B_P^T ( . ) B_P
   } else {
-    sandwich_f<TB::BT>(xi, u);
+    bracket_f<TB::BT>(xi, u);
   }
-  sfor<0, n>([&](auto i) {
-    sfor<0, n>([&](auto j) {
+  rfor<0, n>([&](auto i) {
+    rfor<0, n>([&](auto j) {
       U[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] = u[i][j];
     });
   });
@@ -162,21 +114,21 @@ __global__ __launch_bounds__(256) void k_output_f32(const float* __restrict__ Mq
   const int ty = (t / g.TW) % g.TH;
   const int b = t / (g.TW * g.TH);
   float mi[n][n];
-  sfor<0, n>([&](auto i) {
-    sfor<0, n>([&](auto j) {
+  rfor<0, n>([&](auto i) {
+    rfor<0, n>([&](auto j) {
       mi[i][j] = Mq[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid];
     });
   });
   float out[M][M];
   if constexpr (LEG) {
     float m1[n][n];
-    sandwich_f<TB::PinvT>(mi, m1);    // P^{-T} M P^{-1}
-    sandwich_f<TB::APT>(m1, out);     // A_P^T ( . ) A_P
+    bracket_f<TB::PinvT>(mi, m1);    // P^{-T} M P^{-1}
+    bracket_f<TB::APT>(m1, out);     // A_P^T ( . ) A_P
   } else {
-    sandwich_f<TB::AT>(mi, out);
+    bracket_f<TB::AT>(mi, out);
   }
-  sfor<0, M>([&](auto i) {
-    sfor<0, M>([&](auto j) {
+  rfor<0, M>([&](auto i) {
+    rfor<0, M>([&](auto j) {
       const int h = ty * M + decltype(i)::value;
       const int ww = tx * M + decltype(j)::value;
       if (h < g.H && ww < g.W) {

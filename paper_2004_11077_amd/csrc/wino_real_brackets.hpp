@@ -1,0 +1,85 @@
+// fp32 brackets with the fixed rational matrices of eq. 1-4: T x T^T and its
+// adjoint T^T x T, coefficients rounded to fp32 at compile time, zero
+// coefficients generating no code, explicit fused multiply-adds.  Used by the
+// fp32 forward path and by both backward passes.
+#pragma once
+#include <type_traits>
+
+#include "wino_tables.hpp"
+
+namespace wino {
+
+template <int B, int E, class F>
+__device__ __forceinline__ void rfor(F&& f) {
+  if constexpr (B < E) {
+    f(std::integral_constant<int, B>{});
+    rfor<B + 1, E>(f);
+  }
+}
+
+// The rational matrices of F(M x M, 3 x 3) as template arguments.
+template <int M>
+struct TabF {
+  static constexpr MatrixSet ms = standard_matrix_set(M);
+  static constexpr RMat G = ms.G, BT = ms.BT, AT = ms.AT, PinvT = ms.PinvT, Pinv = ms.Pinv,
+                        GP = ms.GP, BPT = ms.BPT, APT = ms.APT;
+};
+
+template <const RMat& T, int I, int J>
+inline constexpr float kCoef = (float)((double)T.a[I][J].num / (double)T.a[I][J].den);
+
+// out = T x T^T  (x: T.cols x T.cols, out: T.rows x T.rows).
+template <const RMat& T>
+__device__ __forceinline__ void bracket_f(const float (&x)[T.cols][T.cols],
+                                          float (&out)[T.rows][T.rows]) {
+  float tmp[T.rows][T.cols];
+  rfor<0, T.rows>([&](auto i) {
+    rfor<0, T.cols>([&](auto b) {
+      float acc = 0.f;
+      rfor<0, T.cols>([&](auto a) {
+        constexpr int I = decltype(i)::value, A = decltype(a)::value;
+        if constexpr (T.a[I][A].num != 0) acc = __builtin_fmaf(kCoef<T, I, A>, x[a][b], acc);
+      });
+      tmp[i][b] = acc;
+    });
+  });
+  rfor<0, T.rows>([&](auto i) {
+    rfor<0, T.rows>([&](auto j) {
+      float acc = 0.f;
+      rfor<0, T.cols>([&](auto b) {
+        constexpr int J = decltype(j)::value, Bc = decltype(b)::value;
+        if constexpr (T.a[J][Bc].num != 0) acc = __builtin_fmaf(kCoef<T, J, Bc>, tmp[i][b], acc);
+      });
+      out[i][j] = acc;
+    });
+  });
+}
+
+// out = T^T x T  (x: T.rows x T.rows, out: T.cols x T.cols): the adjoint of x -> T x T^T.
+template <const RMat& T>
+__device__ __forceinline__ void adjoint_bracket_f(const float (&x)[T.rows][T.rows],
+                                                  float (&out)[T.cols][T.cols]) {
+  float tmp[T.cols][T.rows];
+  rfor<0, T.cols>([&](auto i) {
+    rfor<0, T.rows>([&](auto b) {
+      float acc = 0.f;
+      rfor<0, T.rows>([&](auto a) {
+        constexpr int I = decltype(i)::value, A = decltype(a)::value;
+        if constexpr (T.a[A][I].num != 0) acc = __builtin_fmaf(kCoef<T, A, I>, x[a][b], acc);
+      });
+      tmp[i][b] = acc;
+    });
+  });
+  rfor<0, T.cols>([&](auto i) {
+    rfor<0, T.cols>([&](auto j) {
+      float acc = 0.f;
+      rfor<0, T.rows>([&](auto b) {
+        constexpr int J = decltype(j)::value, Bc = decltype(b)::value;
+        if constexpr (T.a[Bc][J].num != 0) acc = __builtin_fmaf(kCoef<T, Bc, J>, tmp[i][b], acc);
+      });
+      out[i][j] = acc;
+    });
+  });
+}
+
+}  // namespace wino
