@@ -214,16 +214,6 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
     });
     const long ybase = (((long)b * g.H + ty_m) * g.W + tx_m) * g.K + k;
     const int wk = g.W * g.K;
-    auto to_float_approx = [](auto v) -> float {
-      if constexpr (std::is_same_v<decltype(v), int64_t>) {
-        // v = hi * 2^32 + lo with a SIGNED low half, so small |v| has hi = 0
-        const int32_t lo = (int32_t)v;
-        const int32_t hi = (int32_t)(v >> 32) + (int32_t)((uint32_t)lo >> 31);
-        return __builtin_fmaf((float)hi, 4294967296.0f, (float)lo);
-      } else {
-        return (float)v;
-      }
-    };
     auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {

@@ -280,6 +280,22 @@ __device__ __forceinline__ auto entry(AccT v) {
   return from_slot<entry_kind<T, IN_MAX>(I, J)>(v);
 }
 
+// Numerator -> fp32 for a dequantised output.  64-bit numerators go through
+// their two halves (two conversions and one fma): not the correctly rounded
+// conversion, but within 2 ulp, which an fp32 output tolerates; casts to integer
+// codes keep the exact single-rounding conversion.
+template <typename V>
+__device__ __forceinline__ float to_float_approx(V v) {
+  if constexpr (std::is_same_v<V, int64_t>) {
+    // v = hi * 2^32 + lo with a SIGNED low half, so small |v| has hi = 0
+    const int32_t lo = (int32_t)v;
+    const int32_t hi = (int32_t)(v >> 32) + (int32_t)((uint32_t)lo >> 31);
+    return __builtin_fmaf((float)hi, 4294967296.0f, (float)lo);
+  } else {
+    return (float)v;
+  }
+}
+
 // One symmetric cast: q = clamp(rint(v * mult), +-qmax), where rint rounds the
 // EXACT product of the two fp32 numbers to the nearest integer, ties to even.
 // One fused multiply-add does it: v * mult + 1.5 * 2^23 is rounded once, to a
@@ -580,20 +596,6 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     });
   }
 
-  // Numerator -> fp32 for the dequantised output.  64-bit numerators go
-  // through their two halves (two conversions and one fma): not the correctly
-  // rounded conversion, but within 2 ulp, which the fp32 output tolerates; the
-  // int8 output below keeps the exact single-rounding conversion.
-  auto to_float_approx = [](auto v) -> float {
-    if constexpr (std::is_same_v<decltype(v), int64_t>) {
-      // v = hi * 2^32 + lo with a SIGNED low half, so small |v| has hi = 0
-      const int32_t lo = (int32_t)v;
-      const int32_t hi = (int32_t)(v >> 32) + (int32_t)((uint32_t)lo >> 31);
-      return __builtin_fmaf((float)hi, 4294967296.0f, (float)lo);
-    } else {
-      return (float)v;
-    }
-  };
   // block-uniform part (WHOLE) kept apart from the lane's channel
   const long ytile = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K;
   const int wk = g.W * g.K;
