@@ -166,7 +166,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
     // ---- B: contraction of this chunk for the wave's points ----
     const bool cok = c0 + seg * 16 < g.C;
     const int ccol = cok ? c0 + seg * 16 : 0;
-#pragma unroll(SINGLE ? 3 : NPW)
+#pragma clang loop unroll_count(SINGLE ? 3 : NPW)
     for (int pi = 0; pi < NPW; ++pi) {
       const int p = pi * NWV + wave;
       if (n2 % NWV != 0 && p >= n2) break;           // wave-uniform: this wave has one point less
