@@ -202,27 +202,38 @@ __global__ __launch_bounds__(256) void k_bwd_dx_dw(const float* __restrict__ dU,
 
 // ---------------------------------------------------------------------------
 // Contraction gradients: n*n GEMMs  C[p][row][col] = scale[p] * sum_red
-// A(p, row, red) * B[p][red][col]  with fp32 A (dM), int8 B (codes, converted
-// to fp32 when staged) and fp32 accumulation on v_mfma_f32_32x32x2_f32.
+// A(p, row, red) * B[p][red][col]  with fp32 A (dM) and int8 B (codes).
 //   ARED = true : A is [p][row][red]  (dU: row = t, red = k, col = c, B = V)
 //   ARED = false: A is [p][red][row]  (dV: row = k, red = t, col = c, B = U)
+// The products run on the bf16 matrix pipe without giving up fp32 accuracy: an
+// fp32 value is cut into three bf16 pieces of 8 significant bits each (truncate,
+// subtract, truncate, subtract: both subtractions are exact), the int8 codes
+// are bf16 values as they stand, so every piece * code product is exact in the
+// fp32 accumulator of v_mfma_f32_32x32x16_bf16 and what is lost is what lies
+// below the 24th bit of A.  Three such MFMAs do the work of eight fp32 ones in
+// 3/16 of their cycles.
 // Work group = 4 waves = 64 x 64 outputs, one 32 x 32 block per wave; the
-// reduction runs in chunks of 32 staged through LDS, the next chunk's global
-// loads in flight during the MFMAs.  LDS rows are padded so that the
-// per-lane fragment reads (lane -> row or column = lane % 32, red = lane / 32)
-// hit distinct banks.  red and cols are multiples of 4 resp. 16 (K and C are
-// multiples of 16), rows and red are otherwise arbitrary: out-of-range
-// elements are staged as zeros, out-of-range outputs are not stored.
+// reduction runs in chunks of 32 staged through LDS with the reduction index
+// contiguous ([row][red] and [col][red], rows of 40 bf16 = 80 bytes: 16-byte
+// aligned fragments, and the 32 rows a fragment read touches fall on distinct
+// banks), the next chunk's global loads in flight during the MFMAs.  Where the
+// reduction index is the slow one in memory (B always, A for dV) a lane loads
+// the same columns of two consecutive reduction rows and stores the pairs as
+// dwords.  red and cols are multiples of 4 resp. 16 (K and C are multiples of
+// 16), rows and red are otherwise arbitrary: out-of-range elements are staged
+// as zeros, out-of-range outputs are not stored.  Non-finite dM gives NaN.
 // ---------------------------------------------------------------------------
 using v4f = __attribute__((ext_vector_type(4))) float;
-using v4ib = __attribute__((ext_vector_type(4))) int;
+using v2u = __attribute__((ext_vector_type(2))) unsigned;
 using v16f = __attribute__((ext_vector_type(16))) float;
+using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
 
 constexpr int kGT = 64;        // outputs per work group edge
 constexpr int kGR = 32;        // reduction chunk
-constexpr int kLdA = 33;       // ARED: As[row][red], odd stride
-constexpr int kLdT = 68;       // As[red][row] / Bs[red][col], 16-byte aligned rows
+constexpr int kLdH = 40;       // bf16 per staged row: the chunk and 8 of padding
+constexpr int kLdT = 68;       // floats per row of the staged output block
 constexpr int kXcds = 8;
+constexpr int kPiece = kGT * kLdH;   // bf16 elements of one staged 64-row array
 
 struct GemmArgs {
   const float* A;
@@ -236,8 +247,21 @@ struct GemmArgs {
   long out_stride;             // n*n * rows * cols
 };
 
-constexpr int kGemmLds = (kGT * kLdA > kGR * kLdT ? kGT * kLdA : kGR * kLdT) + kGR * kLdT;
-static_assert(kGemmLds >= kGT * kLdT, "the output block is staged in the same LDS");
+// Three pieces of A and B, or the output block: in floats.
+constexpr int kGemmLds = (4 * kPiece / 2 > kGT * kLdT ? 4 * kPiece / 2 : kGT * kLdT);
+
+// x = h + m + l up to the bits below the 24th; each piece sits in the upper half of its word
+// (for l the caller drops the lower half).
+__device__ __forceinline__ void split3(float x, unsigned& h, unsigned& m, unsigned& l) {
+  h = __float_as_uint(x) & 0xffff0000u;
+  const float r1 = x - __uint_as_float(h);
+  m = __float_as_uint(r1) & 0xffff0000u;
+  l = __float_as_uint(r1 - __uint_as_float(m));
+}
+// Two bf16 (upper halves of a and b) as one dword, a at the lower address.
+__device__ __forceinline__ unsigned pack2(unsigned a, unsigned b) {
+  return (a >> 16) | (b & 0xffff0000u);
+}
 
 template <bool ARED>
 __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& scale,
@@ -247,8 +271,10 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   float* __restrict__ Cout = ga.C;
   const int rows = ga.rows, red = ga.red, cols = ga.cols;
   const int row_blocks = ga.row_blocks, col_blocks = ga.col_blocks, units = ga.units;
-  float* As = smem;
-  float* Bs = smem + (ARED ? kGT * kLdA : kGR * kLdT);
+  unsigned short* Ah = reinterpret_cast<unsigned short*>(smem);
+  unsigned short* Am = Ah + kPiece;
+  unsigned short* Al = Am + kPiece;
+  unsigned short* Bt = Al + kPiece;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per_split = ga.blocks / ga.splits;
   const int split = (int)(block / (unsigned)per_split);
@@ -267,58 +293,65 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   const int row0 = rb * kGT, col0 = cb * kGT;
   const float* Ap = A + (long)p * rows * red;
   const int8_t* Bp = B + (long)p * red * cols;
+  // Pair mapping: reduction rows 2 * rp and 2 * rp + 1 of the chunk, columns 4 * pq .. + 3.
+  const int rp = tid & 15, pq = tid >> 4;
 
   v4f ra[2];
-  v4ib rbv;
+  int rbw[2];
   auto fetch = [&](int r0) {
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
-      const int idx = tid + it * 256;
       v4f v = {0.f, 0.f, 0.f, 0.f};
       if constexpr (ARED) {
+        const int idx = tid + it * 256;
         const int row = idx >> 3, q = idx & 7;
         if (row0 + row < rows && r0 + 4 * q < r_end)
           v = *reinterpret_cast<const v4f*>(Ap + (long)(row0 + row) * red + r0 + 4 * q);
       } else {
-        const int rr = idx >> 4, q = idx & 15;
-        if (r0 + rr < r_end && row0 + 4 * q < rows)
-          v = *reinterpret_cast<const v4f*>(Ap + (long)(r0 + rr) * rows + row0 + 4 * q);
+        const int rr = r0 + 2 * rp + it;
+        if (rr < r_end && row0 + 4 * pq < rows)
+          v = *reinterpret_cast<const v4f*>(Ap + (long)rr * rows + row0 + 4 * pq);
       }
       ra[it] = v;
-    }
-    rbv = v4ib{0, 0, 0, 0};
-    if (tid < 128) {
-      const int rr = tid >> 2, q = tid & 3;
-      if (r0 + rr < r_end && col0 + 16 * q < cols)
-        rbv = *reinterpret_cast<const v4ib*>(Bp + (long)(r0 + rr) * cols + col0 + 16 * q);
+      const int rr = r0 + 2 * rp + it;
+      rbw[it] = 0;
+      if (rr < r_end && col0 + 4 * pq < cols)
+        rbw[it] = *reinterpret_cast<const int*>(Bp + (long)rr * cols + col0 + 4 * pq);
     }
   };
   auto stage = [&]() {
+    if constexpr (ARED) {
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-      const int idx = tid + it * 256;
-      if constexpr (ARED) {
+      for (int it = 0; it < 2; ++it) {
+        const int idx = tid + it * 256;
         const int row = idx >> 3, q = idx & 7;
-        float* d = As + row * kLdA + 4 * q;
-        d[0] = ra[it].x; d[1] = ra[it].y; d[2] = ra[it].z; d[3] = ra[it].w;
-      } else {
-        const int rr = idx >> 4, q = idx & 15;
-        *reinterpret_cast<v4f*>(As + rr * kLdT + 4 * q) = ra[it];
+        unsigned h[4], m[4], l[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split3(ra[it][e], h[e], m[e], l[e]);
+        const int at = row * kLdH + 4 * q;
+        *reinterpret_cast<v2u*>(Ah + at) = v2u{pack2(h[0], h[1]), pack2(h[2], h[3])};
+        *reinterpret_cast<v2u*>(Am + at) = v2u{pack2(m[0], m[1]), pack2(m[2], m[3])};
+        *reinterpret_cast<v2u*>(Al + at) = v2u{pack2(l[0], l[1]), pack2(l[2], l[3])};
       }
-    }
-    if (tid < 128) {
-      const int rr = tid >> 2, q = tid & 3;
-      float* d = Bs + rr * kLdT + 16 * q;
+    } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        const int word = rbv[e];
-        v4f f;
-        f.x = (float)(int8_t)(word & 0xff);
-        f.y = (float)(int8_t)((word >> 8) & 0xff);
-        f.z = (float)(int8_t)((word >> 16) & 0xff);
-        f.w = (float)(word >> 24);
-        *reinterpret_cast<v4f*>(d + 4 * e) = f;
+        unsigned h0, m0, l0, h1, m1, l1;
+        split3(ra[0][e], h0, m0, l0);
+        split3(ra[1][e], h1, m1, l1);
+        const int at = (4 * pq + e) * kLdH + 2 * rp;
+        *reinterpret_cast<unsigned*>(Ah + at) = pack2(h0, h1);
+        *reinterpret_cast<unsigned*>(Am + at) = pack2(m0, m1);
+        *reinterpret_cast<unsigned*>(Al + at) = pack2(l0, l1);
       }
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      // A code as fp32 has at most 7 significant bits: its upper half is the bf16 value.
+      const float f0 = (float)(int8_t)((rbw[0] >> (8 * e)) & 0xff);
+      const float f1 = (float)(int8_t)((rbw[1] >> (8 * e)) & 0xff);
+      *reinterpret_cast<unsigned*>(Bt + (4 * pq + e) * kLdH + 2 * rp) =
+          pack2(__float_as_uint(f0), __float_as_uint(f1));
     }
   };
 
@@ -327,6 +360,8 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   for (int i = 0; i < 16; ++i) acc[i] = 0.f;
   const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
   const int l32 = lane & 31, lk = lane >> 5;
+  // MFMA operands: lane -> row (A) or column (B) lane % 32, reduction indices 8 * (lane / 32) .. + 7.
+  const int fa = (wr + l32) * kLdH + 8 * lk, fb = (wc + l32) * kLdH + 8 * lk;
 
   fetch(r_begin);
   for (int r0 = r_begin; r0 < r_end; r0 += kGR) {
@@ -335,14 +370,14 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
     __syncthreads();
     if (r0 + kGR < r_end) fetch(r0 + kGR);
 #pragma unroll
-    for (int kk = 0; kk < kGR; kk += 2) {
-      float a;
-      if constexpr (ARED)
-        a = As[(wr + l32) * kLdA + kk + lk];
-      else
-        a = As[(kk + lk) * kLdT + wr + l32];
-      const float b = Bs[(kk + lk) * kLdT + wc + l32];
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc, 0, 0, 0);
+    for (int kk = 0; kk < kGR; kk += 16) {
+      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Bt + fb + kk);
+      const bf16x8 al = *reinterpret_cast<const bf16x8*>(Al + fa + kk);
+      const bf16x8 am = *reinterpret_cast<const bf16x8*>(Am + fa + kk);
+      const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Ah + fa + kk);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, b, acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc, 0, 0, 0);
     }
   }
 
