@@ -356,7 +356,7 @@ int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, cons
     e = launch_backward_dx_dw(g, dU, (float*)dx, dV, (float*)dw, st);
     if (e != hipSuccess) return fail_hip(e, "backward dx / dw launch");
   } else if (w_items) {
-    e = launch_backward_transform(3, g, dV, (float*)dw, st);
+    e = launch_backward_dw(g, dV, (float*)dw, st);
     if (e != hipSuccess) return fail_hip(e, "backward dw launch");
   } else if (x_items) {
     e = launch_backward_transform(1, g, dU, (float*)dx, st);

@@ -159,18 +159,14 @@ __global__ __launch_bounds__(256) void k_bwd_dx(const float* __restrict__ dU,
 
 // dV -> dw[k][c][3][3].
 template <int M>
-__device__ __forceinline__ void bwd_dw_body(const float* __restrict__ dV, float* __restrict__ dw,
-                                            const Geometry& g, unsigned block) {
+__device__ __forceinline__ void bwd_dw_body(float* __restrict__ dV, float* __restrict__ dw,
+                                            const Geometry& g, unsigned block, int parts) {
   constexpr int n = M + 2;
   const long total = (long)g.K * g.C;
   const long gid = (long)block * 256 + threadIdx.x;
   if (gid >= total) return;
   float v[n][n];
-  rfor<0, n>([&](auto i) {
-    rfor<0, n>([&](auto j) {
-      v[i][j] = dV[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid];
-    });
-  });
+  load_summed_dv<n>(dV, total, gid, parts, true, v);
   float out[3][3];
   adjoint_bracket_f<TabF<M>::G>(v, out);
   rfor<0, 3>([&](auto a) {
@@ -181,23 +177,24 @@ __device__ __forceinline__ void bwd_dw_body(const float* __restrict__ dV, float*
 }
 
 template <int M>
-__global__ __launch_bounds__(256) void k_bwd_dw(const float* __restrict__ dV,
-                                                float* __restrict__ dw, Geometry g) {
-  bwd_dw_body<M>(dV, dw, g, blockIdx.x);
+__global__ __launch_bounds__(256) void k_bwd_dw(float* __restrict__ dV, float* __restrict__ dw,
+                                                Geometry g, int parts) {
+  bwd_dw_body<M>(dV, dw, g, blockIdx.x, parts);
 }
 
-// The last two steps are independent of each other: one launch, the first nb_dx
-// work groups gather dx, the rest transform dV into dw.
+// The last two steps are independent of each other: one launch, the first nb_dw
+// work groups transform dV into dw (few, and the longer chain of loads where dV
+// comes in parts: they start first), the rest gather dx.
 template <int M>
 __global__ __launch_bounds__(256) void k_bwd_dx_dw(const float* __restrict__ dU,
                                                    float* __restrict__ dx,
-                                                   const float* __restrict__ dV,
+                                                   float* __restrict__ dV,
                                                    float* __restrict__ dw, Geometry g,
-                                                   unsigned nb_dx) {
-  if (blockIdx.x < nb_dx)
-    bwd_dx_body<M>(dU, dx, g, blockIdx.x);
+                                                   unsigned nb_dw, int parts) {
+  if (blockIdx.x < nb_dw)
+    bwd_dw_body<M>(dV, dw, g, blockIdx.x, parts);
   else
-    bwd_dw_body<M>(dV, dw, g, blockIdx.x - nb_dx);
+    bwd_dx_body<M>(dU, dx, g, blockIdx.x - nb_dw);
 }
 
 // ---------------------------------------------------------------------------
@@ -211,12 +208,14 @@ __global__ __launch_bounds__(256) void k_bwd_dx_dw(const float* __restrict__ dU,
 // are bf16 values as they stand, so every piece * code product is exact in the
 // fp32 accumulator of v_mfma_f32_32x32x16_bf16 and what is lost is what lies
 // below the 24th bit of A.  Three such MFMAs do the work of eight fp32 ones in
-// 3/16 of their cycles.
-// Work group = 4 waves = 64 x 64 outputs, one 32 x 32 block per wave; the
-// reduction runs in chunks of 32 staged through LDS with the reduction index
-// contiguous ([row][red] and [col][red], rows of 40 bf16 = 80 bytes: 16-byte
-// aligned fragments, and the 32 rows a fragment read touches fall on distinct
-// banks), the next chunk's global loads in flight during the MFMAs.  Where the
+// 3/16 of their cycles, which leaves LDS traffic and the splitting arithmetic
+// as the costs to keep down: hence the large tiles.
+// Work group = 4 waves (2 x 2) = (64 MB) x (64 NB) outputs, (32 MB) x (32 NB)
+// per wave as MB x NB blocks of 32 x 32, MB and NB 1 or 2.  The reduction runs
+// in chunks of 32 staged through LDS with the reduction index contiguous
+// ([row][red] and [col][red], rows of 40 bf16 = 80 bytes: 16-byte aligned
+// fragments, and the 32 rows a fragment read touches fall on distinct banks),
+// the next chunk's global loads in flight during the MFMAs.  Where the
 // reduction index is the slow one in memory (B always, A for dV) a lane loads
 // the same columns of two consecutive reduction rows and stores the pairs as
 // dwords.  red and cols are multiples of 4 resp. 16 (K and C are multiples of
@@ -228,12 +227,9 @@ using v2u = __attribute__((ext_vector_type(2))) unsigned;
 using v16f = __attribute__((ext_vector_type(16))) float;
 using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
 
-constexpr int kGT = 64;        // outputs per work group edge
 constexpr int kGR = 32;        // reduction chunk
 constexpr int kLdH = 40;       // bf16 per staged row: the chunk and 8 of padding
-constexpr int kLdT = 68;       // floats per row of the staged output block
 constexpr int kXcds = 8;
-constexpr int kPiece = kGT * kLdH;   // bf16 elements of one staged 64-row array
 
 struct GemmArgs {
   const float* A;
@@ -247,8 +243,12 @@ struct GemmArgs {
   long out_stride;             // n*n * rows * cols
 };
 
-// Three pieces of A and B, or the output block: in floats.
-constexpr int kGemmLds = (4 * kPiece / 2 > kGT * kLdT ? 4 * kPiece / 2 : kGT * kLdT);
+// LDS of one work group in floats: three pieces of A and B as bf16, or (afterwards) one
+// 32 x (32 NB) output block per wave in rows of 32 NB + 4 floats.
+constexpr int gemm_lds(int mb, int nb) {
+  const int staged = (3 * mb + nb) * 64 * kLdH / 2, out = 4 * 32 * (32 * nb + 4);
+  return staged > out ? staged : out;
+}
 
 // x = h + m + l up to the bits below the 24th; each piece sits in the upper half of its word
 // (for l the caller drops the lower half).
@@ -260,21 +260,22 @@ __device__ __forceinline__ void split3(float x, unsigned& h, unsigned& m, unsign
 }
 // Two bf16 (upper halves of a and b) as one dword, a at the lower address.
 __device__ __forceinline__ unsigned pack2(unsigned a, unsigned b) {
-  return (a >> 16) | (b & 0xffff0000u);
+  return __builtin_amdgcn_perm(b, a, 0x07060302u);
 }
 
-template <bool ARED>
+template <bool ARED, int MB, int NB>
 __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& scale,
                                           unsigned block, float* __restrict__ smem) {
+  constexpr int TR = 64 * MB, TC = 64 * NB;
   const float* __restrict__ A = ga.A;
   const int8_t* __restrict__ B = ga.B;
   float* __restrict__ Cout = ga.C;
   const int rows = ga.rows, red = ga.red, cols = ga.cols;
   const int row_blocks = ga.row_blocks, col_blocks = ga.col_blocks, units = ga.units;
   unsigned short* Ah = reinterpret_cast<unsigned short*>(smem);
-  unsigned short* Am = Ah + kPiece;
-  unsigned short* Al = Am + kPiece;
-  unsigned short* Bt = Al + kPiece;
+  unsigned short* Am = Ah + TR * kLdH;
+  unsigned short* Al = Am + TR * kLdH;
+  unsigned short* Bt = Al + TR * kLdH;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int per_split = ga.blocks / ga.splits;
   const int split = (int)(block / (unsigned)per_split);
@@ -290,17 +291,17 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   if (unit >= units) return;                     // padding blocks (uniform exit, no barrier yet)
   const int cb = slot % col_blocks;
   const int p = unit / row_blocks, rb = unit - p * row_blocks;
-  const int row0 = rb * kGT, col0 = cb * kGT;
+  const int row0 = rb * TR, col0 = cb * TC;
   const float* Ap = A + (long)p * rows * red;
   const int8_t* Bp = B + (long)p * red * cols;
-  // Pair mapping: reduction rows 2 * rp and 2 * rp + 1 of the chunk, columns 4 * pq .. + 3.
+  // Pair mapping: reduction rows 2 * rp and 2 * rp + 1 of the chunk, columns 4 * (pq + 16 j) .. + 3.
   const int rp = tid & 15, pq = tid >> 4;
 
-  v4f ra[2];
-  int rbw[2];
+  v4f ra[2 * MB];
+  int rbw[2 * NB];
   auto fetch = [&](int r0) {
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
+    for (int it = 0; it < 2 * MB; ++it) {
       v4f v = {0.f, 0.f, 0.f, 0.f};
       if constexpr (ARED) {
         const int idx = tid + it * 256;
@@ -308,21 +309,24 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
         if (row0 + row < rows && r0 + 4 * q < r_end)
           v = *reinterpret_cast<const v4f*>(Ap + (long)(row0 + row) * red + r0 + 4 * q);
       } else {
-        const int rr = r0 + 2 * rp + it;
-        if (rr < r_end && row0 + 4 * pq < rows)
-          v = *reinterpret_cast<const v4f*>(Ap + (long)rr * rows + row0 + 4 * pq);
+        const int rr = r0 + 2 * rp + (it & 1), quad = pq + 16 * (it >> 1);
+        if (rr < r_end && row0 + 4 * quad < rows)
+          v = *reinterpret_cast<const v4f*>(Ap + (long)rr * rows + row0 + 4 * quad);
       }
       ra[it] = v;
-      const int rr = r0 + 2 * rp + it;
+    }
+#pragma unroll
+    for (int it = 0; it < 2 * NB; ++it) {
+      const int rr = r0 + 2 * rp + (it & 1), quad = pq + 16 * (it >> 1);
       rbw[it] = 0;
-      if (rr < r_end && col0 + 4 * pq < cols)
-        rbw[it] = *reinterpret_cast<const int*>(Bp + (long)rr * cols + col0 + 4 * pq);
+      if (rr < r_end && col0 + 4 * quad < cols)
+        rbw[it] = *reinterpret_cast<const int*>(Bp + (long)rr * cols + col0 + 4 * quad);
     }
   };
   auto stage = [&]() {
     if constexpr (ARED) {
 #pragma unroll
-      for (int it = 0; it < 2; ++it) {
+      for (int it = 0; it < 2 * MB; ++it) {
         const int idx = tid + it * 256;
         const int row = idx >> 3, q = idx & 7;
         unsigned h[4], m[4], l[4];
@@ -335,30 +339,38 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
       }
     } else {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        unsigned h0, m0, l0, h1, m1, l1;
-        split3(ra[0][e], h0, m0, l0);
-        split3(ra[1][e], h1, m1, l1);
-        const int at = (4 * pq + e) * kLdH + 2 * rp;
-        *reinterpret_cast<unsigned*>(Ah + at) = pack2(h0, h1);
-        *reinterpret_cast<unsigned*>(Am + at) = pack2(m0, m1);
-        *reinterpret_cast<unsigned*>(Al + at) = pack2(l0, l1);
-      }
+      for (int j = 0; j < MB; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          unsigned h0, m0, l0, h1, m1, l1;
+          split3(ra[2 * j][e], h0, m0, l0);
+          split3(ra[2 * j + 1][e], h1, m1, l1);
+          const int at = (4 * (pq + 16 * j) + e) * kLdH + 2 * rp;
+          *reinterpret_cast<unsigned*>(Ah + at) = pack2(h0, h1);
+          *reinterpret_cast<unsigned*>(Am + at) = pack2(m0, m1);
+          *reinterpret_cast<unsigned*>(Al + at) = pack2(l0, l1);
+        }
     }
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      // A code as fp32 has at most 7 significant bits: its upper half is the bf16 value.
-      const float f0 = (float)(int8_t)((rbw[0] >> (8 * e)) & 0xff);
-      const float f1 = (float)(int8_t)((rbw[1] >> (8 * e)) & 0xff);
-      *reinterpret_cast<unsigned*>(Bt + (4 * pq + e) * kLdH + 2 * rp) =
-          pack2(__float_as_uint(f0), __float_as_uint(f1));
-    }
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        // A code as fp32 has at most 7 significant bits: its upper half is the bf16 value.
+        const float f0 = (float)(int8_t)((rbw[2 * j] >> (8 * e)) & 0xff);
+        const float f1 = (float)(int8_t)((rbw[2 * j + 1] >> (8 * e)) & 0xff);
+        *reinterpret_cast<unsigned*>(Bt + (4 * (pq + 16 * j) + e) * kLdH + 2 * rp) =
+            pack2(__float_as_uint(f0), __float_as_uint(f1));
+      }
   };
 
-  v16f acc;
+  v16f acc[MB][NB];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-  const int wr = (wave >> 1) * 32, wc = (wave & 1) * 32;
+  for (int a = 0; a < MB; ++a)
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+  const int wr = (wave >> 1) * 32 * MB, wc = (wave & 1) * 32 * NB;
   const int l32 = lane & 31, lk = lane >> 5;
   // MFMA operands: lane -> row (A) or column (B) lane % 32, reduction indices 8 * (lane / 32) .. + 7.
   const int fa = (wr + l32) * kLdH + 8 * lk, fb = (wc + l32) * kLdH + 8 * lk;
@@ -371,85 +383,105 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
     if (r0 + kGR < r_end) fetch(r0 + kGR);
 #pragma unroll
     for (int kk = 0; kk < kGR; kk += 16) {
-      const bf16x8 b = *reinterpret_cast<const bf16x8*>(Bt + fb + kk);
-      const bf16x8 al = *reinterpret_cast<const bf16x8*>(Al + fa + kk);
-      const bf16x8 am = *reinterpret_cast<const bf16x8*>(Am + fa + kk);
-      const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Ah + fa + kk);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, b, acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b, acc, 0, 0, 0);
+      bf16x8 bfrag[NB];
+#pragma unroll
+      for (int b = 0; b < NB; ++b)
+        bfrag[b] = *reinterpret_cast<const bf16x8*>(Bt + fb + b * 32 * kLdH + kk);
+#pragma unroll
+      for (int a = 0; a < MB; ++a) {
+        const int at = fa + a * 32 * kLdH + kk;
+        const bf16x8 al = *reinterpret_cast<const bf16x8*>(Al + at);
+        const bf16x8 am = *reinterpret_cast<const bf16x8*>(Am + at);
+        const bf16x8 ah = *reinterpret_cast<const bf16x8*>(Ah + at);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bfrag[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am, bfrag[b], acc[a][b], 0, 0, 0);
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bfrag[b], acc[a][b], 0, 0, 0);
+      }
     }
   }
 
-  // acc[i] holds output (row = (i / 4) * 8 + (lane / 32) * 4 + i % 4, col = lane % 32).
-  // The 64 x 64 block goes through LDS (rows of kLdT floats) so that it leaves in
-  // 16-byte stores, a wave writing four 256-byte row segments per instruction.
+  // acc[a][b][i] holds output (row = 32 a + (i / 4) * 8 + (lane / 32) * 4 + i % 4,
+  // col = 32 b + lane % 32) of the wave's block.  32 rows at a time go through the
+  // wave's own part of LDS so that they leave in 16-byte stores, a wave writing
+  // full row segments of 128 NB bytes.
+  constexpr int kLdC = 32 * NB + 4;
   const float s = scale.v[p];
-  __syncthreads();                    // every wave is done with the last chunk's fragments
-  float* Cs = smem;
-#pragma unroll
-  for (int i = 0; i < 16; ++i)
-    Cs[(wr + (i >> 2) * 8 + lk * 4 + (i & 3)) * kLdT + wc + l32] = acc[i] * s;
-  __syncthreads();
+  float* Cs = smem + wave * 32 * kLdC;
   float* Cp = Cout + (long)p * rows * cols;
 #pragma unroll
-  for (int it = 0; it < 4; ++it) {
-    const int idx = tid + it * 256;
-    const int r = idx >> 4, q = idx & 15;
-    const int row = row0 + r, col = col0 + 4 * q;
-    if (row < rows && col < cols)     // cols is a multiple of 16: a quad is inside or outside
-      *reinterpret_cast<v4f*>(Cp + (long)row * cols + col) =
-          *reinterpret_cast<const v4f*>(Cs + r * kLdT + 4 * q);
+  for (int a = 0; a < MB; ++a) {
+    __syncthreads();                  // the fragments (a = 0) resp. the previous rows have been read
+#pragma unroll
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i)
+        Cs[((i >> 2) * 8 + lk * 4 + (i & 3)) * kLdC + 32 * b + l32] = acc[a][b][i] * s;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 4 * NB; ++it) {
+      const int idx = lane + it * 64;
+      const int r = idx / (8 * NB), q = idx % (8 * NB);
+      const int row = row0 + wr + 32 * a + r, col = col0 + wc + 4 * q;
+      if (row < rows && col < cols)   // cols is a multiple of 16: a quad is inside or outside
+        *reinterpret_cast<v4f*>(Cp + (long)row * cols + col) =
+            *reinterpret_cast<const v4f*>(Cs + r * kLdC + 4 * q);
+    }
   }
-}
-
-// One contraction per launch.
-template <bool ARED>
-__global__ __launch_bounds__(256) void k_bwd_gemm(GemmArgs ga, MultTable scale) {
-  __shared__ __attribute__((aligned(16))) float smem[kGemmLds];
-  gemm_body<ARED>(ga, scale, blockIdx.x, smem);
 }
 
 // Both contractions in one launch (they only share their input dM): the blocks of
 // the dV contraction, whose reduction over the tiles is the longer one, come first,
-// the blocks of dU fill the compute units as those drain.
+// the blocks of dU fill the compute units as those drain.  Either may have no
+// blocks.  MBV: row blocks per wave of dV's tiles (rows = K); dU's tiles are
+// always 128 rows (of tiles) high; NB: column blocks per wave of both (cols = C).
+template <int MBV, int NB>
 __global__ __launch_bounds__(256) void k_bwd_gemm_both(GemmArgs for_dv, MultTable s_u,
                                                         GemmArgs for_du, MultTable s_v) {
-  __shared__ __attribute__((aligned(16))) float smem[kGemmLds];
+  __shared__ __attribute__((aligned(16))) float smem[gemm_lds(2, NB)];
   if (blockIdx.x < (unsigned)for_dv.blocks)
-    gemm_body<false>(for_dv, s_u, blockIdx.x, smem);
+    gemm_body<false, MBV, NB>(for_dv, s_u, blockIdx.x, smem);
   else
-    gemm_body<true>(for_du, s_v, blockIdx.x - (unsigned)for_dv.blocks, smem);
+    gemm_body<true, 2, NB>(for_du, s_v, blockIdx.x - (unsigned)for_dv.blocks, smem);
 }
 
 inline unsigned blocks256(long items) { return (unsigned)((items + 255) / 256); }
 
 template <int M>
-hipError_t bwd_transform(int which, const Geometry& g, const float* in, float* out,
-                         hipStream_t st) {
-  switch (which) {
-    case 0:
-      wino_launch((k_bwd_dm<M>), dim3(blocks256((long)g.T * g.K)), dim3(256), st, in, out, g);
-      break;
-    case 1:
-      wino_launch((k_bwd_dx<M>), dim3(blocks256((long)g.T * g.C)), dim3(256), st, in, out, g);
-      break;
-    default:
-      wino_launch((k_bwd_dw<M>), dim3(blocks256((long)g.K * g.C)), dim3(256), st, in, out, g);
-      break;
-  }
+hipError_t bwd_transform(int which, const Geometry& g, const float* in, float* out, hipStream_t st) {
+  if (which == 0)
+    wino_launch((k_bwd_dm<M>), dim3(blocks256((long)g.T * g.K)), dim3(256), st, in, out, g);
+  else
+    wino_launch((k_bwd_dx<M>), dim3(blocks256((long)g.T * g.C)), dim3(256), st, in, out, g);
   return hipGetLastError();
 }
 
 template <int M>
-hipError_t bwd_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV, float* dw,
+hipError_t bwd_dw(const Geometry& g, float* dV, float* dw, hipStream_t st) {
+  wino_launch((k_bwd_dw<M>), dim3(blocks256((long)g.K * g.C)), dim3(256), st, dV, dw, g,
+              backward_dv_reader_parts(g));
+  return hipGetLastError();
+}
+
+template <int M>
+hipError_t bwd_dx_dw(const Geometry& g, const float* dU, float* dx, float* dV, float* dw,
                      hipStream_t st) {
   const unsigned nb_dx = blocks256((long)g.T * g.C), nb_dw = blocks256((long)g.K * g.C);
-  wino_launch((k_bwd_dx_dw<M>), dim3(nb_dx + nb_dw), dim3(256), st, dU, dx, dV, dw, g, nb_dx);
+  wino_launch((k_bwd_dx_dw<M>), dim3(nb_dx + nb_dw), dim3(256), st, dU, dx, dV, dw, g, nb_dw,
+              backward_dv_reader_parts(g));
   return hipGetLastError();
 }
 
 }  // namespace
+
+// Up to this many partial sums of dV are added by the kernels that read dV (load_summed_dv);
+// more are added by k_sum_splits first.
+constexpr int kReaderParts = 4;
 
 // dV[i] = sum over s < splits of dV[s * count + i], ascending s, i < count.
 __global__ __launch_bounds__(256) void k_sum_splits(float* __restrict__ dV, long count, int splits) {
@@ -464,12 +496,12 @@ __global__ __launch_bounds__(256) void k_sum_splits(float* __restrict__ dV, long
 hipError_t launch_backward_sum_splits(const Geometry& g, float* dV, hipStream_t st) {
   const int splits = backward_dv_splits(g);
   const long count = (long)(g.m + 2) * (g.m + 2) * g.K * g.C;
-  if (splits <= 1 || count == 0) return hipSuccess;
+  if (splits <= kReaderParts || count == 0) return hipSuccess;   // the readers of dV add those up
   wino_launch(k_sum_splits, dim3(blocks256(count)), dim3(256), st, dV, count, splits);
   return hipGetLastError();
 }
 
-hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV,
+hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, float* dV,
                                  float* dw, hipStream_t st) {
   switch (g.m) {
     case 2: return bwd_dx_dw<2>(g, dU, dx, dV, dw, st);
@@ -481,12 +513,23 @@ hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, 
 
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st) {
-  const long items = which == 0 ? (long)g.T * g.K : which == 1 ? (long)g.T * g.C : (long)g.K * g.C;
+  if (which != 0 && which != 1) return hipErrorInvalidValue;
+  const long items = which == 0 ? (long)g.T * g.K : (long)g.T * g.C;
   if (items == 0) return hipSuccess;
   switch (g.m) {
     case 2: return bwd_transform<2>(which, g, in, out, st);
     case 4: return bwd_transform<4>(which, g, in, out, st);
     case 6: return bwd_transform<6>(which, g, in, out, st);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_backward_dw(const Geometry& g, float* dV, float* dw, hipStream_t st) {
+  if ((long)g.K * g.C == 0) return hipSuccess;
+  switch (g.m) {
+    case 2: return bwd_dw<2>(g, dV, dw, st);
+    case 4: return bwd_dw<4>(g, dV, dw, st);
+    case 6: return bwd_dw<6>(g, dV, dw, st);
     default: return hipErrorInvalidValue;
   }
 }
@@ -551,7 +594,7 @@ hipError_t launch_flex_backward_output(const Geometry& g, bool legendre, const v
 
 hipError_t launch_flex_backward_input_weight(const Geometry& g, bool legendre, const int8_t* x,
                                              const float* dU, float* dXt, float* part_in,
-                                             const int8_t* w, const float* dV, float* dw,
+                                             const int8_t* w, float* dV, float* dw,
                                              float* part_w, const FlexMats& fm,
                                              const StageMults& mu, float s_in, float s_w,
                                              hipStream_t st) {
@@ -564,18 +607,30 @@ hipError_t launch_flex_backward_tile_sum(const Geometry& g, const float* dXt, fl
 }
 #undef WINO_BY_M
 
-// The dV contraction has few outputs (n*n x K x C) and a long reduction (all tiles): where its
-// 64 x 64 tiles would leave most compute units idle, the reduction is cut into 2^j ranges that
-// run as separate work groups and leave partial sums, added up (in ascending order) by
-// k_sum_splits before the filter bracket.  Ranges hold at least four chunks; at most 32, and at most 64 MB of
-// partial sums.
+// Tile shapes of the two contractions: a wave takes two 32-wide blocks along a dimension that is
+// longer than one 64-wide tile, else one.
+static int dv_row_blocks(const Geometry& g) { return g.K > 64 ? 2 : 1; }
+static int col_blocks_per_wave(const Geometry& g) { return g.C > 64 ? 2 : 1; }
+
+// Parts of dV that the kernel reading dV finds and adds up itself.
+int backward_dv_reader_parts(const Geometry& g) {
+  const int s = backward_dv_splits(g);
+  return s <= kReaderParts ? s : 1;
+}
+
+// The dV contraction has few outputs (n*n x K x C) and a long reduction (all tiles): while it
+// has fewer tiles than the chip has compute units, the reduction is cut into 2^j ranges that
+// run as separate work groups and leave partial sums, added up in ascending order: up to four
+// by the filter bracket that reads dV, more by k_sum_splits before it.  Ranges hold at least
+// four chunks; at most 32, and at most 64 MB of partial sums.
 int backward_dv_splits(const Geometry& g) {
   const long n2 = (long)(g.m + 2) * (g.m + 2);
-  const long tiles = n2 * ((g.K + kGT - 1) / kGT) * ((g.C + kGT - 1) / kGT);
+  const int tr = 64 * dv_row_blocks(g), tc = 64 * col_blocks_per_wave(g);
+  const long tiles = n2 * ((g.K + tr - 1) / tr) * ((g.C + tc - 1) / tc);
   const long chunks = ((long)g.T + kGR - 1) / kGR;
   const long bytes = n2 * g.K * g.C * 4;
   int s = 1;
-  while (tiles * s < 512 && (long)s * 2 * 4 <= chunks && s < 32 && (long)s * 2 * bytes <= (64L << 20))
+  while (tiles * s < 256 && (long)s * 2 * 4 <= chunks && s < 32 && (long)s * 2 * bytes <= (64L << 20))
     s *= 2;
   return s;
 }
@@ -583,14 +638,15 @@ int backward_dv_splits(const Geometry& g) {
 static bool gemm_args(bool for_weights, const Geometry& g, const float* dM, const int8_t* codes,
                       float* out, GemmArgs* ga) {
   const int n2 = (g.m + 2) * (g.m + 2);
+  const int tr = for_weights ? 64 * dv_row_blocks(g) : 128, tc = 64 * col_blocks_per_wave(g);
   ga->A = dM;
   ga->B = codes;
   ga->C = out;
   ga->rows = for_weights ? g.K : g.T;
   ga->red = for_weights ? g.T : g.K;
   ga->cols = g.C;
-  ga->row_blocks = (ga->rows + kGT - 1) / kGT;
-  ga->col_blocks = (ga->cols + kGT - 1) / kGT;
+  ga->row_blocks = (ga->rows + tr - 1) / tr;
+  ga->col_blocks = (ga->cols + tc - 1) / tc;
   const long units = (long)n2 * ga->row_blocks;
   ga->splits = for_weights ? backward_dv_splits(g) : 1;
   const long chunks = ((long)ga->red + kGR - 1) / kGR;
@@ -598,8 +654,33 @@ static bool gemm_args(bool for_weights, const Geometry& g, const float* dM, cons
   ga->out_stride = (long)n2 * ga->rows * ga->cols;
   const long blocks = (units + kXcds - 1) / kXcds * kXcds * ga->col_blocks * ga->splits;
   ga->units = (int)units;
-  ga->blocks = (int)blocks;
+  ga->blocks = (int)blocks;                      // no outputs: no blocks
   return blocks <= (1L << 30);
+}
+
+static hipError_t launch_gemm_pair(const Geometry& g, const GemmArgs& for_dv, const MultTable& s_u,
+                                   const GemmArgs& for_du, const MultTable& s_v, hipStream_t st) {
+  const unsigned blocks = (unsigned)for_dv.blocks + (unsigned)for_du.blocks;
+  if (blocks == 0) return hipSuccess;
+  const dim3 grid(blocks), wg(256);
+  if (col_blocks_per_wave(g) == 2) {
+    if (dv_row_blocks(g) == 2)
+      wino_launch((k_bwd_gemm_both<2, 2>), grid, wg, st, for_dv, s_u, for_du, s_v);
+    else
+      wino_launch((k_bwd_gemm_both<1, 2>), grid, wg, st, for_dv, s_u, for_du, s_v);
+  } else {
+    if (dv_row_blocks(g) == 2)
+      wino_launch((k_bwd_gemm_both<2, 1>), grid, wg, st, for_dv, s_u, for_du, s_v);
+    else
+      wino_launch((k_bwd_gemm_both<1, 1>), grid, wg, st, for_dv, s_u, for_du, s_v);
+  }
+  return hipGetLastError();
+}
+
+static GemmArgs no_gemm() {
+  GemmArgs ga{};
+  ga.splits = 1;
+  return ga;
 }
 
 hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float* dM,
@@ -607,12 +688,8 @@ hipError_t launch_backward_gemm(bool for_weights, const Geometry& g, const float
                                 hipStream_t st) {
   GemmArgs ga;
   if (!gemm_args(for_weights, g, dM, codes, out, &ga)) return hipErrorInvalidValue;
-  if (ga.rows == 0 || ga.cols == 0) return hipSuccess;
-  if (for_weights)
-    wino_launch((k_bwd_gemm<false>), dim3((unsigned)ga.blocks), dim3(256), st, ga, scale);
-  else
-    wino_launch((k_bwd_gemm<true>), dim3((unsigned)ga.blocks), dim3(256), st, ga, scale);
-  return hipGetLastError();
+  return for_weights ? launch_gemm_pair(g, ga, scale, no_gemm(), scale, st)
+                     : launch_gemm_pair(g, no_gemm(), scale, ga, scale, st);
 }
 
 hipError_t launch_backward_gemms(const Geometry& g, const float* dM, const int8_t* U,
@@ -621,14 +698,11 @@ hipError_t launch_backward_gemms(const Geometry& g, const float* dM, const int8_
   GemmArgs for_dv, for_du;
   if (!gemm_args(true, g, dM, U, dV, &for_dv) || !gemm_args(false, g, dM, V, dU, &for_du))
     return hipErrorInvalidValue;
-  const bool has_dv = for_dv.rows > 0 && for_dv.cols > 0, has_du = for_du.rows > 0 && for_du.cols > 0;
-  if (!has_dv || !has_du || (long)for_dv.blocks + for_du.blocks > (1L << 30)) {
+  if ((long)for_dv.blocks + for_du.blocks > (1L << 30)) {
     hipError_t e = launch_backward_gemm(false, g, dM, V, dU, s_v, st);
     return e == hipSuccess ? launch_backward_gemm(true, g, dM, U, dV, s_u, st) : e;
   }
-  wino_launch(k_bwd_gemm_both, dim3((unsigned)(for_dv.blocks + for_du.blocks)), dim3(256), st, for_dv,
-              s_u, for_du, s_v);
-  return hipGetLastError();
+  return launch_gemm_pair(g, for_dv, s_u, for_du, s_v, st);
 }
 
 }  // namespace wino

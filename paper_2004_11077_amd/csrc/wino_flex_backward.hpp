@@ -237,10 +237,10 @@ __device__ __forceinline__ void fbwd_input_body(const int8_t* __restrict__ x,
 // dV, w -> dw [k][c][3][3] and the partial sums of dGP (n x 3).
 template <int M, bool LEG>
 __device__ __forceinline__ void fbwd_weight_body(const int8_t* __restrict__ w,
-                                                 const float* __restrict__ dV,
+                                                 float* __restrict__ dV,
                                                  float* __restrict__ dw, float* __restrict__ part,
                                                  const Geometry& g, const FlexMats& fm, float s_w,
-                                                 unsigned block) {
+                                                 unsigned block, int parts) {
   constexpr int n = M + 2;
   const long total = (long)g.K * g.C;
   const long gid = (long)block * 256 + threadIdx.x;
@@ -254,11 +254,7 @@ __device__ __forceinline__ void fbwd_weight_body(const int8_t* __restrict__ w,
   float dR[n][n];
   {
     float v[n][n];
-    static_for<0, n>([&](auto i) {
-      static_for<0, n>([&](auto j) {
-        v[i][j] = active ? dV[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] : 0.f;
-      });
-    });
+    load_summed_dv<n>(dV, total, gid, parts, active, v);
     if constexpr (LEG) {
       adjoint_bracket_f<TabF<M>::Pinv>(v, dR);      // V = P^{-1} W1 P^{-T}
     } else {
@@ -281,17 +277,18 @@ __device__ __forceinline__ void fbwd_weight_body(const int8_t* __restrict__ w,
 }
 
 // The input and the filter bracket are independent of each other: one launch, the first
-// nb_in work groups take (tile, channel) items, the rest filters.
+// nb_w work groups take filters (few, and the longer chain of loads where dV comes in
+// parts: they start first), the rest (tile, channel) items.
 template <int M, bool LEG>
 __global__ __launch_bounds__(256) void k_fbwd_input_weight(
     const int8_t* __restrict__ x, const float* __restrict__ dU, float* __restrict__ dXt,
-    float* __restrict__ part_in, const int8_t* __restrict__ w, const float* __restrict__ dV,
+    float* __restrict__ part_in, const int8_t* __restrict__ w, float* __restrict__ dV,
     float* __restrict__ dw, float* __restrict__ part_w, Geometry g, FlexMats fm, StageMults mu,
-    float s_in, float s_w, unsigned nb_in) {
-  if (blockIdx.x < nb_in)
-    fbwd_input_body<M, LEG>(x, dU, dXt, part_in, g, fm, mu, s_in, blockIdx.x);
+    float s_in, float s_w, unsigned nb_w, int parts) {
+  if (blockIdx.x < nb_w)
+    fbwd_weight_body<M, LEG>(w, dV, dw, part_w, g, fm, s_w, blockIdx.x, parts);
   else
-    fbwd_weight_body<M, LEG>(w, dV, dw, part_w, g, fm, s_w, blockIdx.x - nb_in);
+    fbwd_input_body<M, LEG>(x, dU, dXt, part_in, g, fm, mu, s_in, blockIdx.x - nb_w);
 }
 
 // dx[b][h][w][c] from per-tile gradients: tile ty reads input rows ty*M - 1 ... ty*M + M,
@@ -354,18 +351,19 @@ hipError_t PerMFlexBwd<M>::output(const Geometry& g, bool leg, const void* Mq, i
 template <int M>
 hipError_t PerMFlexBwd<M>::input_weight(const Geometry& g, bool leg, const int8_t* x,
                                         const float* dU, float* dXt, float* part_in,
-                                        const int8_t* w, const float* dV, float* dw,
+                                        const int8_t* w, float* dV, float* dw,
                                         float* part_w, const FlexMats& fm, const StageMults& mu,
                                         float s_in, float s_w, hipStream_t st) {
   const unsigned nb_in = (unsigned)(((long)g.T * g.C + 255) / 256);
   const unsigned nb_w = (unsigned)(((long)g.K * g.C + 255) / 256);
   const dim3 grid(nb_in + nb_w), bs(256);
+  const int parts = backward_dv_reader_parts(g);
   if (leg)
     wino_launch((k_fbwd_input_weight<M, true>), grid, bs, st, x, dU, dXt, part_in, w, dV, dw, part_w,
-                g, fm, mu, s_in, s_w, nb_in);
+                g, fm, mu, s_in, s_w, nb_w, parts);
   else
     wino_launch((k_fbwd_input_weight<M, false>), grid, bs, st, x, dU, dXt, part_in, w, dV, dw,
-                part_w, g, fm, mu, s_in, s_w, nb_in);
+                part_w, g, fm, mu, s_in, s_w, nb_w, parts);
   return hipGetLastError();
 }
 

@@ -175,16 +175,19 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
                         const StageMults& out_mu, const MultTable& mm, const ShiftTable* sh,
                         hipStream_t st);
 
-// Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> dx, 3 dV -> dw.
+// Backward pass (wino_backward.hip), fp32.  which: 0 dY -> dM, 1 dU -> dx.
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st);
 // Number of partial sums (a power of two, 1 ... 32) the dV contraction leaves for this
-// shape; the dV buffer holds that many [n*n][K][C] tensors, and launch_backward_sum_splits
-// adds them into the first one (no launch when there is only one).
+// shape; the dV buffer holds that many [n*n][K][C] tensors.  Up to four are added, into the
+// first one, by whichever kernel reads dV next (backward_dv_reader_parts says how many it
+// will find); more are added by launch_backward_sum_splits, which launches nothing otherwise.
 int backward_dv_splits(const Geometry& g);
+int backward_dv_reader_parts(const Geometry& g);
 hipError_t launch_backward_sum_splits(const Geometry& g, float* dV, hipStream_t st);
-// dU -> dx and dV -> dw in one launch (both non-empty).
-hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, const float* dV,
+// dV -> dw alone, and dU -> dx with dV -> dw in one launch (both non-empty).
+hipError_t launch_backward_dw(const Geometry& g, float* dV, float* dw, hipStream_t st);
+hipError_t launch_backward_dx_dw(const Geometry& g, const float* dU, float* dx, float* dV,
                                  float* dw, hipStream_t st);
 // for_weights = false: out = dU[p][t][c] = scale[p] sum_k dM[p][t][k] codes[p][k][c] (codes = V);
 // for_weights = true:  out = dV[p][k][c] = scale[p] sum_t dM[p][t][k] codes[p][t][c] (codes = U).
@@ -201,7 +204,7 @@ struct PerMFlexBwd {
                            const StageMults& mu, float s_in, hipStream_t st);
   static hipError_t input_weight(const Geometry& g, bool legendre, const int8_t* x,
                                  const float* dU, float* dXt, float* part_in, const int8_t* w,
-                                 const float* dV, float* dw, float* part_w, const FlexMats& fm,
+                                 float* dV, float* dw, float* part_w, const FlexMats& fm,
                                  const StageMults& mu, float s_in, float s_w, hipStream_t st);
   static hipError_t tile_sum(const Geometry& g, const float* dXt, float* dx, hipStream_t st);
 };
@@ -214,7 +217,7 @@ hipError_t launch_flex_backward_output(const Geometry& g, bool legendre, const v
                                        const StageMults& mu, float s_in, hipStream_t st);
 hipError_t launch_flex_backward_input_weight(const Geometry& g, bool legendre, const int8_t* x,
                                              const float* dU, float* dXt, float* part_in,
-                                             const int8_t* w, const float* dV, float* dw,
+                                             const int8_t* w, float* dV, float* dw,
                                              float* part_w, const FlexMats& fm,
                                              const StageMults& mu, float s_in, float s_w,
                                              hipStream_t st);

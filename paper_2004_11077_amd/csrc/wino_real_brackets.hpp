@@ -82,4 +82,33 @@ __device__ __forceinline__ void adjoint_bracket_f(const float (&x)[T.rows][T.row
   });
 }
 
+// dV [n*n][K*C] may arrive as `parts` partial sums over ranges of tiles, n*n * total floats
+// apart.  The one lane that reads filter gid adds them in ascending order (one round of
+// independent loads per part) and leaves the sums in the first part.
+template <int N>
+__device__ __forceinline__ void load_summed_dv(float* __restrict__ dV, long total, long gid,
+                                               int parts, bool active, float (&v)[N][N]) {
+  rfor<0, N>([&](auto i) {
+    rfor<0, N>([&](auto j) {
+      v[i][j] = active ? dV[(long)(decltype(i)::value * N + decltype(j)::value) * total + gid] : 0.f;
+    });
+  });
+  if (parts <= 1 || !active) return;
+  for (int sp = 1; sp < parts; ++sp) {
+    const float* part = dV + (long)sp * N * N * total;
+    float t[N][N];
+    rfor<0, N>([&](auto i) {
+      rfor<0, N>([&](auto j) {
+        t[i][j] = part[(long)(decltype(i)::value * N + decltype(j)::value) * total + gid];
+      });
+    });
+    rfor<0, N>([&](auto i) { rfor<0, N>([&](auto j) { v[i][j] += t[i][j]; }); });
+  }
+  rfor<0, N>([&](auto i) {
+    rfor<0, N>([&](auto j) {
+      dV[(long)(decltype(i)::value * N + decltype(j)::value) * total + gid] = v[i][j];
+    });
+  });
+}
+
 }  // namespace wino

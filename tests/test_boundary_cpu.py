@@ -238,10 +238,11 @@ def test_flex_backward_argument_checks_before_any_launch():
 
 def test_backward_dv_parts_and_their_workspace():
     r256 = lambda v: (v + 255) // 256 * 256
-    # (shape, m) -> parts: fewer than 512 tiles of 64 x 64 outputs, ranges of at least four 32-tile chunks
-    cases = [((256, 8, 8, 256, 256), 4, 1), ((128, 32, 32, 64, 64), 4, 16), ((128, 16, 16, 128, 128), 4, 4),
+    # (shape, m) -> parts: fewer than 256 tiles of dV (128 outputs wide where K resp. C exceeds 64, else 64),
+    # ranges of at least four 32-tile chunks
+    cases = [((256, 8, 8, 256, 256), 4, 2), ((128, 32, 32, 64, 64), 4, 8), ((128, 16, 16, 128, 128), 4, 8),
              ((1, 8, 8, 16, 16), 4, 1), ((64, 16, 16, 16, 16), 4, 8), ((37, 12, 12, 16, 32), 4, 2),
-             ((512, 16, 16, 16, 16), 2, 32)]
+             ((512, 16, 16, 16, 16), 2, 16)]
     for shape, m, parts in cases:
         d = wn.ConvDesc(*shape, m=m)
         assert wn.wino_backward_dv_parts(d) == parts, shape
