@@ -249,9 +249,11 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
  * gradients with respect to the REAL output, input (s_x * code) and weights
  * (s_w * code).  U [n*n][T][C], V [n*n][K][C]: the int8 codes the forward pass
  * contracted (device).  s (host): only s_u, s_v (or, with per_point, s_u_pt,
- * s_v_pt) are read.  All arithmetic is fp32 (fp32 matrix instructions for the
- * two contractions); sums over tiles are taken in a fixed order, so results
- * are reproducible.  Int8 path only (d->bits_in = 8).  Pixels of partial tiles
+ * s_v_pt) are read.  All arithmetic is fp32; the two contractions multiply
+ * dM, cut into three bf16 pieces that together hold its upper 24 bits, by the
+ * codes on the bf16 matrix instructions (exact products, fp32 accumulation:
+ * fp32 accuracy; a non-finite dM gives NaN).  Sums over tiles are taken in a
+ * fixed order, so results are reproducible.  Int8 path only (d->bits_in = 8).  Pixels of partial tiles
  * outside H x W receive no gradient.  d->relu, d->out_type, d->bits_hadamard
  * and d->fused are ignored: dy is the gradient at the layer's real output, a
  * ReLU or an output cast behind it is the caller's to apply to dy beforehand.
@@ -264,9 +266,10 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
  * Errors: EINVAL, EUNSUPPORTED, EWORKSPACE, EHIP. */
 int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 /* *parts (host) = number of partial sums over ranges of tiles in which the dV
- * contraction of this shape is computed (a power of two, 1 ... 32).  With more
- * than one, both backward calls launch one more kernel that adds them up, and
- * the dV region of the workspace holds that many tensors. */
+ * contraction of this shape is computed (a power of two, 1 ... 32); the dV
+ * region of the workspace holds that many tensors.  Up to four are added by
+ * the kernel that reads dV next, more by a kernel of their own; either way
+ * the first tensor holds the sum when the call returns. */
 int wino_backward_dv_parts(const wino_conv_desc_t* d, int* parts);
 int wino_backward(const wino_conv_desc_t* d, const void* dy, const void* U, const void* V,
                   const wino_scales_t* s, void* dx, void* dw, void* workspace, size_t ws_bytes,
