@@ -154,3 +154,54 @@ def test_backward_random_shapes(m, shape, per_point, seed):
     dy, Uq, Vq, scales = make_case(shape, m, seed=seed, per_point=per_point)
     got = run_backward(dy, Uq, Vq, shape, m, scales)
     check(reference(dy, Uq, Vq, shape, m, scales), got, 1e-5)
+
+
+ONE_TERM_CASES = [(4, (3, 12, 12, 80, 48)), (4, (5, 9, 9, 144, 272)), (2, (40, 4, 4, 16, 144))]
+
+
+@pytest.mark.parametrize("m,shape", ONE_TERM_CASES)
+def test_contractions_keep_all_24_bits_of_dM(m, shape):
+    """The contractions multiply dM by the codes in pieces on a narrower matrix pipe; a dropped
+    or misplaced piece would cost at least 2^-16 of a product, which the max-relative bound
+    above cannot see.  With codes that leave ONE non-zero term in every reduction, each output
+    is s * dM * code for a single dM value with a full 24-bit significand, and must agree with
+    the fp64 product of the library's own dM to a few units of fp32 roundoff, element by
+    element."""
+    N, H, W, C, K = shape
+    rng = np.random.default_rng(31 + C)
+    n2 = (m + 2) ** 2
+    T = N * (-(-H // m)) * (-(-W // m))
+    dy = rng.standard_normal((N, H, W, K)).astype(np.float32)
+    Uq = np.zeros((n2, T, C), dtype=np.int8)
+    Vq = np.zeros((n2, K, C), dtype=np.int8)
+    code = lambda size: (rng.integers(1, 128, size) * rng.choice([-1, 1], size)).astype(np.int8)
+    t0 = rng.integers(0, T, (n2, C))                 # the one tile with a non-zero code of U, per (p, c)
+    k0 = rng.integers(0, K, (n2, C))                 # the one output channel with a non-zero code of V
+    p_idx, c_idx = np.meshgrid(np.arange(n2), np.arange(C), indexing="ij")
+    Uq[p_idx, t0, c_idx] = code((n2, C))
+    Vq[p_idx, k0, c_idx] = code((n2, C))
+    scales = {"s_u": 0.02, "s_v": 0.011}
+    got = run_backward(dy, Uq, Vq, shape, m, scales)
+    dM = got["dM"].astype(np.float64)                # [n2, T, K], exact fp32 values
+    s_u, s_v = float(np.float32(scales["s_u"])), float(np.float32(scales["s_v"]))
+    dU_ref = dM[p_idx[:, None, :], np.arange(T)[None, :, None], k0[:, None, :]] * \
+        Vq[p_idx, k0, c_idx].astype(np.float64)[:, None, :] * s_v          # [n2, T, C]
+    dV_ref = dM[p_idx[:, None, :], t0[:, None, :], np.arange(K)[None, :, None]] * \
+        Uq[p_idx, t0, c_idx].astype(np.float64)[:, None, :] * s_u          # [n2, K, C]
+    for name, ref in (("dU", dU_ref), ("dV", dV_ref)):
+        err = np.abs(got[name].astype(np.float64) - ref)
+        assert (err <= 4 * 2.0 ** -24 * np.abs(ref)).all(), \
+            "%s: worst relative error %g" % (name, float((err / np.maximum(np.abs(ref), 1e-300)).max()))
+
+
+def test_backward_scales_exactly_with_powers_of_two():
+    """Scaling dy by a power of two must scale every result by exactly that power (no piece
+    of the split operands under- or overflows within 2^-40 ... 2^40)."""
+    m, shape = 4, (3, 11, 6, 144, 80)
+    dy, Uq, Vq, scales = make_case(shape, m, seed=5, per_point=False)
+    base = run_backward(dy, Uq, Vq, shape, m, scales)
+    for e in (-40, 40):
+        f = np.float32(2.0 ** e)
+        got = run_backward(dy * f, Uq, Vq, shape, m, scales)
+        for key in ("dM", "dU", "dV", "dx", "dw"):
+            assert np.array_equal(got[key], base[key] * f), (key, e)
