@@ -340,6 +340,7 @@ def main():
     torch.cuda.synchronize()
     measured_peaks = {"int8_mfma_TOPs": probe(wn.PROBE_MFMA_I8, 256 * 16, 2048),
                       "valu_mad24_Tops": probe(wn.PROBE_VALU_MAD24, 256 * 16, 2048),
+                      "bf16_mfma_TFLOPs": probe(wn.PROBE_MFMA_BF16, 256 * 16, 2048),
                       "copy_GBps": 2 * src.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
     del src, dst
     pts = {2: [0, 1, -1], 4: [0, 1, -1, 2, -2], 6: [0, 1, -1, 2, -2, (1, 2), (-1, 2)]}[wl.m]
@@ -532,6 +533,7 @@ def main():
                          "frac": gemm_bytes / gemm_s / 8e12, "traffic": None,
                          "algorithmic_bytes": gemm_bytes,
                          "bf16_mfma_issued_TFLOPs": issued_tf, "bf16_mfma_frac": issued_tf / 2500.0,
+                         "bf16_mfma_frac_of_measured_peak": issued_tf / measured_peaks["bf16_mfma_TFLOPs"],
                          "fp32_equivalent_TFLOPs": gemm_flops / gemm_s / 1e12,
                          "fp32_mfma_peak_TFLOPs": 157.3},
             "note": "straight-through gradients; the two contraction gradients are GEMMs of fp32 dM with "

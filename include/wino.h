@@ -321,13 +321,13 @@ int wino_profile_next_launch(void* start_event, void* stop_event);
  * sustains on a unit the hot path is priced against.  WINO_PROBE_MFMA_I8:
  * every wave issues iters x 4 independent 32x32x32 int8 MFMAs;
  * WINO_PROBE_VALU_MAD24: every lane issues iters x 8 24-bit multiply-adds;
- * WINO_PROBE_MFMA_F32: every wave issues iters x 4 independent 32x32x2 fp32
- * MFMAs (the instruction of the backward pass's contractions).
+ * WINO_PROBE_MFMA_BF16: every wave issues iters x 4 independent 32x32x16
+ * bf16 MFMAs (the instruction of the backward pass's contractions).
  * `blocks` work groups of 256 lanes; *work (host, may be null) receives the
  * int8 operations resp. flops (2 per multiply-accumulate) resp. lane-operations
  * of the launch; `sink` is a device int the kernel may write.  Time it with
  * wino_profile_next_launch. */
-enum { WINO_PROBE_MFMA_I8 = 0, WINO_PROBE_VALU_MAD24 = 1, WINO_PROBE_MFMA_F32 = 2 };
+enum { WINO_PROBE_MFMA_I8 = 0, WINO_PROBE_VALU_MAD24 = 1, WINO_PROBE_MFMA_BF16 = 2 };
 int wino_probe_peak(int kind, int blocks, int iters, void* sink, double* work, void* hip_stream);
 
 /* Text of the last error on this thread ("" if none); valid until the next

@@ -7,7 +7,7 @@ built library raises: there is no CPU fallback.
 """
 from .binding import (  # noqa: F401
     BASE_CANONICAL, BASE_CHEBYSHEV, BASE_HERMITE, BASE_LEGENDRE, FUSED_AUTO, FUSED_OFF, FUSED_ON,
-    OUT_F32, OUT_I32, OUT_I8, MAT_NAMES, PROBE_MFMA_F32, PROBE_MFMA_I8, PROBE_VALU_MAD24, ConvDesc, FlexGrads, FlexMatrices, Matrices, Scales, WinoError,
+    OUT_F32, OUT_I32, OUT_I8, MAT_NAMES, PROBE_MFMA_BF16, PROBE_MFMA_I8, PROBE_VALU_MAD24, ConvDesc, FlexGrads, FlexMatrices, Matrices, Scales, WinoError,
     lib_path, wino_backward, wino_backward_dv_parts, wino_backward_workspace_bytes, wino_calibrate,
     wino_calibrate_workspace_bytes, wino_contract, wino_conv2d,
     wino_flex_backward, wino_flex_backward_workspace_bytes, wino_flex_calibrate, wino_flex_conv2d, wino_flex_input_transform,

@@ -222,7 +222,7 @@ def wino_profile_next_launch(start_event, stop_event):
     _check(_load().wino_profile_next_launch(C.c_void_p(start_event), C.c_void_p(stop_event)))
 
 
-PROBE_MFMA_I8, PROBE_VALU_MAD24, PROBE_MFMA_F32 = 0, 1, 2
+PROBE_MFMA_I8, PROBE_VALU_MAD24, PROBE_MFMA_BF16 = 0, 1, 2
 
 
 def wino_probe_peak(kind, blocks, iters, sink, stream=None):

@@ -371,14 +371,14 @@ int wino_profile_next_launch(void* start_event, void* stop_event) {
 }
 
 int wino_probe_peak(int kind, int blocks, int iters, void* sink, double* work, void* hip_stream) {
-  if (kind != WINO_PROBE_MFMA_I8 && kind != WINO_PROBE_VALU_MAD24 && kind != WINO_PROBE_MFMA_F32)
+  if (kind != WINO_PROBE_MFMA_I8 && kind != WINO_PROBE_VALU_MAD24 && kind != WINO_PROBE_MFMA_BF16)
     return fail(WINO_EINVAL, "unknown probe %d", kind);
   if (blocks < 1 || blocks > (1 << 20) || iters < 1 || iters > (1 << 24))
     return fail(WINO_EINVAL, "probe size out of range");
   if (int rc = need(sink, "sink")) return rc;
   if (work)
     *work = kind == WINO_PROBE_MFMA_I8    ? (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 32)
-            : kind == WINO_PROBE_MFMA_F32 ? (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 2)
+            : kind == WINO_PROBE_MFMA_BF16 ? (double)blocks * 4.0 * iters * 4.0 * (2.0 * 32 * 32 * 16)
                                           : (double)blocks * 256.0 * iters * 8.0;
   hipError_t e = launch_probe(kind, blocks, iters, (int*)sink, (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "probe launch");

@@ -277,13 +277,19 @@ __global__ __launch_bounds__(256) void k_probe_mfma_i8(int iters, int* __restric
   if (sum == 0x7fffffff) sink[0] = sum;      // keeps the loop alive; practically never true
 }
 
-__global__ __launch_bounds__(256) void k_probe_mfma_f32(int iters, int* __restrict__ sink) {
+__global__ __launch_bounds__(256) void k_probe_mfma_bf16(int iters, int* __restrict__ sink) {
   using v16f = __attribute__((ext_vector_type(16))) float;
-  const float a = (float)(threadIdx.x & 7) * 0.25f, b = (float)(threadIdx.x & 3) - 1.5f;
+  using bf16x8 = __attribute__((ext_vector_type(8))) __bf16;
+  using v4u = __attribute__((ext_vector_type(4))) unsigned;
+  // bf16 pairs 1.0 | 0.5 resp. 2.0 | -1.0 (plus a lane-dependent low mantissa bit)
+  const unsigned ua = 0x3f803f00u | (threadIdx.x & 1), ub = 0x4000bf80u | ((threadIdx.x >> 1) & 1);
+  const v4u wa = {ua, ua, ua, ua}, wb = {ub, ub, ub, ub};
+  const bf16x8 a = __builtin_bit_cast(bf16x8, wa), b = __builtin_bit_cast(bf16x8, wb);
   v16f acc[4] = {};
   for (int i = 0; i < iters; ++i) {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) acc[k] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[k], 0, 0, 0);
+    for (int k = 0; k < 4; ++k)
+      acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[k], 0, 0, 0);
   }
   float sum = 0.f;
 #pragma unroll
@@ -312,7 +318,7 @@ hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t 
   if (kind == 0)
     wino_launch(k_probe_mfma_i8, dim3((unsigned)blocks), dim3(256), st, iters, sink);
   else if (kind == 2)
-    wino_launch(k_probe_mfma_f32, dim3((unsigned)blocks), dim3(256), st, iters, sink);
+    wino_launch(k_probe_mfma_bf16, dim3((unsigned)blocks), dim3(256), st, iters, sink);
   else
     wino_launch(k_probe_valu_mad24, dim3((unsigned)blocks), dim3(256), st, iters, 3, sink);
   return hipGetLastError();

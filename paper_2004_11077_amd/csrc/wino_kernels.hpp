@@ -235,7 +235,7 @@ hipError_t launch_backward_gemms(const Geometry& g, const float* dM, const int8_
 
 // Peak probes: kind 0 = int8 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of
 // 32x32x32), kind 1 = 24-bit multiply-add loop (blocks * 256 lanes * iters * 8),
-// kind 2 = fp32 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of 32x32x2).
+// kind 2 = bf16 MFMA loop (blocks * 4 waves * iters * 4 MFMAs of 32x32x16).
 hipError_t launch_probe(int kind, int blocks, int iters, int* sink, hipStream_t st);
 
 // fp32 path: stage 0 weight (a = w), 1 input (a = x), 2 contraction (a = U, b = V),

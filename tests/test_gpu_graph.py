@@ -56,6 +56,7 @@ def test_peak_probes_run_and_report_their_work():
     sink = torch.zeros(1, dtype=torch.int32, device="cuda:0")
     assert wn.wino_probe_peak(wn.PROBE_MFMA_I8, 8, 16, sink) == 8 * 4 * 16 * 4 * 2 * 32 ** 3
     assert wn.wino_probe_peak(wn.PROBE_VALU_MAD24, 8, 16, sink) == 8 * 256 * 16 * 8
+    assert wn.wino_probe_peak(wn.PROBE_MFMA_BF16, 8, 16, sink) == 8 * 4 * 16 * 4 * 2 * 32 * 32 * 16
     torch.cuda.synchronize()
     assert int(sink.item()) == 0
 
