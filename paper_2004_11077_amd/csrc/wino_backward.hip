@@ -186,7 +186,7 @@ __global__ __launch_bounds__(256) void k_bwd_dw(float* __restrict__ dV, float* _
 // work groups transform dV into dw (few, and the longer chain of loads where dV
 // comes in parts: they start first), the rest gather dx.
 template <int M>
-__global__ __launch_bounds__(256) void k_bwd_dx_dw(const float* __restrict__ dU,
+__global__ __launch_bounds__(256, (M <= 4 ? 4 : 2)) void k_bwd_dx_dw(const float* __restrict__ dU,
                                                    float* __restrict__ dx,
                                                    float* __restrict__ dV,
                                                    float* __restrict__ dw, Geometry g,

@@ -280,7 +280,7 @@ __device__ __forceinline__ void fbwd_weight_body(const int8_t* __restrict__ w,
 // nb_w work groups take filters (few, and the longer chain of loads where dV comes in
 // parts: they start first), the rest (tile, channel) items.
 template <int M, bool LEG>
-__global__ __launch_bounds__(256) void k_fbwd_input_weight(
+__global__ __launch_bounds__(256, (M <= 4 ? 4 : 1)) void k_fbwd_input_weight(
     const int8_t* __restrict__ x, const float* __restrict__ dU, float* __restrict__ dXt,
     float* __restrict__ part_in, const int8_t* __restrict__ w, float* __restrict__ dV,
     float* __restrict__ dw, float* __restrict__ part_w, Geometry g, FlexMats fm, StageMults mu,

@@ -83,11 +83,15 @@ __device__ __forceinline__ void adjoint_bracket_f(const float (&x)[T.rows][T.row
 }
 
 // dV [n*n][K*C] may arrive as `parts` partial sums over ranges of tiles, n*n * total floats
-// apart.  The one lane that reads filter gid adds them in ascending order (one round of
-// independent loads per part) and leaves the sums in the first part.
+// apart.  The one lane that reads filter gid adds them in ascending order and leaves the
+// sums in the first part.  The first part is loaded whole; the others two rows of the
+// N x N points at a time (2 N independent loads per step, kept apart so that the lane
+// needs no second N x N array of registers: the kernels that call this share their
+// register budget with a bandwidth-bound body that wants many waves).
 template <int N>
 __device__ __forceinline__ void load_summed_dv(float* __restrict__ dV, long total, long gid,
                                                int parts, bool active, float (&v)[N][N]) {
+  static_assert(N % 2 == 0, "rows are taken in pairs");
   rfor<0, N>([&](auto i) {
     rfor<0, N>([&](auto j) {
       v[i][j] = active ? dV[(long)(decltype(i)::value * N + decltype(j)::value) * total + gid] : 0.f;
@@ -96,13 +100,19 @@ __device__ __forceinline__ void load_summed_dv(float* __restrict__ dV, long tota
   if (parts <= 1 || !active) return;
   for (int sp = 1; sp < parts; ++sp) {
     const float* part = dV + (long)sp * N * N * total;
-    float t[N][N];
-    rfor<0, N>([&](auto i) {
-      rfor<0, N>([&](auto j) {
-        t[i][j] = part[(long)(decltype(i)::value * N + decltype(j)::value) * total + gid];
+    rfor<0, N / 2>([&](auto ii) {
+      constexpr int i0 = 2 * decltype(ii)::value;
+      float t[2][N];
+      rfor<0, 2>([&](auto d) {
+        rfor<0, N>([&](auto j) {
+          t[d][j] = part[(long)((i0 + decltype(d)::value) * N + decltype(j)::value) * total + gid];
+        });
       });
+      rfor<0, 2>([&](auto d) {
+        rfor<0, N>([&](auto j) { v[i0 + decltype(d)::value][j] += t[d][j]; });
+      });
+      __builtin_amdgcn_sched_barrier(0);
     });
-    rfor<0, N>([&](auto i) { rfor<0, N>([&](auto j) { v[i][j] += t[i][j]; }); });
   }
   rfor<0, N>([&](auto i) {
     rfor<0, N>([&](auto j) {
