@@ -120,6 +120,13 @@ def _load():
     if not os.path.exists(path):
         raise ImportError("libwino.so is not built (run: python -m paper_2004_11077_amd.build); "
                           "there is no fallback path")
+    # The tensors callers pass live in PyTorch's HIP runtime, and the first libamdhip64 loaded
+    # under its SONAME serves the whole process: load PyTorch's first, so that the library's
+    # kernels and the caller's memory and streams belong to one runtime whatever the import order.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(path)
     vp, ip = C.c_void_p, C.POINTER(C.c_int)
     lib.wino_last_error.restype = C.c_char_p
