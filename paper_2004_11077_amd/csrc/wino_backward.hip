@@ -285,9 +285,11 @@ __device__ __forceinline__ void gemm_body(const GemmArgs& ga, const MultTable& s
   // Consecutive blocks are spread round-robin over the 8 XCDs, so block L runs on
   // XCD L % 8.  The column blocks that share one A panel (point p, row block rb: a
   // "unit") are given to consecutive blocks of ONE XCD, whose L2 then serves the
-  // panel to all of them.
+  // panel to all of them; and every XCD takes a contiguous eighth of the units, i.e.
+  // all row blocks of four or five points, so that the codes of a point (the B
+  // operand of all its row blocks) are fetched by one XCD, not by all eight.
   const int xcd = block % kXcds, slot = block / kXcds;
-  const int unit = (slot / col_blocks) * kXcds + xcd;
+  const int unit = xcd * ((units + kXcds - 1) / kXcds) + slot / col_blocks;
   if (unit >= units) return;                     // padding blocks (uniform exit, no barrier yet)
   const int cb = slot % col_blocks;
   const int p = unit / row_blocks, rb = unit - p * row_blocks;
