@@ -493,9 +493,9 @@ def main():
     # synthetic output gradient, U and V as the forward pass left them), fp32; each of its
     # three launches timed by its own event pair
     if want("backward") and reps == 1:
-        # up to 4 partial sums of dV are added by the kernel that reads dV; more cost a launch of their own
+        # up to 8 partial sums of dV are added by the kernel that reads dV; more cost a launch of their own
         parts = wn.wino_backward_dv_parts(desc)
-        extra_launch = ("sum_dV_parts",) if parts > 4 else ()
+        extra_launch = ("sum_dV_parts",) if parts > 8 else ()
         bnames = ("dY_to_dM", "gemm_dV_and_dU") + extra_launch + ("dU_to_dx_and_dV_to_dw",)
         g = torch.Generator(device="cpu").manual_seed(wl.seed + 1)
         dy = torch.randn((wl.N, wl.H, wl.W, wl.K), generator=g, dtype=torch.float32).to(dev)

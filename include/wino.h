@@ -267,7 +267,7 @@ int wino_flex_calibrate(const wino_conv_desc_t* d, const wino_flex_matrices_t* f
 int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 /* *parts (host) = number of partial sums over ranges of tiles in which the dV
  * contraction of this shape is computed (a power of two, 1 ... 32); the dV
- * region of the workspace holds that many tensors.  Up to four are added by
+ * region of the workspace holds that many tensors.  Up to eight are added by
  * the kernel that reads dV next, more by a kernel of their own; either way
  * the first tensor holds the sum when the call returns. */
 int wino_backward_dv_parts(const wino_conv_desc_t* d, int* parts);

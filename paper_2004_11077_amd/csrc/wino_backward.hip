@@ -483,7 +483,7 @@ hipError_t bwd_dx_dw(const Geometry& g, const float* dU, float* dx, float* dV, f
 
 // Up to this many partial sums of dV are added by the kernels that read dV (load_summed_dv);
 // more are added by k_sum_splits first.
-constexpr int kReaderParts = 4;
+constexpr int kReaderParts = 8;
 
 // dV[i] = sum over s < splits of dV[s * count + i], ascending s, i < count.
 __global__ __launch_bounds__(256) void k_sum_splits(float* __restrict__ dV, long count, int splits) {
@@ -622,7 +622,7 @@ int backward_dv_reader_parts(const Geometry& g) {
 
 // The dV contraction has few outputs (n*n x K x C) and a long reduction (all tiles): while it
 // has fewer tiles than the chip has compute units, the reduction is cut into 2^j ranges that
-// run as separate work groups and leave partial sums, added up in ascending order: up to four
+// run as separate work groups and leave partial sums, added up in ascending order: up to eight
 // by the filter bracket that reads dV, more by k_sum_splits before it.  Ranges hold at least
 // four chunks; at most 32, and at most 64 MB of partial sums.
 int backward_dv_splits(const Geometry& g) {

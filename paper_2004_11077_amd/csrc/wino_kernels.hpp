@@ -179,7 +179,7 @@ hipError_t launch_fused(const Geometry& g, bool legendre_inner, const int8_t* x,
 hipError_t launch_backward_transform(int which, const Geometry& g, const float* in, float* out,
                                      hipStream_t st);
 // Number of partial sums (a power of two, 1 ... 32) the dV contraction leaves for this
-// shape; the dV buffer holds that many [n*n][K][C] tensors.  Up to four are added, into the
+// shape; the dV buffer holds that many [n*n][K][C] tensors.  Up to eight are added, into the
 // first one, by whichever kernel reads dV next (backward_dv_reader_parts says how many it
 // will find); more are added by launch_backward_sum_splits, which launches nothing otherwise.
 int backward_dv_splits(const Geometry& g);

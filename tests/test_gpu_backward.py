@@ -89,6 +89,7 @@ CASES = [
     (6, (2, 7, 8, 32, 16), True),
     (4, (40, 4, 4, 16, 32), False),         # T = 40: reduction over tiles not a multiple of 32
     (4, (64, 16, 16, 16, 16), False),       # T = 1024, few outputs: dV summed from 8 ranges of tiles
+    (2, (64, 16, 16, 16, 16), False),       # T = 4096: 16 ranges, added by a kernel of their own
     (2, (37, 12, 12, 32, 16), True),        # T = 1332: 8 ranges, the last one ragged
     (4, (37, 12, 12, 16, 32), False),       # T = 333: 2 ranges of 6 and 5 chunks, the last chunk ragged
 ]
@@ -108,6 +109,7 @@ def test_dv_parts_of_the_shapes_above():
     parts = lambda m, s: wn.wino_backward_dv_parts(wn.ConvDesc(*s, m=m))
     assert parts(4, (64, 16, 16, 16, 16)) == 8 and parts(2, (37, 12, 12, 32, 16)) == 8
     assert parts(4, (37, 12, 12, 16, 32)) == 2 and parts(4, (256, 8, 8, 256, 256)) == 2
+    assert parts(2, (64, 16, 16, 16, 16)) == 16
 
 
 @pytest.mark.parametrize("shape", [(0, 8, 8, 16, 16), (2, 8, 8, 16, 0), (2, 8, 8, 0, 16), (2, 0, 8, 16, 16)])

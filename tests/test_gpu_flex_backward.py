@@ -82,9 +82,11 @@ def run_gpu(dy, xq, wq, fwd, sc, fm, m, base, bits_hadamard):
     return out
 
 
-def check(ref, got):
-    for key, tol in (("dM", 1e-5), ("dU", 1e-5), ("dV", 1e-5), ("dx", 1e-5), ("dw", 1e-5),
-                     ("dGP", 2e-5), ("dBPT", 2e-5), ("dAPT", 2e-5)):
+def check(ref, got, long_sums=1.0):
+    """long_sums: factor on the tolerance of the results summed over all tiles (dV, dw), for
+    reductions much longer than the 1024 tiles the plain tolerance was set for."""
+    for key, tol in (("dM", 1e-5), ("dU", 1e-5), ("dV", 1e-5 * long_sums), ("dx", 1e-5),
+                     ("dw", 1e-5 * long_sums), ("dGP", 2e-5), ("dBPT", 2e-5), ("dAPT", 2e-5)):
         assert got[key].shape == ref[key].shape, key
         assert np.isfinite(got[key]).all(), key + " holds values the kernels did not write"
         bound = tol * max(float(np.abs(ref[key]).max()), 1e-30)
@@ -105,6 +107,7 @@ CASES = [
     (4, "legendre", (8, 16, 16, 64, 64), 8),      # 128 tiles: several work groups per partial-sum array
     (4, "legendre", (40, 12, 12, 16, 16), 8),     # 360 tiles, few outputs: dV summed from 2 ranges of tiles
     (4, "canonical", (64, 16, 16, 16, 16), 9),    # 1024 tiles: 8 ranges
+    (2, "legendre", (64, 16, 16, 16, 16), 8),     # 4096 tiles: 16 ranges, added by a kernel of their own
 ]
 
 
@@ -116,7 +119,8 @@ def test_flex_backward_matches_oracle(m, base, shape, bits_hadamard):
     fwd, sc = oracle_forward(xq, wq, s_x, s_w, fm, m, base, bits_hadamard)
     dy = np.random.default_rng(5 + K).standard_normal((N, H, W, K)).astype(np.float32)
     got = run_gpu(dy, xq, wq, fwd, sc, fm, m, base, bits_hadamard)
-    check(reference(dy, xq, wq, fwd, sc, fm, m, base), got)
+    T = N * (-(-H // m)) * (-(-W // m))
+    check(reference(dy, xq, wq, fwd, sc, fm, m, base), got, long_sums=max(1.0, (T / 1024.0) ** 0.5))
 
 
 def test_flex_backward_with_static_matrices_matches_static_backward():
