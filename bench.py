@@ -23,13 +23,26 @@ INT8_MFMA_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, published
 # (the published 157.3 TFLOP/s fp32 figure counts packed 2-wide FMAs as 4 flops).
 VALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by
-# a plain device copy of known size in the same run (profiles/hbm_traffic_cfg4a_f4_c256.txt).
-MEASURED_TRAFFIC_BYTES = {
-    "cfg4a_f4_c256": {"operand_transforms": (7175.3 + 11520.0) * 1024,
-                      "contraction": (13936.2 + 9216.0) * 1024,
-                      "output_transform": (9334.1 + 16384.0) * 1024},
-}
+MIN_TIMED_LAUNCHES = 200       # a reported step is the mean over at least this many steps
+WARM_SECONDS = 0.3             # back-to-back steps before anything is timed, whatever --warmup says
+STAGE_SAMPLES = 32             # event pairs per launch; the median is reported
+
+
+def measured_traffic(workload):
+    """HBM bytes per launch from profiles/hbm_traffic_<workload>.txt: lines
+    ``TRAFFIC <launch> fetched_KiB=<f> written_KiB=<w>`` hold rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE per dispatch, already scaled by what the same counters read for a plain device
+    copy of known size in the same run.  Empty when the file has no such line."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    out = {}
+    if os.path.exists(path):
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 4 and parts[0] == "TRAFFIC":
+                    kv = dict(p.split("=") for p in parts[2:])
+                    out[parts[1]] = (float(kv["fetched_KiB"]) + float(kv["written_KiB"])) * 1024
+    return out
 
 
 def bracket_ops(mats, names):
@@ -46,7 +59,7 @@ def bracket_ops(mats, names):
 
 
 def stage_model(wl, m_bytes, y_bytes, mats):
-    """Algorithmic work of one launch of each stage (bytes, int8 ops, ALU ops)."""
+    """Algorithmic work of one launch of each kind (bytes, int8 ops, ALU ops)."""
     n = wl.m + 2
     T, C, K = wl.tiles, wl.C, wl.K
     leg = wl.base == "legendre"
@@ -61,6 +74,16 @@ def stage_model(wl, m_bytes, y_bytes, mats):
         "bound": "hbm",
         "work": model["weight_transform"]["work"] + model["input_transform"]["work"],
         "alu_ops": model["weight_transform"]["alu_ops"] + model["input_transform"]["alu_ops"]}
+    # a3 and a4 in one launch: the contraction's multiply-accumulates; U, V in and y out
+    model["contraction_output"] = {
+        "bound": "mfma", "work": model["contraction"]["work"],
+        "bytes": n * n * (T * C + K * C) + T * K * wl.m * wl.m * y_bytes,
+        "alu_ops": alu["output_transform"]}
+    # a2 + a3 + a4 in one launch: x, V in and y out
+    model["fused_layer"] = {
+        "bound": "mfma", "work": model["contraction"]["work"],
+        "bytes": T * C * wl.m * wl.m + n * n * K * C + T * K * wl.m * wl.m * y_bytes,
+        "alu_ops": alu["output_transform"] + alu["input_transform"] * max(1, K // 64)}
     return model
 
 
@@ -94,6 +117,26 @@ def hip_runtime():
     return lib
 
 
+def timed(torch, fn, steps, min_launches=MIN_TIMED_LAUNCHES, warm_seconds=WARM_SECONDS,
+          warmup=0):
+    """Seconds per call of fn: warm-up by time (and at least `warmup` calls), then the mean
+    over steps * inner back-to-back calls, inner chosen so that at least min_launches calls
+    are timed.  Returns (seconds per call, inner, warm-up calls)."""
+    warm, t_end = 0, time.perf_counter() + warm_seconds
+    while warm < warmup or time.perf_counter() < t_end:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
+        warm += 10
+    inner = max(1, -(-min_launches // max(1, steps)))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps * inner):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / (steps * inner), inner, warm
+
+
 def layer_times(wn, si, torch, dev, name, steps):
     """Step time of one whole layer (filters untransformed) through wino_conv2d."""
     wl = si.WORKLOADS[name]
@@ -114,15 +157,9 @@ def layer_times(wn, si, torch, dev, name, steps):
             sc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
             del cws
         ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
-        for _ in range(10):
-            wn.wino_conv2d(desc, x, w, y, sc, ws)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(steps):
-            wn.wino_conv2d(desc, x, w, y, sc, ws)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / steps
-        res[label] = {"ms_per_step": dt * 1e3, "TOPS_direct_equiv": ops / dt / 1e12}
+        dt = timed(torch, lambda: wn.wino_conv2d(desc, x, w, y, sc, ws), steps)[0]
+        res[label] = {"ms_per_step": dt * 1e3, "TOPS_direct_equiv": ops / dt / 1e12,
+                      "launches": wn.wino_conv2d_launches(desc)}
     return res
 
 
@@ -164,14 +201,7 @@ def resnet18_stack(wn, si, torch, dev, steps, N=256):
     def once():
         for run, xi, V, y, sc, ws in layers:
             wn.wino_conv2d(run, xi, V, y, sc, ws)
-    for _ in range(5):
-        once()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        once()
-    torch.cuda.synchronize()
-    dt = (time.perf_counter() - t0) / steps
+    dt = timed(torch, once, steps, min_launches=40)[0]
     return {"ms_per_pass": dt * 1e3, "TOPS_direct_equiv": ops / dt / 1e12, "layers": len(layers),
             "N": N, "note": "int8 in, int8 + ReLU out, filters pretransformed, fused = AUTO"}
 
@@ -199,6 +229,181 @@ def cpu_baseline(wl, min_seconds=12.0):
             "host_cpus": len(os.sched_getaffinity(0))}
 
 
+class Events:
+    """Raw HIP events for the library's per-dispatch timing hook."""
+
+    def __init__(self):
+        self.hip = hip_runtime()
+
+    def new(self):
+        ev = ctypes.c_void_p()
+        assert self.hip.hipEventCreate(ctypes.byref(ev)) == 0
+        return ev
+
+    def ms(self, a, b):
+        out = ctypes.c_float()
+        assert self.hip.hipEventElapsedTime(ctypes.byref(out), a, b) == 0
+        return out.value
+
+    def free(self, evs):
+        for ev in evs:
+            self.hip.hipEventDestroy(ev)
+
+
+def sample_launches(wn, torch, ev, call, n_launches, samples=STAGE_SAMPLES, gap=3):
+    """Median duration (ms) of each of the n_launches kernels that `call` queues.  Every
+    sampled call carries one event pair per launch, attached by the library to that very
+    dispatch (wino_profile_next_launch -> hipExtLaunchKernel), so elapsed(start, stop) is the
+    kernel's own begin-to-end time on its stream -- the interval rocprofv3 reports -- free of
+    the marker overhead an event recorded between launches would add.  `gap` unsampled calls
+    run between two sampled ones."""
+    import numpy as np
+    pairs = [[(ev.new(), ev.new()) for _ in range(n_launches)] for _ in range(samples)]
+    for s in range(samples):
+        for _ in range(gap):
+            call()
+        for a, b in pairs[s]:
+            wn.wino_profile_next_launch(a.value, b.value)
+        call()
+    torch.cuda.synchronize()
+    med = [float(np.median([ev.ms(*pairs[s][j]) for s in range(samples)]))
+           for j in range(n_launches)]
+    for row in pairs:
+        for a, b in row:
+            ev.free((a, b))
+    return med
+
+
+def price_stages(names, stage_ms, model, traffic, measured_peaks):
+    """Every launch against its ceilings.  Transforms are priced against HBM (algorithmic bytes
+    over the kernel's duration; the vector-ALU rate is given beside it because the Legendre
+    brackets are arithmetic-heavy), kernels that contain the contraction against the int8 MFMA
+    peak (Winograd-domain multiply-accumulates actually issued)."""
+    stages = {}
+    for nm in names:
+        sec = stage_ms[nm] * 1e-3
+        mdl = model[nm]
+        st = {"ms": stage_ms[nm], "bound": mdl["bound"]}
+        if mdl["bound"] == "hbm":
+            hbm = mdl["work"] / sec / 1e9
+            st.update({"achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": hbm / HBM_PEAK_GBS, "algorithmic_bytes": mdl["work"],
+                       "frac_of_measured_peak": hbm / measured_peaks["copy_GBps"]})
+        else:
+            ach = mdl["work"] / sec / 1e12
+            st.update({"achieved": ach, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                       "frac": ach / INT8_MFMA_PEAK_TOPS, "algorithmic_ops": mdl["work"],
+                       "frac_of_measured_peak": ach / measured_peaks["int8_mfma_TOPs"]})
+            if "bytes" in mdl:
+                st.update({"algorithmic_bytes": mdl["bytes"],
+                           "hbm_GBps": mdl["bytes"] / sec / 1e9,
+                           "hbm_frac": mdl["bytes"] / sec / 1e9 / HBM_PEAK_GBS})
+        if "alu_ops" in mdl:
+            alu = mdl["alu_ops"] / sec / 1e12
+            st.update({"alu_Tops": alu, "alu_frac": alu / VALU_PEAK_TOPS})
+        st["traffic"] = traffic.get(nm)
+        stages[nm] = st
+    return stages
+
+
+def device_peaks(wn, torch, ev, dev, stream):
+    """What this device sustains on the units the stages are priced against: register-only
+    int8 / bf16 MFMA and 24-bit multiply-add loops (library probes, timed per dispatch) and a
+    plain 256 MiB device copy (read + write bytes)."""
+    def probe(kind, blocks, iters):
+        sink = torch.zeros(1, dtype=torch.int32, device=dev)
+        wn.wino_probe_peak(kind, blocks, iters, sink, stream)          # warm-up
+        a, b = ev.new(), ev.new()
+        wn.wino_profile_next_launch(a.value, b.value)
+        work = wn.wino_probe_peak(kind, blocks, iters, sink, stream)
+        torch.cuda.synchronize()
+        ms = ev.ms(a, b)
+        ev.free((a, b))
+        return work / (ms * 1e-3) / 1e12
+    src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"int8_mfma_TOPs": probe(wn.PROBE_MFMA_I8, 256 * 16, 2048),
+            "valu_mad24_Tops": probe(wn.PROBE_VALU_MAD24, 256 * 16, 2048),
+            "bf16_mfma_TFLOPs": probe(wn.PROBE_MFMA_BF16, 256 * 16, 2048),
+            "copy_GBps": 2 * src.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
+
+
+def measure_layer(wn, si, torch, ev, dev, wl_name, batch_scale, steps, warmup, mode, peaks,
+                  copy_probe=False):
+    """One whole-layer workload through wino_conv2d (filters untransformed): step time, the
+    duration of each of its launches, and their roofline figures."""
+    from fractions import Fraction
+    base_wl = si.WORKLOADS[wl_name]
+    wl = si.Workload(**{**base_wl.__dict__, "N": base_wl.N * batch_scale})
+    L = si.make_layer(base_wl)
+    x = torch.from_numpy(L["xq"]).to(dev).repeat(batch_scale, 1, 1, 1).contiguous()
+    w = torch.from_numpy(L["wq"]).to(dev)
+    base = wn.BASE_LEGENDRE if wl.base == "legendre" else wn.BASE_CANONICAL
+    desc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                       bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=mode)
+    # set-up, outside the timed region: the library chooses the layer's scales itself
+    cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    sc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
+    del cws
+    ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    y = torch.empty((wl.N, wl.H, wl.W, wl.K), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    names = wn.wino_conv2d_launches(desc)
+
+    def step():
+        wn.wino_conv2d(desc, x, w, y, sc, ws, stream)
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    step()                        # first launch of each kernel in this process
+    torch.cuda.synchronize()
+    cold_ms = (time.perf_counter() - t0) * 1e3
+    sec, inner, warm = timed(torch, step, steps, warmup=warmup)
+    if copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    med = sample_launches(wn, torch, ev, step, len(names))
+    stage_ms = dict(zip(names, med))
+    pts = {2: [0, 1, -1], 4: [0, 1, -1, 2, -2], 6: [0, 1, -1, 2, -2, (1, 2), (-1, 2)]}[wl.m]
+    mats = wn.wino_make_matrices(wl.m, 3, [Fraction(*p) if isinstance(p, tuple) else p
+                                           for p in pts], base)
+    m_bytes = {8: 1, 9: 2, 32: 4}[wl.bits_hadamard]
+    model = stage_model(wl, m_bytes, 4, mats)
+    traffic = measured_traffic(wl.name) if batch_scale == 1 else {}
+    stages = price_stages(names, stage_ms, model, traffic, peaks)
+    ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
+    stage_sum = sum(med)
+    res = {"workload": wl.name + ("" if batch_scale == 1 else "_batchx%d" % batch_scale),
+           "wl": wl, "desc": desc, "x": x, "w": w, "y": y, "sc": sc, "L": L, "mats": mats,
+           "ms_per_step": sec * 1e3, "value": ops / sec / 1e12, "ops": ops, "launches": names,
+           "stages": stages, "stage_sum_ms": stage_sum,
+           "stage_sum_exceeds_step": bool(stage_sum > 1.05 * sec * 1e3),
+           "timing": {"timed_steps": steps * inner, "inner_repeats": inner, "warmup_steps": warm,
+                      "stage_samples": STAGE_SAMPLES, "stage_statistic": "median"},
+           "cold_step_ms": cold_ms}
+    return res
+
+
+def public(res):
+    """The JSON-serialisable part of a measure_layer result."""
+    keep = ("workload", "ms_per_step", "value", "launches", "stages", "stage_sum_ms",
+            "stage_sum_exceeds_step", "timing", "cold_step_ms")
+    out = {k: res[k] for k in keep}
+    out["unit"] = "TOPS"
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -207,11 +412,15 @@ def main():
     ap.add_argument("--workload", default="cfg4a_f4_c256")
     ap.add_argument("--batch-scale", type=int, default=1,
                     help="multiply the batch size N (extra, labelled in config)")
+    ap.add_argument("--mode", default="auto", choices=("auto", "split"),
+                    help="kernel selection of the headline step: the library's own choice "
+                         "(fused = AUTO) or one kernel per stage")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra timings of the other layer configurations")
     ap.add_argument("--only-extra", default=None,
-                    choices=("fused", "pretransformed", "per_point", "flex", "backward", "others"),
+                    choices=("split", "batch64", "fused", "pretransformed", "per_point", "flex",
+                             "backward", "others"),
                     help="run just this one of the extra measurements (for profiling it)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 64 MiB device copy after warm-up: the known-size "
@@ -228,244 +437,118 @@ def main():
     import synth_inputs as si
     import paper_2004_11077_amd as wn
 
-    wl = si.WORKLOADS[args.workload]
-    if args.batch_scale != 1:
-        wl = si.Workload(**{**wl.__dict__, "N": wl.N * args.batch_scale})
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-
-    L = si.make_layer(si.WORKLOADS[args.workload])
-    reps = args.batch_scale
-    x = torch.from_numpy(L["xq"]).to(dev).repeat(reps, 1, 1, 1).contiguous()
-    w = torch.from_numpy(L["wq"]).to(dev)
-    base = wn.BASE_LEGENDRE if wl.base == "legendre" else wn.BASE_CANONICAL
-    desc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
-                       bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32)
-    # set-up, outside the timed region: the library chooses the layer's scales itself
-    cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
-    sc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
-    del cws
-    n2, T = desc.n ** 2, desc.tiles
-    mdt = {8: torch.int8, 9: torch.int16, 32: torch.int32}[wl.bits_hadamard]
-    V = torch.empty((n2, wl.K, wl.C), dtype=torch.int8, device=dev)
-    U = torch.empty((n2, T, wl.C), dtype=torch.int8, device=dev)
-    M = torch.empty((n2, T, wl.K), dtype=mdt, device=dev)
-    y = torch.empty((wl.N, wl.H, wl.W, wl.K), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
-
-    # the three launches wino_conv2d makes for a layer whose filters arrive untransformed
-    names = ["operand_transforms", "contraction", "output_transform"]
-
-    # Per-kernel durations: every stage launch of every `stride`-th timed step carries a
-    # pair of HIP events that the library attaches to that very dispatch
-    # (wino_profile_next_launch -> hipExtLaunchKernel), so elapsed(start, stop) is the
-    # kernel's own begin-to-end time on its stream, the same interval rocprofv3 reports,
-    # free of the marker overhead an event recorded between launches would add.
-    hip = hip_runtime()
-
-    def new_event():
-        ev = ctypes.c_void_p()
-        assert hip.hipEventCreate(ctypes.byref(ev)) == 0
-        return ev
-
-    def elapsed_ms(a, b):
-        out = ctypes.c_float()
-        assert hip.hipEventElapsedTime(ctypes.byref(out), a, b) == 0
-        return out.value
-
-    def step(events=None):
-        if events is not None:
-            wn.wino_profile_next_launch(events[0][0].value, events[0][1].value)
-        wn.wino_transform_operands(desc, x, U, w, V, sc, stream)    # a1 + a2, one launch
-        if events is not None:
-            wn.wino_profile_next_launch(events[1][0].value, events[1][1].value)
-        wn.wino_contract(desc, U, V, M, sc, stream)
-        if events is not None:
-            wn.wino_profile_next_launch(events[2][0].value, events[2][1].value)
-        wn.wino_output_transform(desc, M, y, sc, stream)
-
-    # one cold step (first launch of each kernel in this process), reported as an extra
+    ev = Events()
+    # a first burst of work so that the probes below do not see a cold device
+    burn = torch.ones(64 << 20, dtype=torch.uint8, device=dev)
+    for _ in range(20):
+        burn.add_(1)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    step()
-    torch.cuda.synchronize()
-    cold_ms = (time.perf_counter() - t0) * 1e3
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    if args.copy_probe:
-        src = torch.ones(64 << 20, dtype=torch.uint8, device=dev)
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-    stride = 8
-    sampled = list(range(0, args.steps, stride))
-    evs = {i: [(new_event(), new_event()) for _ in names] for i in sampled}
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(evs.get(i))
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    del burn
+    peaks = device_peaks(wn, torch, ev, dev, stream)
 
-    stage_ms = {nm: float(np.mean([elapsed_ms(*evs[i][j]) for i in sampled]))
-                for j, nm in enumerate(names)}
-    for i in sampled:
-        for a, b in evs[i]:
-            hip.hipEventDestroy(a)
-            hip.hipEventDestroy(b)
-    # What this device sustains on the three units the stages are priced against:
-    # register-only int8 MFMA and 24-bit multiply-add loops (library probes, timed per
-    # dispatch like the stages) and a plain 256 MiB device copy (read + write bytes).
-    def probe(kind, blocks, iters):
-        sink = torch.zeros(1, dtype=torch.int32, device=dev)
-        wn.wino_probe_peak(kind, blocks, iters, sink, stream)          # warm-up
-        a, b = new_event(), new_event()
-        wn.wino_profile_next_launch(a.value, b.value)
-        work = wn.wino_probe_peak(kind, blocks, iters, sink, stream)
-        torch.cuda.synchronize()
-        ms = elapsed_ms(a, b)
-        hip.hipEventDestroy(a)
-        hip.hipEventDestroy(b)
-        return work / (ms * 1e-3) / 1e12
-    src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
-    dst = torch.empty_like(src)
-    dst.copy_(src)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(5):
-        dst.copy_(src)
-    e1.record()
-    torch.cuda.synchronize()
-    measured_peaks = {"int8_mfma_TOPs": probe(wn.PROBE_MFMA_I8, 256 * 16, 2048),
-                      "valu_mad24_Tops": probe(wn.PROBE_VALU_MAD24, 256 * 16, 2048),
-                      "bf16_mfma_TFLOPs": probe(wn.PROBE_MFMA_BF16, 256 * 16, 2048),
-                      "copy_GBps": 2 * src.numel() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9}
-    del src, dst
-    pts = {2: [0, 1, -1], 4: [0, 1, -1, 2, -2], 6: [0, 1, -1, 2, -2, (1, 2), (-1, 2)]}[wl.m]
-    from fractions import Fraction
-    mats = wn.wino_make_matrices(wl.m, 3, [Fraction(*p) if isinstance(p, tuple) else p
-                                           for p in pts], base)
-    model = stage_model(wl, M.element_size(), y.element_size(), mats)
-    traffic = MEASURED_TRAFFIC_BYTES.get(wl.name, {}) if reps == 1 else {}
-    stages = {}
-    for nm in names:
-        sec = stage_ms[nm] * 1e-3
-        st = {"ms": stage_ms[nm]}
-        if model[nm]["bound"] == "hbm":
-            hbm = model[nm]["work"] / sec / 1e9
-            alu = model[nm]["alu_ops"] / sec / 1e12
-            st.update({"hbm_GBps": hbm, "hbm_frac": hbm / HBM_PEAK_GBS,
-                       "alu_Tops": alu, "alu_frac": alu / VALU_PEAK_TOPS})
-            # the binding ceiling is the one whose ideal time is longer
-            if model[nm]["alu_ops"] / VALU_PEAK_TOPS / 1e12 > model[nm]["work"] / HBM_PEAK_GBS / 1e9:
-                st.update({"bound": "alu", "achieved": alu, "peak": VALU_PEAK_TOPS,
-                           "unit": "TOP/s", "frac": alu / VALU_PEAK_TOPS})
-            else:
-                st.update({"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS,
-                           "unit": "GB/s", "frac": hbm / HBM_PEAK_GBS})
-        else:
-            ach = model[nm]["work"] / sec / 1e12
-            st.update({"bound": "mfma", "achieved": ach, "peak": INT8_MFMA_PEAK_TOPS,
-                       "unit": "TOP/s", "frac": ach / INT8_MFMA_PEAK_TOPS})
-        own = {"alu": measured_peaks["valu_mad24_Tops"], "hbm": measured_peaks["copy_GBps"],
-               "mfma": measured_peaks["int8_mfma_TOPs"]}[st["bound"]]
-        st["frac_of_measured_peak"] = st["achieved"] / own
-        st["traffic"] = traffic.get(nm)
-        st["algorithmic_bytes"] = (model[nm]["work"] if model[nm]["bound"] == "hbm" else None)
-        stages[nm] = st
-    dominant = max(names, key=lambda nm: stage_ms[nm])
-    roofline = {k: stages[dominant][k] for k in ("bound", "achieved", "peak", "unit", "frac",
-                                                   "traffic")}
+    mode = wn.FUSED_AUTO if args.mode == "auto" else wn.FUSED_OFF
+    head = measure_layer(wn, si, torch, ev, dev, args.workload, args.batch_scale, args.steps,
+                         args.warmup, mode, peaks, copy_probe=args.copy_probe)
+    wl, desc, x, w, y, sc, L, mats = (head[k] for k in ("wl", "desc", "x", "w", "y", "sc", "L",
+                                                        "mats"))
+    reps = args.batch_scale
+    base = desc.base
+    n2, T = desc.n ** 2, desc.tiles
+    ops = head["ops"]
+    stages = head["stages"]
+    names = head["launches"]
+    dominant = max(names, key=lambda nm: stages[nm]["ms"])
+    roofline = {k: stages[dominant].get(k) for k in ("bound", "achieved", "peak", "unit", "frac",
+                                                     "traffic")}
     roofline["kernel"] = dominant
-    for k in ("hbm_GBps", "hbm_frac", "frac_of_measured_peak"):
+    for k in ("frac_of_measured_peak", "algorithmic_bytes", "algorithmic_ops", "hbm_GBps",
+              "hbm_frac", "alu_Tops", "alu_frac"):
         if k in stages[dominant]:
             roofline[k] = stages[dominant][k]
 
-    ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
-    ms_per_step = dt / args.steps * 1e3
     out = {
         "metric": "int8 Winograd conv TOPS (direct-equiv)",
-        "value": ops / (dt / args.steps) / 1e12,
+        "value": head["value"],
         "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
-        "config": {"workload": wl.name + ("" if reps == 1 else "_batchx%d" % reps),
+        "config": {"workload": head["workload"],
                    "N": wl.N, "H": wl.H, "W": wl.W, "C": wl.C, "K": wl.K,
                    "algorithm": "F(%dx%d,3x3) %s base" % (wl.m, wl.m, wl.base),
                    "bits_hadamard": wl.bits_hadamard, "output": "fp32",
-                   "step": "weight+input transforms (one launch), contraction, output transform"},
+                   "step": "wino_conv2d, filters untransformed, fused = %s: %s"
+                           % (args.mode.upper(), " + ".join(names))},
         "roofline": roofline,
         "stages": stages,
-        "measured_peaks": measured_peaks,
-        "cold_step_ms": cold_ms,
+        "stage_sum_ms": head["stage_sum_ms"],
+        "stage_sum_exceeds_step": head["stage_sum_exceeds_step"],
+        "timing": head["timing"],
+        "measured_peaks": peaks,
+        "cold_step_ms": head["cold_step_ms"],
     }
-    # extra: the single-kernel fused variant on the same workload (same step
-    # definition: filter transform + fused kernel), timed the same way
+
     def want(name, always=False):
         if args.only_extra is not None:
             return args.only_extra == name
         return always or not args.no_extras
 
-    if want("fused", always=True) and wl.m in (2, 4) and wl.bits_hadamard in (8, 9):
-        fdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
-                            bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=1)
-        fws = torch.empty(wn.wino_workspace_bytes(fdesc), dtype=torch.uint8, device=dev)
-        for _ in range(args.warmup):
-            wn.wino_conv2d(fdesc, x, w, y, sc, fws, stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            wn.wino_conv2d(fdesc, x, w, y, sc, fws, stream)
-        torch.cuda.synchronize()
-        fdt = (time.perf_counter() - t0) / args.steps
-        out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
-                                "unit": "TOPS",
-                                "note": "input transform recomputed per 64-channel k block"}
+    steps = args.steps
+    # extra: the same layer with one kernel per stage (a1 + a2 | a3 | a4): the contraction on
+    # its own against the int8 MFMA peak, each transform on its own against HBM
+    if want("split", always=True) and args.mode == "auto" and "contraction" not in names:
+        sp = measure_layer(wn, si, torch, ev, dev, args.workload, reps, steps, 0, wn.FUSED_OFF,
+                           peaks)
+        out["split_path"] = public(sp)
+        del sp
+    # extra: the same layer on 64 times the batch (x + U beyond twice the Infinity Cache), so
+    # that kernel efficiency and launch effects can be told apart
+    if want("batch64", always=True) and reps == 1:
+        big = measure_layer(wn, si, torch, ev, dev, args.workload, 64, max(5, steps // 10), 0,
+                            mode, peaks)
+        out["batch_x64"] = public(big)
+        del big
+        torch.cuda.empty_cache()
     # extra: the same layer with its filters transformed ahead of time (a1 is a per-layer,
-    # offline step in deployment): input transform, contraction, output transform
+    # offline step in deployment)
     if want("pretransformed"):
-        def vstep():
-            wn.wino_input_transform(desc, x, U, sc, stream)
-            wn.wino_contract(desc, U, V, M, sc, stream)
-            wn.wino_output_transform(desc, M, y, sc, stream)
-        for _ in range(args.warmup):
-            vstep()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            vstep()
-        torch.cuda.synchronize()
-        vdt = (time.perf_counter() - t0) / args.steps
+        V = torch.empty((n2, wl.K, wl.C), dtype=torch.int8, device=dev)
+        wn.wino_weight_transform(desc, w, V, sc, stream)
+        pdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                            bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=mode,
+                            weights_pretransformed=1)
+        pws = torch.empty(wn.wino_workspace_bytes(pdesc), dtype=torch.uint8, device=dev)
+        vdt = timed(torch, lambda: wn.wino_conv2d(pdesc, x, V, y, sc, pws, stream), steps)[0]
         out["pretransformed_weights"] = {"ms_per_step": vdt * 1e3, "value": ops / vdt / 1e12,
-                                         "unit": "TOPS",
-                                         "note": "a2 + a3 + a4 only; V computed once beforehand"}
+                                         "unit": "TOPS", "launches": wn.wino_conv2d_launches(pdesc),
+                                         "note": "V computed once beforehand"}
+        del V, pws
+    # extra: the single-kernel variant where it exists for this layer (C <= 64)
+    if want("fused") and wl.C <= 64 and wl.m in (2, 4) and wl.bits_hadamard in (8, 9):
+        fdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                            bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=wn.FUSED_ON)
+        fws = torch.empty(wn.wino_workspace_bytes(fdesc), dtype=torch.uint8, device=dev)
+        fdt = timed(torch, lambda: wn.wino_conv2d(fdesc, x, w, y, sc, fws, stream), steps)[0]
+        out["fused_variant"] = {"ms_per_step": fdt * 1e3, "value": ops / fdt / 1e12,
+                                "unit": "TOPS", "launches": wn.wino_conv2d_launches(fdesc)}
+        del fws
     # extra: the same layer with per-Winograd-point scales (U, V per point, M with
-    # power-of-two refinements), calibrated on the device, same three launches
-    if want("per_point"):
+    # power-of-two refinements), calibrated on the device
+    if want("per_point") and wl.bits_hadamard in (8, 9):
         cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
         psc = wn.wino_calibrate(desc, x, w, None, float(L["s_x"]), float(L["s_w"]), cws,
                                 per_point=True)
         del cws
-
-        def pstep():
-            wn.wino_transform_operands(desc, x, U, w, V, psc, stream)
-            wn.wino_contract(desc, U, V, M, psc, stream)
-            wn.wino_output_transform(desc, M, y, psc, stream)
-        for _ in range(args.warmup):
-            pstep()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            pstep()
-        torch.cuda.synchronize()
-        pdt = (time.perf_counter() - t0) / args.steps
+        pws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        pdt = timed(torch, lambda: wn.wino_conv2d(desc, x, w, y, psc, pws, stream), steps)[0]
         out["per_point_variant"] = {"ms_per_step": pdt * 1e3, "value": ops / pdt / 1e12,
                                     "unit": "TOPS", "m_shift_max": max(psc.m_shift[:n2]),
                                     "note": "per-point scales for U, V and M"}
+        del pws
     # extra: the flex layer (run-time fp32 G_P, B_P, A_P; here the static matrices rounded
     # to fp32, as at the start of training) on the same workload, whole-layer call
     if want("flex"):
@@ -477,48 +560,39 @@ def main():
         xsc = wn.wino_flex_calibrate(xdesc, fm, x, w, None, float(L["s_x"]), float(L["s_w"]), cws)
         del cws
         xws = torch.empty(wn.wino_workspace_bytes(xdesc), dtype=torch.uint8, device=dev)
-        for _ in range(args.warmup):
-            wn.wino_flex_conv2d(xdesc, fm, x, w, y, xsc, xws, stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            wn.wino_flex_conv2d(xdesc, fm, x, w, y, xsc, xws, stream)
-        torch.cuda.synchronize()
-        xdt = (time.perf_counter() - t0) / args.steps
+        xdt = timed(torch, lambda: wn.wino_flex_conv2d(xdesc, fm, x, w, y, xsc, xws, stream),
+                    steps)[0]
         out["flex_variant"] = {"ms_per_step": xdt * 1e3, "value": ops / xdt / 1e12,
                                "unit": "TOPS",
                                "note": "fp32 brackets with run-time matrices, three launches"}
         del xws
     # extra: backward pass of the same layer (gradients w.r.t. input and weights from a
-    # synthetic output gradient, U and V as the forward pass left them), fp32; each of its
-    # three launches timed by its own event pair
+    # synthetic output gradient, U and V of the forward pass), fp32; each of its launches
+    # timed by its own event pair
     if want("backward") and reps == 1:
+        sdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
+                            bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32)
+        mdt = {8: torch.int8, 9: torch.int16, 32: torch.int32}[wl.bits_hadamard]
+        V = torch.empty((n2, wl.K, wl.C), dtype=torch.int8, device=dev)
+        U = torch.empty((n2, T, wl.C), dtype=torch.int8, device=dev)
+        M = torch.empty((n2, T, wl.K), dtype=mdt, device=dev)
+        wn.wino_transform_operands(sdesc, x, U, w, V, sc, stream)
+        wn.wino_contract(sdesc, U, V, M, sc, stream)
         # up to 8 partial sums of dV are added by the kernel that reads dV; more cost a launch of their own
-        parts = wn.wino_backward_dv_parts(desc)
+        parts = wn.wino_backward_dv_parts(sdesc)
         extra_launch = ("sum_dV_parts",) if parts > 8 else ()
         bnames = ("dY_to_dM", "gemm_dV_and_dU") + extra_launch + ("dU_to_dx_and_dV_to_dw",)
         g = torch.Generator(device="cpu").manual_seed(wl.seed + 1)
         dy = torch.randn((wl.N, wl.H, wl.W, wl.K), generator=g, dtype=torch.float32).to(dev)
         dx = torch.empty((wl.N, wl.H, wl.W, wl.C), dtype=torch.float32, device=dev)
         dw = torch.empty((wl.K, wl.C, 3, 3), dtype=torch.float32, device=dev)
-        bws = torch.empty(wn.wino_backward_workspace_bytes(desc), dtype=torch.uint8, device=dev)
-        for _ in range(args.warmup):
-            wn.wino_backward(desc, dy, U, V, sc, dx, dw, bws, stream)
-        torch.cuda.synchronize()
-        bsteps = max(10, args.steps // 10)
-        bev = [(new_event(), new_event()) for _ in bnames]
-        t0 = time.perf_counter()
-        for i in range(bsteps):
-            if i == bsteps - 1:
-                for a, b in bev:
-                    wn.wino_profile_next_launch(a.value, b.value)
-            wn.wino_backward(desc, dy, U, V, sc, dx, dw, bws, stream)
-        torch.cuda.synchronize()
-        bdt = (time.perf_counter() - t0) / bsteps
-        kus = {nm: elapsed_ms(a, b) * 1e3 for nm, (a, b) in zip(bnames, bev)}
-        for a, b in bev:
-            hip.hipEventDestroy(a)
-            hip.hipEventDestroy(b)
+        bws = torch.empty(wn.wino_backward_workspace_bytes(sdesc), dtype=torch.uint8, device=dev)
+
+        def bstep():
+            wn.wino_backward(sdesc, dy, U, V, sc, dx, dw, bws, stream)
+        bdt = timed(torch, bstep, steps, min_launches=100)[0]
+        bmed = sample_launches(wn, torch, ev, bstep, len(bnames), samples=16, gap=1)
+        kus = {nm: v * 1e3 for nm, v in zip(bnames, bmed)}
         # Both contractions: 2*n^2*T*C*K fp32-equivalent flops each, run as three bf16 MFMAs per
         # product (dM cut into three exact bf16 pieces), so the matrix pipe issues three times
         # that; algorithmic bytes: dM read by both, U and V, dU and the parts of dV written.
@@ -533,7 +607,7 @@ def main():
                          "frac": gemm_bytes / gemm_s / 8e12, "traffic": None,
                          "algorithmic_bytes": gemm_bytes,
                          "bf16_mfma_issued_TFLOPs": issued_tf, "bf16_mfma_frac": issued_tf / 2500.0,
-                         "bf16_mfma_frac_of_measured_peak": issued_tf / measured_peaks["bf16_mfma_TFLOPs"],
+                         "bf16_mfma_frac_of_measured_peak": issued_tf / peaks["bf16_mfma_TFLOPs"],
                          "fp32_equivalent_TFLOPs": gemm_flops / gemm_s / 1e12,
                          "fp32_mfma_peak_TFLOPs": 157.3},
             "note": "straight-through gradients; the two contraction gradients are GEMMs of fp32 dM with "
@@ -549,36 +623,25 @@ def main():
         dGP = torch.empty((nn, 3), dtype=torch.float32, device=dev)
         dBPT = torch.empty((nn, nn), dtype=torch.float32, device=dev)
         dAPT = torch.empty((wl.m, nn), dtype=torch.float32, device=dev)
-        fws = torch.empty(wn.wino_flex_backward_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+        fws = torch.empty(wn.wino_flex_backward_workspace_bytes(sdesc), dtype=torch.uint8, device=dev)
 
         def fstep():
-            wn.wino_flex_backward(desc, bfm, dy, x, w, U, V, M, sc, dx, dw, dGP, dBPT, dAPT, fws,
+            wn.wino_flex_backward(sdesc, bfm, dy, x, w, U, V, M, sc, dx, dw, dGP, dBPT, dAPT, fws,
                                   stream)
-        for _ in range(args.warmup):
-            fstep()
+        fdt = timed(torch, fstep, steps, min_launches=100)[0]
+        fmed = sample_launches(wn, torch, ev, fstep, len(fnames), samples=16, gap=1)
         torch.cuda.synchronize()
-        fev = [(new_event(), new_event()) for _ in fnames]
-        t0 = time.perf_counter()
-        for i in range(bsteps):
-            if i == bsteps - 1:
-                for a, b in fev:
-                    wn.wino_profile_next_launch(a.value, b.value)
-            fstep()
-        torch.cuda.synchronize()
-        fdt = (time.perf_counter() - t0) / bsteps
         out["flex_backward_variant"] = {
             "ms_per_step": fdt * 1e3, "dtype": "f32",
-            "kernel_us": {nm: elapsed_ms(a, b) * 1e3 for nm, (a, b) in zip(fnames, fev)},
+            "kernel_us": {nm: v * 1e3 for nm, v in zip(fnames, fmed)},
             "note": "dx, dw and the gradients of the three trained matrices"}
-        for a, b in fev:
-            hip.hipEventDestroy(a)
-            hip.hipEventDestroy(b)
-        del dy, dx, dw, bws, fws
-    # extra: whole-layer call (wino_conv2d) on the other single-layer configurations, split
-    # path and AUTO (which takes the fused kernel where C, K <= 64); not the headline figure
+        del dy, dx, dw, bws, fws, U, V, M
+    # extra: whole-layer call (wino_conv2d) on the other single-layer configurations, one
+    # kernel per stage and the library's own choice; not the headline figure
     if want("others") and reps == 1:
         out["other_workloads"] = {}
-        for name in ("cfg2_f4_c64", "cfg3_f4_c128_h9", "cfg4b_f4_c512"):
+        for name in ("cfg2_f4_c64", "cfg3_f4_c128_h9", "cfg4b_f4_c512", "cfg4a_f6_c256",
+                     "cfg4b_f6_c512"):
             if name == wl.name:
                 continue
             out["other_workloads"][name] = layer_times(wn, si, torch, dev, name, 50)

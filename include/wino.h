@@ -106,10 +106,17 @@ typedef struct {
   int relu;                   /* clamp the output at zero                         */
   int weights_pretransformed; /* wino_conv2d: second pointer is V, not w          */
   int fused;                  /* wino_conv2d: WINO_FUSED_*: OFF = one kernel per
-                                 stage; ON = single-kernel variant (U, M stay on
-                                 chip; m = 2 or 4, bits_hadamard 8 or 9, fp32 or
-                                 int8 output); AUTO = ON where it is the faster
-                                 one (C <= 64 and K <= 64), else OFF               */
+                                 stage (V, U, M all in the workspace).  ON = the
+                                 contraction result M never leaves the chip: one
+                                 kernel for the whole layer where C <= 64 and
+                                 m = 2 or 4 (U stays on chip too), otherwise the
+                                 input transform followed by ONE kernel for
+                                 contraction + output transform (U in the
+                                 workspace); needs bits_hadamard 8 or 9 and fp32
+                                 or int8 output.  AUTO = the fastest of the three
+                                 for the shape: the single kernel for C, K <= 64,
+                                 the two-kernel form for every other layer ON
+                                 covers, one kernel per stage for the rest        */
 } wino_conv_desc_t;
 
 /* Symmetric scales, supplied by the caller (or chosen by wino_calibrate).
@@ -137,8 +144,9 @@ typedef struct {
   int m_shift[64];
 } wino_scales_t;
 
-/* Bytes of device workspace wino_conv2d needs for this descriptor (V unless
- * pretransformed, U and M; each 256-byte aligned). */
+/* Bytes of device workspace wino_conv2d needs for this descriptor: V unless
+ * pretransformed, U unless the single-kernel variant runs, M only when one
+ * kernel runs per stage; each region 256-byte aligned, in this order. */
 int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 
 /* Eq. 3 (canonical) / eq. 4 (Legendre) for a whole layer, with a symmetric
@@ -171,6 +179,13 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
 /* Output bracket of eq. 3 / eq. 4: M -> y. */
 int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
                           const wino_scales_t* s, void* hip_stream);
+/* The Hadamard stage and the output bracket of eq. 3 / eq. 4 in ONE kernel:
+ * U, V -> y with the same arithmetic and the same casts as wino_contract
+ * followed by wino_output_transform (results are bit-identical), the cast
+ * contraction result being kept in on-chip memory instead of a tensor M.
+ * Needs bits_hadamard 8 or 9 and out_type F32 or I8 (EUNSUPPORTED otherwise). */
+int wino_contract_output(const wino_conv_desc_t* d, const void* U, const void* V, void* y,
+                         const wino_scales_t* s, void* hip_stream);
 
 /* Chooses the scales of a layer on the device, from the tensors it is given
  * (dynamic quantisation; Section 4.2 casts every stage, the paper leaves the
@@ -306,6 +321,25 @@ int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
                        const void* x, const void* w, const void* U, const void* V, const void* M,
                        const wino_scales_t* s, void* dx, void* dw, const wino_flex_grads_t* grads,
                        void* workspace, size_t ws_bytes, void* hip_stream);
+
+/* Measurement helper: the kernel launches wino_conv2d makes for this descriptor,
+ * in order, as a comma-separated list written to the host buffer `buf`
+ * (NUL-terminated; 128 bytes are always enough).  Names: weight_transform,
+ * input_transform, operand_transforms (both in one launch), contraction,
+ * output_transform, contraction_output, fused_layer. */
+int wino_conv2d_launches(const wino_conv_desc_t* d, char* buf, size_t buf_bytes);
+
+/* Tuning options, process-wide, for measurements and tests; the defaults are
+ * what the library ships with.
+ *   WINO_OPT_CONOUT_SHAPE  work-group block of the contraction + output kernel:
+ *                          0 = chosen from the problem size (default), 1 = small
+ *                          blocks (16 tiles x 32 channels), 2 = large blocks
+ *   WINO_OPT_AUTO_CONOUT   1 (default): WINO_FUSED_AUTO may pick the two-kernel
+ *                          form; 0: it picks between the single kernel and one
+ *                          kernel per stage only
+ * Errors: EINVAL (unknown option, value out of range). */
+enum { WINO_OPT_CONOUT_SHAPE = 0, WINO_OPT_AUTO_CONOUT = 1 };
+int wino_set_option(int option, int value);
 
 /* Measurement hook.  The next kernel that the calling thread launches through
  * this library records its own begin into `start_event` and its own end into

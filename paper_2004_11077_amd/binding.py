@@ -13,7 +13,8 @@ EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_
            "wino_workspace_bytes", "wino_calibrate_workspace_bytes", "wino_calibrate",
            "wino_conv2d", "wino_weight_transform",
            "wino_input_transform", "wino_transform_operands", "wino_contract",
-           "wino_output_transform", "wino_flex_weight_transform", "wino_flex_input_transform",
+           "wino_output_transform", "wino_contract_output", "wino_conv2d_launches",
+           "wino_set_option", "wino_flex_weight_transform", "wino_flex_input_transform",
            "wino_flex_output_transform", "wino_flex_conv2d", "wino_flex_calibrate",
            "wino_backward_workspace_bytes", "wino_backward_dv_parts", "wino_backward",
            "wino_flex_backward_workspace_bytes", "wino_flex_backward",
@@ -147,6 +148,9 @@ def _load():
     lib.wino_transform_operands.argtypes = [dp, vp, vp, vp, vp, sp, vp]
     lib.wino_contract.argtypes = [dp, vp, vp, vp, sp, vp]
     lib.wino_output_transform.argtypes = [dp, vp, vp, sp, vp]
+    lib.wino_contract_output.argtypes = [dp, vp, vp, vp, sp, vp]
+    lib.wino_conv2d_launches.argtypes = [dp, C.c_char_p, C.c_size_t]
+    lib.wino_set_option.argtypes = [C.c_int, C.c_int]
     fp = C.POINTER(FlexMatrices)
     lib.wino_flex_weight_transform.argtypes = [dp, fp, vp, vp, sp, vp]
     lib.wino_flex_input_transform.argtypes = [dp, fp, vp, vp, sp, vp]
@@ -345,6 +349,27 @@ def wino_output_transform(desc, M, y, scales, stream=None):
     _check(_load().wino_output_transform(C.byref(desc), _ptr(M), _ptr(y), C.byref(sc),
                                          _stream(stream)))
     return y
+
+
+def wino_contract_output(desc, U, V, y, scales, stream=None):
+    sc = _scales(scales)
+    _check(_load().wino_contract_output(C.byref(desc), _ptr(U), _ptr(V), _ptr(y), C.byref(sc),
+                                        _stream(stream)))
+    return y
+
+
+OPT_CONOUT_SHAPE, OPT_AUTO_CONOUT = 0, 1
+
+
+def wino_set_option(option, value):
+    _check(_load().wino_set_option(option, value))
+
+
+def wino_conv2d_launches(desc):
+    """Names of the kernel launches wino_conv2d makes for this descriptor, in order."""
+    buf = C.create_string_buffer(128)
+    _check(_load().wino_conv2d_launches(C.byref(desc), buf, 128))
+    return [nm for nm in buf.value.decode().split(",") if nm]
 
 
 def wino_flex_weight_transform(desc, fm, w, V, scales, stream=None):

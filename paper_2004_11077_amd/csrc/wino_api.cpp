@@ -262,11 +262,106 @@ int output_mults(const Plan& p, const wino_conv_desc_t* d, const wino_scales_t* 
   return WINO_OK;
 }
 
+// Which kernels wino_conv2d runs for a descriptor.
+enum Path {
+  kPathSplit,      // one kernel per stage: (operand transforms,) contraction, output transform
+  kPathFusedAll,   // input transform + contraction + output transform in one kernel
+  kPathConOut      // input transform, then contraction + output transform in one kernel
+};
+
+// Tuning options (wino_set_option), process-wide.
+int g_opt_co_shape = 0;      // block shape of the contraction + output kernel: 0 auto, 1 small, 2 large
+int g_opt_auto_conout = 1;   // AUTO may take the contraction + output kernel
+
+// The variants that keep M on chip cover the int8 path with a cast Hadamard stage and fp32 or
+// int8 output; the single-kernel variant additionally needs m = 2 or 4.  C = 0 (an empty
+// channel sum, y = 0) always runs stage by stage.
+bool conout_covers(const wino_conv_desc_t* d, const Plan& p) {
+  return !(p.fp32 || p.m_bits == 32 || d->out_type == WINO_OUT_I32 || d->C == 0);
+}
+bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
+  return conout_covers(d, p) && d->m != 6;
+}
+
+// ON: M never leaves the chip.  The single kernel where the layer has one 64-channel chunk
+// (its input transform is recomputed per 64 output channels and it keeps no accumulators
+// across chunks), the two-kernel form otherwise.  AUTO: whichever form is the fastest for the
+// shape: the single kernel for C, K <= 64, the two-kernel form for every other covered layer.
+int select_path(const wino_conv_desc_t* d, const Plan& p, Path* path) {
+  *path = kPathSplit;
+  if (d->fused != WINO_FUSED_OFF && d->fused != WINO_FUSED_ON && d->fused != WINO_FUSED_AUTO)
+    return fail(WINO_EINVAL, "unknown fused mode %d", d->fused);
+  if (d->fused == WINO_FUSED_OFF || d->C == 0) return WINO_OK;
+  if (d->fused == WINO_FUSED_ON) {
+    if (!conout_covers(d, p))
+      return fail(WINO_EUNSUPPORTED, "the fused variants cover the int8 path with bits_hadamard "
+                                     "8 or 9 and fp32 or int8 output");
+    *path = (fused_all_covers(d, p) && d->C <= 64) ? kPathFusedAll : kPathConOut;
+    return WINO_OK;
+  }
+  if (fused_all_covers(d, p) && d->C <= 64 && d->K <= 64)
+    *path = kPathFusedAll;
+  else if (conout_covers(d, p) && g_opt_auto_conout)
+    *path = kPathConOut;
+  return WINO_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
 const char* wino_last_error(void) { return g_err.c_str(); }
+
+int wino_set_option(int option, int value) {
+  switch (option) {
+    case WINO_OPT_CONOUT_SHAPE:
+      if (value < 0 || value > 2) return fail(WINO_EINVAL, "block shape must be 0, 1 or 2");
+      g_opt_co_shape = value;
+      return WINO_OK;
+    case WINO_OPT_AUTO_CONOUT:
+      g_opt_auto_conout = value != 0;
+      return WINO_OK;
+  }
+  return fail(WINO_EINVAL, "unknown option %d", option);
+}
+
+int wino_conv2d_launches(const wino_conv_desc_t* d, char* buf, size_t buf_bytes) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (!buf || buf_bytes == 0) return fail(WINO_EINVAL, "null buffer");
+  Path path;
+  if (int rc = select_path(d, p, &path)) return rc;
+  std::string names;
+  auto add = [&](const char* nm) { names += names.empty() ? "" : ","; names += nm; };
+  if (p.g.T != 0 && p.g.K != 0) {
+    const bool w = !d->weights_pretransformed && (long)p.g.K * p.g.C != 0;
+    const bool x = (long)p.g.T * p.g.C != 0;
+    if (path == kPathFusedAll) {
+      if (w) add("weight_transform");
+      add("fused_layer");
+    } else {
+      if (p.fp32) {
+        if (w) add("weight_transform");
+        if (x) add("input_transform");
+      } else if (w && x) {
+        add("operand_transforms");
+      } else if (w) {
+        add("weight_transform");
+      } else if (x) {
+        add("input_transform");
+      }
+      if (path == kPathConOut) {
+        add("contraction_output");
+      } else {
+        add("contraction");
+        add("output_transform");
+      }
+    }
+  }
+  if (names.size() + 1 > buf_bytes) return fail(WINO_EINVAL, "buffer too small");
+  std::memcpy(buf, names.c_str(), names.size() + 1);
+  return WINO_OK;
+}
 
 int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   Plan p;
@@ -449,12 +544,13 @@ int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   const size_t eb = p.fp32 ? 4 : 1;
+  Path path;
+  if (int rc = select_path(d, p, &path)) return rc;
   size_t total = 0;
   if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C * eb);
-  if (d->fused != WINO_FUSED_ON) {   // the fused variant keeps U and M on chip (AUTO may pick either)
-    total += round256(n2 * p.g.T * d->C * eb);
-    total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
-  }
+  // U unless the single kernel runs, M only when one kernel runs per stage
+  if (path != kPathFusedAll) total += round256(n2 * p.g.T * d->C * eb);
+  if (path == kPathSplit) total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
   if (total == 0) total = 256;
   *bytes = total;
   return WINO_OK;
@@ -539,8 +635,10 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
   if ((long)p.g.T * p.g.K == 0) return WINO_OK;   // empty problem: nothing to launch, pointers may be null
-  if (int rc = need(U, "U")) return rc;
-  if (int rc = need(V, "V")) return rc;
+  if (p.g.C != 0) {                               // C = 0: U and V are empty and are not read
+    if (int rc = need(U, "U")) return rc;
+    if (int rc = need(V, "V")) return rc;
+  }
   if (int rc = need(M, "M")) return rc;
   if (p.fp32) {
     hipError_t e = launch_stage_f32(2, p.g, p.legendre, (const float*)U, (const float*)V,
@@ -583,6 +681,37 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
                                          d->relu != 0, mu, s->per_point ? &sh : nullptr,
                                          (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "output transform launch");
+}
+
+int wino_contract_output(const wino_conv_desc_t* d, const void* U, const void* V, void* y,
+                         const wino_scales_t* s, void* hip_stream) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if ((long)p.g.T * p.g.K == 0) return WINO_OK;   // no output element exists
+  if (p.fp32 || p.m_bits == 32 || d->out_type == WINO_OUT_I32)
+    return fail(WINO_EUNSUPPORTED, "contraction + output transform in one kernel covers the int8 "
+                                   "path with bits_hadamard 8 or 9 and fp32 or int8 output");
+  if (p.g.C != 0) {                               // C = 0: U and V are empty and are not read
+    if (int rc = need(U, "U")) return rc;
+    if (int rc = need(V, "V")) return rc;
+  }
+  if (int rc = need(y, "y")) return rc;
+  if (int rc = need(s, "scales")) return rc;
+  if (int rc = aligned(U, 16, "U")) return rc;
+  if (int rc = aligned(V, 16, "V")) return rc;
+  if (int rc = aligned(y, 16, "y")) return rc;
+  if (int rc = check_per_point(d, s)) return rc;
+  MultTable mm;
+  ShiftTable sh;
+  double s_m;
+  StageMults mu;
+  if (int rc = contract_mults(p, s, &mm, &sh, &s_m)) return rc;
+  if (int rc = output_mults(p, d, s, &mu, nullptr)) return rc;
+  hipError_t e = launch_contract_output(p.g, p.two_brackets, (const int8_t*)U, (const int8_t*)V, y,
+                                        p.m_bits, d->out_type, d->relu != 0, mu, mm,
+                                        s->per_point ? &sh : nullptr, g_opt_co_shape,
+                                        (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "contraction + output launch");
 }
 
 namespace {
@@ -801,20 +930,13 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   if (int rc = make_plan(d, &p)) return rc;
   if (p.g.T == 0 || p.g.K == 0) return WINO_OK;   // no output element exists
   if (int rc = check_per_point(d, s)) return rc;
-  const bool fusable = !(p.fp32 || d->m == 6 || p.m_bits == 32 || d->out_type == WINO_OUT_I32);
-  if (d->fused == WINO_FUSED_ON && !fusable)
-    return fail(WINO_EUNSUPPORTED, "the fused variant covers the int8 path with m = 2 or 4, "
-                                   "bits_hadamard 8 or 9 and fp32 or int8 output");
-  if (d->fused != WINO_FUSED_OFF && d->fused != WINO_FUSED_ON && d->fused != WINO_FUSED_AUTO)
-    return fail(WINO_EINVAL, "unknown fused mode %d", d->fused);
-  // AUTO: the fused kernel recomputes the input transform once per 64 output
-  // channels and keeps no accumulators when C <= 64; it wins exactly there.
+  Path path;
+  if (int rc = select_path(d, p, &path)) return rc;
+  size_t want = 0;
+  if (int rc = wino_workspace_bytes(d, &want)) return rc;
   wino_conv_desc_t dsel = *d;
-  dsel.fused = d->fused == WINO_FUSED_ON || (d->fused == WINO_FUSED_AUTO && fusable &&
-                                             d->C <= 64 && d->K <= 64);
-  const size_t ws_want_caller = [&] { size_t b = 0; wino_workspace_bytes(d, &b); return b; }();
+  dsel.fused = path == kPathFusedAll;
   d = &dsel;
-  const size_t want = ws_want_caller;   // what wino_workspace_bytes told the caller
   if (int rc = need(workspace, "workspace")) return rc;
   if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
   if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
@@ -856,6 +978,7 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   } else {
     if (int rc = wino_input_transform(d, x, U, s, hip_stream)) return rc;
   }
+  if (path == kPathConOut) return wino_contract_output(d, U, V, y, s, hip_stream);
   if (int rc = wino_contract(d, U, V, M, s, hip_stream)) return rc;
   return wino_output_transform(d, M, y, s, hip_stream);
 }

@@ -3,7 +3,9 @@
 // U [n*n][T][C], V [n*n][K][C], M [n*n][T][K], y NHWC).  It exists as the
 // unquantised reference of the library (checked against fp64 to 1e-4); it is
 // not tuned: one lane per item in the transforms, one lane per output in the
-// contraction.
+// contraction.  Tensors and the contraction are fp32; a Legendre bracket pair
+// is evaluated in double between its fp32 input and its fp32 result (see
+// bracket_d).
 #include "wino_kernels.hpp"
 #include "wino_real_brackets.hpp"
 
@@ -23,9 +25,9 @@ __global__ __launch_bounds__(256) void k_weight_f32(const float* __restrict__ w,
   });
   float v[n][n];
   if constexpr (LEG) {
-    float w1[n][n];
-    bracket_f<TB::GP>(wi, w1);       // G_P W G_P^T
-    bracket_f<TB::Pinv>(w1, v);      // P^{-1} ( . ) P^{-T}
+    double w1[n][n];
+    bracket_d<TB::GP>(wi, w1);       // G_P W G_P^T
+    bracket_d<TB::Pinv>(w1, v);      // P^{-1} ( . ) P^{-T}
   } else {
     bracket_f<TB::G>(wi, v);
   }
@@ -62,9 +64,9 @@ __global__ __launch_bounds__(256) void k_input_f32(const float* __restrict__ x,
   });
   float u[n][n];
   if constexpr (LEG) {
-    float x1[n][n];
-    bracket_f<TB::PinvT>(xi, x1);    // P^{-T} X P^{-1}
-    bracket_f<TB::BPT>(x1, u);       // B_P^T ( . ) B_P
+    double x1[n][n];
+    bracket_d<TB::PinvT>(xi, x1);    // P^{-T} X P^{-1}
+    bracket_d<TB::BPT>(x1, u);       // B_P^T ( . ) B_P
   } else {
     bracket_f<TB::BT>(xi, u);
   }
@@ -121,9 +123,9 @@ __global__ __launch_bounds__(256) void k_output_f32(const float* __restrict__ Mq
   });
   float out[M][M];
   if constexpr (LEG) {
-    float m1[n][n];
-    bracket_f<TB::PinvT>(mi, m1);    // P^{-T} M P^{-1}
-    bracket_f<TB::APT>(m1, out);     // A_P^T ( . ) A_P
+    double m1[n][n];
+    bracket_d<TB::PinvT>(mi, m1);    // P^{-T} M P^{-1}
+    bracket_d<TB::APT>(m1, out);     // A_P^T ( . ) A_P
   } else {
     bracket_f<TB::AT>(mi, out);
   }

@@ -18,8 +18,9 @@
 // transform of (tile, k) items and stores y.
 //
 // The input transform is recomputed by each of the K / KB work groups that
-// share a tile block, so the variant pays off for K <= 64 (one k block); for
-// wide layers the split path is the faster one.
+// share a tile block, so the variant pays off for K <= 64 (one k block).  It is
+// launched for layers with one channel chunk (C <= 64) only; wider layers keep
+// M on chip with the two-kernel form of wino_conout.hpp instead.
 #include "wino_transforms.hpp"
 
 namespace wino {
@@ -259,18 +260,15 @@ static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, 
   const int tblocks = (g.T + kFT - 1) / kFT, kblocks = (g.K + KB - 1) / KB;
   dim3 grid((unsigned)(tblocks * kblocks));
   const int r = relu ? 1 : 0;
-  const bool single = g.C <= kFC;
-  if (out_type == 0 && single)
+  // Only the single-chunk build is launched: wider layers take the two-kernel form
+  // (input transform, then contraction + output transform), which does not recompute the
+  // input transform per block of output channels and holds no accumulators across chunks.
+  if (g.C > kFC) return hipErrorInvalidValue;
+  if (out_type == 0)
     wino_launch((k_fused<M, LEG, MT, 0, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
                        out_mu, mm, sh, r, tblocks);
-  else if (out_type == 0)
-    wino_launch((k_fused<M, LEG, MT, 0, false, PP>), grid, dim3(256), st, x, V, y, g, in_mu,
-                       out_mu, mm, sh, r, tblocks);
-  else if (single)
-    wino_launch((k_fused<M, LEG, MT, 2, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
-                       out_mu, mm, sh, r, tblocks);
   else
-    wino_launch((k_fused<M, LEG, MT, 2, false, PP>), grid, dim3(256), st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 2, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
                        out_mu, mm, sh, r, tblocks);
   return hipGetLastError();
 }

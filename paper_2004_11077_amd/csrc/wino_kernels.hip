@@ -462,9 +462,46 @@ static hipError_t contract_tt(const Geometry& g, const int8_t* U, const int8_t* 
   return hipGetLastError();
 }
 
+// Zero fill in 16-byte stores (a kernel, not hipMemsetAsync, so that a caller may
+// capture the launch in a HIP graph).
+__global__ __launch_bounds__(256) void k_fill_zero16(v4i* __restrict__ dst, long count16) {
+  for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < count16; i += (long)gridDim.x * 256)
+    dst[i] = v4i{0, 0, 0, 0};
+}
+
+hipError_t launch_fill_zero(void* dst, long bytes, hipStream_t st) {
+  const long count16 = bytes / 16;
+  if (count16 == 0) return hipSuccess;
+  long nb = (count16 + 255) / 256;
+  if (nb > 4096) nb = 4096;
+  wino_launch(k_fill_zero16, dim3((unsigned)nb), dim3(256), st, (v4i*)dst, count16);
+  return hipGetLastError();
+}
+
+hipError_t launch_contract_output(const Geometry& g, bool leg, const int8_t* U, const int8_t* V,
+                                  void* y, int m_bits, int out_type, bool relu,
+                                  const StageMults& out_mu, const MultTable& mm,
+                                  const ShiftTable* sh, int shape, hipStream_t st) {
+  if ((long)g.T * g.K == 0) return hipSuccess;
+  if (g.C == 0)   // an empty channel sum: y = 0 (K is a multiple of 16, so the size is one of 16 bytes)
+    return launch_fill_zero(y, (long)g.N * g.H * g.W * g.K * (out_type == 0 ? 4 : 1), st);
+  switch (g.m) {
+    case 2: return PerMCO<2>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, shape, st);
+    case 4: return PerMCO<4>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, shape, st);
+    case 6: return PerMCO<6>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, shape, st);
+  }
+  return hipErrorInvalidValue;
+}
+
 hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,
                            int m_bits, const MultTable& mult, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
+  if (g.C == 0) {
+    // An empty channel sum: every M is the zero code.  k_contract is not launched (its
+    // staging loads assume at least one 16-byte channel segment per row).
+    const int n0 = g.m + 2;   // K is a multiple of 16, so the byte count is one of 16
+    return launch_fill_zero(Mo, (long)n0 * n0 * g.T * g.K * (m_bits == 8 ? 1 : m_bits == 9 ? 2 : 4), st);
+  }
   // Fewer than two 128-row tiles per compute unit: halve the tile, so that twice as many,
   // shorter, work groups share each compute unit (measured: 7 % on a 4x4 x 512-channel
   // layer with 256 tiles; no gain from about two tiles per compute unit on).

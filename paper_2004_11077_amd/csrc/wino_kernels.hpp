@@ -167,6 +167,25 @@ hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const
                                    int m_bits, void* y, int out_type, bool relu,
                                    const StageMults& mu, const ShiftTable* sh, hipStream_t st);
 
+// Contraction and output transform in one kernel, M kept in LDS (wino_conout.hpp);
+// m_bits 8 or 9, out_type 0 or 2, C > 0.  shape: 0 = block shape chosen from the problem
+// size, 1 = small blocks, 2 = large blocks.
+template <int M>
+struct PerMCO {
+  static hipError_t run(const Geometry& g, bool legendre_inner, const int8_t* U, const int8_t* V,
+                        void* y, int m_bits, int out_type, bool relu, const StageMults& out_mu,
+                        const MultTable& mm, const ShiftTable* sh, int shape, hipStream_t st);
+};
+extern template struct PerMCO<2>;
+extern template struct PerMCO<4>;
+extern template struct PerMCO<6>;
+hipError_t launch_contract_output(const Geometry& g, bool legendre_inner, const int8_t* U,
+                                  const int8_t* V, void* y, int m_bits, int out_type, bool relu,
+                                  const StageMults& out_mu, const MultTable& mm,
+                                  const ShiftTable* sh, int shape, hipStream_t st);
+// Zero fill of `bytes` (a multiple of 16) at a 16-byte aligned device address, by a kernel.
+hipError_t launch_fill_zero(void* dst, long bytes, hipStream_t st);
+
 // Fused variant (input transform + contraction + output transform in one kernel);
 // V is the transformed filter tensor.  m = 2 or 4, m_bits 8 or 9, out_type 0 or 2.
 // mm: cast multiplier of the contraction per point; sh: per-point shifts or null.

@@ -28,6 +28,9 @@ struct TabF {
 template <const RMat& T, int I, int J>
 inline constexpr float kCoef = (float)((double)T.a[I][J].num / (double)T.a[I][J].den);
 
+template <const RMat& T, int I, int J>
+inline constexpr double kCoefD = (double)T.a[I][J].num / (double)T.a[I][J].den;
+
 // out = T x T^T  (x: T.cols x T.cols, out: T.rows x T.rows).
 template <const RMat& T>
 __device__ __forceinline__ void bracket_f(const float (&x)[T.cols][T.cols],
@@ -51,6 +54,38 @@ __device__ __forceinline__ void bracket_f(const float (&x)[T.cols][T.cols],
         if constexpr (T.a[J][Bc].num != 0) acc = __builtin_fmaf(kCoef<T, J, Bc>, tmp[i][b], acc);
       });
       out[i][j] = acc;
+    });
+  });
+}
+
+// The same bracket evaluated in double (coefficients rounded to double).  The
+// two brackets of eq. 2 / eq. 4 multiply out to the canonical matrix, but each
+// on its own has large entries of mixed sign (row sums of |B_P^T| near 100 for
+// F(6,3)), so a bracket pair chained in fp32 loses the digits that cancel; the
+// fp32 path therefore keeps the value between the two brackets, and their
+// arithmetic, in double and rounds to fp32 only what it stores.
+template <const RMat& T, typename In, typename Out>
+__device__ __forceinline__ void bracket_d(const In (&x)[T.cols][T.cols],
+                                          Out (&out)[T.rows][T.rows]) {
+  double tmp[T.rows][T.cols];
+  rfor<0, T.rows>([&](auto i) {
+    rfor<0, T.cols>([&](auto b) {
+      double acc = 0.0;
+      rfor<0, T.cols>([&](auto a) {
+        constexpr int I = decltype(i)::value, A = decltype(a)::value;
+        if constexpr (T.a[I][A].num != 0) acc = __builtin_fma(kCoefD<T, I, A>, (double)x[a][b], acc);
+      });
+      tmp[i][b] = acc;
+    });
+  });
+  rfor<0, T.rows>([&](auto i) {
+    rfor<0, T.rows>([&](auto j) {
+      double acc = 0.0;
+      rfor<0, T.cols>([&](auto b) {
+        constexpr int J = decltype(j)::value, Bc = decltype(b)::value;
+        if constexpr (T.a[J][Bc].num != 0) acc = __builtin_fma(kCoefD<T, J, Bc>, tmp[i][b], acc);
+      });
+      out[i][j] = (Out)acc;
     });
   });
 }

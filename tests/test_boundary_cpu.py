@@ -128,8 +128,46 @@ def test_stage_calls_reject_bad_arguments_before_any_launch():
     assert lib.wino_contract(C.byref(d), C.c_void_p(4100), fake, fake, C.byref(s), None) == -1
     assert b"aligned" in lib.wino_last_error()
     assert lib.wino_conv2d(C.byref(d), fake, fake, fake, C.byref(s), fake, 16, None) == -4
-    dfused = wn.ConvDesc(1, 8, 8, 16, 16, m=6, fused=1)     # the fused variant has no F(6,3)
+    dfused = wn.ConvDesc(1, 8, 8, 16, 16, bits_hadamard=32, fused=1)   # M on chip needs a cast M
     assert lib.wino_conv2d(C.byref(dfused), fake, fake, fake, C.byref(s), fake, 1 << 30, None) == -2
+    assert lib.wino_contract_output(C.byref(dfused), fake, fake, fake, C.byref(s), None) == -2
+    assert lib.wino_contract_output(C.byref(d), fake, fake, None, C.byref(s), None) == -1
+
+
+def test_kernel_selection_and_workspace_of_the_whole_layer_call():
+    """Which launches wino_conv2d makes, and the workspace that goes with them."""
+    n2, T = 36, 1024
+    r256 = lambda v: (v + 255) // 256 * 256
+    V, U, M = r256(n2 * 256 * 256), r256(n2 * T * 256), r256(n2 * T * 256)
+    wide = dict(m=4)
+    cases = [
+        (wn.FUSED_OFF, {}, ["operand_transforms", "contraction", "output_transform"], V + U + M),
+        (wn.FUSED_AUTO, {}, ["operand_transforms", "contraction_output"], V + U),
+        (wn.FUSED_ON, {}, ["operand_transforms", "contraction_output"], V + U),
+        (wn.FUSED_AUTO, dict(weights_pretransformed=1), ["input_transform", "contraction_output"], U),
+        (wn.FUSED_AUTO, dict(bits_hadamard=32), ["operand_transforms", "contraction",
+                                                 "output_transform"], V + U + 4 * M),
+    ]
+    for mode, kw, names, ws in cases:
+        d = wn.ConvDesc(256, 8, 8, 256, 256, fused=mode, **wide, **kw)
+        assert wn.wino_conv2d_launches(d) == names, (mode, kw)
+        assert wn.wino_workspace_bytes(d) == ws, (mode, kw)
+    narrow = wn.ConvDesc(128, 32, 32, 64, 64, m=4, fused=wn.FUSED_AUTO)
+    assert wn.wino_conv2d_launches(narrow) == ["weight_transform", "fused_layer"]
+    assert wn.wino_workspace_bytes(narrow) == r256(36 * 64 * 64)
+    f6 = wn.ConvDesc(2, 8, 8, 32, 32, m=6, fused=wn.FUSED_ON)          # no single kernel for F(6,3)
+    assert wn.wino_conv2d_launches(f6) == ["operand_transforms", "contraction_output"]
+    assert wn.wino_conv2d_launches(wn.ConvDesc(0, 8, 8, 16, 16)) == []
+    wn.wino_set_option(wn.OPT_AUTO_CONOUT, 0)
+    try:
+        d = wn.ConvDesc(256, 8, 8, 256, 256, m=4, fused=wn.FUSED_AUTO)
+        assert wn.wino_conv2d_launches(d) == ["operand_transforms", "contraction", "output_transform"]
+    finally:
+        wn.wino_set_option(wn.OPT_AUTO_CONOUT, 1)
+    for opt, val in [(7, 0), (wn.OPT_CONOUT_SHAPE, 3), (wn.OPT_CONOUT_SHAPE, -1)]:
+        with pytest.raises(wn.WinoError) as e:
+            wn.wino_set_option(opt, val)
+        assert e.value.code == -1
 
 
 def test_flex_calls_validate_matrices_and_options_before_any_launch():

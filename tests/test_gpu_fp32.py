@@ -2,13 +2,10 @@
 
 Bar: max |y_gpu - y_fp64| <= 1e-4 * max|y_fp64| against the fp64 oracle
 (eq. 3 / eq. 4 evaluated in float64 on the same fp32 inputs, and the direct
-convolution itself).  The one exception is F(6,3) routed through the Legendre
-brackets, held to 2e-3: its 8 x 8 base-change factors have large entries of
-mixed sign (row sums of |B_P^T| near 100), and the cancellation between the
-two brackets of eq. 4 costs fp32 about two more digits than the canonical
-F(6,3) matrices do (measured 7e-4 against 4e-6).
+convolution itself), for every tile size in both bases.  The tensors of the path
+are fp32; a Legendre bracket pair (whose factors cancel) is evaluated in double
+between its fp32 input and its fp32 result.
 """
-TOL = {(6, "legendre"): 2e-3}
 import numpy as np
 import pytest
 
@@ -60,8 +57,8 @@ def test_fp32_path_matches_fp64(m, base):
         y = run_fp32(x, w, m, base, whole)
         err = np.abs(y - ref).max() / scale
         print("fp32 path F(%d,3) %s whole=%s: rel err %.3g" % (m, base, whole, err))
-        assert err <= TOL.get((m, base), 1e-4)
-        assert np.abs(y - yd).max() <= TOL.get((m, base), 1e-4) * scale
+        assert err <= 1e-4
+        assert np.abs(y - yd).max() <= 1e-4 * scale
 
 
 def test_fp32_path_cfg1_and_relu():

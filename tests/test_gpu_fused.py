@@ -52,7 +52,7 @@ def test_fused_benchmark_configurations(name):
 
 def test_fused_rejects_what_it_does_not_cover():
     import paper_2004_11077_amd as wn
-    for kw in (dict(m=6), dict(bits_hadamard=32), dict(bits_in=32),
+    for kw in (dict(bits_hadamard=32), dict(bits_in=32),
                dict(base=wn.BASE_CANONICAL, out_type=wn.OUT_I32)):
         with pytest.raises(wn.WinoError) as e:
             import torch

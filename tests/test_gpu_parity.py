@@ -187,3 +187,35 @@ def test_largest_exact_contraction_result():
     assert np.array_equal(M.cpu().numpy().astype(np.int64), Mq)
     err = np.abs(y.cpu().numpy().astype(np.float64) - y_ref).max()
     assert err <= 1e-5 * np.abs(y_ref).max()
+
+
+@pytest.mark.parametrize("bits_hadamard", [8, 9, 32])
+def test_no_input_channels_gives_zero_output(bits_hadamard):
+    """C = 0 with tiles and output channels present: an empty channel sum.  The contraction
+    stage must not read U or V (there is nothing to read) and every M and y is zero; split
+    calls and the whole-layer call in all three fused modes."""
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    N, H, W, C, K, m = 2, 9, 7, 0, 32, 4
+    mdt = {8: torch.int8, 9: torch.int16, 32: torch.int32}[bits_hadamard]
+    sc = wn.Scales.from_dict({k: 0.5 for k in ("s_x", "s_x1", "s_u", "s_w", "s_w1", "s_v", "s_m",
+                                               "s_m1", "s_y")})
+    x = torch.empty((N, H, W, 0), dtype=torch.int8, device=dev)
+    w = torch.empty((K, 0, 3, 3), dtype=torch.int8, device=dev)
+    desc = wn.ConvDesc(N, H, W, C, K, m=m, bits_hadamard=bits_hadamard)
+    n2, T = desc.n ** 2, desc.tiles
+    M = torch.full((n2, T, K), 77, dtype=mdt, device=dev)
+    y = torch.full((N, H, W, K), 7.0, dtype=torch.float32, device=dev)
+    wn.wino_contract(desc, None, None, M, sc)    # U and V are empty: null pointers are accepted
+    wn.wino_output_transform(desc, M, y, sc)
+    torch.cuda.synchronize()
+    assert int(M.abs().max()) == 0 and float(y.abs().max()) == 0.0
+    modes = [wn.FUSED_OFF, wn.FUSED_AUTO] + ([wn.FUSED_ON] if bits_hadamard != 32 else [])
+    for mode in modes:
+        d2 = wn.ConvDesc(N, H, W, C, K, m=m, bits_hadamard=bits_hadamard, fused=mode)
+        ws = torch.full((wn.wino_workspace_bytes(d2),), 77, dtype=torch.uint8, device=dev)
+        y2 = torch.full((N, H, W, K), 7.0, dtype=torch.float32, device=dev)
+        wn.wino_conv2d(d2, x, w, y2, sc, ws)
+        torch.cuda.synchronize()
+        assert float(y2.abs().max()) == 0.0, mode

@@ -8,7 +8,10 @@ codes of the next.  A stage starts from a fresh seeded tensor, because the
 stride-2 layers that change the resolution are not part of the list.  The stem's
 3 input channels are zero-padded to 16 (the library's channel granularity).
 Every layer's V, U, M and int8 y must equal the oracle's bit for bit, so any
-drift would show at the layer where it starts.
+drift would show at the layer where it starts.  The chain runs at a reduced
+batch (N = 32) and at the configuration's own N = 256, the size the benchmark
+times; there each layer is also run the way the benchmark runs it (filters
+transformed beforehand, fused = AUTO, which picks the kernels by layer shape).
 """
 import numpy as np
 import pytest
@@ -18,9 +21,6 @@ from helpers import assert_layer_parity, gpu_layer, oracle_layer
 
 pytestmark = pytest.mark.gpu
 
-N = 32          # the chain is checked at a reduced batch; the full-batch layer shapes
-                # are covered one by one in test_gpu_parity.py
-
 
 def stage_layers():
     stages = {}
@@ -29,8 +29,32 @@ def stage_layers():
     return stages
 
 
+def run_as_benchmark(xq, wq, scales):
+    """One layer through wino_conv2d with pretransformed filters and fused = AUTO, int8 + ReLU
+    output: returns y."""
+    import torch
+    import paper_2004_11077_amd as wn
+    dev = torch.device("cuda:0")
+    N, H, W, C = xq.shape
+    K = wq.shape[0]
+    sc = wn.Scales.from_dict(scales)
+    x = torch.from_numpy(np.ascontiguousarray(xq, dtype=np.int8)).to(dev)
+    w = torch.from_numpy(np.ascontiguousarray(wq, dtype=np.int8)).to(dev)
+    desc = wn.ConvDesc(N, H, W, C, K, m=4, out_type=wn.OUT_I8, relu=1)
+    V = torch.empty((36, K, C), dtype=torch.int8, device=dev)
+    wn.wino_weight_transform(desc, w, V, sc)
+    run = wn.ConvDesc(N, H, W, C, K, m=4, out_type=wn.OUT_I8, relu=1, weights_pretransformed=1,
+                      fused=wn.FUSED_AUTO)
+    ws = torch.empty(wn.wino_workspace_bytes(run), dtype=torch.uint8, device=dev)
+    y = torch.full((N, H, W, K), 77, dtype=torch.int8, device=dev)
+    wn.wino_conv2d(run, x, V, y, sc, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("N", [32, 256])
 @pytest.mark.parametrize("HW", [32, 16, 8, 4])
-def test_chain_within_stage(HW):
+def test_chain_within_stage(HW, N):
     layers = stage_layers()[HW]
     rng_seed = 4
     C0 = layers[0][0]
@@ -48,4 +72,6 @@ def test_chain_within_stage(HW):
         got = gpu_layer(xq, wq, sc, whole=True, **kw)
         assert_layer_parity(ora, got, "i8")
         assert got["y"].min() >= 0
+        if N == 256:
+            assert np.array_equal(run_as_benchmark(xq, wq, sc).astype(np.int64), ora["y"])
         xq, s_x = got["y"], sc["s_y"]           # the GPU's own output feeds the next layer
