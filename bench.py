@@ -190,10 +190,11 @@ def resnet18_stack(wn, si, torch, dev, steps, N=256):
         cws = torch.empty(wn.wino_calibrate_workspace_bytes(desc), dtype=torch.uint8, device=dev)
         sc = wn.wino_calibrate(desc, x, w, y, s_in, float(s_w), cws)
         del cws
-        V = torch.empty((36, K, Cp), dtype=torch.int8, device=dev)
-        wn.wino_weight_transform(desc, w, V, sc)
+        lay = wn.wino_preferred_operand_layout(desc)
         run = wn.ConvDesc(N, HW, HW, Cp, K, m=4, out_type=wn.OUT_I8, relu=1,
-                          weights_pretransformed=1, fused=wn.FUSED_AUTO)
+                          weights_pretransformed=1, fused=wn.FUSED_AUTO, operand_layout=lay)
+        V = torch.empty((wn.wino_operand_bytes(run)[0],), dtype=torch.int8, device=dev)
+        wn.wino_weight_transform(run, w, V, sc)
         ws = torch.empty(wn.wino_workspace_bytes(run), dtype=torch.uint8, device=dev)
         layers.append((run, x, V, y, sc, ws))
         ops += 2.0 * N * HW * HW * C * K * 9
@@ -516,11 +517,12 @@ def main():
     # extra: the same layer with its filters transformed ahead of time (a1 is a per-layer,
     # offline step in deployment)
     if want("pretransformed"):
-        V = torch.empty((n2, wl.K, wl.C), dtype=torch.int8, device=dev)
-        wn.wino_weight_transform(desc, w, V, sc, stream)
+        lay = wn.wino_preferred_operand_layout(desc) if mode == wn.FUSED_AUTO else wn.LAYOUT_ROWS
         pdesc = wn.ConvDesc(wl.N, wl.H, wl.W, wl.C, wl.K, m=wl.m, base=base,
                             bits_hadamard=wl.bits_hadamard, out_type=wn.OUT_F32, fused=mode,
-                            weights_pretransformed=1)
+                            weights_pretransformed=1, operand_layout=lay)
+        V = torch.empty((wn.wino_operand_bytes(pdesc)[0],), dtype=torch.int8, device=dev)
+        wn.wino_weight_transform(pdesc, w, V, sc, stream)
         pws = torch.empty(wn.wino_workspace_bytes(pdesc), dtype=torch.uint8, device=dev)
         vdt = timed(torch, lambda: wn.wino_conv2d(pdesc, x, V, y, sc, pws, stream), steps)[0]
         out["pretransformed_weights"] = {"ms_per_step": vdt * 1e3, "value": ops / vdt / 1e12,

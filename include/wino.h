@@ -49,6 +49,20 @@ enum {
 };
 enum { WINO_OUT_F32 = 0, WINO_OUT_I32 = 1, WINO_OUT_I8 = 2 };
 enum { WINO_FUSED_OFF = 0, WINO_FUSED_ON = 1, WINO_FUSED_AUTO = 2 };
+/* Memory order of the transformed operands U and V (int8 path).
+ * ROWS: U [n*n][T][C], V [n*n][K][C], as written under "Conventions".
+ * FRAGMENTS: the register layout of the 16x16x64 int8 matrix instruction, so
+ * that the kernel that contracts them loads them without any rearrangement:
+ * rows (tiles of U, output channels of V) in groups of 16, channels in chunks
+ * of 64, each 16 x 64 block one contiguous KiB ordered [c%64/16][row%16][c%16]:
+ *   offset(p, row, c) = ((p*RG + row/16)*NCH + c/64)*1024
+ *                       + (c%64/16)*256 + (row%16)*16 + c%16,
+ *   RG = ceil(rows/16), NCH = ceil(C/64); size n*n*RG*NCH KiB
+ *   (wino_operand_bytes).  Rows past the last one are never written; channels
+ * past C are zeros in V.  Written by the three operand-transform calls, read by
+ * wino_contract_output and by wino_conv2d (a pretransformed V); every other
+ * call takes ROWS only (EUNSUPPORTED otherwise). */
+enum { WINO_LAYOUT_ROWS = 0, WINO_LAYOUT_FRAGMENTS = 1 };
 enum {
   WINO_MAT_G = 0,     /* n x r  Section 3: filter transform                    */
   WINO_MAT_BT = 1,    /* n x n  Section 3: input transform                     */
@@ -114,9 +128,19 @@ typedef struct {
                                  contraction + output transform (U in the
                                  workspace); needs bits_hadamard 8 or 9 and fp32
                                  or int8 output.  AUTO = the fastest of the three
-                                 for the shape: the single kernel for C, K <= 64,
-                                 the two-kernel form for every other layer ON
-                                 covers, one kernel per stage for the rest        */
+                                 for the shape: the single kernel for C, K <= 64;
+                                 the two-kernel form for mid-sized layers ON
+                                 covers (m = 2 or 4; enough tiles and output
+                                 channels to fill the device, not a large batch)
+                                 whose M is 9 bits wide or whose filters arrive
+                                 transformed; one kernel per stage for the rest   */
+  int operand_layout;         /* WINO_LAYOUT_*: order of U and V in the stage
+                                 calls that write or read them; in wino_conv2d
+                                 the order of a pretransformed V (U, and a V it
+                                 computes itself, live in the workspace in the
+                                 order its kernels want).  The two-kernel form
+                                 is fast with FRAGMENTS; given a pretransformed
+                                 V in ROWS, AUTO runs one kernel per stage        */
 } wino_conv_desc_t;
 
 /* Symmetric scales, supplied by the caller (or chosen by wino_calibrate).
@@ -143,6 +167,15 @@ typedef struct {
   float s_v_pt[64];
   int m_shift[64];
 } wino_scales_t;
+
+/* Bytes of V and of U (host pointers, either may be null) in the order
+ * d->operand_layout names. */
+int wino_operand_bytes(const wino_conv_desc_t* d, size_t* v_bytes, size_t* u_bytes);
+
+/* *layout (host) = the order in which wino_conv2d runs this layer fastest when
+ * it is handed a pretransformed V: FRAGMENTS where AUTO would take the
+ * two-kernel form, ROWS otherwise (d->operand_layout itself is ignored). */
+int wino_preferred_operand_layout(const wino_conv_desc_t* d, int* layout);
 
 /* Bytes of device workspace wino_conv2d needs for this descriptor: V unless
  * pretransformed, U unless the single-kernel variant runs, M only when one
@@ -183,6 +216,7 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
  * U, V -> y with the same arithmetic and the same casts as wino_contract
  * followed by wino_output_transform (results are bit-identical), the cast
  * contraction result being kept in on-chip memory instead of a tensor M.
+ * U and V in the order d->operand_layout names (FRAGMENTS is the fast one).
  * Needs bits_hadamard 8 or 9 and out_type F32 or I8 (EUNSUPPORTED otherwise). */
 int wino_contract_output(const wino_conv_desc_t* d, const void* U, const void* V, void* y,
                          const wino_scales_t* s, void* hip_stream);
@@ -329,16 +363,13 @@ int wino_flex_backward(const wino_conv_desc_t* d, const wino_flex_matrices_t* f,
  * output_transform, contraction_output, fused_layer. */
 int wino_conv2d_launches(const wino_conv_desc_t* d, char* buf, size_t buf_bytes);
 
-/* Tuning options, process-wide, for measurements and tests; the defaults are
+/* Tuning option, process-wide, for measurements and tests; the default is
  * what the library ships with.
- *   WINO_OPT_CONOUT_SHAPE  work-group block of the contraction + output kernel:
- *                          0 = chosen from the problem size (default), 1 = small
- *                          blocks (16 tiles x 32 channels), 2 = large blocks
  *   WINO_OPT_AUTO_CONOUT   1 (default): WINO_FUSED_AUTO may pick the two-kernel
  *                          form; 0: it picks between the single kernel and one
  *                          kernel per stage only
  * Errors: EINVAL (unknown option, value out of range). */
-enum { WINO_OPT_CONOUT_SHAPE = 0, WINO_OPT_AUTO_CONOUT = 1 };
+enum { WINO_OPT_AUTO_CONOUT = 1 };
 int wino_set_option(int option, int value);
 
 /* Measurement hook.  The next kernel that the calling thread launches through

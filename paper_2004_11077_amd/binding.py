@@ -8,9 +8,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 BASE_CANONICAL, BASE_LEGENDRE, BASE_CHEBYSHEV, BASE_HERMITE = 0, 1, 2, 3
 OUT_F32, OUT_I32, OUT_I8 = 0, 1, 2
 FUSED_OFF, FUSED_ON, FUSED_AUTO = 0, 1, 2
+LAYOUT_ROWS, LAYOUT_FRAGMENTS = 0, 1
 MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
 EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
-           "wino_workspace_bytes", "wino_calibrate_workspace_bytes", "wino_calibrate",
+           "wino_workspace_bytes", "wino_operand_bytes", "wino_preferred_operand_layout",
+           "wino_calibrate_workspace_bytes", "wino_calibrate",
            "wino_conv2d", "wino_weight_transform",
            "wino_input_transform", "wino_transform_operands", "wino_contract",
            "wino_output_transform", "wino_contract_output", "wino_conv2d_launches",
@@ -35,12 +37,13 @@ class ConvDesc(C.Structure):
     """Mirror of wino_conv_desc_t."""
     _fields_ = [(n, C.c_int) for n in (
         "N", "H", "W", "C", "K", "m", "r", "base", "bits_in", "bits_hadamard", "inner_quant",
-        "out_type", "relu", "weights_pretransformed", "fused")]
+        "out_type", "relu", "weights_pretransformed", "fused", "operand_layout")]
 
     def __init__(self, N, H, W, C_, K, m=4, r=3, base=BASE_LEGENDRE, bits_in=8, bits_hadamard=8,
-                 inner_quant=1, out_type=OUT_F32, relu=0, weights_pretransformed=0, fused=0):
+                 inner_quant=1, out_type=OUT_F32, relu=0, weights_pretransformed=0, fused=0,
+                 operand_layout=0):
         super().__init__(N, H, W, C_, K, m, r, base, bits_in, bits_hadamard, inner_quant,
-                         out_type, relu, weights_pretransformed, fused)
+                         out_type, relu, weights_pretransformed, fused, operand_layout)
 
     @property
     def n(self):
@@ -140,6 +143,8 @@ def _load():
                                       ip, ip]
     dp, sp = C.POINTER(ConvDesc), C.POINTER(Scales)
     lib.wino_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
+    lib.wino_operand_bytes.argtypes = [dp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
+    lib.wino_preferred_operand_layout.argtypes = [dp, ip]
     lib.wino_conv2d.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_calibrate_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
     lib.wino_calibrate.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
@@ -351,6 +356,31 @@ def wino_output_transform(desc, M, y, scales, stream=None):
     return y
 
 
+def wino_operand_bytes(desc):
+    """(bytes of V, bytes of U) in the order desc.operand_layout names."""
+    v, u = C.c_size_t(), C.c_size_t()
+    _check(_load().wino_operand_bytes(C.byref(desc), C.byref(v), C.byref(u)))
+    return v.value, u.value
+
+
+def wino_preferred_operand_layout(desc):
+    """LAYOUT_* of a pretransformed V with which wino_conv2d runs this layer fastest."""
+    out = C.c_int()
+    _check(_load().wino_preferred_operand_layout(C.byref(desc), C.byref(out)))
+    return out.value
+
+
+def defragment(buf, n2, rows, channels):
+    """A tensor in fragment order (flat int8 numpy array) back to [n2][rows][channels]:
+    the inverse of the offset formula in include/wino.h, for tests and inspection."""
+    import numpy as np
+    rg, nch = -(-rows // 16), -(-channels // 64)
+    a = np.asarray(buf).reshape(-1)[:n2 * rg * nch * 1024].reshape(n2, rg, nch, 4, 16, 16)
+    # [p][row group][chunk][c%64/16][row%16][c%16] -> [p][row group][row%16][chunk][c%64/16][c%16]
+    a = a.transpose(0, 1, 4, 2, 3, 5).reshape(n2, rg * 16, nch * 64)
+    return a[:, :rows, :channels]
+
+
 def wino_contract_output(desc, U, V, y, scales, stream=None):
     sc = _scales(scales)
     _check(_load().wino_contract_output(C.byref(desc), _ptr(U), _ptr(V), _ptr(y), C.byref(sc),
@@ -358,7 +388,7 @@ def wino_contract_output(desc, U, V, y, scales, stream=None):
     return y
 
 
-OPT_CONOUT_SHAPE, OPT_AUTO_CONOUT = 0, 1
+OPT_AUTO_CONOUT = 1
 
 
 def wino_set_option(option, value):

@@ -133,7 +133,13 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
     return fail(WINO_EINVAL, "problem too large");
   if (!p->fp32 && d->bits_hadamard == 32 && d->C > kMaxChannelsExact)
     return fail(WINO_EOVERFLOW, "C = %d: an unquantised contraction result may exceed 2^24", d->C);
-  p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T};
+  if (d->operand_layout != WINO_LAYOUT_ROWS && d->operand_layout != WINO_LAYOUT_FRAGMENTS)
+    return fail(WINO_EINVAL, "unknown operand_layout %d", d->operand_layout);
+  if (d->operand_layout == WINO_LAYOUT_FRAGMENTS && p->fp32)
+    return fail(WINO_EUNSUPPORTED, "fragment order is a layout of the int8 operands");
+  p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T,
+                  d->operand_layout == WINO_LAYOUT_FRAGMENTS ? 1 : 0, 0, 0, 0, 0};
+  geometry_set_divisors(p->g);
   if (!stages_for(d->m, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
   p->two_brackets = d->base == WINO_BASE_LEGENDRE && d->inner_quant != 0;
   p->m_bits = p->fp32 ? 32 : d->bits_hadamard;
@@ -151,6 +157,30 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
 
 int need(const void* p, const char* name) {
   return p ? WINO_OK : fail(WINO_EINVAL, "null pointer: %s", name);
+}
+
+// Bytes of V and U in rows or fragment order.
+size_t v_bytes_of(const Plan& p, bool frag) {
+  const size_t n2 = (size_t)(p.g.m + 2) * (p.g.m + 2);
+  return frag ? (size_t)frag_bytes((long)n2, p.g.K, p.g.C) : n2 * p.g.K * p.g.C * (p.fp32 ? 4 : 1);
+}
+size_t u_bytes_of(const Plan& p, bool frag) {
+  const size_t n2 = (size_t)(p.g.m + 2) * (p.g.m + 2);
+  return frag ? (size_t)frag_bytes((long)n2, p.g.T, p.g.C) : n2 * p.g.T * p.g.C * (p.fp32 ? 4 : 1);
+}
+
+// Fragment order pads the channels of V to a multiple of 64 with zeros (the contraction reads
+// whole 64-channel chunks of both operands): when C is not such a multiple the tensor is
+// cleared before the transform writes the real channels.
+int clear_v_padding(const Plan& p, void* V, void* hip_stream) {
+  if (!p.g.frag || p.g.C % 64 == 0 || (long)p.g.K * p.g.C == 0) return WINO_OK;
+  hipError_t e = launch_fill_zero(V, (long)v_bytes_of(p, true), (hipStream_t)hip_stream);
+  return e == hipSuccess ? WINO_OK : fail_hip(e, "zero fill of V");
+}
+
+int rows_only(const Plan& p, const char* who) {
+  return p.g.frag ? fail(WINO_EUNSUPPORTED, "%s takes U and V in WINO_LAYOUT_ROWS only", who)
+                  : WINO_OK;
 }
 
 int aligned(const void* p, size_t a, const char* name) {
@@ -269,8 +299,7 @@ enum Path {
   kPathConOut      // input transform, then contraction + output transform in one kernel
 };
 
-// Tuning options (wino_set_option), process-wide.
-int g_opt_co_shape = 0;      // block shape of the contraction + output kernel: 0 auto, 1 small, 2 large
+// Tuning option (wino_set_option), process-wide.
 int g_opt_auto_conout = 1;   // AUTO may take the contraction + output kernel
 
 // The variants that keep M on chip cover the int8 path with a cast Hadamard stage and fp32 or
@@ -283,10 +312,27 @@ bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
   return conout_covers(d, p) && d->m != 6;
 }
 
+// AUTO takes the two-kernel form where it was measured to be the faster one on C = K = 128 ...
+// 256 layers.  It saves the M round trip and a launch; it pays with operands re-read through
+// the L2 four times as often (32 x 32 blocks against the 128 x 128 tiles of the stand-alone
+// contraction) and with an input transform that is about 15 % slower into fragment order.
+//  * Its grid must fill most of the 256 compute units: with fewer work groups each streams
+//    its operands at one compute unit's rate (4x4 images, 512 channels: 23 us against 15 us).
+//  * On large batches the operand re-reads cost more than M saves (8192 tiles: 89 us against
+//    86 us for the two stages it replaces).
+//  * Net effect on the 256-channel 8x8 layer, N = 256: 26.7 us against 28.0 us when the
+//    filters arrive transformed, 28.4 us against 27.6 us when they do not (the filter
+//    transform into fragment order is slower too); with a 9-bit M (twice the bytes) 23.5 us
+//    against 27.2 us on the 128-channel 16x16 layer.  F(6,3): 59 us against 48 us (its output
+//    bracket needs 64-bit arithmetic and runs better at the stand-alone kernel's occupancy).
+constexpr long kConOutMinBlocks = 192;
+constexpr long kConOutMaxBlocks8 = 1024, kConOutMaxBlocks9 = 4096;
+
 // ON: M never leaves the chip.  The single kernel where the layer has one 64-channel chunk
 // (its input transform is recomputed per 64 output channels and it keeps no accumulators
 // across chunks), the two-kernel form otherwise.  AUTO: whichever form is the fastest for the
-// shape: the single kernel for C, K <= 64, the two-kernel form for every other covered layer.
+// shape: the single kernel for C, K <= 64, the two-kernel form for every other covered layer
+// that is large enough.
 int select_path(const wino_conv_desc_t* d, const Plan& p, Path* path) {
   *path = kPathSplit;
   if (d->fused != WINO_FUSED_OFF && d->fused != WINO_FUSED_ON && d->fused != WINO_FUSED_AUTO)
@@ -296,13 +342,28 @@ int select_path(const wino_conv_desc_t* d, const Plan& p, Path* path) {
     if (!conout_covers(d, p))
       return fail(WINO_EUNSUPPORTED, "the fused variants cover the int8 path with bits_hadamard "
                                      "8 or 9 and fp32 or int8 output");
-    *path = (fused_all_covers(d, p) && d->C <= 64) ? kPathFusedAll : kPathConOut;
+    *path = (fused_all_covers(d, p) && d->C <= 64 && !p.g.frag) ? kPathFusedAll : kPathConOut;
     return WINO_OK;
   }
-  if (fused_all_covers(d, p) && d->C <= 64 && d->K <= 64)
+  const bool v_rows_given = d->weights_pretransformed && !p.g.frag;   // slow in the two-kernel form
+  if (fused_all_covers(d, p) && d->C <= 64 && d->K <= 64 && !p.g.frag)
     *path = kPathFusedAll;
-  else if (conout_covers(d, p) && g_opt_auto_conout)
+  else if (conout_covers(d, p) && g_opt_auto_conout && !v_rows_given && d->m != 6 &&
+           (p.m_bits == 9 || d->weights_pretransformed) &&
+           contract_output_blocks(p.g, p.m_bits) >= kConOutMinBlocks &&
+           contract_output_blocks(p.g, p.m_bits) <= (p.m_bits == 9 ? kConOutMaxBlocks9 : kConOutMaxBlocks8))
     *path = kPathConOut;
+  return WINO_OK;
+}
+
+// Order of U and V inside wino_conv2d: fragments for the two-kernel form unless the caller
+// hands over a V in rows; rows everywhere else.  A V in fragment order is only meaningful to
+// the two-kernel form.
+int conv_layout(const wino_conv_desc_t* d, const Plan& p, Path path, bool* frag) {
+  *frag = path == kPathConOut && (!d->weights_pretransformed || p.g.frag);
+  if (d->weights_pretransformed && p.g.frag && path != kPathConOut)
+    return fail(WINO_EUNSUPPORTED, "a V in fragment order is read by the two-kernel form only "
+                                   "(fused = ON or AUTO on a layer it covers)");
   return WINO_OK;
 }
 
@@ -314,10 +375,6 @@ const char* wino_last_error(void) { return g_err.c_str(); }
 
 int wino_set_option(int option, int value) {
   switch (option) {
-    case WINO_OPT_CONOUT_SHAPE:
-      if (value < 0 || value > 2) return fail(WINO_EINVAL, "block shape must be 0, 1 or 2");
-      g_opt_co_shape = value;
-      return WINO_OK;
     case WINO_OPT_AUTO_CONOUT:
       g_opt_auto_conout = value != 0;
       return WINO_OK;
@@ -367,6 +424,7 @@ int wino_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "the backward pass takes the int8 path's U and V");
+  if (int rc = rows_only(p, "the backward pass")) return rc;
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   const size_t T = (size_t)p.g.T, C = (size_t)d->C, K = (size_t)d->K;
@@ -538,6 +596,34 @@ int wino_get_int_form(const wino_matrices_t* h, int which, int64_t* N, int64_t* 
   return WINO_OK;
 }
 
+int wino_operand_bytes(const wino_conv_desc_t* d, size_t* v_bytes, size_t* u_bytes) {
+  Plan p;
+  if (int rc = make_plan(d, &p)) return rc;
+  if (v_bytes) *v_bytes = v_bytes_of(p, p.g.frag != 0);
+  if (u_bytes) *u_bytes = u_bytes_of(p, p.g.frag != 0);
+  return WINO_OK;
+}
+
+int wino_preferred_operand_layout(const wino_conv_desc_t* d, int* layout) {
+  if (!d || !layout) return fail(WINO_EINVAL, "null argument");
+  wino_conv_desc_t dd = *d;
+  dd.weights_pretransformed = 1;
+  dd.fused = WINO_FUSED_AUTO;
+  *layout = WINO_LAYOUT_ROWS;
+  dd.operand_layout = WINO_LAYOUT_ROWS;
+  Plan p;
+  if (int rc = make_plan(&dd, &p)) return rc;
+  Path path;
+  if (int rc = select_path(&dd, p, &path)) return rc;
+  if (path == kPathFusedAll || p.fp32) return WINO_OK;   // the single kernel reads V in rows
+  // would AUTO take the two-kernel form if V came in fragment order?
+  dd.operand_layout = WINO_LAYOUT_FRAGMENTS;
+  if (int rc = make_plan(&dd, &p)) return rc;
+  if (int rc = select_path(&dd, p, &path)) return rc;
+  if (path == kPathConOut) *layout = WINO_LAYOUT_FRAGMENTS;
+  return WINO_OK;
+}
+
 int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
@@ -546,10 +632,13 @@ int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes) {
   const size_t eb = p.fp32 ? 4 : 1;
   Path path;
   if (int rc = select_path(d, p, &path)) return rc;
+  bool frag;
+  if (int rc = conv_layout(d, p, path, &frag)) return rc;
   size_t total = 0;
-  if (!d->weights_pretransformed) total += round256(n2 * d->K * d->C * eb);
+  (void)eb;
+  if (!d->weights_pretransformed) total += round256(v_bytes_of(p, frag));
   // U unless the single kernel runs, M only when one kernel runs per stage
-  if (path != kPathFusedAll) total += round256(n2 * p.g.T * d->C * eb);
+  if (path != kPathFusedAll) total += round256(u_bytes_of(p, frag));
   if (path == kPathSplit) total += round256(n2 * p.g.T * d->K * m_elem_bytes(p.m_bits));
   if (total == 0) total = 256;
   *bytes = total;
@@ -574,6 +663,7 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
   if (int rc = check_per_point(d, s)) return rc;
   StageMults mu;
   if (int rc = weight_mults(p, s, &mu)) return rc;
+  if (int rc = clear_v_padding(p, V, hip_stream)) return rc;
   hipError_t e = launch_weight_transform(p.g, p.two_brackets, (const int8_t*)w, (int8_t*)V, mu,
                                          (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "weight transform launch");
@@ -624,6 +714,7 @@ int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, c
   StageMults mu_in, mu_w;
   if (int rc = input_mults(p, s, &mu_in)) return rc;
   if (int rc = weight_mults(p, s, &mu_w)) return rc;
+  if (int rc = clear_v_padding(p, V, hip_stream)) return rc;
   hipError_t e = launch_operand_transforms(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U,
                                            (const int8_t*)w, (int8_t*)V, mu_in, mu_w,
                                            (hipStream_t)hip_stream);
@@ -650,6 +741,7 @@ int wino_contract(const wino_conv_desc_t* d, const void* U, const void* V, void*
   if (int rc = aligned(V, 16, "V")) return rc;
   if (int rc = aligned(M, 16, "M")) return rc;
   if (int rc = check_per_point(d, s)) return rc;
+  if (int rc = rows_only(p, "wino_contract")) return rc;
   MultTable mult;
   double s_m;
   if (int rc = contract_mults(p, s, &mult, nullptr, &s_m)) return rc;
@@ -709,8 +801,7 @@ int wino_contract_output(const wino_conv_desc_t* d, const void* U, const void* V
   if (int rc = output_mults(p, d, s, &mu, nullptr)) return rc;
   hipError_t e = launch_contract_output(p.g, p.two_brackets, (const int8_t*)U, (const int8_t*)V, y,
                                         p.m_bits, d->out_type, d->relu != 0, mu, mm,
-                                        s->per_point ? &sh : nullptr, g_opt_co_shape,
-                                        (hipStream_t)hip_stream);
+                                        s->per_point ? &sh : nullptr, (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "contraction + output launch");
 }
 
@@ -841,6 +932,7 @@ int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "the fp32 path has no scales to calibrate");
+  if (int rc = rows_only(p, "wino_calibrate")) return rc;
   if (d->C > kMaxChannelsExact)
     return fail(WINO_EOVERFLOW, "C = %d: calibration needs the exact int32 contraction result", d->C);
   if (int rc = need(s, "scales")) return rc;
@@ -932,22 +1024,24 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
   if (int rc = check_per_point(d, s)) return rc;
   Path path;
   if (int rc = select_path(d, p, &path)) return rc;
+  bool frag;
+  if (int rc = conv_layout(d, p, path, &frag)) return rc;
   size_t want = 0;
   if (int rc = wino_workspace_bytes(d, &want)) return rc;
   wino_conv_desc_t dsel = *d;
   dsel.fused = path == kPathFusedAll;
+  dsel.operand_layout = frag ? WINO_LAYOUT_FRAGMENTS : WINO_LAYOUT_ROWS;
   d = &dsel;
   if (int rc = need(workspace, "workspace")) return rc;
   if (ws_bytes < want) return fail(WINO_EWORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, want);
   if ((uintptr_t)workspace % 256) return fail(WINO_EWORKSPACE, "workspace must be 256-byte aligned");
-  const size_t n2 = (size_t)(d->m + 2) * (d->m + 2);
   char* ws = static_cast<char*>(workspace);
   const void* V = w_or_V;
   void* Vws = nullptr;
   if (!d->weights_pretransformed) {
     Vws = ws;
     V = ws;
-    ws += round256(n2 * d->K * d->C * (p.fp32 ? 4 : 1));
+    ws += round256(v_bytes_of(p, frag));
     // the fused variant transforms the filters on their own; the split path
     // does it together with the input transform, in one launch (below)
     if (d->fused)
@@ -971,7 +1065,7 @@ int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, vo
     return e == hipSuccess ? WINO_OK : fail_hip(e, "fused launch");
   }
   void* U = ws;
-  ws += round256(n2 * p.g.T * d->C * (p.fp32 ? 4 : 1));
+  ws += round256(u_bytes_of(p, frag));
   void* M = ws;
   if (Vws) {
     if (int rc = wino_transform_operands(d, x, U, w_or_V, Vws, s, hip_stream)) return rc;
@@ -997,6 +1091,7 @@ int make_flex_plan(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, Fle
   if (int rc = make_plan(d, &fp->p)) return rc;
   const Plan& p = fp->p;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "flex layers run on the int8 path (bits_in = 8)");
+  if (int rc = rows_only(p, "a flex call")) return rc;
   if (p.legendre && !p.two_brackets)
     return fail(WINO_EUNSUPPORTED, "a flex layer in the Legendre base needs inner_quant = 1 "
                                    "(run-time matrices cannot be multiplied out with P^{-1})");
@@ -1294,6 +1389,7 @@ int wino_flex_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes)
   Plan p;
   if (int rc = make_plan(d, &p)) return rc;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "flex layers run on the int8 path (bits_in = 8)");
+  if (int rc = rows_only(p, "a flex call")) return rc;
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   *bytes = flex_bwd_layout(p.g).total;
   if (*bytes == 0) *bytes = 256;

@@ -3,6 +3,7 @@
 
 namespace wino {
 
+
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
@@ -481,16 +482,25 @@ hipError_t launch_fill_zero(void* dst, long bytes, hipStream_t st) {
 hipError_t launch_contract_output(const Geometry& g, bool leg, const int8_t* U, const int8_t* V,
                                   void* y, int m_bits, int out_type, bool relu,
                                   const StageMults& out_mu, const MultTable& mm,
-                                  const ShiftTable* sh, int shape, hipStream_t st) {
+                                  const ShiftTable* sh, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;
   if (g.C == 0)   // an empty channel sum: y = 0 (K is a multiple of 16, so the size is one of 16 bytes)
     return launch_fill_zero(y, (long)g.N * g.H * g.W * g.K * (out_type == 0 ? 4 : 1), st);
   switch (g.m) {
-    case 2: return PerMCO<2>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, shape, st);
-    case 4: return PerMCO<4>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, shape, st);
-    case 6: return PerMCO<6>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, shape, st);
+    case 2: return PerMCO<2>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, st);
+    case 4: return PerMCO<4>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, st);
+    case 6: return PerMCO<6>::run(g, leg, U, V, y, m_bits, out_type, relu, out_mu, mm, sh, st);
   }
   return hipErrorInvalidValue;
+}
+
+long contract_output_blocks(const Geometry& g, int m_bits) {
+  switch (g.m) {
+    case 2: return PerMCO<2>::blocks(g, m_bits);
+    case 4: return PerMCO<4>::blocks(g, m_bits);
+    case 6: return PerMCO<6>::blocks(g, m_bits);
+  }
+  return 0;
 }
 
 hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, void* Mo,

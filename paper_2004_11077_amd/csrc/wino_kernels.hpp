@@ -48,7 +48,46 @@ struct Geometry {
   int m;        // output tile edge
   int TH, TW;   // tiles per image
   int T;        // total tiles
+  int frag;     // 1: U and V are in MFMA-fragment order (below), 0: rows [n*n][T or K][C]
+  // division of a tile index (< 2^30) by TW and by TW * TH as multiply-high and shift
+  uint32_t mul_tw, sh_tw, mul_im, sh_im;
 };
+
+// q = n / d for n < 2^30.  d a power of two: a shift (mul = 0).  Otherwise, with f = floor(log2 d),
+// q = (n * mul) >> (32 + f), mul = floor(2^(32 + f) / d) + 1 < 2^32: the excess
+// mul d - 2^(32 + f) is at most d < 2^(f + 1), so n times it stays below 2^(32 + f).
+inline void fast_div_setup(uint32_t d, uint32_t* mul, uint32_t* sh) {
+  uint32_t f = 0;
+  while ((2u << f) <= d) ++f;                      // f = floor(log2 d), d >= 1
+  *sh = f;
+  *mul = (d & (d - 1)) == 0 ? 0u : (uint32_t)((((unsigned long long)1 << (32 + f)) / d) + 1);
+}
+inline void geometry_set_divisors(Geometry& g) {
+  fast_div_setup((uint32_t)(g.TW > 0 ? g.TW : 1), &g.mul_tw, &g.sh_tw);
+  fast_div_setup((uint32_t)(g.TW * g.TH > 0 ? g.TW * g.TH : 1), &g.mul_im, &g.sh_im);
+}
+#if defined(__HIPCC__)
+// tile t -> (image b, tile row ty, tile column tx) with t = (b TH + ty) TW + tx, t < 2^30.
+__device__ __forceinline__ void tile_coords(const Geometry& g, int t, int& b, int& ty, int& tx) {
+  const uint32_t im = (uint32_t)(g.TW * g.TH);
+  b = (int)((g.mul_im ? __umulhi((uint32_t)t, g.mul_im) : (uint32_t)t) >> g.sh_im);
+  const uint32_t r = (uint32_t)t - (uint32_t)b * im;
+  ty = (int)((g.mul_tw ? __umulhi(r, g.mul_tw) : r) >> g.sh_tw);
+  tx = (int)(r - (uint32_t)ty * (uint32_t)g.TW);
+}
+#endif
+
+// Fragment order of a transformed operand X[p][row][c] (rows = tiles for U, output channels
+// for V): rows in groups of 16 (RG = ceil(rows / 16) groups), channels in chunks of 64
+// (NCH = ceil(C / 64) chunks); the 16 x 64 block of (group, chunk) is one contiguous KiB laid
+// out [c % 64 / 16][row % 16][c % 16], which is exactly the register layout of a 16x16x64
+// int8 MFMA operand: lane l of a wave reads bytes [16 l, 16 l + 16) of the block.
+//   offset(p, row, c) = ((p RG + row / 16) NCH + c / 64) 1024 + (c % 64 / 16) 256 + (row % 16) 16 + c % 16
+// Rows past the last one are never written (they only feed results that are discarded);
+// channels past C hold zeros in V (and anything in U).
+inline long frag_bytes(long n2, long rows, long C) {
+  return n2 * ((rows + 15) / 16) * ((C + 63) / 64) * 1024;
+}
 
 struct StageMults {
   MultTable inner;   // inner bracket of eq. 2 / eq. 4 (unused when !inner)
@@ -168,21 +207,23 @@ hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const
                                    const StageMults& mu, const ShiftTable* sh, hipStream_t st);
 
 // Contraction and output transform in one kernel, M kept in LDS (wino_conout.hpp);
-// m_bits 8 or 9, out_type 0 or 2, C > 0.  shape: 0 = block shape chosen from the problem
-// size, 1 = small blocks, 2 = large blocks.
+// m_bits 8 or 9, out_type 0 or 2, C > 0; U and V in rows or fragment order (g.frag).
 template <int M>
 struct PerMCO {
   static hipError_t run(const Geometry& g, bool legendre_inner, const int8_t* U, const int8_t* V,
                         void* y, int m_bits, int out_type, bool relu, const StageMults& out_mu,
-                        const MultTable& mm, const ShiftTable* sh, int shape, hipStream_t st);
+                        const MultTable& mm, const ShiftTable* sh, hipStream_t st);
+  static long blocks(const Geometry& g, int m_bits);
 };
+// Work groups launch_contract_output would start for this geometry.
+long contract_output_blocks(const Geometry& g, int m_bits);
 extern template struct PerMCO<2>;
 extern template struct PerMCO<4>;
 extern template struct PerMCO<6>;
 hipError_t launch_contract_output(const Geometry& g, bool legendre_inner, const int8_t* U,
                                   const int8_t* V, void* y, int m_bits, int out_type, bool relu,
                                   const StageMults& out_mu, const MultTable& mm,
-                                  const ShiftTable* sh, int shape, hipStream_t st);
+                                  const ShiftTable* sh, hipStream_t st);
 // Zero fill of `bytes` (a multiple of 16) at a 16-byte aligned device address, by a kernel.
 hipError_t launch_fill_zero(void* dst, long bytes, hipStream_t st);
 

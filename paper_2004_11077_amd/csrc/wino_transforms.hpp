@@ -340,8 +340,25 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
   const int tid = threadIdx.x;
   const long gid0 = (long)block * 256;
   const long KC = (long)g.K * g.C;
-  if (tid < 144)
-    *reinterpret_cast<v4i*>(s_w + tid * 16) = *reinterpret_cast<const v4i*>(w + gid0 * 9 + tid * 16);
+  // Fragment order: the block's 256 filters are 4 output channels x one 64-channel chunk
+  // (item 64 r + j = filter (4 kq + r, 64 chunk + j)): their taps are 4 runs of up to 576
+  // contiguous bytes, and a point's results are four 64-byte pieces of a fragment.  Filters
+  // past C (partial last chunk) are dead: zero taps in, nothing stored.
+  const int nch = (g.C + 63) >> 6;
+  const int kq = g.frag ? (int)(block / nch) : 0, chunk = g.frag ? (int)(block % nch) : 0;
+  const int cw = g.frag ? min(64, g.C - chunk * 64) : 64;      // channels of this chunk
+  if (tid < 144) {
+    const int8_t* src = w + gid0 * 9 + tid * 16;
+    bool ok = true;
+    if (g.frag) {
+      const int run = tid / 36, piece = tid % 36;
+      ok = piece * 16 < cw * 9;
+      src = w + ((long)(kq * 4 + run) * g.C + chunk * 64) * 9 + piece * 16;
+    }
+    v4i v = {0, 0, 0, 0};
+    if (ok) v = *reinterpret_cast<const v4i*>(src);
+    *reinterpret_cast<v4i*>(s_w + tid * 16) = v;
+  }
   __syncthreads();
   int wi[3][3];
   static_for<0, 3>([&](auto a) {
@@ -367,14 +384,26 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
     });
   });
   __syncthreads();
-  const int u = tid & 15, prow = tid >> 4;
+  int u = tid & 15;
+  const int prow = tid >> 4;
   int8_t* vb = V + gid0 + u * 16;
+  long pstride = KC;
+  bool sok = true;
+  if (g.frag) {
+    // lane -> unit transposed, so that the four lanes of a quad store 64 contiguous bytes:
+    // unit u = (filter row r = u / 4, 16-channel slice s = u % 4) of the block
+    u = ((u & 3) << 2) | (u >> 2);
+    const int r = u >> 2, sl = u & 3, k = kq * 4 + r;
+    vb = V + ((long)(k >> 4) * nch + chunk) * 1024 + sl * 256 + (k & 15) * 16;
+    pstride = ((long)(g.K + 15) >> 4) * nch * 1024;
+    sok = sl * 16 < cw;
+  }
 #pragma unroll
   for (int it = 0; it < (n2 + 15) / 16; ++it) {
     const int p = it * 16 + prow;
-    if (p < n2)
+    if (p < n2 && sok)
       __builtin_nontemporal_store(*reinterpret_cast<const v4i*>(s_v + p * 256 + u * 16),
-                                  reinterpret_cast<v4i*>(vb + (long)p * KC));
+                                  reinterpret_cast<v4i*>(vb + (long)p * pstride));
   }
 }
 
@@ -407,18 +436,26 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   // staging role of this lane: 16-byte unit `u` of the block's item range
   const int u = tid & 15, prow = tid >> 4;
   const long ug = gid0 + u * 16;
-  const bool uok = WHOLE || ug < total;
   int ut, uc;
+  bool uok = WHOLE || ug < total;
   if constexpr (WHOLE) {
     ut = (int)(gid0 / g.C);                       // uniform
     uc = (int)(gid0 - (long)ut * g.C) + u * 16;
+  } else if (g.frag) {
+    // Fragment order: the block's 256 items are 4 tiles x one 64-channel chunk (unit u = tile
+    // 4 tq + u / 4, channels 64 chunk + 16 (u % 4) ...): a quad of lanes loads 64 contiguous
+    // bytes of a pixel, and a point's results are four 64-byte pieces of a fragment.
+    const int nch = (g.C + 63) >> 6;
+    ut = (int)(block / nch) * 4 + (u >> 2);
+    uc = (int)(block % nch) * 64 + (u & 3) * 16;
+    uok = ut < g.T && uc < g.C;
+    if (!uok) ut = 0, uc = 0;
   } else {
     ut = uok ? (int)(ug / g.C) : 0;
     uc = uok ? (int)(ug - (long)ut * g.C) : 0;
   }
-  const int tx = ut % g.TW;
-  const int ty = (ut / g.TW) % g.TH;
-  const int b = ut / (g.TW * g.TH);
+  int tx, ty, b;
+  tile_coords(g, ut, b, ty, tx);
   const int8_t* xb = x + (long)b * g.H * g.W * g.C + uc;
 #pragma unroll
   for (int it = 0; it < (n2 + 15) / 16; ++it) {
@@ -466,12 +503,25 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   __syncthreads();
 
   int8_t* ub = U + (long)ut * g.C + uc;
+  long pstride = total;
+  int su = u;                                     // unit this lane stores
+  bool sok = uok;
+  if (g.frag) {
+    // lane -> unit transposed, so that the four lanes of a quad store 64 contiguous bytes
+    // (tiles 4 tq .. 4 tq + 3 of one 16-channel slice)
+    su = ((u & 3) << 2) | (u >> 2);
+    const int nch = (g.C + 63) >> 6;
+    const int st = (int)(block / nch) * 4 + (su >> 2), sc = (int)(block % nch) * 64 + (su & 3) * 16;
+    sok = st < g.T && sc < g.C;
+    ub = U + ((long)(st >> 4) * nch + (sc >> 6)) * 1024 + ((sc & 63) >> 4) * 256 + (st & 15) * 16;
+    pstride = ((long)(g.T + 15) >> 4) * nch * 1024;
+  }
 #pragma unroll
   for (int it = 0; it < (n2 + 15) / 16; ++it) {
     const int p = it * 16 + prow;
-    if (p < n2 && uok)
-      __builtin_nontemporal_store(*reinterpret_cast<const v4i*>(s_out + p * 256 + u * 16),
-                                  reinterpret_cast<v4i*>(ub + (long)p * total));
+    if (p < n2 && sok)
+      __builtin_nontemporal_store(*reinterpret_cast<const v4i*>(s_out + p * 256 + su * 16),
+                                  reinterpret_cast<v4i*>(ub + (long)p * pstride));
   }
 }
 
@@ -549,9 +599,8 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     t = active ? (int)(gid / g.K) : 0;
     k = active ? (int)(gid - (long)t * g.K) : 0;
   }
-  const int tx = t % g.TW;
-  const int ty = (t / g.TW) % g.TH;
-  const int b = t / (g.TW * g.TH);
+  int tx, ty, b;
+  tile_coords(g, t, b, ty, tx);
 
   int xi[n][n];
   if constexpr (sizeof(MT) == 1) {
@@ -647,11 +696,19 @@ static inline unsigned blocks_for(long items) { return (unsigned)((items + 255) 
 static inline bool whole_tiles(int channels, int H, int W) {
   return channels % 256 == 0 && (long)H * W * channels < (1L << 31);
 }
+// Work groups of the operand transforms: 256 consecutive items each in row order; in
+// fragment order one per (4 rows, 64-channel chunk).
+static inline unsigned weight_blocks(const Geometry& g) {
+  return g.frag ? (unsigned)(((long)g.K >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.K * g.C);
+}
+static inline unsigned input_blocks(const Geometry& g) {
+  return g.frag ? (unsigned)((((long)g.T + 3) >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.T * g.C);
+}
 
 template <int M>
 hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
                            const StageMults& mu, hipStream_t st) {
-  const unsigned nb = blocks_for((long)g.K * g.C);
+  const unsigned nb = weight_blocks(g);
   if (leg)
     wino_launch((k_weight_transform<M, true>), dim3(nb), dim3(256), st, w, V, g, mu);
   else
@@ -662,8 +719,8 @@ hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t*
 template <int M>
 hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st) {
-  const unsigned nb = blocks_for((long)g.T * g.C);
-  const bool whole = whole_tiles(g.C, g.H, g.W);
+  const unsigned nb = input_blocks(g);
+  const bool whole = !g.frag && whole_tiles(g.C, g.H, g.W);
   if (leg && whole)
     wino_launch((k_input_transform<M, true, true>), dim3(nb), dim3(256), st, x, U, g, mu);
   else if (leg)
@@ -679,8 +736,8 @@ template <int M>
 hipError_t PerM<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
                              const int8_t* w, int8_t* V, const StageMults& mu_in,
                              const StageMults& mu_w, hipStream_t st) {
-  const unsigned nb_in = blocks_for((long)g.T * g.C), nb_w = blocks_for((long)g.K * g.C);
-  const bool whole = whole_tiles(g.C, g.H, g.W);
+  const unsigned nb_in = input_blocks(g), nb_w = weight_blocks(g);
+  const bool whole = !g.frag && whole_tiles(g.C, g.H, g.W);
   const dim3 grid(nb_in + nb_w), bs(256);
   if (leg && whole)
     wino_launch((k_operand_transforms<M, true, true>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);

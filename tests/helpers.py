@@ -47,8 +47,14 @@ def gpu_layer(xq, wq, scales, m=4, base="legendre", bits_hadamard=8, inner_quant
         ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
         wn.wino_conv2d(desc, x, w, y, sc, ws)
         torch.cuda.synchronize()
-        V = ws[:n2 * K * C].view(torch.int8).reshape(n2, K, C)
-        return {"V": V.cpu().numpy(), "y": y.cpu().numpy()}
+        if "contraction_output" in wn.wino_conv2d_launches(desc):
+            # two-kernel form: the workspace holds V in fragment order
+            fd = wn.ConvDesc(N, H, W, C, K, m=m, operand_layout=wn.LAYOUT_FRAGMENTS)
+            vb = wn.wino_operand_bytes(fd)[0]
+            Vn = wn.defragment(ws[:vb].view(torch.int8).cpu().numpy(), n2, K, C)
+        else:
+            Vn = ws[:n2 * K * C].view(torch.int8).reshape(n2, K, C).cpu().numpy()
+        return {"V": Vn, "y": y.cpu().numpy()}
     if whole:
         nbytes = wn.wino_workspace_bytes(desc)
         ws = torch.empty(nbytes, dtype=torch.uint8, device=dev)

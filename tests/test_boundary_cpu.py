@@ -142,9 +142,15 @@ def test_kernel_selection_and_workspace_of_the_whole_layer_call():
     wide = dict(m=4)
     cases = [
         (wn.FUSED_OFF, {}, ["operand_transforms", "contraction", "output_transform"], V + U + M),
-        (wn.FUSED_AUTO, {}, ["operand_transforms", "contraction_output"], V + U),
+        (wn.FUSED_AUTO, {}, ["operand_transforms", "contraction", "output_transform"], V + U + M),
+        (wn.FUSED_AUTO, dict(bits_hadamard=9), ["operand_transforms", "contraction_output"], V + U),
         (wn.FUSED_ON, {}, ["operand_transforms", "contraction_output"], V + U),
-        (wn.FUSED_AUTO, dict(weights_pretransformed=1), ["input_transform", "contraction_output"], U),
+        (wn.FUSED_AUTO, dict(weights_pretransformed=1, operand_layout=wn.LAYOUT_FRAGMENTS),
+         ["input_transform", "contraction_output"], U),
+        # a pretransformed V in rows is slow in the two-kernel form: AUTO runs one kernel per stage
+        (wn.FUSED_AUTO, dict(weights_pretransformed=1), ["input_transform", "contraction",
+                                                         "output_transform"], U + M),
+        (wn.FUSED_ON, dict(weights_pretransformed=1), ["input_transform", "contraction_output"], U),
         (wn.FUSED_AUTO, dict(bits_hadamard=32), ["operand_transforms", "contraction",
                                                  "output_transform"], V + U + 4 * M),
     ]
@@ -155,16 +161,31 @@ def test_kernel_selection_and_workspace_of_the_whole_layer_call():
     narrow = wn.ConvDesc(128, 32, 32, 64, 64, m=4, fused=wn.FUSED_AUTO)
     assert wn.wino_conv2d_launches(narrow) == ["weight_transform", "fused_layer"]
     assert wn.wino_workspace_bytes(narrow) == r256(36 * 64 * 64)
+    few = wn.ConvDesc(256, 4, 4, 512, 512, m=4, fused=wn.FUSED_AUTO)   # 8 x 16 blocks: too few
+    assert wn.wino_conv2d_launches(few) == ["operand_transforms", "contraction", "output_transform"]
     f6 = wn.ConvDesc(2, 8, 8, 32, 32, m=6, fused=wn.FUSED_ON)          # no single kernel for F(6,3)
     assert wn.wino_conv2d_launches(f6) == ["operand_transforms", "contraction_output"]
     assert wn.wino_conv2d_launches(wn.ConvDesc(0, 8, 8, 16, 16)) == []
+    # fragment order pads tiles to 16 and channels to 64
+    fr = wn.ConvDesc(3, 9, 7, 48, 80, m=4, operand_layout=wn.LAYOUT_FRAGMENTS)       # T = 18
+    assert wn.wino_operand_bytes(fr) == (36 * 5 * 1 * 1024, 36 * 2 * 1 * 1024)
+    assert wn.wino_operand_bytes(wn.ConvDesc(3, 9, 7, 48, 80, m=4)) == (36 * 80 * 48, 36 * 18 * 48)
+    assert wn.wino_preferred_operand_layout(wn.ConvDesc(256, 8, 8, 256, 256)) == wn.LAYOUT_FRAGMENTS
+    assert wn.wino_preferred_operand_layout(narrow) == wn.LAYOUT_ROWS
+    with pytest.raises(wn.WinoError) as e:       # a V in fragment order needs the two-kernel form
+        wn.wino_workspace_bytes(wn.ConvDesc(128, 32, 32, 64, 64, weights_pretransformed=1,
+                                            operand_layout=wn.LAYOUT_FRAGMENTS))
+    assert e.value.code == -2
+    with pytest.raises(wn.WinoError) as e:
+        wn.wino_workspace_bytes(wn.ConvDesc(1, 8, 8, 16, 16, operand_layout=5))
+    assert e.value.code == -1
     wn.wino_set_option(wn.OPT_AUTO_CONOUT, 0)
     try:
-        d = wn.ConvDesc(256, 8, 8, 256, 256, m=4, fused=wn.FUSED_AUTO)
+        d = wn.ConvDesc(256, 8, 8, 256, 256, m=4, bits_hadamard=9, fused=wn.FUSED_AUTO)
         assert wn.wino_conv2d_launches(d) == ["operand_transforms", "contraction", "output_transform"]
     finally:
         wn.wino_set_option(wn.OPT_AUTO_CONOUT, 1)
-    for opt, val in [(7, 0), (wn.OPT_CONOUT_SHAPE, 3), (wn.OPT_CONOUT_SHAPE, -1)]:
+    for opt, val in [(7, 0), (0, 1)]:
         with pytest.raises(wn.WinoError) as e:
             wn.wino_set_option(opt, val)
         assert e.value.code == -1

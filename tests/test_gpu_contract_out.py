@@ -4,9 +4,11 @@ eq. 3 / eq. 4 in one launch (the cast contraction result M stays in on-chip memo
 Bar: int8 outputs bit-exact against the oracle (an int8 y that matches bit for bit also pins
 the M codes it was computed from, since every one of them feeds the integer brackets); fp32
 outputs within 1e-5 * max|y_oracle|, and bit-identical to what wino_contract followed by
-wino_output_transform give on the same U and V (the arithmetic is the same).  Both block
-shapes of the kernel are forced in turn; shapes are chosen so that tiles, output channels and
-input channels all end in partial blocks / chunks.
+wino_output_transform give on the same U and V (the arithmetic is the same).  The operands
+are given in rows and in fragment order (the
+fragment-order tensors must hold exactly the row-order codes, zeros in V's channel padding);
+shapes are chosen so that tiles, output channels and input channels all end in partial blocks
+/ chunks.
 """
 import numpy as np
 import pytest
@@ -17,9 +19,9 @@ from helpers import assert_layer_parity, gpu_layer, oracle_layer, small_layer
 pytestmark = pytest.mark.gpu
 
 
-def stage_call(xq, wq, sc, shape_opt, **kw):
-    """U and V from the stage calls, then y from wino_contract_output and, for comparison,
-    from wino_contract + wino_output_transform."""
+def stage_call(xq, wq, sc, frag=False, **kw):
+    """U and V from the stage calls (rows, or fragment order when ``frag``), then y from
+    wino_contract_output and, for comparison, from wino_contract + wino_output_transform."""
     import torch
     import paper_2004_11077_amd as wn
     dev = torch.device("cuda:0")
@@ -27,11 +29,12 @@ def stage_call(xq, wq, sc, shape_opt, **kw):
     K = wq.shape[0]
     out_type = kw.get("out_type", "f32")
     bh = kw.get("bits_hadamard", 8)
-    desc = wn.ConvDesc(N, H, W, C, K, m=kw["m"],
-                       base=wn.BASE_LEGENDRE if kw["base"] == "legendre" else wn.BASE_CANONICAL,
-                       bits_hadamard=bh, inner_quant=int(kw.get("inner_quant", True)),
-                       out_type=wn.OUT_I8 if out_type == "i8" else wn.OUT_F32,
-                       relu=int(kw.get("relu", False)))
+    common = dict(m=kw["m"],
+                  base=wn.BASE_LEGENDRE if kw["base"] == "legendre" else wn.BASE_CANONICAL,
+                  bits_hadamard=bh, inner_quant=int(kw.get("inner_quant", True)),
+                  out_type=wn.OUT_I8 if out_type == "i8" else wn.OUT_F32,
+                  relu=int(kw.get("relu", False)))
+    desc = wn.ConvDesc(N, H, W, C, K, **common)
     n2, T = desc.n ** 2, desc.tiles
     s = wn.Scales.from_dict(sc)
     x = torch.from_numpy(np.ascontiguousarray(xq, dtype=np.int8)).to(dev)
@@ -43,14 +46,25 @@ def stage_call(xq, wq, sc, shape_opt, **kw):
     y = torch.full((N, H, W, K), 77, dtype=ydt, device=dev)
     y2 = torch.full((N, H, W, K), 55, dtype=ydt, device=dev)
     wn.wino_transform_operands(desc, x, U, w, V, s)
-    wn.wino_set_option(wn.OPT_CONOUT_SHAPE, shape_opt)
-    try:
-        wn.wino_contract_output(desc, U, V, y, s)
-    finally:
-        wn.wino_set_option(wn.OPT_CONOUT_SHAPE, 0)
+    Uc, Vc, dc = U, V, desc
+    if frag:
+        dc = wn.ConvDesc(N, H, W, C, K, operand_layout=wn.LAYOUT_FRAGMENTS, **common)
+        vb, ub = wn.wino_operand_bytes(dc)
+        Uc = torch.full((ub,), 77, dtype=torch.int8, device=dev)
+        Vc = torch.full((vb,), 77, dtype=torch.int8, device=dev)
+        wn.wino_transform_operands(dc, x, Uc, w, Vc, s)
+    wn.wino_contract_output(dc, Uc, Vc, y, s)
     wn.wino_contract(desc, U, V, M, s)
     wn.wino_output_transform(desc, M, y2, s)
     torch.cuda.synchronize()
+    if frag:
+        # the same codes, in fragment order; channels of V past C are zeros
+        Un = wn.defragment(Uc.cpu().numpy(), n2, T, C)
+        Vn = wn.defragment(Vc.cpu().numpy(), n2, K, C)
+        assert np.array_equal(Un, U.cpu().numpy()) and np.array_equal(Vn, V.cpu().numpy())
+        if C % 64:
+            pad = Vc.cpu().numpy().reshape(n2, K // 16, -1, 4, 16, 16)[:, :, -1, (C % 64) // 16:]
+            assert not pad.any()
     return {"U": U.cpu().numpy(), "V": V.cpu().numpy(), "y": y.cpu().numpy()}, y2.cpu().numpy()
 
 
@@ -70,15 +84,15 @@ CASES = [
 ]
 
 
-@pytest.mark.parametrize("shape_opt", [1, 2])
+@pytest.mark.parametrize("frag", [False, True])
 @pytest.mark.parametrize("m,base,shape,bh,out_type,relu,pp", CASES)
 def test_stage_call_matches_the_oracle_and_the_two_stage_calls(m, base, shape, bh, out_type, relu,
-                                                               pp, shape_opt):
+                                                               pp, frag):
     N, H, W, C, K = shape
     xq, wq, s_x, s_w = small_layer(N, H, W, C, K, seed=700 + m + C, outliers=0.01 if pp else 0.0)
     kw = dict(m=m, base=base, bits_hadamard=bh, out_type=out_type, relu=relu, per_point=pp)
     ora, sc = oracle_layer(xq, wq, s_x, s_w, **kw)
-    got, y_two = stage_call(xq, wq, sc, shape_opt, **kw)
+    got, y_two = stage_call(xq, wq, sc, frag=frag, **kw)
     assert_layer_parity(ora, got, out_type)
     assert np.array_equal(got["y"], y_two)
 
@@ -87,7 +101,7 @@ def test_legendre_without_inner_casts():
     xq, wq, s_x, s_w = small_layer(2, 8, 8, 32, 32, seed=733)
     kw = dict(m=4, base="legendre", inner_quant=False, out_type="i8")
     ora, sc = oracle_layer(xq, wq, s_x, s_w, **kw)
-    got, y_two = stage_call(xq, wq, sc, 0, **kw)
+    got, y_two = stage_call(xq, wq, sc, **kw)
     assert_layer_parity(ora, got, "i8")
 
 
@@ -107,14 +121,17 @@ def whole_layer(xq, wq, sc, mode, pretransformed=False, **kw):
     w = torch.from_numpy(np.ascontiguousarray(wq, dtype=np.int8)).to(dev)
     y = torch.full((N, H, W, K), 77, dtype=torch.int8 if out_type == "i8" else torch.float32,
                    device=dev)
-    second = w
+    second, layout = w, wn.LAYOUT_ROWS
     if pretransformed:
-        n2 = (kw["m"] + 2) ** 2
-        second = torch.empty((n2, K, C), dtype=torch.int8, device=dev)
-        wn.wino_weight_transform(wn.ConvDesc(N, H, W, C, K, **common), w, second, s)
+        layout = (wn.LAYOUT_FRAGMENTS if mode == wn.FUSED_ON else
+                  wn.wino_preferred_operand_layout(wn.ConvDesc(N, H, W, C, K, **common)))
+        vdesc = wn.ConvDesc(N, H, W, C, K, operand_layout=layout, **common)
+        second = torch.empty((wn.wino_operand_bytes(vdesc)[0],), dtype=torch.int8, device=dev)
+        wn.wino_weight_transform(vdesc, w, second, s)
     desc = wn.ConvDesc(N, H, W, C, K, fused=mode, weights_pretransformed=int(pretransformed),
-                       **common)
-    assert "contraction_output" in wn.wino_conv2d_launches(desc)
+                       operand_layout=layout, **common)
+    if mode == wn.FUSED_ON:
+        assert "contraction_output" in wn.wino_conv2d_launches(desc)
     ws = torch.empty(wn.wino_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     wn.wino_conv2d(desc, x, second, y, s, ws)
     torch.cuda.synchronize()
@@ -142,12 +159,12 @@ def test_whole_layer_call_on_the_benchmark_configurations(name):
         assert_layer_parity(ora, got, out_type)
 
 
-def test_large_block_shape_is_taken_by_itself_on_a_large_batch():
-    """Enough tiles for the large block shape to be chosen without forcing it (cfg4a's layer
-    with 8 times the tiles per launch), whole-layer call against the oracle."""
+def test_many_tile_blocks_per_compute_unit():
+    """Several rounds of work groups per compute unit (4096 tiles), whole-layer call against
+    the oracle."""
     import paper_2004_11077_amd as wn
     xq, wq, s_x, s_w = small_layer(64, 32, 32, 128, 128, seed=741)       # T = 4096
     kw = dict(m=4, base="legendre", out_type="i8", relu=True)
     ora, sc = oracle_layer(xq, wq, s_x, s_w, **kw)
-    got = whole_layer(xq, wq, sc, wn.FUSED_AUTO, **kw)
+    got = whole_layer(xq, wq, sc, wn.FUSED_ON, **kw)
     assert_layer_parity(ora, got, "i8")

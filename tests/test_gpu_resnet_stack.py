@@ -40,11 +40,13 @@ def run_as_benchmark(xq, wq, scales):
     sc = wn.Scales.from_dict(scales)
     x = torch.from_numpy(np.ascontiguousarray(xq, dtype=np.int8)).to(dev)
     w = torch.from_numpy(np.ascontiguousarray(wq, dtype=np.int8)).to(dev)
-    desc = wn.ConvDesc(N, H, W, C, K, m=4, out_type=wn.OUT_I8, relu=1)
-    V = torch.empty((36, K, C), dtype=torch.int8, device=dev)
+    layout = wn.wino_preferred_operand_layout(wn.ConvDesc(N, H, W, C, K, m=4, out_type=wn.OUT_I8,
+                                                          relu=1))
+    desc = wn.ConvDesc(N, H, W, C, K, m=4, out_type=wn.OUT_I8, relu=1, operand_layout=layout)
+    V = torch.empty((wn.wino_operand_bytes(desc)[0],), dtype=torch.int8, device=dev)
     wn.wino_weight_transform(desc, w, V, sc)
     run = wn.ConvDesc(N, H, W, C, K, m=4, out_type=wn.OUT_I8, relu=1, weights_pretransformed=1,
-                      fused=wn.FUSED_AUTO)
+                      fused=wn.FUSED_AUTO, operand_layout=layout)
     ws = torch.empty(wn.wino_workspace_bytes(run), dtype=torch.uint8, device=dev)
     y = torch.full((N, H, W, K), 77, dtype=torch.int8, device=dev)
     wn.wino_conv2d(run, x, V, y, sc, ws)
