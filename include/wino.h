@@ -192,6 +192,22 @@ int wino_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes);
 int wino_conv2d(const wino_conv_desc_t* d, const void* x, const void* w_or_V, void* y,
                 const wino_scales_t* s, void* workspace, size_t ws_bytes, void* hip_stream);
 
+/* wino_conv2d for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, arithmetic and results as wino_conv2d;
+ * the workspace is a device array inside the library, WINO_NOALLOC_MAX_BYTES
+ * per GPU, held from the moment the library is loaded until the process ends.
+ * The call allocates nothing (no hipMalloc / hipFree, no allocating library
+ * routine) and never synchronises.  Its first call on a device looks up that
+ * device's copy of the array (hipGetSymbolAddress, not a stream operation).
+ * All calls on one GPU share the array: calls on one stream are ordered and
+ * safe, calls that overlap in time on the same GPU race.
+ * Errors: those of wino_conv2d; EWORKSPACE when wino_workspace_bytes(d)
+ * exceeds WINO_NOALLOC_MAX_BYTES (all benchmark layers need at most 38 MiB). */
+#define WINO_NOALLOC_MAX_BYTES (64u << 20)
+int wino_conv2d_noalloc(const wino_conv_desc_t* d, const void* x, const void* w_or_V, void* y,
+                        const wino_scales_t* s, void* hip_stream);
+
 /* The four stages on their own (same descriptor and scales; device pointers).
  * Eq. 1 / eq. 2: w -> V. */
 int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,

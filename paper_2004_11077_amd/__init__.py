@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     BASE_CANONICAL, BASE_CHEBYSHEV, BASE_HERMITE, BASE_LEGENDRE, FUSED_AUTO, FUSED_OFF, FUSED_ON,
     OUT_F32, OUT_I32, OUT_I8, MAT_NAMES, PROBE_MFMA_BF16, PROBE_MFMA_I8, PROBE_VALU_MAD24, ConvDesc, FlexGrads, FlexMatrices, Matrices, Scales, WinoError,
     lib_path, wino_backward, wino_backward_dv_parts, wino_backward_workspace_bytes, wino_calibrate,
-    wino_calibrate_workspace_bytes, wino_contract, wino_contract_output, wino_conv2d,
+    wino_calibrate_workspace_bytes, wino_contract, wino_contract_output, wino_conv2d, wino_conv2d_noalloc, NOALLOC_MAX_BYTES,
     wino_conv2d_launches, wino_set_option, wino_operand_bytes, wino_preferred_operand_layout, defragment, OPT_AUTO_CONOUT,
     LAYOUT_FRAGMENTS, LAYOUT_ROWS,
     wino_flex_backward, wino_flex_backward_workspace_bytes, wino_flex_calibrate, wino_flex_conv2d, wino_flex_input_transform,

@@ -13,7 +13,7 @@ MAT_NAMES = ("G", "BT", "AT", "PT", "PINVT", "GP", "BPT", "APT")
 EXPORTS = ("wino_make_matrices", "wino_free_matrices", "wino_get_matrix", "wino_get_int_form",
            "wino_workspace_bytes", "wino_operand_bytes", "wino_preferred_operand_layout",
            "wino_calibrate_workspace_bytes", "wino_calibrate",
-           "wino_conv2d", "wino_weight_transform",
+           "wino_conv2d", "wino_conv2d_noalloc", "wino_weight_transform",
            "wino_input_transform", "wino_transform_operands", "wino_contract",
            "wino_output_transform", "wino_contract_output", "wino_conv2d_launches",
            "wino_set_option", "wino_flex_weight_transform", "wino_flex_input_transform",
@@ -146,6 +146,7 @@ def _load():
     lib.wino_operand_bytes.argtypes = [dp, C.POINTER(C.c_size_t), C.POINTER(C.c_size_t)]
     lib.wino_preferred_operand_layout.argtypes = [dp, ip]
     lib.wino_conv2d.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
+    lib.wino_conv2d_noalloc.argtypes = [dp, vp, vp, vp, sp, vp]
     lib.wino_calibrate_workspace_bytes.argtypes = [dp, C.POINTER(C.c_size_t)]
     lib.wino_calibrate.argtypes = [dp, vp, vp, vp, sp, vp, C.c_size_t, vp]
     lib.wino_weight_transform.argtypes = [dp, vp, vp, sp, vp]
@@ -318,6 +319,18 @@ def wino_conv2d(desc, x, w_or_V, y, scales, workspace, stream=None):
     _check(_load().wino_conv2d(C.byref(desc), _ptr(x), _ptr(w_or_V), _ptr(y), C.byref(sc),
                                _ptr(workspace), workspace.numel() * workspace.element_size(),
                                _stream(stream)))
+    return y
+
+
+NOALLOC_MAX_BYTES = 64 << 20
+
+
+def wino_conv2d_noalloc(desc, x, w_or_V, y, scales, stream=None):
+    """Whole layer with the library's built-in workspace (no allocation, no workspace argument);
+    layers needing more than NOALLOC_MAX_BYTES of workspace are rejected."""
+    sc = _scales(scales)
+    _check(_load().wino_conv2d_noalloc(C.byref(desc), _ptr(x), _ptr(w_or_V), _ptr(y), C.byref(sc),
+                                       _stream(stream)))
     return y
 
 

@@ -17,7 +17,7 @@ OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libwino.so")
 
 HIP_SOURCES = ["wino_kernels.hip", "wino_transforms_f2.hip", "wino_transforms_f4.hip",
-               "wino_transforms_f6.hip", "wino_fp32.hip", "wino_fused.hip", "wino_conout_f2.hip", "wino_conout_f4.hip", "wino_conout_f6.hip",
+               "wino_transforms_f6.hip", "wino_fp32.hip", "wino_fused.hip", "wino_noalloc.hip", "wino_conout_f2.hip", "wino_conout_f4.hip", "wino_conout_f6.hip",
                "wino_calibrate_f2.hip", "wino_calibrate_f4.hip", "wino_calibrate_f6.hip",
                "wino_flex_f2.hip", "wino_flex_f4.hip", "wino_flex_f6.hip",
                "wino_backward.hip", "wino_flex_backward_f2.hip", "wino_flex_backward_f4.hip",

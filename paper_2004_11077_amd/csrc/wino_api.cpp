@@ -22,6 +22,22 @@ namespace {
 
 thread_local std::string g_err;
 
+}  // namespace
+
+namespace wino {
+int report_error(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+}  // namespace wino
+
+namespace {
+
 int fail(int code, const char* fmt, ...) {
   char buf[512];
   va_list ap;

@@ -28,6 +28,10 @@ inline void wino_launch(K kernel, dim3 grid, dim3 block, hipStream_t st, Args...
     hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
 }
 
+// Records the text of a failure for wino_last_error() on this thread and returns `code`
+// (for the parts of the C ABI that live outside wino_api.cpp).
+int report_error(int code, const char* fmt, ...);
+
 constexpr int kMaxPts = 64;   // n*n for n = 8
 
 // fp32 multipliers of one cast, indexed [i*cols + j] (Section 4.2 cast after a

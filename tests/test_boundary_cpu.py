@@ -134,6 +134,18 @@ def test_stage_calls_reject_bad_arguments_before_any_launch():
     assert lib.wino_contract_output(C.byref(d), fake, fake, None, C.byref(s), None) == -1
 
 
+def test_no_alloc_call_rejects_oversized_layers_before_touching_the_device():
+    lib = binding._load()
+    fake = C.c_void_p(4096)
+    s = wn.Scales.from_dict({})
+    big = wn.ConvDesc(1024, 32, 32, 64, 64, m=4)
+    assert wn.wino_workspace_bytes(big) > wn.NOALLOC_MAX_BYTES
+    assert lib.wino_conv2d_noalloc(C.byref(big), fake, fake, fake, C.byref(s), None) == -4
+    assert b"scratch" in lib.wino_last_error()
+    bad = wn.ConvDesc(1, 8, 8, 12, 16)
+    assert lib.wino_conv2d_noalloc(C.byref(bad), fake, fake, fake, C.byref(s), None) == -1
+
+
 def test_kernel_selection_and_workspace_of_the_whole_layer_call():
     """Which launches wino_conv2d makes, and the workspace that goes with them."""
     n2, T = 36, 1024
