@@ -44,8 +44,8 @@ enum {
 enum {
   WINO_BASE_CANONICAL = 0,
   WINO_BASE_LEGENDRE = 1,
-  WINO_BASE_CHEBYSHEV = 2, /* wino_make_matrices only */
-  WINO_BASE_HERMITE = 3    /* wino_make_matrices only */
+  WINO_BASE_CHEBYSHEV = 2, /* monic Chebyshev polynomials (first kind)    */
+  WINO_BASE_HERMITE = 3    /* monic Hermite polynomials (probabilists')   */
 };
 enum { WINO_OUT_F32 = 0, WINO_OUT_I32 = 1, WINO_OUT_I8 = 2 };
 enum { WINO_FUSED_OFF = 0, WINO_FUSED_ON = 1, WINO_FUSED_AUTO = 2 };
@@ -84,8 +84,7 @@ typedef struct wino_matrices wino_matrices_t;      /* opaque, host memory */
  * base = WINO_BASE_LEGENDRE: P^T rows are the monic Legendre polynomials;
  * WINO_BASE_CHEBYSHEV / WINO_BASE_HERMITE: the monic Chebyshev (first kind) /
  * Hermite (probabilists') polynomials, the alternatives Section 4.1 names;
- * base = WINO_BASE_CANONICAL: P = I.  m+r-1 <= 8.  (The convolution kernels
- * are built for the canonical and the Legendre base.)
+ * base = WINO_BASE_CANONICAL: P = I.  m+r-1 <= 8.
  * On success *out owns a host handle to be released with wino_free_matrices.
  * Errors: EINVAL (null, sizes, zero denominator, duplicate point),
  * EUNSUPPORTED (m+r-1 > 8), EOVERFLOW (an int64 rational overflowed). */
@@ -107,7 +106,12 @@ typedef struct {
   int N, H, W, C, K;          /* C and K multiples of 16                          */
   int m, r;                   /* (2,3), (4,3) or (6,3); standard point sets
                                  {0,1,-1}, {0,1,-1,2,-2}, {0,1,-1,2,-2,1/2,-1/2}  */
-  int base;                   /* WINO_BASE_*                                      */
+  int base;                   /* WINO_BASE_*.  Chebyshev and Hermite (the other
+                                 bases Section 4.1 names; eq. 4 with their P):
+                                 the four stage calls, wino_transform_operands
+                                 and wino_conv2d with one kernel per stage,
+                                 int8 path, per-tensor scales; every other call
+                                 and variant is EUNSUPPORTED for them             */
   int bits_in;                /* 8: int8 path; 32: fp32 path without any cast: x, w,
                                  U, V, M, y are float in the same layouts, scales
                                  are ignored (may be null), output is fp32        */

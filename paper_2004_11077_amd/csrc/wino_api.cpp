@@ -71,17 +71,26 @@ struct Stages {
   const IMat *G, *BT, *AT, *PinvT, *Pinv, *GP, *BPT, *APT;
 };
 
-template <int M>
+template <int M, int BASE>
 Stages stages_of() {
-  using TB = Tab<M>;
+  using TB = Tab<M, BASE>;
   return Stages{&TB::G, &TB::BT, &TB::AT, &TB::PinvT, &TB::Pinv, &TB::GP, &TB::BPT, &TB::APT};
 }
 
-bool stages_for(int m, Stages* s) {
+template <int M>
+Stages stages_of_base(int base) {
+  switch (base) {
+    case WINO_BASE_CHEBYSHEV: return stages_of<M, 2>();
+    case WINO_BASE_HERMITE: return stages_of<M, 3>();
+  }
+  return stages_of<M, 1>();     // canonical: G, B^T, A^T are the same in every base
+}
+
+bool stages_for(int m, int base, Stages* s) {
   switch (m) {
-    case 2: *s = stages_of<2>(); return true;
-    case 4: *s = stages_of<4>(); return true;
-    case 6: *s = stages_of<6>(); return true;
+    case 2: *s = stages_of_base<2>(base); return true;
+    case 4: *s = stages_of_base<4>(base); return true;
+    case 6: *s = stages_of_base<6>(base); return true;
   }
   return false;
 }
@@ -114,7 +123,8 @@ int check_per_point(const wino_conv_desc_t* d, const wino_scales_t* s);
 struct Plan {
   Geometry g;
   Stages st;
-  bool two_brackets;   // Legendre with casts on the inner brackets
+  bool two_brackets;   // a polynomial base with casts on the inner brackets
+  int br;              // 0: one bracket per stage; else the base of the two-bracket form (WINO_BASE_*)
   int m_bits;
   bool fp32;           // bits_in = 32: float tensors, no cast anywhere
   bool legendre;
@@ -124,7 +134,7 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
   if (!d) return fail(WINO_EINVAL, "null descriptor");
   if (d->r != 3 || !(d->m == 2 || d->m == 4 || d->m == 6))
     return fail(WINO_EUNSUPPORTED, "F(%d,%d) not built: m must be 2, 4 or 6 and r = 3", d->m, d->r);
-  if (d->base != WINO_BASE_CANONICAL && d->base != WINO_BASE_LEGENDRE)
+  if (d->base < WINO_BASE_CANONICAL || d->base > WINO_BASE_HERMITE)
     return fail(WINO_EINVAL, "unknown base %d", d->base);
   if (d->bits_in != 8 && d->bits_in != 32)
     return fail(WINO_EUNSUPPORTED, "bits_in must be 8 or 32 (got %d)", d->bits_in);
@@ -156,10 +166,13 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
   p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T,
                   d->operand_layout == WINO_LAYOUT_FRAGMENTS ? 1 : 0, 0, 0, 0, 0};
   geometry_set_divisors(p->g);
-  if (!stages_for(d->m, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
-  p->two_brackets = d->base == WINO_BASE_LEGENDRE && d->inner_quant != 0;
+  if (!stages_for(d->m, d->base, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
+  p->two_brackets = d->base != WINO_BASE_CANONICAL && d->inner_quant != 0;
+  p->br = p->two_brackets ? d->base : 0;
+  if (p->fp32 && d->base > WINO_BASE_LEGENDRE)
+    return fail(WINO_EUNSUPPORTED, "the fp32 path is built for the canonical and the Legendre base");
   p->m_bits = p->fp32 ? 32 : d->bits_hadamard;
-  p->legendre = d->base == WINO_BASE_LEGENDRE;
+  p->legendre = d->base != WINO_BASE_CANONICAL;
   if (d->out_type == WINO_OUT_I32) {
     const IMat& a = *p->st.AT;
     bool integer = !p->two_brackets;
@@ -192,6 +205,14 @@ int clear_v_padding(const Plan& p, void* V, void* hip_stream) {
   if (!p.g.frag || p.g.C % 64 == 0 || (long)p.g.K * p.g.C == 0) return WINO_OK;
   hipError_t e = launch_fill_zero(V, (long)v_bytes_of(p, true), (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "zero fill of V");
+}
+
+// The Chebyshev and Hermite bases run in the four stage kernels (and the whole-layer call
+// built on them); the other variants are built for the canonical and the Legendre base.
+int legendre_only(const Plan& p, const char* who) {
+  return p.br > WINO_BASE_LEGENDRE
+             ? fail(WINO_EUNSUPPORTED, "%s is built for the canonical and the Legendre base", who)
+             : WINO_OK;
 }
 
 int rows_only(const Plan& p, const char* who) {
@@ -322,7 +343,8 @@ int g_opt_auto_conout = 1;   // AUTO may take the contraction + output kernel
 // int8 output; the single-kernel variant additionally needs m = 2 or 4.  C = 0 (an empty
 // channel sum, y = 0) always runs stage by stage.
 bool conout_covers(const wino_conv_desc_t* d, const Plan& p) {
-  return !(p.fp32 || p.m_bits == 32 || d->out_type == WINO_OUT_I32 || d->C == 0);
+  return !(p.fp32 || p.m_bits == 32 || d->out_type == WINO_OUT_I32 || d->C == 0 ||
+           p.br > WINO_BASE_LEGENDRE);
 }
 bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
   return conout_covers(d, p) && d->m != 6;
@@ -357,7 +379,8 @@ int select_path(const wino_conv_desc_t* d, const Plan& p, Path* path) {
   if (d->fused == WINO_FUSED_ON) {
     if (!conout_covers(d, p))
       return fail(WINO_EUNSUPPORTED, "the fused variants cover the int8 path with bits_hadamard "
-                                     "8 or 9 and fp32 or int8 output");
+                                     "8 or 9 and fp32 or int8 output, in the canonical and the "
+                                     "Legendre base");
     *path = (fused_all_covers(d, p) && d->C <= 64 && !p.g.frag) ? kPathFusedAll : kPathConOut;
     return WINO_OK;
   }
@@ -680,7 +703,7 @@ int wino_weight_transform(const wino_conv_desc_t* d, const void* w, void* V,
   StageMults mu;
   if (int rc = weight_mults(p, s, &mu)) return rc;
   if (int rc = clear_v_padding(p, V, hip_stream)) return rc;
-  hipError_t e = launch_weight_transform(p.g, p.two_brackets, (const int8_t*)w, (int8_t*)V, mu,
+  hipError_t e = launch_weight_transform(p.g, p.br, (const int8_t*)w, (int8_t*)V, mu,
                                          (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "weight transform launch");
 }
@@ -703,7 +726,7 @@ int wino_input_transform(const wino_conv_desc_t* d, const void* x, void* U,
   if (int rc = check_per_point(d, s)) return rc;
   StageMults mu;
   if (int rc = input_mults(p, s, &mu)) return rc;
-  hipError_t e = launch_input_transform(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U, mu,
+  hipError_t e = launch_input_transform(p.g, p.br, (const int8_t*)x, (int8_t*)U, mu,
                                         (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "input transform launch");
 }
@@ -731,7 +754,7 @@ int wino_transform_operands(const wino_conv_desc_t* d, const void* x, void* U, c
   if (int rc = input_mults(p, s, &mu_in)) return rc;
   if (int rc = weight_mults(p, s, &mu_w)) return rc;
   if (int rc = clear_v_padding(p, V, hip_stream)) return rc;
-  hipError_t e = launch_operand_transforms(p.g, p.two_brackets, (const int8_t*)x, (int8_t*)U,
+  hipError_t e = launch_operand_transforms(p.g, p.br, (const int8_t*)x, (int8_t*)U,
                                            (const int8_t*)w, (int8_t*)V, mu_in, mu_w,
                                            (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "operand transforms launch");
@@ -782,10 +805,12 @@ int wino_output_transform(const wino_conv_desc_t* d, const void* M, void* y,
   if (int rc = aligned(M, 16, "M")) return rc;
   if (int rc = aligned(y, 16, "y")) return rc;
   if (int rc = check_per_point(d, s)) return rc;
+  if (p.br > WINO_BASE_LEGENDRE && s->per_point)
+    return fail(WINO_EUNSUPPORTED, "per-point scales are built for the canonical and the Legendre base");
   StageMults mu;
   ShiftTable sh;
   if (int rc = output_mults(p, d, s, &mu, &sh)) return rc;
-  hipError_t e = launch_output_transform(p.g, p.two_brackets, M, p.m_bits, y, d->out_type,
+  hipError_t e = launch_output_transform(p.g, p.br, M, p.m_bits, y, d->out_type,
                                          d->relu != 0, mu, s->per_point ? &sh : nullptr,
                                          (hipStream_t)hip_stream);
   return e == hipSuccess ? WINO_OK : fail_hip(e, "output transform launch");
@@ -799,6 +824,7 @@ int wino_contract_output(const wino_conv_desc_t* d, const void* U, const void* V
   if (p.fp32 || p.m_bits == 32 || d->out_type == WINO_OUT_I32)
     return fail(WINO_EUNSUPPORTED, "contraction + output transform in one kernel covers the int8 "
                                    "path with bits_hadamard 8 or 9 and fp32 or int8 output");
+  if (int rc = legendre_only(p, "wino_contract_output")) return rc;
   if (p.g.C != 0) {                               // C = 0: U and V are empty and are not read
     if (int rc = need(U, "U")) return rc;
     if (int rc = need(V, "V")) return rc;
@@ -949,6 +975,7 @@ int wino_calibrate(const wino_conv_desc_t* d, const void* x, const void* w, void
   if (int rc = make_plan(d, &p)) return rc;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "the fp32 path has no scales to calibrate");
   if (int rc = rows_only(p, "wino_calibrate")) return rc;
+  if (int rc = legendre_only(p, "wino_calibrate")) return rc;
   if (d->C > kMaxChannelsExact)
     return fail(WINO_EOVERFLOW, "C = %d: calibration needs the exact int32 contraction result", d->C);
   if (int rc = need(s, "scales")) return rc;
@@ -1108,6 +1135,8 @@ int make_flex_plan(const wino_conv_desc_t* d, const wino_flex_matrices_t* f, Fle
   const Plan& p = fp->p;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "flex layers run on the int8 path (bits_in = 8)");
   if (int rc = rows_only(p, "a flex call")) return rc;
+  if (p.legendre && d->base != WINO_BASE_LEGENDRE)
+    return fail(WINO_EUNSUPPORTED, "flex layers are built for the canonical and the Legendre base");
   if (p.legendre && !p.two_brackets)
     return fail(WINO_EUNSUPPORTED, "a flex layer in the Legendre base needs inner_quant = 1 "
                                    "(run-time matrices cannot be multiplied out with P^{-1})");
@@ -1406,6 +1435,8 @@ int wino_flex_backward_workspace_bytes(const wino_conv_desc_t* d, size_t* bytes)
   if (int rc = make_plan(d, &p)) return rc;
   if (p.fp32) return fail(WINO_EUNSUPPORTED, "flex layers run on the int8 path (bits_in = 8)");
   if (int rc = rows_only(p, "a flex call")) return rc;
+  if (p.legendre && d->base != WINO_BASE_LEGENDRE)
+    return fail(WINO_EUNSUPPORTED, "flex layers are built for the canonical and the Legendre base");
   if (!bytes) return fail(WINO_EINVAL, "null bytes");
   *bytes = flex_bwd_layout(p.g).total;
   if (*bytes == 0) *bytes = 256;

@@ -404,7 +404,7 @@ hipError_t launch_flex_operands(const Geometry& g, bool leg, const int8_t* x, in
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_weight_transform(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
+hipError_t launch_weight_transform(const Geometry& g, int leg, const int8_t* w, int8_t* V,
                                    const StageMults& mu, hipStream_t st) {
   if ((long)g.K * g.C == 0) return hipSuccess;
   switch (g.m) {
@@ -415,7 +415,7 @@ hipError_t launch_weight_transform(const Geometry& g, bool leg, const int8_t* w,
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_input_transform(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+hipError_t launch_input_transform(const Geometry& g, int leg, const int8_t* x, int8_t* U,
                                   const StageMults& mu, hipStream_t st) {
   if ((long)g.T * g.C == 0) return hipSuccess;
   switch (g.m) {
@@ -426,7 +426,7 @@ hipError_t launch_input_transform(const Geometry& g, bool leg, const int8_t* x, 
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_operand_transforms(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+hipError_t launch_operand_transforms(const Geometry& g, int leg, const int8_t* x, int8_t* U,
                                      const int8_t* w, int8_t* V, const StageMults& mu_in,
                                      const StageMults& mu_w, hipStream_t st) {
   if ((long)g.T * g.C == 0) return launch_weight_transform(g, leg, w, V, mu_w, st);
@@ -522,7 +522,7 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
                : contract_tt<128>(g, U, V, Mo, m_bits, mult, st);
 }
 
-hipError_t launch_output_transform(const Geometry& g, bool leg, const void* Mq, int m_bits,
+hipError_t launch_output_transform(const Geometry& g, int leg, const void* Mq, int m_bits,
                                    void* y, int out_type, bool relu, const StageMults& mu,
                                    const ShiftTable* sh, hipStream_t st) {
   if ((long)g.T * g.K == 0) return hipSuccess;

@@ -100,17 +100,19 @@ struct StageMults {
 
 // Per-M launchers of the transform stages (defined in wino_transforms.hpp and
 // instantiated once per M in its own translation unit).
+// brackets: 0 = one bracket per stage (canonical matrices); 1, 2, 3 = the two-bracket form of
+// eq. 2 / eq. 4 in the monic Legendre, Chebyshev, Hermite base.
 template <int M>
 struct PerM {
-  static hipError_t weight(const Geometry& g, bool legendre_inner, const int8_t* w, int8_t* V,
+  static hipError_t weight(const Geometry& g, int brackets, const int8_t* w, int8_t* V,
                            const StageMults& mu, hipStream_t st);
-  static hipError_t input(const Geometry& g, bool legendre_inner, const int8_t* x, int8_t* U,
+  static hipError_t input(const Geometry& g, int brackets, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st);
-  static hipError_t operands(const Geometry& g, bool legendre_inner, const int8_t* x, int8_t* U,
+  static hipError_t operands(const Geometry& g, int brackets, const int8_t* x, int8_t* U,
                              const int8_t* w, int8_t* V, const StageMults& mu_in,
                              const StageMults& mu_w, hipStream_t st);
   // sh != nullptr: M carries per-point shifts (8- or 9-bit M only)
-  static hipError_t output(const Geometry& g, bool legendre_inner, const void* M_, int m_bits,
+  static hipError_t output(const Geometry& g, int brackets, const void* M_, int m_bits,
                            void* y, int out_type, bool relu, const StageMults& mu,
                            const ShiftTable* sh, hipStream_t st);
 };
@@ -189,14 +191,14 @@ hipError_t launch_calibrate_stage(int stage, const Geometry& g, bool legendre_in
 hipError_t launch_absmax_i32(const int32_t* v, long count, int segments,
                              unsigned long long* amax, hipStream_t st);
 
-// legendre_inner == true selects the two-bracket Legendre pipeline; false the
-// single-bracket (canonical, or Legendre with brackets multiplied out).
-hipError_t launch_weight_transform(const Geometry& g, bool legendre_inner, const int8_t* w,
+// brackets: 0 = the single-bracket form (canonical, or a base with its brackets multiplied
+// out); 1 / 2 / 3 = the two-bracket pipeline in the Legendre / Chebyshev / Hermite base.
+hipError_t launch_weight_transform(const Geometry& g, int brackets, const int8_t* w,
                                    int8_t* V, const StageMults& mu, hipStream_t st);
-hipError_t launch_input_transform(const Geometry& g, bool legendre_inner, const int8_t* x,
+hipError_t launch_input_transform(const Geometry& g, int brackets, const int8_t* x,
                                   int8_t* U, const StageMults& mu, hipStream_t st);
 // Input and weight transform in one launch (both outputs non-empty).
-hipError_t launch_operand_transforms(const Geometry& g, bool legendre_inner, const int8_t* x,
+hipError_t launch_operand_transforms(const Geometry& g, int brackets, const int8_t* x,
                                      int8_t* U, const int8_t* w, int8_t* V,
                                      const StageMults& mu_in, const StageMults& mu_w,
                                      hipStream_t st);
@@ -206,7 +208,7 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
                            int m_bits, const MultTable& mult, hipStream_t st);
 // out_type: 0 fp32 (outer table = dequantisation factors), 1 int32 numerators,
 // 2 int8 codes (outer table = cast multipliers).
-hipError_t launch_output_transform(const Geometry& g, bool legendre_inner, const void* M,
+hipError_t launch_output_transform(const Geometry& g, int brackets, const void* M,
                                    int m_bits, void* y, int out_type, bool relu,
                                    const StageMults& mu, const ShiftTable* sh, hipStream_t st);
 

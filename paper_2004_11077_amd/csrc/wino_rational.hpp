@@ -323,20 +323,20 @@ constexpr MatrixSet make_matrix_set(int m, int r, const Rat* points, int n_finit
 }
 
 // The point sets of the supported F(m x m, 3 x 3) instances.
-constexpr MatrixSet standard_matrix_set(int m) {
+constexpr MatrixSet standard_matrix_set(int m, int base = 1) {
   if (m == 2) {
     const Rat pts[3] = {make_rat(0, 1), make_rat(1, 1), make_rat(-1, 1)};
-    return make_matrix_set(2, 3, pts, 3);
+    return make_matrix_set(2, 3, pts, 3, base);
   }
   if (m == 4) {
     const Rat pts[5] = {make_rat(0, 1), make_rat(1, 1), make_rat(-1, 1), make_rat(2, 1),
                         make_rat(-2, 1)};
-    return make_matrix_set(4, 3, pts, 5);
+    return make_matrix_set(4, 3, pts, 5, base);
   }
   if (m == 6) {
     const Rat pts[7] = {make_rat(0, 1), make_rat(1, 1),  make_rat(-1, 1), make_rat(2, 1),
                         make_rat(-2, 1), make_rat(1, 2), make_rat(-1, 2)};
-    return make_matrix_set(6, 3, pts, 7);
+    return make_matrix_set(6, 3, pts, 7, base);
   }
   MatrixSet bad;
   bad.ok = false;

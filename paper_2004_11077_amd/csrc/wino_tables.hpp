@@ -17,9 +17,12 @@ constexpr bool rmat_equal(const RMat& a, const RMat& b) {
   return true;
 }
 
-template <int M>
+// BASE: the polynomial base of the two-bracket forms (Section 4.1): 1 monic Legendre (the
+// paper's), 2 monic Chebyshev, 3 monic Hermite (the alternatives it names).  G, B^T, A^T do
+// not depend on it.
+template <int M, int BASE = 1>
 struct Tab {
-  static constexpr MatrixSet ms = standard_matrix_set(M);
+  static constexpr MatrixSet ms = standard_matrix_set(M, BASE);
   static_assert(ms.ok, "standard matrix set overflowed");
   // Section 4.1 identities: each Legendre bracket pair multiplies out to the
   // canonical matrix, so eq. 4 without inner casts is eq. 3.

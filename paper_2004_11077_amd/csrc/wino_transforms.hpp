@@ -329,12 +329,12 @@ __device__ __forceinline__ void cast_result(const AccT (&num)[T.rows][T.rows], c
 // loads into LDS and every lane picks its nine taps; the n*n results go back
 // through LDS ([point][filter]) to 16-byte stores, as in the input transform.
 // ---------------------------------------------------------------------------
-template <int M, bool LEG>
+template <int M, bool LEG, int BASE = 1>
 __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t* __restrict__ V,
                                             const Geometry& g, const StageMults& mu,
                                             unsigned block) {
   constexpr int n = M + 2, n2 = n * n;
-  using TB = Tab<M>;
+  using TB = Tab<M, BASE>;
   __shared__ __attribute__((aligned(16))) int8_t s_w[256 * 9];
   __shared__ __attribute__((aligned(16))) int8_t s_v[n2 * 256];
   const int tid = threadIdx.x;
@@ -421,12 +421,12 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
 // channels of ONE tile: the tile index and everything derived from it is
 // block-uniform (scalar registers, scalar arithmetic) and no item is out of
 // range.
-template <int M, bool LEG, bool WHOLE>
+template <int M, bool LEG, bool WHOLE, int BASE = 1>
 __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t* __restrict__ U,
                                            const Geometry& g, const StageMults& mu,
                                            unsigned block) {
   constexpr int n = M + 2, n2 = n * n;
-  using TB = Tab<M>;
+  using TB = Tab<M, BASE>;
   __shared__ __attribute__((aligned(16))) int8_t s_in[n2 * 256];
   __shared__ __attribute__((aligned(16))) int8_t s_out[n2 * 256];
   const int tid = threadIdx.x;
@@ -525,25 +525,25 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   }
 }
 
-template <int M, bool LEG>
+template <int M, bool LEG, int BASE = 1>
 __global__ __launch_bounds__(256) void k_weight_transform(const int8_t* __restrict__ w,
                                                           int8_t* __restrict__ V, Geometry g,
                                                           StageMults mu) {
-  weight_body<M, LEG>(w, V, g, mu, blockIdx.x);
+  weight_body<M, LEG, BASE>(w, V, g, mu, blockIdx.x);
 }
 
-template <int M, bool LEG, bool WHOLE>
+template <int M, bool LEG, bool WHOLE, int BASE = 1>
 __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
                                                          int8_t* __restrict__ U, Geometry g,
                                                          StageMults mu) {
-  input_body<M, LEG, WHOLE>(x, U, g, mu, blockIdx.x);
+  input_body<M, LEG, WHOLE, BASE>(x, U, g, mu, blockIdx.x);
 }
 
 // Both operand transforms in one launch (they are independent): the first
 // `nb_in` work groups transform input tiles, the rest transform filters.  One
 // launch less per layer, and the small filter transform fills the tail of the
 // input transform instead of paying its own ramp-up and drain.
-template <int M, bool LEG, bool WHOLE>
+template <int M, bool LEG, bool WHOLE, int BASE = 1>
 __global__ __launch_bounds__(256) void k_operand_transforms(const int8_t* __restrict__ x,
                                                             int8_t* __restrict__ U,
                                                             const int8_t* __restrict__ w,
@@ -551,9 +551,9 @@ __global__ __launch_bounds__(256) void k_operand_transforms(const int8_t* __rest
                                                             StageMults mu_in, StageMults mu_w,
                                                             unsigned nb_in) {
   if (blockIdx.x < nb_in)
-    input_body<M, LEG, WHOLE>(x, U, g, mu_in, blockIdx.x);
+    input_body<M, LEG, WHOLE, BASE>(x, U, g, mu_in, blockIdx.x);
   else
-    weight_body<M, LEG>(w, V, g, mu_w, blockIdx.x - nb_in);
+    weight_body<M, LEG, BASE>(w, V, g, mu_w, blockIdx.x - nb_in);
 }
 
 // ---------------------------------------------------------------------------
@@ -579,13 +579,13 @@ struct MTraits<int32_t> {
 // channels of ONE tile and the tile arithmetic is block-uniform.
 // PP: M carries per-point power-of-two scales; the codes of point p enter the
 // bracket shifted left by sh.v[p] <= kMaxMShift, which the bounds account for.
-template <int M, bool LEG, typename MT, int OUT, bool WHOLE, bool PP>
+template <int M, bool LEG, typename MT, int OUT, bool WHOLE, bool PP, int BASE = 1>
 __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__ Mq,
                                                           void* __restrict__ yv, Geometry g,
                                                           StageMults mu, int relu, ShiftTable sh) {
   constexpr int n = M + 2, n2 = n * n;
   constexpr int64_t IN_MAX = PP ? (MTraits<MT>::in_max << kMaxMShift) : MTraits<MT>::in_max;
-  using TB = Tab<M>;
+  using TB = Tab<M, BASE>;
   const int tid = threadIdx.x;
   const long gid0 = (long)blockIdx.x * 256;
   const long total = (long)g.T * g.K;
@@ -706,10 +706,15 @@ static inline unsigned input_blocks(const Geometry& g) {
 }
 
 template <int M>
-hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t* V,
+hipError_t PerM<M>::weight(const Geometry& g, int br, const int8_t* w, int8_t* V,
                            const StageMults& mu, hipStream_t st) {
   const unsigned nb = weight_blocks(g);
-  if (leg)
+  const bool leg = br != 0;
+  if (br == 2)
+    wino_launch((k_weight_transform<M, true, 2>), dim3(nb), dim3(256), st, w, V, g, mu);
+  else if (br == 3)
+    wino_launch((k_weight_transform<M, true, 3>), dim3(nb), dim3(256), st, w, V, g, mu);
+  else if (leg)
     wino_launch((k_weight_transform<M, true>), dim3(nb), dim3(256), st, w, V, g, mu);
   else
     wino_launch((k_weight_transform<M, false>), dim3(nb), dim3(256), st, w, V, g, mu);
@@ -717,11 +722,16 @@ hipError_t PerM<M>::weight(const Geometry& g, bool leg, const int8_t* w, int8_t*
 }
 
 template <int M>
-hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+hipError_t PerM<M>::input(const Geometry& g, int br, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st) {
   const unsigned nb = input_blocks(g);
   const bool whole = !g.frag && whole_tiles(g.C, g.H, g.W);
-  if (leg && whole)
+  const bool leg = br != 0;
+  if (br == 2)
+    wino_launch((k_input_transform<M, true, false, 2>), dim3(nb), dim3(256), st, x, U, g, mu);
+  else if (br == 3)
+    wino_launch((k_input_transform<M, true, false, 3>), dim3(nb), dim3(256), st, x, U, g, mu);
+  else if (leg && whole)
     wino_launch((k_input_transform<M, true, true>), dim3(nb), dim3(256), st, x, U, g, mu);
   else if (leg)
     wino_launch((k_input_transform<M, true, false>), dim3(nb), dim3(256), st, x, U, g, mu);
@@ -733,13 +743,18 @@ hipError_t PerM<M>::input(const Geometry& g, bool leg, const int8_t* x, int8_t* 
 }
 
 template <int M>
-hipError_t PerM<M>::operands(const Geometry& g, bool leg, const int8_t* x, int8_t* U,
+hipError_t PerM<M>::operands(const Geometry& g, int br, const int8_t* x, int8_t* U,
                              const int8_t* w, int8_t* V, const StageMults& mu_in,
                              const StageMults& mu_w, hipStream_t st) {
   const unsigned nb_in = input_blocks(g), nb_w = weight_blocks(g);
   const bool whole = !g.frag && whole_tiles(g.C, g.H, g.W);
   const dim3 grid(nb_in + nb_w), bs(256);
-  if (leg && whole)
+  const bool leg = br != 0;
+  if (br == 2)
+    wino_launch((k_operand_transforms<M, true, false, 2>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
+  else if (br == 3)
+    wino_launch((k_operand_transforms<M, true, false, 3>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
+  else if (leg && whole)
     wino_launch((k_operand_transforms<M, true, true>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
   else if (leg)
     wino_launch((k_operand_transforms<M, true, false>), grid, bs, st, x, U, w, V, g, mu_in, mu_w, nb_in);
@@ -795,12 +810,40 @@ static hipError_t output_m(const Geometry& g, const void* Mq, int m_bits, void* 
   return output_mt<M, LEG, int32_t>(g, Mq, y, out_type, relu, mu, sh, st);
 }
 
+// The Chebyshev and Hermite bases: the general kernel (per-lane tile arithmetic), per-tensor
+// scales, fp32 or int8 output.
+template <int M, int BASE>
+static hipError_t output_base(const Geometry& g, const void* Mq, int m_bits, void* y, int out_type,
+                              bool relu, const StageMults& mu, const ShiftTable* sh,
+                              hipStream_t st) {
+  if (sh || (out_type != 0 && out_type != 2)) return hipErrorInvalidValue;
+  const dim3 nb(blocks_for((long)g.T * g.K)), bs(256);
+  const ShiftTable none{};
+  const int r = relu ? 1 : 0;
+#define WINO_OUT_BASE(MT_)                                                                          \
+  (out_type == 0                                                                                    \
+       ? wino_launch((k_output_transform<M, true, MT_, 0, false, false, BASE>), nb, bs, st,         \
+                     static_cast<const MT_*>(Mq), y, g, mu, r, none)                                \
+       : wino_launch((k_output_transform<M, true, MT_, 2, false, false, BASE>), nb, bs, st,         \
+                     static_cast<const MT_*>(Mq), y, g, mu, r, none))
+  if (m_bits == 8)
+    WINO_OUT_BASE(int8_t);
+  else if (m_bits == 9)
+    WINO_OUT_BASE(int16_t);
+  else
+    WINO_OUT_BASE(int32_t);
+#undef WINO_OUT_BASE
+  return hipGetLastError();
+}
+
 template <int M>
-hipError_t PerM<M>::output(const Geometry& g, bool leg, const void* Mq, int m_bits, void* y,
+hipError_t PerM<M>::output(const Geometry& g, int br, const void* Mq, int m_bits, void* y,
                            int out_type, bool relu, const StageMults& mu, const ShiftTable* sh,
                            hipStream_t st) {
-  return leg ? output_m<M, true>(g, Mq, m_bits, y, out_type, relu, mu, sh, st)
-             : output_m<M, false>(g, Mq, m_bits, y, out_type, relu, mu, sh, st);
+  if (br == 2) return output_base<M, 2>(g, Mq, m_bits, y, out_type, relu, mu, sh, st);
+  if (br == 3) return output_base<M, 3>(g, Mq, m_bits, y, out_type, relu, mu, sh, st);
+  return br ? output_m<M, true>(g, Mq, m_bits, y, out_type, relu, mu, sh, st)
+            : output_m<M, false>(g, Mq, m_bits, y, out_type, relu, mu, sh, st);
 }
 
 }  // namespace wino

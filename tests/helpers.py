@@ -30,7 +30,8 @@ def gpu_layer(xq, wq, scales, m=4, base="legendre", bits_hadamard=8, inner_quant
     dev = torch.device("cuda:0")
     N, H, W, C = xq.shape
     K = wq.shape[0]
-    base_id = wn.BASE_LEGENDRE if base == "legendre" else wn.BASE_CANONICAL
+    base_id = {"canonical": wn.BASE_CANONICAL, "legendre": wn.BASE_LEGENDRE,
+               "chebyshev": wn.BASE_CHEBYSHEV, "hermite": wn.BASE_HERMITE}[base]
     out_id = {"f32": wn.OUT_F32, "i32": wn.OUT_I32, "i8": wn.OUT_I8}[out_type]
     desc = wn.ConvDesc(N, H, W, C, K, m=m, base=base_id, bits_hadamard=bits_hadamard,
                        inner_quant=int(inner_quant), out_type=out_id, relu=int(relu))
