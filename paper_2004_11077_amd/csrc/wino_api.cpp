@@ -164,7 +164,7 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
   if (d->operand_layout == WINO_LAYOUT_FRAGMENTS && p->fp32)
     return fail(WINO_EUNSUPPORTED, "fragment order is a layout of the int8 operands");
   p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T,
-                  d->operand_layout == WINO_LAYOUT_FRAGMENTS ? 1 : 0, 0, 0, 0, 0};
+                  d->operand_layout == WINO_LAYOUT_FRAGMENTS ? 1 : 0, 0, 0, 0, 0, 0, 0};
   geometry_set_divisors(p->g);
   if (!stages_for(d->m, d->base, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
   p->two_brackets = d->base != WINO_BASE_CANONICAL && d->inner_quant != 0;

@@ -55,7 +55,25 @@ struct Geometry {
   int frag;     // 1: U and V are in MFMA-fragment order (below), 0: rows [n*n][T or K][C]
   // division of a tile index (< 2^30) by TW and by TW * TH as multiply-high and shift
   uint32_t mul_tw, sh_tw, mul_im, sh_im;
+  // input transform: work groups per image when every image's groups are to run on one XCD
+  // (0 = work groups in plain order), and the number of groups covered by that order
+  int img_blocks, img_blocks_end;
 };
+
+// Work-group ids go round-robin over the 8 XCDs, each with a private L2.  The tiles of an
+// image overlap by two pixel rows / columns, so the input transform lets all work groups of
+// an image run on the same XCD: an overlapping input line then enters one L2 once instead of
+// several L2s.  Groups are dealt out image by image: launch slot b = 8 q + x (XCD x) takes
+// group (q % G) of image 8 (q / G) + x, G = groups per image; the slots past the last full set
+// of eight images keep their plain order.
+#if defined(__HIPCC__)
+__device__ __forceinline__ unsigned image_on_one_xcd(const Geometry& g, unsigned b) {
+  if (g.img_blocks == 0 || b >= (unsigned)g.img_blocks_end) return b;
+  const unsigned x = b & 7, q = b >> 3, G = (unsigned)g.img_blocks;
+  const unsigned set = q / G, within = q - set * G;
+  return (set * 8 + x) * G + within;
+}
+#endif
 
 // q = n / d for n < 2^30.  d a power of two: a shift (mul = 0).  Otherwise, with f = floor(log2 d),
 // q = (n * mul) >> (32 + f), mul = floor(2^(32 + f) / d) + 1 < 2^32: the excess

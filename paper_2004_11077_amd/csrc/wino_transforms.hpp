@@ -536,7 +536,7 @@ template <int M, bool LEG, bool WHOLE, int BASE = 1>
 __global__ __launch_bounds__(256) void k_input_transform(const int8_t* __restrict__ x,
                                                          int8_t* __restrict__ U, Geometry g,
                                                          StageMults mu) {
-  input_body<M, LEG, WHOLE, BASE>(x, U, g, mu, blockIdx.x);
+  input_body<M, LEG, WHOLE, BASE>(x, U, g, mu, image_on_one_xcd(g, blockIdx.x));
 }
 
 // Both operand transforms in one launch (they are independent): the first
@@ -551,7 +551,7 @@ __global__ __launch_bounds__(256) void k_operand_transforms(const int8_t* __rest
                                                             StageMults mu_in, StageMults mu_w,
                                                             unsigned nb_in) {
   if (blockIdx.x < nb_in)
-    input_body<M, LEG, WHOLE, BASE>(x, U, g, mu_in, blockIdx.x);
+    input_body<M, LEG, WHOLE, BASE>(x, U, g, mu_in, image_on_one_xcd(g, blockIdx.x));
   else
     weight_body<M, LEG, BASE>(w, V, g, mu_w, blockIdx.x - nb_in);
 }
@@ -701,6 +701,25 @@ static inline bool whole_tiles(int channels, int H, int W) {
 static inline unsigned weight_blocks(const Geometry& g) {
   return g.frag ? (unsigned)(((long)g.K >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.K * g.C);
 }
+// Geometry with the image-to-XCD dealing of the input transform's work groups switched on
+// where an image is a whole number of work groups (block-uniform row order, or fragment order
+// with a tile count per image that is a multiple of the 4 tiles of a work group).
+static inline Geometry with_image_groups(Geometry g, bool whole) {
+  long per_image = 0;
+  const long tiles = (long)g.TH * g.TW;
+  if (g.frag) {
+    if (tiles % 4 == 0) per_image = tiles / 4 * ((g.C + 63) >> 6);
+  } else if (whole) {
+    per_image = tiles * (g.C / 256);
+  }
+  if (per_image > 0 && per_image < (1L << 20) && g.N >= 8) {
+    g.img_blocks = (int)per_image;
+    const long end = (long)(g.N / 8) * 8 * per_image;
+    g.img_blocks_end = end < 0x7fffffffL ? (int)end : 0;
+    if (g.img_blocks_end == 0) g.img_blocks = 0;
+  }
+  return g;
+}
 static inline unsigned input_blocks(const Geometry& g) {
   return g.frag ? (unsigned)((((long)g.T + 3) >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.T * g.C);
 }
@@ -722,10 +741,11 @@ hipError_t PerM<M>::weight(const Geometry& g, int br, const int8_t* w, int8_t* V
 }
 
 template <int M>
-hipError_t PerM<M>::input(const Geometry& g, int br, const int8_t* x, int8_t* U,
+hipError_t PerM<M>::input(const Geometry& g0, int br, const int8_t* x, int8_t* U,
                           const StageMults& mu, hipStream_t st) {
-  const unsigned nb = input_blocks(g);
-  const bool whole = !g.frag && whole_tiles(g.C, g.H, g.W);
+  const unsigned nb = input_blocks(g0);
+  const bool whole = !g0.frag && whole_tiles(g0.C, g0.H, g0.W);
+  const Geometry g = with_image_groups(g0, whole);
   const bool leg = br != 0;
   if (br == 2)
     wino_launch((k_input_transform<M, true, false, 2>), dim3(nb), dim3(256), st, x, U, g, mu);
@@ -743,11 +763,12 @@ hipError_t PerM<M>::input(const Geometry& g, int br, const int8_t* x, int8_t* U,
 }
 
 template <int M>
-hipError_t PerM<M>::operands(const Geometry& g, int br, const int8_t* x, int8_t* U,
+hipError_t PerM<M>::operands(const Geometry& g0, int br, const int8_t* x, int8_t* U,
                              const int8_t* w, int8_t* V, const StageMults& mu_in,
                              const StageMults& mu_w, hipStream_t st) {
-  const unsigned nb_in = input_blocks(g), nb_w = weight_blocks(g);
-  const bool whole = !g.frag && whole_tiles(g.C, g.H, g.W);
+  const unsigned nb_in = input_blocks(g0), nb_w = weight_blocks(g0);
+  const bool whole = !g0.frag && whole_tiles(g0.C, g0.H, g0.W);
+  const Geometry g = with_image_groups(g0, whole);
   const dim3 grid(nb_in + nb_w), bs(256);
   const bool leg = br != 0;
   if (br == 2)
