@@ -413,9 +413,9 @@ def main():
     ap.add_argument("--workload", default="cfg4a_f4_c256")
     ap.add_argument("--batch-scale", type=int, default=1,
                     help="multiply the batch size N (extra, labelled in config)")
-    ap.add_argument("--mode", default="auto", choices=("auto", "split"),
+    ap.add_argument("--mode", default="auto", choices=("auto", "split", "on"),
                     help="kernel selection of the headline step: the library's own choice "
-                         "(fused = AUTO) or one kernel per stage")
+                         "(fused = AUTO), one kernel per stage (OFF), or M kept on chip (ON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the extra timings of the other layer configurations")
@@ -450,7 +450,7 @@ def main():
     del burn
     peaks = device_peaks(wn, torch, ev, dev, stream)
 
-    mode = wn.FUSED_AUTO if args.mode == "auto" else wn.FUSED_OFF
+    mode = {"auto": wn.FUSED_AUTO, "split": wn.FUSED_OFF, "on": wn.FUSED_ON}[args.mode]
     head = measure_layer(wn, si, torch, ev, dev, args.workload, args.batch_scale, args.steps,
                          args.warmup, mode, peaks, copy_probe=args.copy_probe)
     wl, desc, x, w, y, sc, L, mats = (head[k] for k in ("wl", "desc", "x", "w", "y", "sc", "L",
@@ -501,7 +501,7 @@ def main():
     steps = args.steps
     # extra: the same layer with one kernel per stage (a1 + a2 | a3 | a4): the contraction on
     # its own against the int8 MFMA peak, each transform on its own against HBM
-    if want("split", always=True) and args.mode == "auto" and "contraction" not in names:
+    if want("split", always=True) and args.mode != "split" and "contraction" not in names:
         sp = measure_layer(wn, si, torch, ev, dev, args.workload, reps, steps, 0, wn.FUSED_OFF,
                            peaks)
         out["split_path"] = public(sp)

@@ -457,6 +457,10 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   int tx, ty, b;
   tile_coords(g, ut, b, ty, tx);
   const int8_t* xb = x + (long)b * g.H * g.W * g.C + uc;
+  // Images of fewer than 2^23 pixels and 2^31 bytes (block-uniform): pixel offsets are
+  // 32-bit, computed with the full-rate 24-bit multiplier (pixel index and C below 2^24,
+  // product below 2^31), instead of 64-bit multiply-adds.
+  const bool small_image = (long)g.H * g.W < (1L << 23) && (long)g.H * g.W * g.C < (1L << 31);
 #pragma unroll
   for (int it = 0; it < (n2 + 15) / 16; ++it) {
     const int pix = it * 16 + prow;
@@ -464,9 +468,11 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
       const int a = pix / n, bb = pix - a * n;
       const int h = ty * M - 1 + a, ww = tx * M - 1 + bb;
       v4i v = {0, 0, 0, 0};
-      if (uok && h >= 0 && h < g.H && ww >= 0 && ww < g.W) {
+      if (uok && (unsigned)h < (unsigned)g.H && (unsigned)ww < (unsigned)g.W) {
         if constexpr (WHOLE)   // the launcher keeps H * W * C below 2^31 on this path
           v = *reinterpret_cast<const v4i*>(xb + (uint32_t)((h * g.W + ww) * g.C));
+        else if (small_image)
+          v = *reinterpret_cast<const v4i*>(xb + __umul24(__umul24(h, g.W) + ww, g.C));
         else
           v = *reinterpret_cast<const v4i*>(xb + ((long)h * g.W + ww) * g.C);
       }
