@@ -298,10 +298,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
           if (ty_m + I < g.H && tx_m + J < g.W) {
             const int rel = I * wk + J * g.K;
             if constexpr (OUT == 0) {
-              float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * mu.outer.v[I * M + J];
+              float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * mu.outer.v[shared_mult_index<FT, I, J>()];
               __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ybase + rel);
             } else {
-              int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), mu.outer.v[I * M + J], 127.f);
+              int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), mu.outer.v[shared_mult_index<FT, I, J>()], 127.f);
               __builtin_nontemporal_store((int8_t)(relu ? max(v, 0) : v),
                                           static_cast<int8_t*>(yv) + ybase + rel);
             }
@@ -313,7 +313,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
       acc_t<TBL::PinvT, IN_MAX> num1[n][n];
       sandwich<TBL::PinvT, IN_MAX>(mi, num1);
       int m1[n][n];
-      cast_result<TBL::PinvT, IN_MAX>(num1, mu.inner, 127.f, m1);
+      cast_result<TBL::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
       acc_t<TBL::APT, 127> num2[M][M];
       sandwich<TBL::APT, 127>(m1, num2);
       finish.template operator()<TBL::APT, 127>(num2);

@@ -1,33 +1,31 @@
-// Fused variant: input transform -> per-point contraction -> output transform
-// in ONE kernel; the Winograd-domain tensors U and M never leave the CU
-// (U chunks and the cast M block live in LDS, the int32 accumulators of all
-// n*n points in registers).  Only x, V and y touch HBM.
+// Single-kernel variant for narrow layers (C <= 64): input transform -> per-point
+// contraction -> output transform in ONE kernel; the Winograd-domain tensors U and M never
+// leave the compute unit.  Only x, V and y touch HBM.
 //
-// Work group = 4 waves (8 in the single-chunk mode), 16 tiles x KB output channels (KB = 64 for an int8 M,
-// 32 for the 9-bit int16 M), all n*n Winograd points.  Loop over the input
-// channels in chunks of 64:
-//   A  four tiles at a time: their pixels are staged in LDS with 16-byte loads,
-//      every lane transforms one (tile, channel) item exactly as the split
-//      input-transform kernel does and drops the n*n codes into LDS as
-//      U_s[point][tile][channel];
-//   B  wave w takes points w, w+NW, ...: for each, one 16x16x64 int8 MFMA per
-//      16 output channels, A operand = V rows (k) straight from global / L2,
-//      B operand = the 16 tiles of U_s; accumulators stay in registers.
-// Then the accumulators are cast to bits_hadamard, written to LDS as
-// M_s[point][tile][k] (reusing the U_s storage), and every lane runs the output
-// transform of (tile, k) items and stores y.
+// Work group = 8 waves, 16 tiles x KB output channels (KB = 64 for an int8 M, 32 for the
+// 9-bit int16 M), all n*n Winograd points:
+//   A  eight tiles at a time (one per wave): their n*n pixels x 64 channels are staged in
+//      LDS with 16-byte loads (in the part of U_s that is still free), every lane
+//      transforms one (tile, channel) item exactly as the input-transform kernel does and
+//      drops the n*n codes into LDS as U_s[point][tile][channel];
+//   B  wave w takes points w, w+8, ...: for each, one 16x16x64 int8 MFMA per 16 output
+//      channels, A operand = V rows (k) straight from global / L2, B operand = the 16
+//      tiles of U_s; the result is cast at once and written over that point's own U_s rows
+//      as M_s[point][tile][k] (same wave, same bytes: program order suffices), so no
+//      accumulator outlives a point;
+//   C  every lane runs the output transform of (tile, k) items and stores y.
 //
-// The input transform is recomputed by each of the K / KB work groups that
-// share a tile block, so the variant pays off for K <= 64 (one k block).  It is
-// launched for layers with one channel chunk (C <= 64) only; wider layers keep
-// M on chip with the two-kernel form of wino_conout.hpp instead.
+// The input transform is recomputed by each of the K / KB work groups that share a tile
+// block, so the variant pays off for K <= 64 (one k block).  Wider layers keep M on chip
+// with the two-kernel form of wino_conout.hpp instead.
 #include "wino_transforms.hpp"
 
 namespace wino {
 
 constexpr int kFT = 16;          // tiles per work group
-constexpr int kFC = 64;          // input channels per chunk
+constexpr int kFC = 64;          // input channels (the whole reduction)
 constexpr int kPt = kFT * kFC;   // bytes of one point's block in LDS: 16 tiles x 64 bytes
+constexpr int kFW = 8;           // waves per work group
 
 // Byte offset of (tile, byte) inside a point's 1 KB block.  Rows are 64 bytes
 // with no padding; the 16-byte segment index is XOR-ed with bits 1-2 of the
@@ -41,8 +39,8 @@ __device__ __forceinline__ int sw(int tile, int byte) {
 // PP: per-point scales -- the cast of point p uses mm.v[p], and its codes enter
 // the output bracket shifted left by sh.v[p] (<= kMaxMShift, priced into the
 // bounds).  Without PP every entry of mm is the same and sh is not read.
-template <int M, bool LEG, typename MT, int OUT, bool SINGLE, bool PP>
-__global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* __restrict__ x,
+template <int M, bool LEG, typename MT, int OUT, bool PP>
+__global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict__ x,
                                                const int8_t* __restrict__ V,
                                                void* __restrict__ yv, Geometry g, StageMults in_mu,
                                                StageMults out_mu, MultTable mm, ShiftTable sh,
@@ -50,18 +48,20 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
   constexpr int n = M + 2, n2 = n * n;
   constexpr int KB = sizeof(MT) == 1 ? 64 : 32;      // output channels per work group
   constexpr int NKB = KB / 16;                       // 16-wide MFMA column blocks
-  constexpr int NT = SINGLE ? 512 : 256;             // lanes per work group
-  constexpr int NWV = NT / 64;                       // waves: one tile each per pass of phase A
-  constexpr int NPW = (n2 + NWV - 1) / NWV;          // points per wave (the last may be empty)
-  static_assert(n2 % 4 == 0);
+  constexpr int NT = kFW * 64;                       // lanes per work group
+  constexpr int NPW = (n2 + kFW - 1) / kFW;          // points per wave (the last may be empty)
+  static_assert(n2 % 4 == 0 && kFT == 2 * kFW);
   constexpr float QM = sizeof(MT) == 1 ? 127.f : 255.f;
   using TB = Tab<M>;
+  // U_s, then M_s: one KiB per point, tile-major.  The pixels of a pass (8 tiles x n*n
+  // pixels x 64 bytes = n*n half KiB) are staged in the upper half of every point's KiB,
+  // pixel `pix` of the pass's tile `w` at stage_at(pix, w): those halves hold the codes of
+  // tiles 8-15, which only the second pass writes, after all its pixels have been read.
   __shared__ __attribute__((aligned(16))) int8_t smem[n2 * kPt];
-  __shared__ __attribute__((aligned(16))) int8_t s_x[NWV * n2 * kFC];   // input pixels of one pass
+  auto stage_at = [](int pix, int w) { return pix * kPt + kPt / 2 + w * kFC; };
 
-  // Image and pixel origin of the block's 16 tiles, worked out once (three
-  // integer divisions per tile) and read back from LDS by the staging loops
-  // and the output transform: ti = {b, ty*M, tx*M, tile exists}.
+  // Image and pixel origin of the block's 16 tiles, worked out once and read back from LDS
+  // by the staging loop and the output transform: ti = {b, ty*M, tx*M, tile exists}.
   __shared__ int4 s_tile[kFT];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -69,33 +69,91 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
   const int t0 = tb * kFT, k0 = kblk * KB;
   const int jl = lane & 15, seg = lane >> 4;         // MFMA operand row / 16-byte K segment
   if (tid < kFT) {
-    const int t = t0 + tid;
-    const int tx = t % g.TW;
-    const int ty = (t / g.TW) % g.TH;
-    const int b = t / (g.TW * g.TH);
-    s_tile[tid] = make_int4(b, ty * M, tx * M, t < g.T ? 1 : 0);
+    const int t = min(t0 + tid, g.T - 1);
+    int b, ty, tx;
+    tile_coords(g, t, b, ty, tx);
+    s_tile[tid] = make_int4(b, ty * M, tx * M, t0 + tid < g.T ? 1 : 0);
   }
   __syncthreads();
 
-  // SINGLE (C <= 64, one channel chunk): a point's contraction is complete
-  // after its MFMAs, so it is cast at once and written over that point's own
-  // U_s rows (same wave, same bytes: program order suffices) and no
-  // accumulator outlives a point.  Otherwise the accumulators of all the
-  // wave's points live in registers across the channel loop.
-  v4i acc[SINGLE ? 1 : NPW][NKB];
-  if constexpr (!SINGLE) {
+  // ---- A: input transform of 16 tiles x 64 channels, one tile per wave and pass ----
+#pragma unroll 1
+  for (int it = 0; it < kFT / kFW; ++it) {
+    // stage the n*n pixels x 64 channels of the pass's 8 tiles with 16-byte loads (zeros
+    // outside the image, past the last tile or channel)
+    if (it) __syncthreads();                         // the previous pass's pixels are consumed
 #pragma unroll
-    for (int a = 0; a < NPW; ++a)
-#pragma unroll
-      for (int b = 0; b < NKB; ++b) acc[a][b] = v4i{0, 0, 0, 0};
+    for (int j = 0; j < (kFW * n2 * 4 + NT - 1) / NT; ++j) {
+      const int idx = j * NT + tid;
+      if (idx < kFW * n2 * 4) {
+        const int tq = idx / (n2 * 4), rem = idx - tq * (n2 * 4);
+        const int pix = rem >> 2, sg = rem & 3;
+        const int4 ti = s_tile[it * kFW + tq];
+        v4i v = {0, 0, 0, 0};
+        if (ti.w && sg * 16 < g.C) {
+          const int a = pix / n, bb = pix - a * n;
+          const int h = ti.y - 1 + a, ww = ti.z - 1 + bb;
+          if (h >= 0 && h < g.H && ww >= 0 && ww < g.W)
+            v = *reinterpret_cast<const v4i*>(x + (((long)ti.x * g.H + h) * g.W + ww) * g.C + sg * 16);
+        }
+        *reinterpret_cast<v4i*>(smem + stage_at(pix, tq) + sg * 16) = v;
+      }
+    }
+    __syncthreads();
+    const int tl = it * kFW + wave;                  // a wave = one tile, 64 channels
+    int xi[n][n];
+    static_for<0, n>([&](auto a) {
+      static_for<0, n>([&](auto bb) {
+        xi[a][bb] = smem[stage_at(decltype(a)::value * n + decltype(bb)::value, wave) + lane];
+      });
+    });
+    if (it) __syncthreads();                         // this pass's codes go where its pixels were
+    int q[n][n];
+    if constexpr (LEG) {
+      acc_t<TB::PinvT, 127> num1[n][n];
+      sandwich<TB::PinvT, 127>(xi, num1);
+      int x1[n][n];
+      cast_result<TB::PinvT, 127, true>(num1, in_mu.inner, 127.f, x1);
+      acc_t<TB::BPT, 127> num2[n][n];
+      sandwich<TB::BPT, 127>(x1, num2);
+      cast_result<TB::BPT, 127, !PP>(num2, in_mu.outer, 127.f, q);
+    } else {
+      acc_t<TB::BT, 127> num[n][n];
+      sandwich<TB::BT, 127>(xi, num);
+      cast_result<TB::BT, 127, !PP>(num, in_mu.outer, 127.f, q);
+    }
+    static_for<0, n>([&](auto i) {
+      static_for<0, n>([&](auto j) {
+        // a dead item (tile or channel out of range) has all-zero input, hence zero codes
+        smem[(decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, lane)] = (int8_t)q[i][j];
+      });
+    });
   }
-  auto park = [&](const v4i (&av)[NKB], int p) {       // cast one point, store as M_s[p][tile][k]
-    const float m_mult = PP ? mm.v[p] : mm.v[0];       // p is wave-uniform
+  __syncthreads();
+
+  // ---- B: contraction for the wave's points; cast and park as M_s[p][tile][k] ----
+  // D[k = 16 kb + 4 seg + v][tile = jl]
+  const bool cok = seg * 16 < g.C;
+  const int ccol = cok ? seg * 16 : 0;
+#pragma clang loop unroll_count(3)
+  for (int pi = 0; pi < NPW; ++pi) {
+    const int p = pi * kFW + wave;
+    if (n2 % kFW != 0 && p >= n2) break;             // wave-uniform: this wave has one point less
+    const v4i bu = *reinterpret_cast<const v4i*>(smem + p * kPt + sw(jl, seg * 16));
+    v4i a4[NKB];
+#pragma unroll
+    for (int kb = 0; kb < NKB; ++kb) {
+      const int kr = min(k0 + kb * 16 + jl, g.K - 1);            // clamp, masked at the store
+      v4i av = *reinterpret_cast<const v4i*>(V + ((long)p * g.K + kr) * g.C + ccol);
+      if (!cok) av = v4i{0, 0, 0, 0};
+      a4[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, v4i{0, 0, 0, 0}, 0, 0, 0);
+    }
+    const float m_mult = PP ? mm.v[p] : mm.v[0];     // p is wave-uniform
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) {
       int q[4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)av[kb][v], m_mult, QM);
+      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)a4[kb][v], m_mult, QM);
       int8_t* dst = smem + p * kPt + sw(jl, (kb * 16 + 4 * seg) * (int)sizeof(MT));
       if constexpr (sizeof(MT) == 1) {
         *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
@@ -106,97 +164,10 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
         reinterpret_cast<uint32_t*>(dst)[1] = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
       }
     }
-  };
-
-  for (int c0 = 0; c0 < g.C; c0 += kFC) {
-    if (c0) __syncthreads();                         // U_s of the previous chunk consumed
-    // ---- A: input transform of 16 tiles x 64 channels, one tile per wave and pass ----
-#pragma unroll 1
-    for (int it = 0; it < kFT / NWV; ++it) {
-      // stage the n*n pixels x 64 channels of the pass's NWV tiles with 16-byte
-      // loads (zeros outside the image, past the last tile or channel)
-      if (it) __syncthreads();                       // s_x of the previous pass consumed
-#pragma unroll
-      for (int j = 0; j < (NWV * n2 * 4 + NT - 1) / NT; ++j) {
-        const int idx = j * NT + tid;
-        if (idx < NWV * n2 * 4) {
-          const int tq = idx / (n2 * 4), rem = idx - tq * (n2 * 4);
-          const int pix = rem >> 2, sg = rem & 3;
-          const int c = c0 + sg * 16;
-          const int4 ti = s_tile[it * NWV + tq];
-          v4i v = {0, 0, 0, 0};
-          if (ti.w && c < g.C) {
-            const int a = pix / n, bb = pix - a * n;
-            const int h = ti.y - 1 + a, ww = ti.z - 1 + bb;
-            if (h >= 0 && h < g.H && ww >= 0 && ww < g.W)
-              v = *reinterpret_cast<const v4i*>(x + (((long)ti.x * g.H + h) * g.W + ww) * g.C + c);
-          }
-          *reinterpret_cast<v4i*>(s_x + (tq * n2 + pix) * kFC + sg * 16) = v;
-        }
-      }
-      __syncthreads();
-      const int tl = it * NWV + wave;                // a wave = one tile, 64 channels
-      int xi[n][n];
-      static_for<0, n>([&](auto a) {
-        static_for<0, n>([&](auto bb) {
-          xi[a][bb] = s_x[(wave * n2 + decltype(a)::value * n + decltype(bb)::value) * kFC + lane];
-        });
-      });
-      int q[n][n];
-      if constexpr (LEG) {
-        acc_t<TB::PinvT, 127> num1[n][n];
-        sandwich<TB::PinvT, 127>(xi, num1);
-        int x1[n][n];
-        cast_result<TB::PinvT, 127>(num1, in_mu.inner, 127.f, x1);
-        acc_t<TB::BPT, 127> num2[n][n];
-        sandwich<TB::BPT, 127>(x1, num2);
-        cast_result<TB::BPT, 127>(num2, in_mu.outer, 127.f, q);
-      } else {
-        acc_t<TB::BT, 127> num[n][n];
-        sandwich<TB::BT, 127>(xi, num);
-        cast_result<TB::BT, 127>(num, in_mu.outer, 127.f, q);
-      }
-      static_for<0, n>([&](auto i) {
-        static_for<0, n>([&](auto j) {
-          // a dead item (tile or channel out of range) has all-zero input, hence zero codes
-          smem[(decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, lane)] = (int8_t)q[i][j];
-        });
-      });
-    }
-    __syncthreads();
-    // ---- B: contraction of this chunk for the wave's points ----
-    const bool cok = c0 + seg * 16 < g.C;
-    const int ccol = cok ? c0 + seg * 16 : 0;
-#pragma clang loop unroll_count(SINGLE ? 3 : NPW)
-    for (int pi = 0; pi < NPW; ++pi) {
-      const int p = pi * NWV + wave;
-      if (n2 % NWV != 0 && p >= n2) break;           // wave-uniform: this wave has one point less
-      const v4i bu = *reinterpret_cast<const v4i*>(smem + p * kPt + sw(jl, seg * 16));
-      v4i (&a4)[NKB] = acc[SINGLE ? 0 : pi];
-#pragma unroll
-      for (int kb = 0; kb < NKB; ++kb) {
-        const int kr = min(k0 + kb * 16 + jl, g.K - 1);          // clamp, masked at the store
-        v4i av = *reinterpret_cast<const v4i*>(V + ((long)p * g.K + kr) * g.C + ccol);
-        if (!cok) av = v4i{0, 0, 0, 0};
-        if constexpr (SINGLE)
-          a4[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, v4i{0, 0, 0, 0}, 0, 0, 0);
-        else
-          a4[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, a4[kb], 0, 0, 0);
-      }
-      if constexpr (SINGLE) park(a4, p);
-    }
-  }
-
-  // ---- cast the contraction result and park it in LDS as M_s[p][tile][k] ----
-  // acc[pi][kb][v] = D[k = 16 kb + 4 seg + v][tile = jl]
-  if constexpr (!SINGLE) {
-    __syncthreads();                                 // every wave is done reading U_s
-#pragma unroll
-    for (int pi = 0; pi < NPW; ++pi) park(acc[pi], pi * NWV + wave);
   }
   __syncthreads();
 
-  // ---- output transform of 16 tiles x KB channels ----
+  // ---- C: output transform of 16 tiles x KB channels ----
 #pragma unroll 1
   for (int it = 0; it < kFT * KB / NT; ++it) {
     const int item = it * NT + tid;
@@ -218,7 +189,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
     auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
-          constexpr int idx = decltype(i)::value * M + decltype(j)::value;
+          constexpr int idx = shared_mult_index<FT, decltype(i)::value, decltype(j)::value>();
           const int h = ty_m + decltype(i)::value;
           const int ww = tx_m + decltype(j)::value;
           if (h < g.H && ww < g.W) {
@@ -240,7 +211,7 @@ __global__ __launch_bounds__(SINGLE ? 512 : 256, 2) void k_fused(const int8_t* _
       acc_t<TB::PinvT, IN_MAX> num1[n][n];
       sandwich<TB::PinvT, IN_MAX>(mi, num1);
       int m1[n][n];
-      cast_result<TB::PinvT, IN_MAX>(num1, out_mu.inner, 127.f, m1);
+      cast_result<TB::PinvT, IN_MAX, true>(num1, out_mu.inner, 127.f, m1);
       acc_t<TB::APT, 127> num2[M][M];
       sandwich<TB::APT, 127>(m1, num2);
       finish.template operator()<TB::APT, 127>(num2);
@@ -260,15 +231,15 @@ static hipError_t fused_mt(const Geometry& g, const int8_t* x, const int8_t* V, 
   const int tblocks = (g.T + kFT - 1) / kFT, kblocks = (g.K + KB - 1) / KB;
   dim3 grid((unsigned)(tblocks * kblocks));
   const int r = relu ? 1 : 0;
-  // Only the single-chunk build is launched: wider layers take the two-kernel form
-  // (input transform, then contraction + output transform), which does not recompute the
-  // input transform per block of output channels and holds no accumulators across chunks.
+  // One channel chunk only: wider layers take the two-kernel form (input transform, then
+  // contraction + output transform), which does not recompute the input transform per block
+  // of output channels.
   if (g.C > kFC) return hipErrorInvalidValue;
   if (out_type == 0)
-    wino_launch((k_fused<M, LEG, MT, 0, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 0, PP>), grid, dim3(kFW * 64), st, x, V, y, g, in_mu,
                        out_mu, mm, sh, r, tblocks);
   else
-    wino_launch((k_fused<M, LEG, MT, 2, true, PP>), grid, dim3(512), st, x, V, y, g, in_mu,
+    wino_launch((k_fused<M, LEG, MT, 2, PP>), grid, dim3(kFW * 64), st, x, V, y, g, in_mu,
                        out_mu, mm, sh, r, tblocks);
   return hipGetLastError();
 }

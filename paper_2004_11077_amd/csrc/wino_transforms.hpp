@@ -309,15 +309,30 @@ __device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
   return __float_as_int(t) - 0x4B400000;
 }
 
+// With one scale for the whole tensor the multiplier of entry (i, j) depends on the product
+// rho_i rho_j of its row denominators only, so entries with equal products hold the same
+// float: this is the index of the first of them (row-major).  Reading that one keeps a
+// handful of multipliers in scalar registers instead of rows * rows (F(4,3) Legendre: 15
+// for the base-change bracket, 3 for each main bracket, instead of 36 / 36 / 16).
+template <const IMat& T, int I, int J>
+constexpr int shared_mult_index() {
+  for (int a = 0; a < T.rows; ++a)
+    for (int b = 0; b < T.rows; ++b)
+      if (T.rho[a] * T.rho[b] == T.rho[I] * T.rho[J]) return a * T.rows + b;
+  return I * T.rows + J;
+}
+
 // Casts the result of sandwich<T, IN_MAX>, one multiplier per entry; entries
-// that fit 32 bits are converted as such.
-template <const IMat& T, int64_t IN_MAX, typename AccT>
+// that fit 32 bits are converted as such.  SHARE: the table was filled with one
+// target scale (not per-point scales), see shared_mult_index.
+template <const IMat& T, int64_t IN_MAX, bool SHARE = false, typename AccT>
 __device__ __forceinline__ void cast_result(const AccT (&num)[T.rows][T.rows], const MultTable& mu,
                                             float qmax, int (&q)[T.rows][T.rows]) {
   static_for<0, T.rows>([&](auto i) {
     static_for<0, T.rows>([&](auto j) {
       constexpr int I = decltype(i)::value, J = decltype(j)::value;
-      q[i][j] = cast_code((float)entry<T, IN_MAX, I, J>(num[i][j]), mu.v[I * T.rows + J], qmax);
+      constexpr int at = SHARE ? shared_mult_index<T, I, J>() : I * T.rows + J;
+      q[i][j] = cast_code((float)entry<T, IN_MAX, I, J>(num[i][j]), mu.v[at], qmax);
     });
   });
 }
@@ -369,7 +384,7 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
     acc_t<TB::GP, 127> num1[n][n];
     sandwich<TB::GP, 127>(wi, num1);
     int w1[n][n];
-    cast_result<TB::GP, 127>(num1, mu.inner, 127.f, w1);
+    cast_result<TB::GP, 127, true>(num1, mu.inner, 127.f, w1);
     acc_t<TB::Pinv, 127> num2[n][n];
     sandwich<TB::Pinv, 127>(w1, num2);
     cast_result<TB::Pinv, 127>(num2, mu.outer, 127.f, q);
@@ -492,7 +507,7 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
     acc_t<TB::PinvT, 127> num1[n][n];
     sandwich<TB::PinvT, 127>(xi, num1);
     int x1[n][n];
-    cast_result<TB::PinvT, 127>(num1, mu.inner, 127.f, x1);
+    cast_result<TB::PinvT, 127, true>(num1, mu.inner, 127.f, x1);
     acc_t<TB::BPT, 127> num2[n][n];
     sandwich<TB::BPT, 127>(x1, num2);
     cast_result<TB::BPT, 127>(num2, mu.outer, 127.f, q);
@@ -657,7 +672,8 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
     static_for<0, M>([&](auto i) {
       static_for<0, M>([&](auto j) {
-        constexpr int idx = decltype(i)::value * M + decltype(j)::value;
+        // y has one scale: entries with equal row-denominator products share a multiplier
+        constexpr int idx = shared_mult_index<FT, decltype(i)::value, decltype(j)::value>();
         const int h = ty * M + decltype(i)::value;
         const int ww = tx * M + decltype(j)::value;
         if (h < g.H && ww < g.W) {
@@ -681,7 +697,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     acc_t<TB::PinvT, IN_MAX> num1[n][n];
     sandwich<TB::PinvT, IN_MAX>(xi, num1);
     int m1[n][n];
-    cast_result<TB::PinvT, IN_MAX>(num1, mu.inner, 127.f, m1);
+    cast_result<TB::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
     acc_t<TB::APT, 127> num2[M][M];
     sandwich<TB::APT, 127>(m1, num2);
     finish.template operator()<TB::APT, 127>(num2);
