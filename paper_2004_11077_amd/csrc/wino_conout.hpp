@@ -38,14 +38,6 @@
 
 namespace wino {
 
-// One cast kept in its biased float form 1.5 * 2^23 + q: the code sits, in two's complement,
-// in the low bits of the returned pattern, so packing needs only its low byte (or half).
-__device__ __forceinline__ uint32_t co_cast_biased(float v, float mult, float qmax) {
-  float t = __builtin_fmaf(v, mult, kMagic);
-  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
-  return __float_as_uint(t);
-}
-
 constexpr int kCoChunk = 64;      // channels per MFMA step (16x16x64)
 
 // Block shape: 32 tiles x 32 output channels where the codes of such a block fit 80 KB of LDS
@@ -240,7 +232,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
         for (int j = 0; j < NTB; ++j) {
           uint32_t q[4];
 #pragma unroll
-          for (int v = 0; v < 4; ++v) q[v] = co_cast_biased((float)acc[i][j][v], mult, QM);
+          for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)acc[i][j][v], mult, QM);
           acc[i][j] = v4i{0, 0, 0, 0};
           // the four-code group index inside a tile's row is XOR-ed with the tile's low
           // bits: the 16 tiles a store covers then fall on distinct LDS banks

@@ -64,7 +64,8 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
   // by the staging loop and the output transform: ti = {b, ty*M, tx*M, tile exists}.
   __shared__ int4 s_tile[kFT];
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // in a scalar register
   const int tb = blockIdx.x % tblocks, kblk = blockIdx.x / tblocks;
   const int t0 = tb * kFT, k0 = kblk * KB;
   const int jl = lane & 15, seg = lane >> 4;         // MFMA operand row / 16-byte K segment
@@ -134,7 +135,10 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
   // ---- B: contraction for the wave's points; cast and park as M_s[p][tile][k] ----
   // D[k = 16 kb + 4 seg + v][tile = jl]
   const bool cok = seg * 16 < g.C;
-  const int ccol = cok ? seg * 16 : 0;
+  int voff[NKB];                                     // the lane's V row and channel segment
+#pragma unroll
+  for (int kb = 0; kb < NKB; ++kb)
+    voff[kb] = min(k0 + kb * 16 + jl, g.K - 1) * g.C + (cok ? seg * 16 : 0);   // clamp, masked at the store
 #pragma clang loop unroll_count(3)
   for (int pi = 0; pi < NPW; ++pi) {
     const int p = pi * kFW + wave;
@@ -143,39 +147,54 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
     v4i a4[NKB];
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) {
-      const int kr = min(k0 + kb * 16 + jl, g.K - 1);            // clamp, masked at the store
-      v4i av = *reinterpret_cast<const v4i*>(V + ((long)p * g.K + kr) * g.C + ccol);
-      if (!cok) av = v4i{0, 0, 0, 0};
+      // a segment past C re-reads segment 0: its U_s codes are zero, whatever V holds
+      const v4i av = *reinterpret_cast<const v4i*>(V + (long)p * g.K * g.C + voff[kb]);
       a4[kb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, bu, v4i{0, 0, 0, 0}, 0, 0, 0);
     }
     const float m_mult = PP ? mm.v[p] : mm.v[0];     // p is wave-uniform
 #pragma unroll
     for (int kb = 0; kb < NKB; ++kb) {
-      int q[4];
+      uint32_t q[4];
 #pragma unroll
-      for (int v = 0; v < 4; ++v) q[v] = cast_code((float)a4[kb][v], m_mult, QM);
+      for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)a4[kb][v], m_mult, QM);
       int8_t* dst = smem + p * kPt + sw(jl, (kb * 16 + 4 * seg) * (int)sizeof(MT));
       if constexpr (sizeof(MT) == 1) {
-        *reinterpret_cast<uint32_t*>(dst) = ((uint32_t)q[0] & 0xffu) | (((uint32_t)q[1] & 0xffu) << 8) |
-                                            (((uint32_t)q[2] & 0xffu) << 16) |
-                                            (((uint32_t)q[3] & 0xffu) << 24);
+        const uint32_t lo = __builtin_amdgcn_perm(q[1], q[0], 0x0c0c0400u);
+        const uint32_t hi = __builtin_amdgcn_perm(q[3], q[2], 0x04000c0cu);
+        *reinterpret_cast<uint32_t*>(dst) = lo | hi;
       } else {
-        reinterpret_cast<uint32_t*>(dst)[0] = ((uint32_t)q[0] & 0xffffu) | ((uint32_t)q[1] << 16);
-        reinterpret_cast<uint32_t*>(dst)[1] = ((uint32_t)q[2] & 0xffffu) | ((uint32_t)q[3] << 16);
+        reinterpret_cast<uint32_t*>(dst)[0] = __builtin_amdgcn_perm(q[1], q[0], 0x05040100u);
+        reinterpret_cast<uint32_t*>(dst)[1] = __builtin_amdgcn_perm(q[3], q[2], 0x05040100u);
       }
     }
   }
   __syncthreads();
 
   // ---- C: output transform of 16 tiles x KB channels ----
+  // ReLU as a lower bound (none: below every value).  A float is bounded through its bit
+  // pattern: negative values are negative integers, so one integer maximum with 0 clears
+  // them (and -0.0), with INT_MIN it changes nothing.
+  const int lo_f = relu ? 0 : (int)0x80000000;
+  const int lo_i = relu ? 0 : -128;
 #pragma unroll 1
   for (int it = 0; it < kFT * KB / NT; ++it) {
-    const int item = it * NT + tid;
-    const int tl = item / KB, kl = item - tl * KB;
+    int tl, kl;
+    int4 ti;
+    if constexpr (KB == 64) {
+      // a wave = the 64 output channels of one tile: the tile's coordinates, the edge tests
+      // and the tile part of every address stay in scalar registers
+      tl = it * (NT / KB) + wave, kl = lane;
+      const int4 tv = s_tile[tl];
+      ti = make_int4(__builtin_amdgcn_readfirstlane(tv.x), __builtin_amdgcn_readfirstlane(tv.y),
+                     __builtin_amdgcn_readfirstlane(tv.z), __builtin_amdgcn_readfirstlane(tv.w));
+    } else {
+      const int item = it * NT + tid;
+      tl = item / KB, kl = item - tl * KB;
+      ti = s_tile[tl];
+    }
     const int k = k0 + kl;
-    const int4 ti = s_tile[tl];
     if (!ti.w || k >= g.K) continue;
-    const int b = ti.x, ty_m = ti.y, tx_m = ti.z;    // image, first output row and column
+    const int ty_m = ti.y, tx_m = ti.z;              // first output row and column
     int mi[n][n];
     static_for<0, n>([&](auto i) {
       static_for<0, n>([&](auto j) {
@@ -184,23 +203,23 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
         if constexpr (PP) mi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
       });
     });
-    const long ybase = (((long)b * g.H + ty_m) * g.W + tx_m) * g.K + k;
-    const int wk = g.W * g.K;
+    constexpr int YB = OUT == 0 ? 4 : 1;             // bytes of one output
+    char* ytile = static_cast<char*>(yv) + (((long)ti.x * g.H + ty_m) * g.W + tx_m) * g.K * YB;
+    const long wkb = (long)g.W * g.K * YB, kb1 = (long)g.K * YB;
+    const unsigned kbyte = (unsigned)k * YB;
     auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
-          constexpr int idx = shared_mult_index<FT, decltype(i)::value, decltype(j)::value>();
-          const int h = ty_m + decltype(i)::value;
-          const int ww = tx_m + decltype(j)::value;
-          if (h < g.H && ww < g.W) {
-            const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
+          constexpr int I = decltype(i)::value, J = decltype(j)::value;
+          constexpr int idx = shared_mult_index<FT, I, J>();
+          if (ty_m + I < g.H && tx_m + J < g.W) {
+            char* at = ytile + (I * wkb + J * kb1) + kbyte;
             if constexpr (OUT == 0) {
-              float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * out_mu.outer.v[idx];
-              __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ybase + rel);
+              const float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * out_mu.outer.v[idx];
+              __builtin_nontemporal_store(max(__float_as_int(v), lo_f), reinterpret_cast<int*>(at));
             } else {
-              int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), out_mu.outer.v[idx], 127.f);
-              __builtin_nontemporal_store((int8_t)(relu ? max(v, 0) : v),
-                                          static_cast<int8_t*>(yv) + ybase + rel);
+              const int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), out_mu.outer.v[idx], 127.f);
+              __builtin_nontemporal_store((int8_t)max(v, lo_i), reinterpret_cast<int8_t*>(at));
             }
           }
         });

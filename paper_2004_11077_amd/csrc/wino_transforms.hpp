@@ -308,6 +308,14 @@ __device__ __forceinline__ int cast_code(float v, float mult, float qmax) {
   t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
   return __float_as_int(t) - 0x4B400000;
 }
+// The same cast left in its biased float form 1.5 * 2^23 + q: the code sits, in two's
+// complement, in the low bits of the returned pattern, so packing needs only its low byte
+// (or half).
+__device__ __forceinline__ uint32_t cast_biased(float v, float mult, float qmax) {
+  float t = __builtin_fmaf(v, mult, kMagic);
+  t = __builtin_amdgcn_fmed3f(t, kMagic - qmax, kMagic + qmax);
+  return __float_as_uint(t);
+}
 
 // With one scale for the whole tensor the multiplier of entry (i, j) depends on the product
 // rho_i rho_j of its row denominators only, so entries with equal products hold the same
