@@ -203,8 +203,14 @@ def resnet18_stack(wn, si, torch, dev, steps, N=256):
         for run, xi, V, y, sc, ws in layers:
             wn.wino_conv2d(run, xi, V, y, sc, ws)
     dt = timed(torch, once, steps, min_launches=40)[0]
+    per_layer = []
+    for (C, K, HW), (run, xi, V, y, sc, ws) in zip(si.RESNET18_STACK, layers):
+        t = timed(torch, lambda: wn.wino_conv2d(run, xi, V, y, sc, ws), steps, min_launches=200)[0]
+        per_layer.append({"C": C, "K": K, "HW": HW, "us": round(t * 1e6, 2),
+                          "launches": wn.wino_conv2d_launches(run)})
     return {"ms_per_pass": dt * 1e3, "TOPS_direct_equiv": ops / dt / 1e12, "layers": len(layers),
-            "N": N, "note": "int8 in, int8 + ReLU out, filters pretransformed, fused = AUTO"}
+            "N": N, "note": "int8 in, int8 + ReLU out, filters pretransformed, fused = AUTO",
+            "per_layer": per_layer}
 
 
 def cpu_baseline(wl, min_seconds=12.0):

@@ -106,6 +106,7 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
     static_for<0, n>([&](auto a) {
       static_for<0, n>([&](auto bb) {
         xi[a][bb] = smem[stage_at(decltype(a)::value * n + decltype(bb)::value, wave) + lane];
+        asm("" : "+v"(xi[a][bb]));                   // keeps the load a sign-extending byte read
       });
     });
     if (it) __syncthreads();                         // this pass's codes go where its pixels were
