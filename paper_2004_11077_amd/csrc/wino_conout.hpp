@@ -264,6 +264,11 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
 
   // ---- phase 2: output transform of TB x KB items ---------------------------------------
   constexpr int64_t IN_MAX = (sizeof(MT) == 1 ? 127 : 255) << (PP ? kMaxMShift : 0);
+  // ReLU as a lower bound (none: below every value).  A float is bounded through its bit
+  // pattern: negative values are negative integers, so one integer maximum with 0 clears
+  // them (and -0.0), with INT_MIN it changes nothing.
+  const int lo_f = relu ? 0 : (int)0x80000000;
+  const int lo_i = relu ? 0 : -128;
 #pragma unroll 1
   for (int it = 0; it < (tid < NT2 ? TB * KB / NT2 : 0); ++it) {
     const int item = it * NT2 + tid;
@@ -281,26 +286,30 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
         if constexpr (PP) mi[i][j] <<= sh.v[P];
       });
     });
-    const long ybase = (((long)ti.x * g.H + ty_m) * g.W + tx_m) * g.K + k;
-    const int wk = g.W * g.K;
-    auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
+    constexpr int YB = OUT == 0 ? 4 : 1;             // bytes of one output
+    char* yitem = static_cast<char*>(yv) + ((((long)ti.x * g.H + ty_m) * g.W + tx_m) * g.K + k) * YB;
+    const long wkb = (long)g.W * g.K * YB, kb1 = (long)g.K * YB;
+    // FULL: no lane of the wave has a tile that reaches past the image (always so when the
+    // tile edge divides H and W): the stores need no edge tests
+    auto finish = [&]<const IMat& FT, int64_t FIN, bool FULL>(auto& num) {
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
           constexpr int I = decltype(i)::value, J = decltype(j)::value;
-          if (ty_m + I < g.H && tx_m + J < g.W) {
-            const int rel = I * wk + J * g.K;
+          if (FULL || (ty_m + I < g.H && tx_m + J < g.W)) {
+            char* at = yitem + (I * wkb + J * kb1);
             if constexpr (OUT == 0) {
-              float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * mu.outer.v[shared_mult_index<FT, I, J>()];
-              __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ybase + rel);
+              const float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * mu.outer.v[shared_mult_index<FT, I, J>()];
+              __builtin_nontemporal_store(max(__float_as_int(v), lo_f), reinterpret_cast<int*>(at));
             } else {
-              int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), mu.outer.v[shared_mult_index<FT, I, J>()], 127.f);
-              __builtin_nontemporal_store((int8_t)(relu ? max(v, 0) : v),
-                                          static_cast<int8_t*>(yv) + ybase + rel);
+              const int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), mu.outer.v[shared_mult_index<FT, I, J>()], 127.f);
+              __builtin_nontemporal_store((int8_t)max(v, lo_i), reinterpret_cast<int8_t*>(at));
             }
           }
         });
       });
     };
+    const bool inside = ty_m + M <= g.H && tx_m + M <= g.W;
+    const bool all_inside = __builtin_amdgcn_ballot_w64(!inside) == 0;
     if constexpr (LEG) {
       acc_t<TBL::PinvT, IN_MAX> num1[n][n];
       sandwich<TBL::PinvT, IN_MAX>(mi, num1);
@@ -308,11 +317,17 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
       cast_result<TBL::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
       acc_t<TBL::APT, 127> num2[M][M];
       sandwich<TBL::APT, 127>(m1, num2);
-      finish.template operator()<TBL::APT, 127>(num2);
+      if (all_inside)
+        finish.template operator()<TBL::APT, 127, true>(num2);
+      else
+        finish.template operator()<TBL::APT, 127, false>(num2);
     } else {
       acc_t<TBL::AT, IN_MAX> num[M][M];
       sandwich<TBL::AT, IN_MAX>(mi, num);
-      finish.template operator()<TBL::AT, IN_MAX>(num);
+      if (all_inside)
+        finish.template operator()<TBL::AT, IN_MAX, true>(num);
+      else
+        finish.template operator()<TBL::AT, IN_MAX, false>(num);
     }
   }
 }

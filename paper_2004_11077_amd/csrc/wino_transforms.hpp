@@ -674,6 +674,10 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
     });
   }
 
+  // ReLU as a lower bound (none: below every value).  A float is bounded through its bit
+  // pattern: negative values are negative integers, so one integer maximum with 0 clears
+  // them (and -0.0), with INT_MIN it changes nothing.
+  const int lo = relu ? 0 : (int)0x80000000;
   // block-uniform part (WHOLE) kept apart from the lane's channel
   const long ytile = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K;
   const int wk = g.W * g.K;
@@ -688,14 +692,14 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
           const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
           if constexpr (OUT == 0) {
             float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * mu.outer.v[idx];
-            __builtin_nontemporal_store(relu ? fmaxf(v, 0.f) : v, static_cast<float*>(yv) + ytile + rel + k);
+            __builtin_nontemporal_store(max(__float_as_int(v), lo),
+                                        static_cast<int*>(yv) + ytile + rel + k);
           } else if constexpr (OUT == 1) {
             int v = (int)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]);
-            __builtin_nontemporal_store(relu ? max(v, 0) : v, static_cast<int*>(yv) + ytile + rel + k);
+            __builtin_nontemporal_store(max(v, lo), static_cast<int*>(yv) + ytile + rel + k);
           } else {
             int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), mu.outer.v[idx], 127.f);
-            __builtin_nontemporal_store((int8_t)(relu ? max(v, 0) : v),
-                                        static_cast<int8_t*>(yv) + ytile + rel + k);
+            __builtin_nontemporal_store((int8_t)max(v, lo), static_cast<int8_t*>(yv) + ytile + rel + k);
           }
         }
       });
