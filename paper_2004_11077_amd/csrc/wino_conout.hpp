@@ -313,10 +313,10 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
     if constexpr (LEG) {
       acc_t<TBL::PinvT, IN_MAX> num1[n][n];
       sandwich<TBL::PinvT, IN_MAX>(mi, num1);
-      int m1[n][n];
-      cast_result<TBL::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
+      uint32_t m1[n][n];
+      cast_result_biased<TBL::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
       acc_t<TBL::APT, 127> num2[M][M];
-      sandwich<TBL::APT, 127>(m1, num2);
+      sandwich_codes<TBL::APT, 127>(m1, num2);
       if (all_inside)
         finish.template operator()<TBL::APT, 127, true>(num2);
       else

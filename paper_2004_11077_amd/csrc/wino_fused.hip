@@ -114,10 +114,10 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
     if constexpr (LEG) {
       acc_t<TB::PinvT, 127> num1[n][n];
       sandwich<TB::PinvT, 127>(xi, num1);
-      int x1[n][n];
-      cast_result<TB::PinvT, 127, true>(num1, in_mu.inner, 127.f, x1);
+      uint32_t x1[n][n];
+      cast_result_biased<TB::PinvT, 127, true>(num1, in_mu.inner, 127.f, x1);
       acc_t<TB::BPT, 127> num2[n][n];
-      sandwich<TB::BPT, 127>(x1, num2);
+      sandwich_codes<TB::BPT, 127>(x1, num2);
       cast_result<TB::BPT, 127, !PP>(num2, in_mu.outer, 127.f, q);
     } else {
       acc_t<TB::BT, 127> num[n][n];
@@ -230,10 +230,10 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
     if constexpr (LEG) {
       acc_t<TB::PinvT, IN_MAX> num1[n][n];
       sandwich<TB::PinvT, IN_MAX>(mi, num1);
-      int m1[n][n];
-      cast_result<TB::PinvT, IN_MAX, true>(num1, out_mu.inner, 127.f, m1);
+      uint32_t m1[n][n];
+      cast_result_biased<TB::PinvT, IN_MAX, true>(num1, out_mu.inner, 127.f, m1);
       acc_t<TB::APT, 127> num2[M][M];
-      sandwich<TB::APT, 127>(m1, num2);
+      sandwich_codes<TB::APT, 127>(m1, num2);
       finish.template operator()<TB::APT, 127>(num2);
     } else {
       acc_t<TB::AT, IN_MAX> num[M][M];

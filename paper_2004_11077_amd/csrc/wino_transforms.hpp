@@ -280,6 +280,100 @@ __device__ __forceinline__ auto entry(AccT v) {
   return from_slot<entry_kind<T, IN_MAX>(I, J)>(v);
 }
 
+// ---------------------------------------------------------------------------
+// Second bracket of a pair, fed with the 8-bit codes of the inner cast while they
+// are still biased floats (cast_biased: 1.5 * 2^23 + q; the low half of the
+// pattern is q as a 16-bit integer).  Where every coefficient of T.N fits 16 bits
+// the first pass runs on v_dot2_i32_i16: the codes of two columns are packed into
+// one register (one v_perm_b32 per pair, instead of one bias subtraction per
+// code) and a dot product takes two coefficients at a time.  Columns are paired
+// (0,2) (1,3) (4,6) (5,7) ..., so that a pair has one parity and serves the even /
+// odd parts that paired rows share; a last pair (cols-2, cols-1) of mixed parity
+// takes a zero coefficient for the column that is not wanted.  All sums are exact
+// 32-bit integers as before.  Otherwise the bias is subtracted and sandwich() runs.
+// ---------------------------------------------------------------------------
+typedef short v2s __attribute__((ext_vector_type(2)));
+
+template <const IMat& T, int64_t IN_MAX>
+constexpr bool dot2_first_pass() {
+  if (IN_MAX > 127 || !all_tmp_i32<T, IN_MAX>() || T.cols % 2 != 0) return false;
+  for (int i = 0; i < T.rows; ++i)
+    for (int a = 0; a < T.cols; ++a)
+      if (T.N[i][a] > 32767 || T.N[i][a] < -32768) return false;
+  return true;
+}
+// Columns of pair Q (see above).
+constexpr int pair_col(int cols, int q, int which) {
+  const int block = q / 2 * 4;
+  if (block + 3 < cols) return block + (q & 1) + 2 * which;
+  return cols - 2 + which;
+}
+// Coefficient of row ROW at column A if that column has parity PAR (2: any), else 0.
+template <const IMat& T, int ROW, int PAR>
+constexpr int64_t par_coef(int a) {
+  return (PAR == 2 || (a & 1) == PAR) ? T.N[ROW][a] : 0;
+}
+// sum over the columns of parity PAR of T.N[ROW][a] * code[a], codes packed in pairs.
+template <const IMat& T, int ROW, int PAR>
+__device__ __forceinline__ int32_t row_dot2(const uint32_t (&pk)[T.cols / 2]) {
+  int32_t acc = 0;
+  static_for<0, T.cols / 2>([&](auto q) {
+    constexpr int Q = decltype(q)::value;
+    constexpr int64_t c0 = par_coef<T, ROW, PAR>(pair_col(T.cols, Q, 0));
+    constexpr int64_t c1 = par_coef<T, ROW, PAR>(pair_col(T.cols, Q, 1));
+    if constexpr (c0 != 0 || c1 != 0) {
+      constexpr uint32_t k = (uint32_t)(uint16_t)(int16_t)c0 | ((uint32_t)(uint16_t)(int16_t)c1 << 16);
+      // Saturation on: no sum here can reach 2^31 (all_tmp_i32), so it never acts; it selects
+      // the three-operand form, whose accumulator may be the constant 0 (the two-operand
+      // v_dot2c accumulates in place and would need a zeroed register per chain).
+      acc = __builtin_amdgcn_sdot2(__builtin_bit_cast(v2s, pk[Q]), __builtin_bit_cast(v2s, k), acc,
+                                   true);
+    }
+  });
+  return acc;
+}
+
+template <const IMat& T, int64_t IN_MAX, typename AccT>
+__device__ __forceinline__ void sandwich_codes(const uint32_t (&bits)[T.cols][T.cols],
+                                               AccT (&num)[T.rows][T.rows]) {
+  static_assert(std::is_same_v<AccT, acc_t<T, IN_MAX>>);
+  if constexpr (dot2_first_pass<T, IN_MAX>()) {
+    constexpr bool s2 = (__int128)IN_MAX * T.rowsum < (1 << 23);
+    int32_t tmp[T.rows][T.cols];
+    static_for<0, T.cols>([&](auto b) {                    // tmp = N x, column by column
+      uint32_t pk[T.cols / 2];
+      static_for<0, T.cols / 2>([&](auto q) {
+        constexpr int Q = decltype(q)::value;
+        // low halves of the two patterns: (code of the first column) | (code of the second) << 16
+        pk[Q] = __builtin_amdgcn_perm(bits[pair_col(T.cols, Q, 1)][b], bits[pair_col(T.cols, Q, 0)][b],
+                                      0x05040100u);
+      });
+      static_for<0, T.rows>([&](auto i) {
+        constexpr int I = decltype(i)::value;
+        constexpr int PJ = partner_of(T, I);
+        if constexpr (PJ > I) {
+          const int32_t e = row_dot2<T, I, 0>(pk), o = row_dot2<T, I, 1>(pk);
+          tmp[I][b] = e + o;
+          tmp[PJ][b] = e - o;
+        } else if constexpr (PJ < 0) {
+          tmp[I][b] = row_dot2<T, I, 2>(pk);
+        }
+      });
+    });
+    static_for<0, T.rows>([&](auto i) {                    // num = tmp N^T, row by row
+      constexpr int I = decltype(i)::value;
+      apply_rows<T, s2, IN_MAX, I>([&](auto b) { return tmp[i][b]; },
+                                   [&](auto j, auto v) { num[i][j] = to_slot<AccT>(v); });
+    });
+  } else {
+    int x[T.cols][T.cols];
+    static_for<0, T.cols>([&](auto a) {
+      static_for<0, T.cols>([&](auto b) { x[a][b] = (int)bits[a][b] - 0x4B400000; });
+    });
+    sandwich<T, IN_MAX>(x, num);
+  }
+}
+
 // Numerator -> fp32 for a dequantised output.  64-bit numerators go through
 // their two halves (two conversions and one fma): not the correctly rounded
 // conversion, but within 2 ulp, which an fp32 output tolerates; casts to integer
@@ -345,6 +439,20 @@ __device__ __forceinline__ void cast_result(const AccT (&num)[T.rows][T.rows], c
   });
 }
 
+// The same casts left in their biased float form (for sandwich_codes).
+template <const IMat& T, int64_t IN_MAX, bool SHARE = false, typename AccT>
+__device__ __forceinline__ void cast_result_biased(const AccT (&num)[T.rows][T.rows],
+                                                   const MultTable& mu, float qmax,
+                                                   uint32_t (&q)[T.rows][T.rows]) {
+  static_for<0, T.rows>([&](auto i) {
+    static_for<0, T.rows>([&](auto j) {
+      constexpr int I = decltype(i)::value, J = decltype(j)::value;
+      constexpr int at = SHARE ? shared_mult_index<T, I, J>() : I * T.rows + J;
+      q[i][j] = cast_biased((float)entry<T, IN_MAX, I, J>(num[i][j]), mu.v[at], qmax);
+    });
+  });
+}
+
 // ---------------------------------------------------------------------------
 // Weight transform: one lane per (k, c) filter; a work group owns 256
 // consecutive filters (K * C is a multiple of 256, so every block is full).
@@ -391,10 +499,10 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
   if constexpr (LEG) {
     acc_t<TB::GP, 127> num1[n][n];
     sandwich<TB::GP, 127>(wi, num1);
-    int w1[n][n];
-    cast_result<TB::GP, 127, true>(num1, mu.inner, 127.f, w1);
+    uint32_t w1[n][n];
+    cast_result_biased<TB::GP, 127, true>(num1, mu.inner, 127.f, w1);
     acc_t<TB::Pinv, 127> num2[n][n];
-    sandwich<TB::Pinv, 127>(w1, num2);
+    sandwich_codes<TB::Pinv, 127>(w1, num2);
     cast_result<TB::Pinv, 127>(num2, mu.outer, 127.f, q);
   } else {
     acc_t<TB::G, 127> num[n][n];
@@ -514,10 +622,10 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   if constexpr (LEG) {
     acc_t<TB::PinvT, 127> num1[n][n];
     sandwich<TB::PinvT, 127>(xi, num1);
-    int x1[n][n];
-    cast_result<TB::PinvT, 127, true>(num1, mu.inner, 127.f, x1);
+    uint32_t x1[n][n];
+    cast_result_biased<TB::PinvT, 127, true>(num1, mu.inner, 127.f, x1);
     acc_t<TB::BPT, 127> num2[n][n];
-    sandwich<TB::BPT, 127>(x1, num2);
+    sandwich_codes<TB::BPT, 127>(x1, num2);
     cast_result<TB::BPT, 127>(num2, mu.outer, 127.f, q);
   } else {
     acc_t<TB::BT, 127> num[n][n];
@@ -708,10 +816,10 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   if constexpr (LEG) {
     acc_t<TB::PinvT, IN_MAX> num1[n][n];
     sandwich<TB::PinvT, IN_MAX>(xi, num1);
-    int m1[n][n];
-    cast_result<TB::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
+    uint32_t m1[n][n];
+    cast_result_biased<TB::PinvT, IN_MAX, true>(num1, mu.inner, 127.f, m1);
     acc_t<TB::APT, 127> num2[M][M];
-    sandwich<TB::APT, 127>(m1, num2);
+    sandwich_codes<TB::APT, 127>(m1, num2);
     finish.template operator()<TB::APT, 127>(num2);
   } else {
     acc_t<TB::AT, IN_MAX> num[M][M];
