@@ -28,62 +28,44 @@ WARM_SECONDS = 0.3             # back-to-back steps before anything is timed, wh
 STAGE_SAMPLES = 32             # event pairs per launch; the median is reported
 
 
-def measured_traffic(workload):
-    """HBM bytes per launch from profiles/hbm_traffic_<workload>.txt: lines
-    ``TRAFFIC <launch> fetched_KiB=<f> written_KiB=<w>`` hold rocprofv3 --pmc FETCH_SIZE /
+def profile_counters(workload):
+    """Per-launch counters from profiles/hbm_traffic_<workload>.txt (rocprofv3 --pmc runs of
+    this program).  Lines ``TRAFFIC <launch> fetched_KiB=<f> written_KiB=<w>`` hold FETCH_SIZE /
     WRITE_SIZE per dispatch, already scaled by what the same counters read for a plain device
-    copy of known size in the same run.  Empty when the file has no such line."""
+    copy of known size in the same run; lines ``VALU <launch> instructions=<n>`` hold
+    SQ_INSTS_VALU per dispatch (wave-level vector instructions).  Returns (bytes per launch,
+    vector instructions per launch); empty where the file has no such line."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
-    out = {}
+    traffic, valu = {}, {}
     if os.path.exists(path):
         with open(path) as f:
             for line in f:
                 parts = line.split()
                 if len(parts) == 4 and parts[0] == "TRAFFIC":
                     kv = dict(p.split("=") for p in parts[2:])
-                    out[parts[1]] = (float(kv["fetched_KiB"]) + float(kv["written_KiB"])) * 1024
-    return out
+                    traffic[parts[1]] = (float(kv["fetched_KiB"]) + float(kv["written_KiB"])) * 1024
+                elif len(parts) == 3 and parts[0] == "VALU":
+                    valu[parts[1]] = float(parts[2].split("=")[1])
+    return traffic, valu
 
 
-def bracket_ops(mats, names):
-    """Algorithmic vector-ALU operations of one item: per bracket N X N^T, one
-    operation per non-zero coefficient application (two passes) plus four per
-    cast (convert, multiply, clamp, round)."""
-    ops = 0
-    for name in names:
-        N, _ = mats.int_form(name)
-        rows, cols = len(N), len(N[0])
-        nnz = sum(1 for r in N for v in r if v != 0)
-        ops += nnz * cols + nnz * rows + 4 * rows * rows
-    return ops
-
-
-def stage_model(wl, m_bytes, y_bytes, mats):
-    """Algorithmic work of one launch of each kind (bytes, int8 ops, ALU ops)."""
+def stage_model(wl, m_bytes, y_bytes):
+    """Algorithmic work of one launch of each kind (bytes, int8 ops)."""
     n = wl.m + 2
     T, C, K = wl.tiles, wl.C, wl.K
-    leg = wl.base == "legendre"
-    alu = {"weight_transform": K * C * bracket_ops(mats, ["GP", "PINVT"] if leg else ["G"]),
-           "input_transform": T * C * bracket_ops(mats, ["PINVT", "BPT"] if leg else ["BT"]),
-           "output_transform": T * K * bracket_ops(mats, ["PINVT", "APT"] if leg else ["AT"])}
     model = _stage_bytes(wl, m_bytes, y_bytes, n, T, C, K)
-    for k, v in alu.items():
-        model[k]["alu_ops"] = v
     # a1 and a2 run as one launch
     model["operand_transforms"] = {
         "bound": "hbm",
-        "work": model["weight_transform"]["work"] + model["input_transform"]["work"],
-        "alu_ops": model["weight_transform"]["alu_ops"] + model["input_transform"]["alu_ops"]}
+        "work": model["weight_transform"]["work"] + model["input_transform"]["work"]}
     # a3 and a4 in one launch: the contraction's multiply-accumulates; U, V in and y out
     model["contraction_output"] = {
         "bound": "mfma", "work": model["contraction"]["work"],
-        "bytes": n * n * (T * C + K * C) + T * K * wl.m * wl.m * y_bytes,
-        "alu_ops": alu["output_transform"]}
+        "bytes": n * n * (T * C + K * C) + T * K * wl.m * wl.m * y_bytes}
     # a2 + a3 + a4 in one launch: x, V in and y out
     model["fused_layer"] = {
         "bound": "mfma", "work": model["contraction"]["work"],
-        "bytes": T * C * wl.m * wl.m + n * n * K * C + T * K * wl.m * wl.m * y_bytes,
-        "alu_ops": alu["output_transform"] + alu["input_transform"] * max(1, K // 64)}
+        "bytes": T * C * wl.m * wl.m + n * n * K * C + T * K * wl.m * wl.m * y_bytes}
     return model
 
 
@@ -281,11 +263,13 @@ def sample_launches(wn, torch, ev, call, n_launches, samples=STAGE_SAMPLES, gap=
     return med
 
 
-def price_stages(names, stage_ms, model, traffic, measured_peaks):
+def price_stages(names, stage_ms, model, traffic, valu, measured_peaks):
     """Every launch against its ceilings.  Transforms are priced against HBM (algorithmic bytes
-    over the kernel's duration; the vector-ALU rate is given beside it because the Legendre
-    brackets are arithmetic-heavy), kernels that contain the contraction against the int8 MFMA
-    peak (Winograd-domain multiply-accumulates actually issued)."""
+    over the kernel's duration), kernels that contain the contraction against the int8 MFMA
+    peak (Winograd-domain multiply-accumulates actually issued).  Because the Legendre brackets
+    are arithmetic-heavy, the rate at which the launch issued vector instructions is given
+    beside it where the profile holds its instruction count (valu_issue_*: SQ_INSTS_VALU x 64
+    lanes over the duration, against 256 CUs x 64 lanes x 2.4 GHz)."""
     stages = {}
     for nm in names:
         sec = stage_ms[nm] * 1e-3
@@ -305,9 +289,10 @@ def price_stages(names, stage_ms, model, traffic, measured_peaks):
                 st.update({"algorithmic_bytes": mdl["bytes"],
                            "hbm_GBps": mdl["bytes"] / sec / 1e9,
                            "hbm_frac": mdl["bytes"] / sec / 1e9 / HBM_PEAK_GBS})
-        if "alu_ops" in mdl:
-            alu = mdl["alu_ops"] / sec / 1e12
-            st.update({"alu_Tops": alu, "alu_frac": alu / VALU_PEAK_TOPS})
+        if nm in valu:
+            rate = valu[nm] * 64 / sec / 1e12
+            st.update({"valu_instructions": valu[nm], "valu_issue_Tops": rate,
+                       "valu_issue_frac": rate / VALU_PEAK_TOPS})
         st["traffic"] = traffic.get(nm)
         stages[nm] = st
     return stages
@@ -386,9 +371,13 @@ def measure_layer(wn, si, torch, ev, dev, wl_name, batch_scale, steps, warmup, m
     mats = wn.wino_make_matrices(wl.m, 3, [Fraction(*p) if isinstance(p, tuple) else p
                                            for p in pts], base)
     m_bytes = {8: 1, 9: 2, 32: 4}[wl.bits_hadamard]
-    model = stage_model(wl, m_bytes, 4, mats)
-    traffic = measured_traffic(wl.name) if batch_scale == 1 else {}
-    stages = price_stages(names, stage_ms, model, traffic, peaks)
+    model = stage_model(wl, m_bytes, 4)
+    traffic, valu = profile_counters(base_wl.name)
+    if batch_scale != 1:
+        # byte counters are not carried over to another batch size; a wave's instruction
+        # count does not depend on the batch, so the launch's count scales with it
+        traffic, valu = {}, {k: v * batch_scale for k, v in valu.items()}
+    stages = price_stages(names, stage_ms, model, traffic, valu, peaks)
     ops = 2.0 * wl.N * wl.H * wl.W * wl.C * wl.K * 9
     stage_sum = sum(med)
     res = {"workload": wl.name + ("" if batch_scale == 1 else "_batchx%d" % batch_scale),
@@ -472,7 +461,7 @@ def main():
                                                      "traffic")}
     roofline["kernel"] = dominant
     for k in ("frac_of_measured_peak", "algorithmic_bytes", "algorithmic_ops", "hbm_GBps",
-              "hbm_frac", "alu_Tops", "alu_frac"):
+              "hbm_frac", "valu_instructions", "valu_issue_Tops", "valu_issue_frac"):
         if k in stages[dominant]:
             roofline[k] = stages[dominant][k]
 
