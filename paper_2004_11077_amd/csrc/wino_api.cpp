@@ -350,21 +350,40 @@ bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
   return conout_covers(d, p) && d->m != 6;
 }
 
-// AUTO takes the two-kernel form where it was measured to be the faster one on C = K = 128 ...
-// 256 layers.  It saves the M round trip and a launch; it pays with operands re-read through
-// the L2 four times as often (32 x 32 blocks against the 128 x 128 tiles of the stand-alone
-// contraction) and with an input transform that is about 15 % slower into fragment order.
-//  * Its grid must fill most of the 256 compute units: with fewer work groups each streams
-//    its operands at one compute unit's rate (4x4 images, 512 channels: 23 us against 15 us).
-//  * On large batches the operand re-reads cost more than M saves (8192 tiles: 89 us against
-//    86 us for the two stages it replaces).
-//  * Net effect on the 256-channel 8x8 layer, N = 256: 26.7 us against 28.0 us when the
-//    filters arrive transformed, 28.4 us against 27.6 us when they do not (the filter
-//    transform into fragment order is slower too); with a 9-bit M (twice the bytes) 23.5 us
-//    against 27.2 us on the 128-channel 16x16 layer.  F(6,3): 59 us against 48 us (its output
-//    bracket needs 64-bit arithmetic and runs better at the stand-alone kernel's occupancy).
-constexpr long kConOutMinBlocks = 192;
-constexpr long kConOutMaxBlocks8 = 1024, kConOutMaxBlocks9 = 4096;
+// AUTO takes the two-kernel form where it was measured to be the faster one.  It saves the M
+// round trip and a launch; it pays with operands re-read through the L2 four times as often
+// (32 x 32 blocks against the 128 x 128 tiles of the stand-alone contraction) and with
+// operand transforms that are about 10 % slower into fragment order.  Measured, whole layer,
+// two-kernel form against one kernel per stage (us):
+//  * C <= 128: it wins at every size tried, with raw or transformed filters, fp32 or int8
+//    output: 16x16 images, C = K = 128, N = 32 / 256 / 2048: 18.1 / 36.5 / 223 against
+//    19.4 / 41.9 / 243; C = 64, K = 128: 28 against 32; C = 128, K = 256: 54 against 59.
+//    (A block's operand bytes go with C, its output brackets do not, and the stand-alone
+//    kernels waste half of their 128-byte channel chunks and 128-wide k blocks on such
+//    layers.)
+//  * C > 128: its grid must fill most of the 256 compute units (4x4 images, 512 channels, 128
+//    blocks: 32 against 22), and on large batches the operand re-reads cost more than M
+//    saves (C = K = 256: 8x8 images, N = 1024: 77 against 74 with fp32 output, 70 against 73
+//    with int8 output; 16384 tiles: 164 against 156).  In between, on the 256-channel 8x8
+//    layer at N = 256: 25.6 against 27 when the filters arrive transformed, 28.2 against 27.3
+//    when they do not and y is fp32 (28.2 against 29.0 with int8 output); with a 9-bit M
+//    (twice the bytes) 22.5 against 26.3 on the 128-channel 16x16 layer.
+//  * F(6,3): 59 against 48 (its output bracket needs 64-bit arithmetic and runs better at the
+//    stand-alone kernel's occupancy).
+constexpr int kConOutNarrowC = 128;            // up to here: whenever the grid has kConOutMinBlocksNarrow
+constexpr long kConOutMinBlocksNarrow = 64;
+constexpr long kConOutMinBlocks = 192;         // wider layers: between these block counts, and only
+constexpr long kConOutMaxBlocks8 = 1024;       // with transformed filters, an int8 y (up to twice the
+constexpr long kConOutMaxBlocks9 = 4096;       // blocks) or a 9-bit M
+
+bool auto_takes_conout(const wino_conv_desc_t* d, const Plan& p) {
+  const long blocks = contract_output_blocks(p.g, p.m_bits);
+  if (d->C <= kConOutNarrowC) return blocks >= kConOutMinBlocksNarrow;
+  if (blocks < kConOutMinBlocks) return false;
+  if (p.m_bits == 9) return blocks <= kConOutMaxBlocks9;
+  if (d->out_type == WINO_OUT_I8) return blocks <= 2 * kConOutMaxBlocks8;
+  return d->weights_pretransformed && blocks <= kConOutMaxBlocks8;
+}
 
 // ON: M never leaves the chip.  The single kernel where the layer has one 64-channel chunk
 // (its input transform is recomputed per 64 output channels and it keeps no accumulators
@@ -388,9 +407,7 @@ int select_path(const wino_conv_desc_t* d, const Plan& p, Path* path) {
   if (fused_all_covers(d, p) && d->C <= 64 && d->K <= 64 && !p.g.frag)
     *path = kPathFusedAll;
   else if (conout_covers(d, p) && g_opt_auto_conout && !v_rows_given && d->m != 6 &&
-           (p.m_bits == 9 || d->weights_pretransformed) &&
-           contract_output_blocks(p.g, p.m_bits) >= kConOutMinBlocks &&
-           contract_output_blocks(p.g, p.m_bits) <= (p.m_bits == 9 ? kConOutMaxBlocks9 : kConOutMaxBlocks8))
+           auto_takes_conout(d, p))
     *path = kPathConOut;
   return WINO_OK;
 }

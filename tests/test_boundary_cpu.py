@@ -175,6 +175,16 @@ def test_kernel_selection_and_workspace_of_the_whole_layer_call():
     assert wn.wino_workspace_bytes(narrow) == r256(36 * 64 * 64)
     few = wn.ConvDesc(256, 4, 4, 512, 512, m=4, fused=wn.FUSED_AUTO)   # 8 x 16 blocks: too few
     assert wn.wino_conv2d_launches(few) == ["operand_transforms", "contraction", "output_transform"]
+    # up to 128 input channels AUTO keeps M on chip whenever the grid is not tiny, raw filters too
+    for shape in [(256, 16, 16, 128, 128), (2048, 16, 16, 128, 128), (256, 16, 16, 64, 128)]:
+        d = wn.ConvDesc(*shape, m=4, fused=wn.FUSED_AUTO)
+        assert wn.wino_conv2d_launches(d) == ["operand_transforms", "contraction_output"], shape
+    tiny = wn.ConvDesc(2, 8, 8, 128, 32, m=4, fused=wn.FUSED_AUTO)     # one block
+    assert wn.wino_conv2d_launches(tiny) == ["operand_transforms", "contraction", "output_transform"]
+    # 256 channels, raw filters: with an int8 y, and up to 2048 blocks
+    i8 = dict(m=4, fused=wn.FUSED_AUTO, out_type=wn.OUT_I8)
+    assert wn.wino_conv2d_launches(wn.ConvDesc(256, 8, 8, 256, 256, **i8))[-1] == "contraction_output"
+    assert wn.wino_conv2d_launches(wn.ConvDesc(4096, 8, 8, 256, 256, **i8))[-1] == "output_transform"
     f6 = wn.ConvDesc(2, 8, 8, 32, 32, m=6, fused=wn.FUSED_ON)          # no single kernel for F(6,3)
     assert wn.wino_conv2d_launches(f6) == ["operand_transforms", "contraction_output"]
     assert wn.wino_conv2d_launches(wn.ConvDesc(0, 8, 8, 16, 16)) == []
