@@ -132,11 +132,12 @@ typedef struct {
                                  contraction + output transform (U in the
                                  workspace); needs bits_hadamard 8 or 9 and fp32
                                  or int8 output.  AUTO = the fastest of the three
-                                 for the shape: the single kernel for C, K <= 64;
-                                 the two-kernel form for mid-sized layers ON
-                                 covers (m = 2 or 4; enough tiles and output
-                                 channels to fill the device, not a large batch)
-                                 whose M is 9 bits wide or whose filters arrive
+                                 for the shape, as measured: the single kernel for
+                                 C, K <= 64; the two-kernel form (m = 2 or 4) for
+                                 layers with C <= 128, and for wider layers with
+                                 enough tiles and output channels to fill the
+                                 device but not a large batch whose M is 9 bits
+                                 wide, whose y is int8 or whose filters arrive
                                  transformed; one kernel per stage for the rest   */
   int operand_layout;         /* WINO_LAYOUT_*: order of U and V in the stage
                                  calls that write or read them; in wino_conv2d
