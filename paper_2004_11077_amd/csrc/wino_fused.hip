@@ -136,10 +136,10 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
   // ---- B: contraction for the wave's points; cast and park as M_s[p][tile][k] ----
   // D[k = 16 kb + 4 seg + v][tile = jl]
   const bool cok = seg * 16 < g.C;
-  int voff[NKB];                                     // the lane's V row and channel segment
+  unsigned voff[NKB];                                // the lane's V row and channel segment
 #pragma unroll
   for (int kb = 0; kb < NKB; ++kb)
-    voff[kb] = min(k0 + kb * 16 + jl, g.K - 1) * g.C + (cok ? seg * 16 : 0);   // clamp, masked at the store
+    voff[kb] = (unsigned)(min(k0 + kb * 16 + jl, g.K - 1) * g.C + (cok ? seg * 16 : 0));   // clamp, masked at the store
 #pragma clang loop unroll_count(3)
   for (int pi = 0; pi < NPW; ++pi) {
     const int p = pi * kFW + wave;
@@ -207,13 +207,16 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
     constexpr int YB = OUT == 0 ? 4 : 1;             // bytes of one output
     char* ytile = static_cast<char*>(yv) + (((long)ti.x * g.H + ty_m) * g.W + tx_m) * g.K * YB;
     const long wkb = (long)g.W * g.K * YB, kb1 = (long)g.K * YB;
-    const unsigned kbyte = (unsigned)k * YB;
+    unsigned kbyte = (unsigned)k * YB;               // the lane's part of every store address
     auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
           constexpr int I = decltype(i)::value, J = decltype(j)::value;
           constexpr int idx = shared_mult_index<FT, I, J>();
           if (ty_m + I < g.H && tx_m + J < g.W) {
+            // the lane's part of the address enters the sum inside this block, so that the store
+            // takes the form scalar base + 32-bit lane offset (no vector address arithmetic)
+            if constexpr (KB == 64) asm("" : "+v"(kbyte));
             char* at = ytile + (I * wkb + J * kb1) + kbyte;
             if constexpr (OUT == 0) {
               const float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * out_mu.outer.v[idx];

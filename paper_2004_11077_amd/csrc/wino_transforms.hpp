@@ -786,8 +786,14 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   // pattern: negative values are negative integers, so one integer maximum with 0 clears
   // them (and -0.0), with INT_MIN it changes nothing.
   const int lo = relu ? 0 : (int)0x80000000;
-  // block-uniform part (WHOLE) kept apart from the lane's channel
+  // Store addresses: with WHOLE the block is one tile, so everything but the lane's own
+  // channel is block-uniform and stays in scalar registers; the lane's byte offset is made
+  // opaque inside each store's block so that the sum is formed there and the store takes the
+  // form scalar base + 32-bit lane offset (no vector address arithmetic).
+  constexpr int YB = OUT == 2 ? 1 : 4;               // bytes of one output
   const long ytile = (((long)b * g.H + ty * M) * g.W + tx * M) * g.K;
+  char* ybase = static_cast<char*>(yv) + (ytile + (WHOLE ? k - tid : k)) * YB;
+  unsigned lane_off = WHOLE ? (unsigned)tid * YB : 0u;
   const int wk = g.W * g.K;
   auto finish = [&]<const IMat& FT, int64_t FIN>(auto& num) {
     static_for<0, M>([&](auto i) {
@@ -798,16 +804,17 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
         const int ww = tx * M + decltype(j)::value;
         if (h < g.H && ww < g.W) {
           const int rel = decltype(i)::value * wk + decltype(j)::value * g.K;
+          if constexpr (WHOLE) asm("" : "+v"(lane_off));
+          char* at = ybase + (long)rel * YB + lane_off;
           if constexpr (OUT == 0) {
             float v = to_float_approx(entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j])) * mu.outer.v[idx];
-            __builtin_nontemporal_store(max(__float_as_int(v), lo),
-                                        static_cast<int*>(yv) + ytile + rel + k);
+            __builtin_nontemporal_store(max(__float_as_int(v), lo), reinterpret_cast<int*>(at));
           } else if constexpr (OUT == 1) {
             int v = (int)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]);
-            __builtin_nontemporal_store(max(v, lo), static_cast<int*>(yv) + ytile + rel + k);
+            __builtin_nontemporal_store(max(v, lo), reinterpret_cast<int*>(at));
           } else {
             int v = cast_code((float)entry<FT, FIN, decltype(i)::value, decltype(j)::value>(num[i][j]), mu.outer.v[idx], 127.f);
-            __builtin_nontemporal_store((int8_t)max(v, lo), static_cast<int8_t*>(yv) + ytile + rel + k);
+            __builtin_nontemporal_store((int8_t)max(v, lo), reinterpret_cast<int8_t*>(at));
           }
         }
       });
