@@ -55,6 +55,9 @@ struct Geometry {
   int frag;     // 1: U and V are in MFMA-fragment order (below), 0: rows [n*n][T or K][C]
   // division of a tile index (< 2^30) by TW and by TW * TH as multiply-high and shift
   uint32_t mul_tw, sh_tw, mul_im, sh_im;
+  // division of a work-group index (< 2^30) by the groups per tile of the one-tile-per-group
+  // transform kernels: C / 256 (input), K / 256 (output); 1 where that is not a whole number
+  uint32_t mul_cg, sh_cg, mul_kg, sh_kg;
   // input transform: work groups per image when every image's groups are to run on one XCD
   // (0 = work groups in plain order), and the number of groups covered by that order
   int img_blocks, img_blocks_end;
@@ -87,7 +90,15 @@ inline void fast_div_setup(uint32_t d, uint32_t* mul, uint32_t* sh) {
 inline void geometry_set_divisors(Geometry& g) {
   fast_div_setup((uint32_t)(g.TW > 0 ? g.TW : 1), &g.mul_tw, &g.sh_tw);
   fast_div_setup((uint32_t)(g.TW * g.TH > 0 ? g.TW * g.TH : 1), &g.mul_im, &g.sh_im);
+  fast_div_setup((uint32_t)(g.C >= 256 && g.C % 256 == 0 ? g.C / 256 : 1), &g.mul_cg, &g.sh_cg);
+  fast_div_setup((uint32_t)(g.K >= 256 && g.K % 256 == 0 ? g.K / 256 : 1), &g.mul_kg, &g.sh_kg);
 }
+#if defined(__HIPCC__)
+// n / d with the pair prepared by fast_div_setup for d (n < 2^30).
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, uint32_t mul, uint32_t sh) {
+  return (mul ? __umulhi(n, mul) : n) >> sh;
+}
+#endif
 #if defined(__HIPCC__)
 // tile t -> (image b, tile row ty, tile column tx) with t = (b TH + ty) TW + tx, t < 2^30.
 __device__ __forceinline__ void tile_coords(const Geometry& g, int t, int& b, int& ty, int& tx) {

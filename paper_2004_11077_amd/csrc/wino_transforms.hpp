@@ -570,8 +570,8 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
   int ut, uc;
   bool uok = WHOLE || ug < total;
   if constexpr (WHOLE) {
-    ut = (int)(gid0 / g.C);                       // uniform
-    uc = (int)(gid0 - (long)ut * g.C) + u * 16;
+    ut = (int)fast_div(block, g.mul_cg, g.sh_cg);                    // uniform: C / 256 groups per tile
+    uc = (int)(block - (unsigned)ut * (unsigned)(g.C >> 8)) * 256 + u * 16;
   } else if (g.frag) {
     // Fragment order: the block's 256 items are 4 tiles x one 64-channel chunk (unit u = tile
     // 4 tq + u / 4, channels 64 chunk + 16 (u % 4) ...): a quad of lanes loads 64 contiguous
@@ -730,8 +730,9 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   const bool active = WHOLE || gid < total;
   int t, k;
   if constexpr (WHOLE) {
-    t = (int)(gid0 / g.K);                        // uniform
-    k = (int)(gid0 - (long)t * g.K) + tid;
+    const unsigned block = (unsigned)(gid0 >> 8);
+    t = (int)fast_div(block, g.mul_kg, g.sh_kg);                     // uniform: K / 256 groups per tile
+    k = (int)(block - (unsigned)t * (unsigned)(g.K >> 8)) * 256 + tid;
   } else {
     t = active ? (int)(gid / g.K) : 0;
     k = active ? (int)(gid - (long)t * g.K) : 0;
@@ -843,7 +844,7 @@ static inline unsigned blocks_for(long items) { return (unsigned)((items + 255) 
 // A work group's 256 items are the channels of one tile (and offsets inside one
 // image fit 32 bits): the kernels then keep the tile arithmetic in scalar registers.
 static inline bool whole_tiles(int channels, int H, int W) {
-  return channels % 256 == 0 && (long)H * W * channels < (1L << 31);
+  return channels > 0 && channels % 256 == 0 && (long)H * W * channels < (1L << 31);
 }
 // Work groups of the operand transforms: 256 consecutive items each in row order; in
 // fragment order one per (4 rows, 64-channel chunk).
