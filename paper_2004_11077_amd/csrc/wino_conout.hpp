@@ -154,10 +154,13 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
   const long ustep = FRAG ? (long)kCoWaves * rgU * nch * 1024 : (long)kCoWaves * g.T * C;
   const int8_t* vrow = FRAG ? V : V + ((long)wave * g.K + k0) * C;
   const int8_t* urow = FRAG ? U : U + ((long)wave * g.T + t0) * C;
-  const uint32_t lane16 = lane * 16;
+  uint32_t lane16 = lane * 16;
   int lpi = 0, lci = 0;
   auto load = [&](Frag& f) {
     if constexpr (FRAG) {
+      // made opaque here so that its zero-extension is formed in this block and the loads take
+      // the form scalar base + 32-bit lane offset (no 64-bit vector adds)
+      asm("" : "+v"(lane16));
       const long c0 = (long)(2 * lci) * 1024, c1 = (long)min(2 * lci + 1, nch - 1) * 1024;
 #pragma unroll
       for (int i = 0; i < NKB; ++i) {
@@ -192,10 +195,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
   };
 
   v4i acc[NKB][NTB];
-#pragma unroll
-  for (int i = 0; i < NKB; ++i)
-#pragma unroll
-    for (int j = 0; j < NTB; ++j) acc[i][j] = v4i{0, 0, 0, 0};
   int cpi = 0, cci = 0;                              // unit being consumed
   auto consume = [&](Frag& f) {
     const bool last = cci == nchunks - 1;
@@ -208,11 +207,21 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
         for (int i = 0; i < NTB; ++i) f.b[i][h] &= keep[h];
       }
     }
+    // the first unit of a point starts from the constant zero (wave-uniform branch): no
+    // accumulator is cleared between points
+    if (cci == 0) {
 #pragma unroll
-    for (int i = 0; i < NKB; ++i)
+      for (int i = 0; i < NKB; ++i)
 #pragma unroll
-      for (int j = 0; j < NTB; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(f.a[i][0], f.b[j][0], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < NTB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(f.a[i][0], f.b[j][0], v4i{0, 0, 0, 0}, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NKB; ++i)
+#pragma unroll
+        for (int j = 0; j < NTB; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_i32_16x16x64_i8(f.a[i][0], f.b[j][0], acc[i][j], 0, 0, 0);
+    }
     if (!last || last_has_two) {
 #pragma unroll
       for (int i = 0; i < NKB; ++i)
@@ -233,7 +242,6 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
           uint32_t q[4];
 #pragma unroll
           for (int v = 0; v < 4; ++v) q[v] = cast_biased((float)acc[i][j][v], mult, QM);
-          acc[i][j] = v4i{0, 0, 0, 0};
           // the four-code group index inside a tile's row is XOR-ed with the tile's low
           // bits: the 16 tiles a store covers then fall on distinct LDS banks
           MT* dst = M_s + (p * TB + j * 16 + jl) * KB + (((i * 4 + seg) ^ (jl & (KB / 4 - 1))) << 2);
@@ -295,13 +303,14 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
       static_for<0, M>([&](auto i) {
         static_for<0, M>([&](auto j) {
           constexpr int I = decltype(i)::value, J = decltype(j)::value;
+          constexpr int at_mult = shared_mult_index<FT, I, J>();   // one scale for y
           if (FULL || (ty_m + I < g.H && tx_m + J < g.W)) {
             char* at = yitem + (I * wkb + J * kb1);
             if constexpr (OUT == 0) {
-              const float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * mu.outer.v[shared_mult_index<FT, I, J>()];
+              const float v = to_float_approx(entry<FT, FIN, I, J>(num[i][j])) * mu.outer.v[at_mult];
               __builtin_nontemporal_store(max(__float_as_int(v), lo_f), reinterpret_cast<int*>(at));
             } else {
-              const int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), mu.outer.v[shared_mult_index<FT, I, J>()], 127.f);
+              const int v = cast_code((float)entry<FT, FIN, I, J>(num[i][j]), mu.outer.v[at_mult], 127.f);
               __builtin_nontemporal_store((int8_t)max(v, lo_i), reinterpret_cast<int8_t*>(at));
             }
           }
