@@ -134,18 +134,22 @@ typedef struct {
                                  or int8 output.  AUTO = the fastest of the three
                                  for the shape, as measured: the single kernel for
                                  C, K <= 64; the two-kernel form (m = 2 or 4) for
-                                 layers with C <= 128, and for wider layers with
-                                 enough tiles and output channels to fill the
-                                 device but not a large batch whose M is 9 bits
-                                 wide, whose y is int8 or whose filters arrive
-                                 transformed; one kernel per stage for the rest   */
+                                 layers with C <= 128, for layers with C <= 256
+                                 whose M is 9 bits wide, or whose filters arrive
+                                 transformed and whose grid is about one work
+                                 group per compute unit, and whenever V is handed
+                                 over in fragment order; one kernel per stage for
+                                 the rest                                         */
   int operand_layout;         /* WINO_LAYOUT_*: order of U and V in the stage
                                  calls that write or read them; in wino_conv2d
                                  the order of a pretransformed V (U, and a V it
                                  computes itself, live in the workspace in the
                                  order its kernels want).  The two-kernel form
                                  is fast with FRAGMENTS; given a pretransformed
-                                 V in ROWS, AUTO runs one kernel per stage        */
+                                 V in ROWS, AUTO runs one kernel per stage; given
+                                 one in FRAGMENTS it runs the two-kernel form
+                                 (wino_preferred_operand_layout says which of
+                                 the two is the faster for a layer)               */
 } wino_conv_desc_t;
 
 /* Symmetric scales, supplied by the caller (or chosen by wino_calibrate).

@@ -356,32 +356,34 @@ bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
 // operand transforms that are about 10 % slower into fragment order.  Measured, whole layer,
 // two-kernel form against one kernel per stage (us):
 //  * C <= 128: it wins at every size tried, with raw or transformed filters, fp32 or int8
-//    output: 16x16 images, C = K = 128, N = 32 / 256 / 2048: 18.1 / 36.5 / 223 against
-//    19.4 / 41.9 / 243; C = 64, K = 128: 28 against 32; C = 128, K = 256: 54 against 59.
+//    output: 16x16 images, C = K = 128, N = 32 / 256 / 2048: 16.8 / 35.4 / 218 against
+//    20.8 / 37.2 / 226; C = 64, K = 128: 26 against 31; C = 128, K = 256: 52 against 54.
 //    (A block's operand bytes go with C, its output brackets do not, and the stand-alone
 //    kernels waste half of their 128-byte channel chunks and 128-wide k blocks on such
 //    layers.)
-//  * C > 128: its grid must fill most of the 256 compute units (4x4 images, 512 channels, 128
-//    blocks: 32 against 22), and on large batches the operand re-reads cost more than M
-//    saves (C = K = 256: 8x8 images, N = 1024: 77 against 74 with fp32 output, 70 against 73
-//    with int8 output; 16384 tiles: 164 against 156).  In between, on the 256-channel 8x8
-//    layer at N = 256: 25.6 against 27 when the filters arrive transformed, 28.2 against 27.3
-//    when they do not and y is fp32 (28.2 against 29.0 with int8 output); with a 9-bit M
-//    (twice the bytes) 22.5 against 26.3 on the 128-channel 16x16 layer.
+//  * 128 < C <= 256, 8-bit M: the stand-alone kernels are as fast or faster at every size
+//    (8x8 images, C = K = 256, fp32 y, filters transformed, N = 128 / 384 / 512 / 1024: 21.3 /
+//    37.3 / 41.1 / 72.9 against 20.1 / 32.0 / 39.1 / 68.0) except where the grid is one work
+//    group per compute unit and the filters arrive transformed (N = 256: 24.4 against 24.7
+//    with fp32 y, 23.8 against 25.0 with int8 y; raw filters 26.9 against 26.5).
+//  * 128 < C <= 256, 9-bit M (twice the bytes of M): it wins from 256 to 16384 tiles (N = 256 /
+//    1024 / 4096: 24.5 / 72.4 / 257 against 27.0 / 77.9 / 268).
+//  * C > 256: a block's operand bytes go with C and it loses (C = K = 512, 4x4 images: 32 against
+//    22 at N = 256, 8-bit; 8x8 images, 9-bit: 57 against 48).
 //  * F(6,3): 59 against 48 (its output bracket needs 64-bit arithmetic and runs better at the
 //    stand-alone kernel's occupancy).
 constexpr int kConOutNarrowC = 128;            // up to here: whenever the grid has kConOutMinBlocksNarrow
 constexpr long kConOutMinBlocksNarrow = 64;
-constexpr long kConOutMinBlocks = 192;         // wider layers: between these block counts, and only
-constexpr long kConOutMaxBlocks8 = 1024;       // with transformed filters, an int8 y (up to twice the
-constexpr long kConOutMaxBlocks9 = 4096;       // blocks) or a 9-bit M
+constexpr int kConOutWideC = 256;              // up to here: between these block counts, with a 9-bit M,
+constexpr long kConOutMinBlocks = 192;         // or with an 8-bit M and transformed filters when the
+constexpr long kConOutMaxBlocks8 = 256;        // grid is about one work group per compute unit
+constexpr long kConOutMaxBlocks9 = 4096;
 
 bool auto_takes_conout(const wino_conv_desc_t* d, const Plan& p) {
   const long blocks = contract_output_blocks(p.g, p.m_bits);
   if (d->C <= kConOutNarrowC) return blocks >= kConOutMinBlocksNarrow;
-  if (blocks < kConOutMinBlocks) return false;
+  if (d->C > kConOutWideC || blocks < kConOutMinBlocks) return false;
   if (p.m_bits == 9) return blocks <= kConOutMaxBlocks9;
-  if (d->out_type == WINO_OUT_I8) return blocks <= 2 * kConOutMaxBlocks8;
   return d->weights_pretransformed && blocks <= kConOutMaxBlocks8;
 }
 
@@ -406,6 +408,8 @@ int select_path(const wino_conv_desc_t* d, const Plan& p, Path* path) {
   const bool v_rows_given = d->weights_pretransformed && !p.g.frag;   // slow in the two-kernel form
   if (fused_all_covers(d, p) && d->C <= 64 && d->K <= 64 && !p.g.frag)
     *path = kPathFusedAll;
+  else if (conout_covers(d, p) && d->weights_pretransformed && p.g.frag)
+    *path = kPathConOut;                       // the only form that reads a V in fragment order
   else if (conout_covers(d, p) && g_opt_auto_conout && !v_rows_given && d->m != 6 &&
            auto_takes_conout(d, p))
     *path = kPathConOut;
@@ -672,11 +676,9 @@ int wino_preferred_operand_layout(const wino_conv_desc_t* d, int* layout) {
   Path path;
   if (int rc = select_path(&dd, p, &path)) return rc;
   if (path == kPathFusedAll || p.fp32) return WINO_OK;   // the single kernel reads V in rows
-  // would AUTO take the two-kernel form if V came in fragment order?
-  dd.operand_layout = WINO_LAYOUT_FRAGMENTS;
-  if (int rc = make_plan(&dd, &p)) return rc;
-  if (int rc = select_path(&dd, p, &path)) return rc;
-  if (path == kPathConOut) *layout = WINO_LAYOUT_FRAGMENTS;
+  // would AUTO take the two-kernel form, on its merits, for filters that arrive transformed?
+  if (conout_covers(&dd, p) && g_opt_auto_conout && dd.m != 6 && auto_takes_conout(&dd, p))
+    *layout = WINO_LAYOUT_FRAGMENTS;
   return WINO_OK;
 }
 

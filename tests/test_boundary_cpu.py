@@ -181,10 +181,17 @@ def test_kernel_selection_and_workspace_of_the_whole_layer_call():
         assert wn.wino_conv2d_launches(d) == ["operand_transforms", "contraction_output"], shape
     tiny = wn.ConvDesc(2, 8, 8, 128, 32, m=4, fused=wn.FUSED_AUTO)     # one block
     assert wn.wino_conv2d_launches(tiny) == ["operand_transforms", "contraction", "output_transform"]
-    # 256 channels, raw filters: with an int8 y, and up to 2048 blocks
-    i8 = dict(m=4, fused=wn.FUSED_AUTO, out_type=wn.OUT_I8)
-    assert wn.wino_conv2d_launches(wn.ConvDesc(256, 8, 8, 256, 256, **i8))[-1] == "contraction_output"
-    assert wn.wino_conv2d_launches(wn.ConvDesc(4096, 8, 8, 256, 256, **i8))[-1] == "output_transform"
+    # 256 channels, 8-bit M: only with transformed filters and one work group per compute unit
+    pre = dict(m=4, fused=wn.FUSED_AUTO, weights_pretransformed=1, operand_layout=wn.LAYOUT_FRAGMENTS)
+    assert wn.wino_conv2d_launches(wn.ConvDesc(256, 8, 8, 256, 256, **pre))[-1] == "contraction_output"
+    big = wn.ConvDesc(512, 8, 8, 256, 256, m=4, fused=wn.FUSED_AUTO)
+    assert wn.wino_preferred_operand_layout(big) == wn.LAYOUT_ROWS      # a larger grid: stage by stage
+    # ... but a V that is handed over in fragment order is read by the form that can read it
+    assert wn.wino_conv2d_launches(wn.ConvDesc(512, 8, 8, 256, 256, **pre))[-1] == "contraction_output"
+    # ... with a 9-bit M at any size, but not beyond 256 channels
+    h9 = dict(m=4, fused=wn.FUSED_AUTO, bits_hadamard=9)
+    assert wn.wino_conv2d_launches(wn.ConvDesc(4096, 8, 8, 256, 256, **h9))[-1] == "contraction_output"
+    assert wn.wino_conv2d_launches(wn.ConvDesc(256, 8, 8, 512, 512, **h9))[-1] == "output_transform"
     f6 = wn.ConvDesc(2, 8, 8, 32, 32, m=6, fused=wn.FUSED_ON)          # no single kernel for F(6,3)
     assert wn.wino_conv2d_launches(f6) == ["operand_transforms", "contraction_output"]
     assert wn.wino_conv2d_launches(wn.ConvDesc(0, 8, 8, 16, 16)) == []
