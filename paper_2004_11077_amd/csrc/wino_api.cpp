@@ -303,7 +303,7 @@ int contract_mults(const Plan& p, const wino_scales_t* s, MultTable* mult, Shift
   for (int q = 0; q < n2; ++q) {
     const double s_uv = (double)s->s_u_pt[q] * (double)s->s_v_pt[q];
     mult->v[q] = (float)(s_uv * std::ldexp(1.0, s->m_shift[q]) / (double)s->s_m);
-    if (sh) sh->v[q] = smax - s->m_shift[q];
+    if (sh) sh->set(q, smax - s->m_shift[q]);
   }
   *s_fed = std::ldexp((double)s->s_m, -smax);
   return WINO_OK;
@@ -958,7 +958,7 @@ int calibrate_contraction(CalCtx& c, const wino_conv_desc_t* d, const wino_conv_
       s->m_shift[q] = sft;
       if (sft > smax) smax = sft;
     }
-    for (int q = 0; q < n2; ++q) sh->v[q] = smax - s->m_shift[q];
+    for (int q = 0; q < n2; ++q) sh->set(q, smax - s->m_shift[q]);
     *s_fed = std::ldexp((double)s->s_m, -smax);
   }
   return wino_contract(&dd, U, V, M, s, c.st);

@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void k_cal_output(const MT* __restrict__ Mq,
   static_for<0, n>([&](auto i) {
     static_for<0, n>([&](auto j) {
       xi[i][j] = active ? (int)Mq[(long)(decltype(i)::value * n + decltype(j)::value) * total + gid] : 0;
-      if constexpr (PP) xi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
+      if constexpr (PP) xi[i][j] <<= sh.template at<decltype(i)::value * n + decltype(j)::value>();
     });
   });
   // entries of partial tiles that fall outside the image are cropped, so they

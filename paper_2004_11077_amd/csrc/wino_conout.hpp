@@ -291,7 +291,7 @@ __global__ __launch_bounds__(NW * 64, WPE) void k_contract_out(const int8_t* __r
       static_for<0, n>([&](auto j) {
         constexpr int P = decltype(i)::value * n + decltype(j)::value;
         mi[i][j] = (int)M_s[(P * TB + tl) * KB + ksw];
-        if constexpr (PP) mi[i][j] <<= sh.v[P];
+        if constexpr (PP) mi[i][j] <<= sh.template at<P>();
       });
     });
     constexpr int YB = OUT == 0 ? 4 : 1;             // bytes of one output

@@ -37,7 +37,7 @@ __device__ __forceinline__ int sw(int tile, int byte) {
 }
 
 // PP: per-point scales -- the cast of point p uses mm.v[p], and its codes enter
-// the output bracket shifted left by sh.v[p] (<= kMaxMShift, priced into the
+// the output bracket shifted left by entry p of sh (<= kMaxMShift, priced into the
 // bounds).  Without PP every entry of mm is the same and sh is not read.
 template <int M, bool LEG, typename MT, int OUT, bool PP>
 __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict__ x,
@@ -201,7 +201,7 @@ __global__ __launch_bounds__(kFW * 64, 6) void k_fused(const int8_t* __restrict_
       static_for<0, n>([&](auto j) {
         mi[i][j] = (int)*reinterpret_cast<const MT*>(
             smem + (decltype(i)::value * n + decltype(j)::value) * kPt + sw(tl, kl * (int)sizeof(MT)));
-        if constexpr (PP) mi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
+        if constexpr (PP) mi[i][j] <<= sh.template at<decltype(i)::value * n + decltype(j)::value>();
       });
     });
     constexpr int YB = OUT == 0 ? 4 : 1;             // bytes of one output

@@ -41,9 +41,25 @@ struct MultTable {
 };
 
 // Left shifts applied to the codes of M before the output bracket when M has
-// per-point power-of-two scales (entry p = i*n + j; all zero otherwise).
+// per-point power-of-two scales (entry p = i*n + j; all zero otherwise).  Four bits per
+// entry (a shift is at most kMaxMShift = 8), eight entries per word: a kernel keeps the whole
+// table in 8 scalar registers and extracts an entry where it is used, instead of holding up
+// to 64 registers live across its loops.
 struct ShiftTable {
-  int v[kMaxPts];
+  uint32_t w[kMaxPts / 8];
+  void set(int p, int shift) {
+    w[p >> 3] = (w[p >> 3] & ~(15u << ((p & 7) * 4))) | ((uint32_t)shift << ((p & 7) * 4));
+  }
+#if defined(__HIPCC__)
+  // Entry P as a wave-uniform value.  The extraction is kept where it is written (volatile):
+  // moved out of a loop, the entries would again occupy one scalar register each.
+  template <int P>
+  __device__ __forceinline__ int at() const {
+    uint32_t r;
+    asm volatile("s_bfe_u32 %0, %1, %2" : "=s"(r) : "s"(w[P >> 3]), "n"(((P & 7) * 4) | (4 << 16)) : "scc");
+    return (int)r;
+  }
+#endif
 };
 constexpr int kMaxMShift = 8;
 

@@ -715,7 +715,7 @@ struct MTraits<int32_t> {
 // WHOLE: K is a multiple of 256, so a work group's items are 256 output
 // channels of ONE tile and the tile arithmetic is block-uniform.
 // PP: M carries per-point power-of-two scales; the codes of point p enter the
-// bracket shifted left by sh.v[p] <= kMaxMShift, which the bounds account for.
+// bracket shifted left by entry p of sh <= kMaxMShift, which the bounds account for.
 template <int M, bool LEG, typename MT, int OUT, bool WHOLE, bool PP, int BASE = 1>
 __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__ Mq,
                                                           void* __restrict__ yv, Geometry g,
@@ -778,7 +778,7 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   if constexpr (PP) {
     static_for<0, n>([&](auto i) {
       static_for<0, n>([&](auto j) {
-        xi[i][j] <<= sh.v[decltype(i)::value * n + decltype(j)::value];
+        xi[i][j] <<= sh.template at<decltype(i)::value * n + decltype(j)::value>();
       });
     });
   }
