@@ -163,8 +163,10 @@ int make_plan(const wino_conv_desc_t* d, Plan* p) {
     return fail(WINO_EINVAL, "unknown operand_layout %d", d->operand_layout);
   if (d->operand_layout == WINO_LAYOUT_FRAGMENTS && p->fp32)
     return fail(WINO_EUNSUPPORTED, "fragment order is a layout of the int8 operands");
-  p->g = Geometry{d->N, d->H, d->W, d->C, d->K, d->m, (int)TH, (int)TW, (int)T,
-                  d->operand_layout == WINO_LAYOUT_FRAGMENTS ? 1 : 0, 0, 0, 0, 0, 0, 0};
+  p->g = Geometry{};   // divisors and the XCD dealing are filled in below / by the launchers
+  p->g.N = d->N, p->g.H = d->H, p->g.W = d->W, p->g.C = d->C, p->g.K = d->K, p->g.m = d->m;
+  p->g.TH = (int)TH, p->g.TW = (int)TW, p->g.T = (int)T;
+  p->g.frag = d->operand_layout == WINO_LAYOUT_FRAGMENTS ? 1 : 0;
   geometry_set_divisors(p->g);
   if (!stages_for(d->m, d->base, &p->st)) return fail(WINO_EUNSUPPORTED, "m = %d", d->m);
   p->two_brackets = d->base != WINO_BASE_CANONICAL && d->inner_quant != 0;
