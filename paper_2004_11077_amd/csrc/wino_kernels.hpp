@@ -74,6 +74,9 @@ struct Geometry {
   // division of a work-group index (< 2^30) by the groups per tile of the one-tile-per-group
   // transform kernels: C / 256 (input), K / 256 (output); 1 where that is not a whole number
   uint32_t mul_cg, sh_cg, mul_kg, sh_kg;
+  // division of a work-group index by the 64-channel chunks of a row, ceil(C / 64): the groups
+  // of the fragment-order transforms are (four rows, one chunk)
+  uint32_t mul_ch, sh_ch;
   // input transform: work groups per image when every image's groups are to run on one XCD
   // (0 = work groups in plain order), and the number of groups covered by that order
   int img_blocks, img_blocks_end;
@@ -108,6 +111,7 @@ inline void geometry_set_divisors(Geometry& g) {
   fast_div_setup((uint32_t)(g.TW * g.TH > 0 ? g.TW * g.TH : 1), &g.mul_im, &g.sh_im);
   fast_div_setup((uint32_t)(g.C >= 256 && g.C % 256 == 0 ? g.C / 256 : 1), &g.mul_cg, &g.sh_cg);
   fast_div_setup((uint32_t)(g.K >= 256 && g.K % 256 == 0 ? g.K / 256 : 1), &g.mul_kg, &g.sh_kg);
+  fast_div_setup((uint32_t)(g.C > 64 ? (g.C + 63) / 64 : 1), &g.mul_ch, &g.sh_ch);
 }
 #if defined(__HIPCC__)
 // n / d with the pair prepared by fast_div_setup for d (n < 2^30).

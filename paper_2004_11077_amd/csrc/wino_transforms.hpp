@@ -476,7 +476,8 @@ __device__ __forceinline__ void weight_body(const int8_t* __restrict__ w, int8_t
   // contiguous bytes, and a point's results are four 64-byte pieces of a fragment.  Filters
   // past C (partial last chunk) are dead: zero taps in, nothing stored.
   const int nch = (g.C + 63) >> 6;
-  const int kq = g.frag ? (int)(block / nch) : 0, chunk = g.frag ? (int)(block % nch) : 0;
+  const int kq = g.frag ? (int)fast_div(block, g.mul_ch, g.sh_ch) : 0;
+  const int chunk = g.frag ? (int)block - kq * nch : 0;
   const int cw = g.frag ? min(64, g.C - chunk * 64) : 64;      // channels of this chunk
   if (tid < 144) {
     const int8_t* src = w + gid0 * 9 + tid * 16;
@@ -577,8 +578,9 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
     // 4 tq + u / 4, channels 64 chunk + 16 (u % 4) ...): a quad of lanes loads 64 contiguous
     // bytes of a pixel, and a point's results are four 64-byte pieces of a fragment.
     const int nch = (g.C + 63) >> 6;
-    ut = (int)(block / nch) * 4 + (u >> 2);
-    uc = (int)(block % nch) * 64 + (u & 3) * 16;
+    const int quad = (int)fast_div(block, g.mul_ch, g.sh_ch);      // uniform
+    ut = quad * 4 + (u >> 2);
+    uc = ((int)block - quad * nch) * 64 + (u & 3) * 16;
     uok = ut < g.T && uc < g.C;
     if (!uok) ut = 0, uc = 0;
   } else {
@@ -648,7 +650,8 @@ __device__ __forceinline__ void input_body(const int8_t* __restrict__ x, int8_t*
     // (tiles 4 tq .. 4 tq + 3 of one 16-channel slice)
     su = ((u & 3) << 2) | (u >> 2);
     const int nch = (g.C + 63) >> 6;
-    const int st = (int)(block / nch) * 4 + (su >> 2), sc = (int)(block % nch) * 64 + (su & 3) * 16;
+    const int quad = (int)fast_div(block, g.mul_ch, g.sh_ch);
+    const int st = quad * 4 + (su >> 2), sc = ((int)block - quad * nch) * 64 + (su & 3) * 16;
     sok = st < g.T && sc < g.C;
     ub = U + ((long)(st >> 4) * nch + (sc >> 6)) * 1024 + ((sc & 63) >> 4) * 256 + (st & 15) * 16;
     pstride = ((long)(g.T + 15) >> 4) * nch * 1024;
