@@ -89,13 +89,51 @@ struct Geometry {
 // group (q % G) of image 8 (q / G) + x, G = groups per image; the slots past the last full set
 // of eight images keep their plain order.
 #if defined(__HIPCC__)
-__device__ __forceinline__ unsigned image_on_one_xcd(const Geometry& g, unsigned b) {
+#define WINO_HOST_DEVICE __host__ __device__ __forceinline__
+#else
+#define WINO_HOST_DEVICE inline
+#endif
+WINO_HOST_DEVICE unsigned image_on_one_xcd(const Geometry& g, unsigned b) {
   if (g.img_blocks == 0 || b >= (unsigned)g.img_blocks_end) return b;
   const unsigned x = b & 7, q = b >> 3, G = (unsigned)g.img_blocks;
   const unsigned set = q / G, within = q - set * G;
   return (set * 8 + x) * G + within;
 }
-#endif
+
+// Work groups of 256 lanes for `items` lanes' worth of work.
+inline unsigned blocks_for(long items) { return (unsigned)((items + 255) / 256); }
+// A work group's 256 items are the channels of one tile (and offsets inside one
+// image fit 32 bits): the kernels then keep the tile arithmetic in scalar registers.
+inline bool whole_tiles(int channels, int H, int W) {
+  return channels > 0 && channels % 256 == 0 && (long)H * W * channels < (1L << 31);
+}
+// Work groups of the operand transforms: 256 consecutive items each in row order; in
+// fragment order one per (4 rows, 64-channel chunk).
+inline unsigned weight_blocks(const Geometry& g) {
+  return g.frag ? (unsigned)(((long)g.K >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.K * g.C);
+}
+inline unsigned input_blocks(const Geometry& g) {
+  return g.frag ? (unsigned)((((long)g.T + 3) >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.T * g.C);
+}
+// Geometry with the image-to-XCD dealing of the input transform's work groups switched on
+// where an image is a whole number of work groups (block-uniform row order, or fragment order
+// with a tile count per image that is a multiple of the 4 tiles of a work group).
+inline Geometry with_image_groups(Geometry g, bool whole) {
+  long per_image = 0;
+  const long tiles = (long)g.TH * g.TW;
+  if (g.frag) {
+    if (tiles % 4 == 0) per_image = tiles / 4 * ((g.C + 63) >> 6);
+  } else if (whole) {
+    per_image = tiles * (g.C / 256);
+  }
+  if (per_image > 0 && per_image < (1L << 20) && g.N >= 8) {
+    g.img_blocks = (int)per_image;
+    const long end = (long)(g.N / 8) * 8 * per_image;
+    g.img_blocks_end = end < 0x7fffffffL ? (int)end : 0;
+    if (g.img_blocks_end == 0) g.img_blocks = 0;
+  }
+  return g;
+}
 
 // q = n / d for n < 2^30.  d a power of two: a shift (mul = 0).  Otherwise, with f = floor(log2 d),
 // q = (n * mul) >> (32 + f), mul = floor(2^(32 + f) / d) + 1 < 2^32: the excess
