@@ -76,7 +76,8 @@ def _stage_bytes(wl, m_bytes, y_bytes, n, T, C, K):
         # per (tile, c): m*m fresh input bytes in, n*n transformed bytes out
         "input_transform": {"bound": "hbm", "work": T * C * (wl.m * wl.m + n * n)},
         # Winograd-domain multiply-accumulates actually issued, 2 ops each
-        "contraction": {"bound": "mfma", "work": 2 * n * n * T * C * K},
+        "contraction": {"bound": "mfma", "work": 2 * n * n * T * C * K,
+                        "bytes": n * n * (T * C + K * C + T * K * m_bytes)},
         # per (tile, k): n*n contraction results in, m*m outputs out
         "output_transform": {"bound": "hbm",
                              "work": T * K * (n * n * m_bytes + wl.m * wl.m * y_bytes)},
@@ -271,6 +272,7 @@ def price_stages(names, stage_ms, model, traffic, valu, measured_peaks):
     beside it where the profile holds its instruction count (valu_issue_*: SQ_INSTS_VALU x 64
     lanes over the duration, against 256 CUs x 64 lanes x 2.4 GHz)."""
     stages = {}
+    frag = "contraction_output" in names    # its operands are written in fragment order
     for nm in names:
         sec = stage_ms[nm] * 1e-3
         mdl = model[nm]
@@ -280,6 +282,18 @@ def price_stages(names, stage_ms, model, traffic, valu, measured_peaks):
             st.update({"achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": hbm / HBM_PEAK_GBS, "algorithmic_bytes": mdl["work"],
                        "frac_of_measured_peak": hbm / measured_peaks["copy_GBps"]})
+        elif "bytes" in mdl and (mdl["bytes"] / (HBM_PEAK_GBS * 1e9)
+                                 > mdl["work"] / (INT8_MFMA_PEAK_TOPS * 1e12)):
+            # the layer's arithmetic intensity is below the machine balance: moving the
+            # algorithmic bytes at the HBM peak takes longer than the multiply-accumulates at
+            # the MFMA peak, so HBM is the ceiling of this launch; the MFMA rate is given beside it
+            hbm = mdl["bytes"] / sec / 1e9
+            ach = mdl["work"] / sec / 1e12
+            st.update({"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                       "frac": hbm / HBM_PEAK_GBS, "algorithmic_bytes": mdl["bytes"],
+                       "frac_of_measured_peak": hbm / measured_peaks["copy_GBps"],
+                       "algorithmic_ops": mdl["work"], "mfma_TOPs": ach,
+                       "mfma_frac": ach / INT8_MFMA_PEAK_TOPS})
         else:
             ach = mdl["work"] / sec / 1e12
             st.update({"achieved": ach, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
@@ -289,11 +303,13 @@ def price_stages(names, stage_ms, model, traffic, valu, measured_peaks):
                 st.update({"algorithmic_bytes": mdl["bytes"],
                            "hbm_GBps": mdl["bytes"] / sec / 1e9,
                            "hbm_frac": mdl["bytes"] / sec / 1e9 / HBM_PEAK_GBS})
-        if nm in valu:
-            rate = valu[nm] * 64 / sec / 1e12
-            st.update({"valu_instructions": valu[nm], "valu_issue_Tops": rate,
+        # counters of the fragment-order build of a transform, where the profile has them
+        key = nm + "_fragments" if frag and (nm + "_fragments") in traffic else nm
+        if key in valu:
+            rate = valu[key] * 64 / sec / 1e12
+            st.update({"valu_instructions": valu[key], "valu_issue_Tops": rate,
                        "valu_issue_frac": rate / VALU_PEAK_TOPS})
-        st["traffic"] = traffic.get(nm)
+        st["traffic"] = traffic.get(key)
         stages[nm] = st
     return stages
 
@@ -461,7 +477,8 @@ def main():
                                                      "traffic")}
     roofline["kernel"] = dominant
     for k in ("frac_of_measured_peak", "algorithmic_bytes", "algorithmic_ops", "hbm_GBps",
-              "hbm_frac", "valu_instructions", "valu_issue_Tops", "valu_issue_frac"):
+              "hbm_frac", "mfma_TOPs", "mfma_frac", "valu_instructions", "valu_issue_Tops",
+              "valu_issue_frac"):
         if k in stages[dominant]:
             roofline[k] = stages[dominant][k]
 

@@ -355,38 +355,39 @@ bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
 // AUTO takes the two-kernel form where it was measured to be the faster one.  It saves the M
 // round trip and a launch; it pays with operands re-read through the L2 four times as often
 // (32 x 32 blocks against the 128 x 128 tiles of the stand-alone contraction) and with
-// operand transforms that are about 10 % slower into fragment order.  Measured, whole layer,
-// two-kernel form against one kernel per stage (us):
+// operand transforms that are about 5 % slower into fragment order.  Its tile blocks run on the
+// XCD whose input-transform work groups wrote their U (image_on_one_xcd), which is what makes it
+// the faster form on layers that fit the L2s.  Measured, whole layer, fp32 y, two-kernel form
+// against one kernel per stage (us):
 //  * C <= 128: it wins at every size tried, with raw or transformed filters, fp32 or int8
-//    output: 16x16 images, C = K = 128, N = 32 / 256 / 2048: 16.8 / 35.4 / 218 against
-//    20.8 / 37.2 / 226; C = 64, K = 128: 26 against 31; C = 128, K = 256: 52 against 54.
+//    output: 16x16 images, C = K = 128, N = 32 / 256 / 2048: 16.5 / 30.7 / 216 against
+//    17.6 / 37.0 / 227; C = 64, K = 128: 26 against 31; C = 128, K = 256: 52 against 54.
 //    (A block's operand bytes go with C, its output brackets do not, and the stand-alone
 //    kernels waste half of their 128-byte channel chunks and 128-wide k blocks on such
 //    layers.)
-//  * 128 < C <= 256, 8-bit M: the stand-alone kernels are as fast or faster at every size
-//    (8x8 images, C = K = 256, fp32 y, filters transformed, N = 128 / 384 / 512 / 1024: 21.3 /
-//    37.3 / 41.1 / 72.9 against 20.1 / 32.0 / 39.1 / 68.0) except where the grid is one work
-//    group per compute unit and the filters arrive transformed (N = 256: 24.4 against 24.7
-//    with fp32 y, 23.8 against 25.0 with int8 y; raw filters 26.9 against 26.5).
+//  * 128 < C <= 256, 8-bit M: it wins where the grid is about one work group per compute unit
+//    (8x8 images, C = K = 256, raw filters, N = 192 / 256: 22.0 / 24.2 against 23.2 / 25.6;
+//    filters transformed: 18.4 / 21.4 against 21.9 / 22.4), and loses on smaller and on larger
+//    grids (N = 64 / 128 / 320 / 512 / 1024 / 4096, raw filters: 19.9 / 21.0 / 32.8 / 42.6 / 75.8 /
+//    263 against 17.0 / 19.9 / 28.4 / 39.7 / 68.4 / 229).
 //  * 128 < C <= 256, 9-bit M (twice the bytes of M): it wins from 256 to 16384 tiles (N = 256 /
-//    1024 / 4096: 24.5 / 72.4 / 257 against 27.0 / 77.9 / 268).
-//  * C > 256: a block's operand bytes go with C and it loses (C = K = 512, 4x4 images: 32 against
-//    22 at N = 256, 8-bit; 8x8 images, 9-bit: 57 against 48).
+//    1024 / 4096: 24.1 / 74.5 / 263 against 27.6 / 77.5 / 269; N = 16384: 1108 against 1077).
+//  * C > 256: a block's operand bytes go with C and it loses (C = K = 512, 4x4 images: 35 against
+//    25 at N = 256, 8-bit; C = K = 384, 8x8 images: 47 against 42).
 //  * F(6,3): 59 against 48 (its output bracket needs 64-bit arithmetic and runs better at the
 //    stand-alone kernel's occupancy).
 constexpr int kConOutNarrowC = 128;            // up to here: whenever the grid has kConOutMinBlocksNarrow
 constexpr long kConOutMinBlocksNarrow = 64;
 constexpr int kConOutWideC = 256;              // up to here: between these block counts, with a 9-bit M,
-constexpr long kConOutMinBlocks = 192;         // or with an 8-bit M and transformed filters when the
-constexpr long kConOutMaxBlocks8 = 256;        // grid is about one work group per compute unit
+constexpr long kConOutMinBlocks = 192;         // or with an 8-bit M when the grid is about one work
+constexpr long kConOutMaxBlocks8 = 256;        // group per compute unit
 constexpr long kConOutMaxBlocks9 = 4096;
 
 bool auto_takes_conout(const wino_conv_desc_t* d, const Plan& p) {
   const long blocks = contract_output_blocks(p.g, p.m_bits);
   if (d->C <= kConOutNarrowC) return blocks >= kConOutMinBlocksNarrow;
   if (d->C > kConOutWideC || blocks < kConOutMinBlocks) return false;
-  if (p.m_bits == 9) return blocks <= kConOutMaxBlocks9;
-  return d->weights_pretransformed && blocks <= kConOutMaxBlocks8;
+  return blocks <= (p.m_bits == 9 ? kConOutMaxBlocks9 : kConOutMaxBlocks8);
 }
 
 // ON: M never leaves the chip.  The single kernel where the layer has one 64-channel chunk

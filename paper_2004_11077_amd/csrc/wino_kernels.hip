@@ -444,8 +444,7 @@ static hipError_t contract_tt(const Geometry& g, const int8_t* U, const int8_t* 
                               int m_bits, const MultTable& mult, hipStream_t st) {
   const int n = g.m + 2;
   const int tblocks = (g.T + kTT - 1) / kTT, kblocks = (g.K + kKT - 1) / kKT;
-  int tgroups = 1;                                   // smallest split that fills 8 XCDs evenly
-  while (tgroups < 8 && (n * n * tgroups) % 8 != 0 && tgroups * 2 <= tblocks) tgroups *= 2;
+  const int tgroups = contract_tile_groups(g, kTT);
   const int tpg = (tblocks + tgroups - 1) / tgroups;
   const int units = n * n * tgroups;
   const long nblocks = (long)((units + 7) / 8) * 8 * tpg * kblocks;
@@ -512,14 +511,8 @@ hipError_t launch_contract(const Geometry& g, const int8_t* U, const int8_t* V, 
     const int n0 = g.m + 2;   // K is a multiple of 16, so the byte count is one of 16
     return launch_fill_zero(Mo, (long)n0 * n0 * g.T * g.K * (m_bits == 8 ? 1 : m_bits == 9 ? 2 : 4), st);
   }
-  // Fewer than two 128-row tiles per compute unit: halve the tile, so that twice as many,
-  // shorter, work groups share each compute unit (measured: 7 % on a 4x4 x 512-channel
-  // layer with 256 tiles; no gain from about two tiles per compute unit on).
-  const int n = g.m + 2;
-  const long big_tiles = (long)n * n * ((g.T + 127) / 128) * ((g.K + kKT - 1) / kKT);
-  const bool small = big_tiles < 2 * 256;
-  return small ? contract_tt<64>(g, U, V, Mo, m_bits, mult, st)
-               : contract_tt<128>(g, U, V, Mo, m_bits, mult, st);
+  return contract_tile_rows(g) == 64 ? contract_tt<64>(g, U, V, Mo, m_bits, mult, st)
+                                     : contract_tt<128>(g, U, V, Mo, m_bits, mult, st);
 }
 
 hipError_t launch_output_transform(const Geometry& g, int leg, const void* Mq, int m_bits,

@@ -77,17 +77,24 @@ struct Geometry {
   // division of a work-group index by the 64-channel chunks of a row, ceil(C / 64): the groups
   // of the fragment-order transforms are (four rows, one chunk)
   uint32_t mul_ch, sh_ch;
-  // input transform: work groups per image when every image's groups are to run on one XCD
-  // (0 = work groups in plain order), and the number of groups covered by that order
+  // input and output transform: work groups per unit (an image or a run of tiles) when every
+  // unit's groups are to run on one XCD (0 = work groups in plain order), and the number of
+  // groups covered by that order; set per launch (with_image_groups, with_output_groups)
   int img_blocks, img_blocks_end;
 };
 
-// Work-group ids go round-robin over the 8 XCDs, each with a private L2.  The tiles of an
-// image overlap by two pixel rows / columns, so the input transform lets all work groups of
-// an image run on the same XCD: an overlapping input line then enters one L2 once instead of
-// several L2s.  Groups are dealt out image by image: launch slot b = 8 q + x (XCD x) takes
-// group (q % G) of image 8 (q / G) + x, G = groups per image; the slots past the last full set
-// of eight images keep their plain order.
+// Work-group ids go round-robin over the 8 XCDs, each with a private L2 that keeps its lines
+// from one kernel to the next.  A line that one XCD wrote and another one read is expensive to
+// write again (the other L2's copy has to be found and dropped), and tiles of an image share
+// input lines.  The transforms therefore deal their work groups to XCDs in units: launch slot
+// b = 8 q + x (XCD x) takes group (q % G) of unit 8 (q / G) + x, G = groups per unit; the slots
+// past the last full set of eight units keep their plain order.  A unit is
+//   * fragment order: 32 consecutive tiles, the tile block of the contraction + output kernel,
+//     which takes tile block j on XCD j % 8: U is read, and written again by the next call, on
+//     the XCD that wrote it;
+//   * rows, small layers: an eighth of the tiles, which the contraction kernel and the output
+//     transform then give to the same XCD (xcd_chunk_tiles), so that U and M stay in one L2;
+//   * rows otherwise: one image (shared input lines enter one L2 once).
 #if defined(__HIPCC__)
 #define WINO_HOST_DEVICE __host__ __device__ __forceinline__
 #else
@@ -115,24 +122,58 @@ inline unsigned weight_blocks(const Geometry& g) {
 inline unsigned input_blocks(const Geometry& g) {
   return g.frag ? (unsigned)((((long)g.T + 3) >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.T * g.C);
 }
-// Geometry with the image-to-XCD dealing of the input transform's work groups switched on
-// where an image is a whole number of work groups (block-uniform row order, or fragment order
-// with a tile count per image that is a multiple of the 4 tiles of a work group).
-inline Geometry with_image_groups(Geometry g, bool whole) {
-  long per_image = 0;
-  const long tiles = (long)g.TH * g.TW;
-  if (g.frag) {
-    if (tiles % 4 == 0) per_image = tiles / 4 * ((g.C + 63) >> 6);
-  } else if (whole) {
-    per_image = tiles * (g.C / 256);
-  }
-  if (per_image > 0 && per_image < (1L << 20) && g.N >= 8) {
-    g.img_blocks = (int)per_image;
-    const long end = (long)(g.N / 8) * 8 * per_image;
-    g.img_blocks_end = end < 0x7fffffffL ? (int)end : 0;
-    if (g.img_blocks_end == 0) g.img_blocks = 0;
-  }
+// Tile rows of a work group of the contraction kernel: 128, or 64 where fewer than two
+// 128-row blocks per compute unit would exist (measured: 7 % on a 4x4 x 512-channel layer with
+// 256 tiles; no gain from about two blocks per compute unit on).
+inline int contract_tile_rows(const Geometry& g) {
+  const int n = g.m + 2;
+  const long big_tiles = (long)n * n * ((g.T + 127) / 128) * ((g.K + 127) / 128);
+  return big_tiles < 2 * 256 ? 64 : 128;
+}
+// Row order, one kernel per stage: tiles per XCD when input transform, contraction and output
+// transform all give the same eighth of the tiles to an XCD, 0 when they do not.  They do when
+// the eighths are whole contraction blocks and U and M together (n*n T (C + K) bytes) fit the
+// eight L2s: measured on 8x8 images with 256 channels, 26.9 -> 25.8 us per layer at N = 256,
+// but 229 -> 240 us at N = 4096, where nothing stays in an L2 and the output transform loses
+// by reading and writing one long run per XCD.
+constexpr long kAlignedXcdBytes = 32L << 20;
+inline long xcd_chunk_tiles(const Geometry& g) {
+  const int tt = contract_tile_rows(g), n = g.m + 2;
+  if (g.frag || g.T <= 0 || g.T % (8L * tt) != 0) return 0;
+  return (long)n * n * g.T * ((long)g.C + g.K) <= kAlignedXcdBytes ? g.T / 8 : 0;
+}
+// Groups of tile rows of the contraction kernel: a unit of its block numbering is (point,
+// group), and unit u runs on XCD u % 8.  Aligned with the transforms: 8 groups, group j on XCD j.
+// Otherwise the smallest split that spreads n*n points over the 8 XCDs evenly.
+inline int contract_tile_groups(const Geometry& g, int tile_rows) {
+  const int n = g.m + 2, tblocks = (g.T + tile_rows - 1) / tile_rows;
+  if (tile_rows == contract_tile_rows(g) && xcd_chunk_tiles(g) > 0) return 8;
+  int tgroups = 1;
+  while (tgroups < 8 && (n * n * tgroups) % 8 != 0 && tgroups * 2 <= tblocks) tgroups *= 2;
+  return tgroups;
+}
+// Sets the dealing of `per_unit` work groups per unit over `units` units (off when there are
+// fewer than eight units or the numbers do not fit).
+inline Geometry with_dealt_units(Geometry g, long per_unit, long units) {
+  g.img_blocks = 0, g.img_blocks_end = 0;
+  const long end = (units / 8) * 8 * per_unit;
+  if (per_unit > 0 && per_unit < (1L << 20) && units >= 8 && end < 0x7fffffffL)
+    g.img_blocks = (int)per_unit, g.img_blocks_end = (int)end;
   return g;
+}
+// Geometry for the input transform's launch (whole: the block-uniform row-order kernel, one
+// work group per tile and 256 channels).
+inline Geometry with_image_groups(const Geometry& g, bool whole) {
+  const long nch = (g.C + 63) >> 6;
+  if (g.frag) return with_dealt_units(g, 8 * nch, g.T / 32);
+  if (!whole) return with_dealt_units(g, 0, 0);
+  if (const long chunk = xcd_chunk_tiles(g)) return with_dealt_units(g, chunk * (g.C / 256), 8);
+  return with_dealt_units(g, (long)g.TH * g.TW * (g.C / 256), g.N);
+}
+// Geometry for the launch of the block-uniform output transform (one work group per tile and
+// 256 output channels).
+inline Geometry with_output_groups(const Geometry& g) {
+  return with_dealt_units(g, xcd_chunk_tiles(g) * (g.K / 256), 8);
 }
 
 // q = n / d for n < 2^30.  d a power of two: a shift (mul = 0).  Otherwise, with f = floor(log2 d),

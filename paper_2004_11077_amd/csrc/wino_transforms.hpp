@@ -727,13 +727,15 @@ __global__ __launch_bounds__(256) void k_output_transform(const MT* __restrict__
   constexpr int64_t IN_MAX = PP ? (MTraits<MT>::in_max << kMaxMShift) : MTraits<MT>::in_max;
   using TB = Tab<M, BASE>;
   const int tid = threadIdx.x;
-  const long gid0 = (long)blockIdx.x * 256;
+  // WHOLE: the work groups of a run of tiles may be dealt to one XCD (the one whose
+  // contraction blocks wrote those tiles' M)
+  const unsigned block = WHOLE ? image_on_one_xcd(g, blockIdx.x) : blockIdx.x;
+  const long gid0 = (long)block * 256;
   const long total = (long)g.T * g.K;
   const long gid = gid0 + tid;
   const bool active = WHOLE || gid < total;
   int t, k;
   if constexpr (WHOLE) {
-    const unsigned block = (unsigned)(gid0 >> 8);
     t = (int)fast_div(block, g.mul_kg, g.sh_kg);                     // uniform: K / 256 groups per tile
     k = (int)(block - (unsigned)t * (unsigned)(g.K >> 8)) * 256 + tid;
   } else {
@@ -937,7 +939,7 @@ static hipError_t output_mt(const Geometry& g, const void* Mq, void* y, int out_
   // the block-uniform fast path is built for the int8 M of the all-8-bit pipeline
   if constexpr (sizeof(MT) == 1)
     if (whole_tiles(g.K, g.H, g.W))
-      return output_mtw<M, LEG, MT, true, false>(g, Mq, y, out_type, relu, mu, none, st);
+      return output_mtw<M, LEG, MT, true, false>(with_output_groups(g), Mq, y, out_type, relu, mu, none, st);
   return output_mtw<M, LEG, MT, false, false>(g, Mq, y, out_type, relu, mu, none, st);
 }
 

@@ -154,7 +154,7 @@ def test_kernel_selection_and_workspace_of_the_whole_layer_call():
     wide = dict(m=4)
     cases = [
         (wn.FUSED_OFF, {}, ["operand_transforms", "contraction", "output_transform"], V + U + M),
-        (wn.FUSED_AUTO, {}, ["operand_transforms", "contraction", "output_transform"], V + U + M),
+        (wn.FUSED_AUTO, {}, ["operand_transforms", "contraction_output"], V + U),
         (wn.FUSED_AUTO, dict(bits_hadamard=9), ["operand_transforms", "contraction_output"], V + U),
         (wn.FUSED_ON, {}, ["operand_transforms", "contraction_output"], V + U),
         (wn.FUSED_AUTO, dict(weights_pretransformed=1, operand_layout=wn.LAYOUT_FRAGMENTS),
@@ -181,9 +181,12 @@ def test_kernel_selection_and_workspace_of_the_whole_layer_call():
         assert wn.wino_conv2d_launches(d) == ["operand_transforms", "contraction_output"], shape
     tiny = wn.ConvDesc(2, 8, 8, 128, 32, m=4, fused=wn.FUSED_AUTO)     # one block
     assert wn.wino_conv2d_launches(tiny) == ["operand_transforms", "contraction", "output_transform"]
-    # 256 channels, 8-bit M: only with transformed filters and one work group per compute unit
+    # 256 channels, 8-bit M: only where the grid is about one work group per compute unit
     pre = dict(m=4, fused=wn.FUSED_AUTO, weights_pretransformed=1, operand_layout=wn.LAYOUT_FRAGMENTS)
     assert wn.wino_conv2d_launches(wn.ConvDesc(256, 8, 8, 256, 256, **pre))[-1] == "contraction_output"
+    for n_img, last in [(128, "output_transform"), (192, "contraction_output"), (320, "output_transform")]:
+        raw = wn.ConvDesc(n_img, 8, 8, 256, 256, m=4, fused=wn.FUSED_AUTO)
+        assert wn.wino_conv2d_launches(raw)[-1] == last, n_img
     big = wn.ConvDesc(512, 8, 8, 256, 256, m=4, fused=wn.FUSED_AUTO)
     assert wn.wino_preferred_operand_layout(big) == wn.LAYOUT_ROWS      # a larger grid: stage by stage
     # ... but a V that is handed over in fragment order is read by the form that can read it

@@ -1,7 +1,7 @@
 """Host arithmetic the kernels' indexing rests on, checked by C++ host programs built from the
 library's own header: the prepared index dividers (fast_div_setup) against plain division, and
-the dealing of the input transform's work groups to XCDs (a one-to-one map that keeps an
-image on one XCD).  No GPU: only the host half of the header is used."""
+the dealing of the transforms' work groups to XCDs (a one-to-one map that keeps a unit of
+tiles on one XCD, the same XCD in every stage kernel where the library says so).  No GPU: only the host half of the header is used."""
 import os
 import shutil
 import subprocess
@@ -38,6 +38,6 @@ def test_index_dividers_are_exact(tmp_path):
 
 
 @needs_hipcc
-def test_input_work_groups_are_dealt_one_to_one_with_an_image_on_one_xcd(tmp_path):
-    word, shapes, dealt = run_host_program(tmp_path, "image_groups")
-    assert word == "ok" and int(shapes) == 2 * 3 * 9 * 7 * 7 and int(dealt) > 300
+def test_work_groups_are_dealt_one_to_one_with_a_unit_on_one_xcd(tmp_path):
+    word, shapes, dealt, aligned = run_host_program(tmp_path, "image_groups")
+    assert word == "ok" and int(shapes) == 2 * 3 * 9 * 7 * 7 and int(dealt) > 300 and int(aligned) > 10
