@@ -135,11 +135,10 @@ typedef struct {
                                  for the shape, as measured: the single kernel for
                                  C, K <= 64; the two-kernel form (m = 2 or 4) for
                                  layers with C <= 128, for layers with C <= 256
-                                 whose M is 9 bits wide, or whose filters arrive
-                                 transformed and whose grid is about one work
-                                 group per compute unit, and whenever V is handed
-                                 over in fragment order; one kernel per stage for
-                                 the rest                                         */
+                                 whose M is 9 bits wide or whose grid is about
+                                 one work group per compute unit, and whenever V
+                                 is handed over in fragment order; one kernel per
+                                 stage for the rest                               */
   int operand_layout;         /* WINO_LAYOUT_*: order of U and V in the stage
                                  calls that write or read them; in wino_conv2d
                                  the order of a pretransformed V (U, and a V it

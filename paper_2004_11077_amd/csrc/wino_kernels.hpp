@@ -132,14 +132,18 @@ inline int contract_tile_rows(const Geometry& g) {
 }
 // Row order, one kernel per stage: tiles per XCD when input transform, contraction and output
 // transform all give the same eighth of the tiles to an XCD, 0 when they do not.  They do when
-// the eighths are whole contraction blocks and U and M together (n*n T (C + K) bytes) fit the
-// eight L2s: measured on 8x8 images with 256 channels, 26.9 -> 25.8 us per layer at N = 256,
-// but 229 -> 240 us at N = 4096, where nothing stays in an L2 and the output transform loses
-// by reading and writing one long run per XCD.
-constexpr long kAlignedXcdBytes = 32L << 20;
+// the eighths are whole contraction blocks, both transforms run their one-tile-per-group
+// kernels (the ones that can be dealt) and U and M together (n*n T (C + K) bytes) fit the eight
+// 4 MiB L2s with room to spare: measured on 8x8 images with 256 channels, 26.9 -> 25.8 us per
+// layer at N = 256 (19 MB); but 45.9 -> 47.6 us for F(6,3) on the same images (32 MiB), and
+// 229 -> 240 us at N = 4096, where nothing stays in an L2 and the output transform loses by
+// reading and writing one long run per XCD.  With the contraction alone renumbered (a
+// 128-channel layer, whose transforms keep their plain order) a layer lost 10 %.
+constexpr long kAlignedXcdBytes = 24L << 20;
 inline long xcd_chunk_tiles(const Geometry& g) {
   const int tt = contract_tile_rows(g), n = g.m + 2;
   if (g.frag || g.T <= 0 || g.T % (8L * tt) != 0) return 0;
+  if (!whole_tiles(g.C, g.H, g.W) || !whole_tiles(g.K, g.H, g.W)) return 0;
   return (long)n * n * g.T * ((long)g.C + g.K) <= kAlignedXcdBytes ? g.T / 8 : 0;
 }
 // Groups of tile rows of the contraction kernel: a unit of its block numbering is (point,
