@@ -108,7 +108,7 @@ WINO_HOST_DEVICE unsigned image_on_one_xcd(const Geometry& g, unsigned b) {
 }
 
 // Work groups of 256 lanes for `items` lanes' worth of work.
-inline unsigned blocks_for(long items) { return (unsigned)((items + 255) / 256); }
+WINO_HOST_DEVICE unsigned blocks_for(long items) { return (unsigned)((items + 255) / 256); }
 // A work group's 256 items are the channels of one tile (and offsets inside one
 // image fit 32 bits): the kernels then keep the tile arithmetic in scalar registers.
 inline bool whole_tiles(int channels, int H, int W) {
@@ -116,7 +116,7 @@ inline bool whole_tiles(int channels, int H, int W) {
 }
 // Work groups of the operand transforms: 256 consecutive items each in row order; in
 // fragment order one per (4 rows, 64-channel chunk).
-inline unsigned weight_blocks(const Geometry& g) {
+WINO_HOST_DEVICE unsigned weight_blocks(const Geometry& g) {
   return g.frag ? (unsigned)(((long)g.K >> 2) * ((g.C + 63) >> 6)) : blocks_for((long)g.K * g.C);
 }
 inline unsigned input_blocks(const Geometry& g) {
