@@ -366,7 +366,8 @@ bool fused_all_covers(const wino_conv_desc_t* d, const Plan& p) {
 //    kernels waste half of their 128-byte channel chunks and 128-wide k blocks on such
 //    layers.)
 //  * 128 < C <= 256, 8-bit M: it wins where the grid is about one work group per compute unit
-//    (8x8 images, C = K = 256, raw filters, N = 192 / 256: 22.0 / 24.2 against 23.2 / 25.6;
+//    (8x8 images, C = K = 256, raw filters, N = 192 / 256: 22.0 / 24.2 against 23.2 / 25.6 --
+//    23.0 against 24.6 at N = 256 since the filter work groups lead the operand launch;
 //    filters transformed: 18.4 / 21.4 against 21.9 / 22.4), and loses on smaller and on larger
 //    grids (N = 64 / 128 / 320 / 512 / 1024 / 4096, raw filters: 19.9 / 21.0 / 32.8 / 42.6 / 75.8 /
 //    263 against 17.0 / 19.9 / 28.4 / 39.7 / 68.4 / 229).
